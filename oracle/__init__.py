@@ -1,0 +1,162 @@
+"""CPU oracle for the dictionary-assembly path -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes wrapper over ``sr_oracle.c`` (plain C, double precision).  Only
+``tests/``, ``__graft_entry__.smoke()`` and ``bench.py``'s ``cpu_baseline`` leg
+may import this package; the HIP library and its Python binding never do.
+
+The arithmetic lives in the C file; this module only marshals numpy arrays.
+Paper passages followed: section II-A Eq. 2 / Eq. 3 (``F = Phi D``,
+``y = F B^T``), section II-B stages 1, 3 and 4, section III-A (atoms with a
+zero selector are ignored; kept atoms may be re-scaled).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sr_oracle.c")
+_LIB = os.path.join(_HERE, "libsr_oracle.so")
+
+_DT = {np.dtype(np.float32): 0, np.dtype(np.float16): 1, np.dtype(np.float64): 2}
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (OpenMP over rows).  Returns the .so path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
+             "-ffp-contract=off", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        c_int, c_dbl, c_vp = ctypes.c_int, ctypes.c_double, ctypes.c_void_p
+        lib.orc_half_to_double.restype = c_dbl
+        lib.orc_half_to_double.argtypes = [ctypes.c_uint16]
+        lib.orc_keys.restype = c_dbl
+        lib.orc_keys.argtypes = [c_dbl, c_dbl]
+        lib.orc_taps.restype = None
+        lib.orc_taps.argtypes = [ctypes.c_long, c_int, c_dbl,
+                                 ctypes.POINTER(ctypes.c_long), ctypes.POINTER(c_dbl)]
+        lib.orc_bicubic.restype = c_int
+        lib.orc_bicubic.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_dbl, c_vp]
+        lib.orc_assemble_rows.restype = c_int
+        lib.orc_assemble_rows.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_vp, c_int, c_int,
+                                          c_vp, c_int, c_vp, c_int, c_vp, c_int, c_int, c_vp]
+        lib.orc_assemble_points.restype = c_int
+        lib.orc_assemble_points.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_vp, c_int, c_int,
+                                            c_vp, c_int, c_vp, c_int, c_vp, c_vp, c_int, c_vp]
+        lib.orc_threads.restype = c_int
+        _lib = lib
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _stored(a, name):
+    """The caller's stored bytes, untouched: fp16/fp32/fp64, C-contiguous."""
+    a = np.asarray(a)
+    if a.dtype not in _DT:
+        raise TypeError(f"{name}: dtype {a.dtype} not one of float16/32/64")
+    return np.ascontiguousarray(a)
+
+
+def half_to_double(bits: int) -> float:
+    return _load().orc_half_to_double(int(bits) & 0xFFFF)
+
+
+def keys(t: float, a: float = -0.5) -> float:
+    return _load().orc_keys(float(t), float(a))
+
+
+def taps(index: int, scale: int, a: float = -0.5):
+    """(first LR tap index, four weights) for HR index ``index``."""
+    first = ctypes.c_long()
+    w = (ctypes.c_double * 4)()
+    _load().orc_taps(int(index), int(scale), float(a), ctypes.byref(first), w)
+    return first.value, [w[i] for i in range(4)]
+
+
+def threads() -> int:
+    return _load().orc_threads()
+
+
+def bicubic(lr, scale: int, a: float = -0.5) -> np.ndarray:
+    """Stage 1: ``lr`` [N][C][h][w] -> float64 [N][C][s*h][s*w]."""
+    lr = _stored(lr, "lr")
+    if lr.ndim != 4:
+        raise ValueError("lr must be [N][C][h][w]")
+    n, c, h, w = lr.shape
+    U = np.empty((n, c, scale * h, scale * w), dtype=np.float64)
+    rc = _load().orc_bicubic(_ptr(lr), _DT[lr.dtype], n, c, h, w, int(scale), float(a), _ptr(U))
+    if rc:
+        raise ValueError("orc_bicubic rejected its arguments")
+    return U
+
+
+def _common(U, coeff, dictionary, kept, gamma):
+    U = np.ascontiguousarray(U, dtype=np.float64)
+    coeff = _stored(coeff, "coeff")
+    D = np.ascontiguousarray(np.asarray(dictionary).astype(np.float64))
+    if U.ndim != 4 or coeff.ndim != 4 or D.ndim != 3 or D.shape[1] != D.shape[2]:
+        raise ValueError("shapes: U [N][C][H][W], coeff [N][L][H][W], dict [L][k][k]")
+    n, c, H, W = U.shape
+    L, k = D.shape[0], D.shape[1]
+    if coeff.shape != (n, L, H, W):
+        raise ValueError(f"coeff shape {coeff.shape} != {(n, L, H, W)}")
+    kept_a = None if kept is None else np.ascontiguousarray(kept, dtype=np.int32)
+    gamma_a = None if gamma is None else np.ascontiguousarray(gamma, dtype=np.float64)
+    if gamma_a is not None:
+        count = L if kept_a is None else kept_a.size
+        if gamma_a.size != count:
+            raise ValueError("gamma needs one entry per listed atom")
+        if kept_a is None:
+            kept_a = np.arange(L, dtype=np.int32)
+    n_kept = 0 if kept_a is None else int(kept_a.size)
+    return U, coeff, D, kept_a, n_kept, gamma_a, (n, c, H, W, L, k)
+
+
+def assemble(U, coeff, dictionary, kept=None, gamma=None, rows=None) -> np.ndarray:
+    """Stages 3 + 4 on a stage-1 result ``U``.  ``rows=(y0, y1)`` limits the HR
+    rows computed (others are left at zero)."""
+    U, coeff, D, kept_a, n_kept, gamma_a, (n, c, H, W, L, k) = _common(U, coeff, dictionary, kept, gamma)
+    y0, y1 = (0, H) if rows is None else rows
+    out = np.zeros((n, c, H, W), dtype=np.float64)
+    rc = _load().orc_assemble_rows(_ptr(U), n, c, H, W, _ptr(coeff), _DT[coeff.dtype], L,
+                                   _ptr(D), k, _ptr(kept_a), n_kept, _ptr(gamma_a),
+                                   int(y0), int(y1), _ptr(out))
+    if rc:
+        raise ValueError("orc_assemble_rows rejected its arguments")
+    return out
+
+
+def assemble_points(U, coeff, dictionary, pts, kept=None, gamma=None) -> np.ndarray:
+    """Stages 3 + 4 at listed pixels ``pts`` = [(image, Y, X), ...] -> [n_pts][C]."""
+    U, coeff, D, kept_a, n_kept, gamma_a, (n, c, H, W, L, k) = _common(U, coeff, dictionary, kept, gamma)
+    pts = np.ascontiguousarray(pts, dtype=np.int32).reshape(-1, 3)
+    out = np.zeros((pts.shape[0], c), dtype=np.float64)
+    rc = _load().orc_assemble_points(_ptr(U), n, c, H, W, _ptr(coeff), _DT[coeff.dtype], L,
+                                     _ptr(D), k, _ptr(kept_a), n_kept, _ptr(gamma_a),
+                                     _ptr(pts), pts.shape[0], _ptr(out))
+    if rc:
+        raise ValueError("orc_assemble_points rejected its arguments")
+    return out
+
+
+def dict_assemble(lr, coeff, dictionary, scale: int, kept=None, gamma=None, a: float = -0.5) -> np.ndarray:
+    """The whole path: stage 1, then stages 3 + 4.  float64 [N][C][s*h][s*w]."""
+    return assemble(bicubic(lr, scale, a), coeff, dictionary, kept, gamma)

@@ -1,0 +1,271 @@
+/*
+ * sr_oracle.c -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+ *
+ * A plain, slow, double-precision CPU statement of what the pixel-adaptive
+ * dictionary-assembly path computes.  Only the tests, the smoke check and the
+ * benchmark's CPU-baseline leg may call it.  It shares no code, table or
+ * constant with the HIP library and the HIP library never calls it.
+ *
+ * What is computed (paper section II-A, Eq. 2 and Eq. 3; stages 1, 3 and 4 of
+ * the four-stage inference flow in section II-B):
+ *
+ *   stage 1   U = upsample(x)             the upsampled LR image; row i of the
+ *                                         patch matrix B is the k x k window of
+ *                                         U centred on HR pixel i
+ *   stage 3   F_i = Phi_i D               per-pixel filter from L atoms
+ *   stage 4   y_i = F_i B_i^T             dot product of filter and patch
+ *
+ * and the compressed-dictionary form of section III-A: atoms whose selector
+ * beta is zero are ignored, kept atoms may carry a regression scale gamma
+ * (Eq. 5, Eq. 9).
+ *
+ * Readings taken where the paper is silent (all are this build's choices):
+ *   - the upsampler is the separable Keys cubic-convolution interpolator with
+ *     parameter a (a = -0.5 in every workload), half-pixel centres
+ *     (source coordinate (Y + 0.5)/s - 0.5) and replicated LR borders;
+ *   - a patch tap that falls outside the HR image reads the nearest HR pixel
+ *     of U (U is replicate-padded, the interpolator is not extrapolated);
+ *   - the dot product is a correlation: tap j = dy*k + dx multiplies
+ *     U[Y + dy - r][X + dx - r], r = (k-1)/2, no flip;
+ *   - the same coefficients serve every image channel;
+ *   - nothing is clamped or rounded on the way.
+ *
+ * Every function is the definition written out; there is no blocking, fusion
+ * or reordering.  Rows may be split over OpenMP threads (each output element
+ * is still computed by the same sequence of operations).
+ *
+ * Parity pins (tests/test_oracle_*.py): exact rational phase weights, quadratic
+ * reproduction (fixes a = -0.5 and the coordinate convention), a library
+ * bicubic at that library's own a, delta atoms, linearity, constant
+ * preservation, an exact-rational apply-then-weight evaluator, a library
+ * unfold + einsum for stages 3 + 4.  No function here is unpinned.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORC_F32 = 0, ORC_F16 = 1, ORC_F64 = 2 };
+
+/* IEEE binary16 bit pattern -> double, exactly (subnormals, inf, nan). */
+double orc_half_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int e = (h >> 10) & 0x1f;
+    int m = h & 0x3ff;
+    double v;
+    if (e == 0)
+        v = ldexp((double)m, -24);
+    else if (e == 31)
+        v = m ? NAN : INFINITY;
+    else
+        v = ldexp((double)(m + 1024), e - 25);
+    return sign ? -v : v;
+}
+
+static double load_elem(const void *p, int dtype, size_t i)
+{
+    switch (dtype) {
+    case ORC_F32: return (double)((const float *)p)[i];
+    case ORC_F16: return orc_half_to_double(((const uint16_t *)p)[i]);
+    default:      return ((const double *)p)[i];
+    }
+}
+
+static long clampl(long v, long lo, long hi)
+{
+    return v < lo ? lo : (v > hi ? hi : v);
+}
+
+/* Keys cubic convolution kernel with free parameter a. */
+double orc_keys(double t, double a)
+{
+    t = fabs(t);
+    if (t <= 1.0)
+        return (a + 2.0) * t * t * t - (a + 3.0) * t * t + 1.0;
+    if (t < 2.0)
+        return a * t * t * t - 5.0 * a * t * t + 8.0 * a * t - 4.0 * a;
+    return 0.0;
+}
+
+/*
+ * Source position of HR index Y at scale s: first tap index (floor - 1) and the
+ * four weights for taps floor-1 .. floor+2.
+ */
+void orc_taps(long Y, int s, double a, long *first, double w[4])
+{
+    double src = ((double)Y + 0.5) / (double)s - 0.5;
+    double fl = floor(src);
+    double t = src - fl;
+    *first = (long)fl - 1;
+    w[0] = orc_keys(1.0 + t, a);
+    w[1] = orc_keys(t, a);
+    w[2] = orc_keys(1.0 - t, a);
+    w[3] = orc_keys(2.0 - t, a);
+}
+
+/* One upsampled value U[n][c][Y][X] (stage 1). */
+static double bicubic_at(const void *lr, int dtype, int c_total, int h, int w,
+                         int s, double a, int n, int c, long Y, long X)
+{
+    long fy, fx;
+    double wy[4], wx[4];
+    orc_taps(Y, s, a, &fy, wy);
+    orc_taps(X, s, a, &fx, wx);
+    size_t plane = ((size_t)n * c_total + c) * (size_t)h * w;
+    double acc = 0.0;
+    for (int i = 0; i < 4; ++i) {
+        long yy = clampl(fy + i, 0, h - 1);
+        for (int j = 0; j < 4; ++j) {
+            long xx = clampl(fx + j, 0, w - 1);
+            acc += wy[i] * wx[j] * load_elem(lr, dtype, plane + (size_t)yy * w + xx);
+        }
+    }
+    return acc;
+}
+
+/*
+ * Stage 1 for a whole batch.  lr: [n][c][h][w] of lr_dtype; U: [n][c][s*h][s*w]
+ * double, written.  Returns 0, or -1 on a bad argument.
+ */
+int orc_bicubic(const void *lr, int lr_dtype, int n, int c, int h, int w,
+                int s, double a, double *U)
+{
+    if (!lr || !U || n < 0 || c < 1 || h < 1 || w < 1 || s < 1)
+        return -1;
+    long H = (long)s * h, W = (long)s * w;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (long nc = 0; nc < (long)n * c; ++nc)
+        for (long Y = 0; Y < H; ++Y)
+            for (long X = 0; X < W; ++X)
+                U[((size_t)nc * H + Y) * W + X] =
+                    bicubic_at(lr, lr_dtype, c, h, w, s, a,
+                               (int)(nc / c), (int)(nc % c), Y, X);
+    return 0;
+}
+
+/* Stage 3 for one pixel: F[j] = sum over kept atoms of gamma * Phi * D. */
+static void fold_pixel(const void *coeff, int cdtype, size_t pix_base,
+                       size_t plane_stride, int L, const double *dict, int kk,
+                       const int *kept, int n_kept, const double *gamma,
+                       double *F)
+{
+    for (int j = 0; j < kk; ++j)
+        F[j] = 0.0;
+    int count = kept ? n_kept : L;
+    for (int i = 0; i < count; ++i) {
+        int l = kept ? kept[i] : i;
+        double phi = load_elem(coeff, cdtype, pix_base + (size_t)l * plane_stride);
+        if (gamma)
+            phi *= gamma[i];
+        for (int j = 0; j < kk; ++j)
+            F[j] += phi * dict[(size_t)l * kk + j];
+    }
+}
+
+/* Stage 4 for one pixel and one channel plane of U. */
+static double apply_pixel(const double *Uplane, long H, long W, long Y, long X,
+                          const double *F, int k)
+{
+    int r = (k - 1) / 2;
+    double acc = 0.0;
+    for (int dy = 0; dy < k; ++dy) {
+        long yy = clampl(Y + dy - r, 0, H - 1);
+        for (int dx = 0; dx < k; ++dx) {
+            long xx = clampl(X + dx - r, 0, W - 1);
+            acc += F[dy * k + dx] * Uplane[(size_t)yy * W + xx];
+        }
+    }
+    return acc;
+}
+
+static int check_kept(const int *kept, int n_kept, int L)
+{
+    if (!kept)
+        return 0;
+    if (n_kept < 0)
+        return -1;
+    for (int i = 0; i < n_kept; ++i)
+        if (kept[i] < 0 || kept[i] >= L)
+            return -1;
+    return 0;
+}
+
+/*
+ * Stages 3 + 4 on HR rows [y0, y1) of every image of the batch.
+ *   U      [n][c][H][W] double  (stage-1 result)
+ *   coeff  [n][L][H][W] of coeff_dtype
+ *   dict   [L][k][k] double
+ *   kept   NULL (all L atoms, in order) or n_kept atom indices
+ *   gamma  NULL (all 1) or one scale per listed atom
+ *   out    [n][c][H][W] double; only rows [y0, y1) are written
+ */
+int orc_assemble_rows(const double *U, int n, int c, int H, int W,
+                      const void *coeff, int coeff_dtype, int L,
+                      const double *dict, int k,
+                      const int *kept, int n_kept, const double *gamma,
+                      int y0, int y1, double *out)
+{
+    if (!U || !coeff || !dict || !out || k < 1 || (k % 2) == 0 || k > 15 ||
+        L < 1 || c < 1 || H < 1 || W < 1 || n < 0 || y0 < 0 || y1 > H ||
+        check_kept(kept, n_kept, L))
+        return -1;
+    int kk = k * k;
+    size_t plane = (size_t)H * W;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int b = 0; b < n; ++b)
+        for (int Y = y0; Y < y1; ++Y) {
+            double F[225];
+            for (int X = 0; X < W; ++X) {
+                size_t pix = (size_t)b * L * plane + (size_t)Y * W + X;
+                fold_pixel(coeff, coeff_dtype, pix, plane, L, dict, kk,
+                           kept, n_kept, gamma, F);
+                for (int ch = 0; ch < c; ++ch)
+                    out[(((size_t)b * c + ch) * H + Y) * W + X] =
+                        apply_pixel(U + ((size_t)b * c + ch) * plane, H, W, Y, X, F, k);
+            }
+        }
+    return 0;
+}
+
+/*
+ * Stages 3 + 4 at listed HR pixels.  pts: n_pts triples (image, Y, X);
+ * out: [n_pts][c] double.
+ */
+int orc_assemble_points(const double *U, int n, int c, int H, int W,
+                        const void *coeff, int coeff_dtype, int L,
+                        const double *dict, int k,
+                        const int *kept, int n_kept, const double *gamma,
+                        const int *pts, int n_pts, double *out)
+{
+    if (!U || !coeff || !dict || !out || !pts || k < 1 || (k % 2) == 0 ||
+        k > 15 || L < 1 || check_kept(kept, n_kept, L))
+        return -1;
+    int kk = k * k;
+    size_t plane = (size_t)H * W;
+    for (int p = 0; p < n_pts; ++p) {
+        int b = pts[3 * p], Y = pts[3 * p + 1], X = pts[3 * p + 2];
+        if (b < 0 || b >= n || Y < 0 || Y >= H || X < 0 || X >= W)
+            return -1;
+        double F[225];
+        size_t pix = (size_t)b * L * plane + (size_t)Y * W + X;
+        fold_pixel(coeff, coeff_dtype, pix, plane, L, dict, kk, kept, n_kept, gamma, F);
+        for (int ch = 0; ch < c; ++ch)
+            out[(size_t)p * c + ch] =
+                apply_pixel(U + ((size_t)b * c + ch) * plane, H, W, Y, X, F, k);
+    }
+    return 0;
+}
+
+/* Threads the row loops above will use. */
+int orc_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,195 @@
+"""Seeded synthetic inputs for the dictionary-assembly path.
+
+This module serves both the CPU oracle's tests and the HIP path's tests and
+benchmark, and holds none of the method's arithmetic: it only draws inputs with
+the shapes, dtypes and value distributions of the workloads (the paper's
+Table I input sizes and scales, plus the 4K and video cases).  The paper's
+benchmark images and trained coefficient network are not available; i.i.d.
+uniform pixels and softmax-of-Gaussian coefficients stand in for them, because
+the cost and the arithmetic of the path do not depend on image content.
+
+Recipe
+  * LR image: i.i.d. uniform [0, 1), NCHW.
+  * Dictionary [L][k][k] fp32: even atoms are anisotropic rotated Gaussians,
+    odd atoms are (1+g)*G(sigma_a) - g*G(sigma_b) with g in [0.5, 2]; every
+    Gaussian is sum-normalised on the k x k support and the atom is divided by
+    its sum, so each atom sums to 1.
+  * Coefficients [N][L][H][W]: per-pixel softmax over the L atoms of Gaussian
+    logits, computed in fp32 and then cast to the storage dtype.  "N(m, v)" in
+    the workload list is read as mean m, variance v.
+  * Selective workload: a seeded set of 8 dominant atoms has logits N(4, 1) at
+    every pixel, the rest N(0, 1).  The kept list is the 8 atoms with the
+    largest mean coefficient over the frame (ties go to the lower index).
+
+Everything is drawn with torch generators on the requested device in fixed
+row chunks, so a given (config, device type) always yields the same bytes.
+Both sides of a parity test consume the same stored bytes.
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+
+import numpy as np
+import torch
+
+BASE_SEED = 230308999
+_CHUNK_ROWS = 64  # fixed: changing it changes the drawn bytes
+
+
+@dataclasses.dataclass(frozen=True)
+class Workload:
+    name: str
+    index: int           # position in the workload list (seed offset)
+    n: int
+    c: int
+    h: int
+    w: int
+    scale: int
+    L: int
+    k: int
+    coeff_dtype: str     # "f32" | "f16"
+    lr_dtype: str        # "f32" | "f16"  (the output has the LR dtype)
+    logit_mean: float = 0.0
+    logit_var: float = 1.0
+    dominant: int = 0    # >0: that many dominant atoms with logits N(4, 1)
+
+    @property
+    def H(self):
+        return self.h * self.scale
+
+    @property
+    def W(self):
+        return self.w * self.scale
+
+    @property
+    def hr_pixels(self):
+        return self.n * self.H * self.W
+
+    def algorithmic_bytes(self, n_read_atoms=None):
+        """Bytes per launch that must cross HBM: every read coefficient once,
+        the output once, the LR image once."""
+        b_c = 2 if self.coeff_dtype == "f16" else 4
+        b_io = 2 if self.lr_dtype == "f16" else 4
+        atoms = self.L if n_read_atoms is None else n_read_atoms
+        per_px = atoms * b_c + self.c * b_io + self.c * b_io / (self.scale ** 2)
+        return per_px * self.hr_pixels
+
+
+WORKLOADS = {
+    "tiny": Workload("tiny", 0, 1, 1, 64, 64, 2, 72, 5, "f32", "f32"),
+    "720p": Workload("720p", 1, 1, 3, 180, 320, 4, 72, 5, "f32", "f32"),
+    "1080p_fp16": Workload("1080p_fp16", 2, 1, 3, 360, 640, 3, 72, 5, "f16", "f32", 0.0, 2.0),
+    "4k_dense": Workload("4k_dense", 3, 1, 3, 540, 960, 4, 72, 5, "f16", "f32"),
+    "4k_selective": Workload("4k_selective", 3, 1, 3, 540, 960, 4, 72, 5, "f16", "f32", 0.0, 1.0, 8),
+    "video": Workload("video", 4, 16, 3, 270, 480, 4, 128, 7, "f16", "f16"),
+}
+
+
+def scaled(wl: Workload, **kw) -> Workload:
+    """A copy of ``wl`` with some fields replaced (for small test cases)."""
+    return dataclasses.replace(wl, **kw)
+
+
+def torch_dtype(code: str):
+    return {"f32": torch.float32, "f16": torch.float16}[code]
+
+
+def _gen(device, seed):
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed))
+    return g
+
+
+def _seed(wl: Workload, stream: int) -> int:
+    return (BASE_SEED + wl.index) * 8 + stream
+
+
+def make_lr(wl: Workload, device="cpu") -> torch.Tensor:
+    g = _gen(device, _seed(wl, 0))
+    x = torch.rand((wl.n, wl.c, wl.h, wl.w), generator=g, device=device, dtype=torch.float32)
+    return x.to(torch_dtype(wl.lr_dtype)).contiguous()
+
+
+def _gauss(k, sx, sy, theta):
+    r = (k - 1) / 2.0
+    yy, xx = np.mgrid[0:k, 0:k].astype(np.float64)
+    yy -= r
+    xx -= r
+    ct, st = math.cos(theta), math.sin(theta)
+    u = ct * xx + st * yy
+    v = -st * xx + ct * yy
+    g = np.exp(-0.5 * ((u / sx) ** 2 + (v / sy) ** 2))
+    return g / g.sum()
+
+
+def make_dictionary(wl: Workload, device="cpu") -> torch.Tensor:
+    """[L][k][k] fp32 Gaussian / difference-of-Gaussians atoms, each summing to 1."""
+    rng = np.random.Generator(np.random.PCG64(_seed(wl, 1)))
+    smax = 2.5 if wl.k <= 5 else 3.5
+    atoms = np.empty((wl.L, wl.k, wl.k), dtype=np.float64)
+    for l in range(wl.L):
+        if l % 2 == 0:
+            sx, sy = rng.uniform(0.5, smax, size=2)
+            atom = _gauss(wl.k, sx, sy, rng.uniform(0.0, math.pi))
+        else:
+            sa, sb = np.sort(rng.uniform(0.5, smax, size=2))
+            gain = rng.uniform(0.5, 2.0)
+            th = rng.uniform(0.0, math.pi)
+            atom = (1.0 + gain) * _gauss(wl.k, sa, sa * rng.uniform(0.7, 1.0), th) \
+                - gain * _gauss(wl.k, sb + 0.25, sb + 0.25, 0.0)
+        atoms[l] = atom / atom.sum()
+    return torch.from_numpy(atoms.astype(np.float32)).to(device).contiguous()
+
+
+def dominant_atoms(wl: Workload) -> np.ndarray:
+    """The seeded set of dominant atoms of a selective workload (sorted)."""
+    rng = np.random.Generator(np.random.PCG64(_seed(wl, 3)))
+    return np.sort(rng.choice(wl.L, size=wl.dominant, replace=False)).astype(np.int32)
+
+
+def make_coeff(wl: Workload, device="cpu", return_mean=False):
+    """[N][L][H][W] coefficients in the storage dtype; optionally also the
+    per-atom mean of the stored values (float64 numpy, length L)."""
+    dt = torch_dtype(wl.coeff_dtype)
+    H, W = wl.H, wl.W
+    out = torch.empty((wl.n, wl.L, H, W), device=device, dtype=dt)
+    g = _gen(device, _seed(wl, 2))
+    std = math.sqrt(wl.logit_var)
+    shift = None
+    if wl.dominant:
+        shift = torch.zeros((wl.L, 1, 1), device=device, dtype=torch.float32)
+        shift[torch.from_numpy(dominant_atoms(wl).astype(np.int64)).to(device)] = 4.0
+    total = torch.zeros(wl.L, device=device, dtype=torch.float64)
+    for b in range(wl.n):
+        for y0 in range(0, H, _CHUNK_ROWS):
+            rows = min(_CHUNK_ROWS, H - y0)
+            logits = torch.randn((wl.L, rows, W), generator=g, device=device, dtype=torch.float32)
+            logits = logits * std + wl.logit_mean
+            if shift is not None:
+                logits = logits + shift
+            chunk = torch.softmax(logits, dim=0).to(dt)
+            out[b, :, y0:y0 + rows, :] = chunk
+            if return_mean:
+                total += chunk.to(torch.float64).sum(dim=(1, 2))
+    if return_mean:
+        return out, (total / float(wl.n * H * W)).cpu().numpy()
+    return out
+
+
+def kept_from_mean(mean: np.ndarray, count: int) -> np.ndarray:
+    """Indices of the ``count`` largest means, ties to the lower index, ascending."""
+    order = sorted(range(len(mean)), key=lambda i: (-float(mean[i]), i))
+    return np.array(sorted(order[:count]), dtype=np.int32)
+
+
+def make_inputs(wl: Workload, device="cpu"):
+    """dict(lr, coeff, dict[, kept]) of torch tensors on ``device`` (kept: numpy int32)."""
+    res = {"lr": make_lr(wl, device), "dict": make_dictionary(wl, device)}
+    if wl.dominant:
+        coeff, mean = make_coeff(wl, device, return_mean=True)
+        res["coeff"] = coeff
+        res["kept"] = kept_from_mean(mean, wl.dominant)
+    else:
+        res["coeff"] = make_coeff(wl, device)
+    return res
