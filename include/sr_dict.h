@@ -1,0 +1,164 @@
+/*
+ * sr_dict.h -- C ABI of the MI355X (gfx950) pixel-adaptive dictionary-assembly
+ * library: the "dictionary query and filtering" path of a LAPAR-style
+ * super-resolution model (paper section II-A, Eq. 2 and Eq. 3; stages 1, 3
+ * and 4 of the inference flow in section II-B; compressed dictionaries per
+ * section III-A).
+ *
+ * For every HR pixel i the path computes
+ *
+ *     F_i = Phi_i D          (stage 3, dictionary assembling, Eq. 2)
+ *     y_i = F_i B_i^T        (stage 4, filtering, Eq. 2)
+ *
+ * where D is the L x k^2 dictionary, Phi_i the pixel's L coefficients and B_i
+ * the k x k neighbourhood of the up-sampled LR image centred on pixel i
+ * (stage 1).  The patch matrix B and the filter matrix F of Eq. 3 are never
+ * written to memory: one fused kernel up-samples, folds and filters.
+ *
+ * Fixed semantics (the paper leaves them open; every workload uses these):
+ *   - up-sampling is separable cubic convolution (Keys), a = -0.5, half-pixel
+ *     centres (source coordinate (Y + 0.5)/scale - 0.5), LR indices clamped;
+ *   - patch taps outside the HR image read the nearest pixel of the
+ *     up-sampled image (replicate padding of the up-sampled image);
+ *   - tap j = dy*k + dx of F_i multiplies U[Y + dy - r][X + dx - r],
+ *     r = (k-1)/2: a correlation, no flip;
+ *   - the same coefficients are applied to every image channel;
+ *   - no clamping or rounding of intermediate values; arithmetic is fp32
+ *     (fp16 coefficients enter matrix-core products exactly, accumulation is
+ *     fp32).
+ *
+ * All tensors are contiguous NCHW in DEVICE memory, allocated, owned and freed
+ * by the caller.  The library allocates nothing, keeps no state between calls
+ * and is re-entrant.  Work is enqueued on `stream` and the call returns without
+ * synchronising: inputs and outputs must stay valid until the stream reaches
+ * the end of the kernel.  `out` must not overlap any input.
+ *
+ * Every argument check happens on the host before anything is launched.  On
+ * error nothing is launched, nothing is written, and a negative status is
+ * returned; the library never aborts, throws or prints.
+ */
+#ifndef SR_DICT_H
+#define SR_DICT_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SR_VERSION 100           /* major*10000 + minor*100 + patch */
+#define SR_MAX_ATOMS 256         /* largest L (and n_kept) accepted   */
+#define SR_MAX_CHANNELS 16       /* largest C accepted                */
+
+typedef enum { SR_F32 = 0, SR_F16 = 1 } sr_dtype;
+
+/* Contiguous NCHW tensor in device memory. */
+typedef struct {
+    void*    data;
+    sr_dtype dtype;
+    int      n, c, h, w;
+} sr_tensor;
+
+typedef enum {
+    SR_OK              =  0,
+    SR_ERR_NULL        = -1,   /* a required pointer is NULL                      */
+    SR_ERR_SHAPE       = -2,   /* descriptor sizes disagree with L/k/scale/channels */
+    SR_ERR_UNSUPPORTED = -3,   /* even k, k not in {3,5,7}, scale not in {2,3,4},
+                                  L or C over the maximum, dtype mix not built     */
+    SR_ERR_ALIAS       = -4,   /* out overlaps an input                            */
+    SR_ERR_KEPT        = -5,   /* kept list empty, too long, out of range or with
+                                  a repeated index                                 */
+    SR_ERR_LAUNCH      = -6,   /* the HIP runtime refused the launch               */
+    SR_ERR_ALIGN       = -7    /* a data pointer is not aligned to its element     */
+} sr_status;
+
+/* Kernel choice for sr_dict_assemble_ex. */
+typedef enum {
+    SR_KERNEL_AUTO    = 0,     /* the library picks                                */
+    SR_KERNEL_GENERIC = 1,     /* fp32 vector-ALU kernel: every supported case      */
+    SR_KERNEL_MFMA    = 2      /* fp16-coefficient matrix-core kernel; the call
+                                  fails with SR_ERR_UNSUPPORTED if the case does
+                                  not qualify (see sr_dict_assemble_ex)            */
+} sr_kernel;
+
+typedef struct {
+    int kernel;                /* sr_kernel                                        */
+    int tile;                  /* MFMA kernel tile shape index, 0 = default        */
+    int reserved[6];           /* must be zero                                     */
+} sr_options;
+
+/*
+ * Dense dictionary assembly (Eq. 2 / Eq. 3 with stage 1 fused in).
+ *
+ *   lr     [N][C][h][w]            f32 or f16   LR image x
+ *   coeff  [N][L][s*h][s*w]        f32 or f16   Phi, one plane per atom
+ *   dict   [1][L][k][k]            f32          D, row-major taps
+ *   out    [N][C][s*h][s*w]        same dtype as lr; written
+ *   L, k, scale, channels          must equal coeff->c, dict->h (= dict->w),
+ *                                  the HR/LR size ratio and lr->c
+ *   stream hipStream_t, NULL = the default stream
+ *
+ * Supported: k in {3,5,7}; scale in {2,3,4}; 1 <= L <= SR_MAX_ATOMS;
+ * 1 <= C <= SR_MAX_CHANNELS; N >= 0 (N = 0 or an empty image is a no-op
+ * returning SR_OK).  With f16 coefficients the dictionary entries must be
+ * finite in fp16 (|D| < 65504).
+ */
+int sr_dict_assemble(const sr_tensor* lr, const sr_tensor* coeff, const sr_tensor* dict,
+                     int L, int k, int scale, int channels,
+                     sr_tensor* out, void* stream);
+
+/*
+ * Dictionary-selective assembly (section III-A: atoms whose selector beta_i is
+ * zero are ignored; Eq. 9: kept atoms may carry a regression scale gamma).
+ * Same nine leading arguments as sr_dict_assemble, `coeff` still holds all L
+ * planes, but only the listed planes are read:
+ *
+ *     F_i = sum over j < n_kept of gamma[j] * Phi_i[kept[j]] * D[kept[j]]
+ *
+ *   kept   HOST array of n_kept distinct atom indices in [0, L), any order
+ *   gamma  HOST array of n_kept scales, or NULL for all ones
+ * Both arrays are copied before the call returns.
+ */
+int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, const sr_tensor* dict,
+                               int L, int k, int scale, int channels,
+                               sr_tensor* out, void* stream,
+                               const int* kept, int n_kept, const float* gamma);
+
+/*
+ * As sr_dict_assemble_selective (kept == NULL means dense), with an explicit
+ * kernel choice; `opts` == NULL means SR_KERNEL_AUTO.  The matrix-core kernel
+ * qualifies when coeff is f16, k is 5 or 7, C is 1 or 3, the HR width is a
+ * multiple of 8 and coeff->data is 16-byte aligned.
+ */
+int sr_dict_assemble_ex(const sr_tensor* lr, const sr_tensor* coeff, const sr_tensor* dict,
+                        int L, int k, int scale, int channels,
+                        sr_tensor* out, void* stream,
+                        const int* kept, int n_kept, const float* gamma,
+                        const sr_options* opts);
+
+/*
+ * Stage 1 alone (section II-B, stage 1): the up-sampled image U that the
+ * patches B_i are cut from.
+ *   lr [N][C][h][w] f32|f16  ->  out [N][C][scale*h][scale*w], dtype f32 or
+ *   the dtype of lr.  The values are bit-identical to the ones the fused
+ *   kernels use internally (before any narrowing to an f16 `out`).
+ */
+int sr_bicubic_upsample(const sr_tensor* lr, int scale, int channels,
+                        sr_tensor* out, void* stream);
+
+/* Which kernel sr_dict_assemble_ex would run for these arguments
+ * (SR_KERNEL_GENERIC or SR_KERNEL_MFMA), or a negative sr_status.  Launches
+ * nothing. */
+int sr_dict_assemble_plan(const sr_tensor* lr, const sr_tensor* coeff, const sr_tensor* dict,
+                          int L, int k, int scale, int channels,
+                          const sr_tensor* out,
+                          const int* kept, int n_kept, const sr_options* opts);
+
+/* Static, NUL-terminated description of a status code. */
+const char* sr_strerror(int status);
+
+/* SR_VERSION of the built library. */
+int sr_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SR_DICT_H */

@@ -1,0 +1,166 @@
+"""ctypes binding of libsrdict.so: argument marshalling only.
+
+Each function has the name and argument order of the C entry point declared in
+include/sr_dict.h and takes torch tensors living in device memory; every step
+of the path runs inside the library's HIP kernels.  There is no CPU fallback:
+if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsrdict.so")
+
+SR_F32, SR_F16 = 0, 1
+SR_KERNEL_AUTO, SR_KERNEL_GENERIC, SR_KERNEL_MFMA = 0, 1, 2
+SR_MAX_ATOMS = 256
+
+EXPORTS = ("sr_dict_assemble", "sr_dict_assemble_selective", "sr_dict_assemble_ex",
+           "sr_bicubic_upsample", "sr_dict_assemble_plan", "sr_strerror", "sr_version")
+
+
+class sr_tensor(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("dtype", ctypes.c_int),
+                ("n", ctypes.c_int), ("c", ctypes.c_int), ("h", ctypes.c_int), ("w", ctypes.c_int)]
+
+
+class sr_options(ctypes.Structure):
+    _fields_ = [("kernel", ctypes.c_int), ("tile", ctypes.c_int), ("reserved", ctypes.c_int * 6)]
+
+
+class SrError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"libsrdict status {status}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def load():
+    """Load the built library (never builds, never falls back)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first with __graft_entry__.build() "
+            "(python -m paper_2303_08999_amd.build); there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    T, O = ctypes.POINTER(sr_tensor), ctypes.POINTER(sr_options)
+    i, vp = ctypes.c_int, ctypes.c_void_p
+    ip, fp = ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)
+    lib.sr_dict_assemble.argtypes = [T, T, T, i, i, i, i, T, vp]
+    lib.sr_dict_assemble_selective.argtypes = [T, T, T, i, i, i, i, T, vp, ip, i, fp]
+    lib.sr_dict_assemble_ex.argtypes = [T, T, T, i, i, i, i, T, vp, ip, i, fp, O]
+    lib.sr_dict_assemble_plan.argtypes = [T, T, T, i, i, i, i, T, ip, i, O]
+    lib.sr_bicubic_upsample.argtypes = [T, i, i, T, vp]
+    lib.sr_strerror.argtypes = [i]
+    lib.sr_strerror.restype = ctypes.c_char_p
+    lib.sr_version.argtypes = []
+    for name in EXPORTS:
+        if name not in ("sr_strerror",):
+            getattr(lib, name).restype = i
+    _lib = lib
+    return lib
+
+
+def describe(t) -> sr_tensor:
+    """sr_tensor descriptor of a contiguous 4-D torch tensor (no copy)."""
+    import torch
+    if t.dim() != 4 or not t.is_contiguous():
+        raise ValueError("expected a contiguous [N][C][H][W] tensor")
+    if t.dtype == torch.float32:
+        code = SR_F32
+    elif t.dtype == torch.float16:
+        code = SR_F16
+    else:
+        raise TypeError(f"dtype {t.dtype} is not float32/float16")
+    ptr = t.data_ptr() if t.numel() else 0
+    return sr_tensor(ptr or None, code, *[int(v) for v in t.shape])
+
+
+def _dict4(d):
+    return d if d.dim() == 4 else d.reshape(1, *d.shape)
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(status):
+    if status != 0:
+        raise SrError(status, sr_strerror(status))
+
+
+def _host_lists(kept, gamma):
+    if kept is None:
+        return None, 0, None, ()
+    kept = [int(v) for v in kept]
+    ka = (ctypes.c_int * max(1, len(kept)))(*kept)
+    ga = None
+    if gamma is not None:
+        gamma = [float(v) for v in gamma]
+        if len(gamma) != len(kept):
+            raise ValueError("gamma needs one entry per kept atom")
+        ga = (ctypes.c_float * max(1, len(gamma)))(*gamma)
+    return ka, len(kept), ga, (ka, ga)
+
+
+def sr_strerror(status: int) -> str:
+    return load().sr_strerror(int(status)).decode()
+
+
+def sr_version() -> int:
+    return load().sr_version()
+
+
+def sr_dict_assemble(lr, coeff, dict, L, k, scale, channels, out, stream=None):
+    a, b, c, o = describe(lr), describe(coeff), describe(_dict4(dict)), describe(out)
+    _check(load().sr_dict_assemble(a, b, c, L, k, scale, channels, o, _stream(stream)))
+    return out
+
+
+def sr_dict_assemble_selective(lr, coeff, dict, L, k, scale, channels, out, stream=None,
+                               kept=None, n_kept=None, gamma=None):
+    a, b, c, o = describe(lr), describe(coeff), describe(_dict4(dict)), describe(out)
+    ka, n, ga, _keep = _host_lists(kept, gamma)
+    n = n if n_kept is None else int(n_kept)
+    _check(load().sr_dict_assemble_selective(a, b, c, L, k, scale, channels, o, _stream(stream), ka, n, ga))
+    return out
+
+
+def make_options(kernel=SR_KERNEL_AUTO, tile=0) -> sr_options:
+    o = sr_options()
+    o.kernel, o.tile = int(kernel), int(tile)
+    return o
+
+
+def sr_dict_assemble_ex(lr, coeff, dict, L, k, scale, channels, out, stream=None,
+                        kept=None, n_kept=None, gamma=None, opts=None):
+    a, b, c, o = describe(lr), describe(coeff), describe(_dict4(dict)), describe(out)
+    ka, n, ga, _keep = _host_lists(kept, gamma)
+    n = n if n_kept is None else int(n_kept)
+    op = ctypes.byref(opts) if opts is not None else None
+    _check(load().sr_dict_assemble_ex(a, b, c, L, k, scale, channels, o, _stream(stream), ka, n, ga, op))
+    return out
+
+
+def sr_dict_assemble_plan(lr, coeff, dict, L, k, scale, channels, out, kept=None, n_kept=None, opts=None) -> int:
+    a, b, c, o = describe(lr), describe(coeff), describe(_dict4(dict)), describe(out)
+    ka, n, _ga, _keep = _host_lists(kept, None)
+    n = n if n_kept is None else int(n_kept)
+    op = ctypes.byref(opts) if opts is not None else None
+    return load().sr_dict_assemble_plan(a, b, c, L, k, scale, channels, o, ka, n, op)
+
+
+def sr_bicubic_upsample(lr, scale, channels, out, stream=None):
+    _check(load().sr_bicubic_upsample(describe(lr), scale, channels, describe(out), _stream(stream)))
+    return out

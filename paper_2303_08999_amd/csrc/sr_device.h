@@ -1,0 +1,148 @@
+// Device-side helpers shared by every kernel of the library (gfx950 only).
+//
+// Stage 1 of the path (paper section II-B): separable cubic-convolution
+// up-sampling.  Every kernel that needs an up-sampled value U[Y][X] goes through
+// keys_weights() and dot4() below in the same order (horizontal pass over four
+// LR columns, then vertical pass over four LR rows), so the fused kernels and
+// the stand-alone up-sampler produce bit-identical U.
+//
+// The library is built with -ffp-contract=off: every fused multiply-add is
+// written out with fmaf(), nothing is contracted behind our back.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "../../include/sr_dict.h"
+
+namespace srd {
+
+// Kernel arguments common to the assembly kernels (passed by value).
+struct AssembleArgs {
+    const void*  lr;      // [N][C][h][w]
+    const void*  coeff;   // [N][L][H][W]
+    const float* dict;    // [L][k][k]
+    void*        out;     // [N][C][H][W]
+    int N, C, h, w, H, W, s, L;
+    int n_fold;           // atoms folded: L (dense) or n_kept
+    int use_table;        // 0: atom i is plane i, scale 1
+    int   kept[SR_MAX_ATOMS];
+    float gamma[SR_MAX_ATOMS];
+};
+
+struct BicubicArgs {
+    const void* lr;
+    void*       out;
+    int NC, h, w, H, W, s;
+};
+
+__device__ __forceinline__ int clampi(int v, int lo, int hi) {
+    return v < lo ? lo : (v > hi ? hi : v);
+}
+
+__device__ __forceinline__ float ld_as_float(const float* p, size_t i) { return p[i]; }
+__device__ __forceinline__ float ld_as_float(const __half* p, size_t i) { return __half2float(p[i]); }
+__device__ __forceinline__ void st_from_float(float* p, size_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void st_from_float(__half* p, size_t i, float v) { p[i] = __float2half_rn(v); }
+
+// Source position of HR index Y (0 <= Y) at integer scale s, half-pixel
+// centres: source = (2Y + 1 - s) / (2s).  Returns floor(source); `m` receives
+// the numerator of the fractional part over 2s (0 <= m < 2s).  Integer
+// arithmetic only, so large coordinates lose nothing.
+__device__ __forceinline__ int src_floor(int Y, int s, int& m) {
+    const int two_s = 2 * s;
+    const int num = 2 * Y + 1 - s + two_s;      // > 0 for Y >= 0
+    const int q = num / two_s;
+    m = num - q * two_s;
+    return q - 1;
+}
+
+// Keys cubic-convolution weights (a = -1/2) for taps floor-1 .. floor+2 at
+// fractional offset t = m / (2s).  Exact in fp32 for s = 2 and s = 4.
+__device__ __forceinline__ void keys_weights(int m, int s, float w[4]) {
+    const float t = (float)m / (float)(2 * s);
+    const float u0 = 1.0f + t, u1 = t, u2 = 1.0f - t, u3 = 2.0f - t;
+    // 1 < |u| < 2 :  ((-1/2 u + 5/2) u - 4) u + 2
+    w[0] = fmaf(fmaf(fmaf(-0.5f, u0, 2.5f), u0, -4.0f), u0, 2.0f);
+    w[3] = fmaf(fmaf(fmaf(-0.5f, u3, 2.5f), u3, -4.0f), u3, 2.0f);
+    // |u| <= 1    :  (3/2 u - 5/2) u^2 + 1
+    w[1] = fmaf(fmaf(1.5f, u1, -2.5f), u1 * u1, 1.0f);
+    w[2] = fmaf(fmaf(1.5f, u2, -2.5f), u2 * u2, 1.0f);
+}
+
+__device__ __forceinline__ float dot4(const float w[4], float a, float b, float c, float d) {
+    float r = w[0] * a;
+    r = fmaf(w[1], b, r);
+    r = fmaf(w[2], c, r);
+    r = fmaf(w[3], d, r);
+    return r;
+}
+
+// ---------------------------------------------------------------------------
+// Cooperative production of one channel's up-sampled tile in LDS.
+//
+// The tile covers HR rows Y0-R .. Y0-R+UH-1 and columns X0-R .. X0-R+UW-1;
+// coordinates outside the image are clamped BEFORE the interpolator is
+// evaluated (the up-sampled image is replicate-padded).  Three phases, the
+// caller puts a workgroup barrier after each:
+//   load_lr_tile : clamped LR footprint -> lrT   [MAXLRY][MAXLRX]
+//   hpass        : four-tap horizontal pass      -> hbuf [MAXLRY][UW]
+//   vpass        : four-tap vertical pass        -> U via store(yy, xx, value)
+// MAXLR* must be >= ceil((extent-1)/s) + 4.
+// ---------------------------------------------------------------------------
+struct TileOrigin {
+    int ly0, lx0;   // LR coordinate of lrT[0][0] (may be negative: reads are clamped)
+};
+
+__device__ __forceinline__ TileOrigin tile_origin(int Y0, int X0, int R, int H, int W, int s) {
+    int m;
+    TileOrigin o;
+    o.ly0 = src_floor(clampi(Y0 - R, 0, H - 1), s, m) - 1;
+    o.lx0 = src_floor(clampi(X0 - R, 0, W - 1), s, m) - 1;
+    return o;
+}
+
+template <typename TIO, int MAXLRY, int MAXLRX, int NT>
+__device__ __forceinline__ void load_lr_tile(const TIO* __restrict__ plane, int h, int w,
+                                             TileOrigin o, float* __restrict__ lrT, int tid) {
+    for (int idx = tid; idx < MAXLRY * MAXLRX; idx += NT) {
+        const int ry = idx / MAXLRX, rx = idx - ry * MAXLRX;
+        const int yy = clampi(o.ly0 + ry, 0, h - 1);
+        const int xx = clampi(o.lx0 + rx, 0, w - 1);
+        lrT[idx] = ld_as_float(plane, (size_t)yy * w + xx);
+    }
+}
+
+template <int MAXLRY, int MAXLRX, int UW, int NT>
+__device__ __forceinline__ void hpass(const float* __restrict__ lrT, float* __restrict__ hbuf,
+                                      int X0, int R, int W, int s, TileOrigin o, int tid) {
+    for (int idx = tid; idx < MAXLRY * UW; idx += NT) {
+        const int ry = idx / UW, xx = idx - ry * UW;
+        int m;
+        const int fx = src_floor(clampi(X0 - R + xx, 0, W - 1), s, m);
+        float wt[4];
+        keys_weights(m, s, wt);
+        int b = fx - 1 - o.lx0;
+        b = clampi(b, 0, MAXLRX - 4);          // never moves a needed tap; keeps LDS reads in range
+        const float* p = lrT + ry * MAXLRX + b;
+        hbuf[idx] = dot4(wt, p[0], p[1], p[2], p[3]);
+    }
+}
+
+template <int MAXLRY, int UW, int UH, int NT, typename Store>
+__device__ __forceinline__ void vpass(const float* __restrict__ hbuf, int Y0, int R, int H, int s,
+                                      TileOrigin o, int tid, Store store) {
+    for (int idx = tid; idx < UH * UW; idx += NT) {
+        const int yy = idx / UW, xx = idx - yy * UW;
+        int m;
+        const int fy = src_floor(clampi(Y0 - R + yy, 0, H - 1), s, m);
+        float wt[4];
+        keys_weights(m, s, wt);
+        int b = fy - 1 - o.ly0;
+        b = clampi(b, 0, MAXLRY - 4);
+        const float* p = hbuf + b * UW + xx;
+        store(yy, xx, dot4(wt, p[0], p[UW], p[2 * UW], p[3 * UW]));
+    }
+}
+
+}  // namespace srd

@@ -1,0 +1,140 @@
+// Generic fp32 vector-ALU kernels: every supported (dtype, k, L, C, scale, size)
+// combination, including odd widths and kept-atom lists.  One thread per HR
+// pixel; the fold F_i = Phi_i D (paper Eq. 2, stage 3) is kept in registers,
+// the up-sampled patch tile (stage 1) lives in LDS, the filtering
+// y_i = F_i B_i^T (stage 4) reads it from there.  The matrices F and B of
+// Eq. 3 are never written to memory.
+//
+// This kernel is bound by the fp32 ALUs (L*k^2 multiply-adds per pixel), not by
+// HBM; the matrix-core kernel in sr_mfma.hip is the fast path for fp16
+// coefficients.
+#include "sr_device.h"
+#include "sr_launch.h"
+
+namespace srd {
+
+constexpr int GTW = 64;   // tile width  (HR pixels) = one wavefront per row
+constexpr int GTH = 4;    // tile height (HR pixels)
+constexpr int GNT = GTW * GTH;
+
+template <typename TC, typename TIO, int K>
+__global__ __launch_bounds__(GNT) void k_assemble_generic(const AssembleArgs a) {
+    constexpr int KK = K * K;
+    constexpr int R = (K - 1) / 2;
+    constexpr int UW = GTW + K - 1;
+    constexpr int UH = GTH + K - 1;
+    constexpr int MAXLRY = (UH - 1) / 2 + 5;   // scale >= 2
+    constexpr int MAXLRX = (UW - 1) / 2 + 5;
+
+    __shared__ float lrT[MAXLRY * MAXLRX];
+    __shared__ float hbuf[MAXLRY * UW];
+    __shared__ float U[UH * UW];
+
+    const int tid = threadIdx.x;
+    const int tx = tid % GTW, ty = tid / GTW;
+    const int X0 = blockIdx.x * GTW, Y0 = blockIdx.y * GTH, n = blockIdx.z;
+    const int X = X0 + tx, Y = Y0 + ty;
+    const bool valid = X < a.W && Y < a.H;
+    const size_t plane = (size_t)a.H * a.W;
+
+    // ---- stage 3: F = Phi_i D, all k^2 taps in registers -------------------
+    float F[KK];
+#pragma unroll
+    for (int t = 0; t < KK; ++t) F[t] = 0.0f;
+    if (valid) {
+        const TC* cbase = (const TC*)a.coeff + (size_t)n * a.L * plane + (size_t)Y * a.W + X;
+        for (int i = 0; i < a.n_fold; ++i) {
+            const int l = a.use_table ? a.kept[i] : i;
+            float phi = ld_as_float(cbase, (size_t)l * plane);
+            if (a.use_table) phi *= a.gamma[i];
+            const float* d = a.dict + (size_t)l * KK;   // wave-uniform: scalar loads
+#pragma unroll
+            for (int t = 0; t < KK; ++t) F[t] = fmaf(phi, d[t], F[t]);
+        }
+    }
+
+    // ---- stages 1 + 4, one channel at a time -------------------------------
+    const TileOrigin o = tile_origin(Y0, X0, R, a.H, a.W, a.s);
+    for (int c = 0; c < a.C; ++c) {
+        const TIO* lrp = (const TIO*)a.lr + ((size_t)n * a.C + c) * (size_t)a.h * a.w;
+        load_lr_tile<TIO, MAXLRY, MAXLRX, GNT>(lrp, a.h, a.w, o, lrT, tid);
+        __syncthreads();
+        hpass<MAXLRY, MAXLRX, UW, GNT>(lrT, hbuf, X0, R, a.W, a.s, o, tid);
+        __syncthreads();
+        vpass<MAXLRY, UW, UH, GNT>(hbuf, Y0, R, a.H, a.s, o, tid,
+                                   [&](int yy, int xx, float v) { U[yy * UW + xx] = v; });
+        __syncthreads();
+        if (valid) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int dy = 0; dy < K; ++dy)
+#pragma unroll
+                for (int dx = 0; dx < K; ++dx)
+                    acc = fmaf(F[dy * K + dx], U[(ty + dy) * UW + tx + dx], acc);
+            st_from_float((TIO*)a.out, ((size_t)n * a.C + c) * plane + (size_t)Y * a.W + X, acc);
+        }
+        // The next channel's lrT/hbuf writes do not touch U; two barriers separate
+        // this read of U from the next vpass.
+    }
+}
+
+// Stage 1 alone: one thread per up-sampled pixel, same arithmetic as the tiles.
+template <typename TI, typename TO>
+__global__ __launch_bounds__(256) void k_bicubic(const BicubicArgs a) {
+    const int X = blockIdx.x * 64 + threadIdx.x % 64;
+    const int Y = blockIdx.y * 4 + threadIdx.x / 64;
+    if (X >= a.W || Y >= a.H) return;
+    const int nc = blockIdx.z;
+    const TI* p = (const TI*)a.lr + (size_t)nc * a.h * a.w;
+    int mx, my;
+    const int fx = src_floor(X, a.s, mx), fy = src_floor(Y, a.s, my);
+    float wx[4], wy[4];
+    keys_weights(mx, a.s, wx);
+    keys_weights(my, a.s, wy);
+    int xs[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) xs[j] = clampi(fx - 1 + j, 0, a.w - 1);
+    float hrow[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const size_t row = (size_t)clampi(fy - 1 + i, 0, a.h - 1) * a.w;
+        hrow[i] = dot4(wx, ld_as_float(p, row + xs[0]), ld_as_float(p, row + xs[1]),
+                       ld_as_float(p, row + xs[2]), ld_as_float(p, row + xs[3]));
+    }
+    st_from_float((TO*)a.out, ((size_t)nc * a.H + Y) * a.W + X,
+                  dot4(wy, hrow[0], hrow[1], hrow[2], hrow[3]));
+}
+
+template <typename TC, typename TIO>
+static hipError_t launch_generic_k(const AssembleArgs& a, int k, dim3 grid, hipStream_t st) {
+    switch (k) {
+    case 3: hipLaunchKernelGGL((k_assemble_generic<TC, TIO, 3>), grid, dim3(GNT), 0, st, a); break;
+    case 5: hipLaunchKernelGGL((k_assemble_generic<TC, TIO, 5>), grid, dim3(GNT), 0, st, a); break;
+    case 7: hipLaunchKernelGGL((k_assemble_generic<TC, TIO, 7>), grid, dim3(GNT), 0, st, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_generic(const AssembleArgs& a, int k, bool coeff_f16, bool io_f16, hipStream_t st) {
+    const dim3 grid((a.W + GTW - 1) / GTW, (a.H + GTH - 1) / GTH, a.N);
+    if (coeff_f16)
+        return io_f16 ? launch_generic_k<__half, __half>(a, k, grid, st)
+                      : launch_generic_k<__half, float>(a, k, grid, st);
+    return io_f16 ? launch_generic_k<float, __half>(a, k, grid, st)
+                  : launch_generic_k<float, float>(a, k, grid, st);
+}
+
+hipError_t launch_bicubic(const BicubicArgs& a, bool in_f16, bool out_f16, hipStream_t st) {
+    const dim3 grid((a.W + 63) / 64, (a.H + 3) / 4, a.NC);
+    if (in_f16) {
+        if (out_f16) hipLaunchKernelGGL((k_bicubic<__half, __half>), grid, dim3(256), 0, st, a);
+        else         hipLaunchKernelGGL((k_bicubic<__half, float>), grid, dim3(256), 0, st, a);
+    } else {
+        if (out_f16) hipLaunchKernelGGL((k_bicubic<float, __half>), grid, dim3(256), 0, st, a);
+        else         hipLaunchKernelGGL((k_bicubic<float, float>), grid, dim3(256), 0, st, a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace srd

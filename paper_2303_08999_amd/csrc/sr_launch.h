@@ -1,0 +1,15 @@
+// Host-side launch entry points of the individual kernel families.
+#pragma once
+#include <hip/hip_runtime.h>
+#include "sr_device.h"
+
+namespace srd {
+
+hipError_t launch_generic(const AssembleArgs& a, int k, bool coeff_f16, bool io_f16, hipStream_t st);
+hipError_t launch_bicubic(const BicubicArgs& a, bool in_f16, bool out_f16, hipStream_t st);
+
+// Matrix-core kernel.  mfma_supported() is a pure host-side predicate.
+bool mfma_supported(const AssembleArgs& a, int k, bool coeff_f16, int tile);
+hipError_t launch_mfma(const AssembleArgs& a, int k, bool io_f16, int tile, hipStream_t st);
+
+}  // namespace srd

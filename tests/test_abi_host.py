@@ -1,0 +1,160 @@
+"""Host-side checks of the C ABI: the library loads without a GPU, exports every
+symbol the header declares, and rejects bad arguments before launching anything.
+No compute call is made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2303_08999_amd as sr
+from paper_2303_08999_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2303_08999_amd import build
+        build.build_library()
+    return sr.load()
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "sr_dict.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sr_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared()
+    assert set(names) == set(binding.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_version_and_strerror(lib):
+    assert sr.sr_version() == 100
+    assert sr.sr_strerror(0) == "success"
+    for code in range(-7, 0):
+        assert sr.sr_strerror(code) not in ("", "success", "unknown status")
+    assert sr.sr_strerror(-99) == "unknown status"
+
+
+def T(ptr, dtype, n, c, h, w):
+    return sr.sr_tensor(ptr, dtype, n, c, h, w)
+
+
+def case(L=72, k=5, s=4, C=3, h=8, w=16, cd=sr.SR_F16, io=sr.SR_F32, base=0x10000000):
+    """Descriptors with fake, well-separated, aligned device addresses."""
+    lr = T(base, io, 1, C, h, w)
+    coeff = T(base + 0x1000000, cd, 1, L, s * h, s * w)
+    d = T(base + 0x8000000, sr.SR_F32, 1, L, k, k)
+    out = T(base + 0x9000000, io, 1, C, s * h, s * w)
+    return lr, coeff, d, out
+
+
+def plan(lr, coeff, d, out, L=72, k=5, s=4, C=3, kept=None, opts=None):
+    ka = None
+    n = 0
+    if kept is not None:
+        ka = (ctypes.c_int * max(1, len(kept)))(*kept)
+        n = len(kept)
+    op = ctypes.byref(opts) if opts is not None else None
+    return sr.load().sr_dict_assemble_plan(lr, coeff, d, L, k, s, C, out, ka, n, op)
+
+
+def test_plan_accepts_a_good_case(lib):
+    assert plan(*case()) in (sr.SR_KERNEL_GENERIC, sr.SR_KERNEL_MFMA)
+    assert plan(*case(cd=sr.SR_F32)) == sr.SR_KERNEL_GENERIC
+    assert plan(*case(w=15, s=3), s=3) == sr.SR_KERNEL_GENERIC   # HR width 45: not a multiple of 8
+    assert plan(*case(), opts=sr.make_options(sr.SR_KERNEL_GENERIC)) == sr.SR_KERNEL_GENERIC
+
+
+def test_null_pointers(lib):
+    lr, coeff, d, out = case()
+    assert plan(None, coeff, d, out) == -1
+    assert plan(lr, None, d, out) == -1
+    assert plan(lr, coeff, None, out) == -1
+    assert plan(lr, coeff, d, None) == -1
+    lr.data = None
+    assert plan(lr, coeff, d, out) == -1
+
+
+def test_shape_mismatches(lib):
+    assert plan(*case(), L=71) == -2
+    assert plan(*case(), C=1) == -2
+    assert plan(*case(), s=2) == -2
+    lr, coeff, d, out = case()
+    out.w += 1
+    assert plan(lr, coeff, d, out) == -2
+    lr, coeff, d, out = case()
+    d.h = 7
+    assert plan(lr, coeff, d, out) == -2
+    lr, coeff, d, out = case()
+    coeff.n = 2
+    assert plan(lr, coeff, d, out) == -2
+
+
+def test_unsupported(lib):
+    assert plan(*case(k=4), k=4) == -3       # even k
+    assert plan(*case(k=9), k=9) == -3
+    assert plan(*case(s=5), s=5) == -3
+    assert plan(*case(s=1), s=1) == -3
+    assert plan(*case(L=257), L=257) == -3
+    assert plan(*case(C=17), C=17) == -3
+    lr, coeff, d, out = case()
+    out.dtype = sr.SR_F16                      # out dtype must follow lr
+    assert plan(lr, coeff, d, out) == -3
+    lr, coeff, d, out = case()
+    d.dtype = sr.SR_F16
+    assert plan(lr, coeff, d, out) == -3
+    o = sr.make_options()
+    o.reserved[2] = 1
+    assert plan(*case(), opts=o) == -3
+    assert plan(*case(cd=sr.SR_F32), opts=sr.make_options(sr.SR_KERNEL_MFMA)) == -3
+
+
+def test_alias_and_alignment(lib):
+    lr, coeff, d, out = case()
+    out.data = coeff.data + 64
+    assert plan(lr, coeff, d, out) == -4
+    lr, coeff, d, out = case()
+    out.data = lr.data
+    assert plan(lr, coeff, d, out) == -4
+    lr, coeff, d, out = case()
+    coeff.data += 1
+    assert plan(lr, coeff, d, out) == -7
+
+
+def test_kept_lists(lib):
+    assert plan(*case(), kept=[0, 5, 71]) > 0
+    assert plan(*case(), kept=[0, 72]) == -5
+    assert plan(*case(), kept=[-1]) == -5
+    assert plan(*case(), kept=[3, 3]) == -5
+    assert plan(*case(), kept=list(range(72)) + [0]) == -5
+    lr, coeff, d, out = case()
+    empty = (ctypes.c_int * 1)(0)
+    assert sr.load().sr_dict_assemble_plan(lr, coeff, d, 72, 5, 4, 3, out, empty, 0, None) == -5
+    # the selective entry point needs a list
+    assert sr.load().sr_dict_assemble_selective(lr, coeff, d, 72, 5, 4, 3, out, None, None, 0, None) == -1
+
+
+def test_errors_launch_nothing_through_the_real_entry_points(lib):
+    """Bad arguments come back as statuses from the launching entry points too
+    (they return before any HIP call, so this is safe without a GPU)."""
+    lr, coeff, d, out = case()
+    assert lib.sr_dict_assemble(lr, coeff, d, 71, 5, 4, 3, out, None) == -2
+    assert lib.sr_dict_assemble(None, coeff, d, 72, 5, 4, 3, out, None) == -1
+    assert lib.sr_bicubic_upsample(lr, 5, 3, out, None) == -3
+    assert lib.sr_bicubic_upsample(lr, 2, 3, out, None) == -2
+    assert lib.sr_bicubic_upsample(None, 2, 3, out, None) == -1
+
+
+def test_empty_batches_are_noops(lib):
+    lr, coeff, d, out = case()
+    for t in (lr, coeff, out):
+        t.n = 0
+    assert lib.sr_dict_assemble(lr, coeff, d, 72, 5, 4, 3, out, None) == 0
+    assert lib.sr_bicubic_upsample(lr, 4, 3, out, None) == 0

@@ -1,0 +1,248 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same
+stored input bytes, element by element.
+
+Tolerances (written out, from the stated targets):
+  * fp32 coefficients:  |gpu - ref| <= 1e-5 * max(1, |ref|)
+  * fp16 coefficients (fp32 accumulation):  |gpu - ref| <= 2e-3 absolute
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2303_08999_amd as sr
+import sr_synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+GENERIC, MFMA = sr.SR_KERNEL_GENERIC, sr.SR_KERNEL_MFMA
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    sr.load()
+
+
+def tolerance_ok(got, ref, coeff_f16):
+    got = np.asarray(got, dtype=np.float64)
+    err = np.abs(got - ref)
+    if coeff_f16:
+        return float(err.max(initial=0.0)), 2e-3, bool((err <= 2e-3).all())
+    bound = 1e-5 * np.maximum(1.0, np.abs(ref))
+    return float((err / np.maximum(1.0, np.abs(ref))).max(initial=0.0)), 1e-5, bool((err <= bound).all())
+
+
+def run_gpu(inp, wl, kernel, kept=None, gamma=None, tile=0):
+    out = torch.full((wl.n, wl.c, wl.H, wl.W), float("nan"), device=DEV, dtype=inp["lr"].dtype)
+    opts = sr.make_options(kernel, tile)
+    sr.sr_dict_assemble_ex(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, out,
+                           kept=kept, gamma=gamma, opts=opts)
+    torch.cuda.synchronize()
+    return out
+
+
+def host(inp):
+    return {k: (v.cpu().numpy() if torch.is_tensor(v) else v) for k, v in inp.items()}
+
+
+def planned(inp, wl, kernel, kept=None, tile=0):
+    out = torch.empty((wl.n, wl.c, wl.H, wl.W), device=DEV, dtype=inp["lr"].dtype)
+    return sr.sr_dict_assemble_plan(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c,
+                                    out, kept=kept, opts=sr.make_options(kernel, tile))
+
+
+def check_full(oracle, wl, kernel, kept=None, gamma=None, inp=None, tile=0):
+    inp = inp or sr_synth.make_inputs(wl, DEV)
+    if planned(inp, wl, kernel, kept, tile) != kernel:
+        pytest.skip("this kernel does not take this case")
+    got = run_gpu(inp, wl, kernel, kept, gamma, tile).float().cpu().numpy()
+    hi = host(inp)
+    ref = oracle.dict_assemble(hi["lr"], hi["coeff"], hi["dict"], wl.scale, kept=kept, gamma=gamma)
+    assert not np.isnan(got).any(), "some output pixel was never written"
+    worst, tol, ok = tolerance_ok(got, ref, wl.coeff_dtype == "f16")
+    assert ok, f"{wl.name}: worst error {worst:.3e} exceeds {tol:.0e}"
+    return worst
+
+
+KERNELS = [pytest.param(GENERIC, id="generic"), pytest.param(MFMA, id="mfma")]
+
+
+# ---- the stated workloads, whole frames --------------------------------------
+@pytest.mark.parametrize("kernel", KERNELS)
+@pytest.mark.parametrize("name", ["tiny", "720p", "1080p_fp16"])
+def test_workload_full_frame(oracle, name, kernel):
+    check_full(oracle, sr_synth.WORKLOADS[name], kernel)
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_video_workload_two_frames(oracle, kernel):
+    """L=128, 7x7 atoms, fp16 LR and output; two of the sixteen frames in full."""
+    check_full(oracle, sr_synth.scaled(sr_synth.WORKLOADS["video"], n=2), kernel)
+
+
+# ---- shapes that span several tiles and leave ragged tails --------------------
+RAGGED = [
+    # (h, w, scale, C, L, k, coeff dtype, io dtype, N)
+    (5, 7, 3, 3, 72, 5, "f32", "f32", 1),
+    (37, 50, 2, 1, 72, 5, "f16", "f32", 2),
+    (33, 26, 4, 3, 72, 5, "f16", "f32", 1),
+    (21, 40, 3, 3, 72, 5, "f16", "f32", 1),
+    (19, 30, 4, 3, 128, 7, "f16", "f16", 3),
+    (11, 13, 2, 2, 5, 3, "f32", "f16", 1),
+    (9, 10, 4, 4, 256, 7, "f16", "f32", 1),
+    (1, 1, 2, 1, 1, 3, "f32", "f32", 1),
+    (1, 2, 4, 3, 72, 5, "f16", "f32", 1),
+    (2, 1, 3, 1, 17, 7, "f32", "f32", 1),
+    (70, 66, 4, 1, 72, 5, "f16", "f32", 1),
+    (45, 64, 4, 3, 40, 5, "f16", "f32", 1),
+    (16, 96, 4, 3, 8, 5, "f16", "f32", 1),
+    (16, 48, 4, 3, 13, 7, "f16", "f16", 1),
+]
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+@pytest.mark.parametrize("case", RAGGED, ids=lambda c: "h%dw%ds%dC%dL%dk%d%s%sN%d" % c)
+def test_ragged_shapes(oracle, case, kernel):
+    h, w, s, C, L, k, cd, io, N = case
+    wl = sr_synth.Workload("ragged", 7, N, C, h, w, s, L, k, cd, io, 0.0, 1.5)
+    check_full(oracle, wl, kernel)
+
+
+# ---- dictionary-selective form -------------------------------------------------
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_selective_kept_list_with_and_without_gamma(oracle, kernel):
+    wl = sr_synth.scaled(sr_synth.WORKLOADS["4k_selective"], h=60, w=104)
+    inp = sr_synth.make_inputs(wl, DEV)
+    kept = inp["kept"]
+    assert len(kept) == 8
+    check_full(oracle, wl, kernel, kept=kept, inp=inp)
+    gamma = np.linspace(0.5, 1.75, 8).astype(np.float32)
+    check_full(oracle, wl, kernel, kept=kept[::-1].copy(), gamma=gamma, inp=inp)
+    # an unordered list of odd length, and the full list in reverse
+    check_full(oracle, wl, kernel, kept=np.array([70, 3, 41, 8, 0, 19, 5, 66, 23, 71, 12]), inp=inp)
+    check_full(oracle, wl, kernel, kept=np.arange(71, -1, -1), inp=inp)
+
+
+# ---- arbitrary real coefficients: negative, unnormalised, fp16 subnormal ---------
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_unnormalised_negative_and_subnormal_coefficients(oracle, kernel):
+    wl = sr_synth.Workload("wild", 9, 1, 3, 24, 32, 4, 72, 5, "f16", "f32")
+    inp = sr_synth.make_inputs(wl, DEV)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(99)
+    c = torch.randn(inp["coeff"].shape, generator=g, device=DEV)
+    c[:, ::3] *= 3e-5                      # lands in the fp16 subnormal range
+    c[:, 1::3] *= 0.05
+    inp["coeff"] = c.to(torch.float16)
+    assert int(((inp["coeff"].abs() < 6.1e-5) & (inp["coeff"] != 0)).sum()) > 1000
+    check_full(oracle, wl, kernel, inp=inp)
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_subnormal_only_coefficients_are_not_flushed(oracle, kernel):
+    """All coefficients subnormal in fp16, dictionary scaled up so the exact
+    result is O(1): a path that flushed subnormals would return zeros."""
+    wl = sr_synth.Workload("subn", 10, 1, 3, 8, 16, 4, 72, 5, "f16", "f32")
+    inp = sr_synth.make_inputs(wl, DEV)
+    inp["coeff"] = (inp["coeff"].float() * 2e-3).clamp(max=6.0e-5).to(torch.float16)
+    assert float(inp["coeff"].abs().max()) < 6.1e-5      # every stored value is subnormal
+    inp["dict"] = inp["dict"] * 500.0
+    worst = check_full(oracle, wl, kernel, inp=inp)
+    got = run_gpu(inp, wl, kernel).cpu().numpy()
+    assert np.abs(got).mean() > 0.2, "output collapsed: subnormals were flushed"
+    assert worst < 2e-3
+
+
+# ---- stage 1 alone, and the delta-atom identity -----------------------------------
+@pytest.mark.parametrize("scale", [2, 3, 4])
+@pytest.mark.parametrize("io", ["f32", "f16"])
+def test_bicubic_entry_point(oracle, scale, io):
+    wl = sr_synth.Workload("bic", 11, 2, 3, 37, 53, scale, 1, 3, "f32", io)
+    lr = sr_synth.make_lr(wl, DEV)
+    out = torch.full((wl.n, wl.c, wl.H, wl.W), float("nan"), device=DEV, dtype=torch.float32)
+    sr.sr_bicubic_upsample(lr, scale, wl.c, out)
+    torch.cuda.synchronize()
+    ref = oracle.bicubic(lr.cpu().numpy(), scale)
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - ref) <= 1e-5 * np.maximum(1.0, np.abs(ref)))
+    if io == "f16":
+        out16 = torch.empty_like(out, dtype=torch.float16)
+        sr.sr_bicubic_upsample(lr, scale, wl.c, out16)
+        torch.cuda.synchronize()
+        assert torch.equal(out16, out.to(torch.float16))
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+@pytest.mark.parametrize("scale,k", [(2, 5), (3, 5), (4, 5), (4, 7), (3, 3)])
+def test_centred_delta_atom_equals_bicubic_bit_for_bit(kernel, scale, k):
+    wl = sr_synth.Workload("delta", 12, 1, 3, 23, 34, scale, 8, k, "f16", "f32")
+    inp = sr_synth.make_inputs(wl, DEV)
+    D = torch.randn_like(inp["dict"])
+    D[5] = 0
+    D[5, k // 2, k // 2] = 1.0
+    inp["dict"] = D
+    coeff = torch.zeros_like(inp["coeff"])
+    coeff[:, 5] = 1.0
+    inp["coeff"] = coeff
+    if planned(inp, wl, kernel) != kernel:
+        pytest.skip("this kernel does not take this case")
+    got = run_gpu(inp, wl, kernel)
+    bic = torch.empty_like(got)
+    sr.sr_bicubic_upsample(inp["lr"], scale, wl.c, bic)
+    torch.cuda.synchronize()
+    assert torch.equal(got, bic)
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_off_centre_delta_atoms_on_gpu(oracle, kernel):
+    """Orientation and border clamp of the patch, with deltas in each corner."""
+    wl = sr_synth.Workload("corner", 13, 1, 1, 10, 18, 4, 8, 5, "f16", "f32")
+    inp = sr_synth.make_inputs(wl, DEV)
+    D = torch.zeros_like(inp["dict"])
+    for l, (dy, dx) in enumerate([(0, 0), (0, 4), (4, 0), (4, 4), (1, 3), (3, 1), (2, 0), (0, 2)]):
+        D[l, dy, dx] = 1.0
+    inp["dict"] = D
+    check_full(oracle, wl, kernel, inp=inp)
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_constant_image_is_preserved(kernel):
+    wl = sr_synth.Workload("const", 14, 1, 3, 20, 24, 4, 72, 5, "f16", "f32")
+    inp = sr_synth.make_inputs(wl, DEV)
+    inp["lr"] = torch.full_like(inp["lr"], 0.625)
+    if planned(inp, wl, kernel) != kernel:
+        pytest.skip("this kernel does not take this case")
+    got = run_gpu(inp, wl, kernel)
+    assert float((got - 0.625).abs().max()) < 2e-3
+
+
+def test_empty_batch_and_error_statuses_on_device():
+    wl = sr_synth.Workload("empty", 15, 0, 3, 8, 8, 2, 4, 3, "f32", "f32")
+    inp = sr_synth.make_inputs(wl, DEV)
+    out = torch.empty((0, 3, 16, 16), device=DEV)
+    sr.sr_dict_assemble(inp["lr"], inp["coeff"], inp["dict"], 4, 3, 2, 3, out)
+    wl = sr_synth.scaled(wl, n=1)
+    inp = sr_synth.make_inputs(wl, DEV)
+    out = torch.zeros((1, 3, 16, 16), device=DEV)
+    with pytest.raises(sr.SrError) as e:
+        sr.sr_dict_assemble(inp["lr"], inp["coeff"], inp["dict"], 4, 3, 3, 3, out)
+    assert e.value.status == -2
+    with pytest.raises(sr.SrError) as e:
+        sr.sr_dict_assemble_selective(inp["lr"], inp["coeff"], inp["dict"], 4, 3, 2, 3, out, kept=[1, 1])
+    assert e.value.status == -5
+    torch.cuda.synchronize()
+    assert not out.any()      # nothing was written by the failed calls
+
+
+def test_runs_on_a_side_stream():
+    wl = sr_synth.scaled(sr_synth.WORKLOADS["tiny"])
+    inp = sr_synth.make_inputs(wl, DEV)
+    a = run_gpu(inp, wl, sr.SR_KERNEL_AUTO)
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    b = torch.empty_like(a)
+    with torch.cuda.stream(st):
+        sr.sr_dict_assemble(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, b, stream=st)
+    st.synchronize()
+    assert torch.equal(a, b)
