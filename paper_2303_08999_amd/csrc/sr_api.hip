@@ -77,13 +77,13 @@ void make_plan(Plan& p, const sr_tensor* lr, const sr_tensor* coeff, const sr_te
             a.kept[i] = kept[i];
             a.gamma[i] = gamma ? gamma[i] : 1.0f;
         }
-        a.use_table = 1;
         a.n_fold = n_kept;
     } else {
         if (gamma) { p.status = SR_ERR_KEPT; return; }
-        a.use_table = 0;
+        for (int i = 0; i < L; ++i) { a.kept[i] = i; a.gamma[i] = 1.0f; }
         a.n_fold = L;
     }
+    a.io_f16 = lr->dtype == SR_F16;
     p.empty = lr->n == 0 || lr->h == 0 || lr->w == 0;
     if (!p.empty) {
         if (!lr->data || !coeff->data || !dict->data || !out->data) { p.status = SR_ERR_NULL; return; }

@@ -25,9 +25,9 @@ struct AssembleArgs {
     void*        out;     // [N][C][H][W]
     int N, C, h, w, H, W, s, L;
     int n_fold;           // atoms folded: L (dense) or n_kept
-    int use_table;        // 0: atom i is plane i, scale 1
-    int   kept[SR_MAX_ATOMS];
-    float gamma[SR_MAX_ATOMS];
+    int io_f16;           // lr and out are fp16 (else fp32)
+    int   kept[SR_MAX_ATOMS];    // plane read for folded atom i (identity when dense)
+    float gamma[SR_MAX_ATOMS];   // its scale (1 when dense)
 };
 
 struct BicubicArgs {
@@ -43,18 +43,34 @@ __device__ __forceinline__ int clampi(int v, int lo, int hi) {
 __device__ __forceinline__ float ld_as_float(const float* p, size_t i) { return p[i]; }
 __device__ __forceinline__ float ld_as_float(const __half* p, size_t i) { return __half2float(p[i]); }
 __device__ __forceinline__ void st_from_float(float* p, size_t i, float v) { p[i] = v; }
-__device__ __forceinline__ void st_from_float(__half* p, size_t i, float v) { p[i] = __float2half_rn(v); }
+// fp32 -> fp16 with the fp32 value materialised first: the empty asm keeps the
+// compiler from folding the producing fma and the narrowing into one
+// mixed-precision instruction (a single rounding), so every kernel narrows the
+// same fp32 value the same way.
+__device__ __forceinline__ __half narrow_f16(float v) {
+    asm volatile("" : "+v"(v));
+    return __float2half_rn(v);
+}
+__device__ __forceinline__ void st_from_float(__half* p, size_t i, float v) { p[i] = narrow_f16(v); }
 
 // Source position of HR index Y (0 <= Y) at integer scale s, half-pixel
 // centres: source = (2Y + 1 - s) / (2s).  Returns floor(source); `m` receives
 // the numerator of the fractional part over 2s (0 <= m < 2s).  Integer
 // arithmetic only, so large coordinates lose nothing.
-__device__ __forceinline__ int src_floor(int Y, int s, int& m) {
-    const int two_s = 2 * s;
-    const int num = 2 * Y + 1 - s + two_s;      // > 0 for Y >= 0
-    const int q = num / two_s;
+template <int S>
+__device__ __forceinline__ int src_floor_s(int Y, int& m) {
+    constexpr int two_s = 2 * S;
+    const int num = 2 * Y + 1 - S + two_s;      // > 0 for Y >= 0
+    const int q = num / two_s;                   // constant divisor
     m = num - q * two_s;
     return q - 1;
+}
+__device__ __forceinline__ int src_floor(int Y, int s, int& m) {
+    switch (s) {                                 // wave-uniform branch
+    case 2:  return src_floor_s<2>(Y, m);
+    case 3:  return src_floor_s<3>(Y, m);
+    default: return src_floor_s<4>(Y, m);
+    }
 }
 
 // Keys cubic-convolution weights (a = -1/2) for taps floor-1 .. floor+2 at
@@ -79,27 +95,44 @@ __device__ __forceinline__ float dot4(const float w[4], float a, float b, float 
 }
 
 // ---------------------------------------------------------------------------
-// Cooperative production of one channel's up-sampled tile in LDS.
+// Cooperative production of an up-sampled tile in LDS.
 //
 // The tile covers HR rows Y0-R .. Y0-R+UH-1 and columns X0-R .. X0-R+UW-1;
 // coordinates outside the image are clamped BEFORE the interpolator is
-// evaluated (the up-sampled image is replicate-padded).  Three phases, the
-// caller puts a workgroup barrier after each:
-//   load_lr_tile : clamped LR footprint -> lrT   [MAXLRY][MAXLRX]
-//   hpass        : four-tap horizontal pass      -> hbuf [MAXLRY][UW]
-//   vpass        : four-tap vertical pass        -> U via store(yy, xx, value)
-// MAXLR* must be >= ceil((extent-1)/s) + 4.
+// evaluated (the up-sampled image is replicate-padded).  Phases, the caller
+// puts a workgroup barrier between them:
+//   build_taps (x and y) + LR footprint -> lrT [MAXLRY][MAXLRX]   (clamped reads)
+//   hpass : four-tap horizontal pass    -> hbuf [nly][UW]
+//   vpass : four-tap vertical pass      -> U via store(yy, xx, value)
+// MAXLR* must be >= ceil((extent-1)/s) + 4 for the smallest scale (2).
 // ---------------------------------------------------------------------------
 struct TileOrigin {
     int ly0, lx0;   // LR coordinate of lrT[0][0] (may be negative: reads are clamped)
+    int nly;        // LR rows the tile really needs (<= MAXLRY)
 };
 
-__device__ __forceinline__ TileOrigin tile_origin(int Y0, int X0, int R, int H, int W, int s) {
+__device__ __forceinline__ TileOrigin tile_origin(int Y0, int X0, int R, int UH, int H, int W, int s) {
     int m;
     TileOrigin o;
     o.ly0 = src_floor(clampi(Y0 - R, 0, H - 1), s, m) - 1;
     o.lx0 = src_floor(clampi(X0 - R, 0, W - 1), s, m) - 1;
+    o.nly = src_floor(clampi(Y0 - R + UH - 1, 0, H - 1), s, m) + 2 - o.ly0 + 1;
     return o;
+}
+
+// Per-coordinate interpolation taps of one tile axis: weights and the index of
+// the first of the four source rows/columns inside the LDS footprint.
+template <int N, int MAXLR, int NT>
+__device__ __forceinline__ void build_taps(int origin, int R, int limit, int s, int l0,
+                                           float4* __restrict__ wtab, int* __restrict__ btab, int tid) {
+    for (int i = tid; i < N; i += NT) {
+        int m;
+        const int f = src_floor(clampi(origin - R + i, 0, limit - 1), s, m);
+        float wt[4];
+        keys_weights(m, s, wt);
+        wtab[i] = make_float4(wt[0], wt[1], wt[2], wt[3]);
+        btab[i] = clampi(f - 1 - l0, 0, MAXLR - 4);   // the clamp never moves a needed tap
+    }
 }
 
 template <typename TIO, int MAXLRY, int MAXLRX, int NT>
@@ -113,34 +146,28 @@ __device__ __forceinline__ void load_lr_tile(const TIO* __restrict__ plane, int 
     }
 }
 
-template <int MAXLRY, int MAXLRX, int UW, int NT>
+template <int MAXLRX, int UW, int NT>
 __device__ __forceinline__ void hpass(const float* __restrict__ lrT, float* __restrict__ hbuf,
-                                      int X0, int R, int W, int s, TileOrigin o, int tid) {
-    for (int idx = tid; idx < MAXLRY * UW; idx += NT) {
+                                      const float4* __restrict__ xw, const int* __restrict__ xb,
+                                      int nly, int tid) {
+    for (int idx = tid; idx < nly * UW; idx += NT) {
         const int ry = idx / UW, xx = idx - ry * UW;
-        int m;
-        const int fx = src_floor(clampi(X0 - R + xx, 0, W - 1), s, m);
-        float wt[4];
-        keys_weights(m, s, wt);
-        int b = fx - 1 - o.lx0;
-        b = clampi(b, 0, MAXLRX - 4);          // never moves a needed tap; keeps LDS reads in range
-        const float* p = lrT + ry * MAXLRX + b;
+        const float4 w4 = xw[xx];
+        const float wt[4] = {w4.x, w4.y, w4.z, w4.w};
+        const float* p = lrT + ry * MAXLRX + xb[xx];
         hbuf[idx] = dot4(wt, p[0], p[1], p[2], p[3]);
     }
 }
 
-template <int MAXLRY, int UW, int UH, int NT, typename Store>
-__device__ __forceinline__ void vpass(const float* __restrict__ hbuf, int Y0, int R, int H, int s,
-                                      TileOrigin o, int tid, Store store) {
+template <int UW, int UH, int NT, typename Store>
+__device__ __forceinline__ void vpass(const float* __restrict__ hbuf,
+                                      const float4* __restrict__ yw, const int* __restrict__ yb,
+                                      int tid, Store store) {
     for (int idx = tid; idx < UH * UW; idx += NT) {
         const int yy = idx / UW, xx = idx - yy * UW;
-        int m;
-        const int fy = src_floor(clampi(Y0 - R + yy, 0, H - 1), s, m);
-        float wt[4];
-        keys_weights(m, s, wt);
-        int b = fy - 1 - o.ly0;
-        b = clampi(b, 0, MAXLRY - 4);
-        const float* p = hbuf + b * UW + xx;
+        const float4 w4 = yw[yy];
+        const float wt[4] = {w4.x, w4.y, w4.z, w4.w};
+        const float* p = hbuf + yb[yy] * UW + xx;
         store(yy, xx, dot4(wt, p[0], p[UW], p[2 * UW], p[3 * UW]));
     }
 }

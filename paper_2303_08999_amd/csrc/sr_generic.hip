@@ -29,6 +29,8 @@ __global__ __launch_bounds__(GNT) void k_assemble_generic(const AssembleArgs a) 
     __shared__ float lrT[MAXLRY * MAXLRX];
     __shared__ float hbuf[MAXLRY * UW];
     __shared__ float U[UH * UW];
+    __shared__ float4 xw[UW], yw[UH];
+    __shared__ int xb[UW], yb[UH];
 
     const int tid = threadIdx.x;
     const int tx = tid % GTW, ty = tid / GTW;
@@ -44,9 +46,8 @@ __global__ __launch_bounds__(GNT) void k_assemble_generic(const AssembleArgs a) 
     if (valid) {
         const TC* cbase = (const TC*)a.coeff + (size_t)n * a.L * plane + (size_t)Y * a.W + X;
         for (int i = 0; i < a.n_fold; ++i) {
-            const int l = a.use_table ? a.kept[i] : i;
-            float phi = ld_as_float(cbase, (size_t)l * plane);
-            if (a.use_table) phi *= a.gamma[i];
+            const int l = a.kept[i];
+            const float phi = ld_as_float(cbase, (size_t)l * plane) * a.gamma[i];
             const float* d = a.dict + (size_t)l * KK;   // wave-uniform: scalar loads
 #pragma unroll
             for (int t = 0; t < KK; ++t) F[t] = fmaf(phi, d[t], F[t]);
@@ -54,15 +55,16 @@ __global__ __launch_bounds__(GNT) void k_assemble_generic(const AssembleArgs a) 
     }
 
     // ---- stages 1 + 4, one channel at a time -------------------------------
-    const TileOrigin o = tile_origin(Y0, X0, R, a.H, a.W, a.s);
+    const TileOrigin o = tile_origin(Y0, X0, R, UH, a.H, a.W, a.s);
+    build_taps<UW, MAXLRX, GNT>(X0, R, a.W, a.s, o.lx0, xw, xb, tid);
+    build_taps<UH, MAXLRY, GNT>(Y0, R, a.H, a.s, o.ly0, yw, yb, tid);
     for (int c = 0; c < a.C; ++c) {
         const TIO* lrp = (const TIO*)a.lr + ((size_t)n * a.C + c) * (size_t)a.h * a.w;
         load_lr_tile<TIO, MAXLRY, MAXLRX, GNT>(lrp, a.h, a.w, o, lrT, tid);
         __syncthreads();
-        hpass<MAXLRY, MAXLRX, UW, GNT>(lrT, hbuf, X0, R, a.W, a.s, o, tid);
+        hpass<MAXLRX, UW, GNT>(lrT, hbuf, xw, xb, o.nly, tid);
         __syncthreads();
-        vpass<MAXLRY, UW, UH, GNT>(hbuf, Y0, R, a.H, a.s, o, tid,
-                                   [&](int yy, int xx, float v) { U[yy * UW + xx] = v; });
+        vpass<UW, UH, GNT>(hbuf, yw, yb, tid, [&](int yy, int xx, float v) { U[yy * UW + xx] = v; });
         __syncthreads();
         if (valid) {
             float acc = 0.0f;
