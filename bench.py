@@ -1,0 +1,150 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused bicubic + dictionary-assembly hot path on one MI355X.
+
+One "step" is one pass of the whole path (stage 1 up-sampling, stage 3
+F = Phi D, stage 4 y = F B^T) over one synthetic 4K x4 frame: 3-channel 960x540
+LR -> 3840x2160 HR, L = 72 atoms of 5x5, fp16 coefficients, fp32 accumulation.
+Inputs are resident in HBM before the timed region; three coefficient tensors
+(1.19 GB each) are rotated so no launch re-reads a cached tensor.
+
+Prints ONE JSON line: whole-job HR Mpixel/s, the HBM roofline of the dominant
+kernel (algorithmic bytes / HIP-event time of the launches), and the CPU
+oracle timed on a bounded sample of the same frame.
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published peak
+N_ROTATE = 3
+
+
+def read_traffic(workload):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE),
+    taken from the committed summary if there is one; else None."""
+    path = os.path.join(ROOT, "profiles", f"sr_mfma_{workload}_traffic.txt")
+    try:
+        m = re.search(r"^traffic_bytes_per_launch\s*[:=]\s*([0-9.eE+]+)", open(path).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def cpu_baseline(wl, lr, coeff, dictionary, budget_s=20.0):
+    """The oracle as it stands, on the host cores, on a band of HR rows of the same
+    frame sized to take roughly `budget_s` of CPU work."""
+    import numpy as np
+    import oracle
+    oracle.build()
+    lr_h = lr.cpu().numpy()
+    d_h = dictionary.cpu().numpy()
+    c_h = coeff.cpu().numpy()
+    threads = oracle.threads()
+    t0 = time.perf_counter()
+    U = oracle.bicubic(lr_h, wl.scale)
+    t_up = time.perf_counter() - t0
+    # calibrate on 16 rows, then size the band
+    t0 = time.perf_counter()
+    oracle.assemble(U, c_h, d_h, rows=(0, 16))
+    per_row = (time.perf_counter() - t0) / 16
+    rows = int(max(16, min(wl.H, budget_s / max(per_row, 1e-9))))
+    t0 = time.perf_counter()
+    oracle.assemble(U, c_h, d_h, rows=(0, rows))
+    t_band = time.perf_counter() - t0
+    # stage 1 is charged in proportion to the band
+    t_total = t_band + t_up * rows / wl.H
+    mpx = rows * wl.W * wl.n / t_total / 1e6
+    return {"value": round(mpx, 3), "unit": "HR Mpixel/s", "cores": threads, "kind": "oracle",
+            "sample": f"HR rows 0..{rows - 1} of {wl.H} of the same 4K frame ({rows * wl.W} pixels), "
+                      f"double precision, OpenMP over rows; {t_total:.2f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="4k_dense")
+    ap.add_argument("--kernel", type=int, default=0, help="0 auto, 1 generic, 2 mfma")
+    ap.add_argument("--tile", type=int, default=0)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--cpu-budget", type=float, default=20.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures ONE GPU; the path shards over HR row bands with no "
+                 "exchange step and no multi-GPU run is part of it (got --gpus %d)" % args.gpus)
+
+    import torch
+    import paper_2303_08999_amd as sr
+    import sr_synth
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    sr.load()
+    wl = sr_synth.WORKLOADS[args.workload]
+    dev = "cuda"
+    inp = sr_synth.make_inputs(wl, dev)
+    kept = inp.get("kept")
+    coeffs = [inp["coeff"]]
+    for r in range(1, N_ROTATE):
+        coeffs.append(sr_synth.make_coeff(sr_synth.scaled(wl, index=wl.index + 10 * r), dev))
+    outs = [torch.empty((wl.n, wl.c, wl.H, wl.W), device=dev, dtype=inp["lr"].dtype) for _ in range(2)]
+    opts = sr.make_options(args.kernel, args.tile)
+    plan = sr.sr_dict_assemble_plan(inp["lr"], coeffs[0], inp["dict"], wl.L, wl.k, wl.scale, wl.c,
+                                    outs[0], kept=kept, opts=opts)
+    assert plan > 0, sr.sr_strerror(plan)
+
+    def step(i):
+        sr.sr_dict_assemble_ex(inp["lr"], coeffs[i % N_ROTATE], inp["dict"], wl.L, wl.k, wl.scale, wl.c,
+                               outs[i % 2], kept=kept, opts=opts)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        step(i)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernel_ms = [a.elapsed_time(b) for a, b in ev]
+    avg_ms = sum(kernel_ms) / len(kernel_ms)
+
+    px = wl.hr_pixels
+    n_read = len(kept) if kept is not None else wl.L
+    alg_bytes = wl.algorithmic_bytes(n_read)
+    achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
+    result = {
+        "metric": "HR Mpixel/s of dictionary assembly (4K x4, L=72, fp16) + % of HBM peak",
+        "value": round(px * args.steps / wall / 1e6, 1),
+        "unit": "HR Mpixel/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall / args.steps * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 coefficients x f16(hi+lo) dictionary on MFMA, f32 accumulate, f32 image",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "hr": f"{wl.W}x{wl.H}", "scale": wl.scale, "channels": wl.c,
+                   "L": wl.L, "k": wl.k, "atoms_read": n_read, "batch": wl.n,
+                   "kernel": {1: "generic", 2: "mfma"}[plan], "rotating_coeff_buffers": N_ROTATE},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(wl.name),
+                     "kernel_ms_avg": round(avg_ms, 4), "kernel_ms_min": round(min(kernel_ms), 4),
+                     "algorithmic_bytes": alg_bytes},
+        "pct_of_hbm_peak": round(100.0 * achieved / HBM_PEAK_GBS, 2),
+    }
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(wl, inp["lr"], coeffs[0], inp["dict"], args.cpu_budget)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

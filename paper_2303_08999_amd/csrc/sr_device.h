@@ -172,4 +172,50 @@ __device__ __forceinline__ void vpass(const float* __restrict__ hbuf,
     }
 }
 
+// Column-per-thread forms of the two passes (used by the matrix-core kernel):
+// a thread owns one (channel, column) and walks the rows, so the tap weights of
+// the horizontal pass are loaded once per thread and the vertical pass keeps a
+// sliding window of four values in registers.  Same dot4() per element as above.
+template <int C, int MAXLRY, int MAXLRX, int UW, int NT>
+__device__ __forceinline__ void hpass_cols(const float* __restrict__ lrT, float* __restrict__ hbuf,
+                                           const float4* __restrict__ xw, const int* __restrict__ xb,
+                                           int nly, int tid) {
+    for (int col = tid; col < C * UW; col += NT) {
+        const int c = col / UW, xx = col - c * UW;
+        const float4 w4 = xw[xx];
+        const float wt[4] = {w4.x, w4.y, w4.z, w4.w};
+        const float* src = lrT + c * MAXLRY * MAXLRX + xb[xx];
+        float* dst = hbuf + c * MAXLRY * UW + xx;
+        for (int ry = 0; ry < nly; ++ry) {
+            const float* p = src + ry * MAXLRX;
+            dst[ry * UW] = dot4(wt, p[0], p[1], p[2], p[3]);
+        }
+    }
+}
+
+template <int C, int MAXLRY, int UW, int UH, int NT, typename Store>
+__device__ __forceinline__ void vpass_cols(const float* __restrict__ hbuf,
+                                           const float4* __restrict__ yw, const int* __restrict__ yb,
+                                           int tid, Store store) {
+    for (int col = tid; col < C * UW; col += NT) {
+        const int c = col / UW, xx = col - c * UW;
+        const float* src = hbuf + c * MAXLRY * UW + xx;
+        int bcur = __builtin_amdgcn_readfirstlane(yb[0]);
+        float h0 = src[bcur * UW], h1 = src[(bcur + 1) * UW], h2 = src[(bcur + 2) * UW], h3 = src[(bcur + 3) * UW];
+#pragma unroll
+        for (int yy = 0; yy < UH; ++yy) {
+            const int b = __builtin_amdgcn_readfirstlane(yb[yy]);   // the same for every thread
+            if (b == bcur + 1) {
+                h0 = h1; h1 = h2; h2 = h3; h3 = src[(b + 3) * UW];
+            } else if (b != bcur) {
+                h0 = src[b * UW]; h1 = src[(b + 1) * UW]; h2 = src[(b + 2) * UW]; h3 = src[(b + 3) * UW];
+            }
+            bcur = b;
+            const float4 w4 = yw[yy];
+            const float wt[4] = {w4.x, w4.y, w4.z, w4.w};
+            store(c, yy, xx, dot4(wt, h0, h1, h2, h3));
+        }
+    }
+}
+
 }  // namespace srd
