@@ -2,9 +2,9 @@
 //
 // Stage 1 of the path (paper section II-B): separable cubic-convolution
 // up-sampling.  Every kernel that needs an up-sampled value U[Y][X] goes through
-// keys_weights() and dot4() below in the same order (horizontal pass over four
-// LR columns, then vertical pass over four LR rows), so the fused kernels and
-// the stand-alone up-sampler produce bit-identical U.
+// keys_weights() and dot4() below in the same order (vertical pass over four LR
+// rows, then horizontal pass over four columns), so the fused kernels and the
+// stand-alone up-sampler produce bit-identical U.
 //
 // The library is built with -ffp-contract=off: every fused multiply-add is
 // written out with fmaf(), nothing is contracted behind our back.
@@ -102,21 +102,25 @@ __device__ __forceinline__ float dot4(const float w[4], float a, float b, float 
 // evaluated (the up-sampled image is replicate-padded).  Phases, the caller
 // puts a workgroup barrier between them:
 //   build_taps (x and y) + LR footprint -> lrT [MAXLRY][MAXLRX]   (clamped reads)
-//   hpass : four-tap horizontal pass    -> hbuf [nly][UW]
-//   vpass : four-tap vertical pass      -> U via store(yy, xx, value)
-// MAXLR* must be >= ceil((extent-1)/s) + 4 for the smallest scale (2).
+//   vertical pass  : V[yy][rx] = dot4(wy[yy], lrT[yb[yy] .. +3][rx])
+//   horizontal pass: U[yy][xx] = dot4(wx[xx], V[yy][xb[xx] .. +3])
+// Vertical first: the intermediate is only as wide as the LR footprint.  Every
+// kernel of the library evaluates stage 1 in this order, so their up-sampled
+// values agree bit for bit.  MAXLR* must be >= ceil((extent-1)/s) + 4 for the
+// smallest scale (2).
 // ---------------------------------------------------------------------------
 struct TileOrigin {
     int ly0, lx0;   // LR coordinate of lrT[0][0] (may be negative: reads are clamped)
-    int nly;        // LR rows the tile really needs (<= MAXLRY)
+    int nly, nlx;   // LR rows / columns the tile really needs (<= MAXLRY / MAXLRX)
 };
 
-__device__ __forceinline__ TileOrigin tile_origin(int Y0, int X0, int R, int UH, int H, int W, int s) {
+__device__ __forceinline__ TileOrigin tile_origin(int Y0, int X0, int R, int UH, int UW, int H, int W, int s) {
     int m;
     TileOrigin o;
     o.ly0 = src_floor(clampi(Y0 - R, 0, H - 1), s, m) - 1;
     o.lx0 = src_floor(clampi(X0 - R, 0, W - 1), s, m) - 1;
     o.nly = src_floor(clampi(Y0 - R + UH - 1, 0, H - 1), s, m) + 2 - o.ly0 + 1;
+    o.nlx = src_floor(clampi(X0 - R + UW - 1, 0, W - 1), s, m) + 2 - o.lx0 + 1;
     return o;
 }
 
@@ -146,75 +150,30 @@ __device__ __forceinline__ void load_lr_tile(const TIO* __restrict__ plane, int 
     }
 }
 
-template <int MAXLRX, int UW, int NT>
-__device__ __forceinline__ void hpass(const float* __restrict__ lrT, float* __restrict__ hbuf,
-                                      const float4* __restrict__ xw, const int* __restrict__ xb,
-                                      int nly, int tid) {
-    for (int idx = tid; idx < nly * UW; idx += NT) {
-        const int ry = idx / UW, xx = idx - ry * UW;
-        const float4 w4 = xw[xx];
+// vertical pass, one element per step: V[yy][rx], pitch MAXLRX
+template <int MAXLRX, int UH, int NT>
+__device__ __forceinline__ void vpass(const float* __restrict__ lrT, float* __restrict__ V,
+                                      const float4* __restrict__ yw, const int* __restrict__ yb, int tid) {
+    for (int idx = tid; idx < UH * MAXLRX; idx += NT) {
+        const int yy = idx / MAXLRX, rx = idx - yy * MAXLRX;
+        const float4 w4 = yw[yy];
         const float wt[4] = {w4.x, w4.y, w4.z, w4.w};
-        const float* p = lrT + ry * MAXLRX + xb[xx];
-        hbuf[idx] = dot4(wt, p[0], p[1], p[2], p[3]);
+        const float* p = lrT + yb[yy] * MAXLRX + rx;
+        V[idx] = dot4(wt, p[0], p[MAXLRX], p[2 * MAXLRX], p[3 * MAXLRX]);
     }
 }
 
-template <int UW, int UH, int NT, typename Store>
-__device__ __forceinline__ void vpass(const float* __restrict__ hbuf,
-                                      const float4* __restrict__ yw, const int* __restrict__ yb,
+// horizontal pass, one element per step
+template <int MAXLRX, int UW, int UH, int NT, typename Store>
+__device__ __forceinline__ void hpass(const float* __restrict__ V,
+                                      const float4* __restrict__ xw, const int* __restrict__ xb,
                                       int tid, Store store) {
     for (int idx = tid; idx < UH * UW; idx += NT) {
         const int yy = idx / UW, xx = idx - yy * UW;
-        const float4 w4 = yw[yy];
-        const float wt[4] = {w4.x, w4.y, w4.z, w4.w};
-        const float* p = hbuf + yb[yy] * UW + xx;
-        store(yy, xx, dot4(wt, p[0], p[UW], p[2 * UW], p[3 * UW]));
-    }
-}
-
-// Column-per-thread forms of the two passes (used by the matrix-core kernel):
-// a thread owns one (channel, column) and walks the rows, so the tap weights of
-// the horizontal pass are loaded once per thread and the vertical pass keeps a
-// sliding window of four values in registers.  Same dot4() per element as above.
-template <int C, int MAXLRY, int MAXLRX, int UW, int NT>
-__device__ __forceinline__ void hpass_cols(const float* __restrict__ lrT, float* __restrict__ hbuf,
-                                           const float4* __restrict__ xw, const int* __restrict__ xb,
-                                           int nly, int tid) {
-    for (int col = tid; col < C * UW; col += NT) {
-        const int c = col / UW, xx = col - c * UW;
         const float4 w4 = xw[xx];
         const float wt[4] = {w4.x, w4.y, w4.z, w4.w};
-        const float* src = lrT + c * MAXLRY * MAXLRX + xb[xx];
-        float* dst = hbuf + c * MAXLRY * UW + xx;
-        for (int ry = 0; ry < nly; ++ry) {
-            const float* p = src + ry * MAXLRX;
-            dst[ry * UW] = dot4(wt, p[0], p[1], p[2], p[3]);
-        }
-    }
-}
-
-template <int C, int MAXLRY, int UW, int UH, int NT, typename Store>
-__device__ __forceinline__ void vpass_cols(const float* __restrict__ hbuf,
-                                           const float4* __restrict__ yw, const int* __restrict__ yb,
-                                           int tid, Store store) {
-    for (int col = tid; col < C * UW; col += NT) {
-        const int c = col / UW, xx = col - c * UW;
-        const float* src = hbuf + c * MAXLRY * UW + xx;
-        int bcur = __builtin_amdgcn_readfirstlane(yb[0]);
-        float h0 = src[bcur * UW], h1 = src[(bcur + 1) * UW], h2 = src[(bcur + 2) * UW], h3 = src[(bcur + 3) * UW];
-#pragma unroll
-        for (int yy = 0; yy < UH; ++yy) {
-            const int b = __builtin_amdgcn_readfirstlane(yb[yy]);   // the same for every thread
-            if (b == bcur + 1) {
-                h0 = h1; h1 = h2; h2 = h3; h3 = src[(b + 3) * UW];
-            } else if (b != bcur) {
-                h0 = src[b * UW]; h1 = src[(b + 1) * UW]; h2 = src[(b + 2) * UW]; h3 = src[(b + 3) * UW];
-            }
-            bcur = b;
-            const float4 w4 = yw[yy];
-            const float wt[4] = {w4.x, w4.y, w4.z, w4.w};
-            store(c, yy, xx, dot4(wt, h0, h1, h2, h3));
-        }
+        const float* p = V + yy * MAXLRX + xb[xx];
+        store(yy, xx, dot4(wt, p[0], p[1], p[2], p[3]));
     }
 }
 

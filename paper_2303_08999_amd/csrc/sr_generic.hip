@@ -27,7 +27,7 @@ __global__ __launch_bounds__(GNT) void k_assemble_generic(const AssembleArgs a) 
     constexpr int MAXLRX = (UW - 1) / 2 + 5;
 
     __shared__ float lrT[MAXLRY * MAXLRX];
-    __shared__ float hbuf[MAXLRY * UW];
+    __shared__ float V[UH * MAXLRX];
     __shared__ float U[UH * UW];
     __shared__ float4 xw[UW], yw[UH];
     __shared__ int xb[UW], yb[UH];
@@ -55,16 +55,16 @@ __global__ __launch_bounds__(GNT) void k_assemble_generic(const AssembleArgs a) 
     }
 
     // ---- stages 1 + 4, one channel at a time -------------------------------
-    const TileOrigin o = tile_origin(Y0, X0, R, UH, a.H, a.W, a.s);
+    const TileOrigin o = tile_origin(Y0, X0, R, UH, UW, a.H, a.W, a.s);
     build_taps<UW, MAXLRX, GNT>(X0, R, a.W, a.s, o.lx0, xw, xb, tid);
     build_taps<UH, MAXLRY, GNT>(Y0, R, a.H, a.s, o.ly0, yw, yb, tid);
     for (int c = 0; c < a.C; ++c) {
         const TIO* lrp = (const TIO*)a.lr + ((size_t)n * a.C + c) * (size_t)a.h * a.w;
         load_lr_tile<TIO, MAXLRY, MAXLRX, GNT>(lrp, a.h, a.w, o, lrT, tid);
         __syncthreads();
-        hpass<MAXLRX, UW, GNT>(lrT, hbuf, xw, xb, o.nly, tid);
+        vpass<MAXLRX, UH, GNT>(lrT, V, yw, yb, tid);
         __syncthreads();
-        vpass<UW, UH, GNT>(hbuf, yw, yb, tid, [&](int yy, int xx, float v) { U[yy * UW + xx] = v; });
+        hpass<MAXLRX, UW, UH, GNT>(V, xw, xb, tid, [&](int yy, int xx, float v) { U[yy * UW + xx] = v; });
         __syncthreads();
         if (valid) {
             float acc = 0.0f;
@@ -75,8 +75,8 @@ __global__ __launch_bounds__(GNT) void k_assemble_generic(const AssembleArgs a) 
                     acc = fmaf(F[dy * K + dx], U[(ty + dy) * UW + tx + dx], acc);
             st_from_float((TIO*)a.out, ((size_t)n * a.C + c) * plane + (size_t)Y * a.W + X, acc);
         }
-        // The next channel's lrT/hbuf writes do not touch U; two barriers separate
-        // this read of U from the next vpass.
+        // The next channel's lrT/V writes do not touch U; two barriers separate
+        // this read of U from the next horizontal pass.
     }
 }
 
@@ -93,18 +93,18 @@ __global__ __launch_bounds__(256) void k_bicubic(const BicubicArgs a) {
     float wx[4], wy[4];
     keys_weights(mx, a.s, wx);
     keys_weights(my, a.s, wy);
-    int xs[4];
+    size_t rows[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) xs[j] = clampi(fx - 1 + j, 0, a.w - 1);
-    float hrow[4];
+    for (int i = 0; i < 4; ++i) rows[i] = (size_t)clampi(fy - 1 + i, 0, a.h - 1) * a.w;
+    float vcol[4];   // vertical pass first, as in the tiled kernels
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const size_t row = (size_t)clampi(fy - 1 + i, 0, a.h - 1) * a.w;
-        hrow[i] = dot4(wx, ld_as_float(p, row + xs[0]), ld_as_float(p, row + xs[1]),
-                       ld_as_float(p, row + xs[2]), ld_as_float(p, row + xs[3]));
+    for (int j = 0; j < 4; ++j) {
+        const int xs = clampi(fx - 1 + j, 0, a.w - 1);
+        vcol[j] = dot4(wy, ld_as_float(p, rows[0] + xs), ld_as_float(p, rows[1] + xs),
+                       ld_as_float(p, rows[2] + xs), ld_as_float(p, rows[3] + xs));
     }
     st_from_float((TO*)a.out, ((size_t)nc * a.H + Y) * a.W + X,
-                  dot4(wy, hrow[0], hrow[1], hrow[2], hrow[3]));
+                  dot4(wx, vcol[0], vcol[1], vcol[2], vcol[3]));
 }
 
 template <typename TC, typename TIO>

@@ -39,6 +39,16 @@
 #include "sr_device.h"
 #include "sr_launch.h"
 
+#ifndef SR_DBG_NHL
+#define SR_DBG_NHL 2
+#endif
+#ifndef SR_DBG_PXQ
+#define SR_DBG_PXQ PX
+#endif
+#ifndef SR_DBG_NSLOT
+#define SR_DBG_NSLOT F::NSLOT
+#endif
+
 namespace srd {
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -94,7 +104,7 @@ __device__ __forceinline__ int tap_of_row(int i, int mb) {
     return dy < K ? dy * K + dx : -1;
 }
 
-struct TilePos { int n, Y0, X0; };
+struct TilePos { int n, ty, tx; };
 
 template <int K, int C, int NP8, int PX, int WR, int NW, int WPE>
 __global__ __launch_bounds__(64 * NW, WPE)
@@ -105,20 +115,26 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     constexpr int N16 = F::N16, N8 = F::N8, NMB = F::NMB;
     constexpr int MAXLRY = F::MAXLRY, MAXLRX = F::MAXLRX;
 
-    __shared__ float U[C * UH * P];
-    __shared__ float hbuf[C * MAXLRY * UW];
-    __shared__ float lrT[C * MAXLRY * MAXLRX];
-    __shared__ float4 xw[UW], yw[UH];
-    __shared__ int xb[UW], yb[UH];
+    __shared__ float U[C * UH * P];                 // up-sampled tile, column-swizzled
+    __shared__ float V[C * UH * MAXLRX];            // after the vertical pass
+    __shared__ float lrT[C * MAXLRY * MAXLRX];      // LR footprint (clamped reads)
+    __shared__ float4 xw[UW], yw[UH];               // per-column / per-row tap weights
+    __shared__ int xb[UW], yb[UH];                  // ... and first source index
+    __shared__ float4 wk[8];                        // Keys weights by phase numerator m
     __shared__ u32x4 A16[(N16 ? N16 : 1) * NMB * 2 * 64];
     __shared__ u32x2 A8[NMB * 2 * 64];
-    __shared__ unsigned ptab[2 * F::NLOAD];   // byte offset of the plane each lane half loads
+    __shared__ unsigned ptab[2 * F::NLOAD];         // byte offset of the plane each lane half loads
 
     const int tid0 = threadIdx.x;
     if ((int)blockIdx.x >= ntiles) return;
 
-    // ---- once per workgroup: plane offsets and dictionary operand tables ---------
+    // ---- once per workgroup: weight, plane-offset and dictionary operand tables ---
     const unsigned plane_b = (unsigned)a.H * (unsigned)a.W * 2u;   // bytes per coefficient plane
+    if (tid0 < 2 * a.s) {
+        float wt[4];
+        keys_weights(tid0, a.s, wt);
+        wk[tid0] = make_float4(wt[0], wt[1], wt[2], wt[3]);
+    }
     for (int e = tid0; e < 2 * F::NLOAD; e += NT) {
         const int h = e / F::NLOAD, i = e - h * F::NLOAD;
         // load i of half h serves folded atom idx; padding atoms re-read the last plane
@@ -159,102 +175,184 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     }
     __syncthreads();
 
+#ifdef SR_DBG_STAGGER
+    for (int k = (int)(blockIdx.x % SR_DBG_STAGGER); k > 0; --k) __builtin_amdgcn_s_sleep(SR_DBG_SLEEP);
+#endif
+    // ---- tile walk: this workgroup takes tiles blockIdx.x, +gridDim.x, ...  The
+    //      step is pre-split into (image, tile row, tile column) so that no
+    //      division is left in the loop.  All of it is scalar.
     const int per_img = tiles_x * tiles_y;
-    auto tile_pos = [&](int t) -> TilePos {
-        TilePos p;
-        p.n = t / per_img;
-        const int r2 = t - p.n * per_img, tyi = r2 / tiles_x;
-        p.Y0 = tyi * F::TH;
-        p.X0 = (r2 - tyi * tiles_x) * F::TW;
+    const int G = gridDim.x;
+    const int step_n = G / per_img, step_r = G - step_n * per_img;
+    const int step_y = step_r / tiles_x, step_x = step_r - step_y * tiles_x;
+    auto advance = [&](TilePos p) -> TilePos {
+        p.tx += step_x;
+        if (p.tx >= tiles_x) { p.tx -= tiles_x; p.ty += 1; }
+        p.ty += step_y;
+        if (p.ty >= tiles_y) { p.ty -= tiles_y; p.n += 1; }
+        p.n += step_n;
         return p;
     };
+    TilePos cur;
+    {
+        const int t0 = blockIdx.x;
+        cur.n = t0 / per_img;
+        const int r2 = t0 - cur.n * per_img;
+        cur.ty = r2 / tiles_x;
+        cur.tx = r2 - cur.ty * tiles_x;
+    }
 
-    // LR footprint of a tile -> registers.  Wavefront w takes (channel,row) pairs
-    // w, w+NW, ...; the lane is the column.  Everything but the column is scalar.
-    auto load_lr = [&](const TilePos tp, int lane, int wave, float (&lrv)[F::NLRP][F::NXC]) {
-        const TileOrigin o = tile_origin(tp.Y0, tp.X0, F::R, UH, a.H, a.W, a.s);
-        int xo[F::NXC];
+    const int wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);     // scalar, loop-invariant
+    const char* lr_base = (const char*)a.lr;
+    const unsigned lr_esz = a.io_f16 ? 2u : 4u;
+
+    // LR footprint of a tile -> registers, as raw bits (fp16 is widened when it is
+    // written to LDS).  Wavefront w takes (channel,row) pairs w, w+NW, ...; the lane
+    // is the column.  Row addressing is scalar; one add per load on the vector side.
+    auto load_lr = [&](const TilePos tp, int lane, unsigned (&lrv)[F::NLRP][F::NXC]) {
+        const TileOrigin o = tile_origin(tp.ty * F::TH, tp.tx * F::TW, F::R, UH, UW, a.H, a.W, a.s);
+        unsigned xo[F::NXC];
 #pragma unroll
-        for (int xc = 0; xc < F::NXC; ++xc) xo[xc] = clampi(o.lx0 + lane + 64 * xc, 0, a.w - 1);
+        for (int xc = 0; xc < F::NXC; ++xc) xo[xc] = (unsigned)clampi(o.lx0 + lane + 64 * xc, 0, a.w - 1) * lr_esz;
 #pragma unroll
         for (int u = 0; u < F::NLRP; ++u) {
             const int p = wave + NW * u, c = p / MAXLRY, ry = p - c * MAXLRY;
-#pragma unroll
-            for (int xc = 0; xc < F::NXC; ++xc) lrv[u][xc] = 0.0f;
             if (p < C * MAXLRY && ry < o.nly) {
-                const size_t row = (((size_t)tp.n * C + c) * a.h + clampi(o.ly0 + ry, 0, a.h - 1)) * (size_t)a.w;
+                const unsigned row = ((unsigned)(tp.n * C + c) * (unsigned)a.h +
+                                      (unsigned)clampi(o.ly0 + ry, 0, a.h - 1)) * (unsigned)a.w * lr_esz;
 #pragma unroll
-                for (int xc = 0; xc < F::NXC; ++xc)
-                    lrv[u][xc] = a.io_f16 ? __half2float(((const __half*)a.lr + row)[xo[xc]])
-                                          : ((const float*)a.lr + row)[xo[xc]];
+                for (int xc = 0; xc < F::NXC; ++xc) {
+                    const char* q = lr_base + (size_t)(row + xo[xc]);
+                    lrv[u][xc] = a.io_f16 ? (unsigned)*(const unsigned short*)q : *(const unsigned*)q;
+                }
             }
         }
     };
 
     // coefficient base of a tile for this lane: image base (scalar) + pixel offset
-    auto phi_base = [&](const TilePos tp, int wave, int jr, int jc, unsigned& pix_off) -> const char* {
-        const int y = tp.Y0 + wave * WR + jr, x = tp.X0 + PX * jc;
+    auto phi_base = [&](const TilePos tp, int jr, int jc, unsigned& pix_off) -> const char* {
+        const int y = tp.ty * F::TH + wave * WR + jr, x = tp.tx * F::TW + PX * jc;
         const int yc = y < a.H ? y : a.H - 1, xc = x < a.W ? x : a.W - PX;   // out-of-image lanes re-read
         pix_off = ((unsigned)yc * (unsigned)a.W + (unsigned)xc) * 2u;         // a valid address; never stored
         return (const char*)a.coeff + (size_t)tp.n * a.L * (size_t)plane_b;
     };
 
     Raw raw[F::NLOAD];
-    float lrv[F::NLRP][F::NXC];
+    unsigned lrv[F::NLRP][F::NXC];
+#pragma unroll
+    for (int u = 0; u < F::NLRP; ++u)
+#pragma unroll
+        for (int xc = 0; xc < F::NXC; ++xc) lrv[u][xc] = 0u;
     {
-        const int lane = tid0 & 63, wave = tid0 >> 6, hf = lane >> 5, j = lane & 31;
-        const TilePos tp = tile_pos(blockIdx.x);
-        load_lr(tp, lane, wave, lrv);
+        const int lane = tid0 & 63, hf = lane >> 5, j = lane & 31;
+        load_lr(cur, lane, lrv);
         unsigned pix_off;
-        const char* cimg = phi_base(tp, wave, j / F::WC, j % F::WC, pix_off);
+        const char* cimg = phi_base(cur, j / F::WC, j % F::WC, pix_off);
         const unsigned* pt = ptab + hf * F::NLOAD;
 #pragma unroll
         for (int i = 0; i < F::NLOAD; ++i)
             raw[i] = __builtin_nontemporal_load((const Raw*)(cimg + (pix_off + pt[i])));
     }
 
-    for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
+#ifdef SR_DBG_TIMING
+    unsigned long long tacc[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#define SR_TICK(i) { unsigned long long now_ = __builtin_readcyclecounter(); tacc[i] += now_ - tprev_; tprev_ = now_; }
+#else
+#define SR_TICK(i)
+#endif
+    for (int t = blockIdx.x; t < ntiles; t += G) {
+#ifdef SR_DBG_TIMING
+        unsigned long long tprev_ = __builtin_readcyclecounter();
+#endif
         // Per-iteration copy of the thread id the optimiser cannot see through:
         // index arithmetic derived from it is recomputed each tile instead of
         // being hoisted out of the loop into dozens of long-lived registers.
         int tid = tid0;
         asm volatile("" : "+v"(tid));
-        const int lane = tid & 63, wave = tid >> 6;
+        const int lane = tid & 63;
         const int hf = lane >> 5, j = lane & 31, jr = j / F::WC, jc = j % F::WC;
-        const TilePos tp = tile_pos(t);
-        const TileOrigin o = tile_origin(tp.Y0, tp.X0, F::R, UH, a.H, a.W, a.s);
+        const int Y0 = cur.ty * F::TH, X0 = cur.tx * F::TW;
+        const TileOrigin o = tile_origin(Y0, X0, F::R, UH, UW, a.H, a.W, a.s);
 
-        // (1) stage 1: up-sampled patch tile -> LDS.  This tile's coefficient loads
-        //     were issued one iteration ago and stay in flight meanwhile.
-        build_taps<UW, MAXLRX, NT>(tp.X0, F::R, a.W, a.s, o.lx0, xw, xb, tid);
-        build_taps<UH, MAXLRY, NT>(tp.Y0, F::R, a.H, a.s, o.ly0, yw, yb, tid);
+        // (1) stage 1 set-up: LR footprint registers -> LDS, tap tables of the tile
+        if (tid < UW) {
+            int m;
+            const int f = src_floor(clampi(X0 - F::R + tid, 0, a.W - 1), a.s, m);
+            xw[tid] = wk[m];
+            xb[tid] = clampi(f - 1 - o.lx0, 0, MAXLRX - 4);
+        }
+        if (tid >= NT - 64 && tid - (NT - 64) < UH) {
+            const int i = tid - (NT - 64);
+            int m;
+            const int f = src_floor(clampi(Y0 - F::R + i, 0, a.H - 1), a.s, m);
+            yw[i] = wk[m];
+            yb[i] = clampi(f - 1 - o.ly0, 0, MAXLRY - 4);
+        }
 #pragma unroll
         for (int u = 0; u < F::NLRP; ++u) {
             const int p = wave + NW * u;
             if (p < C * MAXLRY) {
 #pragma unroll
                 for (int xc = 0; xc < F::NXC; ++xc)
-                    if (lane + 64 * xc < MAXLRX) lrT[p * MAXLRX + lane + 64 * xc] = lrv[u][xc];
+                    if (lane + 64 * xc < MAXLRX) {
+                        const unsigned bits = lrv[u][xc];
+                        lrT[p * MAXLRX + lane + 64 * xc] =
+                            a.io_f16 ? __half2float(__ushort_as_half((unsigned short)bits)) : __uint_as_float(bits);
+                    }
+            }
+        }
+        SR_TICK(7)
+        // (2) prefetch the next tile's LR footprint now: it lands while this tile is
+        //     up-sampled, before the matrix-core phase waits on outstanding loads
+        const bool more = t + G < ntiles;
+        const TilePos nxt = more ? advance(cur) : cur;
+        if (more) load_lr(nxt, lane, lrv);
+        SR_TICK(0)
+#ifndef SR_DBG_SKIP_U
+        __syncthreads();
+        SR_TICK(5)
+        // vertical pass on the narrow LR footprint: V[c][yy][rx]
+        {
+            const int sh = o.nlx <= 32 ? 5 : (o.nlx <= 64 ? 6 : 7);
+            const int total = (C * UH) << sh;
+            for (int idx = tid; idx < total; idx += NT) {
+                const int pr = idx >> sh, rx = idx & ((1 << sh) - 1);
+                if (rx < MAXLRX) {
+                    const int c = pr / UH, yy = pr - c * UH;
+                    const float4 w4 = yw[yy];
+                    const float wt[4] = {w4.x, w4.y, w4.z, w4.w};
+                    const float* p = lrT + (c * MAXLRY + yb[yy]) * MAXLRX + rx;
+                    V[pr * MAXLRX + rx] = dot4(wt, p[0], p[MAXLRX], p[2 * MAXLRX], p[3 * MAXLRX]);
+                }
             }
         }
         __syncthreads();
-        hpass_cols<C, MAXLRY, MAXLRX, UW, NT>(lrT, hbuf, xw, xb, o.nly, tid);
+        SR_TICK(6)
+        // horizontal pass: a thread owns one (channel, column), its weights stay in
+        // registers, rows are independent (no tables, immediate offsets)
+        for (int col = tid; col < C * UW; col += NT) {
+            const int c = col / UW, xx = col - c * UW;
+            const float4 w4 = xw[xx];
+            const float wt[4] = {w4.x, w4.y, w4.z, w4.w};
+            const float* src = V + c * UH * MAXLRX + xb[xx];
+            float* dst = U + c * UH * P + (xx % PX) * NG + xx / PX;
+#pragma unroll
+            for (int yy = 0; yy < UH; ++yy) {
+                const float* p = src + yy * MAXLRX;
+                dst[yy * P] = dot4(wt, p[0], p[1], p[2], p[3]);
+            }
+        }
         __syncthreads();
-        vpass_cols<C, MAXLRY, UW, UH, NT>(hbuf, yw, yb, tid, [&](int c, int yy, int xx, float v) {
-            U[c * UH * P + yy * P + (xx % PX) * NG + xx / PX] = v;
-        });
-        __syncthreads();
-
-        // (2) prefetch for the next tile of this workgroup: LR footprint now, the
-        //     coefficient steps as their registers fall free below
-        const int tn = t + gridDim.x;
-        const bool more = tn < ntiles;
-        const TilePos tq = tile_pos(more ? tn : t);
-        if (more) load_lr(tq, lane, wave, lrv);
+#endif
+        SR_TICK(1)
+        //     ... and its coefficient steps as their registers fall free below
         unsigned pix_next;
-        const char* cnext = phi_base(tq, wave, jr, jc, pix_next);
+        const char* cnext = phi_base(nxt, jr, jc, pix_next);
         const unsigned* pt = ptab + hf * F::NLOAD;
 
+#ifdef SR_DBG_LOADONLY
+        unsigned dbg_sink = 0;
+#endif
         // (3) stage 3 on the matrix cores: atom steps outer, pixel slots inner
         f32x16 acc[PX][NMB];
 #pragma unroll
@@ -271,8 +369,12 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 #pragma unroll
                 for (int hl = 0; hl < 2; ++hl)
                     av[mb][hl] = __builtin_bit_cast(f16x8, A16[((c16 * NMB + mb) * 2 + hl) * 64 + lane]);
+#ifdef SR_DBG_LOADONLY
 #pragma unroll
-            for (int q = 0; q < PX; ++q) {
+            for (int i = 0; i < 8; ++i) dbg_sink ^= raw_word(raw[8 * c16 + i], 0) ^ raw_word(raw[8 * c16 + i], (PX / 2) - 1);
+#endif
+#pragma unroll
+            for (int q = 0; q < SR_DBG_PXQ; ++q) {
                 u32x4 bw;
 #pragma unroll
                 for (int m = 0; m < 4; ++m)
@@ -282,16 +384,18 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 #pragma unroll
                 for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
-                    for (int hl = 0; hl < 2; ++hl)
+                    for (int hl = 0; hl < SR_DBG_NHL; ++hl)
                         acc[q][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[mb][hl], b, acc[q][mb], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
+            SR_TICK(8)
             if (more) {
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
                     raw[8 * c16 + i] = __builtin_nontemporal_load((const Raw*)(cnext + (pix_next + pt[8 * c16 + i])));
             }
             __builtin_amdgcn_sched_barrier(0);
+            SR_TICK(9)
         }
         if (N8) {
             f16x4 av[NMB][2];
@@ -300,8 +404,12 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 #pragma unroll
                 for (int hl = 0; hl < 2; ++hl)
                     av[mb][hl] = __builtin_bit_cast(f16x4, A8[(mb * 2 + hl) * 64 + lane]);
+#ifdef SR_DBG_LOADONLY
 #pragma unroll
-            for (int q = 0; q < PX; ++q) {
+            for (int i = 0; i < 4; ++i) dbg_sink ^= raw_word(raw[8 * N16 + i], 0) ^ raw_word(raw[8 * N16 + i], (PX / 2) - 1);
+#endif
+#pragma unroll
+            for (int q = 0; q < SR_DBG_PXQ; ++q) {
                 u32x2 bw;
 #pragma unroll
                 for (int m = 0; m < 2; ++m)
@@ -311,7 +419,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 #pragma unroll
                 for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
-                    for (int hl = 0; hl < 2; ++hl)
+                    for (int hl = 0; hl < SR_DBG_NHL; ++hl)
                         acc[q][mb] = __builtin_amdgcn_mfma_f32_32x32x8f16(av[mb][hl], b, acc[q][mb], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -322,6 +430,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+        SR_TICK(2)
 
         // (4) stage 4: each half filters its taps against the LDS tile, channel by
         //     channel (a lane's PX slots share most of their patch values)
@@ -333,7 +442,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             for (int q = 0; q < PX; ++q) {
                 float s = 0.0f;
 #pragma unroll
-                for (int vv = 0; vv < F::NSLOT; ++vv) {
+                for (int vv = 0; vv < SR_DBG_NSLOT; ++vv) {
                     const int dyv = vv / K, dxv = vv % K;
                     const int off = c * UH * P + dyv * P + ((q + dxv) % PX) * NG + (q + dxv) / PX;
                     s = fmaf(acc[q][vv / 16][vv % 16], ub[off], s);
@@ -342,27 +451,37 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+        SR_TICK(3)
 
-        // (5) add the two halves' partial sums; half 0 keeps pixels 0..PX/2-1 of the
-        //     lane's group, half 1 the rest; one vector store per channel
-        const int y = tp.Y0 + wave * WR + jr, x = tp.X0 + PX * jc;
+        // (5) add the two halves' partial sums: one cross-half swap per slot pair
+        //     leaves half 0 with pixels 0..PX/2-1 of the lane's group and half 1
+        //     with the rest; one vector store per channel
+        const int y = Y0 + wave * WR + jr, x = X0 + PX * jc;
         const bool valid = y < a.H && x < a.W;
-        const int swap_addr = (lane ^ 32) << 2;
-        const size_t plane_px = (size_t)a.H * a.W;
-        const size_t o0 = ((size_t)tp.n * C * a.H + y) * (size_t)a.W + x + hf * (PX / 2);
+        const unsigned plane_px = (unsigned)a.H * (unsigned)a.W;
+        const unsigned o0 = ((unsigned)(cur.n * C) * (unsigned)a.H + (unsigned)y) * (unsigned)a.W + x + hf * (PX / 2);
 #pragma unroll
         for (int c = 0; c < C; ++c) {
             float tot[PX / 2];
 #pragma unroll
             for (int q = 0; q < PX / 2; ++q) {
-                const float mine = hf ? outp[c][q + PX / 2] : outp[c][q];
-                const float send = hf ? outp[c][q] : outp[c][q + PX / 2];
-                tot[q] = mine + __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(
-                                    swap_addr, __builtin_bit_cast(int, send)));
+                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(outp[c][q]),
+                                                                 __float_as_uint(outp[c][q + PX / 2]), false, false);
+                tot[q] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
             }
+#if defined(SR_DBG_LOADONLY) && !defined(SR_DBG_LOADONLY_ST)
+            if (dbg_sink == 0x12345678u) {
+#elif defined(SR_DBG_LOADONLY)
+            tot[0] += __uint_as_float(dbg_sink & 0xffu);
             if (valid) {
+#elif defined(SR_DBG_NOSTORE)
+            if (valid && tot[0] == 123.456f) {
+#else
+            if (valid) {
+#endif
+                const unsigned oe = o0 + c * plane_px;
                 if (a.io_f16) {
-                    __half* op = (__half*)a.out + o0 + c * plane_px;
+                    __half* op = (__half*)((char*)a.out + (size_t)(oe * 2u));
                     if constexpr (PX >= 4) {
 #pragma unroll
                         for (int q = 0; q < PX / 2; q += 2) {
@@ -375,14 +494,27 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                         op[0] = narrow_f16(tot[0]);
                     }
                 } else {
-                    float* op = (float*)a.out + o0 + c * plane_px;
+                    float* op = (float*)((char*)a.out + (size_t)(oe * 4u));
+#ifdef SR_DBG_NTSTORE
+                    if constexpr (PX == 4) { __builtin_nontemporal_store(tot[0], op); __builtin_nontemporal_store(tot[1], op + 1); }
+                    else
+#endif
                     if constexpr (PX == 8) *(float4*)op = make_float4(tot[0], tot[1], tot[2], tot[3]);
                     else if constexpr (PX == 4) *(float2*)op = make_float2(tot[0], tot[1]);
                     else op[0] = tot[0];
                 }
             }
         }
+        cur = nxt;
+        SR_TICK(4)
     }
+#ifdef SR_DBG_TIMING
+    __syncthreads();
+    if ((tid0 & 63) == 0) {
+        float* dbg = (float*)a.out + ((size_t)blockIdx.x * NW + (tid0 >> 6)) * 16;
+        for (int i = 0; i < 10; ++i) dbg[i] = (float)tacc[i];
+    }
+#endif
 }
 
 // ---------------------------------------------------------------------------
@@ -414,7 +546,7 @@ int np8_for(int k, int n_fold) {
     return 0;
 }
 
-constexpr int N_TILE_SHAPES = 4;
+constexpr int N_TILE_SHAPES = 10;
 
 }  // namespace
 
@@ -423,6 +555,7 @@ bool mfma_supported(const AssembleArgs& a, int k, bool coeff_f16, int tile) {
     if (a.W % 8 != 0 || a.W < 8 || a.H < 1) return false;
     if (((uintptr_t)a.coeff % 16) != 0 || ((uintptr_t)a.out % 16) != 0) return false;
     if ((unsigned long long)a.L * a.H * a.W * 2ull >= (1ull << 32)) return false;   // 32-bit plane offsets
+    if ((unsigned long long)a.N * a.C * a.H * a.W * 4ull >= (1ull << 32)) return false;   // 32-bit image offsets
     if (np8_for(k, a.n_fold) == 0) return false;
     if (tile < 0 || tile >= N_TILE_SHAPES) return false;
     return true;
@@ -437,6 +570,12 @@ hipError_t launch_mfma(const AssembleArgs& a, int k, bool io_f16, int tile, hipS
             case 1:  return launch_one<5, 3, 9, 4, 1, 4>(a, st);    // 128 x 4
             case 2:  return launch_one<5, 3, 9, 4, 2, 8>(a, st);    //  64 x 16, 8 wavefronts
             case 3:  return launch_one<5, 3, 9, 4, 1, 8>(a, st);    // 128 x 8,  8 wavefronts
+            case 4:  return launch_one<5, 3, 9, 2, 2, 8, 4>(a, st); //  32 x 16, 8 wavefronts, 4 per SIMD
+            case 5:  return launch_one<5, 3, 9, 2, 2, 4, 4>(a, st); //  32 x 8
+            case 6:  return launch_one<5, 3, 9, 2, 1, 8, 4>(a, st); //  64 x 8
+            case 7:  return launch_one<5, 3, 9, 2, 1, 4, 4>(a, st); //  64 x 4
+            case 8:  return launch_one<5, 3, 9, 2, 2, 8, 3>(a, st); //  32 x 16, 3 per SIMD
+            case 9:  return launch_one<5, 3, 9, 4, 2, 4, 3>(a, st); //  64 x 8, 3 per SIMD
             default: return launch_one<5, 3, 9, 4, 2, 4>(a, st);    //  64 x 8
             }
         }
