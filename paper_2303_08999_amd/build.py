@@ -8,11 +8,12 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsrdict.so")
-SOURCES = ["sr_api.hip", "sr_generic.hip", "sr_mfma.hip"]
-HEADERS = ["sr_device.h", "sr_launch.h", os.path.join("..", "..", "include", "sr_dict.h")]
+SOURCES = ["sr_api.hip", "sr_generic.hip", "sr_mfma.hip", "sr_mfma_k5.hip", "sr_mfma_k7.hip"]
+HEADERS = ["sr_device.h", "sr_launch.h", "sr_mfma_kernel.h", os.path.join("..", "..", "include", "sr_dict.h")]
+OBJDIR = os.path.join(HERE, "_build")
 
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-ffp-contract=off", "-fvisibility=hidden", "-fno-gpu-rdc",
     # packed-fp32 VALU forms are kept out of the generated code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -35,12 +36,7 @@ def stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build_library(force: bool = True, verbose: bool = False, extra=()) -> str:
-    """Compile every HIP source into one shared library.  Returns its path."""
-    if not force and not stale():
-        return LIB
-    tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [hipcc()] + FLAGS + list(extra) + ["-o", tmp] + [os.path.join(CSRC, s) for s in SOURCES]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -48,12 +44,33 @@ def build_library(force: bool = True, verbose: bool = False, extra=()) -> str:
     err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
     if res.returncode != 0:
         sys.stderr.write(err + "\n")
-        raise RuntimeError("hipcc failed")
+        raise RuntimeError("hipcc failed: " + " ".join(cmd[-3:]))
     if verbose and err.strip():
         sys.stderr.write(err + "\n")
-    os.replace(tmp, LIB)
-    return LIB
+
+
+def build_library(force: bool = True, verbose: bool = False, extra=(), out: str = LIB) -> str:
+    """Compile every HIP source (in parallel) and link one shared library.  Returns its path."""
+    if not force and out == LIB and not stale():
+        return LIB
+    from concurrent.futures import ThreadPoolExecutor
+    objdir = OBJDIR + ("" if out == LIB else "_" + os.path.basename(out))
+    os.makedirs(objdir, exist_ok=True)
+    cc = hipcc()
+    objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in SOURCES]
+    cmds = [[cc] + FLAGS + list(extra) + ["-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
+    with ThreadPoolExecutor(max_workers=min(8, len(cmds))) as pool:
+        list(pool.map(lambda c: _run(c, verbose), cmds))
+    tmp = out + ".tmp%d" % os.getpid()
+    _run([cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fvisibility=hidden", "-o", tmp] + objs, verbose)
+    os.replace(tmp, out)
+    return out
 
 
 if __name__ == "__main__":
-    print(build_library(force=True, verbose=True))
+    # python -m paper_2303_08999_amd.build [-o other.so] [extra hipcc flags ...]
+    args = sys.argv[1:]
+    target = LIB
+    if args[:1] == ["-o"]:
+        target, args = os.path.abspath(args[1]), args[2:]
+    print(build_library(force=True, verbose=False, extra=args, out=target))

@@ -1,552 +1,29 @@
-// Matrix-core kernel for fp16 coefficients (gfx950 / CDNA4).
-//
-// One fused, persistent kernel does stage 1 (up-sampling), stage 3
-// (F_i = Phi_i D, paper Eq. 2) and stage 4 (y_i = F_i B_i^T) for tiles of HR
-// pixels; neither F nor B of Eq. 3 ever reaches memory.  The only large stream
-// is the coefficient tensor Phi (L planes, fp16), read exactly once.
-//
-// Stage 3 is a (taps x atoms) . (atoms x pixels) product per wavefront:
-//
-//     A = D^T, rows = filter taps (padded to 32), K = atoms  (constant per launch)
-//     B = Phi, K = atoms, columns = 32 pixels                 (streamed from HBM)
-//     v_mfma_f32_32x32x16_f16 (+ one v_mfma_f32_32x32x8_f16 when L % 16 == 8)
-//
-// The dictionary is fp32; it enters as hi + lo fp16 halves (two MFMAs per
-// step), so the only rounding left is the one already in the stored fp16
-// coefficients; accumulation is fp32.
-//
-// Lane roles.  Lane (j, hf) = (lane % 32, lane / 32):
-//   * as B operand it supplies atoms 8*hf .. 8*hf+7 of a 16-atom step for pixel
-//     j, so lanes j and j+32 load different coefficient planes of the SAME
-//     pixels: each lane loads PX consecutive pixels of a plane with one vector
-//     load and re-packs (atom pair, pixel) with v_perm_b32;
-//   * the MFMA result leaves pixel j's taps split over lanes j and j+32
-//     (rows 8*(v/4) + 4*hf + v%4).  Dictionary rows are ordered so that half 0
-//     owns filter rows 0 .. RH0-1 and half 1 owns rows RH0 .. (one dummy row
-//     with zero weights): both halves then use the same LDS offsets, shifted by
-//     RH0 tile rows.  Each half filters its taps against the LDS patch tile
-//     and the two partial sums are exchanged across the halves.
-//
-// Software pipeline.  The atom steps are the outer loop and the PX pixel slots
-// the inner one, so the registers of a step are free as soon as its MFMAs are
-// issued: the same step of the NEXT tile is loaded into them right away.  The
-// coefficient loads of tile t+1 are therefore in flight during stage 4 of tile
-// t and during the up-sampling of tile t+1; the LR footprint is prefetched one
-// tile ahead as well.
-//
-// The up-sampled tile is stored in LDS column-swizzled, (x % PX) major, so the
-// 32 pixels of one MFMA (stride PX in x) read consecutive banks.
-#include "sr_device.h"
+// Matrix-core path, host side: which kernel instantiation serves a call.
+// The kernel itself is in sr_mfma_kernel.h; its instantiations are compiled in
+// sr_mfma_k5.hip and sr_mfma_k7.hip.
 #include "sr_launch.h"
-
-#ifndef SR_DBG_NHL
-#define SR_DBG_NHL 2
-#endif
-#ifndef SR_DBG_PXQ
-#define SR_DBG_PXQ PX
-#endif
-#ifndef SR_DBG_NSLOT
-#define SR_DBG_NSLOT F::NSLOT
-#endif
 
 namespace srd {
 
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+hipError_t launch_mfma_k5(const AssembleArgs& a, int np8, int shape, hipStream_t st);
+hipError_t launch_mfma_k7(const AssembleArgs& a, int np8, int shape, hipStream_t st);
 
-template <int K, int C, int NP8, int PX, int WR, int NW>
-struct Cfg {
-    static constexpr int KK = K * K, R = (K - 1) / 2;
-    static constexpr int RH0 = (K + 1) / 2;            // filter rows owned by lane half 0
-    static constexpr int NSLOT = RH0 * K;              // accumulator rows used per half
-    static constexpr int NMB = (NSLOT + 15) / 16;      // 32-row MFMA blocks
-    static constexpr int WC = 32 / WR;                 // lane columns per wavefront
-    static constexpr int TW = WC * PX, TH = WR * NW;   // tile of HR pixels per workgroup
-    static constexpr int NT = 64 * NW;
-    static constexpr int UW = TW + K - 1;
-    static constexpr int UH = TH + K;                  // + one dummy row for half 1
-    static constexpr int NG = (UW + PX - 1) / PX;      // stride between x % PX classes
-    static constexpr int P0 = PX * NG;
-    // rows of one wavefront must land on disjoint banks: pitch == WC (mod 32)
-    static constexpr int P = WR == 1 ? P0 : P0 + ((WC - P0 % 32) + 32) % 32;
-    static constexpr int MAXLRY = (UH - 1) / 2 + 5, MAXLRX = (UW - 1) / 2 + 5;
-    static constexpr int N16 = NP8 / 2, N8 = NP8 % 2;  // 16-atom steps, optional 8-atom step
-    static constexpr int NLOAD = 8 * N16 + 4 * N8;     // coefficient loads per lane and tile
-    static constexpr int NXC = (MAXLRX + 63) / 64;     // 64-column chunks of the LR footprint
-    static constexpr int NLRP = (C * MAXLRY + NW - 1) / NW;   // (channel,row) pairs per wavefront
-};
-
-template <int PX> struct RawT;
-template <> struct RawT<8> { typedef u32x4 type; };
-template <> struct RawT<4> { typedef u32x2 type; };
-template <> struct RawT<2> { typedef unsigned type; };
-
-__device__ __forceinline__ unsigned raw_word(const u32x4& v, int m) { return v[m]; }
-__device__ __forceinline__ unsigned raw_word(const u32x2& v, int m) { return v[m]; }
-__device__ __forceinline__ unsigned raw_word(const unsigned& v, int) { return v; }
-
-// (atom pair, pixel q) from two planes' packed pixels
-__device__ __forceinline__ unsigned pack_pair(unsigned plane_even, unsigned plane_odd, int q) {
-    return __builtin_amdgcn_perm(plane_odd, plane_even, (q & 1) ? 0x07060302u : 0x05040100u);
-}
-
-// filter tap served by MFMA row i of block mb, or -1 (padding / dummy row)
-template <int K>
-__device__ __forceinline__ int tap_of_row(int i, int mb) {
-    constexpr int RH0 = (K + 1) / 2, NSLOT = RH0 * K;
-    const int half = (i >> 2) & 1;
-    const int vv = 16 * mb + (((i >> 3) << 2) | (i & 3));
-    if (vv >= NSLOT) return -1;
-    const int dy = half * RH0 + vv / K, dx = vv % K;
-    return dy < K ? dy * K + dx : -1;
-}
-
-struct TilePos { int n, ty, tx; };
-
-template <int K, int C, int NP8, int PX, int WR, int NW, int WPE>
-__global__ __launch_bounds__(64 * NW, WPE)
-void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y, const int ntiles) {
-    using F = Cfg<K, C, NP8, PX, WR, NW>;
-    using Raw = typename RawT<PX>::type;
-    constexpr int NT = F::NT, P = F::P, NG = F::NG, UH = F::UH, UW = F::UW;
-    constexpr int N16 = F::N16, N8 = F::N8, NMB = F::NMB;
-    constexpr int MAXLRY = F::MAXLRY, MAXLRX = F::MAXLRX;
-
-    __shared__ float U[C * UH * P];                 // up-sampled tile, column-swizzled
-    __shared__ float V[C * UH * MAXLRX];            // after the vertical pass
-    __shared__ float lrT[C * MAXLRY * MAXLRX];      // LR footprint (clamped reads)
-    __shared__ float4 xw[UW], yw[UH];               // per-column / per-row tap weights
-    __shared__ int xb[UW], yb[UH];                  // ... and first source index
-    __shared__ float4 wk[8];                        // Keys weights by phase numerator m
-    __shared__ u32x4 A16[(N16 ? N16 : 1) * NMB * 2 * 64];
-    __shared__ u32x2 A8[NMB * 2 * 64];
-    __shared__ unsigned ptab[2 * F::NLOAD];         // byte offset of the plane each lane half loads
-
-    const int tid0 = threadIdx.x;
-    if ((int)blockIdx.x >= ntiles) return;
-
-    // ---- once per workgroup: weight, plane-offset and dictionary operand tables ---
-    const unsigned plane_b = (unsigned)a.H * (unsigned)a.W * 2u;   // bytes per coefficient plane
-    if (tid0 < 2 * a.s) {
-        float wt[4];
-        keys_weights(tid0, a.s, wt);
-        wk[tid0] = make_float4(wt[0], wt[1], wt[2], wt[3]);
-    }
-    for (int e = tid0; e < 2 * F::NLOAD; e += NT) {
-        const int h = e / F::NLOAD, i = e - h * F::NLOAD;
-        // load i of half h serves folded atom idx; padding atoms re-read the last plane
-        const int idx = i < 8 * N16 ? 16 * (i >> 3) + 8 * h + (i & 7) : 16 * N16 + 4 * h + (i - 8 * N16);
-        ptab[e] = (unsigned)a.kept[idx < a.n_fold ? idx : a.n_fold - 1] * plane_b;
-    }
-    auto dval = [&](int idx, int tap) -> float {    // gamma * D[kept], zero for padding
-        if (tap < 0 || idx >= a.n_fold) return 0.0f;
-        return a.gamma[idx] * a.dict[(size_t)a.kept[idx] * F::KK + tap];
-    };
-    for (int e = tid0; e < N16 * NMB * 64; e += NT) {
-        const int l = e & 63, blk = e >> 6, mb = blk % NMB, c16 = blk / NMB;
-        const int tap = tap_of_row<K>(l & 31, mb);
-        f16x8 hi, lo;
-#pragma unroll
-        for (int jj = 0; jj < 8; ++jj) {
-            const float d = dval(16 * c16 + 8 * (l >> 5) + jj, tap);
-            hi[jj] = (_Float16)d;
-            lo[jj] = (_Float16)(d - (float)hi[jj]);
-        }
-        A16[(blk * 2 + 0) * 64 + l] = __builtin_bit_cast(u32x4, hi);
-        A16[(blk * 2 + 1) * 64 + l] = __builtin_bit_cast(u32x4, lo);
-    }
-    if (N8) {
-        for (int e = tid0; e < NMB * 64; e += NT) {
-            const int l = e & 63, mb = e >> 6;
-            const int tap = tap_of_row<K>(l & 31, mb);
-            f16x4 hi, lo;
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                const float d = dval(16 * N16 + 4 * (l >> 5) + jj, tap);
-                hi[jj] = (_Float16)d;
-                lo[jj] = (_Float16)(d - (float)hi[jj]);
-            }
-            A8[(mb * 2 + 0) * 64 + l] = __builtin_bit_cast(u32x2, hi);
-            A8[(mb * 2 + 1) * 64 + l] = __builtin_bit_cast(u32x2, lo);
-        }
-    }
-    __syncthreads();
-
-#ifdef SR_DBG_STAGGER
-    for (int k = (int)(blockIdx.x % SR_DBG_STAGGER); k > 0; --k) __builtin_amdgcn_s_sleep(SR_DBG_SLEEP);
-#endif
-    // ---- tile walk: this workgroup takes tiles blockIdx.x, +gridDim.x, ...  The
-    //      step is pre-split into (image, tile row, tile column) so that no
-    //      division is left in the loop.  All of it is scalar.
-    const int per_img = tiles_x * tiles_y;
-    const int G = gridDim.x;
-    const int step_n = G / per_img, step_r = G - step_n * per_img;
-    const int step_y = step_r / tiles_x, step_x = step_r - step_y * tiles_x;
-    auto advance = [&](TilePos p) -> TilePos {
-        p.tx += step_x;
-        if (p.tx >= tiles_x) { p.tx -= tiles_x; p.ty += 1; }
-        p.ty += step_y;
-        if (p.ty >= tiles_y) { p.ty -= tiles_y; p.n += 1; }
-        p.n += step_n;
-        return p;
-    };
-    TilePos cur;
-    {
-        const int t0 = blockIdx.x;
-        cur.n = t0 / per_img;
-        const int r2 = t0 - cur.n * per_img;
-        cur.ty = r2 / tiles_x;
-        cur.tx = r2 - cur.ty * tiles_x;
-    }
-
-    const int wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);     // scalar, loop-invariant
-    const char* lr_base = (const char*)a.lr;
-    const unsigned lr_esz = a.io_f16 ? 2u : 4u;
-
-    // LR footprint of a tile -> registers, as raw bits (fp16 is widened when it is
-    // written to LDS).  Wavefront w takes (channel,row) pairs w, w+NW, ...; the lane
-    // is the column.  Row addressing is scalar; one add per load on the vector side.
-    auto load_lr = [&](const TilePos tp, int lane, unsigned (&lrv)[F::NLRP][F::NXC]) {
-        const TileOrigin o = tile_origin(tp.ty * F::TH, tp.tx * F::TW, F::R, UH, UW, a.H, a.W, a.s);
-        unsigned xo[F::NXC];
-#pragma unroll
-        for (int xc = 0; xc < F::NXC; ++xc) xo[xc] = (unsigned)clampi(o.lx0 + lane + 64 * xc, 0, a.w - 1) * lr_esz;
-#pragma unroll
-        for (int u = 0; u < F::NLRP; ++u) {
-            const int p = wave + NW * u, c = p / MAXLRY, ry = p - c * MAXLRY;
-            if (p < C * MAXLRY && ry < o.nly) {
-                const unsigned row = ((unsigned)(tp.n * C + c) * (unsigned)a.h +
-                                      (unsigned)clampi(o.ly0 + ry, 0, a.h - 1)) * (unsigned)a.w * lr_esz;
-#pragma unroll
-                for (int xc = 0; xc < F::NXC; ++xc) {
-                    const char* q = lr_base + (size_t)(row + xo[xc]);
-                    lrv[u][xc] = a.io_f16 ? (unsigned)*(const unsigned short*)q : *(const unsigned*)q;
-                }
-            }
-        }
-    };
-
-    // coefficient base of a tile for this lane: image base (scalar) + pixel offset
-    auto phi_base = [&](const TilePos tp, int jr, int jc, unsigned& pix_off) -> const char* {
-        const int y = tp.ty * F::TH + wave * WR + jr, x = tp.tx * F::TW + PX * jc;
-        const int yc = y < a.H ? y : a.H - 1, xc = x < a.W ? x : a.W - PX;   // out-of-image lanes re-read
-        pix_off = ((unsigned)yc * (unsigned)a.W + (unsigned)xc) * 2u;         // a valid address; never stored
-        return (const char*)a.coeff + (size_t)tp.n * a.L * (size_t)plane_b;
-    };
-
-    Raw raw[F::NLOAD];
-    unsigned lrv[F::NLRP][F::NXC];
-#pragma unroll
-    for (int u = 0; u < F::NLRP; ++u)
-#pragma unroll
-        for (int xc = 0; xc < F::NXC; ++xc) lrv[u][xc] = 0u;
-    {
-        const int lane = tid0 & 63, hf = lane >> 5, j = lane & 31;
-        load_lr(cur, lane, lrv);
-        unsigned pix_off;
-        const char* cimg = phi_base(cur, j / F::WC, j % F::WC, pix_off);
-        const unsigned* pt = ptab + hf * F::NLOAD;
-#pragma unroll
-        for (int i = 0; i < F::NLOAD; ++i)
-            raw[i] = __builtin_nontemporal_load((const Raw*)(cimg + (pix_off + pt[i])));
-    }
-
-#ifdef SR_DBG_TIMING
-    unsigned long long tacc[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#define SR_TICK(i) { unsigned long long now_ = __builtin_readcyclecounter(); tacc[i] += now_ - tprev_; tprev_ = now_; }
-#else
-#define SR_TICK(i)
-#endif
-    for (int t = blockIdx.x; t < ntiles; t += G) {
-#ifdef SR_DBG_TIMING
-        unsigned long long tprev_ = __builtin_readcyclecounter();
-#endif
-        // Per-iteration copy of the thread id the optimiser cannot see through:
-        // index arithmetic derived from it is recomputed each tile instead of
-        // being hoisted out of the loop into dozens of long-lived registers.
-        int tid = tid0;
-        asm volatile("" : "+v"(tid));
-        const int lane = tid & 63;
-        const int hf = lane >> 5, j = lane & 31, jr = j / F::WC, jc = j % F::WC;
-        const int Y0 = cur.ty * F::TH, X0 = cur.tx * F::TW;
-        const TileOrigin o = tile_origin(Y0, X0, F::R, UH, UW, a.H, a.W, a.s);
-
-        // (1) stage 1 set-up: LR footprint registers -> LDS, tap tables of the tile
-        if (tid < UW) {
-            int m;
-            const int f = src_floor(clampi(X0 - F::R + tid, 0, a.W - 1), a.s, m);
-            xw[tid] = wk[m];
-            xb[tid] = clampi(f - 1 - o.lx0, 0, MAXLRX - 4);
-        }
-        if (tid >= NT - 64 && tid - (NT - 64) < UH) {
-            const int i = tid - (NT - 64);
-            int m;
-            const int f = src_floor(clampi(Y0 - F::R + i, 0, a.H - 1), a.s, m);
-            yw[i] = wk[m];
-            yb[i] = clampi(f - 1 - o.ly0, 0, MAXLRY - 4);
-        }
-#pragma unroll
-        for (int u = 0; u < F::NLRP; ++u) {
-            const int p = wave + NW * u;
-            if (p < C * MAXLRY) {
-#pragma unroll
-                for (int xc = 0; xc < F::NXC; ++xc)
-                    if (lane + 64 * xc < MAXLRX) {
-                        const unsigned bits = lrv[u][xc];
-                        lrT[p * MAXLRX + lane + 64 * xc] =
-                            a.io_f16 ? __half2float(__ushort_as_half((unsigned short)bits)) : __uint_as_float(bits);
-                    }
-            }
-        }
-        SR_TICK(7)
-        // (2) prefetch the next tile's LR footprint now: it lands while this tile is
-        //     up-sampled, before the matrix-core phase waits on outstanding loads
-        const bool more = t + G < ntiles;
-        const TilePos nxt = more ? advance(cur) : cur;
-        if (more) load_lr(nxt, lane, lrv);
-        SR_TICK(0)
-#ifndef SR_DBG_SKIP_U
-        __syncthreads();
-        SR_TICK(5)
-        // vertical pass on the narrow LR footprint: V[c][yy][rx]
-        {
-            const int sh = o.nlx <= 32 ? 5 : (o.nlx <= 64 ? 6 : 7);
-            const int total = (C * UH) << sh;
-            for (int idx = tid; idx < total; idx += NT) {
-                const int pr = idx >> sh, rx = idx & ((1 << sh) - 1);
-                if (rx < MAXLRX) {
-                    const int c = pr / UH, yy = pr - c * UH;
-                    const float4 w4 = yw[yy];
-                    const float wt[4] = {w4.x, w4.y, w4.z, w4.w};
-                    const float* p = lrT + (c * MAXLRY + yb[yy]) * MAXLRX + rx;
-                    V[pr * MAXLRX + rx] = dot4(wt, p[0], p[MAXLRX], p[2 * MAXLRX], p[3 * MAXLRX]);
-                }
-            }
-        }
-        __syncthreads();
-        SR_TICK(6)
-        // horizontal pass: a thread owns one (channel, column), its weights stay in
-        // registers, rows are independent (no tables, immediate offsets)
-        for (int col = tid; col < C * UW; col += NT) {
-            const int c = col / UW, xx = col - c * UW;
-            const float4 w4 = xw[xx];
-            const float wt[4] = {w4.x, w4.y, w4.z, w4.w};
-            const float* src = V + c * UH * MAXLRX + xb[xx];
-            float* dst = U + c * UH * P + (xx % PX) * NG + xx / PX;
-#pragma unroll
-            for (int yy = 0; yy < UH; ++yy) {
-                const float* p = src + yy * MAXLRX;
-                dst[yy * P] = dot4(wt, p[0], p[1], p[2], p[3]);
-            }
-        }
-        __syncthreads();
-#endif
-        SR_TICK(1)
-        //     ... and its coefficient steps as their registers fall free below
-        unsigned pix_next;
-        const char* cnext = phi_base(nxt, jr, jc, pix_next);
-        const unsigned* pt = ptab + hf * F::NLOAD;
-
-#ifdef SR_DBG_LOADONLY
-        unsigned dbg_sink = 0;
-#endif
-        // (3) stage 3 on the matrix cores: atom steps outer, pixel slots inner
-        f32x16 acc[PX][NMB];
-#pragma unroll
-        for (int q = 0; q < PX; ++q)
-#pragma unroll
-            for (int mb = 0; mb < NMB; ++mb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[q][mb][v] = 0.0f;
-#pragma unroll
-        for (int c16 = 0; c16 < N16; ++c16) {
-            f16x8 av[NMB][2];
-#pragma unroll
-            for (int mb = 0; mb < NMB; ++mb)
-#pragma unroll
-                for (int hl = 0; hl < 2; ++hl)
-                    av[mb][hl] = __builtin_bit_cast(f16x8, A16[((c16 * NMB + mb) * 2 + hl) * 64 + lane]);
-#ifdef SR_DBG_LOADONLY
-#pragma unroll
-            for (int i = 0; i < 8; ++i) dbg_sink ^= raw_word(raw[8 * c16 + i], 0) ^ raw_word(raw[8 * c16 + i], (PX / 2) - 1);
-#endif
-#pragma unroll
-            for (int q = 0; q < SR_DBG_PXQ; ++q) {
-                u32x4 bw;
-#pragma unroll
-                for (int m = 0; m < 4; ++m)
-                    bw[m] = pack_pair(raw_word(raw[8 * c16 + 2 * m], q >> 1),
-                                      raw_word(raw[8 * c16 + 2 * m + 1], q >> 1), q);
-                const f16x8 b = __builtin_bit_cast(f16x8, bw);
-#pragma unroll
-                for (int mb = 0; mb < NMB; ++mb)
-#pragma unroll
-                    for (int hl = 0; hl < SR_DBG_NHL; ++hl)
-                        acc[q][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[mb][hl], b, acc[q][mb], 0, 0, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            SR_TICK(8)
-            if (more) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    raw[8 * c16 + i] = __builtin_nontemporal_load((const Raw*)(cnext + (pix_next + pt[8 * c16 + i])));
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            SR_TICK(9)
-        }
-        if (N8) {
-            f16x4 av[NMB][2];
-#pragma unroll
-            for (int mb = 0; mb < NMB; ++mb)
-#pragma unroll
-                for (int hl = 0; hl < 2; ++hl)
-                    av[mb][hl] = __builtin_bit_cast(f16x4, A8[(mb * 2 + hl) * 64 + lane]);
-#ifdef SR_DBG_LOADONLY
-#pragma unroll
-            for (int i = 0; i < 4; ++i) dbg_sink ^= raw_word(raw[8 * N16 + i], 0) ^ raw_word(raw[8 * N16 + i], (PX / 2) - 1);
-#endif
-#pragma unroll
-            for (int q = 0; q < SR_DBG_PXQ; ++q) {
-                u32x2 bw;
-#pragma unroll
-                for (int m = 0; m < 2; ++m)
-                    bw[m] = pack_pair(raw_word(raw[8 * N16 + 2 * m], q >> 1),
-                                      raw_word(raw[8 * N16 + 2 * m + 1], q >> 1), q);
-                const f16x4 b = __builtin_bit_cast(f16x4, bw);
-#pragma unroll
-                for (int mb = 0; mb < NMB; ++mb)
-#pragma unroll
-                    for (int hl = 0; hl < SR_DBG_NHL; ++hl)
-                        acc[q][mb] = __builtin_amdgcn_mfma_f32_32x32x8f16(av[mb][hl], b, acc[q][mb], 0, 0, 0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            if (more) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    raw[8 * N16 + i] = __builtin_nontemporal_load((const Raw*)(cnext + (pix_next + pt[8 * N16 + i])));
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        SR_TICK(2)
-
-        // (4) stage 4: each half filters its taps against the LDS tile, channel by
-        //     channel (a lane's PX slots share most of their patch values)
-        const float* ub = U + (wave * WR + jr + hf * F::RH0) * P + jc;
-        float outp[C][PX];
-#pragma unroll
-        for (int c = 0; c < C; ++c) {
-#pragma unroll
-            for (int q = 0; q < PX; ++q) {
-                float s = 0.0f;
-#pragma unroll
-                for (int vv = 0; vv < SR_DBG_NSLOT; ++vv) {
-                    const int dyv = vv / K, dxv = vv % K;
-                    const int off = c * UH * P + dyv * P + ((q + dxv) % PX) * NG + (q + dxv) / PX;
-                    s = fmaf(acc[q][vv / 16][vv % 16], ub[off], s);
-                }
-                outp[c][q] = s;
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        SR_TICK(3)
-
-        // (5) add the two halves' partial sums: one cross-half swap per slot pair
-        //     leaves half 0 with pixels 0..PX/2-1 of the lane's group and half 1
-        //     with the rest; one vector store per channel
-        const int y = Y0 + wave * WR + jr, x = X0 + PX * jc;
-        const bool valid = y < a.H && x < a.W;
-        const unsigned plane_px = (unsigned)a.H * (unsigned)a.W;
-        const unsigned o0 = ((unsigned)(cur.n * C) * (unsigned)a.H + (unsigned)y) * (unsigned)a.W + x + hf * (PX / 2);
-#pragma unroll
-        for (int c = 0; c < C; ++c) {
-            float tot[PX / 2];
-#pragma unroll
-            for (int q = 0; q < PX / 2; ++q) {
-                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(outp[c][q]),
-                                                                 __float_as_uint(outp[c][q + PX / 2]), false, false);
-                tot[q] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
-            }
-#if defined(SR_DBG_LOADONLY) && !defined(SR_DBG_LOADONLY_ST)
-            if (dbg_sink == 0x12345678u) {
-#elif defined(SR_DBG_LOADONLY)
-            tot[0] += __uint_as_float(dbg_sink & 0xffu);
-            if (valid) {
-#elif defined(SR_DBG_NOSTORE)
-            if (valid && tot[0] == 123.456f) {
-#else
-            if (valid) {
-#endif
-                const unsigned oe = o0 + c * plane_px;
-                if (a.io_f16) {
-                    __half* op = (__half*)((char*)a.out + (size_t)(oe * 2u));
-                    if constexpr (PX >= 4) {
-#pragma unroll
-                        for (int q = 0; q < PX / 2; q += 2) {
-                            __half2 h2;
-                            h2.x = narrow_f16(tot[q]);
-                            h2.y = narrow_f16(tot[q + 1]);
-                            *(__half2*)(op + q) = h2;
-                        }
-                    } else {
-                        op[0] = narrow_f16(tot[0]);
-                    }
-                } else {
-                    float* op = (float*)((char*)a.out + (size_t)(oe * 4u));
-#ifdef SR_DBG_NTSTORE
-                    if constexpr (PX == 4) { __builtin_nontemporal_store(tot[0], op); __builtin_nontemporal_store(tot[1], op + 1); }
-                    else
-#endif
-                    if constexpr (PX == 8) *(float4*)op = make_float4(tot[0], tot[1], tot[2], tot[3]);
-                    else if constexpr (PX == 4) *(float2*)op = make_float2(tot[0], tot[1]);
-                    else op[0] = tot[0];
-                }
-            }
-        }
-        cur = nxt;
-        SR_TICK(4)
-    }
-#ifdef SR_DBG_TIMING
-    __syncthreads();
-    if ((tid0 & 63) == 0) {
-        float* dbg = (float*)a.out + ((size_t)blockIdx.x * NW + (tid0 >> 6)) * 16;
-        for (int i = 0; i < 10; ++i) dbg[i] = (float)tacc[i];
-    }
-#endif
-}
-
-// ---------------------------------------------------------------------------
-// Host side: which instantiation serves a call.
-// ---------------------------------------------------------------------------
 namespace {
 
-template <int K, int C, int NP8, int PX, int WR, int NW, int WPE = 2>
-hipError_t launch_one(const AssembleArgs& a, hipStream_t st) {
-    using F = Cfg<K, C, NP8, PX, WR, NW>;
-    const int tiles_x = (a.W + F::TW - 1) / F::TW, tiles_y = (a.H + F::TH - 1) / F::TH;
-    const long long nt = (long long)tiles_x * tiles_y * a.N;
-    if (nt > 0x7fffffffLL) return hipErrorInvalidValue;
-    // persistent grid: as many workgroups as stay resident (WPE wavefronts per SIMD)
-    int dev = 0, cus = 256;
-    if (hipGetDevice(&dev) == hipSuccess)
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    const int cap = cus * (4 * WPE / NW > 0 ? 4 * WPE / NW : 1);
-    const int blocks = nt < cap ? (int)nt : cap;
-    hipLaunchKernelGGL((k_assemble_mfma<K, C, NP8, PX, WR, NW, WPE>), dim3(blocks), dim3(F::NT), 0, st,
-                       a, tiles_x, tiles_y, (int)nt);
-    return hipGetLastError();
-}
+constexpr int N_TILE_SHAPES = 6;
 
-// atoms-per-launch capacity (in groups of 8) of the built instantiations, 0 = none
-int np8_for(int k, int n_fold) {
+// Capacity (in groups of 8 folded atoms) of the smallest built instantiation
+// that holds n_fold atoms; 0 = none.  Unused capacity costs MFMA issue slots
+// only: padding atoms meet zero dictionary rows and re-read a cached plane.
+int np8_for(int k, int channels, int n_fold) {
     const int need = (n_fold + 7) / 8;
-    if (k == 5) return need <= 9 ? 9 : 0;
+    static const int k5c3[] = {1, 2, 4, 6, 9, 0}, k5c1[] = {1, 4, 9, 0};
+    static const int k7c3[] = {2, 9, 16, 0}, k7c1[] = {16, 0};
+    const int* built = k == 5 ? (channels == 3 ? k5c3 : k5c1) : (channels == 3 ? k7c3 : k7c1);
+    for (; *built; ++built)
+        if (*built >= need) return *built;
     return 0;
 }
-
-constexpr int N_TILE_SHAPES = 10;
 
 }  // namespace
 
@@ -554,33 +31,18 @@ bool mfma_supported(const AssembleArgs& a, int k, bool coeff_f16, int tile) {
     if (!coeff_f16 || (k != 5 && k != 7) || (a.C != 1 && a.C != 3)) return false;
     if (a.W % 8 != 0 || a.W < 8 || a.H < 1) return false;
     if (((uintptr_t)a.coeff % 16) != 0 || ((uintptr_t)a.out % 16) != 0) return false;
-    if ((unsigned long long)a.L * a.H * a.W * 2ull >= (1ull << 32)) return false;   // 32-bit plane offsets
+    if ((unsigned long long)a.L * a.H * a.W * 2ull >= (1ull << 32)) return false;         // 32-bit plane offsets
     if ((unsigned long long)a.N * a.C * a.H * a.W * 4ull >= (1ull << 32)) return false;   // 32-bit image offsets
-    if (np8_for(k, a.n_fold) == 0) return false;
+    if (np8_for(k, a.C, a.n_fold) == 0) return false;
     if (tile < 0 || tile >= N_TILE_SHAPES) return false;
     return true;
 }
 
 hipError_t launch_mfma(const AssembleArgs& a, int k, bool io_f16, int tile, hipStream_t st) {
     (void)io_f16;
-    const int np8 = np8_for(k, a.n_fold);
-    if (k == 5 && np8 == 9) {
-        if (a.C == 3) {
-            switch (tile) {
-            case 1:  return launch_one<5, 3, 9, 4, 1, 4>(a, st);    // 128 x 4
-            case 2:  return launch_one<5, 3, 9, 4, 2, 8>(a, st);    //  64 x 16, 8 wavefronts
-            case 3:  return launch_one<5, 3, 9, 4, 1, 8>(a, st);    // 128 x 8,  8 wavefronts
-            case 4:  return launch_one<5, 3, 9, 2, 2, 8, 4>(a, st); //  32 x 16, 8 wavefronts, 4 per SIMD
-            case 5:  return launch_one<5, 3, 9, 2, 2, 4, 4>(a, st); //  32 x 8
-            case 6:  return launch_one<5, 3, 9, 2, 1, 8, 4>(a, st); //  64 x 8
-            case 7:  return launch_one<5, 3, 9, 2, 1, 4, 4>(a, st); //  64 x 4
-            case 8:  return launch_one<5, 3, 9, 2, 2, 8, 3>(a, st); //  32 x 16, 3 per SIMD
-            case 9:  return launch_one<5, 3, 9, 4, 2, 4, 3>(a, st); //  64 x 8, 3 per SIMD
-            default: return launch_one<5, 3, 9, 4, 2, 4>(a, st);    //  64 x 8
-            }
-        }
-        return launch_one<5, 1, 9, 4, 2, 4>(a, st);
-    }
+    const int np8 = np8_for(k, a.C, a.n_fold);
+    if (k == 5) return launch_mfma_k5(a, np8, tile, st);
+    if (k == 7) return launch_mfma_k7(a, np8, tile, st);
     return hipErrorInvalidValue;
 }
 

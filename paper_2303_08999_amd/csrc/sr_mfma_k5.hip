@@ -1,0 +1,34 @@
+// Matrix-core kernel instantiations for 5x5 atoms (see sr_mfma_kernel.h).
+#include "sr_mfma_kernel.h"
+
+namespace srd {
+
+// np8: capacity in groups of 8 folded atoms; shape: tile shape index (C = 3, np8 = 9 only)
+hipError_t launch_mfma_k5(const AssembleArgs& a, int np8, int shape, hipStream_t st) {
+    if (a.C == 3) {
+        switch (np8) {
+        case 1:  return launch_one<5, 3, 1, 4, 1, 4, 4, 2>(a, st);
+        case 2:  return launch_one<5, 3, 2, 4, 1, 4, 4, 2>(a, st);
+        case 4:  return launch_one<5, 3, 4, 4, 1, 4, 4, 2>(a, st);
+        case 6:  return launch_one<5, 3, 6, 4, 1, 4, 4, 2>(a, st);
+        case 9:
+            switch (shape) {
+            case 1:  return launch_one<5, 3, 9, 4, 2, 4, 1, 2>(a, st);    //  64 x 8
+            case 2:  return launch_one<5, 3, 9, 4, 1, 4, 1, 2>(a, st);    // 128 x 4
+            case 3:  return launch_one<5, 3, 9, 4, 2, 4, 2, 2>(a, st);    //  64 x 16, 2 units per wavefront
+            case 4:  return launch_one<5, 3, 9, 4, 1, 4, 2, 2>(a, st);    // 128 x 8,  2 units
+            case 5:  return launch_one<5, 3, 9, 4, 2, 4, 4, 2>(a, st);    //  64 x 32, 4 units
+            default: return launch_one<5, 3, 9, 4, 1, 4, 4, 2>(a, st);    // 128 x 16, 4 units
+            }
+        default: return hipErrorInvalidValue;
+        }
+    }
+    switch (np8) {
+    case 1:  return launch_one<5, 1, 1, 4, 1, 4, 4, 2>(a, st);
+    case 4:  return launch_one<5, 1, 4, 4, 1, 4, 4, 2>(a, st);
+    case 9:  return launch_one<5, 1, 9, 4, 1, 4, 4, 2>(a, st);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace srd

@@ -86,6 +86,46 @@ def test_video_workload_two_frames(oracle, kernel):
     check_full(oracle, sr_synth.scaled(sr_synth.WORKLOADS["video"], n=2), kernel)
 
 
+def test_4k_dense_full_frame_in_the_benchmarked_configuration(oracle):
+    """The headline workload at full size, default kernel choice (what bench.py
+    times), every one of the 3 x 2160 x 3840 outputs against the oracle."""
+    wl = sr_synth.WORKLOADS["4k_dense"]
+    inp = sr_synth.make_inputs(wl, DEV)
+    assert planned(inp, wl, sr.SR_KERNEL_AUTO) == MFMA
+    got = run_gpu(inp, wl, sr.SR_KERNEL_AUTO).cpu().numpy()
+    hi = host(inp)
+    ref = oracle.dict_assemble(hi["lr"], hi["coeff"], hi["dict"], wl.scale)
+    err = np.abs(got.astype(np.float64) - ref)
+    assert not np.isnan(got).any()
+    assert float(err.max()) <= 2e-3, f"worst error {err.max():.3e}"
+
+
+def test_4k_selective_full_frame(oracle):
+    """4K with the 8 kept atoms of the selective workload (global kept list)."""
+    wl = sr_synth.WORKLOADS["4k_selective"]
+    inp = sr_synth.make_inputs(wl, DEV)
+    kept = inp["kept"]
+    assert planned(inp, wl, sr.SR_KERNEL_AUTO, kept) == MFMA
+    got = run_gpu(inp, wl, sr.SR_KERNEL_AUTO, kept=kept).cpu().numpy()
+    hi = host(inp)
+    ref = oracle.dict_assemble(hi["lr"], hi["coeff"], hi["dict"], wl.scale, kept=kept)
+    err = np.abs(got.astype(np.float64) - ref)
+    assert float(err.max()) <= 2e-3, f"worst error {err.max():.3e}"
+    # about 13 % of the coefficient mass is dropped: the result must differ from dense
+    dense = oracle.assemble(oracle.bicubic(hi["lr"], wl.scale), hi["coeff"], hi["dict"], rows=(0, 8))
+    assert np.abs(dense[:, :, :8] - ref[:, :, :8]).max() > 1e-2
+
+
+@pytest.mark.parametrize("tile", range(6))
+@pytest.mark.parametrize("shape", [(50, 72, 4), (37, 40, 3), (61, 100, 2)])
+def test_every_tile_shape_of_the_matrix_core_kernel(oracle, tile, shape):
+    """All built tile shapes (a tuning option) on images that leave ragged tails
+    in both directions and span several tiles."""
+    h, w, s = shape
+    wl = sr_synth.Workload("tiles", 16, 2, 3, h, w, s, 72, 5, "f16", "f32")
+    check_full(oracle, wl, MFMA, tile=tile)
+
+
 # ---- shapes that span several tiles and leave ragged tails --------------------
 RAGGED = [
     # (h, w, scale, C, L, k, coeff dtype, io dtype, N)
