@@ -76,6 +76,9 @@ def main():
     ap.add_argument("--tile", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a known-size kernel that scales the "
+                         "FETCH_SIZE / WRITE_SIZE counters when profiling)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures ONE GPU; the path shards over HR row bands with no "
@@ -104,6 +107,12 @@ def main():
         sr.sr_dict_assemble_ex(inp["lr"], coeffs[i % N_ROTATE], inp["dict"], wl.L, wl.k, wl.scale, wl.c,
                                outs[i % 2], kept=kept, opts=opts)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, device=dev, dtype=torch.float32).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
