@@ -40,15 +40,6 @@
 #include "sr_device.h"
 #include "sr_launch.h"
 
-#ifndef SR_DBG_NHL
-#define SR_DBG_NHL 2
-#endif
-#ifndef SR_DBG_PXQ
-#define SR_DBG_PXQ PX
-#endif
-#ifndef SR_DBG_NSLOT
-#define SR_DBG_NSLOT F::NSLOT
-#endif
 
 namespace srd {
 
@@ -177,9 +168,6 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     }
     __syncthreads();
 
-#ifdef SR_DBG_STAGGER
-    for (int k = (int)(blockIdx.x % SR_DBG_STAGGER); k > 0; --k) __builtin_amdgcn_s_sleep(SR_DBG_SLEEP);
-#endif
     // ---- tile walk: this workgroup takes tiles blockIdx.x, +gridDim.x, ...  The
     //      step is pre-split into (image, tile row, tile column) so that no
     //      division is left in the loop.  All of it is scalar.
@@ -256,16 +244,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             raw[i] = __builtin_nontemporal_load((const Raw*)(cimg + (pix_off + pt[i])));
     }
 
-#ifdef SR_DBG_TIMING
-    unsigned long long tacc[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#define SR_TICK(i) { unsigned long long now_ = __builtin_readcyclecounter(); tacc[i] += now_ - tprev_; tprev_ = now_; }
-#else
-#define SR_TICK(i)
-#endif
     for (int t = blockIdx.x; t < ntiles; t += G) {
-#ifdef SR_DBG_TIMING
-        unsigned long long tprev_ = __builtin_readcyclecounter();
-#endif
         // Per-iteration copy of the thread id the optimiser cannot see through:
         // index arithmetic derived from it is recomputed each tile instead of
         // being hoisted out of the loop into dozens of long-lived registers.
@@ -303,16 +282,12 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                     }
             }
         }
-        SR_TICK(7)
         // (2) prefetch the next tile's LR footprint now: it lands while this tile is
         //     up-sampled, before the matrix-core phase waits on outstanding loads
         const bool more_tiles = t + G < ntiles;
         const TilePos nxt = more_tiles ? advance(cur) : cur;
         if (more_tiles) load_lr(nxt, lane, lrv);
-        SR_TICK(0)
-#ifndef SR_DBG_SKIP_U
         __syncthreads();
-        SR_TICK(5)
         // vertical pass on the narrow LR footprint: V[c][yy][rx]
         {
             const int sh = o.nlx <= 32 ? 5 : (o.nlx <= 64 ? 6 : 7);
@@ -329,7 +304,6 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             }
         }
         __syncthreads();
-        SR_TICK(6)
         // horizontal pass: a thread owns one (channel, column), its weights stay in
         // registers, rows are independent (no tables, immediate offsets)
         for (int col = tid; col < C * UW; col += NT) {
@@ -345,8 +319,6 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             }
         }
         __syncthreads();
-#endif
-        SR_TICK(1)
         const unsigned* pt = ptab + hf * F::NLOAD;
         // The wavefront's NU units of this tile, one after the other; while a unit
         // is folded, the coefficients of the next one (same tile, or unit 0 of the
@@ -358,9 +330,6 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         unsigned pix_next;
         const char* cnext = last_unit ? phi_base(nxt, 0, jr, jc, pix_next) : phi_base(cur, unit + 1, jr, jc, pix_next);
 
-#ifdef SR_DBG_LOADONLY
-        unsigned dbg_sink = 0;
-#endif
         // (3) stage 3 on the matrix cores: atom steps outer, pixel slots inner
         f32x16 acc[PX][NMB];
 #pragma unroll
@@ -377,12 +346,8 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 #pragma unroll
                 for (int hl = 0; hl < 2; ++hl)
                     av[mb][hl] = __builtin_bit_cast(f16x8, A16[((c16 * NMB + mb) * 2 + hl) * 64 + lane]);
-#ifdef SR_DBG_LOADONLY
 #pragma unroll
-            for (int i = 0; i < 8; ++i) dbg_sink ^= raw_word(raw[8 * c16 + i], 0) ^ raw_word(raw[8 * c16 + i], (PX / 2) - 1);
-#endif
-#pragma unroll
-            for (int q = 0; q < SR_DBG_PXQ; ++q) {
+            for (int q = 0; q < PX; ++q) {
                 u32x4 bw;
 #pragma unroll
                 for (int m = 0; m < 4; ++m)
@@ -392,18 +357,16 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 #pragma unroll
                 for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
-                    for (int hl = 0; hl < SR_DBG_NHL; ++hl)
+                    for (int hl = 0; hl < 2; ++hl)
                         acc[q][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[mb][hl], b, acc[q][mb], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
-            SR_TICK(8)
             if (more) {
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
                     raw[8 * c16 + i] = __builtin_nontemporal_load((const Raw*)(cnext + (pix_next + pt[8 * c16 + i])));
             }
             __builtin_amdgcn_sched_barrier(0);
-            SR_TICK(9)
         }
         if (N8) {
             f16x4 av[NMB][2];
@@ -412,12 +375,8 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 #pragma unroll
                 for (int hl = 0; hl < 2; ++hl)
                     av[mb][hl] = __builtin_bit_cast(f16x4, A8[(mb * 2 + hl) * 64 + lane]);
-#ifdef SR_DBG_LOADONLY
 #pragma unroll
-            for (int i = 0; i < 4; ++i) dbg_sink ^= raw_word(raw[8 * N16 + i], 0) ^ raw_word(raw[8 * N16 + i], (PX / 2) - 1);
-#endif
-#pragma unroll
-            for (int q = 0; q < SR_DBG_PXQ; ++q) {
+            for (int q = 0; q < PX; ++q) {
                 u32x2 bw;
 #pragma unroll
                 for (int m = 0; m < 2; ++m)
@@ -427,7 +386,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 #pragma unroll
                 for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
-                    for (int hl = 0; hl < SR_DBG_NHL; ++hl)
+                    for (int hl = 0; hl < 2; ++hl)
                         acc[q][mb] = __builtin_amdgcn_mfma_f32_32x32x8f16(av[mb][hl], b, acc[q][mb], 0, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -438,7 +397,6 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        SR_TICK(2)
 
         // (4) stage 4: each half filters its taps against the LDS tile, channel by
         //     channel (a lane's PX slots share most of their patch values)
@@ -450,7 +408,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             for (int q = 0; q < PX; ++q) {
                 float s = 0.0f;
 #pragma unroll
-                for (int vv = 0; vv < SR_DBG_NSLOT; ++vv) {
+                for (int vv = 0; vv < F::NSLOT; ++vv) {
                     const int dyv = vv / K, dxv = vv % K;
                     const int off = c * UH * P + dyv * P + ((q + dxv) % PX) * NG + (q + dxv) / PX;
                     s = fmaf(acc[q][vv / 16][vv % 16], ub[off], s);
@@ -459,7 +417,6 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        SR_TICK(3)
 
         // (5) add the two halves' partial sums: one cross-half swap per slot pair
         //     leaves half 0 with pixels 0..PX/2-1 of the lane's group and half 1
@@ -477,16 +434,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                                                                  __float_as_uint(outp[c][q + PX / 2]), false, false);
                 tot[q] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
             }
-#if defined(SR_DBG_LOADONLY) && !defined(SR_DBG_LOADONLY_ST)
-            if (dbg_sink == 0x12345678u) {
-#elif defined(SR_DBG_LOADONLY)
-            tot[0] += __uint_as_float(dbg_sink & 0xffu);
             if (valid) {
-#elif defined(SR_DBG_NOSTORE)
-            if (valid && tot[0] == 123.456f) {
-#else
-            if (valid) {
-#endif
                 const unsigned oe = o0 + c * plane_px;
                 if (a.io_f16) {
                     __half* op = (__half*)((char*)a.out + (size_t)(oe * 2u));
@@ -503,27 +451,15 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                     }
                 } else {
                     float* op = (float*)((char*)a.out + (size_t)(oe * 4u));
-#ifdef SR_DBG_NTSTORE
-                    if constexpr (PX == 4) { float2 val_ = make_float2(tot[0], tot[1]); asm volatile("global_store_dwordx2 %0, %1, off sc1" :: "v"(op), "v"(val_) : "memory"); }
-                    else
-#endif
                     if constexpr (PX == 8) *(float4*)op = make_float4(tot[0], tot[1], tot[2], tot[3]);
                     else if constexpr (PX == 4) *(float2*)op = make_float2(tot[0], tot[1]);
                     else op[0] = tot[0];
                 }
             }
         }
-        SR_TICK(4)
         }   // unit
         cur = nxt;
     }
-#ifdef SR_DBG_TIMING
-    __syncthreads();
-    if ((tid0 & 63) == 0) {
-        float* dbg = (float*)a.out + ((size_t)blockIdx.x * NW + (tid0 >> 6)) * 16;
-        for (int i = 0; i < 10; ++i) dbg[i] = (float)tacc[i];
-    }
-#endif
 }
 
 // ---------------------------------------------------------------------------
