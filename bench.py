@@ -76,6 +76,9 @@ def main():
     ap.add_argument("--tile", type=int, default=0)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
+    ap.add_argument("--kept-sweep", action="store_true",
+                    help="also time kept-atom lists of 72, 58, 43, 29, 14 and 8 atoms (the paper's "
+                         "compression-ratio ablation, Fig. 7) and add them to the JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size kernel that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters when profiling)")
@@ -150,6 +153,34 @@ def main():
                      "algorithmic_bytes": alg_bytes},
         "pct_of_hbm_peak": round(100.0 * achieved / HBM_PEAK_GBS, 2),
     }
+    if args.kept_sweep:
+        import numpy as np
+        rng = np.random.default_rng(7)
+        sweep = []
+        for n_keep in (72, 58, 43, 29, 14, 8):
+            if n_keep > wl.L:
+                continue
+            klist = np.sort(rng.choice(wl.L, size=n_keep, replace=False)).astype(np.int32)
+            gam = np.ones(n_keep, dtype=np.float32)
+
+            def kstep(i):
+                sr.sr_dict_assemble_ex(inp["lr"], coeffs[i % N_ROTATE], inp["dict"], wl.L, wl.k, wl.scale,
+                                       wl.c, outs[i % 2], kept=klist, gamma=gam, opts=opts)
+            for i in range(3):
+                kstep(i)
+            torch.cuda.synchronize()
+            kev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+            for i, (a, b) in enumerate(kev):
+                a.record(); kstep(i); b.record()
+            torch.cuda.synchronize()
+            ms = sum(a.elapsed_time(b) for a, b in kev) / len(kev)
+            sweep.append({"atoms_read": n_keep, "kernel_ms_avg": round(ms, 4),
+                          "hr_mpixel_per_s": round(px / ms / 1e3, 1),
+                          "algorithmic_GBps": round(wl.algorithmic_bytes(n_keep) / ms / 1e6, 1)})
+        base = sweep[0]["kernel_ms_avg"]
+        for row in sweep:
+            row["speedup_vs_all_atoms"] = round(base / row["kernel_ms_avg"], 2)
+        result["kept_sweep"] = sweep
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(wl, inp["lr"], coeffs[0], inp["dict"], args.cpu_budget)
     print(json.dumps(result))
