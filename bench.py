@@ -55,15 +55,20 @@ def cpu_baseline(wl, lr, coeff, dictionary, budget_s=20.0):
     oracle.assemble(U, c_h, d_h, rows=(0, 16))
     per_row = (time.perf_counter() - t0) / 16
     rows = int(max(16, min(wl.H, budget_s / max(per_row, 1e-9))))
-    t0 = time.perf_counter()
-    oracle.assemble(U, c_h, d_h, rows=(0, rows))
-    t_band = time.perf_counter() - t0
+    # repeat the band until about half the budget is spent (at most 16 passes): a
+    # whole 4K frame takes the oracle well under a second on a many-core host
+    passes, t_band = 0, 0.0
+    while passes < 16 and (passes == 0 or t_band < 0.5 * budget_s):
+        t0 = time.perf_counter()
+        oracle.assemble(U, c_h, d_h, rows=(0, rows))
+        t_band += time.perf_counter() - t0
+        passes += 1
     # stage 1 is charged in proportion to the band
-    t_total = t_band + t_up * rows / wl.H
+    t_total = t_band / passes + t_up * rows / wl.H
     mpx = rows * wl.W * wl.n / t_total / 1e6
     return {"value": round(mpx, 3), "unit": "HR Mpixel/s", "cores": threads, "kind": "oracle",
             "sample": f"HR rows 0..{rows - 1} of {wl.H} of the same 4K frame ({rows * wl.W} pixels), "
-                      f"double precision, OpenMP over rows; {t_total:.2f} s"}
+                      f"double precision, OpenMP over rows; mean of {passes} passes, {t_total:.2f} s each"}
 
 
 def main():
@@ -142,7 +147,9 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(wall / args.steps * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 coefficients x f16(hi+lo) dictionary on MFMA, f32 accumulate, f32 image",
+        "dtype": "f16" if plan == 2 else "f32",
+        "arithmetic": ("f16 coefficients x f16 (hi+lo) dictionary on MFMA with f32 accumulation; f32 up-sampling "
+                       "and filtering" if plan == 2 else "f32 vector ALU"),
         "data": "synthetic",
         "config": {"workload": wl.name, "hr": f"{wl.W}x{wl.H}", "scale": wl.scale, "channels": wl.c,
                    "L": wl.L, "k": wl.k, "atoms_read": n_read, "batch": wl.n,
