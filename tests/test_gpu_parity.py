@@ -291,3 +291,21 @@ def test_runs_on_a_side_stream():
         sr.sr_dict_assemble(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, b, stream=st)
     st.synchronize()
     assert torch.equal(a, b)
+
+
+def test_tile_sweep_returns_a_valid_shape():
+    """The measured launch-shape search (stand-in for the paper's constrained
+    Bayesian search) visits every built tile shape and picks one of them."""
+    from paper_2303_08999_amd import tune
+    wl = sr_synth.scaled(sr_synth.WORKLOADS["4k_dense"], h=96, w=128)
+    inp = sr_synth.make_inputs(wl, DEV)
+    out = torch.empty((wl.n, wl.c, wl.H, wl.W), device=DEV)
+    res = tune.sweep_tiles(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, out, reps=3)
+    assert [t for t, _ in res] == list(range(6))
+    assert all(ms > 0 for _, ms in res)
+    assert tune.best_tile(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, out, reps=3) in range(6)
+    # fp32 coefficients: the matrix-core kernel does not apply, nothing to sweep
+    wl32 = sr_synth.scaled(sr_synth.WORKLOADS["tiny"])
+    i32 = sr_synth.make_inputs(wl32, DEV)
+    o32 = torch.empty((1, 1, wl32.H, wl32.W), device=DEV)
+    assert tune.sweep_tiles(i32["lr"], i32["coeff"], i32["dict"], wl32.L, wl32.k, wl32.scale, wl32.c, o32) == []
