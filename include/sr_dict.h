@@ -125,8 +125,10 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
 /*
  * As sr_dict_assemble_selective (kept == NULL means dense), with an explicit
  * kernel choice; `opts` == NULL means SR_KERNEL_AUTO.  The matrix-core kernel
- * qualifies when coeff is f16, k is 5 or 7, C is 1 or 3, the HR width is a
- * multiple of 8 and coeff->data is 16-byte aligned.
+ * qualifies when coeff is f16, k is 5 or 7, C is 1 or 3, at most 72 (k = 5) or
+ * 128 (k = 7) atoms are folded, the HR width is a multiple of 4 (k = 5) or 2
+ * (k = 7), coeff->data and out->data are 16-byte aligned and the tensors are
+ * small enough for 32-bit offsets (L*H*W < 2^31, N*C*H*W < 2^30).
  */
 int sr_dict_assemble_ex(const sr_tensor* lr, const sr_tensor* coeff, const sr_tensor* dict,
                         int L, int k, int scale, int channels,

@@ -29,7 +29,10 @@ int np8_for(int k, int channels, int n_fold) {
 
 bool mfma_supported(const AssembleArgs& a, int k, bool coeff_f16, int tile) {
     if (!coeff_f16 || (k != 5 && k != 7) || (a.C != 1 && a.C != 3)) return false;
-    if (a.W % 8 != 0 || a.W < 8 || a.H < 1) return false;
+    // a lane loads PX consecutive fp16 pixels of a row with one PX*2-byte load and
+    // stores PX/2 results per channel: rows must keep that alignment
+    const int px = k == 5 ? 4 : 2;
+    if (a.W % px != 0 || a.W < px || a.H < 1) return false;
     if (((uintptr_t)a.coeff % 16) != 0 || ((uintptr_t)a.out % 16) != 0) return false;
     if ((unsigned long long)a.L * a.H * a.W * 2ull >= (1ull << 32)) return false;         // 32-bit plane offsets
     if ((unsigned long long)a.N * a.C * a.H * a.W * 4ull >= (1ull << 32)) return false;   // 32-bit image offsets

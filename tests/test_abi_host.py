@@ -68,7 +68,10 @@ def plan(lr, coeff, d, out, L=72, k=5, s=4, C=3, kept=None, opts=None):
 def test_plan_accepts_a_good_case(lib):
     assert plan(*case()) in (sr.SR_KERNEL_GENERIC, sr.SR_KERNEL_MFMA)
     assert plan(*case(cd=sr.SR_F32)) == sr.SR_KERNEL_GENERIC
-    assert plan(*case(w=15, s=3), s=3) == sr.SR_KERNEL_GENERIC   # HR width 45: not a multiple of 8
+    assert plan(*case(w=15, s=3), s=3) == sr.SR_KERNEL_GENERIC   # HR width 45: not a multiple of 4
+    assert plan(*case(w=15), opts=sr.make_options(sr.SR_KERNEL_MFMA)) == sr.SR_KERNEL_MFMA   # width 60
+    assert plan(*case(L=73), L=73) == sr.SR_KERNEL_GENERIC       # more atoms than the 5x5 kernel holds
+    assert plan(*case(L=128, k=7), L=128, k=7) == sr.SR_KERNEL_MFMA
     assert plan(*case(), opts=sr.make_options(sr.SR_KERNEL_GENERIC)) == sr.SR_KERNEL_GENERIC
 
 

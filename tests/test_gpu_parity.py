@@ -143,6 +143,10 @@ RAGGED = [
     (45, 64, 4, 3, 40, 5, "f16", "f32", 1),
     (16, 96, 4, 3, 8, 5, "f16", "f32", 1),
     (16, 48, 4, 3, 13, 7, "f16", "f16", 1),
+    (23, 27, 4, 3, 72, 5, "f16", "f32", 1),     # HR width 108: multiple of 4, not of 8
+    (19, 31, 2, 3, 72, 5, "f16", "f32", 1),     # HR width 62: matrix-core kernel declines (k = 5)
+    (19, 31, 2, 3, 100, 7, "f16", "f16", 2),    # HR width 62: fine for 7x7 (2 pixels per lane)
+    (14, 29, 4, 1, 30, 5, "f16", "f16", 1),     # HR width 116, one channel, fp16 output
 ]
 
 
