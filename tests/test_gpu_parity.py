@@ -86,6 +86,31 @@ def test_video_workload_two_frames(oracle, kernel):
     check_full(oracle, sr_synth.scaled(sr_synth.WORKLOADS["video"], n=2), kernel)
 
 
+def test_video_workload_all_sixteen_frames(oracle):
+    """The whole video-stress batch (16 frames, 8.5 GB of coefficients) in one call:
+    frame 11 in full and 4000 sampled pixels of the other frames, oracle pixel by
+    pixel."""
+    wl = sr_synth.WORKLOADS["video"]
+    inp = sr_synth.make_inputs(wl, DEV)
+    assert planned(inp, wl, sr.SR_KERNEL_AUTO) == MFMA
+    got = run_gpu(inp, wl, sr.SR_KERNEL_AUTO).float().cpu().numpy()
+    assert not np.isnan(got).any()
+    lr, D = inp["lr"].cpu().numpy(), inp["dict"].cpu().numpy()
+    U = oracle.bicubic(lr, wl.scale)
+    f = 11
+    cf = inp["coeff"][f:f + 1].cpu().numpy()
+    ref = oracle.assemble(U[f:f + 1], cf, D)
+    assert float(np.abs(got[f:f + 1] - ref).max()) <= 2e-3
+    rng = np.random.default_rng(5)
+    for frame in (0, 3, 7, 15):
+        pts = np.stack([np.zeros(1000, dtype=np.int64), rng.integers(0, wl.H, 1000), rng.integers(0, wl.W, 1000)], axis=1)
+        pts[:4] = [(0, 0, 0), (0, wl.H - 1, wl.W - 1), (0, 0, wl.W - 1), (0, wl.H - 1, 0)]
+        cf = inp["coeff"][frame:frame + 1].cpu().numpy()
+        want = oracle.assemble_points(U[frame:frame + 1], cf, D, pts)
+        have = got[frame][:, pts[:, 1], pts[:, 2]].T
+        assert float(np.abs(have - want).max()) <= 2e-3, f"frame {frame}"
+
+
 def test_4k_dense_full_frame_in_the_benchmarked_configuration(oracle):
     """The headline workload at full size, default kernel choice (what bench.py
     times), every one of the 3 x 2160 x 3840 outputs against the oracle."""
