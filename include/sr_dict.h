@@ -74,7 +74,8 @@ typedef enum {
 typedef enum {
     SR_KERNEL_AUTO    = 0,     /* the library picks                                */
     SR_KERNEL_GENERIC = 1,     /* fp32 vector-ALU kernel: every supported case      */
-    SR_KERNEL_MFMA    = 2      /* fp16-coefficient matrix-core kernel; the call
+    SR_KERNEL_MFMA    = 2      /* matrix-core kernel (fp16 coefficients on fp16
+                                  MFMA, fp32 coefficients on fp32 MFMA); the call
                                   fails with SR_ERR_UNSUPPORTED if the case does
                                   not qualify (see sr_dict_assemble_ex)            */
 } sr_kernel;
@@ -125,10 +126,13 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
 /*
  * As sr_dict_assemble_selective (kept == NULL means dense), with an explicit
  * kernel choice; `opts` == NULL means SR_KERNEL_AUTO.  The matrix-core kernel
- * qualifies when coeff is f16, k is 5 or 7, C is 1 or 3, at most 72 (k = 5) or
- * 128 (k = 7) atoms are folded, the HR width is a multiple of 4 (k = 5) or 2
- * (k = 7), coeff->data and out->data are 16-byte aligned and the tensors are
- * small enough for 32-bit offsets (L*H*W < 2^31, N*C*H*W < 2^30).
+ * qualifies when C is 1 or 3, coeff->data and out->data are 16-byte aligned,
+ * the tensors are small enough for 32-bit byte offsets (L*H*W*sizeof(coeff)
+ * < 2^32, N*C*H*W < 2^30) and
+ *   f16 coefficients: k = 5 with at most 72 folded atoms and HR width % 4 == 0,
+ *                     or k = 7 with at most 128 atoms and HR width % 2 == 0;
+ *   f32 coefficients: k = 5 with at most 72 folded atoms and HR width % 2 == 0.
+ * Every other supported case runs on the generic kernel.
  */
 int sr_dict_assemble_ex(const sr_tensor* lr, const sr_tensor* coeff, const sr_tensor* dict,
                         int L, int k, int scale, int channels,

@@ -84,6 +84,7 @@ void make_plan(Plan& p, const sr_tensor* lr, const sr_tensor* coeff, const sr_te
         a.n_fold = L;
     }
     a.io_f16 = lr->dtype == SR_F16;
+    a.coeff_f32 = coeff->dtype == SR_F32;
     p.empty = lr->n == 0 || lr->h == 0 || lr->w == 0;
     if (!p.empty) {
         if (!lr->data || !coeff->data || !dict->data || !out->data) { p.status = SR_ERR_NULL; return; }

@@ -26,6 +26,7 @@ struct AssembleArgs {
     int N, C, h, w, H, W, s, L;
     int n_fold;           // atoms folded: L (dense) or n_kept
     int io_f16;           // lr and out are fp16 (else fp32)
+    int coeff_f32;        // coefficients are fp32 (else fp16)
     int   kept[SR_MAX_ATOMS];    // plane read for folded atom i (identity when dense)
     float gamma[SR_MAX_ATOMS];   // its scale (1 when dense)
 };

@@ -49,7 +49,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
-template <int K, int C, int NP8, int PX, int WR, int NW, int NU>
+template <int K, int C, int NP8, int PX, int WR, int NW, int NU, bool F32 = false>
 struct Cfg {
     static constexpr int KK = K * K, R = (K - 1) / 2;
     static constexpr int RH0 = (K + 1) / 2;            // filter rows owned by lane half 0
@@ -66,16 +66,20 @@ struct Cfg {
     // rows of one wavefront must land on disjoint banks: pitch == WC (mod 32)
     static constexpr int P = WR == 1 ? P0 : P0 + ((WC - P0 % 32) + 32) % 32;
     static constexpr int MAXLRY = (UH - 1) / 2 + 5, MAXLRX = (UW - 1) / 2 + 5;
-    static constexpr int N16 = NP8 / 2, N8 = NP8 % 2;  // 16-atom steps, optional 8-atom step
-    static constexpr int NLOAD = 8 * N16 + 4 * N8;     // coefficient loads per lane and tile
+    // fp16 coefficients: 16-atom MFMA steps and an optional 8-atom step;
+    // fp32 coefficients: 2-atom steps of v_mfma_f32_32x32x2_f32, one load each
+    static constexpr int N16 = F32 ? 0 : NP8 / 2, N8 = F32 ? 0 : NP8 % 2;
+    static constexpr int N2 = F32 ? 4 * NP8 : 0;
+    static constexpr int NLOAD = F32 ? N2 : 8 * N16 + 4 * N8;   // coefficient loads per lane and unit
+    static constexpr int CB = F32 ? 4 : 2;             // bytes per stored coefficient
     static constexpr int NXC = (MAXLRX + 63) / 64;     // 64-column chunks of the LR footprint
     static constexpr int NLRP = (C * MAXLRY + NW - 1) / NW;   // (channel,row) pairs per wavefront
 };
 
-template <int PX> struct RawT;
-template <> struct RawT<8> { typedef u32x4 type; };
-template <> struct RawT<4> { typedef u32x2 type; };
-template <> struct RawT<2> { typedef unsigned type; };
+template <int BYTES> struct RawT;      // PX consecutive coefficients of one plane
+template <> struct RawT<16> { typedef u32x4 type; };
+template <> struct RawT<8> { typedef u32x2 type; };
+template <> struct RawT<4> { typedef unsigned type; };
 
 __device__ __forceinline__ unsigned raw_word(const u32x4& v, int m) { return v[m]; }
 __device__ __forceinline__ unsigned raw_word(const u32x2& v, int m) { return v[m]; }
@@ -99,11 +103,11 @@ __device__ __forceinline__ int tap_of_row(int i, int mb) {
 
 struct TilePos { int n, ty, tx; };
 
-template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE>
+template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, bool F32>
 __global__ __launch_bounds__(64 * NW, WPE)
 void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y, const int ntiles) {
-    using F = Cfg<K, C, NP8, PX, WR, NW, NU>;
-    using Raw = typename RawT<PX>::type;
+    using F = Cfg<K, C, NP8, PX, WR, NW, NU, F32>;
+    using Raw = typename RawT<PX * F::CB>::type;
     constexpr int NT = F::NT, P = F::P, NG = F::NG, UH = F::UH, UW = F::UW;
     constexpr int N16 = F::N16, N8 = F::N8, NMB = F::NMB;
     constexpr int MAXLRY = F::MAXLRY, MAXLRX = F::MAXLRX;
@@ -115,14 +119,15 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     __shared__ int xb[UW], yb[UH];                  // ... and first source index
     __shared__ float4 wk[8];                        // Keys weights by phase numerator m
     __shared__ u32x4 A16[(N16 ? N16 : 1) * NMB * 2 * 64];
-    __shared__ u32x2 A8[NMB * 2 * 64];
+    __shared__ u32x2 A8[(F32 ? 1 : NMB * 2) * 64];
+    __shared__ float A32[(F32 ? F::N2 * NMB : 1) * 64];   // fp32 path: D[2*step + hf][tap of row]
     __shared__ unsigned ptab[2 * F::NLOAD];         // byte offset of the plane each lane half loads
 
     const int tid0 = threadIdx.x;
     if ((int)blockIdx.x >= ntiles) return;
 
     // ---- once per workgroup: weight, plane-offset and dictionary operand tables ---
-    const unsigned plane_b = (unsigned)a.H * (unsigned)a.W * 2u;   // bytes per coefficient plane
+    const unsigned plane_b = (unsigned)a.H * (unsigned)a.W * (unsigned)F::CB;   // bytes per coefficient plane
     if (tid0 < 2 * a.s) {
         float wt[4];
         keys_weights(tid0, a.s, wt);
@@ -131,13 +136,20 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     for (int e = tid0; e < 2 * F::NLOAD; e += NT) {
         const int h = e / F::NLOAD, i = e - h * F::NLOAD;
         // load i of half h serves folded atom idx; padding atoms re-read the last plane
-        const int idx = i < 8 * N16 ? 16 * (i >> 3) + 8 * h + (i & 7) : 16 * N16 + 4 * h + (i - 8 * N16);
+        const int idx = F32 ? 2 * i + h
+                            : (i < 8 * N16 ? 16 * (i >> 3) + 8 * h + (i & 7) : 16 * N16 + 4 * h + (i - 8 * N16));
         ptab[e] = (unsigned)a.kept[idx < a.n_fold ? idx : a.n_fold - 1] * plane_b;
     }
     auto dval = [&](int idx, int tap) -> float {    // gamma * D[kept], zero for padding
         if (tap < 0 || idx >= a.n_fold) return 0.0f;
         return a.gamma[idx] * a.dict[(size_t)a.kept[idx] * F::KK + tap];
     };
+    if (F32) {
+        for (int e = tid0; e < F::N2 * NMB * 64; e += NT) {
+            const int l = e & 63, blk = e >> 6, mb = blk % NMB, st = blk / NMB;
+            A32[e] = dval(2 * st + (l >> 5), tap_of_row<K>(l & 31, mb));
+        }
+    }
     for (int e = tid0; e < N16 * NMB * 64; e += NT) {
         const int l = e & 63, blk = e >> 6, mb = blk % NMB, c16 = blk / NMB;
         const int tap = tap_of_row<K>(l & 31, mb);
@@ -223,7 +235,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     auto phi_base = [&](const TilePos tp, int unit, int jr, int jc, unsigned& pix_off) -> const char* {
         const int y = tp.ty * F::TH + (unit * NW + wave) * WR + jr, x = tp.tx * F::TW + PX * jc;
         const int yc = y < a.H ? y : a.H - 1, xc = x < a.W ? x : a.W - PX;   // out-of-image lanes re-read
-        pix_off = ((unsigned)yc * (unsigned)a.W + (unsigned)xc) * 2u;         // a valid address; never stored
+        pix_off = ((unsigned)yc * (unsigned)a.W + (unsigned)xc) * (unsigned)F::CB;   // a valid address; never stored
         return (const char*)a.coeff + (size_t)tp.n * a.L * (size_t)plane_b;
     };
 
@@ -338,6 +350,26 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[q][mb][v] = 0.0f;
+        if constexpr (F32) {
+            // fp32 coefficients: the loaded words ARE the B operand (lane half hf holds
+            // atom 2*step + hf of its pixels), no re-packing, exact fp32 products
+#pragma unroll
+            for (int st = 0; st < F::N2; ++st) {
+                float av[NMB];
+#pragma unroll
+                for (int mb = 0; mb < NMB; ++mb) av[mb] = A32[(st * NMB + mb) * 64 + lane];
+#pragma unroll
+                for (int q = 0; q < PX; ++q)
+#pragma unroll
+                    for (int mb = 0; mb < NMB; ++mb)
+                        acc[q][mb] = __builtin_amdgcn_mfma_f32_32x32x2f32(
+                            av[mb], __uint_as_float(raw_word(raw[st], q)), acc[q][mb], 0, 0, 0);
+                if ((st & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+                if (more)
+                    raw[st] = __builtin_nontemporal_load((const Raw*)(cnext + (pix_next + pt[st])));
+                if ((st & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+            }
+        }
 #pragma unroll
         for (int c16 = 0; c16 < N16; ++c16) {
             f16x8 av[NMB][2];
@@ -465,9 +497,9 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 // ---------------------------------------------------------------------------
 // Host side: launch of one instantiation on a persistent grid.
 // ---------------------------------------------------------------------------
-template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE>
+template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, bool F32 = false>
 hipError_t launch_one(const AssembleArgs& a, hipStream_t st) {
-    using F = Cfg<K, C, NP8, PX, WR, NW, NU>;
+    using F = Cfg<K, C, NP8, PX, WR, NW, NU, F32>;
     const int tiles_x = (a.W + F::TW - 1) / F::TW, tiles_y = (a.H + F::TH - 1) / F::TH;
     const long long nt = (long long)tiles_x * tiles_y * a.N;
     if (nt > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -477,7 +509,7 @@ hipError_t launch_one(const AssembleArgs& a, hipStream_t st) {
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     const int cap = cus * (4 * WPE / NW > 0 ? 4 * WPE / NW : 1);
     const int blocks = nt < cap ? (int)nt : cap;
-    hipLaunchKernelGGL((k_assemble_mfma<K, C, NP8, PX, WR, NW, NU, WPE>), dim3(blocks), dim3(F::NT), 0, st,
+    hipLaunchKernelGGL((k_assemble_mfma<K, C, NP8, PX, WR, NW, NU, WPE, F32>), dim3(blocks), dim3(F::NT), 0, st,
                        a, tiles_x, tiles_y, (int)nt);
     return hipGetLastError();
 }

@@ -172,6 +172,10 @@ RAGGED = [
     (19, 31, 2, 3, 72, 5, "f16", "f32", 1),     # HR width 62: matrix-core kernel declines (k = 5)
     (19, 31, 2, 3, 100, 7, "f16", "f16", 2),    # HR width 62: fine for 7x7 (2 pixels per lane)
     (14, 29, 4, 1, 30, 5, "f16", "f16", 1),     # HR width 116, one channel, fp16 output
+    (25, 33, 2, 3, 72, 5, "f32", "f32", 2),     # fp32 coefficients on the fp32 matrix-core path, HR width 66
+    (20, 27, 3, 1, 41, 5, "f32", "f16", 1),     # ... HR width 81: odd, generic kernel only
+    (18, 26, 3, 1, 41, 5, "f32", "f16", 1),     # ... HR width 78, one channel, fp16 image
+    (31, 45, 4, 3, 9, 5, "f32", "f32", 1),      # ... few atoms
 ]
 
 
@@ -333,8 +337,8 @@ def test_tile_sweep_returns_a_valid_shape():
     assert [t for t, _ in res] == list(range(6))
     assert all(ms > 0 for _, ms in res)
     assert tune.best_tile(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, out, reps=3) in range(6)
-    # fp32 coefficients: the matrix-core kernel does not apply, nothing to sweep
-    wl32 = sr_synth.scaled(sr_synth.WORKLOADS["tiny"])
+    # 3x3 atoms: the matrix-core kernel does not apply, nothing to sweep
+    wl32 = sr_synth.scaled(sr_synth.WORKLOADS["tiny"], k=3)
     i32 = sr_synth.make_inputs(wl32, DEV)
     o32 = torch.empty((1, 1, wl32.H, wl32.W), device=DEV)
     assert tune.sweep_tiles(i32["lr"], i32["coeff"], i32["dict"], wl32.L, wl32.k, wl32.scale, wl32.c, o32) == []
