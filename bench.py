@@ -147,9 +147,11 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(wall / args.steps * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16" if plan == 2 else "f32",
-        "arithmetic": ("f16 coefficients x f16 (hi+lo) dictionary on MFMA with f32 accumulation; f32 up-sampling "
-                       "and filtering" if plan == 2 else "f32 vector ALU"),
+        "dtype": "f16" if (plan == 2 and wl.coeff_dtype == "f16") else "f32",
+        "arithmetic": ("f32 vector ALU" if plan != 2 else
+                       "f16 coefficients x f16 (hi+lo) dictionary on MFMA with f32 accumulation; f32 up-sampling "
+                       "and filtering" if wl.coeff_dtype == "f16" else
+                       "f32 coefficients x f32 dictionary on f32 MFMA; f32 up-sampling and filtering"),
         "data": "synthetic",
         "config": {"workload": wl.name, "hr": f"{wl.W}x{wl.H}", "scale": wl.scale, "channels": wl.c,
                    "L": wl.L, "k": wl.k, "atoms_read": n_read, "batch": wl.n,
