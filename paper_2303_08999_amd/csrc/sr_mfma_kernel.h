@@ -39,6 +39,7 @@
 #pragma once
 #include "sr_device.h"
 #include "sr_launch.h"
+#include <type_traits>
 
 
 namespace srd {
@@ -124,7 +125,12 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     __shared__ unsigned ptab[2 * F::NLOAD];         // byte offset of the plane each lane half loads
 
     const int tid0 = threadIdx.x;
-    if ((int)blockIdx.x >= ntiles) return;
+    const int groups = (gridDim.x & 7) == 0 ? 8 : 1;
+    const int G = gridDim.x / groups;                              // stride inside a share
+    const int share = (ntiles + groups - 1) / groups;
+    const int t_first = (int)(blockIdx.x % groups) * share + (int)(blockIdx.x / groups);
+    const int t_end = min(ntiles, ((int)(blockIdx.x % groups) + 1) * share);
+    if (t_first >= t_end) return;                                  // whole workgroup: no tile
 
     // ---- once per workgroup: weight, plane-offset and dictionary operand tables ---
     const unsigned plane_b = (unsigned)a.H * (unsigned)a.W * (unsigned)F::CB;   // bytes per coefficient plane
@@ -180,11 +186,14 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     }
     __syncthreads();
 
-    // ---- tile walk: this workgroup takes tiles blockIdx.x, +gridDim.x, ...  The
+    // ---- tile walk.  Workgroups are dealt to the 8 XCDs round-robin by index, and
+    //      each XCD has its own L2.  When the grid is a multiple of 8, XCD x (the
+    //      workgroups with blockIdx.x % 8 == x) walks its own contiguous share of the
+    //      tiles in raster order, so that tiles above one another, whose LR
+    //      footprints overlap, meet in the same L2 at about the same time.  The
     //      step is pre-split into (image, tile row, tile column) so that no
     //      division is left in the loop.  All of it is scalar.
     const int per_img = tiles_x * tiles_y;
-    const int G = gridDim.x;
     const int step_n = G / per_img, step_r = G - step_n * per_img;
     const int step_y = step_r / tiles_x, step_x = step_r - step_y * tiles_x;
     auto advance = [&](TilePos p) -> TilePos {
@@ -197,7 +206,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     };
     TilePos cur;
     {
-        const int t0 = blockIdx.x;
+        const int t0 = t_first;
         cur.n = t0 / per_img;
         const int r2 = t0 - cur.n * per_img;
         cur.ty = r2 / tiles_x;
@@ -216,19 +225,24 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         unsigned xo[F::NXC];
 #pragma unroll
         for (int xc = 0; xc < F::NXC; ++xc) xo[xc] = (unsigned)clampi(o.lx0 + lane + 64 * xc, 0, a.w - 1) * lr_esz;
+        auto rows = [&](auto f16) {
 #pragma unroll
-        for (int u = 0; u < F::NLRP; ++u) {
-            const int p = wave + NW * u, c = p / MAXLRY, ry = p - c * MAXLRY;
-            if (p < C * MAXLRY && ry < o.nly) {
-                const unsigned row = ((unsigned)(tp.n * C + c) * (unsigned)a.h +
-                                      (unsigned)clampi(o.ly0 + ry, 0, a.h - 1)) * (unsigned)a.w * lr_esz;
+            for (int u = 0; u < F::NLRP; ++u) {
+                const int p = wave + NW * u, c = p / MAXLRY, ry = p - c * MAXLRY;
+                if (p < C * MAXLRY && ry < o.nly) {
+                    const unsigned row = ((unsigned)(tp.n * C + c) * (unsigned)a.h +
+                                          (unsigned)clampi(o.ly0 + ry, 0, a.h - 1)) * (unsigned)a.w * lr_esz;
 #pragma unroll
-                for (int xc = 0; xc < F::NXC; ++xc) {
-                    const char* q = lr_base + (size_t)(row + xo[xc]);
-                    lrv[u][xc] = a.io_f16 ? (unsigned)*(const unsigned short*)q : *(const unsigned*)q;
+                    for (int xc = 0; xc < F::NXC; ++xc)
+                        if (xc == 0 || 64 * xc < o.nlx) {     // whole 64-column chunks the tile never reads
+                            const char* q = lr_base + (size_t)(row + xo[xc]);
+                            lrv[u][xc] = decltype(f16)::value ? (unsigned)*(const unsigned short*)q : *(const unsigned*)q;
+                        }
                 }
             }
-        }
+        };
+        if (a.io_f16) rows(std::true_type{});
+        else rows(std::false_type{});
     };
 
     // coefficient base of a tile for this lane: image base (scalar) + pixel offset
@@ -256,18 +270,12 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             raw[i] = __builtin_nontemporal_load((const Raw*)(cimg + (pix_off + pt[i])));
     }
 
-    for (int t = blockIdx.x; t < ntiles; t += G) {
-        // Per-iteration copy of the thread id the optimiser cannot see through:
-        // index arithmetic derived from it is recomputed each tile instead of
-        // being hoisted out of the loop into dozens of long-lived registers.
-        int tid = tid0;
-        asm volatile("" : "+v"(tid));
+    // ---- stage 1 in three steps; a workgroup barrier separates each from the next.
+    // (a) tap tables of a tile and its LR footprint, registers -> LDS
+    auto stage1_setup = [&](const TilePos tp, int tid) {
         const int lane = tid & 63;
-        const int hf = lane >> 5, j = lane & 31, jr = j / F::WC, jc = j % F::WC;
-        const int Y0 = cur.ty * F::TH, X0 = cur.tx * F::TW;
+        const int Y0 = tp.ty * F::TH, X0 = tp.tx * F::TW;
         const TileOrigin o = tile_origin(Y0, X0, F::R, UH, UW, a.H, a.W, a.s);
-
-        // (1) stage 1 set-up: LR footprint registers -> LDS, tap tables of the tile
         if (tid < UW) {
             int m;
             const int f = src_floor(clampi(X0 - F::R + tid, 0, a.W - 1), a.s, m);
@@ -294,42 +302,93 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                     }
             }
         }
-        // (2) prefetch the next tile's LR footprint now: it lands while this tile is
-        //     up-sampled, before the matrix-core phase waits on outstanding loads
-        const bool more_tiles = t + G < ntiles;
-        const TilePos nxt = more_tiles ? advance(cur) : cur;
-        if (more_tiles) load_lr(nxt, lane, lrv);
-        __syncthreads();
-        // vertical pass on the narrow LR footprint: V[c][yy][rx]
-        {
-            const int sh = o.nlx <= 32 ? 5 : (o.nlx <= 64 ? 6 : 7);
-            const int total = (C * UH) << sh;
-            for (int idx = tid; idx < total; idx += NT) {
-                const int pr = idx >> sh, rx = idx & ((1 << sh) - 1);
-                if (rx < MAXLRX) {
-                    const int c = pr / UH, yy = pr - c * UH;
-                    const float4 w4 = yw[yy];
-                    const float wt[4] = {w4.x, w4.y, w4.z, w4.w};
-                    const float* p = lrT + (c * MAXLRY + yb[yy]) * MAXLRX + rx;
-                    V[pr * MAXLRX + rx] = dot4(wt, p[0], p[MAXLRX], p[2 * MAXLRX], p[3 * MAXLRX]);
-                }
+    };
+    // (b) vertical pass on the narrow LR footprint: V[c][yy][rx].  Four elements per
+    //     thread at a time, their table reads and then their 16 footprint reads
+    //     issued together, so that LDS latency is paid once per batch and not twice
+    //     per element.  Loads are clamped into range; only the store is guarded.
+    auto stage1_vertical = [&](const TilePos tp, int tid) {
+        const TileOrigin o = tile_origin(tp.ty * F::TH, tp.tx * F::TW, F::R, UH, UW, a.H, a.W, a.s);
+        const int sh = o.nlx <= 32 ? 5 : (o.nlx <= 64 ? 6 : 7);
+        const int total = (C * UH) << sh;
+        const int rx = tid & ((1 << sh) - 1);
+        const int rxc = rx < MAXLRX ? rx : MAXLRX - 1;
+        for (int base = tid; base < total; base += 4 * NT) {
+            float4 w4[4];
+            int src[4], dst[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int idx = base + k * NT;
+                const int pr = idx < total ? idx >> sh : C * UH - 1;
+                const int c = pr / UH, yy = pr - c * UH;
+                w4[k] = yw[yy];
+                src[k] = (c * MAXLRY + yb[yy]) * MAXLRX + rxc;
+                dst[k] = (idx < total && rx < MAXLRX) ? pr * MAXLRX + rx : -1;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            float v[4][4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[k][i] = lrT[src[k] + i * MAXLRX];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float wt[4] = {w4[k].x, w4[k].y, w4[k].z, w4[k].w};
+                if (dst[k] >= 0) V[dst[k]] = dot4(wt, v[k][0], v[k][1], v[k][2], v[k][3]);
             }
         }
-        __syncthreads();
-        // horizontal pass: a thread owns one (channel, column), its weights stay in
-        // registers, rows are independent (no tables, immediate offsets)
+    };
+    // (c) horizontal pass into the swizzled tile: a thread owns one (channel,
+    //     column), its weights stay in registers, rows are independent (no tables,
+    //     immediate offsets).  Rows go in batches: all reads of a batch are issued
+    //     before its arithmetic.
+    auto stage1_horizontal = [&](int tid) {
         for (int col = tid; col < C * UW; col += NT) {
             const int c = col / UW, xx = col - c * UW;
             const float4 w4 = xw[xx];
             const float wt[4] = {w4.x, w4.y, w4.z, w4.w};
             const float* src = V + c * UH * MAXLRX + xb[xx];
             float* dst = U + c * UH * P + (xx % PX) * NG + xx / PX;
+            constexpr int RB = 7;
 #pragma unroll
-            for (int yy = 0; yy < UH; ++yy) {
-                const float* p = src + yy * MAXLRX;
-                dst[yy * P] = dot4(wt, p[0], p[1], p[2], p[3]);
+            for (int y0 = 0; y0 < UH; y0 += RB) {
+                float v[RB][4];
+#pragma unroll
+                for (int r = 0; r < RB; ++r)
+                    if (y0 + r < UH) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) v[r][i] = src[(y0 + r) * MAXLRX + i];
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int r = 0; r < RB; ++r)
+                    if (y0 + r < UH) dst[(y0 + r) * P] = dot4(wt, v[r][0], v[r][1], v[r][2], v[r][3]);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
+    };
+
+    for (int t = t_first; t < t_end; t += G) {
+        // Per-iteration copy of the thread id the optimiser cannot see through:
+        // index arithmetic derived from it is recomputed each tile instead of
+        // being hoisted out of the loop into dozens of long-lived registers.
+        int tid = tid0;
+        asm volatile("" : "+v"(tid));
+        const int lane = tid & 63;
+        const int hf = lane >> 5, j = lane & 31, jr = j / F::WC, jc = j % F::WC;
+        const int Y0 = cur.ty * F::TH, X0 = cur.tx * F::TW;
+        const bool more_tiles = t + G < t_end;
+        const TilePos nxt = more_tiles ? advance(cur) : cur;
+
+        // (1) stage 1 of this tile.  (Spreading steps (a) and (b) of the next tile
+        //     over the unit loop was measured slower: the extra mid-tile barrier and
+        //     LDS traffic cost more than the shorter gap between tiles gains.)
+        stage1_setup(cur, tid);
+        __syncthreads();
+        stage1_vertical(cur, tid);
+        __syncthreads();      // also: every wavefront is done with the previous tile's U
+        stage1_horizontal(tid);
         __syncthreads();
         const unsigned* pt = ptab + hf * F::NLOAD;
         // The wavefront's NU units of this tile, one after the other; while a unit
@@ -489,6 +548,10 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 }
             }
         }
+        // (2) prefetch the next tile's LR footprint from inside the unit loop, where
+        //     the wavefront waits on memory anyway, and not in the barrier-to-barrier
+        //     up-sampling phase that every wavefront of the workgroup has to sit out
+        if (unit == (NU > 1 ? 1 : 0) && more_tiles) load_lr(nxt, lane, lrv);
         }   // unit
         cur = nxt;
     }
@@ -506,7 +569,7 @@ hipError_t launch_one(const AssembleArgs& a, hipStream_t st) {
     // as many workgroups as stay resident (WPE wavefronts per SIMD)
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess)
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     const int cap = cus * (4 * WPE / NW > 0 ? 4 * WPE / NW : 1);
     const int blocks = nt < cap ? (int)nt : cap;
     hipLaunchKernelGGL((k_assemble_mfma<K, C, NP8, PX, WR, NW, NU, WPE, F32>), dim3(blocks), dim3(F::NT), 0, st,
