@@ -37,6 +37,35 @@ def read_traffic(workload):
         return None
 
 
+def empirical_ceilings(sr, torch, wl, coeffs, outs, kernel_ms):
+    """Secondary roofline context: the machine's own streaming rates for this byte mix,
+    from the library's probes (no arithmetic in them), timed like the kernel."""
+    if wl.coeff_dtype != "f16" or wl.L not in (72, 128) or wl.hr_pixels % 128 or outs[0].dtype != torch.float32:
+        return None
+    sink = torch.zeros(4, device="cuda", dtype=torch.int32)
+
+    def timed(fn, reps=20):
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for i, (a, b) in enumerate(ev):
+            a.record(); fn(i); b.record()
+        torch.cuda.synchronize()
+        return sum(a.elapsed_time(b) for a, b in ev) / reps
+
+    px = wl.hr_pixels // wl.n
+    coeff_bytes = wl.L * px * 2
+    t_read = timed(lambda i: sr.sr_probe_read(coeffs[i % len(coeffs)][0], sink))
+    t_mix = timed(lambda i: sr.sr_probe_mix(coeffs[i % len(coeffs)][0], wl.L, px, outs[i % 2][0], wl.c))
+    mix_bytes = coeff_bytes + wl.c * px * 4
+    return {"read_only_GBps": round(coeff_bytes / t_read / 1e6, 1),
+            "mix_GBps": round(mix_bytes / t_mix / 1e6, 1), "mix_ms": round(t_mix, 4),
+            "kernel_time_over_mix_time": round(kernel_ms * 1.0 / (t_mix * wl.n), 3),
+            "note": "streaming probes of the same library on one frame's coefficient planes: read-only, and "
+                    "the kernel's read + write mix with no arithmetic (same planes, same output size)"}
+
+
 def cpu_baseline(wl, lr, coeff, dictionary, budget_s=20.0):
     """The oracle as it stands, on the host cores, on a band of HR rows of the same
     frame sized to take roughly `budget_s` of CPU work."""
@@ -162,6 +191,9 @@ def main():
                      "algorithmic_bytes": alg_bytes},
         "pct_of_hbm_peak": round(100.0 * achieved / HBM_PEAK_GBS, 2),
     }
+    emp = empirical_ceilings(sr, torch, wl, coeffs, outs, avg_ms)
+    if emp is not None:
+        result["roofline"]["empirical"] = emp
     if args.kept_sweep:
         import numpy as np
         rng = np.random.default_rng(7)

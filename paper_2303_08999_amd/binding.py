@@ -18,7 +18,8 @@ SR_KERNEL_AUTO, SR_KERNEL_GENERIC, SR_KERNEL_MFMA = 0, 1, 2
 SR_MAX_ATOMS = 256
 
 EXPORTS = ("sr_dict_assemble", "sr_dict_assemble_selective", "sr_dict_assemble_ex",
-           "sr_bicubic_upsample", "sr_dict_assemble_plan", "sr_strerror", "sr_version")
+           "sr_bicubic_upsample", "sr_dict_assemble_plan", "sr_strerror", "sr_version",
+           "sr_probe_read", "sr_probe_mix")
 
 
 class sr_tensor(ctypes.Structure):
@@ -58,6 +59,8 @@ def load():
     lib.sr_dict_assemble_plan.argtypes = [T, T, T, i, i, i, i, T, ip, i, O]
     lib.sr_bicubic_upsample.argtypes = [T, i, i, T, vp]
     lib.sr_strerror.argtypes = [i]
+    lib.sr_probe_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    lib.sr_probe_mix.argtypes = [vp, i, ctypes.c_size_t, vp, i, vp]
     lib.sr_strerror.restype = ctypes.c_char_p
     lib.sr_version.argtypes = []
     for name in EXPORTS:
@@ -164,3 +167,19 @@ def sr_dict_assemble_plan(lr, coeff, dict, L, k, scale, channels, out, kept=None
 def sr_bicubic_upsample(lr, scale, channels, out, stream=None):
     _check(load().sr_bicubic_upsample(describe(lr), scale, channels, describe(out), _stream(stream)))
     return out
+
+
+def sr_probe_read(src, sink, stream=None):
+    """Streaming read of the whole tensor ``src`` (include/sr_probe.h); ``sink`` is any
+    device tensor of at least 4 bytes."""
+    nbytes = src.numel() * src.element_size()
+    _check(load().sr_probe_read(ctypes.c_void_p(src.data_ptr()), nbytes,
+                                ctypes.c_void_p(sink.data_ptr()), _stream(stream)))
+
+
+def sr_probe_mix(coeff, planes, pixels, out, channels, stream=None):
+    """The assembly kernel's read + write stream with no work in it (include/sr_probe.h)."""
+    assert coeff.numel() * coeff.element_size() >= planes * pixels * 2
+    assert out.numel() * out.element_size() >= channels * pixels * 4
+    _check(load().sr_probe_mix(ctypes.c_void_p(coeff.data_ptr()), planes, pixels,
+                               ctypes.c_void_p(out.data_ptr()), channels, _stream(stream)))

@@ -22,9 +22,13 @@ def lib():
 
 
 def _declared():
-    text = open(os.path.join(ROOT, "include", "sr_dict.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(sr_[a-z_]+)\s*\(", text)))
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for header in sorted(os.listdir(inc)):
+        if header.endswith(".h"):
+            text = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, header)).read(), flags=re.S)
+            names.update(re.findall(r"\b(sr_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -165,3 +169,19 @@ def test_empty_batches_are_noops(lib):
         t.n = 0
     assert lib.sr_dict_assemble(lr, coeff, d, 72, 5, 4, 3, out, None) == 0
     assert lib.sr_bicubic_upsample(lr, 4, 3, out, None) == 0
+
+
+def test_probe_argument_checks_launch_nothing(lib):
+    vp = ctypes.c_void_p
+    good, sink = vp(0x10000000), vp(0x20000000)
+    assert lib.sr_probe_read(None, 1024, sink, None) == -1
+    assert lib.sr_probe_read(good, 1024, None, None) == -1
+    assert lib.sr_probe_read(good, 1000, sink, None) == -3          # not a multiple of 16 bytes
+    assert lib.sr_probe_read(vp(0x10000004), 1024, sink, None) == -7
+    assert lib.sr_probe_read(good, 0, sink, None) == 0               # empty: nothing to launch
+    assert lib.sr_probe_mix(None, 72, 1280, sink, 3, None) == -1
+    assert lib.sr_probe_mix(good, 70, 1280, sink, 3, None) == -3     # plane count not built
+    assert lib.sr_probe_mix(good, 72, 1000, sink, 3, None) == -3     # not whole 128-pixel runs
+    assert lib.sr_probe_mix(good, 72, 1280, sink, 5, None) == -3
+    assert lib.sr_probe_mix(good, 72, 1280, vp(0x20000008), 3, None) == -7
+    assert lib.sr_probe_mix(good, 128, 0, sink, 1, None) == 0
