@@ -66,6 +66,11 @@ def empirical_ceilings(sr, torch, wl, coeffs, outs, kernel_ms):
                     "the kernel's read + write mix with no arithmetic (same planes, same output size)"}
 
 
+def sr_synth_stored(t):
+    import sr_synth
+    return sr_synth.stored_numpy(t)
+
+
 def cpu_baseline(wl, lr, coeff, dictionary, budget_s=20.0):
     """The oracle as it stands, on the host cores, on a band of HR rows of the same
     frame sized to take roughly `budget_s` of CPU work."""
@@ -74,7 +79,7 @@ def cpu_baseline(wl, lr, coeff, dictionary, budget_s=20.0):
     oracle.build()
     lr_h = lr.cpu().numpy()
     d_h = dictionary.cpu().numpy()
-    c_h = coeff.cpu().numpy()
+    c_h = sr_synth_stored(coeff)
     threads = oracle.threads()
     t0 = time.perf_counter()
     U = oracle.bicubic(lr_h, wl.scale)
@@ -170,16 +175,20 @@ def main():
     alg_bytes = wl.algorithmic_bytes(n_read)
     achieved = alg_bytes / (avg_ms * 1e-3) / 1e9
     result = {
-        "metric": "HR Mpixel/s of dictionary assembly (4K x4, L=72, fp16) + % of HBM peak",
+        "metric": ("HR Mpixel/s of dictionary assembly (4K x4, L=72, fp16) + % of HBM peak" if wl.name == "4k_dense"
+                   else f"HR Mpixel/s of dictionary assembly ({wl.name}) + % of HBM peak"),
         "value": round(px * args.steps / wall / 1e6, 1),
         "unit": "HR Mpixel/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(wall / args.steps * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16" if (plan == 2 and wl.coeff_dtype == "f16") else "f32",
+        "dtype": "f16" if (plan == 2 and wl.coeff_dtype in ("f16", "f8")) else "f32",
         "arithmetic": ("f32 vector ALU" if plan != 2 else
                        "f16 coefficients x f16 (hi+lo) dictionary on MFMA with f32 accumulation; f32 up-sampling "
                        "and filtering" if wl.coeff_dtype == "f16" else
+                       "coefficients stored as 8-bit E4M3, widened exactly to f16 in registers, x f16 (hi+lo) "
+                       "dictionary on MFMA with f32 accumulation; f32 up-sampling and filtering"
+                       if wl.coeff_dtype == "f8" else
                        "f32 coefficients x f32 dictionary on f32 MFMA; f32 up-sampling and filtering"),
         "data": "synthetic",
         "config": {"workload": wl.name, "hr": f"{wl.W}x{wl.H}", "scale": wl.scale, "channels": wl.c,

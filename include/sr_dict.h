@@ -24,8 +24,8 @@
  *     r = (k-1)/2: a correlation, no flip;
  *   - the same coefficients are applied to every image channel;
  *   - no clamping or rounding of intermediate values; arithmetic is fp32
- *     (fp16 coefficients enter matrix-core products exactly, accumulation is
- *     fp32).
+ *     (fp16 and fp8 coefficients enter matrix-core products exactly,
+ *     accumulation is fp32).
  *
  * All tensors are contiguous NCHW in DEVICE memory, allocated, owned and freed
  * by the caller.  The library allocates nothing, keeps no state between calls
@@ -44,11 +44,15 @@
 extern "C" {
 #endif
 
-#define SR_VERSION 100           /* major*10000 + minor*100 + patch */
+#define SR_VERSION 200           /* major*10000 + minor*100 + patch */
 #define SR_MAX_ATOMS 256         /* largest L (and n_kept) accepted   */
 #define SR_MAX_CHANNELS 16       /* largest C accepted                */
 
-typedef enum { SR_F32 = 0, SR_F16 = 1 } sr_dtype;
+/* SR_F8E4M3: one byte per value, 1 sign / 4 exponent (bias 7) / 3 mantissa bits,
+ * subnormals, no infinities, largest finite 448, 0x7f and 0xff are NaN (the OCP
+ * 8-bit "E4M3" format).  Accepted for the coefficient tensor only: a storage
+ * format that halves the stream again; it is widened exactly before use. */
+typedef enum { SR_F32 = 0, SR_F16 = 1, SR_F8E4M3 = 2 } sr_dtype;
 
 /* Contiguous NCHW tensor in device memory. */
 typedef struct {
@@ -74,8 +78,8 @@ typedef enum {
 typedef enum {
     SR_KERNEL_AUTO    = 0,     /* the library picks                                */
     SR_KERNEL_GENERIC = 1,     /* fp32 vector-ALU kernel: every supported case      */
-    SR_KERNEL_MFMA    = 2      /* matrix-core kernel (fp16 coefficients on fp16
-                                  MFMA, fp32 coefficients on fp32 MFMA); the call
+    SR_KERNEL_MFMA    = 2      /* matrix-core kernel (fp16 and fp8 coefficients on
+                                  fp16 MFMA, fp32 coefficients on fp32 MFMA); the call
                                   fails with SR_ERR_UNSUPPORTED if the case does
                                   not qualify (see sr_dict_assemble_ex)            */
 } sr_kernel;
@@ -90,7 +94,7 @@ typedef struct {
  * Dense dictionary assembly (Eq. 2 / Eq. 3 with stage 1 fused in).
  *
  *   lr     [N][C][h][w]            f32 or f16   LR image x
- *   coeff  [N][L][s*h][s*w]        f32 or f16   Phi, one plane per atom
+ *   coeff  [N][L][s*h][s*w]        f32, f16 or f8e4m3   Phi, one plane per atom
  *   dict   [1][L][k][k]            f32          D, row-major taps
  *   out    [N][C][s*h][s*w]        same dtype as lr; written
  *   L, k, scale, channels          must equal coeff->c, dict->h (= dict->w),
@@ -99,8 +103,8 @@ typedef struct {
  *
  * Supported: k in {3,5,7}; scale in {2,3,4}; 1 <= L <= SR_MAX_ATOMS;
  * 1 <= C <= SR_MAX_CHANNELS; N >= 0 (N = 0 or an empty image is a no-op
- * returning SR_OK).  With f16 coefficients the dictionary entries must be
- * finite in fp16 (|D| < 65504).
+ * returning SR_OK).  With f16 or f8 coefficients the dictionary entries must
+ * be finite in fp16 (|D| < 65504); f8 NaN codes give unspecified results.
  */
 int sr_dict_assemble(const sr_tensor* lr, const sr_tensor* coeff, const sr_tensor* dict,
                      int L, int k, int scale, int channels,
@@ -131,7 +135,8 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
  * < 2^32, N*C*H*W < 2^30) and
  *   f16 coefficients: k = 5 with at most 72 folded atoms and HR width % 4 == 0,
  *                     or k = 7 with at most 128 atoms and HR width % 2 == 0;
- *   f32 coefficients: k = 5 with at most 72 folded atoms and HR width % 2 == 0.
+ *   f32 coefficients: k = 5 with at most 72 folded atoms and HR width % 2 == 0;
+ *   f8  coefficients: k = 5 with at most 72 folded atoms and HR width % 4 == 0.
  * Every other supported case runs on the generic kernel.
  */
 int sr_dict_assemble_ex(const sr_tensor* lr, const sr_tensor* coeff, const sr_tensor* dict,

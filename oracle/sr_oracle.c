@@ -48,7 +48,7 @@
 #include <omp.h>
 #endif
 
-enum { ORC_F32 = 0, ORC_F16 = 1, ORC_F64 = 2 };
+enum { ORC_F32 = 0, ORC_F16 = 1, ORC_F64 = 2, ORC_F8E4M3 = 3 };
 
 /* IEEE binary16 bit pattern -> double, exactly (subnormals, inf, nan). */
 double orc_half_to_double(uint16_t h)
@@ -66,11 +66,35 @@ double orc_half_to_double(uint16_t h)
     return sign ? -v : v;
 }
 
+/*
+ * 8-bit float "E4M3" (1 sign, 4 exponent bits with bias 7, 3 mantissa bits;
+ * exponent field 0 holds subnormals m * 2^-9; there are no infinities, the
+ * all-ones magnitude 0x7f is NaN, the largest finite value is 1.75 * 2^8 = 448)
+ * -> double, exactly.  A storage format for coefficients only (an extension of
+ * the paper's "do not move what you do not need", section III-A): the path
+ * computes with the widened value.
+ */
+double orc_e4m3_to_double(uint8_t b)
+{
+    int sign = (b >> 7) & 1;
+    int e = (b >> 3) & 0xf;
+    int m = b & 0x7;
+    double v;
+    if (e == 15 && m == 7)
+        v = NAN;
+    else if (e == 0)
+        v = ldexp((double)m, -9);
+    else
+        v = ldexp((double)(m + 8), e - 10);
+    return sign ? -v : v;
+}
+
 static double load_elem(const void *p, int dtype, size_t i)
 {
     switch (dtype) {
     case ORC_F32: return (double)((const float *)p)[i];
     case ORC_F16: return orc_half_to_double(((const uint16_t *)p)[i]);
+    case ORC_F8E4M3: return orc_e4m3_to_double(((const uint8_t *)p)[i]);
     default:      return ((const double *)p)[i];
     }
 }

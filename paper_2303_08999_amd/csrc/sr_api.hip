@@ -9,8 +9,9 @@ using namespace srd;
 
 namespace {
 
-size_t elem_size(sr_dtype d) { return d == SR_F16 ? 2 : 4; }
-bool dtype_ok(int d) { return d == SR_F32 || d == SR_F16; }
+size_t elem_size(sr_dtype d) { return d == SR_F16 ? 2 : (d == SR_F8E4M3 ? 1 : 4); }
+bool dtype_ok(int d) { return d == SR_F32 || d == SR_F16; }                    // images
+bool coeff_dtype_ok(int d) { return dtype_ok(d) || d == SR_F8E4M3; }           // coefficients
 
 size_t tensor_bytes(const sr_tensor* t) {
     return (size_t)t->n * t->c * t->h * t->w * elem_size(t->dtype);
@@ -43,7 +44,7 @@ void make_plan(Plan& p, const sr_tensor* lr, const sr_tensor* coeff, const sr_te
     p.tile = 0;
     p.empty = false;
     if (!lr || !coeff || !dict || !out) { p.status = SR_ERR_NULL; return; }
-    if (!dtype_ok(lr->dtype) || !dtype_ok(coeff->dtype) || !dtype_ok(out->dtype) ||
+    if (!dtype_ok(lr->dtype) || !coeff_dtype_ok(coeff->dtype) || !dtype_ok(out->dtype) ||
         dict->dtype != SR_F32 || out->dtype != lr->dtype) { p.status = SR_ERR_UNSUPPORTED; return; }
     if (!dims_ok(lr) || !dims_ok(coeff) || !dims_ok(dict) || !dims_ok(out)) { p.status = SR_ERR_SHAPE; return; }
     if (k != 3 && k != 5 && k != 7) { p.status = SR_ERR_UNSUPPORTED; return; }
@@ -84,7 +85,7 @@ void make_plan(Plan& p, const sr_tensor* lr, const sr_tensor* coeff, const sr_te
         a.n_fold = L;
     }
     a.io_f16 = lr->dtype == SR_F16;
-    a.coeff_f32 = coeff->dtype == SR_F32;
+    a.coeff_dtype = coeff->dtype;
     p.empty = lr->n == 0 || lr->h == 0 || lr->w == 0;
     if (!p.empty) {
         if (!lr->data || !coeff->data || !dict->data || !out->data) { p.status = SR_ERR_NULL; return; }
@@ -97,7 +98,7 @@ void make_plan(Plan& p, const sr_tensor* lr, const sr_tensor* coeff, const sr_te
 
     const int want = opts ? opts->kernel : SR_KERNEL_AUTO;
     const int tile = opts ? opts->tile : 0;
-    const bool can_mfma = !p.empty && mfma_supported(a, k, coeff->dtype == SR_F16, tile);
+    const bool can_mfma = !p.empty && mfma_supported(a, k, coeff->dtype, tile);
     if (want == SR_KERNEL_MFMA && !can_mfma) { p.status = SR_ERR_UNSUPPORTED; return; }
     p.kernel = (want == SR_KERNEL_GENERIC || !can_mfma) ? SR_KERNEL_GENERIC : SR_KERNEL_MFMA;
     p.tile = tile;
@@ -118,7 +119,7 @@ __attribute__((visibility("default"))) int sr_dict_assemble_ex(const sr_tensor* 
     const bool io_f16 = lr->dtype == SR_F16;
     hipError_t e = (p.kernel == SR_KERNEL_MFMA)
                        ? launch_mfma(p.args, k, io_f16, p.tile, st)
-                       : launch_generic(p.args, k, coeff->dtype == SR_F16, io_f16, st);
+                       : launch_generic(p.args, k, io_f16, st);
     return e == hipSuccess ? SR_OK : SR_ERR_LAUNCH;
 }
 

@@ -26,7 +26,7 @@ struct AssembleArgs {
     int N, C, h, w, H, W, s, L;
     int n_fold;           // atoms folded: L (dense) or n_kept
     int io_f16;           // lr and out are fp16 (else fp32)
-    int coeff_f32;        // coefficients are fp32 (else fp16)
+    int coeff_dtype;      // sr_dtype of the stored coefficients
     int   kept[SR_MAX_ATOMS];    // plane read for folded atom i (identity when dense)
     float gamma[SR_MAX_ATOMS];   // its scale (1 when dense)
 };
@@ -43,6 +43,12 @@ __device__ __forceinline__ int clampi(int v, int lo, int hi) {
 
 __device__ __forceinline__ float ld_as_float(const float* p, size_t i) { return p[i]; }
 __device__ __forceinline__ float ld_as_float(const __half* p, size_t i) { return __half2float(p[i]); }
+// fp8 e4m3 (OCP: bias 7, no infinities, largest 448) coefficient, one byte each;
+// the conversion instruction widens exactly
+struct f8e4m3 { unsigned char bits; };
+__device__ __forceinline__ float ld_as_float(const f8e4m3* p, size_t i) {
+    return __builtin_amdgcn_cvt_f32_fp8((int)p[i].bits, 0);
+}
 __device__ __forceinline__ void st_from_float(float* p, size_t i, float v) { p[i] = v; }
 // fp32 -> fp16 with the fp32 value materialised first: the empty asm keeps the
 // compiler from folding the producing fma and the narrowing into one

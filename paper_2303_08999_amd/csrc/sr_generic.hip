@@ -118,11 +118,14 @@ static hipError_t launch_generic_k(const AssembleArgs& a, int k, dim3 grid, hipS
     return hipGetLastError();
 }
 
-hipError_t launch_generic(const AssembleArgs& a, int k, bool coeff_f16, bool io_f16, hipStream_t st) {
+hipError_t launch_generic(const AssembleArgs& a, int k, bool io_f16, hipStream_t st) {
     const dim3 grid((a.W + GTW - 1) / GTW, (a.H + GTH - 1) / GTH, a.N);
-    if (coeff_f16)
+    if (a.coeff_dtype == SR_F16)
         return io_f16 ? launch_generic_k<__half, __half>(a, k, grid, st)
                       : launch_generic_k<__half, float>(a, k, grid, st);
+    if (a.coeff_dtype == SR_F8E4M3)
+        return io_f16 ? launch_generic_k<f8e4m3, __half>(a, k, grid, st)
+                      : launch_generic_k<f8e4m3, float>(a, k, grid, st);
     return io_f16 ? launch_generic_k<float, __half>(a, k, grid, st)
                   : launch_generic_k<float, float>(a, k, grid, st);
 }

@@ -5,11 +5,11 @@
 
 namespace srd {
 
-hipError_t launch_generic(const AssembleArgs& a, int k, bool coeff_f16, bool io_f16, hipStream_t st);
+hipError_t launch_generic(const AssembleArgs& a, int k, bool io_f16, hipStream_t st);   // coefficient dtype: a.coeff_dtype
 hipError_t launch_bicubic(const BicubicArgs& a, bool in_f16, bool out_f16, hipStream_t st);
 
 // Matrix-core kernel.  mfma_supported() is a pure host-side predicate.
-bool mfma_supported(const AssembleArgs& a, int k, bool coeff_f16, int tile);
+bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile);
 hipError_t launch_mfma(const AssembleArgs& a, int k, bool io_f16, int tile, hipStream_t st);
 
 }  // namespace srd

@@ -8,6 +8,7 @@ namespace srd {
 hipError_t launch_mfma_k5(const AssembleArgs& a, int np8, int shape, hipStream_t st);
 hipError_t launch_mfma_k7(const AssembleArgs& a, int np8, int shape, hipStream_t st);
 hipError_t launch_mfma_k5_f32(const AssembleArgs& a, int np8, hipStream_t st);
+hipError_t launch_mfma_k5_f8(const AssembleArgs& a, int np8, hipStream_t st);
 
 namespace {
 
@@ -16,9 +17,13 @@ constexpr int N_TILE_SHAPES = 6;
 // Capacity (in groups of 8 folded atoms) of the smallest built instantiation
 // that holds n_fold atoms; 0 = none.  Unused capacity costs MFMA issue slots
 // only: padding atoms meet zero dictionary rows and re-read a cached plane.
-int np8_for(int k, int channels, int n_fold, bool coeff_f16) {
+int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
     const int need = (n_fold + 7) / 8;
-    if (!coeff_f16) return (k == 5 && need <= 9) ? 9 : 0;     // fp32 coefficients: 5x5, up to 72 atoms
+    if (coeff_dtype == SR_F32) return (k == 5 && need <= 9) ? 9 : 0;     // fp32 coefficients: 5x5, up to 72 atoms
+    if (coeff_dtype == SR_F8E4M3) {                                     // fp8: 5x5, up to 72 atoms
+        if (k != 5 || need > 9) return 0;
+        return (channels == 3 && need <= 1) ? 1 : 9;
+    }
     static const int k5c3[] = {1, 2, 4, 6, 9, 0}, k5c1[] = {1, 4, 9, 0};
     static const int k7c3[] = {2, 9, 16, 0}, k7c1[] = {16, 0};
     const int* built = k == 5 ? (channels == 3 ? k5c3 : k5c1) : (channels == 3 ? k7c3 : k7c1);
@@ -29,25 +34,26 @@ int np8_for(int k, int channels, int n_fold, bool coeff_f16) {
 
 }  // namespace
 
-bool mfma_supported(const AssembleArgs& a, int k, bool coeff_f16, int tile) {
+bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
     if ((k != 5 && k != 7) || (a.C != 1 && a.C != 3)) return false;
-    // a lane loads PX consecutive fp16 pixels of a row with one PX*2-byte load and
-    // stores PX/2 results per channel: rows must keep that alignment
-    const int px = (k == 5 && coeff_f16) ? 4 : 2;
-    const unsigned long long cb = coeff_f16 ? 2ull : 4ull;
+    // a lane loads PX consecutive pixels of a row with one load and stores PX/2
+    // results per channel: rows must keep that alignment
+    const int px = (k == 5 && coeff_dtype != SR_F32) ? 4 : 2;
+    const unsigned long long cb = coeff_dtype == SR_F32 ? 4ull : (coeff_dtype == SR_F16 ? 2ull : 1ull);
     if (a.W % px != 0 || a.W < px || a.H < 1) return false;
     if (((uintptr_t)a.coeff % 16) != 0 || ((uintptr_t)a.out % 16) != 0) return false;
     if ((unsigned long long)a.L * a.H * a.W * cb >= (1ull << 32)) return false;           // 32-bit plane offsets
     if ((unsigned long long)a.N * a.C * a.H * a.W * 4ull >= (1ull << 32)) return false;   // 32-bit image offsets
-    if (np8_for(k, a.C, a.n_fold, coeff_f16) == 0) return false;
+    if (np8_for(k, a.C, a.n_fold, coeff_dtype) == 0) return false;
     if (tile < 0 || tile >= N_TILE_SHAPES) return false;
     return true;
 }
 
 hipError_t launch_mfma(const AssembleArgs& a, int k, bool io_f16, int tile, hipStream_t st) {
     (void)io_f16;
-    const int np8 = np8_for(k, a.C, a.n_fold, !a.coeff_f32);
-    if (a.coeff_f32) return launch_mfma_k5_f32(a, np8, st);
+    const int np8 = np8_for(k, a.C, a.n_fold, a.coeff_dtype);
+    if (a.coeff_dtype == SR_F32) return launch_mfma_k5_f32(a, np8, st);
+    if (a.coeff_dtype == SR_F8E4M3) return launch_mfma_k5_f8(a, np8, st);
     if (k == 5) return launch_mfma_k5(a, np8, tile, st);
     if (k == 7) return launch_mfma_k7(a, np8, tile, st);
     return hipErrorInvalidValue;

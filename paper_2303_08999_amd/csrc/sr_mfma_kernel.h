@@ -50,8 +50,12 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
-template <int K, int C, int NP8, int PX, int WR, int NW, int NU, bool F32 = false>
+// how the coefficients are stored (template argument CT of the kernel)
+constexpr int CT_F16 = 0, CT_F32 = 1, CT_F8 = 2;
+
+template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int CT = CT_F16>
 struct Cfg {
+    static constexpr bool F32 = CT == CT_F32, F8 = CT == CT_F8;
     static constexpr int KK = K * K, R = (K - 1) / 2;
     static constexpr int RH0 = (K + 1) / 2;            // filter rows owned by lane half 0
     static constexpr int NSLOT = RH0 * K;              // accumulator rows used per half
@@ -72,7 +76,7 @@ struct Cfg {
     static constexpr int N16 = F32 ? 0 : NP8 / 2, N8 = F32 ? 0 : NP8 % 2;
     static constexpr int N2 = F32 ? 4 * NP8 : 0;
     static constexpr int NLOAD = F32 ? N2 : 8 * N16 + 4 * N8;   // coefficient loads per lane and unit
-    static constexpr int CB = F32 ? 4 : 2;             // bytes per stored coefficient
+    static constexpr int CB = F32 ? 4 : (F8 ? 1 : 2);  // bytes per stored coefficient
     static constexpr int NXC = (MAXLRX + 63) / 64;     // 64-column chunks of the LR footprint
     static constexpr int NLRP = (C * MAXLRY + NW - 1) / NW;   // (channel,row) pairs per wavefront
 };
@@ -85,6 +89,22 @@ template <> struct RawT<4> { typedef unsigned type; };
 __device__ __forceinline__ unsigned raw_word(const u32x4& v, int m) { return v[m]; }
 __device__ __forceinline__ unsigned raw_word(const u32x2& v, int m) { return v[m]; }
 __device__ __forceinline__ unsigned raw_word(const unsigned& v, int) { return v; }
+
+// Word m (fp16 pixels 2m, 2m+1) of one plane's raw load.  fp8 (e4m3) coefficients
+// are widened here, two at a time; every e4m3 value is exact in fp16.
+template <bool F8, int NWORD, typename RawV>
+__device__ __forceinline__ void plane_words(const RawV& r, unsigned (&w)[NWORD]) {
+    if constexpr (F8) {
+        static_assert(NWORD == 2, "fp8 coefficients: four pixels per lane");
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+        const unsigned bits = raw_word(r, 0);           // four fp8 pixels
+        w[0] = __builtin_bit_cast(unsigned, (h2)__builtin_amdgcn_cvt_scalef32_pk_f16_fp8(bits, 1.0f, false));
+        w[1] = __builtin_bit_cast(unsigned, (h2)__builtin_amdgcn_cvt_scalef32_pk_f16_fp8(bits, 1.0f, true));
+    } else {
+#pragma unroll
+        for (int m = 0; m < NWORD; ++m) w[m] = raw_word(r, m);
+    }
+}
 
 // (atom pair, pixel q) from two planes' packed pixels
 __device__ __forceinline__ unsigned pack_pair(unsigned plane_even, unsigned plane_odd, int q) {
@@ -104,10 +124,11 @@ __device__ __forceinline__ int tap_of_row(int i, int mb) {
 
 struct TilePos { int n, ty, tx; };
 
-template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, bool F32>
+template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT>
 __global__ __launch_bounds__(64 * NW, WPE)
 void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y, const int ntiles) {
-    using F = Cfg<K, C, NP8, PX, WR, NW, NU, F32>;
+    using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT>;
+    constexpr bool F32 = F::F32, F8 = F::F8;
     using Raw = typename RawT<PX * F::CB>::type;
     constexpr int NT = F::NT, P = F::P, NG = F::NG, UH = F::UH, UW = F::UW;
     constexpr int N16 = F::N16, N8 = F::N8, NMB = F::NMB;
@@ -437,13 +458,15 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 #pragma unroll
                 for (int hl = 0; hl < 2; ++hl)
                     av[mb][hl] = __builtin_bit_cast(f16x8, A16[((c16 * NMB + mb) * 2 + hl) * 64 + lane]);
+            constexpr int NWORD = PX / 2 > 0 ? PX / 2 : 1;
+            unsigned cw[8][NWORD];                  // the step's 8 planes as fp16 pixel pairs
+#pragma unroll
+            for (int i = 0; i < 8; ++i) plane_words<F8>(raw[8 * c16 + i], cw[i]);
 #pragma unroll
             for (int q = 0; q < PX; ++q) {
                 u32x4 bw;
 #pragma unroll
-                for (int m = 0; m < 4; ++m)
-                    bw[m] = pack_pair(raw_word(raw[8 * c16 + 2 * m], q >> 1),
-                                      raw_word(raw[8 * c16 + 2 * m + 1], q >> 1), q);
+                for (int m = 0; m < 4; ++m) bw[m] = pack_pair(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q);
                 const f16x8 b = __builtin_bit_cast(f16x8, bw);
 #pragma unroll
                 for (int mb = 0; mb < NMB; ++mb)
@@ -466,13 +489,15 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 #pragma unroll
                 for (int hl = 0; hl < 2; ++hl)
                     av[mb][hl] = __builtin_bit_cast(f16x4, A8[(mb * 2 + hl) * 64 + lane]);
+            constexpr int NWORD = PX / 2 > 0 ? PX / 2 : 1;
+            unsigned cw[4][NWORD];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) plane_words<F8>(raw[8 * N16 + i], cw[i]);
 #pragma unroll
             for (int q = 0; q < PX; ++q) {
                 u32x2 bw;
 #pragma unroll
-                for (int m = 0; m < 2; ++m)
-                    bw[m] = pack_pair(raw_word(raw[8 * N16 + 2 * m], q >> 1),
-                                      raw_word(raw[8 * N16 + 2 * m + 1], q >> 1), q);
+                for (int m = 0; m < 2; ++m) bw[m] = pack_pair(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q);
                 const f16x4 b = __builtin_bit_cast(f16x4, bw);
 #pragma unroll
                 for (int mb = 0; mb < NMB; ++mb)
@@ -560,9 +585,9 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 // ---------------------------------------------------------------------------
 // Host side: launch of one instantiation on a persistent grid.
 // ---------------------------------------------------------------------------
-template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, bool F32 = false>
+template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT = CT_F16>
 hipError_t launch_one(const AssembleArgs& a, hipStream_t st) {
-    using F = Cfg<K, C, NP8, PX, WR, NW, NU, F32>;
+    using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT>;
     const int tiles_x = (a.W + F::TW - 1) / F::TW, tiles_y = (a.H + F::TH - 1) / F::TH;
     const long long nt = (long long)tiles_x * tiles_y * a.N;
     if (nt > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -572,7 +597,7 @@ hipError_t launch_one(const AssembleArgs& a, hipStream_t st) {
         (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     const int cap = cus * (4 * WPE / NW > 0 ? 4 * WPE / NW : 1);
     const int blocks = nt < cap ? (int)nt : cap;
-    hipLaunchKernelGGL((k_assemble_mfma<K, C, NP8, PX, WR, NW, NU, WPE, F32>), dim3(blocks), dim3(F::NT), 0, st,
+    hipLaunchKernelGGL((k_assemble_mfma<K, C, NP8, PX, WR, NW, NU, WPE, CT>), dim3(blocks), dim3(F::NT), 0, st,
                        a, tiles_x, tiles_y, (int)nt);
     return hipGetLastError();
 }

@@ -39,7 +39,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_version_and_strerror(lib):
-    assert sr.sr_version() == 100
+    assert sr.sr_version() == 200
     assert sr.sr_strerror(0) == "success"
     for code in range(-7, 0):
         assert sr.sr_strerror(code) not in ("", "success", "unknown status")
@@ -185,3 +185,22 @@ def test_probe_argument_checks_launch_nothing(lib):
     assert lib.sr_probe_mix(good, 72, 1280, sink, 5, None) == -3
     assert lib.sr_probe_mix(good, 72, 1280, vp(0x20000008), 3, None) == -7
     assert lib.sr_probe_mix(good, 128, 0, sink, 1, None) == 0
+
+
+def test_e4m3_coefficients_are_a_coefficient_format_only(lib):
+    F8 = sr.SR_F8E4M3
+    assert F8 == 2
+    lr, coeff, d, out = case(cd=F8)
+    assert plan(lr, coeff, d, out) == sr.SR_KERNEL_MFMA              # 5x5, 72 atoms, width % 4 == 0
+    lr, coeff, d, out = case(cd=F8, w=15)                             # HR width 60 is fine, 4-byte loads
+    assert plan(lr, coeff, d, out) == sr.SR_KERNEL_MFMA
+    lr, coeff, d, out = case(cd=F8, s=2, w=15)                        # HR width 30: not a multiple of 4
+    assert plan(lr, coeff, d, out, s=2) == sr.SR_KERNEL_GENERIC
+    lr, coeff, d, out = case(cd=F8, k=7, L=100)
+    assert plan(lr, coeff, d, out, L=100, k=7) == sr.SR_KERNEL_GENERIC
+    coeff_odd = T(0x11000001, F8, 1, 72, 32, 64)                      # one-byte elements: any address
+    assert plan(lr, coeff_odd, T(0x18000000, sr.SR_F32, 1, 72, 5, 5), out) == sr.SR_KERNEL_GENERIC
+    lr8, coeff, d, out = case(io=F8)
+    assert plan(lr8, coeff, d, out) == -3                             # images cannot be E4M3
+    lr, coeff, d, out = case()
+    assert plan(lr, coeff, T(0x18000000, F8, 1, 72, 5, 5), out) == -3  # nor the dictionary

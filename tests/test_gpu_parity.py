@@ -48,7 +48,7 @@ def run_gpu(inp, wl, kernel, kept=None, gamma=None, tile=0):
 
 
 def host(inp):
-    return {k: (v.cpu().numpy() if torch.is_tensor(v) else v) for k, v in inp.items()}
+    return {k: (sr_synth.stored_numpy(v) if torch.is_tensor(v) else v) for k, v in inp.items()}
 
 
 def planned(inp, wl, kernel, kept=None, tile=0):
@@ -65,7 +65,7 @@ def check_full(oracle, wl, kernel, kept=None, gamma=None, inp=None, tile=0):
     hi = host(inp)
     ref = oracle.dict_assemble(hi["lr"], hi["coeff"], hi["dict"], wl.scale, kept=kept, gamma=gamma)
     assert not np.isnan(got).any(), "some output pixel was never written"
-    worst, tol, ok = tolerance_ok(got, ref, wl.coeff_dtype == "f16", wl.lr_dtype == "f16")
+    worst, tol, ok = tolerance_ok(got, ref, wl.coeff_dtype in ("f16", "f8"), wl.lr_dtype == "f16")
     assert ok, f"{wl.name}: worst error {worst:.3e} exceeds {tol:.0e}"
     return worst
 
@@ -125,6 +125,39 @@ def test_4k_dense_full_frame_in_the_benchmarked_configuration(oracle):
     assert float(err.max()) <= 2e-3, f"worst error {err.max():.3e}"
 
 
+def test_4k_dense_fp8_full_frame(oracle):
+    """The 4K frame with the coefficients stored as 8-bit E4M3 floats: every output
+    against the oracle, which widens the same stored bytes."""
+    wl = sr_synth.WORKLOADS["4k_dense_fp8"]
+    inp = sr_synth.make_inputs(wl, DEV)
+    assert planned(inp, wl, sr.SR_KERNEL_AUTO) == MFMA
+    got = run_gpu(inp, wl, sr.SR_KERNEL_AUTO).cpu().numpy()
+    hi = host(inp)
+    assert hi["coeff"].dtype == np.uint8
+    ref = oracle.dict_assemble(hi["lr"], hi["coeff"], hi["dict"], wl.scale)
+    err = np.abs(got.astype(np.float64) - ref)
+    assert not np.isnan(got).any()
+    assert float(err.max()) <= 2e-3, f"worst error {err.max():.3e}"
+
+
+def test_every_fp8_code_is_widened_as_the_oracle_does(oracle):
+    """All 254 finite E4M3 codes, one per pixel, through a single centred delta atom on a
+    constant image: the output IS the widened coefficient (both kernels, bit for bit)."""
+    codes = [b for b in range(256) if b & 0x7F != 0x7F]
+    H, W = 8, 32                                    # 256 HR pixels >= 254 codes
+    bits = torch.tensor((codes + [0, 0])[:H * W], dtype=torch.uint8).reshape(1, 1, H, W)
+    coeff = bits.view(torch.float8_e4m3fn).to(DEV)
+    lr = torch.ones((1, 1, H // 2, W // 2), device=DEV)
+    D = torch.zeros((1, 1, 5, 5), device=DEV)
+    D[0, 0, 2, 2] = 1.0
+    want = np.array([oracle.e4m3_to_double(int(b)) for b in bits.flatten()]).reshape(H, W)
+    for kernel in (sr.SR_KERNEL_GENERIC, sr.SR_KERNEL_MFMA):
+        out = torch.full((1, 1, H, W), float("nan"), device=DEV)
+        sr.sr_dict_assemble_ex(lr, coeff, D, 1, 5, 2, 1, out, opts=sr.make_options(kernel, 0))
+        torch.cuda.synchronize()
+        assert np.array_equal(out[0, 0].cpu().numpy().astype(np.float64), want), f"kernel {kernel}"
+
+
 def test_4k_selective_full_frame(oracle):
     """4K with the 8 kept atoms of the selective workload (global kept list)."""
     wl = sr_synth.WORKLOADS["4k_selective"]
@@ -176,6 +209,11 @@ RAGGED = [
     (20, 27, 3, 1, 41, 5, "f32", "f16", 1),     # ... HR width 81: odd, generic kernel only
     (18, 26, 3, 1, 41, 5, "f32", "f16", 1),     # ... HR width 78, one channel, fp16 image
     (31, 45, 4, 3, 9, 5, "f32", "f32", 1),      # ... few atoms
+    (33, 47, 4, 3, 72, 5, "f8", "f32", 2),      # 8-bit E4M3 coefficients on the matrix-core path
+    (29, 36, 3, 1, 72, 5, "f8", "f16", 1),      # ... one channel, fp16 image, x3
+    (17, 34, 4, 3, 7, 5, "f8", "f32", 1),       # ... few atoms (the 8-atom instantiation)
+    (26, 31, 2, 3, 50, 5, "f8", "f32", 1),      # ... HR width 62: generic kernel only
+    (12, 20, 4, 3, 100, 7, "f8", "f16", 1),     # ... 7x7 atoms: generic kernel only
 ]
 
 
