@@ -38,7 +38,9 @@
  * reproduction (fixes a = -0.5 and the coordinate convention), a library
  * bicubic at that library's own a, delta atoms, linearity, constant
  * preservation, an exact-rational apply-then-weight evaluator, a library
- * unfold + einsum for stages 3 + 4.  No function here is unpinned.
+ * unfold + einsum for stages 3 + 4; the 8-bit E4M3 decoder by hand-computed
+ * codes and a library decoder over all 256 codes (tests/test_oracle_fp8.py).
+ * No function here is unpinned.
  */
 #include <math.h>
 #include <stddef.h>
