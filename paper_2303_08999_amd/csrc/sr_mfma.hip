@@ -42,6 +42,8 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
     const unsigned long long cb = coeff_dtype == SR_F32 ? 4ull : (coeff_dtype == SR_F16 ? 2ull : 1ull);
     if (a.W % px != 0 || a.W < px || a.H < 1) return false;
     if (((uintptr_t)a.coeff % 16) != 0 || ((uintptr_t)a.out % 16) != 0) return false;
+    // the fp8 instantiations read the LR image as aligned 32-bit words
+    if (coeff_dtype == SR_F8E4M3 && ((uintptr_t)a.lr % 4) != 0) return false;
     if ((unsigned long long)a.L * a.H * a.W * cb >= (1ull << 32)) return false;           // 32-bit plane offsets
     if ((unsigned long long)a.N * a.C * a.H * a.W * 4ull >= (1ull << 32)) return false;   // 32-bit image offsets
     if (np8_for(k, a.C, a.n_fold, coeff_dtype) == 0) return false;

@@ -241,29 +241,68 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     // LR footprint of a tile -> registers, as raw bits (fp16 is widened when it is
     // written to LDS).  Wavefront w takes (channel,row) pairs w, w+NW, ...; the lane
     // is the column.  Row addressing is scalar; one add per load on the vector side.
-    auto load_lr = [&](const TilePos tp, int lane, unsigned (&lrv)[F::NLRP][F::NXC]) {
+    //
+    // Two forms.  LRBF (used where the coefficient stream is light enough for the
+    // issue time of these loads to show, measured 4 % on the 8-bit 4K frame): every
+    // slot is loaded unconditionally, as the aligned 32-bit word holding the
+    // element (an fp16 image keeps which half in `par`, one bit per slot); slots
+    // the tile does not need repeat the wavefront's first row / chunk, a line that
+    // is already on its way.  No branch and one load type leave the compiler
+    // nothing to merge at a join, so the loads go out back to back.  Otherwise:
+    // only the needed slots are loaded (fewer requests, which is what counts when
+    // the stream is the bound or the tile is small).
+    constexpr bool LRBF = F8 && NP8 > 2;
+    static_assert(!LRBF || F::NLRP * F::NXC <= 32, "one parity bit per footprint slot");
+    const unsigned lr_sh = a.io_f16 ? 1u : 2u;          // log2 of the element size
+    auto load_lr = [&](const TilePos tp, int lane, unsigned (&lrv)[F::NLRP][F::NXC], unsigned& par) {
         const TileOrigin o = tile_origin(tp.ty * F::TH, tp.tx * F::TW, F::R, UH, UW, a.H, a.W, a.s);
-        unsigned xo[F::NXC];
+        if constexpr (LRBF) {
+            unsigned xcol[F::NXC];
 #pragma unroll
-        for (int xc = 0; xc < F::NXC; ++xc) xo[xc] = (unsigned)clampi(o.lx0 + lane + 64 * xc, 0, a.w - 1) * lr_esz;
-        auto rows = [&](auto f16) {
+            for (int xc = 0; xc < F::NXC; ++xc) {
+                xcol[xc] = (unsigned)clampi(o.lx0 + lane + 64 * xc, 0, a.w - 1);
+                if (xc > 0 && 64 * xc >= o.nlx) xcol[xc] = xcol[0];
+            }
+            par = 0u;
+            unsigned row0 = 0u;
 #pragma unroll
             for (int u = 0; u < F::NLRP; ++u) {
                 const int p = wave + NW * u, c = p / MAXLRY, ry = p - c * MAXLRY;
-                if (p < C * MAXLRY && ry < o.nly) {
-                    const unsigned row = ((unsigned)(tp.n * C + c) * (unsigned)a.h +
-                                          (unsigned)clampi(o.ly0 + ry, 0, a.h - 1)) * (unsigned)a.w * lr_esz;
+                const bool need = p < C * MAXLRY && ry < o.nly;
+                unsigned row = ((unsigned)(tp.n * C + (need ? c : 0)) * (unsigned)a.h +
+                                (unsigned)clampi(o.ly0 + (need ? ry : 0), 0, a.h - 1)) * (unsigned)a.w;   // in elements
+                if (u == 0) row0 = row;
+                if (!need) row = row0;
 #pragma unroll
-                    for (int xc = 0; xc < F::NXC; ++xc)
-                        if (xc == 0 || 64 * xc < o.nlx) {     // whole 64-column chunks the tile never reads
-                            const char* q = lr_base + (size_t)(row + xo[xc]);
-                            lrv[u][xc] = decltype(f16)::value ? (unsigned)*(const unsigned short*)q : *(const unsigned*)q;
-                        }
+                for (int xc = 0; xc < F::NXC; ++xc) {
+                    const unsigned byte = (row + xcol[xc]) << lr_sh;
+                    par |= ((byte >> 1) & 1u) << (u * F::NXC + xc);
+                    lrv[u][xc] = *(const unsigned*)(lr_base + (size_t)(byte & ~3u));
                 }
             }
-        };
-        if (a.io_f16) rows(std::true_type{});
-        else rows(std::false_type{});
+        } else {
+            unsigned xo[F::NXC];
+#pragma unroll
+            for (int xc = 0; xc < F::NXC; ++xc) xo[xc] = (unsigned)clampi(o.lx0 + lane + 64 * xc, 0, a.w - 1) * lr_esz;
+            auto rows = [&](auto f16) {
+#pragma unroll
+                for (int u = 0; u < F::NLRP; ++u) {
+                    const int p = wave + NW * u, c = p / MAXLRY, ry = p - c * MAXLRY;
+                    if (p < C * MAXLRY && ry < o.nly) {
+                        const unsigned row = ((unsigned)(tp.n * C + c) * (unsigned)a.h +
+                                              (unsigned)clampi(o.ly0 + ry, 0, a.h - 1)) * (unsigned)a.w * lr_esz;
+#pragma unroll
+                        for (int xc = 0; xc < F::NXC; ++xc)
+                            if (xc == 0 || 64 * xc < o.nlx) {     // whole 64-column chunks the tile never reads
+                                const char* q = lr_base + (size_t)(row + xo[xc]);
+                                lrv[u][xc] = decltype(f16)::value ? (unsigned)*(const unsigned short*)q : *(const unsigned*)q;
+                            }
+                    }
+                }
+            };
+            if (a.io_f16) rows(std::true_type{});
+            else rows(std::false_type{});
+        }
     };
 
     // coefficient base of a tile for this lane: image base (scalar) + pixel offset
@@ -275,14 +314,14 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     };
 
     Raw raw[F::NLOAD];
-    unsigned lrv[F::NLRP][F::NXC];
+    unsigned lrv[F::NLRP][F::NXC], lrpar = 0u;
 #pragma unroll
     for (int u = 0; u < F::NLRP; ++u)
 #pragma unroll
         for (int xc = 0; xc < F::NXC; ++xc) lrv[u][xc] = 0u;
     {
         const int lane = tid0 & 63, hf = lane >> 5, j = lane & 31;
-        load_lr(cur, lane, lrv);
+        load_lr(cur, lane, lrv, lrpar);
         unsigned pix_off;
         const char* cimg = phi_base(cur, 0, j / F::WC, j % F::WC, pix_off);
         const unsigned* pt = ptab + hf * F::NLOAD;
@@ -317,7 +356,8 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 #pragma unroll
                 for (int xc = 0; xc < F::NXC; ++xc)
                     if (lane + 64 * xc < MAXLRX) {
-                        const unsigned bits = lrv[u][xc];
+                        unsigned bits = lrv[u][xc];
+                        if (LRBF && a.io_f16) bits = ((lrpar >> (u * F::NXC + xc)) & 1u) ? bits >> 16 : bits & 0xffffu;
                         lrT[p * MAXLRX + lane + 64 * xc] =
                             a.io_f16 ? __half2float(__ushort_as_half((unsigned short)bits)) : __uint_as_float(bits);
                     }
@@ -576,7 +616,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         // (2) prefetch the next tile's LR footprint from inside the unit loop, where
         //     the wavefront waits on memory anyway, and not in the barrier-to-barrier
         //     up-sampling phase that every wavefront of the workgroup has to sit out
-        if (unit == (NU > 1 ? 1 : 0) && more_tiles) load_lr(nxt, lane, lrv);
+        if (unit == (NU > 1 ? 1 : 0) && more_tiles) load_lr(nxt, lane, lrv, lrpar);
         }   // unit
         cur = nxt;
     }
