@@ -71,7 +71,7 @@ def sr_synth_stored(t):
     return sr_synth.stored_numpy(t)
 
 
-def cpu_baseline(wl, lr, coeff, dictionary, budget_s=20.0):
+def cpu_baseline(wl, lr, coeff, dictionary, budget_s=20.0, single_thread_720p=True):
     """The oracle as it stands, on the host cores, on a band of HR rows of the same
     frame sized to take roughly `budget_s` of CPU work."""
     import numpy as np
@@ -100,7 +100,21 @@ def cpu_baseline(wl, lr, coeff, dictionary, budget_s=20.0):
     # stage 1 is charged in proportion to the band
     t_total = t_band / passes + t_up * rows / wl.H
     mpx = rows * wl.W * wl.n / t_total / 1e6
+    single = None
+    if single_thread_720p:
+        # the same oracle on ONE thread, whole 720p frame (fp32 coefficients) of the workload list
+        import sr_synth
+        w7 = sr_synth.WORKLOADS["720p"]
+        i7 = sr_synth.make_inputs(w7, "cpu")
+        oracle.set_threads(1)
+        t0 = time.perf_counter()
+        oracle.dict_assemble(i7["lr"].numpy(), i7["coeff"].numpy(), i7["dict"].numpy(), w7.scale)
+        t1 = time.perf_counter() - t0
+        oracle.set_threads(threads)
+        single = {"value": round(w7.hr_pixels / t1 / 1e6, 3), "unit": "HR Mpixel/s", "cores": 1,
+                  "sample": f"whole 720p frame ({w7.hr_pixels} pixels, fp32 coefficients), {t1:.2f} s"}
     return {"value": round(mpx, 3), "unit": "HR Mpixel/s", "cores": threads, "kind": "oracle",
+            "single_thread": single,
             "sample": f"HR rows 0..{rows - 1} of {wl.H} of the same 4K frame ({rows * wl.W} pixels), "
                       f"double precision, OpenMP over rows; mean of {passes} passes, {t_total:.2f} s each"}
 

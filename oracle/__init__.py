@@ -62,6 +62,8 @@ def _load():
         lib.orc_assemble_points.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_vp, c_int, c_int,
                                             c_vp, c_int, c_vp, c_int, c_vp, c_vp, c_int, c_vp]
         lib.orc_threads.restype = c_int
+        lib.orc_set_threads.restype = c_int
+        lib.orc_set_threads.argtypes = [c_int]
         _lib = lib
     return _lib
 
@@ -100,6 +102,11 @@ def taps(index: int, scale: int, a: float = -0.5):
 
 def threads() -> int:
     return _load().orc_threads()
+
+
+def set_threads(n: int) -> int:
+    """Threads for the row loops from now on (timing only); returns the number in force."""
+    return _load().orc_set_threads(int(n))
 
 
 def bicubic(lr, scale: int, a: float = -0.5) -> np.ndarray:

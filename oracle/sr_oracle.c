@@ -295,3 +295,16 @@ int orc_threads(void)
     return 1;
 #endif
 }
+
+/* Set that number (n >= 1); returns the number now in force.  Timing only: the
+ * results do not depend on it. */
+int orc_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1)
+        omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+    return orc_threads();
+}

@@ -204,3 +204,25 @@ def test_e4m3_coefficients_are_a_coefficient_format_only(lib):
     assert plan(lr8, coeff, d, out) == -3                             # images cannot be E4M3
     lr, coeff, d, out = case()
     assert plan(lr, coeff, T(0x18000000, F8, 1, 72, 5, 5), out) == -3  # nor the dictionary
+
+
+def test_matrix_core_kernel_declines_tensors_beyond_32_bit_offsets(lib):
+    def big(L, cd, n=1, h=2048, w=1024):
+        lr = T(0x10000000, sr.SR_F32, n, 3, h, w)
+        coeff = T(0x1000000000, cd, n, L, 4 * h, 4 * w)
+        d = T(0x80000000, sr.SR_F32, 1, L, 5, 5)
+        out = T(0x4000000000, sr.SR_F32, n, 3, 4 * h, 4 * w)
+        return lr, coeff, d, out
+    # 72 planes of 8192 x 4096 fp16 = 4.5 GiB: plane offsets no longer fit 32 bits
+    lr, coeff, d, out = big(72, sr.SR_F16)
+    assert plan(lr, coeff, d, out) == sr.SR_KERNEL_GENERIC
+    assert plan(lr, coeff, d, out, opts=sr.make_options(sr.SR_KERNEL_MFMA, 0)) == -3
+    # the same frame with 40 atoms (2.5 GiB) still qualifies
+    lr, coeff, d, out = big(40, sr.SR_F16)
+    assert plan(lr, coeff, d, out, L=40) == sr.SR_KERNEL_MFMA
+    # ... and as 8-bit coefficients all 72 planes do (2.25 GiB)
+    lr, coeff, d, out = big(72, sr.SR_F8E4M3)
+    assert plan(lr, coeff, d, out) == sr.SR_KERNEL_MFMA
+    # a batch whose fp32 output exceeds 2^32 bytes
+    lr, coeff, d, out = big(8, sr.SR_F16, n=44, h=540, w=960)
+    assert plan(lr, coeff, d, out, L=8) == sr.SR_KERNEL_GENERIC

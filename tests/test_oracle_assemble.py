@@ -154,3 +154,18 @@ def test_bad_arguments_are_rejected(oracle):
         oracle.assemble(U, coeff[:, :2], D)
     with pytest.raises(ValueError):
         oracle.assemble(U, coeff, np.zeros((5, 4, 4)))
+
+
+def test_results_do_not_depend_on_the_thread_count(oracle):
+    wl = sr_synth.Workload("thr", 22, 1, 2, 9, 7, 2, 11, 3, "f32", "f32")
+    inp = sr_synth.make_inputs(wl, "cpu")
+    args = (inp["lr"].numpy(), inp["coeff"].numpy(), inp["dict"].numpy(), wl.scale)
+    before = oracle.threads()
+    try:
+        assert oracle.set_threads(1) == 1
+        one = oracle.dict_assemble(*args)
+        assert oracle.set_threads(3) == 3
+        three = oracle.dict_assemble(*args)
+    finally:
+        oracle.set_threads(before)
+    assert np.array_equal(one, three)
