@@ -157,15 +157,13 @@ def test_bad_arguments_are_rejected(oracle):
 
 
 def test_results_do_not_depend_on_the_thread_count(oracle):
-    wl = sr_synth.Workload("thr", 22, 1, 2, 9, 7, 2, 11, 3, "f32", "f32")
-    inp = sr_synth.make_inputs(wl, "cpu")
-    args = (inp["lr"].numpy(), inp["coeff"].numpy(), inp["dict"].numpy(), wl.scale)
+    U, coeff, D = _rand_case(77, n=2, c=2, H=19, W=11, L=7, k=5)
     before = oracle.threads()
     try:
         assert oracle.set_threads(1) == 1
-        one = oracle.dict_assemble(*args)
+        one = oracle.assemble(U, coeff, D)
         assert oracle.set_threads(3) == 3
-        three = oracle.dict_assemble(*args)
+        three = oracle.assemble(U, coeff, D)
     finally:
         oracle.set_threads(before)
     assert np.array_equal(one, three)
