@@ -6,8 +6,8 @@
 // Eq. 3 are never written to memory.
 //
 // This kernel is bound by the fp32 ALUs (L*k^2 multiply-adds per pixel), not by
-// HBM; the matrix-core kernel in sr_mfma.hip is the fast path for fp16
-// coefficients.
+// HBM; the matrix-core kernel (sr_mfma_kernel.h) is the fast path wherever it
+// qualifies.
 #include "sr_device.h"
 #include "sr_launch.h"
 

@@ -1,4 +1,6 @@
-// Matrix-core kernel for fp16 coefficients (gfx950 / CDNA4).
+// Matrix-core kernel (gfx950 / CDNA4).  Described for fp16 coefficients, the
+// headline case; fp32 and 8-bit coefficients differ only in stage 3's operand
+// handling (end of this comment).
 //
 // One fused, persistent kernel does stage 1 (up-sampling), stage 3
 // (F_i = Phi_i D, paper Eq. 2) and stage 4 (y_i = F_i B_i^T) for tiles of HR
@@ -36,11 +38,18 @@
 //
 // The up-sampled tile is stored in LDS column-swizzled, (x % PX) major, so the
 // 32 pixels of one MFMA (stride PX in x) read consecutive banks.
+//
+// Other coefficient types (template argument CT):
+//   * CT_F32: 2-atom steps of v_mfma_f32_32x32x2_f32; lane half hf loads plane
+//     2*step + hf and the loaded words are the B operand as they are; the
+//     dictionary stays fp32, products and sums are true fp32;
+//   * CT_F8 (8-bit E4M3 storage): 4 pixels per 4-byte load, widened exactly to
+//     fp16 pairs in registers, then the fp16 steps above.
 #pragma once
-#include "sr_device.h"
-#include "sr_launch.h"
 #include <type_traits>
 
+#include "sr_device.h"
+#include "sr_launch.h"
 
 namespace srd {
 
