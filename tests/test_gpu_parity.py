@@ -364,6 +364,33 @@ def test_runs_on_a_side_stream():
     assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_replays_inside_a_captured_graph(kernel):
+    """The library allocates nothing and enqueues one kernel, so a call can be captured
+    in a HIP graph.  Three replays, new inputs copied into the captured buffers between
+    them and eager work in between, each compared with an eager call."""
+    wl = sr_synth.scaled(sr_synth.WORKLOADS["4k_dense"], h=40, w=64)
+    first = sr_synth.make_inputs(wl, DEV)
+    if planned(first, wl, kernel) != kernel:
+        pytest.skip("this kernel does not take this case")
+    lr, coeff, D = first["lr"].clone(), first["coeff"].clone(), first["dict"].clone()
+    out = torch.zeros((wl.n, wl.c, wl.H, wl.W), device=DEV)
+    opts = sr.make_options(kernel, 0)
+    sr.sr_dict_assemble_ex(lr, coeff, D, wl.L, wl.k, wl.scale, wl.c, out, opts=opts)   # warm-up outside capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sr.sr_dict_assemble_ex(lr, coeff, D, wl.L, wl.k, wl.scale, wl.c, out, opts=opts)
+    for rep in range(3):
+        fresh = sr_synth.make_inputs(sr_synth.scaled(wl, index=wl.index + 1 + rep), DEV)
+        lr.copy_(fresh["lr"]); coeff.copy_(fresh["coeff"]); D.copy_(fresh["dict"])
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        eager = run_gpu(fresh, wl, kernel)
+        assert torch.equal(out, eager), f"replay {rep}"
+
+
 def test_tile_sweep_returns_a_valid_shape():
     """The measured launch-shape search (stand-in for the paper's constrained
     Bayesian search) visits every built tile shape and picks one of them."""
