@@ -209,6 +209,8 @@ RAGGED = [
     (20, 27, 3, 1, 41, 5, "f32", "f16", 1),     # ... HR width 81: odd, generic kernel only
     (18, 26, 3, 1, 41, 5, "f32", "f16", 1),     # ... HR width 78, one channel, fp16 image
     (31, 45, 4, 3, 9, 5, "f32", "f32", 1),      # ... few atoms
+    (6, 8, 2, 16, 9, 3, "f16", "f32", 1),       # the largest channel count accepted
+    (60, 128, 4, 3, 24, 5, "f16", "f32", 9),    # 540 tiles over 9 images: every XCD share crosses image borders
     (33, 47, 4, 3, 72, 5, "f8", "f32", 2),      # 8-bit E4M3 coefficients on the matrix-core path
     (29, 36, 3, 1, 72, 5, "f8", "f16", 1),      # ... one channel, fp16 image, x3
     (17, 34, 4, 3, 7, 5, "f8", "f32", 1),       # ... few atoms (the 8-atom instantiation)
