@@ -18,8 +18,10 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "sr_oracle.c")
-_LIB = os.path.join(_HERE, "libsr_oracle.so")
+# The mutation test (tests/test_oracle_mutations.py) points these two at a deliberately
+# broken copy of the source to check that the pins notice; nothing else sets them.
+_SRC = os.environ.get("SR_ORACLE_SRC") or os.path.join(_HERE, "sr_oracle.c")
+_LIB = os.environ.get("SR_ORACLE_LIB") or os.path.join(_HERE, "libsr_oracle.so")
 
 # uint8 arrays are stored 8-bit E4M3 floats (numpy has no such dtype)
 _DT = {np.dtype(np.float32): 0, np.dtype(np.float16): 1, np.dtype(np.float64): 2, np.dtype(np.uint8): 3}
