@@ -1,0 +1,71 @@
+"""Would the GPU parity comparison notice a wrong result?  The HIP path's output is
+compared, with the very tolerances of the parity tests, against deliberately broken
+copies of the oracle (the mistakes are planted in the oracle's C source, on the CPU;
+the GPU code is untouched).  Every broken copy must be told apart from the GPU
+result; the unmodified copy must agree with it."""
+import importlib.util
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+import paper_2303_08999_amd as sr
+import sr_synth
+from test_oracle_mutations import MUTATIONS, ROOT, SRC
+
+pytestmark = pytest.mark.gpu
+
+# mistakes that change the result on ordinary inputs of this case (decoder mutations and
+# the batch stride are exercised by their own pins and by the batched parity cases)
+PLANTED = ["keys_inner_coefficient", "keys_outer_coefficient", "no_half_pixel_centres", "first_tap_off_by_one",
+           "inner_tap_weights_swapped", "upsampler_axes_transposed", "lr_border_not_replicated",
+           "kept_position_instead_of_atom", "gamma_dropped", "filter_transposed", "filter_flipped",
+           "patch_not_centred", "hr_border_zero_instead_of_replicate", "same_channel_for_all"]
+
+
+def _oracle_copy(text, workdir, tag):
+    src, lib = os.path.join(workdir, f"o_{tag}.c"), os.path.join(workdir, f"libo_{tag}.so")
+    with open(src, "w") as f:
+        f.write(text)
+    subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-ffp-contract=off",
+                           "-o", lib, src, "-lm"])
+    os.environ["SR_ORACLE_SRC"], os.environ["SR_ORACLE_LIB"] = src, lib
+    try:
+        spec = importlib.util.spec_from_file_location(f"oracle_copy_{tag}", os.path.join(ROOT, "oracle", "__init__.py"))
+        mod = importlib.util.module_from_spec(spec)
+        spec.loader.exec_module(mod)
+        mod._load()
+    finally:
+        del os.environ["SR_ORACLE_SRC"], os.environ["SR_ORACLE_LIB"]
+    return mod
+
+
+@pytest.mark.parametrize("coeff_dtype,tol", [("f16", 2e-3), ("f32", 1e-5)])
+def test_parity_tolerances_tell_broken_oracles_apart(tmp_path, coeff_dtype, tol):
+    wl = sr_synth.Workload("sharp", 23, 1, 3, 21, 34, 2, 40, 5, coeff_dtype, "f32", 0.0, 1.5)
+    inp = sr_synth.make_inputs(wl, "cuda")
+    kept = np.array([5, 1, 33, 8, 20, 39, 2], dtype=np.int32)       # any order, not sorted
+    gamma = np.array([0.5, 1.5, -1.0, 2.0, 0.75, 1.25, 1.0], dtype=np.float32)
+    out = torch.empty((wl.n, wl.c, wl.H, wl.W), device="cuda")
+    sr.sr_dict_assemble_ex(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, out,
+                           kept=kept, gamma=gamma)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    lr, cf, D = (sr_synth.stored_numpy(inp[k]) for k in ("lr", "coeff", "dict"))
+
+    def agrees(mod):
+        ref = mod.dict_assemble(lr, cf, D, wl.scale, kept=kept, gamma=gamma.astype(np.float64))
+        bound = tol if coeff_dtype == "f16" else tol * np.maximum(1.0, np.abs(ref))
+        return bool((np.abs(got - ref) <= bound).all())
+
+    text = open(SRC).read()
+    assert agrees(_oracle_copy(text, str(tmp_path), "control")), "GPU result disagrees with the true oracle"
+    missed = []
+    for name in PLANTED:
+        old, new = MUTATIONS[name]
+        assert text.count(old) == 1
+        if agrees(_oracle_copy(text.replace(old, new), str(tmp_path), name)):
+            missed.append(name)
+    assert not missed, f"the parity tolerance cannot tell these broken oracles from the GPU result: {missed}"
