@@ -114,7 +114,7 @@ __device__ __forceinline__ float dot4(const float w[4], float a, float b, float 
 // Vertical first: the intermediate is only as wide as the LR footprint.  Every
 // kernel of the library evaluates stage 1 in this order, so their up-sampled
 // values agree bit for bit.  MAXLR* must be >= ceil((extent-1)/s) + 4 for the
-// smallest scale (2).
+// smallest scale the kernel is launched with.
 // ---------------------------------------------------------------------------
 struct TileOrigin {
     int ly0, lx0;   // LR coordinate of lrT[0][0] (may be negative: reads are clamped)

@@ -62,7 +62,11 @@ typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 // how the coefficients are stored (template argument CT of the kernel)
 constexpr int CT_F16 = 0, CT_F32 = 1, CT_F8 = 2;
 
-template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int CT = CT_F16>
+// SMIN: smallest scale the instantiation may be launched with.  The LR footprint
+// of a tile shrinks with the scale, so an instantiation for scale 4 only needs half
+// the LDS for the footprint and the vertical-pass buffer, and can afford a taller
+// tile (fewer halo rows up-sampled per output row).
+template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int CT = CT_F16, int SMIN = 2>
 struct Cfg {
     static constexpr bool F32 = CT == CT_F32, F8 = CT == CT_F8;
     static constexpr int KK = K * K, R = (K - 1) / 2;
@@ -79,7 +83,7 @@ struct Cfg {
     static constexpr int P0 = PX * NG;
     // rows of one wavefront must land on disjoint banks: pitch == WC (mod 32)
     static constexpr int P = WR == 1 ? P0 : P0 + ((WC - P0 % 32) + 32) % 32;
-    static constexpr int MAXLRY = (UH - 1) / 2 + 5, MAXLRX = (UW - 1) / 2 + 5;
+    static constexpr int MAXLRY = (UH - 1) / SMIN + 5, MAXLRX = (UW - 1) / SMIN + 5;
     // fp16 coefficients: 16-atom MFMA steps and an optional 8-atom step;
     // fp32 coefficients: 2-atom steps of v_mfma_f32_32x32x2_f32, one load each
     static constexpr int N16 = F32 ? 0 : NP8 / 2, N8 = F32 ? 0 : NP8 % 2;
@@ -133,10 +137,10 @@ __device__ __forceinline__ int tap_of_row(int i, int mb) {
 
 struct TilePos { int n, ty, tx; };
 
-template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT>
+template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT, int SMIN>
 __global__ __launch_bounds__(64 * NW, WPE)
 void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y, const int ntiles) {
-    using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT>;
+    using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN>;
     constexpr bool F32 = F::F32, F8 = F::F8;
     using Raw = typename RawT<PX * F::CB>::type;
     constexpr int NT = F::NT, P = F::P, NG = F::NG, UH = F::UH, UW = F::UW;
@@ -634,9 +638,10 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 // ---------------------------------------------------------------------------
 // Host side: launch of one instantiation on a persistent grid.
 // ---------------------------------------------------------------------------
-template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT = CT_F16>
+template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT = CT_F16, int SMIN = 2>
 hipError_t launch_one(const AssembleArgs& a, hipStream_t st) {
-    using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT>;
+    using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN>;
+    if (a.s < SMIN) return hipErrorInvalidValue;        // its LDS footprint buffers would be too small
     const int tiles_x = (a.W + F::TW - 1) / F::TW, tiles_y = (a.H + F::TH - 1) / F::TH;
     const long long nt = (long long)tiles_x * tiles_y * a.N;
     if (nt > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -646,7 +651,7 @@ hipError_t launch_one(const AssembleArgs& a, hipStream_t st) {
         (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     const int cap = cus * (4 * WPE / NW > 0 ? 4 * WPE / NW : 1);
     const int blocks = nt < cap ? (int)nt : cap;
-    hipLaunchKernelGGL((k_assemble_mfma<K, C, NP8, PX, WR, NW, NU, WPE, CT>), dim3(blocks), dim3(F::NT), 0, st,
+    hipLaunchKernelGGL((k_assemble_mfma<K, C, NP8, PX, WR, NW, NU, WPE, CT, SMIN>), dim3(blocks), dim3(F::NT), 0, st,
                        a, tiles_x, tiles_y, (int)nt);
     return hipGetLastError();
 }
