@@ -66,6 +66,42 @@ def empirical_ceilings(sr, torch, wl, coeffs, outs, kernel_ms):
                     "the kernel's read + write mix with no arithmetic (same planes, same output size)"}
 
 
+def selection_leg(sr, torch, wl, inp, stride):
+    """Offline selection on the workload's own frame: the target is the dense result, so the
+    search answers "which 10 % of the atoms, rescaled, reproduce the full dictionary best"."""
+    shape = (wl.n, wl.c, wl.H, wl.W)
+    up, target = torch.empty(shape, device="cuda"), torch.empty(shape, device="cuda")
+    sr.sr_bicubic_upsample(inp["lr"], wl.scale, wl.c, up)
+    sr.sr_dict_assemble(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, target)
+    ws = torch.empty(sr.sr_atom_gram_workspace_bytes(wl.L), device="cuda", dtype=torch.uint8)
+    nm = torch.empty(wl.L * wl.L + wl.L + 2, device="cuda", dtype=torch.float64)
+    run = lambda: sr.sr_atom_gram(up, inp["coeff"], inp["dict"], target, wl.L, wl.k, wl.c, stride,
+                                  workspace=ws, normal=nm)
+    for _ in range(2):
+        run()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(5):
+        run()
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / 5
+    host = nm.cpu().numpy()
+    samples = float(host[-1])
+    lp = 4 * ((wl.L + 1 + 3) // 4)
+    flop = samples * (2.0 * wl.L * wl.k * wl.k + 2.0 * lp * (lp + 4) / 2)     # responses + upper-triangle blocks
+    t0 = time.perf_counter()
+    kept, gamma, lam = sr.sr_select_atoms(host, wl.L, alpha=0.1, delta_alpha=0.1)
+    t_host = time.perf_counter() - t0
+    return {"stride": stride, "samples": int(samples), "gram_ms": round(ms, 4),
+            "roofline": {"bound": "alu", "achieved": round(flop / ms / 1e9, 2), "peak": 78.6, "unit": "TFLOP/s",
+                         "frac": round(flop / ms / 1e9 / 78.6, 4),
+                         "note": "fp32 vector ALU without packed math: 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz"},
+            "host_search_s": round(t_host, 3), "kept": [int(v) for v in kept],
+            "gamma": [round(float(g), 4) for g in gamma], "lambda": lam}
+
+
 def sr_synth_stored(t):
     import sr_synth
     return sr_synth.stored_numpy(t)
@@ -132,6 +168,9 @@ def main():
     ap.add_argument("--kept-sweep", action="store_true",
                     help="also time kept-atom lists of 72, 58, 43, 29, 14 and 8 atoms (the paper's "
                          "compression-ratio ablation, Fig. 7) and add them to the JSON line")
+    ap.add_argument("--selection", type=int, default=0, metavar="STRIDE",
+                    help="also time the offline dictionary selection (section III-A, Alg. 1) on this frame: "
+                         "normal equations on the GPU over every STRIDE-th row and column, then the host search")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size kernel that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters when profiling)")
@@ -257,6 +296,8 @@ def main():
         for row in sweep:
             row["speedup_vs_all_atoms"] = round(base / row["kernel_ms_avg"], 2)
         result["kept_sweep"] = sweep
+    if args.selection > 0 and wl.coeff_dtype in ("f16", "f32") and inp["lr"].dtype == torch.float32 and wl.L <= 128:
+        result["selection"] = selection_leg(sr, torch, wl, inp, args.selection)
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(wl, inp["lr"], coeffs[0], inp["dict"], args.cpu_budget)
     print(json.dumps(result))

@@ -19,7 +19,8 @@ SR_MAX_ATOMS = 256
 
 EXPORTS = ("sr_dict_assemble", "sr_dict_assemble_selective", "sr_dict_assemble_ex",
            "sr_bicubic_upsample", "sr_dict_assemble_plan", "sr_strerror", "sr_version",
-           "sr_probe_read", "sr_probe_mix")
+           "sr_probe_read", "sr_probe_mix",
+           "sr_atom_gram_workspace_bytes", "sr_atom_gram", "sr_select_atoms")
 
 
 class sr_tensor(ctypes.Structure):
@@ -61,11 +62,17 @@ def load():
     lib.sr_strerror.argtypes = [i]
     lib.sr_probe_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     lib.sr_probe_mix.argtypes = [vp, i, ctypes.c_size_t, vp, i, vp]
+    dp = ctypes.POINTER(ctypes.c_double)
+    lib.sr_atom_gram_workspace_bytes.argtypes = [i]
+    lib.sr_atom_gram.argtypes = [T, T, T, T, i, i, i, i, vp, ctypes.c_size_t, vp, vp]
+    lib.sr_select_atoms.argtypes = [dp, i, ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_double,
+                                    ip, ip, fp, dp]
     lib.sr_strerror.restype = ctypes.c_char_p
     lib.sr_version.argtypes = []
     for name in EXPORTS:
-        if name not in ("sr_strerror",):
+        if name not in ("sr_strerror", "sr_atom_gram_workspace_bytes"):
             getattr(lib, name).restype = i
+    lib.sr_atom_gram_workspace_bytes.restype = ctypes.c_size_t
     _lib = lib
     return lib
 
@@ -185,3 +192,41 @@ def sr_probe_mix(coeff, planes, pixels, out, channels, stream=None):
     assert out.numel() * out.element_size() >= channels * pixels * 4
     _check(load().sr_probe_mix(ctypes.c_void_p(coeff.data_ptr()), planes, pixels,
                                ctypes.c_void_p(out.data_ptr()), channels, _stream(stream)))
+
+
+def sr_atom_gram_workspace_bytes(L: int) -> int:
+    return int(load().sr_atom_gram_workspace_bytes(int(L)))
+
+
+def sr_atom_gram(up, coeff, dict, target, L, k, channels, stride=1, workspace=None, normal=None, stream=None):
+    """Normal equations of the selection regression (include/sr_select.h).  Returns the
+    device tensor of L*L + L + 2 doubles (G, b, hh, M); scratch and result are torch
+    tensors made here unless the caller passes them."""
+    import torch
+    need = sr_atom_gram_workspace_bytes(L)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), device=up.device, dtype=torch.uint8)
+    if normal is None:
+        normal = torch.empty(L * L + L + 2, device=up.device, dtype=torch.float64)
+    _check(load().sr_atom_gram(describe(up), describe(coeff), describe(_dict4(dict)), describe(target),
+                               L, k, channels, stride, ctypes.c_void_p(workspace.data_ptr()),
+                               workspace.numel() * workspace.element_size(),
+                               ctypes.c_void_p(normal.data_ptr()), _stream(stream)))
+    return normal
+
+
+def sr_select_atoms(normal, L, alpha, delta_alpha=0.1, lambda0=1e-6, eps=0.0):
+    """Alg. 1 on host normal equations (a numpy float64 array of L*L + L + 2 values).
+    Returns (kept indices int32 ascending, gamma float32, lambda reached)."""
+    import numpy as np
+    nm = np.ascontiguousarray(normal, dtype=np.float64)
+    if nm.size != L * L + L + 2:
+        raise ValueError("normal must hold L*L + L + 2 values")
+    kept = np.zeros(L, dtype=np.int32)
+    gamma = np.zeros(L, dtype=np.float32)
+    n = ctypes.c_int(0)
+    lam = ctypes.c_double(0.0)
+    _check(load().sr_select_atoms(nm.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), L, alpha, delta_alpha,
+                                  lambda0, eps, kept.ctypes.data_as(ctypes.POINTER(ctypes.c_int)), ctypes.byref(n),
+                                  gamma.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), ctypes.byref(lam)))
+    return kept[:n.value].copy(), gamma[:n.value].copy(), lam.value

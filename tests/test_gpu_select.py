@@ -1,0 +1,101 @@
+"""GPU parity of the selection's normal equations (sr_atom_gram) against the numpy
+oracle, and the whole chain on a planted problem: up-sample, normal equations, Alg. 1,
+selective assembly with the kept list and gamma it returned."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+import paper_2303_08999_amd as sr
+import sr_synth
+from oracle import select_oracle as so
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+CASES = [
+    # (N, C, h, w, scale, L, k, coeff dtype, stride)
+    (1, 3, 9, 11, 2, 5, 3, "f32", 1),
+    (2, 3, 12, 17, 4, 72, 5, "f16", 1),      # 3264 lattice pixels: 51 runs of 64 samples
+    (1, 1, 16, 16, 3, 128, 7, "f16", 2),     # the largest atom count, three blocks per thread
+    (3, 2, 10, 13, 2, 17, 7, "f32", 3),      # ragged lattice, L + 1 not a multiple of 4
+    (1, 3, 40, 48, 4, 72, 5, "f16", 5),
+    (1, 16, 6, 7, 2, 3, 3, "f32", 1),        # 16 channels
+]
+
+
+def _inputs(case):
+    N, C, h, w, s, L, k, cd, stride = case
+    wl = sr_synth.Workload("gram", 30, N, C, h, w, s, L, k, cd, "f32", 0.0, 1.5)
+    inp = sr_synth.make_inputs(wl, DEV)
+    up = torch.empty((N, C, wl.H, wl.W), device=DEV)
+    sr.sr_bicubic_upsample(inp["lr"], s, C, up)
+    g = torch.Generator(device=DEV).manual_seed(77 + L)
+    target = torch.rand((N, C, wl.H, wl.W), device=DEV, generator=g)
+    return wl, inp, up, target
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "N%dC%dh%dw%ds%dL%dk%d%sst%d" % c)
+def test_normal_equations_match_the_oracle(oracle, case):
+    wl, inp, up, target = _inputs(case)
+    stride = case[-1]
+    normal = sr.sr_atom_gram(up, inp["coeff"], inp["dict"], target, wl.L, wl.k, wl.c, stride)
+    again = sr.sr_atom_gram(up, inp["coeff"], inp["dict"], target, wl.L, wl.k, wl.c, stride)
+    torch.cuda.synchronize()
+    assert torch.equal(normal, again), "the sums must not depend on the run"
+    got = normal.cpu().numpy()
+    L = wl.L
+    G, b, hh, M = got[:L * L].reshape(L, L), got[L * L:L * L + L], got[L * L + L], got[L * L + L + 1]
+    U = oracle.bicubic(inp["lr"].cpu().numpy(), wl.scale)
+    G0, b0, hh0, M0 = so.normal_equations(U, sr_synth.stored_numpy(inp["coeff"]), inp["dict"].cpu().numpy(),
+                                          target.cpu().numpy(), stride)
+    assert M == M0
+    assert np.array_equal(G, G.T)
+    # fp32 responses (relative 1e-6 each), fp32 sums over 64 samples, double beyond
+    scale = np.sqrt(np.outer(np.diag(G0), np.diag(G0)))
+    assert np.abs(G - G0).max() <= 2e-5 * scale.max() and (np.abs(G - G0) <= 2e-5 * scale + 1e-12).all()
+    assert (np.abs(b - b0) <= 2e-5 * np.sqrt(np.diag(G0) * hh0) + 1e-12).all()
+    assert abs(hh - hh0) <= 1e-6 * hh0
+
+
+def test_empty_batch_and_undersized_scratch():
+    wl, inp, up, target = _inputs(CASES[0])
+    z = torch.empty((0, 3, wl.H, wl.W), device=DEV)
+    zc = torch.empty((0, wl.L, wl.H, wl.W), device=DEV)
+    normal = sr.sr_atom_gram(z, zc, inp["dict"], z.clone(), wl.L, wl.k, 3)
+    torch.cuda.synchronize()
+    assert not normal.cpu().numpy().any()
+    small = torch.empty(1024, device=DEV, dtype=torch.uint8)
+    with pytest.raises(sr.SrError) as err:
+        sr.sr_atom_gram(up, inp["coeff"], inp["dict"], target, wl.L, wl.k, 3, workspace=small)
+    assert err.value.status == -2
+
+
+def test_whole_chain_recovers_a_planted_selection(oracle):
+    """The target is what the path itself produces from 6 of 40 atoms with known scales;
+    the selection must find exactly them, and assembling with what it returns must
+    reproduce the target."""
+    wl = sr_synth.Workload("plant", 31, 2, 3, 20, 26, 4, 40, 5, "f16", "f32", 0.0, 1.0)
+    inp = sr_synth.make_inputs(wl, DEV)
+    planted = np.array([4, 9, 17, 22, 30, 39], dtype=np.int32)
+    scales = np.array([1.5, 0.5, -1.0, 2.0, 0.75, 1.25], dtype=np.float32)
+    target = torch.empty((wl.n, wl.c, wl.H, wl.W), device=DEV)
+    sr.sr_dict_assemble_selective(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, target,
+                                  kept=planted, gamma=scales)
+    up = torch.empty_like(target)
+    sr.sr_bicubic_upsample(inp["lr"], wl.scale, wl.c, up)
+    normal = sr.sr_atom_gram(up, inp["coeff"], inp["dict"], target, wl.L, wl.k, wl.c, stride=2)
+    torch.cuda.synchronize()
+    kept, gamma, lam = sr.sr_select_atoms(normal.cpu().numpy(), wl.L, alpha=6 / 40, delta_alpha=0.3)
+    assert np.array_equal(kept, planted)
+    assert np.allclose(gamma, scales, atol=2e-3)
+    out = torch.empty_like(target)
+    sr.sr_dict_assemble_selective(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, out,
+                                  kept=kept, gamma=gamma)
+    torch.cuda.synchronize()
+    assert float((out - target).abs().max()) <= 5e-3
+    # the oracle's selection from the oracle's normal equations agrees
+    U = oracle.bicubic(inp["lr"].cpu().numpy(), wl.scale)
+    G0, b0, hh0, M0 = so.normal_equations(U, inp["coeff"].cpu().numpy(), inp["dict"].cpu().numpy(),
+                                          target.cpu().numpy(), 2)
+    k0, g0, _ = so.select_atoms(G0, b0, hh0, M0, 6 / 40, 0.3)
+    assert np.array_equal(k0, kept) and np.allclose(g0, gamma, atol=2e-3)

@@ -1,0 +1,83 @@
+"""Host side of the dictionary selection (sr_select_atoms, Alg. 1) against the numpy
+oracle on the same normal equations.  No GPU involved."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import paper_2303_08999_amd as sr
+from oracle import select_oracle as so
+
+
+def _problem(seed, M=500, L=24, noise=0.05):
+    rng = np.random.default_rng(seed)
+    X = rng.normal(size=(M, L)) * rng.uniform(0.3, 3.0, size=L)
+    X[:, 1] = 0.7 * X[:, 0] + 0.3 * X[:, 1]                       # correlated atoms
+    w = rng.normal(size=L) * (rng.uniform(size=L) < 0.4)
+    y = X @ w + noise * rng.normal(size=M)
+    G, b, hh = X.T @ X, X.T @ y, float(y @ y)
+    return G, b, hh, M, np.concatenate([G.reshape(-1), b, [hh, float(M)]])
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+@pytest.mark.parametrize("alpha,step", [(0.75, 0.25), (0.5, 0.1), (0.25, 0.25), (0.1, 0.3), (1 / 24, 1.0)])
+def test_same_selection_as_the_oracle(seed, alpha, step):
+    G, b, hh, M, normal = _problem(seed)
+    k0, g0, l0 = so.select_atoms(G, b, hh, M, alpha, step, lam0=1e-5)
+    k1, g1, l1 = sr.sr_select_atoms(normal, 24, alpha, step, lambda0=1e-5)
+    assert np.array_equal(k0, k1)
+    assert len(k1) <= alpha * 24 + 1e-9
+    assert np.allclose(g0, g1, rtol=1e-6, atol=1e-7)
+    assert np.isclose(l0, l1, rtol=1e-12)
+
+
+def test_planted_subset_is_recovered():
+    rng = np.random.default_rng(9)
+    X = rng.normal(size=(300, 16))
+    planted, scales = [3, 8, 12, 15], np.array([2.0, -1.0, 0.5, 1.25])
+    y = X[:, planted] @ scales
+    normal = np.concatenate([(X.T @ X).reshape(-1), X.T @ y, [float(y @ y), 300.0]])
+    kept, gamma, _ = sr.sr_select_atoms(normal, 16, 4 / 16, delta_alpha=0.25)
+    assert kept.tolist() == planted and np.allclose(gamma, scales, atol=1e-5)
+
+
+def test_alpha_one_keeps_everything_untouched():
+    G, b, hh, M, normal = _problem(4)
+    kept, gamma, lam = sr.sr_select_atoms(normal, 24, 1.0)
+    assert kept.tolist() == list(range(24)) and np.all(gamma == 1.0) and lam == 1e-6
+
+
+def test_argument_checks():
+    lib = sr.load()
+    G, b, hh, M, normal = _problem(5)
+    dp = normal.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+    kept = (ctypes.c_int * 24)(); gam = (ctypes.c_float * 24)(); n = ctypes.c_int()
+    ok = lambda *a: lib.sr_select_atoms(*a)
+    assert ok(None, 24, 0.5, 0.1, 1e-6, 0.0, kept, ctypes.byref(n), gam, None) == -1
+    assert ok(dp, 24, 0.5, 0.1, 1e-6, 0.0, None, ctypes.byref(n), gam, None) == -1
+    assert ok(dp, 0, 0.5, 0.1, 1e-6, 0.0, kept, ctypes.byref(n), gam, None) == -3
+    assert ok(dp, 129, 0.5, 0.1, 1e-6, 0.0, kept, ctypes.byref(n), gam, None) == -3
+    for bad in ((0.0, 0.1, 1e-6, 0.0), (1.5, 0.1, 1e-6, 0.0), (0.5, 0.0, 1e-6, 0.0), (0.5, 0.1, 0.0, 0.0),
+                (0.5, 0.1, 1e-6, -1.0), (float("nan"), 0.1, 1e-6, 0.0)):
+        assert ok(dp, 24, *bad, kept, ctypes.byref(n), gam, None) == -3
+    assert ok(dp, 24, 0.5, 0.1, 1e-6, 0.0, kept, ctypes.byref(n), gam, None) == 0 and 1 <= n.value <= 12
+    # gram entry point: everything is checked before anything is launched
+    assert lib.sr_atom_gram_workspace_bytes(72) == 512 * 190 * 128
+    assert lib.sr_atom_gram_workspace_bytes(0) == 0 and lib.sr_atom_gram_workspace_bytes(129) == 0
+    T = sr.sr_tensor
+    up = T(0x10000000, sr.SR_F32, 1, 3, 32, 64); tg = T(0x20000000, sr.SR_F32, 1, 3, 32, 64)
+    cf = T(0x30000000, sr.SR_F16, 1, 72, 32, 64); d = T(0x40000000, sr.SR_F32, 1, 72, 5, 5)
+    ws, nm = ctypes.c_void_p(0x50000000), ctypes.c_void_p(0x60000000)
+    need = lib.sr_atom_gram_workspace_bytes(72)
+    g = lambda *a: lib.sr_atom_gram(*a)
+    assert g(None, cf, d, tg, 72, 5, 3, 1, ws, need, nm, None) == -1
+    assert g(up, cf, d, tg, 72, 5, 3, 1, ws, need, None, None) == -1
+    assert g(up, cf, d, tg, 72, 5, 3, 1, None, need, nm, None) == -2           # no scratch
+    assert g(up, cf, d, tg, 72, 5, 3, 1, ws, need - 1, nm, None) == -2         # scratch too small
+    assert g(up, cf, d, tg, 72, 4, 3, 1, ws, need, nm, None) == -3
+    assert g(up, cf, d, tg, 72, 5, 3, 0, ws, need, nm, None) == -3
+    assert g(up, cf, d, tg, 71, 5, 3, 1, ws, need, nm, None) == -2             # L disagrees with coeff
+    assert g(up, cf, d, T(0x20000000, sr.SR_F32, 1, 3, 32, 60), 72, 5, 3, 1, ws, need, nm, None) == -2
+    assert g(up, T(0x30000000, sr.SR_F8E4M3, 1, 72, 32, 64), d, tg, 72, 5, 3, 1, ws, need, nm, None) == -3
+    assert g(T(0x10000000, sr.SR_F16, 1, 3, 32, 64), cf, d, tg, 72, 5, 3, 1, ws, need, nm, None) == -3
+    assert g(up, cf, d, tg, 72, 5, 3, 1, ctypes.c_void_p(0x50000008), need, nm, None) == -7
