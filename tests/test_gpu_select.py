@@ -99,3 +99,30 @@ def test_whole_chain_recovers_a_planted_selection(oracle):
                                           target.cpu().numpy(), 2)
     k0, g0, _ = so.select_atoms(G0, b0, hh0, M0, 6 / 40, 0.3)
     assert np.array_equal(k0, kept) and np.allclose(g0, gamma, atol=2e-3)
+
+
+def test_selection_finds_the_dominant_atoms_of_the_selective_workload():
+    """The selective workload gives 8 seeded atoms most of the coefficient mass.  Asked for
+    8 of 72 atoms to reproduce the DENSE result, Alg. 1 must pick exactly those 8 (the
+    list the workload itself derives from the mean coefficients), and assembling with its
+    kept list and gamma must come closer to the dense result than the unscaled kept list."""
+    wl = sr_synth.scaled(sr_synth.WORKLOADS["4k_selective"], h=90, w=120)
+    inp = sr_synth.make_inputs(wl, DEV)
+    shape = (wl.n, wl.c, wl.H, wl.W)
+    dense, up = torch.empty(shape, device=DEV), torch.empty(shape, device=DEV)
+    sr.sr_dict_assemble(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, dense)
+    sr.sr_bicubic_upsample(inp["lr"], wl.scale, wl.c, up)
+    normal = sr.sr_atom_gram(up, inp["coeff"], inp["dict"], dense, wl.L, wl.k, wl.c, stride=3)
+    torch.cuda.synchronize()
+    kept, gamma, _ = sr.sr_select_atoms(normal.cpu().numpy(), wl.L, alpha=8 / 72, delta_alpha=0.2)
+    assert np.array_equal(kept, inp["kept"])
+    assert np.array_equal(np.sort(sr_synth.dominant_atoms(wl)), kept)
+    assert np.all(gamma > 1.0) and np.all(gamma < 1.5)          # they make up for the dropped ~13 % of the mass
+    plain, scaled = torch.empty(shape, device=DEV), torch.empty(shape, device=DEV)
+    sr.sr_dict_assemble_selective(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, plain, kept=kept)
+    sr.sr_dict_assemble_selective(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, scaled,
+                                  kept=kept, gamma=gamma)
+    torch.cuda.synchronize()
+    err_plain = float(((plain - dense) ** 2).mean())
+    err_scaled = float(((scaled - dense) ** 2).mean())
+    assert err_scaled < 0.25 * err_plain
