@@ -77,3 +77,46 @@ def test_every_planted_mistake_is_caught(tmp_path):
     # exit status 1 = some test FAILED; anything else (collection error, crash) is not a catch
     odd = [(name, rc) for name, rc in results if rc != 1]
     assert not odd, f"these runs did not end in an ordinary test failure: {odd}"
+
+
+SELECT_SRC = os.path.join(ROOT, "oracle", "select_oracle.py")
+SELECT_MUTATIONS = {
+    "threshold_not_halved": ("thr = 0.5 * lam * M", "thr = lam * M"),
+    "soft_threshold_sign": ("(rho + thr if rho < -thr else 0.0)", "(rho - thr if rho < -thr else 0.0)"),
+    "own_term_not_excluded": ("rho = b[j] - (G[j] @ beta - G[j, j] * beta[j])", "rho = b[j] - G[j] @ beta"),
+    "responses_without_coefficient": ("R *= np.moveaxis(phi, 1, -1)[:, None]", "R *= 1.0"),
+    "atom_transposed": ("R += tap[..., None] * D[:, dy, dx]", "R += tap[..., None] * D[:, dx, dy]"),
+    "zero_padding": ('mode="edge"', 'mode="constant"'),
+    "lattice_offset": ("ys, xs = np.arange(0, H, stride), np.arange(0, W, stride)",
+                       "ys, xs = np.arange(stride - 1, H, stride), np.arange(stride - 1, W, stride)"),
+    "target_term_abs": ("return R.T @ R, R.T @ h, float(h @ h), R.shape[0]", "return R.T @ R, R.T @ np.abs(h), float(h @ h), R.shape[0]"),
+    "gamma_not_accumulated": ("        gamma_tot[S] *= gam\n", "        pass\n"),
+    "right_side_not_rescaled": ("        b[S] *= gam\n", "        pass\n"),
+    "keeps_fewer_than_allowed": ("        while cnt > want:\n", "        while cnt >= want:\n"),
+    "regression_on_all_atoms": ("Gs, bs = np.asarray(G, dtype=np.float64)[np.ix_(S, S)], np.asarray(b, dtype=np.float64)[S]",
+                                "Gs, bs = np.asarray(G, dtype=np.float64)[np.ix_(S, S)], np.asarray(b, dtype=np.float64)[S] * 0.5"),
+}
+
+
+def test_every_planted_mistake_in_the_selection_oracle_is_caught(tmp_path):
+    text = open(SELECT_SRC).read()
+    for name, (old, new) in SELECT_MUTATIONS.items():
+        assert text.count(old) == 1, f"{name}: the source line to break was not found exactly once"
+
+    def run(tag, body):
+        src = os.path.join(str(tmp_path), f"select_{tag}.py")
+        with open(src, "w") as f:
+            f.write(body)
+        compile(body, src, "exec")                       # a copy that is not valid Python proves nothing
+        env = dict(os.environ, SR_SELECT_ORACLE_SRC=src, OMP_NUM_THREADS="2")
+        res = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
+                              "tests/test_oracle_select.py"], cwd=ROOT, env=env, capture_output=True, text=True)
+        return tag, res.returncode
+
+    assert run("control", text)[1] == 0, "the unmodified copy must pass its pins"
+    with ThreadPoolExecutor(max_workers=4) as pool:
+        results = list(pool.map(lambda kv: run(kv[0], text.replace(*kv[1])), SELECT_MUTATIONS.items()))
+    survivors = [name for name, rc in results if rc == 0]
+    assert not survivors, f"no pin noticed these planted mistakes: {survivors}"
+    odd = [(name, rc) for name, rc in results if rc != 1]
+    assert not odd, f"these runs did not end in an ordinary test failure: {odd}"

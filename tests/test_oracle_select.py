@@ -2,10 +2,26 @@
 the pinned assembly oracle and brute force, the LASSO solver against closed forms and a
 library solver, the regression scales against a library least squares, and Alg. 1 on
 problems whose answer is known."""
+import importlib.util
+import os
+
 import numpy as np
 import pytest
 
-from oracle import select_oracle as so
+
+def _selection_oracle():
+    # the mutation test (test_oracle_mutations.py) points this at a deliberately broken copy
+    path = os.environ.get("SR_SELECT_ORACLE_SRC")
+    if not path:
+        from oracle import select_oracle
+        return select_oracle
+    spec = importlib.util.spec_from_file_location("select_oracle_copy", path)
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    return mod
+
+
+so = _selection_oracle()
 
 
 def _case(seed, n=1, c=2, H=9, W=11, L=6, k=3):
@@ -117,6 +133,10 @@ def test_selection_recovers_a_planted_subset(oracle):
     # one round straight to the target gives the same answer
     kept1, gamma1, _ = so.select_atoms(G, b, hh, M, alpha=3 / 12, delta_alpha=1.0)
     assert np.array_equal(kept1, planted) and np.allclose(gamma1, scales, atol=1e-8)
+    # with the bisection switched off (eps = 1) the doubling alone must stop at the first
+    # lambda that leaves at most alpha*L atoms: here the very first, which leaves these 3
+    kept2, gamma2, lam2 = so.select_atoms(G, b, hh, M, alpha=3 / 12, delta_alpha=1.0, lam0=1e-6, eps=1.0)
+    assert np.array_equal(kept2, planted) and np.allclose(gamma2, scales, atol=1e-8) and lam2 == 1e-6
 
 
 def test_selection_keeps_at_most_alpha_L_and_never_raises_the_error_of_dropping_at_random():

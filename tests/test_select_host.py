@@ -39,6 +39,8 @@ def test_planted_subset_is_recovered():
     normal = np.concatenate([(X.T @ X).reshape(-1), X.T @ y, [float(y @ y), 300.0]])
     kept, gamma, _ = sr.sr_select_atoms(normal, 16, 4 / 16, delta_alpha=0.25)
     assert kept.tolist() == planted and np.allclose(gamma, scales, atol=1e-5)
+    kept, gamma, lam = sr.sr_select_atoms(normal, 16, 4 / 16, delta_alpha=1.0, lambda0=1e-6, eps=1.0)
+    assert kept.tolist() == planted and np.allclose(gamma, scales, atol=1e-5) and lam == 1e-6
 
 
 def test_alpha_one_keeps_everything_untouched():
