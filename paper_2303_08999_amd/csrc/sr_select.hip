@@ -86,6 +86,14 @@ __global__ __launch_bounds__(NT) void k_atom_gram(const GramArgs a) {
             Y = iy * a.stride;
             X = (rem - iy * a.nx) * a.stride;
         }
+        // the coefficients of this thread's atoms at its sample: the same for every channel
+        float phi[LPMAX / 4];
+#pragma unroll
+        for (int i = 0; i < LPMAX / 4; ++i) {
+            const int l = g + 4 * i;
+            phi[i] = (ok && l < a.L)
+                         ? ldf((const TC*)a.coeff, ((size_t)n * a.L + l) * plane + (size_t)Y * a.W + X) : 0.0f;
+        }
         for (int c = 0; c < a.C; ++c) {
             // (1) responses of every atom at this thread's sample, plus the target column
             float patch[KK];
@@ -97,19 +105,23 @@ __global__ __launch_bounds__(NT) void k_atom_gram(const GramArgs a) {
                     const int yy = clampi(Y + dy - R, 0, a.H - 1), xx = clampi(X + dx - R, 0, a.W - 1);
                     patch[dy * K + dx] = ok ? uplane[(size_t)yy * a.W + xx] : 0.0f;
                 }
-            for (int l = g; l < Lp; l += 4) {           // l is the same for the whole wavefront
-                float r = 0.0f;
-                if (l < a.L) {
-                    const float* d = a.dict + (size_t)l * KK;
-                    float dot = 0.0f;
+            const float hval = ok ? a.target[((size_t)n * a.C + c) * plane + (size_t)Y * a.W + X] : 0.0f;
 #pragma unroll
-                    for (int j = 0; j < KK; ++j) dot = fmaf(d[j], patch[j], dot);
-                    const float phi = ok ? ldf((const TC*)a.coeff, ((size_t)n * a.L + l) * plane + (size_t)Y * a.W + X) : 0.0f;
-                    r = phi * dot;
-                } else if (l == a.L) {
-                    r = ok ? a.target[((size_t)n * a.C + c) * plane + (size_t)Y * a.W + X] : 0.0f;
+            for (int i = 0; i < LPMAX / 4; ++i) {
+                const int l = g + 4 * i;                // the same for the whole wavefront
+                if (l < Lp) {
+                    float r = 0.0f;
+                    if (l < a.L) {
+                        const float* d = a.dict + (size_t)l * KK;
+                        float dot = 0.0f;
+#pragma unroll
+                        for (int j = 0; j < KK; ++j) dot = fmaf(d[j], patch[j], dot);
+                        r = phi[i] * dot;
+                    } else if (l == a.L) {
+                        r = hval;
+                    }
+                    tile[si * Lp + l] = r;
                 }
-                tile[si * Lp + l] = r;
             }
             __syncthreads();
             // (2) this thread's blocks of tile^T tile over the 64 samples
