@@ -43,7 +43,11 @@ def atom_responses(U, coeff, dictionary, stride=1):
     [n][L][H][W], dictionary [L][k][k]; patch taps outside the image read the
     nearest pixel (as everywhere in this build)."""
     U = np.asarray(U, dtype=np.float64)
-    coeff = np.asarray(coeff).astype(np.float64)
+    coeff = np.asarray(coeff)
+    if coeff.dtype == np.uint8:                      # stored 8-bit E4M3 floats, widened by the assembly oracle's decoder
+        from . import e4m3_to_double
+        coeff = np.array([e4m3_to_double(b) for b in range(256)])[coeff]
+    coeff = coeff.astype(np.float64)
     D = np.asarray(dictionary, dtype=np.float64)
     n, c, H, W = U.shape
     L, k, _ = D.shape

@@ -41,6 +41,8 @@ int upper_blocks(int Lp) { const int n = Lp / 4; return n * (n + 1) / 2; }
 
 __device__ __forceinline__ float ldf(const float* p, size_t i) { return p[i]; }
 __device__ __forceinline__ float ldf(const __half* p, size_t i) { return __half2float(p[i]); }
+struct e4m3 { unsigned char bits; };        // 8-bit E4M3 storage, widened exactly by the conversion instruction
+__device__ __forceinline__ float ldf(const e4m3* p, size_t i) { return __builtin_amdgcn_cvt_f32_fp8((int)p[i].bits, 0); }
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
 // q-th 4x4 block of the upper triangle, row-major: (bi, bj) with bi <= bj
@@ -262,7 +264,7 @@ int sr_atom_gram(const sr_tensor* up, const sr_tensor* coeff, const sr_tensor* d
                  double* normal, void* stream) {
     if (!up || !coeff || !dict || !target || !normal) return SR_ERR_NULL;
     if (up->dtype != SR_F32 || target->dtype != SR_F32 || dict->dtype != SR_F32 ||
-        (coeff->dtype != SR_F32 && coeff->dtype != SR_F16)) return SR_ERR_UNSUPPORTED;
+        (coeff->dtype != SR_F32 && coeff->dtype != SR_F16 && coeff->dtype != SR_F8E4M3)) return SR_ERR_UNSUPPORTED;
     if ((k != 3 && k != 5 && k != 7) || L < 1 || L > SR_SELECT_MAX_ATOMS || channels < 1 ||
         channels > SR_MAX_CHANNELS || stride < 1) return SR_ERR_UNSUPPORTED;
     if (up->n < 0 || up->c < 0 || up->h < 0 || up->w < 0) return SR_ERR_SHAPE;
@@ -277,7 +279,7 @@ int sr_atom_gram(const sr_tensor* up, const sr_tensor* coeff, const sr_tensor* d
     if (!empty) {
         if (!up->data || !coeff->data || !dict->data || !target->data) return SR_ERR_NULL;
         if ((uintptr_t)up->data % 4 || (uintptr_t)target->data % 4 || (uintptr_t)dict->data % 4 ||
-            (uintptr_t)coeff->data % (coeff->dtype == SR_F16 ? 2 : 4)) return SR_ERR_ALIGN;
+            (uintptr_t)coeff->data % (coeff->dtype == SR_F16 ? 2 : (coeff->dtype == SR_F32 ? 4 : 1))) return SR_ERR_ALIGN;
     }
     GramArgs a;
     a.up = (const float*)up->data; a.coeff = coeff->data; a.dict = (const float*)dict->data;
@@ -288,15 +290,18 @@ int sr_atom_gram(const sr_tensor* up, const sr_tensor* coeff, const sr_tensor* d
     a.Lp = padded_columns(L);
     a.nblk = upper_blocks(a.Lp);
     const hipStream_t st = (hipStream_t)stream;
-    const bool f16 = coeff->dtype == SR_F16;
+#define SR_GRAM_LAUNCH(KS)                                                                                  \
+    do {                                                                                                    \
+        if (coeff->dtype == SR_F16) hipLaunchKernelGGL((k_atom_gram<KS, __half>), dim3(GRID), dim3(NT), 0, st, a);    \
+        else if (coeff->dtype == SR_F32) hipLaunchKernelGGL((k_atom_gram<KS, float>), dim3(GRID), dim3(NT), 0, st, a); \
+        else hipLaunchKernelGGL((k_atom_gram<KS, e4m3>), dim3(GRID), dim3(NT), 0, st, a);                             \
+    } while (0)
     switch (k) {
-    case 3: if (f16) hipLaunchKernelGGL((k_atom_gram<3, __half>), dim3(GRID), dim3(NT), 0, st, a);
-            else     hipLaunchKernelGGL((k_atom_gram<3, float>), dim3(GRID), dim3(NT), 0, st, a); break;
-    case 5: if (f16) hipLaunchKernelGGL((k_atom_gram<5, __half>), dim3(GRID), dim3(NT), 0, st, a);
-            else     hipLaunchKernelGGL((k_atom_gram<5, float>), dim3(GRID), dim3(NT), 0, st, a); break;
-    default: if (f16) hipLaunchKernelGGL((k_atom_gram<7, __half>), dim3(GRID), dim3(NT), 0, st, a);
-             else     hipLaunchKernelGGL((k_atom_gram<7, float>), dim3(GRID), dim3(NT), 0, st, a); break;
+    case 3:  SR_GRAM_LAUNCH(3); break;
+    case 5:  SR_GRAM_LAUNCH(5); break;
+    default: SR_GRAM_LAUNCH(7); break;
     }
+#undef SR_GRAM_LAUNCH
     if (hipGetLastError() != hipSuccess) return SR_ERR_LAUNCH;
     const double M = (double)a.N * a.ny * a.nx * a.C;
     const int items = a.nblk * 16;

@@ -20,6 +20,7 @@ CASES = [
     (3, 2, 10, 13, 2, 17, 7, "f32", 3),      # ragged lattice, L + 1 not a multiple of 4
     (1, 3, 40, 48, 4, 72, 5, "f16", 5),
     (1, 16, 6, 7, 2, 3, 3, "f32", 1),        # 16 channels
+    (2, 3, 11, 14, 4, 40, 5, "f8", 2),       # coefficients stored as 8-bit E4M3
 ]
 
 

@@ -80,6 +80,5 @@ def test_argument_checks():
     assert g(up, cf, d, tg, 72, 5, 3, 0, ws, need, nm, None) == -3
     assert g(up, cf, d, tg, 71, 5, 3, 1, ws, need, nm, None) == -2             # L disagrees with coeff
     assert g(up, cf, d, T(0x20000000, sr.SR_F32, 1, 3, 32, 60), 72, 5, 3, 1, ws, need, nm, None) == -2
-    assert g(up, T(0x30000000, sr.SR_F8E4M3, 1, 72, 32, 64), d, tg, 72, 5, 3, 1, ws, need, nm, None) == -3
     assert g(T(0x10000000, sr.SR_F16, 1, 3, 32, 64), cf, d, tg, 72, 5, 3, 1, ws, need, nm, None) == -3
     assert g(up, cf, d, tg, 72, 5, 3, 1, ctypes.c_void_p(0x50000008), need, nm, None) == -7
