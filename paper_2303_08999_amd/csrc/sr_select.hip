@@ -4,11 +4,15 @@
 // GPU part.  A workgroup takes runs of 64 samples (lattice pixels).  For one run and
 // one channel it first forms the responses r_{p,l} = Phi_{p,l} (D_l . B_p) of all
 // atoms (one thread per sample and quarter of the atoms; the dictionary row is
-// wave-uniform, so it comes through scalar loads) into an LDS tile [64][Lp], with
-// the ground-truth pixel as one more column, then every thread accumulates its
-// 4 x 4 blocks of the upper triangle of tile^T tile.  Sums are fp32 within a run and
-// double across runs; each workgroup leaves its partial sums in the caller's
-// scratch and a second kernel adds them in a fixed order.
+// wave-uniform, so it comes through scalar loads) into an LDS tile [column][sample],
+// with the ground-truth pixel as one more column.  tile^T tile is a dense
+// contraction over the samples and runs on the matrix cores: the upper triangle is
+// cut into 16 x 16 blocks, dealt to the four wavefronts, and each block takes 16
+// v_mfma_f32_16x16x4_f32 steps per run (a lane reads four consecutive samples of its
+// column with one 16-byte LDS load and spends them on four steps; which sample goes
+// to which step does not matter to the sum as long as both operands agree).  Sums
+// are fp32 within a run and double across runs; each workgroup leaves its partial
+// sums in the caller's scratch and a second kernel adds them in a fixed order.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 #include <math.h>
@@ -22,9 +26,10 @@ namespace {
 
 constexpr int NT = 256;          // threads per workgroup
 constexpr int RUN = 64;          // samples per run
-constexpr int NBMAX = 3;         // 4x4 blocks per thread: covers Lp = 132 (561 blocks)
-constexpr int LPMAX = 132;       // SR_SELECT_MAX_ATOMS + 1, padded to a multiple of 4
+constexpr int TSS = RUN + 4;     // floats per tile column: 16-byte loads of 16 columns x 4 sample groups miss each other's banks
 constexpr int GRID = 512;        // workgroups (two per CU)
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 struct GramArgs {
     const float* up;
@@ -33,152 +38,236 @@ struct GramArgs {
     const float* target;
     double* ws;
     int N, C, H, W, L, stride, ny, nx;
-    int Lp, nblk;                // padded column count (L + 1 -> multiple of 4), blocks in the upper triangle
+    int n16, ntile;              // 16-column blocks covering L + 1 columns, blocks in the upper triangle
 };
 
-int padded_columns(int L) { return 4 * ((L + 1 + 3) / 4); }
-int upper_blocks(int Lp) { const int n = Lp / 4; return n * (n + 1) / 2; }
+int column_blocks(int L) { return (L + 1 + 15) / 16; }
+int upper_blocks(int n) { return n * (n + 1) / 2; }
 
-__device__ __forceinline__ float ldf(const float* p, size_t i) { return p[i]; }
-__device__ __forceinline__ float ldf(const __half* p, size_t i) { return __half2float(p[i]); }
 struct e4m3 { unsigned char bits; };        // 8-bit E4M3 storage, widened exactly by the conversion instruction
-__device__ __forceinline__ float ldf(const e4m3* p, size_t i) { return __builtin_amdgcn_cvt_f32_fp8((int)p[i].bits, 0); }
+__device__ __forceinline__ float widen(float v) { return v; }
+__device__ __forceinline__ float widen(__half v) { return __half2float(v); }
+__device__ __forceinline__ float widen(e4m3 v) { return __builtin_amdgcn_cvt_f32_fp8((int)v.bits, 0); }
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
-// q-th 4x4 block of the upper triangle, row-major: (bi, bj) with bi <= bj
-__device__ __forceinline__ void block_of(int q, int n4, int& bi, int& bj) {
+// q-th block of the upper triangle of an n x n block matrix, row-major: (bi, bj) with bi <= bj
+__device__ __forceinline__ void block_of(int q, int n, int& bi, int& bj) {
     int r = 0, start = 0;
-    while (start + (n4 - r) <= q) { start += n4 - r; ++r; }
+    while (start + (n - r) <= q) { start += n - r; ++r; }
     bi = r;
     bj = r + (q - start);
 }
 
-template <int K, typename TC>
-__global__ __launch_bounds__(NT) void k_atom_gram(const GramArgs a) {
+// N16: 16-column blocks the LDS tile has room for (2, 5 or 9; the frame's own count
+// a.n16 may be smaller: the columns beyond it are computed as zeros and never read).
+// Up to 5 blocks there are two LDS tiles, so that one barrier per run and channel is
+// enough.  The response loop has no branches: atoms past L read the last dictionary
+// row with a zero coefficient, so the scalar loads of one atom's row overlap the
+// multiply-adds of the one before.
+template <int K, typename TC, int N16>
+__global__ __launch_bounds__(NT, (N16 <= 5 && K <= 5) ? 2 : 1) void k_atom_gram(const GramArgs a) {
     constexpr int KK = K * K, R = (K - 1) / 2;
-    __shared__ float tile[RUN * LPMAX];
+    constexpr int NTW = N16 == 2 ? 1 : (N16 == 5 ? 4 : 12);     // blocks per wavefront
+    constexpr int NBUF = N16 <= 5 ? 2 : 1;
+    constexpr int NPHI = N16 * 4;                     // columns per thread (one wavefront takes every fourth)
+    __shared__ float tile[NBUF][N16 * 16 * TSS];
 
-    const int tid = threadIdx.x, si = tid & 63;
+    const int tid = threadIdx.x, si = tid & 63, c16 = tid & 15, kq = (tid >> 4) & 3;
     const int g = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int Lp = a.Lp, n4 = Lp / 4;
-    int bi[NBMAX], bj[NBMAX];
+    // blocks g, g + 4, ... of the upper triangle; a wavefront with fewer blocks than
+    // the others repeats the last block (and does not store it) so that the
+    // matrix-core loop has no branches
+    int bi[NTW], bj[NTW];
 #pragma unroll
-    for (int i = 0; i < NBMAX; ++i) {
-        const int q = tid + NT * i;
-        bi[i] = -1; bj[i] = 0;
-        if (q < a.nblk) block_of(q, n4, bi[i], bj[i]);
+    for (int t = 0; t < NTW; ++t) {
+        const int q = g + 4 * t;
+        block_of(q < a.ntile ? q : a.ntile - 1, a.n16, bi[t], bj[t]);
     }
-    double dacc[NBMAX][16];
+    double dacc[NTW][4];
 #pragma unroll
-    for (int i = 0; i < NBMAX; ++i)
+    for (int t = 0; t < NTW; ++t)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) dacc[i][e] = 0.0;
+        for (int e = 0; e < 4; ++e) dacc[t][e] = 0.0;
 
     const size_t plane = (size_t)a.H * a.W;
     const long long per_img = (long long)a.ny * a.nx, P = per_img * a.N;
     const long long nrun = (P + RUN - 1) / RUN;
-    for (long long run = blockIdx.x; run < nrun; run += gridDim.x) {
+
+    // A thread's sample: validity, image, and the offsets of its clamped k x k
+    // neighbourhood (nearest pixel outside the image) within a plane.
+    // (a sample past the end is clamped to the last one, so that every load has a
+    // valid address and needs no branch; its responses are zeroed instead)
+    struct Sample { bool ok; int n; size_t row[K], col[K], centre; };
+    auto sample_of = [&](long long run) {
         const long long s = run * RUN + si;
-        const bool ok = s < P;
-        int n = 0, Y = 0, X = 0;
-        if (ok) {
-            n = (int)(s / per_img);
-            const int rem = (int)(s - (long long)n * per_img);
-            const int iy = rem / a.nx;
-            Y = iy * a.stride;
-            X = (rem - iy * a.nx) * a.stride;
-        }
-        // the coefficients of this thread's atoms at its sample: the same for every channel
-        float phi[LPMAX / 4];
+        Sample p;
+        p.ok = s < P;
+        const long long sc = p.ok ? s : P - 1;
+        p.n = (int)(sc / per_img);
+        const int rem = (int)(sc - (long long)p.n * per_img);
+        const int iy = rem / a.nx;
+        const int Y = iy * a.stride, X = (rem - iy * a.nx) * a.stride;
 #pragma unroll
-        for (int i = 0; i < LPMAX / 4; ++i) {
+        for (int d = 0; d < K; ++d) {
+            p.row[d] = (size_t)clampi(Y + d - R, 0, a.H - 1) * a.W;
+            p.col[d] = clampi(X + d - R, 0, a.W - 1);
+        }
+        p.centre = (size_t)Y * a.W + X;
+        return p;
+    };
+    // The coefficients of this thread's atoms at its sample (the same for every
+    // channel), the k x k neighbourhood and the target pixel: requested here as
+    // stored, widened and masked only where they are used, so that a request never
+    // waits for its own data.
+    auto load_phi = [&](const Sample& p, TC (&raw)[NPHI]) {
+        const TC* base = (const TC*)a.coeff + (size_t)p.n * a.L * plane + p.centre;
+#pragma unroll
+        for (int i = 0; i < NPHI; ++i) {
             const int l = g + 4 * i;
-            phi[i] = (ok && l < a.L)
-                         ? ldf((const TC*)a.coeff, ((size_t)n * a.L + l) * plane + (size_t)Y * a.W + X) : 0.0f;
+            raw[i] = base[(size_t)(l < a.L ? l : a.L - 1) * plane];
         }
-        for (int c = 0; c < a.C; ++c) {
+    };
+    auto finish_phi = [&](const Sample& p, const TC (&raw)[NPHI], float (&phi)[NPHI]) {
+#pragma unroll
+        for (int i = 0; i < NPHI; ++i) phi[i] = (p.ok && g + 4 * i < a.L) ? widen(raw[i]) : 0.0f;
+    };
+    auto load_patch = [&](const Sample& p, int c, float (&patch)[KK], float& h) {
+        const size_t pl = ((size_t)p.n * a.C + c) * plane;
+        const float* uplane = a.up + pl;
+#pragma unroll
+        for (int dy = 0; dy < K; ++dy)
+#pragma unroll
+            for (int dx = 0; dx < K; ++dx) patch[dy * K + dx] = uplane[p.row[dy] + p.col[dx]];
+        h = a.target[pl + p.centre];
+    };
+
+    long long run = blockIdx.x;
+    if (run < nrun) {
+        // One iteration per (run, channel).  The operands of the next iteration are
+        // requested before the matrix-core phase of this one and used after it.
+        Sample smp = sample_of(run), smp_n = smp;
+        TC raw_n[NPHI];
+        float phi[NPHI], patch[KK], patch_n[KK], hval, hval_n;
+        load_phi(smp, raw_n);
+        load_patch(smp, 0, patch, hval);
+        finish_phi(smp, raw_n, phi);
+        hval = smp.ok ? hval : 0.0f;
+        hval_n = 0.0f;
+#pragma unroll
+        for (int j = 0; j < KK; ++j) patch_n[j] = 0.0f;
+        int c = 0, buf = 0;
+        for (;;) {
             // (1) responses of every atom at this thread's sample, plus the target column
-            float patch[KK];
-            const float* uplane = a.up + ((size_t)n * a.C + c) * plane;
-#pragma unroll
-            for (int dy = 0; dy < K; ++dy)
-#pragma unroll
-                for (int dx = 0; dx < K; ++dx) {
-                    const int yy = clampi(Y + dy - R, 0, a.H - 1), xx = clampi(X + dx - R, 0, a.W - 1);
-                    patch[dy * K + dx] = ok ? uplane[(size_t)yy * a.W + xx] : 0.0f;
-                }
-            const float hval = ok ? a.target[((size_t)n * a.C + c) * plane + (size_t)Y * a.W + X] : 0.0f;
-#pragma unroll
-            for (int i = 0; i < LPMAX / 4; ++i) {
+            float* T = tile[buf];
+            // (the dictionary row of the next atom is requested before the multiply-adds
+            // of this one: scalar loads return out of order, so a wait is always for all
+            // of them, and the scheduling fences keep the request one atom ahead)
+            float drow[KK], drow_n[KK];
+            auto dict_row = [&](int i, float (&d)[KK]) {
                 const int l = g + 4 * i;                // the same for the whole wavefront
-                if (l < Lp) {
-                    float r = 0.0f;
-                    if (l < a.L) {
-                        const float* d = a.dict + (size_t)l * KK;
-                        float dot = 0.0f;
+                const float* src = a.dict + (size_t)(l < a.L ? l : a.L - 1) * KK;
 #pragma unroll
-                        for (int j = 0; j < KK; ++j) dot = fmaf(d[j], patch[j], dot);
-                        r = phi[i] * dot;
-                    } else if (l == a.L) {
-                        r = hval;
+                for (int j = 0; j < KK; ++j) d[j] = src[j];
+            };
+            dict_row(0, drow);
+#pragma unroll
+            for (int i = 0; i < NPHI; ++i) {
+                const int l = g + 4 * i;
+                if (i + 1 < NPHI) dict_row(i + 1, drow_n);
+                __builtin_amdgcn_sched_barrier(0);
+                float dot = 0.0f;
+#pragma unroll
+                for (int j = 0; j < KK; ++j) dot = fmaf(drow[j], patch[j], dot);
+                T[l * TSS + si] = l == a.L ? hval : phi[i] * dot;      // phi is zero past L
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int j = 0; j < KK; ++j) drow[j] = drow_n[j];
+            }
+            __syncthreads();
+            int c_n = c + 1;
+            long long run_n = run;
+            if (c_n == a.C) { c_n = 0; run_n = run + gridDim.x; }
+            const bool more = run_n < nrun;
+            if (more) {
+                if (c_n == 0) {
+                    smp_n = sample_of(run_n);
+                    load_phi(smp_n, raw_n);
+                }
+                load_patch(smp_n, c_n, patch_n, hval_n);
+            }
+            // (2) this wavefront's blocks of tile^T tile over the 64 samples
+            f32x4 acc[NTW];
+#pragma unroll
+            for (int t = 0; t < NTW; ++t) acc[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            // (blocks go four at a time: their operands are read together and their
+            // steps interleaved, so that a step never waits for the one before it)
+            constexpr int TG = NTW < 4 ? NTW : 4;
+#pragma unroll
+            for (int sg = 0; sg < RUN / 16; ++sg) {
+#pragma unroll
+                for (int t0 = 0; t0 < NTW; t0 += TG) {
+                    float4 u[TG], v[TG];
+#pragma unroll
+                    for (int t = 0; t < TG; ++t) {
+                        u[t] = *(const float4*)&T[(16 * bi[t0 + t] + c16) * TSS + 16 * sg + 4 * kq];
+                        v[t] = *(const float4*)&T[(16 * bj[t0 + t] + c16) * TSS + 16 * sg + 4 * kq];
                     }
-                    tile[si * Lp + l] = r;
+#pragma unroll
+                    for (int t = 0; t < TG; ++t) acc[t0 + t] = __builtin_amdgcn_mfma_f32_16x16x4f32(u[t].x, v[t].x, acc[t0 + t], 0, 0, 0);
+#pragma unroll
+                    for (int t = 0; t < TG; ++t) acc[t0 + t] = __builtin_amdgcn_mfma_f32_16x16x4f32(u[t].y, v[t].y, acc[t0 + t], 0, 0, 0);
+#pragma unroll
+                    for (int t = 0; t < TG; ++t) acc[t0 + t] = __builtin_amdgcn_mfma_f32_16x16x4f32(u[t].z, v[t].z, acc[t0 + t], 0, 0, 0);
+#pragma unroll
+                    for (int t = 0; t < TG; ++t) acc[t0 + t] = __builtin_amdgcn_mfma_f32_16x16x4f32(u[t].w, v[t].w, acc[t0 + t], 0, 0, 0);
                 }
             }
-            __syncthreads();
-            // (2) this thread's blocks of tile^T tile over the 64 samples
-            float acc[NBMAX][16];
 #pragma unroll
-            for (int i = 0; i < NBMAX; ++i)
+            for (int t = 0; t < NTW; ++t)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[i][e] = 0.0f;
-            for (int ss = 0; ss < RUN; ++ss) {
-#pragma unroll
-                for (int i = 0; i < NBMAX; ++i)
-                    if (bi[i] >= 0) {
-                        const float4 u = *(const float4*)&tile[ss * Lp + 4 * bi[i]];
-                        const float4 v = *(const float4*)&tile[ss * Lp + 4 * bj[i]];
-                        const float uu[4] = {u.x, u.y, u.z, u.w}, vv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-#pragma unroll
-                            for (int f = 0; f < 4; ++f) acc[i][4 * e + f] = fmaf(uu[e], vv[f], acc[i][4 * e + f]);
-                    }
+                for (int e = 0; e < 4; ++e) dacc[t][e] += (double)acc[t][e];
+            if (NBUF == 1) __syncthreads();
+            else buf ^= 1;
+            if (!more) break;
+            if (c_n == 0) {
+                smp = smp_n;
+                finish_phi(smp, raw_n, phi);
             }
 #pragma unroll
-            for (int i = 0; i < NBMAX; ++i)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) dacc[i][e] += (double)acc[i][e];
-            __syncthreads();
+            for (int j = 0; j < KK; ++j) patch[j] = patch_n[j];
+            hval = smp.ok ? hval_n : 0.0f;
+            c = c_n;
+            run = run_n;
         }
     }
+    // lane (c16, kq), register e of block (bi, bj) holds row 16 bi + 4 kq + e, column 16 bj + c16
 #pragma unroll
-    for (int i = 0; i < NBMAX; ++i)
-        if (bi[i] >= 0) {
-            double* dst = a.ws + ((size_t)blockIdx.x * a.nblk + (tid + NT * i)) * 16;
+    for (int t = 0; t < NTW; ++t)
+        if (g + 4 * t < a.ntile) {
+            double* dst = a.ws + ((size_t)blockIdx.x * a.ntile + (g + 4 * t)) * 256 + si * 4;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) dst[e] = dacc[i][e];
+            for (int e = 0; e < 4; ++e) dst[e] = dacc[t][e];
         }
 }
 
 // Adds the workgroups' partial sums in workgroup order and scatters them into
 // G (both triangles), b, hh; also stores the sample count.
-__global__ __launch_bounds__(NT) void k_gram_reduce(const double* __restrict__ ws, int grid, int nblk, int n4, int L,
+__global__ __launch_bounds__(NT) void k_gram_reduce(const double* __restrict__ ws, int grid, int ntile, int n16, int L,
                                                     double M, double* __restrict__ normal) {
     const int idx = blockIdx.x * NT + threadIdx.x;
     if (idx == 0) normal[(size_t)L * L + L + 1] = M;
-    if (idx >= nblk * 16) return;
-    const int q = idx >> 4, e = idx & 15;
+    if (idx >= ntile * 256) return;
+    const int q = idx >> 8, lane = (idx >> 2) & 63, e = idx & 3;
     int bi, bj;
-    block_of(q, n4, bi, bj);
+    block_of(q, n16, bi, bj);
+    const int row = 16 * bi + 4 * (lane >> 4) + e, col = 16 * bj + (lane & 15);
+    if (row > col || col > L) return;           // diagonal blocks hold both triangles: keep the upper one
     double sum = 0.0;
-    for (int w = 0; w < grid; ++w) sum += ws[((size_t)w * nblk + q) * 16 + e];
-    const int row = 4 * bi + (e >> 2), col = 4 * bj + (e & 3);
-    if (row > col) return;                      // diagonal blocks hold both triangles: keep the upper one
+    for (int w = 0; w < grid; ++w) sum += ws[((size_t)w * ntile + q) * 256 + (idx & 255)];
     if (col < L) {
         normal[(size_t)row * L + col] = sum;
         normal[(size_t)col * L + row] = sum;
-    } else if (col == L) {
+    } else {
         if (row < L) normal[(size_t)L * L + row] = sum;
         else normal[(size_t)L * L + L] = sum;   // row == col == L: h^T h
     }
@@ -255,7 +344,7 @@ vec solve_dense(vec A, vec y, int n) {
 extern "C" __attribute__((visibility("default")))
 size_t sr_atom_gram_workspace_bytes(int L) {
     if (L < 1 || L > SR_SELECT_MAX_ATOMS) return 0;
-    return (size_t)GRID * upper_blocks(padded_columns(L)) * 16 * sizeof(double);
+    return (size_t)GRID * upper_blocks(column_blocks(L)) * 256 * sizeof(double);
 }
 
 extern "C" __attribute__((visibility("default")))
@@ -287,14 +376,20 @@ int sr_atom_gram(const sr_tensor* up, const sr_tensor* coeff, const sr_tensor* d
     a.N = up->n; a.C = channels; a.H = up->h; a.W = up->w; a.L = L; a.stride = stride;
     a.ny = empty ? 0 : (up->h + stride - 1) / stride;
     a.nx = empty ? 0 : (up->w + stride - 1) / stride;
-    a.Lp = padded_columns(L);
-    a.nblk = upper_blocks(a.Lp);
+    a.n16 = column_blocks(L);
+    a.ntile = upper_blocks(a.n16);
     const hipStream_t st = (hipStream_t)stream;
+#define SR_GRAM_LAUNCH_T(KS, TC)                                                                           \
+    do {                                                                                                    \
+        if (a.n16 <= 2) hipLaunchKernelGGL((k_atom_gram<KS, TC, 2>), dim3(GRID), dim3(NT), 0, st, a);       \
+        else if (a.n16 <= 5) hipLaunchKernelGGL((k_atom_gram<KS, TC, 5>), dim3(GRID), dim3(NT), 0, st, a);  \
+        else hipLaunchKernelGGL((k_atom_gram<KS, TC, 9>), dim3(GRID), dim3(NT), 0, st, a);                  \
+    } while (0)
 #define SR_GRAM_LAUNCH(KS)                                                                                  \
     do {                                                                                                    \
-        if (coeff->dtype == SR_F16) hipLaunchKernelGGL((k_atom_gram<KS, __half>), dim3(GRID), dim3(NT), 0, st, a);    \
-        else if (coeff->dtype == SR_F32) hipLaunchKernelGGL((k_atom_gram<KS, float>), dim3(GRID), dim3(NT), 0, st, a); \
-        else hipLaunchKernelGGL((k_atom_gram<KS, e4m3>), dim3(GRID), dim3(NT), 0, st, a);                             \
+        if (coeff->dtype == SR_F16) SR_GRAM_LAUNCH_T(KS, __half);                                           \
+        else if (coeff->dtype == SR_F32) SR_GRAM_LAUNCH_T(KS, float);                                       \
+        else SR_GRAM_LAUNCH_T(KS, e4m3);                                                                    \
     } while (0)
     switch (k) {
     case 3:  SR_GRAM_LAUNCH(3); break;
@@ -302,11 +397,12 @@ int sr_atom_gram(const sr_tensor* up, const sr_tensor* coeff, const sr_tensor* d
     default: SR_GRAM_LAUNCH(7); break;
     }
 #undef SR_GRAM_LAUNCH
+#undef SR_GRAM_LAUNCH_T
     if (hipGetLastError() != hipSuccess) return SR_ERR_LAUNCH;
     const double M = (double)a.N * a.ny * a.nx * a.C;
-    const int items = a.nblk * 16;
+    const int items = a.ntile * 256;
     hipLaunchKernelGGL(k_gram_reduce, dim3((items + NT - 1) / NT), dim3(NT), 0, st,
-                       (const double*)workspace, GRID, a.nblk, a.Lp / 4, L, M, normal);
+                       (const double*)workspace, GRID, a.ntile, a.n16, L, M, normal);
     return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_LAUNCH;
 }
 
