@@ -64,7 +64,7 @@ def test_argument_checks():
         assert ok(dp, 24, *bad, kept, ctypes.byref(n), gam, None) == -3
     assert ok(dp, 24, 0.5, 0.1, 1e-6, 0.0, kept, ctypes.byref(n), gam, None) == 0 and 1 <= n.value <= 12
     # gram entry point: everything is checked before anything is launched
-    assert lib.sr_atom_gram_workspace_bytes(72) == 512 * 190 * 128
+    assert lib.sr_atom_gram_workspace_bytes(72) == 512 * 15 * 256 * 8        # 15 blocks of 16 x 16 doubles per workgroup
     assert lib.sr_atom_gram_workspace_bytes(0) == 0 and lib.sr_atom_gram_workspace_bytes(129) == 0
     T = sr.sr_tensor
     up = T(0x10000000, sr.SR_F32, 1, 3, 32, 64); tg = T(0x20000000, sr.SR_F32, 1, 3, 32, 64)
