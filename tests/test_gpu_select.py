@@ -16,7 +16,7 @@ CASES = [
     # (N, C, h, w, scale, L, k, coeff dtype, stride)
     (1, 3, 9, 11, 2, 5, 3, "f32", 1),
     (2, 3, 12, 17, 4, 72, 5, "f16", 1),      # 3264 lattice pixels: 51 runs of 64 samples
-    (1, 1, 16, 16, 3, 128, 7, "f16", 2),     # the largest atom count, three blocks per thread
+    (1, 1, 16, 16, 3, 128, 7, "f16", 2),     # the largest atom count: 9 column blocks, 12 blocks per wavefront
     (3, 2, 10, 13, 2, 17, 7, "f32", 3),      # ragged lattice, L + 1 not a multiple of 4
     (1, 3, 40, 48, 4, 72, 5, "f16", 5),
     (1, 16, 6, 7, 2, 3, 3, "f32", 1),        # 16 channels
