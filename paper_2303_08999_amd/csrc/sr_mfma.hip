@@ -1,6 +1,6 @@
 // Matrix-core path, host side: which kernel instantiation serves a call.
 // The kernel itself is in sr_mfma_kernel.h; its instantiations are compiled in
-// sr_mfma_k5.hip and sr_mfma_k7.hip.
+// sr_mfma_k5*.hip and sr_mfma_k7.hip.
 #include "sr_launch.h"
 
 namespace srd {
@@ -19,10 +19,14 @@ constexpr int N_TILE_SHAPES = 6;
 // only: padding atoms meet zero dictionary rows and re-read a cached plane.
 int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
     const int need = (n_fold + 7) / 8;
-    if (coeff_dtype == SR_F32) return (k == 5 && need <= 9) ? 9 : 0;     // fp32 coefficients: 5x5, up to 72 atoms
+    if (coeff_dtype == SR_F32) {                                        // fp32 coefficients: 5x5, up to 72 atoms
+        if (k != 5 || need > 9) return 0;
+        if (channels != 3) return 9;
+        return need <= 1 ? 1 : (need <= 2 ? 2 : (need <= 4 ? 4 : (need <= 6 ? 6 : 9)));
+    }
     if (coeff_dtype == SR_F8E4M3) {                                     // fp8: 5x5, up to 72 atoms
         if (k != 5 || need > 9) return 0;
-        return (channels == 3 && need <= 1) ? 1 : 9;
+        return channels != 3 ? 9 : (need <= 1 ? 1 : (need <= 4 ? 4 : 9));
     }
     static const int k5c3[] = {1, 2, 4, 6, 9, 0}, k5c1[] = {1, 4, 9, 0};
     static const int k7c3[] = {2, 9, 16, 0}, k7c1[] = {16, 0};

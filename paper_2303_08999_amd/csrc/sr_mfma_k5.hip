@@ -4,13 +4,6 @@
 namespace srd {
 
 // np8: capacity in groups of 8 folded atoms; shape: tile shape index (C = 3, np8 = 9 only)
-// fp32 coefficients: 2 pixels per lane (8-byte loads), tile 64 x 16
-hipError_t launch_mfma_k5_f32(const AssembleArgs& a, int np8, hipStream_t st) {
-    if (np8 != 9) return hipErrorInvalidValue;
-    return a.C == 3 ? launch_one<5, 3, 9, 2, 1, 4, 4, 2, true>(a, st)
-                    : launch_one<5, 1, 9, 2, 1, 4, 4, 2, true>(a, st);
-}
-
 hipError_t launch_mfma_k5(const AssembleArgs& a, int np8, int shape, hipStream_t st) {
     // Few atoms: the kernel is bound by up-sampling, filtering and the output
     // write rather than by the coefficient stream; the register budget then

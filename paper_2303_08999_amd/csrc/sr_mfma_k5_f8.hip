@@ -15,6 +15,9 @@ hipError_t launch_mfma_k5_f8(const AssembleArgs& a, int np8, hipStream_t st) {
         case 1:
             if (a.s == 4) return launch_one<5, 3, 1, 4, 2, 4, 4, 3, CT_F8, 4>(a, st);        //  64 x 32
             return launch_one<5, 3, 1, 4, 2, 4, 2, 3, CT_F8>(a, st);
+        case 4:
+            if (a.s == 4) return launch_one<5, 3, 4, 4, 1, 4, 6, 2, CT_F8, 4>(a, st);
+            return launch_one<5, 3, 4, 4, 1, 4, 4, 2, CT_F8>(a, st);
         case 9:
             if (a.s == 4) return launch_one<5, 3, 9, 4, 1, 4, 6, 2, CT_F8, 4>(a, st);    // 128 x 24
             return launch_one<5, 3, 9, 4, 1, 4, 4, 2, CT_F8>(a, st);

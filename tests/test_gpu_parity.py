@@ -242,6 +242,21 @@ def test_selective_kept_list_with_and_without_gamma(oracle, kernel):
     check_full(oracle, wl, kernel, kept=np.arange(71, -1, -1), inp=inp)
 
 
+@pytest.mark.parametrize("cd", ["f16", "f32", "f8"])
+def test_kept_lists_around_every_built_capacity(oracle, cd):
+    """The matrix-core kernel is built for 8/16/32/48/72 atoms (fewer sizes for some
+    storage types); a kept list runs in the smallest one that holds it.  Lists one
+    below, at and one above each size, with scales, against the oracle."""
+    wl = sr_synth.Workload("capacity", 11, 1, 3, 20, 36, 4, 72, 5, cd, "f32", 0.0, 1.5)
+    inp = sr_synth.make_inputs(wl, DEV)
+    rng = np.random.default_rng(5)
+    for n_keep in (1, 7, 8, 9, 15, 16, 17, 31, 32, 33, 47, 48, 49, 71, 72):
+        kept = rng.permutation(72)[:n_keep].astype(np.int32)
+        gamma = rng.uniform(0.5, 1.5, size=n_keep).astype(np.float32)
+        assert planned(inp, wl, MFMA, kept) == MFMA
+        check_full(oracle, wl, MFMA, kept=kept, gamma=gamma, inp=inp)
+
+
 # ---- arbitrary real coefficients: negative, unnormalised, fp16 subnormal ---------
 @pytest.mark.parametrize("kernel", KERNELS)
 def test_unnormalised_negative_and_subnormal_coefficients(oracle, kernel):
