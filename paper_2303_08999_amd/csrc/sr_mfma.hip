@@ -8,6 +8,7 @@ namespace srd {
 hipError_t launch_mfma_k5(const AssembleArgs& a, int np8, int shape, hipStream_t st);
 hipError_t launch_mfma_k7(const AssembleArgs& a, int np8, int shape, hipStream_t st);
 hipError_t launch_mfma_k5_f32(const AssembleArgs& a, int np8, hipStream_t st);
+hipError_t launch_mfma_k7_f32(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_k5_f8(const AssembleArgs& a, int np8, hipStream_t st);
 
 namespace {
@@ -19,17 +20,23 @@ constexpr int N_TILE_SHAPES = 6;
 // only: padding atoms meet zero dictionary rows and re-read a cached plane.
 int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
     const int need = (n_fold + 7) / 8;
-    if (coeff_dtype == SR_F32) {                                        // fp32 coefficients: 5x5, up to 72 atoms
-        if (k != 5 || need > 9) return 0;
-        if (channels != 3) return 9;
-        return need <= 1 ? 1 : (need <= 2 ? 2 : (need <= 4 ? 4 : (need <= 6 ? 6 : 9)));
+    if (coeff_dtype == SR_F32) {                                        // fp32 coefficients
+        static const int k5c3[] = {1, 2, 4, 6, 9, 0}, k5c1[] = {1, 4, 6, 9, 0}, k7[] = {9, 16, 0};
+        if (k == 7 && need <= 2) return 0;                                // short 7x7 lists: the generic kernel is faster
+        const int* built = k == 5 ? (channels == 3 ? k5c3 : k5c1) : k7;
+        for (; *built; ++built)
+            if (*built >= need) return *built;
+        return 0;
     }
-    if (coeff_dtype == SR_F8E4M3) {                                     // fp8: 5x5, up to 72 atoms
-        if (k != 5 || need > 9) return 0;
-        return channels != 3 ? 9 : (need <= 1 ? 1 : (need <= 4 ? 4 : 9));
+    if (coeff_dtype == SR_F8E4M3) {                                     // 8-bit coefficients: 5x5, up to 72 atoms
+        static const int c3[] = {1, 4, 6, 9, 0}, c1[] = {1, 4, 9, 0};
+        if (k != 5) return 0;
+        for (const int* built = channels == 3 ? c3 : c1; *built; ++built)
+            if (*built >= need) return *built;
+        return 0;
     }
-    static const int k5c3[] = {1, 2, 4, 6, 9, 0}, k5c1[] = {1, 4, 9, 0};
-    static const int k7c3[] = {2, 9, 16, 0}, k7c1[] = {16, 0};
+    static const int k5c3[] = {1, 2, 4, 6, 9, 0}, k5c1[] = {1, 4, 6, 9, 0};
+    static const int k7c3[] = {2, 9, 16, 0}, k7c1[] = {2, 9, 16, 0};
     const int* built = k == 5 ? (channels == 3 ? k5c3 : k5c1) : (channels == 3 ? k7c3 : k7c1);
     for (; *built; ++built)
         if (*built >= need) return *built;
@@ -58,7 +65,7 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
 hipError_t launch_mfma(const AssembleArgs& a, int k, bool io_f16, int tile, hipStream_t st) {
     (void)io_f16;
     const int np8 = np8_for(k, a.C, a.n_fold, a.coeff_dtype);
-    if (a.coeff_dtype == SR_F32) return launch_mfma_k5_f32(a, np8, st);
+    if (a.coeff_dtype == SR_F32) return k == 5 ? launch_mfma_k5_f32(a, np8, st) : launch_mfma_k7_f32(a, np8, st);
     if (a.coeff_dtype == SR_F8E4M3) return launch_mfma_k5_f8(a, np8, st);
     if (k == 5) return launch_mfma_k5(a, np8, tile, st);
     if (k == 7) return launch_mfma_k7(a, np8, tile, st);

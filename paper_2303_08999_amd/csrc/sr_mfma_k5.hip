@@ -41,6 +41,7 @@ hipError_t launch_mfma_k5(const AssembleArgs& a, int np8, int shape, hipStream_t
     switch (np8) {
     case 1:  return launch_one<5, 1, 1, 4, 1, 4, 4, 2>(a, st);
     case 4:  return launch_one<5, 1, 4, 4, 1, 4, 4, 2>(a, st);
+    case 6:  return launch_one<5, 1, 6, 4, 1, 4, 4, 2>(a, st);
     case 9:
         if (a.s == 4) return launch_one<5, 1, 9, 4, 1, 4, 6, 2, CT_F16, 4>(a, st);
         return launch_one<5, 1, 9, 4, 1, 4, 4, 2>(a, st);

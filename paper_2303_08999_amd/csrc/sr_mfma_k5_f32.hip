@@ -1,5 +1,5 @@
-// Matrix-core kernel instantiations for 5x5 atoms and fp32 coefficients (see
-// sr_mfma_kernel.h): 2 pixels per lane (8-byte loads), tile 64 x 16.
+// Matrix-core kernel instantiations for fp32 coefficients (see sr_mfma_kernel.h):
+// 2 pixels per lane (8-byte loads), tile 64 x 16.
 #include "sr_mfma_kernel.h"
 
 namespace srd {
@@ -16,8 +16,31 @@ hipError_t launch_mfma_k5_f32(const AssembleArgs& a, int np8, hipStream_t st) {
         default: return hipErrorInvalidValue;
         }
     }
-    if (np8 != 9) return hipErrorInvalidValue;
-    return launch_one<5, 1, 9, 2, 1, 4, 4, 2, CT_F32>(a, st);
+    switch (np8) {
+    case 1:  return launch_one<5, 1, 1, 2, 1, 4, 4, 2, CT_F32>(a, st);
+    case 4:  return launch_one<5, 1, 4, 2, 1, 4, 4, 2, CT_F32>(a, st);
+    case 6:  return launch_one<5, 1, 6, 2, 1, 4, 4, 2, CT_F32>(a, st);
+    case 9:  return launch_one<5, 1, 9, 2, 1, 4, 4, 2, CT_F32>(a, st);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+// 7x7 atoms: two 32-row MFMA blocks per pixel slot; 128 atoms need the whole
+// register file of a SIMD (one wavefront per SIMD).  Lists of up to 16 atoms are
+// left to the generic kernel, which measured faster there (62 against 80 us at 1080p).
+hipError_t launch_mfma_k7_f32(const AssembleArgs& a, int np8, hipStream_t st) {
+    if (a.C == 3) {
+        switch (np8) {
+        case 9:  return launch_one<7, 3, 9, 2, 1, 4, 4, 2, CT_F32>(a, st);
+        case 16: return launch_one<7, 3, 16, 2, 1, 4, 4, 1, CT_F32>(a, st);
+        default: return hipErrorInvalidValue;
+        }
+    }
+    switch (np8) {
+    case 9:  return launch_one<7, 1, 9, 2, 1, 4, 4, 2, CT_F32>(a, st);
+    case 16: return launch_one<7, 1, 16, 2, 1, 4, 4, 1, CT_F32>(a, st);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace srd

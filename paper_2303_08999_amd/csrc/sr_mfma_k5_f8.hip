@@ -18,15 +18,23 @@ hipError_t launch_mfma_k5_f8(const AssembleArgs& a, int np8, hipStream_t st) {
         case 4:
             if (a.s == 4) return launch_one<5, 3, 4, 4, 1, 4, 6, 2, CT_F8, 4>(a, st);
             return launch_one<5, 3, 4, 4, 1, 4, 4, 2, CT_F8>(a, st);
+        case 6:
+            if (a.s == 4) return launch_one<5, 3, 6, 4, 1, 4, 6, 2, CT_F8, 4>(a, st);
+            return launch_one<5, 3, 6, 4, 1, 4, 4, 2, CT_F8>(a, st);
         case 9:
             if (a.s == 4) return launch_one<5, 3, 9, 4, 1, 4, 6, 2, CT_F8, 4>(a, st);    // 128 x 24
             return launch_one<5, 3, 9, 4, 1, 4, 4, 2, CT_F8>(a, st);
         default: return hipErrorInvalidValue;
         }
     }
-    if (np8 != 9) return hipErrorInvalidValue;
-    if (a.s == 4) return launch_one<5, 1, 9, 4, 1, 4, 6, 2, CT_F8, 4>(a, st);
-    return launch_one<5, 1, 9, 4, 1, 4, 4, 2, CT_F8>(a, st);
+    switch (np8) {
+    case 1:  return launch_one<5, 1, 1, 4, 1, 4, 4, 2, CT_F8>(a, st);
+    case 4:  return launch_one<5, 1, 4, 4, 1, 4, 4, 2, CT_F8>(a, st);
+    case 9:
+        if (a.s == 4) return launch_one<5, 1, 9, 4, 1, 4, 6, 2, CT_F8, 4>(a, st);
+        return launch_one<5, 1, 9, 4, 1, 4, 4, 2, CT_F8>(a, st);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace srd

@@ -25,6 +25,8 @@ hipError_t launch_mfma_k7(const AssembleArgs& a, int np8, int shape, hipStream_t
         }
     }
     switch (np8) {
+    case 2:  return launch_k7<1, 2>(a, st);
+    case 9:  return launch_k7<1, 9>(a, st);
     case 16: return launch_k7<1, 16>(a, st);
     default: return hipErrorInvalidValue;
     }

@@ -71,8 +71,9 @@ def plan(lr, coeff, d, out, L=72, k=5, s=4, C=3, kept=None, opts=None):
 
 def test_plan_accepts_a_good_case(lib):
     assert plan(*case()) in (sr.SR_KERNEL_GENERIC, sr.SR_KERNEL_MFMA)
-    assert plan(*case(cd=sr.SR_F32)) == sr.SR_KERNEL_MFMA           # fp32 coefficients: fp32 MFMA, 5x5 only
-    assert plan(*case(cd=sr.SR_F32, k=7), k=7) == sr.SR_KERNEL_GENERIC
+    assert plan(*case(cd=sr.SR_F32)) == sr.SR_KERNEL_MFMA           # fp32 coefficients: fp32 MFMA
+    assert plan(*case(cd=sr.SR_F32, k=7), k=7) == sr.SR_KERNEL_MFMA
+    assert plan(*case(cd=sr.SR_F8E4M3, k=7), k=7) == sr.SR_KERNEL_GENERIC   # 8-bit coefficients: 5x5 only
     assert plan(*case(cd=sr.SR_F32, w=15, s=2), s=2) == sr.SR_KERNEL_MFMA   # HR width 30: even is enough
     assert plan(*case(k=3), k=3) == sr.SR_KERNEL_GENERIC
     assert plan(*case(w=15, s=3), s=3) == sr.SR_KERNEL_GENERIC   # HR width 45: not a multiple of 4
@@ -123,7 +124,7 @@ def test_unsupported(lib):
     o = sr.make_options()
     o.reserved[2] = 1
     assert plan(*case(), opts=o) == -3
-    assert plan(*case(cd=sr.SR_F32, k=7), k=7, opts=sr.make_options(sr.SR_KERNEL_MFMA)) == -3
+    assert plan(*case(cd=sr.SR_F8E4M3, k=7), k=7, opts=sr.make_options(sr.SR_KERNEL_MFMA)) == -3
     assert plan(*case(C=2), C=2, opts=sr.make_options(sr.SR_KERNEL_MFMA)) == -3
 
 

@@ -216,6 +216,16 @@ RAGGED = [
     (17, 34, 4, 3, 7, 5, "f8", "f32", 1),       # ... few atoms (the 8-atom instantiation)
     (26, 31, 2, 3, 50, 5, "f8", "f32", 1),      # ... HR width 62: generic kernel only
     (12, 20, 4, 3, 100, 7, "f8", "f16", 1),     # ... 7x7 atoms: generic kernel only
+    (22, 37, 4, 3, 128, 7, "f32", "f32", 2),    # fp32 coefficients, 7x7: the 128-atom instantiation (one wavefront per SIMD)
+    (19, 30, 2, 3, 72, 7, "f32", "f16", 1),     # ... 72 atoms, fp16 image
+    (27, 21, 3, 1, 100, 7, "f32", "f32", 1),    # ... one channel
+    (20, 28, 4, 1, 60, 7, "f32", "f32", 1),     # ... one channel, 72-atom instantiation
+    (16, 40, 4, 3, 11, 7, "f32", "f32", 1),     # ... few atoms: left to the generic kernel
+    (24, 33, 4, 1, 9, 7, "f16", "f32", 1),      # 7x7, one channel, few atoms (16-atom instantiation)
+    (24, 33, 4, 1, 70, 7, "f16", "f16", 1),     # ... 72-atom instantiation
+    (30, 41, 4, 1, 8, 5, "f32", "f32", 1),      # 5x5, one channel, fp32 coefficients, 8-atom instantiation
+    (30, 41, 4, 1, 30, 5, "f8", "f32", 1),      # ... 8-bit coefficients, 32-atom instantiation
+    (30, 41, 4, 3, 44, 5, "f8", "f32", 1),      # 8-bit coefficients, 48-atom instantiation
 ]
 
 
