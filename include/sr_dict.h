@@ -133,11 +133,11 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
  * qualifies when C is 1 or 3, coeff->data and out->data are 16-byte aligned,
  * the tensors are small enough for 32-bit byte offsets (L*H*W*sizeof(coeff)
  * < 2^32, N*C*H*W < 2^30) and
- *   f16 coefficients: k = 5 with at most 72 folded atoms and HR width % 4 == 0,
+ *   f16 coefficients: k = 3 or 5 with at most 72 folded atoms and HR width % 4 == 0,
  *                     or k = 7 with at most 128 atoms and HR width % 2 == 0;
- *   f32 coefficients: k = 5 with at most 72 folded atoms, or k = 7 with 17 to 128
- *                     folded atoms; HR width % 2 == 0;
- *   f8  coefficients: k = 5 with at most 72 folded atoms, HR width % 4 == 0 and
+ *   f32 coefficients: k = 3 or 5 with at most 72 folded atoms, or k = 7 with 17 to
+ *                     128 folded atoms; HR width % 2 == 0;
+ *   f8  coefficients: k = 3 or 5 with at most 72 folded atoms, HR width % 4 == 0 and
  *                     lr->data 4-byte aligned.
  * Every other supported case runs on the generic kernel.
  */

@@ -1,10 +1,11 @@
 // Matrix-core path, host side: which kernel instantiation serves a call.
 // The kernel itself is in sr_mfma_kernel.h; its instantiations are compiled in
-// sr_mfma_k5*.hip and sr_mfma_k7.hip.
+// sr_mfma_k3.hip, sr_mfma_k5*.hip and sr_mfma_k7.hip.
 #include "sr_launch.h"
 
 namespace srd {
 
+hipError_t launch_mfma_k3(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_k5(const AssembleArgs& a, int np8, int shape, hipStream_t st);
 hipError_t launch_mfma_k7(const AssembleArgs& a, int np8, int shape, hipStream_t st);
 hipError_t launch_mfma_k5_f32(const AssembleArgs& a, int np8, hipStream_t st);
@@ -20,6 +21,10 @@ constexpr int N_TILE_SHAPES = 6;
 // only: padding atoms meet zero dictionary rows and re-read a cached plane.
 int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
     const int need = (n_fold + 7) / 8;
+    if (k == 3) {                                                       // 3x3: up to 72 atoms
+        if (need > 9) return 0;
+        return need <= 1 ? 1 : (need <= 4 ? 4 : 9);
+    }
     if (coeff_dtype == SR_F32) {                                        // fp32 coefficients
         static const int k5c3[] = {1, 2, 4, 6, 9, 0}, k5c1[] = {1, 4, 6, 9, 0}, k7[] = {9, 16, 0};
         if (k == 7 && need <= 2) return 0;                                // short 7x7 lists: the generic kernel is faster
@@ -30,7 +35,7 @@ int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
     }
     if (coeff_dtype == SR_F8E4M3) {                                     // 8-bit coefficients: 5x5, up to 72 atoms
         static const int c3[] = {1, 4, 6, 9, 0}, c1[] = {1, 4, 9, 0};
-        if (k != 5) return 0;
+        if (k != 5) return 0;                                           // (3x3 is handled above)
         for (const int* built = channels == 3 ? c3 : c1; *built; ++built)
             if (*built >= need) return *built;
         return 0;
@@ -46,10 +51,10 @@ int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
 }  // namespace
 
 bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
-    if ((k != 5 && k != 7) || (a.C != 1 && a.C != 3)) return false;
+    if ((k != 3 && k != 5 && k != 7) || (a.C != 1 && a.C != 3)) return false;
     // a lane loads PX consecutive pixels of a row with one load and stores PX/2
     // results per channel: rows must keep that alignment
-    const int px = (k == 5 && coeff_dtype != SR_F32) ? 4 : 2;
+    const int px = (k != 7 && coeff_dtype != SR_F32) ? 4 : 2;
     const unsigned long long cb = coeff_dtype == SR_F32 ? 4ull : (coeff_dtype == SR_F16 ? 2ull : 1ull);
     if (a.W % px != 0 || a.W < px || a.H < 1) return false;
     if (((uintptr_t)a.coeff % 16) != 0 || ((uintptr_t)a.out % 16) != 0) return false;
@@ -65,6 +70,7 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
 hipError_t launch_mfma(const AssembleArgs& a, int k, bool io_f16, int tile, hipStream_t st) {
     (void)io_f16;
     const int np8 = np8_for(k, a.C, a.n_fold, a.coeff_dtype);
+    if (k == 3) return launch_mfma_k3(a, np8, st);
     if (a.coeff_dtype == SR_F32) return k == 5 ? launch_mfma_k5_f32(a, np8, st) : launch_mfma_k7_f32(a, np8, st);
     if (a.coeff_dtype == SR_F8E4M3) return launch_mfma_k5_f8(a, np8, st);
     if (k == 5) return launch_mfma_k5(a, np8, tile, st);

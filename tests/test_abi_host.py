@@ -75,7 +75,8 @@ def test_plan_accepts_a_good_case(lib):
     assert plan(*case(cd=sr.SR_F32, k=7), k=7) == sr.SR_KERNEL_MFMA
     assert plan(*case(cd=sr.SR_F8E4M3, k=7), k=7) == sr.SR_KERNEL_GENERIC   # 8-bit coefficients: 5x5 only
     assert plan(*case(cd=sr.SR_F32, w=15, s=2), s=2) == sr.SR_KERNEL_MFMA   # HR width 30: even is enough
-    assert plan(*case(k=3), k=3) == sr.SR_KERNEL_GENERIC
+    assert plan(*case(k=3), k=3) == sr.SR_KERNEL_MFMA
+    assert plan(*case(k=3, C=2), k=3, C=2) == sr.SR_KERNEL_GENERIC          # one or three channels only
     assert plan(*case(w=15, s=3), s=3) == sr.SR_KERNEL_GENERIC   # HR width 45: not a multiple of 4
     assert plan(*case(w=15), opts=sr.make_options(sr.SR_KERNEL_MFMA)) == sr.SR_KERNEL_MFMA   # width 60
     assert plan(*case(L=73), L=73) == sr.SR_KERNEL_GENERIC       # more atoms than the 5x5 kernel holds

@@ -226,6 +226,17 @@ RAGGED = [
     (30, 41, 4, 1, 8, 5, "f32", "f32", 1),      # 5x5, one channel, fp32 coefficients, 8-atom instantiation
     (30, 41, 4, 1, 30, 5, "f8", "f32", 1),      # ... 8-bit coefficients, 32-atom instantiation
     (30, 41, 4, 3, 44, 5, "f8", "f32", 1),      # 8-bit coefficients, 48-atom instantiation
+    (33, 47, 4, 3, 72, 3, "f16", "f32", 2),     # 3x3 atoms on the matrix-core path
+    (29, 38, 2, 3, 72, 3, "f16", "f16", 1),     # ... x2, fp16 image
+    (27, 36, 3, 1, 30, 3, "f16", "f32", 1),     # ... one channel, 32-atom instantiation
+    (21, 30, 4, 3, 6, 3, "f16", "f32", 1),      # ... 8-atom instantiation
+    (25, 33, 2, 3, 72, 3, "f32", "f32", 1),     # ... fp32 coefficients, HR width 66
+    (18, 26, 4, 1, 50, 3, "f32", "f16", 1),     # ... one channel
+    (23, 35, 4, 3, 72, 3, "f8", "f32", 1),      # ... 8-bit coefficients
+    (23, 35, 3, 1, 20, 3, "f8", "f16", 1),      # ... one channel, x3 (HR width 105: generic kernel only)
+    (24, 36, 3, 1, 20, 3, "f8", "f16", 1),      # ... HR width 108
+    (21, 30, 4, 3, 8, 3, "f32", "f32", 1),      # ... fp32 coefficients, 8-atom instantiation
+    (21, 30, 4, 1, 5, 3, "f8", "f32", 1),       # ... 8-bit coefficients, 8-atom instantiation
 ]
 
 
@@ -429,8 +440,8 @@ def test_tile_sweep_returns_a_valid_shape():
     assert [t for t, _ in res] == list(range(6))
     assert all(ms > 0 for _, ms in res)
     assert tune.best_tile(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, out, reps=3) in range(6)
-    # 3x3 atoms: the matrix-core kernel does not apply, nothing to sweep
-    wl32 = sr_synth.scaled(sr_synth.WORKLOADS["tiny"], k=3)
+    # odd HR width: the matrix-core kernel does not apply, nothing to sweep
+    wl32 = sr_synth.scaled(sr_synth.WORKLOADS["tiny"], w=21, scale=3)
     i32 = sr_synth.make_inputs(wl32, DEV)
     o32 = torch.empty((1, 1, wl32.H, wl32.W), device=DEV)
     assert tune.sweep_tiles(i32["lr"], i32["coeff"], i32["dict"], wl32.L, wl32.k, wl32.scale, wl32.c, o32) == []
