@@ -137,8 +137,8 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
  *                     or k = 7 with at most 128 atoms and HR width % 2 == 0;
  *   f32 coefficients: k = 3 or 5 with at most 72 folded atoms, or k = 7 with 17 to
  *                     128 folded atoms; HR width % 2 == 0;
- *   f8  coefficients: k = 3 or 5 with at most 72 folded atoms, HR width % 4 == 0 and
- *                     lr->data 4-byte aligned.
+ *   f8  coefficients: k = 3 or 5 with at most 72 folded atoms, or k = 7 with 17 to
+ *                     128 folded atoms; HR width % 4 == 0 and lr->data 4-byte aligned.
  * Every other supported case runs on the generic kernel.
  */
 int sr_dict_assemble_ex(const sr_tensor* lr, const sr_tensor* coeff, const sr_tensor* dict,

@@ -11,6 +11,7 @@ hipError_t launch_mfma_k7(const AssembleArgs& a, int np8, int shape, hipStream_t
 hipError_t launch_mfma_k5_f32(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_k7_f32(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_k5_f8(const AssembleArgs& a, int np8, hipStream_t st);
+hipError_t launch_mfma_k7_f8(const AssembleArgs& a, int np8, hipStream_t st);
 
 namespace {
 
@@ -33,9 +34,9 @@ int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
             if (*built >= need) return *built;
         return 0;
     }
-    if (coeff_dtype == SR_F8E4M3) {                                     // 8-bit coefficients: 5x5, up to 72 atoms
+    if (coeff_dtype == SR_F8E4M3) {                                     // 8-bit coefficients
         static const int c3[] = {1, 4, 6, 9, 0}, c1[] = {1, 4, 9, 0};
-        if (k != 5) return 0;                                           // (3x3 is handled above)
+        if (k == 7) return need <= 2 ? 0 : (need <= 9 ? 9 : (need <= 16 ? 16 : 0));   // short lists: generic kernel
         for (const int* built = channels == 3 ? c3 : c1; *built; ++built)
             if (*built >= need) return *built;
         return 0;
@@ -54,7 +55,7 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
     if ((k != 3 && k != 5 && k != 7) || (a.C != 1 && a.C != 3)) return false;
     // a lane loads PX consecutive pixels of a row with one load and stores PX/2
     // results per channel: rows must keep that alignment
-    const int px = (k != 7 && coeff_dtype != SR_F32) ? 4 : 2;
+    const int px = coeff_dtype == SR_F8E4M3 ? 4 : ((k != 7 && coeff_dtype != SR_F32) ? 4 : 2);
     const unsigned long long cb = coeff_dtype == SR_F32 ? 4ull : (coeff_dtype == SR_F16 ? 2ull : 1ull);
     if (a.W % px != 0 || a.W < px || a.H < 1) return false;
     if (((uintptr_t)a.coeff % 16) != 0 || ((uintptr_t)a.out % 16) != 0) return false;
@@ -72,7 +73,7 @@ hipError_t launch_mfma(const AssembleArgs& a, int k, bool io_f16, int tile, hipS
     const int np8 = np8_for(k, a.C, a.n_fold, a.coeff_dtype);
     if (k == 3) return launch_mfma_k3(a, np8, st);
     if (a.coeff_dtype == SR_F32) return k == 5 ? launch_mfma_k5_f32(a, np8, st) : launch_mfma_k7_f32(a, np8, st);
-    if (a.coeff_dtype == SR_F8E4M3) return launch_mfma_k5_f8(a, np8, st);
+    if (a.coeff_dtype == SR_F8E4M3) return k == 5 ? launch_mfma_k5_f8(a, np8, st) : launch_mfma_k7_f8(a, np8, st);
     if (k == 5) return launch_mfma_k5(a, np8, tile, st);
     if (k == 7) return launch_mfma_k7(a, np8, tile, st);
     return hipErrorInvalidValue;

@@ -73,7 +73,8 @@ def test_plan_accepts_a_good_case(lib):
     assert plan(*case()) in (sr.SR_KERNEL_GENERIC, sr.SR_KERNEL_MFMA)
     assert plan(*case(cd=sr.SR_F32)) == sr.SR_KERNEL_MFMA           # fp32 coefficients: fp32 MFMA
     assert plan(*case(cd=sr.SR_F32, k=7), k=7) == sr.SR_KERNEL_MFMA
-    assert plan(*case(cd=sr.SR_F8E4M3, k=7), k=7) == sr.SR_KERNEL_GENERIC   # 8-bit coefficients: 5x5 only
+    assert plan(*case(cd=sr.SR_F8E4M3, k=7), k=7) == sr.SR_KERNEL_MFMA
+    assert plan(*case(cd=sr.SR_F8E4M3, k=7, L=16), k=7, L=16) == sr.SR_KERNEL_GENERIC   # short 7x7 lists stay generic
     assert plan(*case(cd=sr.SR_F32, w=15, s=2), s=2) == sr.SR_KERNEL_MFMA   # HR width 30: even is enough
     assert plan(*case(k=3), k=3) == sr.SR_KERNEL_MFMA
     assert plan(*case(k=3, C=2), k=3, C=2) == sr.SR_KERNEL_GENERIC          # one or three channels only
@@ -125,7 +126,7 @@ def test_unsupported(lib):
     o = sr.make_options()
     o.reserved[2] = 1
     assert plan(*case(), opts=o) == -3
-    assert plan(*case(cd=sr.SR_F8E4M3, k=7), k=7, opts=sr.make_options(sr.SR_KERNEL_MFMA)) == -3
+    assert plan(*case(cd=sr.SR_F8E4M3, k=7, L=16), k=7, L=16, opts=sr.make_options(sr.SR_KERNEL_MFMA)) == -3
     assert plan(*case(C=2), C=2, opts=sr.make_options(sr.SR_KERNEL_MFMA)) == -3
 
 
@@ -199,7 +200,9 @@ def test_e4m3_coefficients_are_a_coefficient_format_only(lib):
     lr, coeff, d, out = case(cd=F8, s=2, w=15)                        # HR width 30: not a multiple of 4
     assert plan(lr, coeff, d, out, s=2) == sr.SR_KERNEL_GENERIC
     lr, coeff, d, out = case(cd=F8, k=7, L=100)
-    assert plan(lr, coeff, d, out, L=100, k=7) == sr.SR_KERNEL_GENERIC
+    assert plan(lr, coeff, d, out, L=100, k=7) == sr.SR_KERNEL_MFMA          # 7x7: 17 to 128 atoms
+    lr, coeff, d, out = case(cd=F8, k=7, L=200)
+    assert plan(lr, coeff, d, out, L=200, k=7) == sr.SR_KERNEL_GENERIC
     coeff_odd = T(0x11000001, F8, 1, 72, 32, 64)                      # one-byte elements: any address
     assert plan(lr, coeff_odd, T(0x18000000, sr.SR_F32, 1, 72, 5, 5), out) == sr.SR_KERNEL_GENERIC
     lr8, coeff, d, out = case(io=F8)

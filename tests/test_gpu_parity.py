@@ -215,7 +215,11 @@ RAGGED = [
     (29, 36, 3, 1, 72, 5, "f8", "f16", 1),      # ... one channel, fp16 image, x3
     (17, 34, 4, 3, 7, 5, "f8", "f32", 1),       # ... few atoms (the 8-atom instantiation)
     (26, 31, 2, 3, 50, 5, "f8", "f32", 1),      # ... HR width 62: generic kernel only
-    (12, 20, 4, 3, 100, 7, "f8", "f16", 1),     # ... 7x7 atoms: generic kernel only
+    (12, 20, 4, 3, 100, 7, "f8", "f16", 1),     # ... 7x7 atoms: the 128-atom instantiation (one wavefront per SIMD)
+    (35, 49, 4, 3, 128, 7, "f8", "f16", 2),     # ... several tiles, two images
+    (22, 36, 3, 1, 60, 7, "f8", "f32", 1),      # ... one channel, 72-atom instantiation, x3
+    (26, 30, 2, 3, 72, 7, "f8", "f32", 1),      # ... x2
+    (20, 24, 4, 3, 12, 7, "f8", "f32", 1),      # ... few atoms: generic kernel
     (22, 37, 4, 3, 128, 7, "f32", "f32", 2),    # fp32 coefficients, 7x7: the 128-atom instantiation (one wavefront per SIMD)
     (19, 30, 2, 3, 72, 7, "f32", "f16", 1),     # ... 72 atoms, fp16 image
     (27, 21, 3, 1, 100, 7, "f32", "f32", 1),    # ... one channel
