@@ -315,8 +315,9 @@ def test_subnormal_only_coefficients_are_not_flushed(oracle, kernel):
 # ---- stage 1 alone, and the delta-atom identity -----------------------------------
 @pytest.mark.parametrize("scale", [2, 3, 4])
 @pytest.mark.parametrize("io", ["f32", "f16"])
-def test_bicubic_entry_point(oracle, scale, io):
-    wl = sr_synth.Workload("bic", 11, 2, 3, 37, 53, scale, 1, 3, "f32", io)
+@pytest.mark.parametrize("w", [53, 52, 1, 130])     # HR widths with and without whole groups of four pixels
+def test_bicubic_entry_point(oracle, scale, io, w):
+    wl = sr_synth.Workload("bic", 11, 2, 3, 37, w, scale, 1, 3, "f32", io)
     lr = sr_synth.make_lr(wl, DEV)
     out = torch.full((wl.n, wl.c, wl.H, wl.W), float("nan"), device=DEV, dtype=torch.float32)
     sr.sr_bicubic_upsample(lr, scale, wl.c, out)
@@ -324,11 +325,21 @@ def test_bicubic_entry_point(oracle, scale, io):
     ref = oracle.bicubic(lr.cpu().numpy(), scale)
     got = out.cpu().numpy().astype(np.float64)
     assert np.all(np.abs(got - ref) <= 1e-5 * np.maximum(1.0, np.abs(ref)))
+    # an output that starts 4 bytes off a 16-byte boundary: same values
+    buf = torch.full((out.numel() + 1,), float("nan"), device=DEV, dtype=torch.float32)
+    shifted = buf[1:].view(out.shape)
+    sr.sr_bicubic_upsample(lr, scale, wl.c, shifted)
+    torch.cuda.synchronize()
+    assert torch.equal(shifted, out) and torch.isnan(buf[0])
     if io == "f16":
         out16 = torch.empty_like(out, dtype=torch.float16)
         sr.sr_bicubic_upsample(lr, scale, wl.c, out16)
         torch.cuda.synchronize()
         assert torch.equal(out16, out.to(torch.float16))
+        buf16 = torch.zeros((out.numel() + 1,), device=DEV, dtype=torch.float16)
+        sr.sr_bicubic_upsample(lr, scale, wl.c, buf16[1:].view(out.shape))
+        torch.cuda.synchronize()
+        assert torch.equal(buf16[1:].view(out.shape), out16) and float(buf16[0]) == 0.0
 
 
 @pytest.mark.parametrize("kernel", KERNELS)
