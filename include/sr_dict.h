@@ -132,13 +132,15 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
  * kernel choice; `opts` == NULL means SR_KERNEL_AUTO.  The matrix-core kernel
  * qualifies when C is 1 or 3, coeff->data and out->data are 16-byte aligned,
  * the tensors are small enough for 32-bit byte offsets (L*H*W*sizeof(coeff)
- * < 2^32, N*C*H*W < 2^30) and
- *   f16 coefficients: k = 3 or 5 with at most 72 folded atoms and HR width % 4 == 0,
- *                     or k = 7 with at most 128 atoms and HR width % 2 == 0;
+ * < 2^32, N*C*H*W < 2^30), the HR width is a whole number of pixel groups (4
+ * pixels; 2 for f32 coefficients and for f16 coefficients with k = 7) or at
+ * least 128, and
+ *   f16 coefficients: k = 3 or 5 with at most 72 folded atoms, or k = 7 with at
+ *                     most 128;
  *   f32 coefficients: k = 3 or 5 with at most 72 folded atoms, or k = 7 with 17 to
- *                     128 folded atoms; HR width % 2 == 0;
- *   f8  coefficients: k = 3 or 5 with at most 72 folded atoms, or k = 7 with 17 to
- *                     128 folded atoms; HR width % 4 == 0 and lr->data 4-byte aligned.
+ *                     128;
+ *   f8  coefficients: as f32, and lr->data 4-byte aligned with an even number of
+ *                     elements if the image is f16.
  * Every other supported case runs on the generic kernel.
  */
 int sr_dict_assemble_ex(const sr_tensor* lr, const sr_tensor* coeff, const sr_tensor* dict,

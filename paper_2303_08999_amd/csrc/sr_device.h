@@ -24,6 +24,7 @@ struct AssembleArgs {
     const float* dict;    // [L][k][k]
     void*        out;     // [N][C][H][W]
     int N, C, h, w, H, W, s, L;
+    int xlast;            // matrix-core kernel: first column of the last tile column (set at launch)
     int n_fold;           // atoms folded: L (dense) or n_kept
     int io_f16;           // lr and out are fp16 (else fp32)
     int coeff_dtype;      // sr_dtype of the stored coefficients

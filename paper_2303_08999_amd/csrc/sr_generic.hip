@@ -45,12 +45,22 @@ __global__ __launch_bounds__(GNT) void k_assemble_generic(const AssembleArgs a) 
     for (int t = 0; t < KK; ++t) F[t] = 0.0f;
     if (valid) {
         const TC* cbase = (const TC*)a.coeff + (size_t)n * a.L * plane + (size_t)Y * a.W + X;
-        for (int i = 0; i < a.n_fold; ++i) {
-            const int l = a.kept[i];
-            const float phi = ld_as_float(cbase, (size_t)l * plane) * a.gamma[i];
-            const float* d = a.dict + (size_t)l * KK;   // wave-uniform: scalar loads
+        // eight atoms at a time: their coefficient loads are in flight together
+        constexpr int NB = 8;
+        for (int i0 = 0; i0 < a.n_fold; i0 += NB) {
+            float phi[NB];
 #pragma unroll
-            for (int t = 0; t < KK; ++t) F[t] = fmaf(phi, d[t], F[t]);
+            for (int b = 0; b < NB; ++b) {
+                const int i = i0 + b < a.n_fold ? i0 + b : a.n_fold - 1;      // past the end: re-read, unused
+                phi[b] = ld_as_float(cbase, (size_t)a.kept[i] * plane) * a.gamma[i];
+            }
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+                if (i0 + b < a.n_fold) {                    // wave-uniform
+                    const float* d = a.dict + (size_t)a.kept[i0 + b] * KK;   // wave-uniform: scalar loads
+#pragma unroll
+                    for (int t = 0; t < KK; ++t) F[t] = fmaf(phi[b], d[t], F[t]);
+                }
         }
     }
 
@@ -139,7 +149,8 @@ __global__ __launch_bounds__(256) void k_bicubic(const BicubicArgs a) {
 }
 
 template <typename TC, typename TIO>
-static hipError_t launch_generic_k(const AssembleArgs& a, int k, dim3 grid, hipStream_t st) {
+static hipError_t launch_generic_k(const AssembleArgs& a, int k, hipStream_t st) {
+    const dim3 grid((a.W + GTW - 1) / GTW, (a.H + GTH - 1) / GTH, a.N);
     switch (k) {
     case 3: hipLaunchKernelGGL((k_assemble_generic<TC, TIO, 3>), grid, dim3(GNT), 0, st, a); break;
     case 5: hipLaunchKernelGGL((k_assemble_generic<TC, TIO, 5>), grid, dim3(GNT), 0, st, a); break;
@@ -150,15 +161,11 @@ static hipError_t launch_generic_k(const AssembleArgs& a, int k, dim3 grid, hipS
 }
 
 hipError_t launch_generic(const AssembleArgs& a, int k, bool io_f16, hipStream_t st) {
-    const dim3 grid((a.W + GTW - 1) / GTW, (a.H + GTH - 1) / GTH, a.N);
     if (a.coeff_dtype == SR_F16)
-        return io_f16 ? launch_generic_k<__half, __half>(a, k, grid, st)
-                      : launch_generic_k<__half, float>(a, k, grid, st);
+        return io_f16 ? launch_generic_k<__half, __half>(a, k, st) : launch_generic_k<__half, float>(a, k, st);
     if (a.coeff_dtype == SR_F8E4M3)
-        return io_f16 ? launch_generic_k<f8e4m3, __half>(a, k, grid, st)
-                      : launch_generic_k<f8e4m3, float>(a, k, grid, st);
-    return io_f16 ? launch_generic_k<float, __half>(a, k, grid, st)
-                  : launch_generic_k<float, float>(a, k, grid, st);
+        return io_f16 ? launch_generic_k<f8e4m3, __half>(a, k, st) : launch_generic_k<f8e4m3, float>(a, k, st);
+    return io_f16 ? launch_generic_k<float, __half>(a, k, st) : launch_generic_k<float, float>(a, k, st);
 }
 
 hipError_t launch_bicubic(const BicubicArgs& a, bool in_f16, bool out_f16, hipStream_t st) {

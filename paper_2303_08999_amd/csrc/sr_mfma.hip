@@ -51,16 +51,25 @@ int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
 
 }  // namespace
 
+// pixels a lane loads with one vector load (its pixel group)
+static int pixel_group(int k, int coeff_dtype) {
+    return coeff_dtype == SR_F8E4M3 ? 4 : ((k != 7 && coeff_dtype != SR_F32) ? 4 : 2);
+}
+
 bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
     if ((k != 3 && k != 5 && k != 7) || (a.C != 1 && a.C != 3)) return false;
-    // a lane loads PX consecutive pixels of a row with one load and stores PX/2
-    // results per channel: rows must keep that alignment
-    const int px = coeff_dtype == SR_F8E4M3 ? 4 : ((k != 7 && coeff_dtype != SR_F32) ? 4 : 2);
+    // A lane loads one pixel group of a row and stores half a group per channel.  Rows
+    // need not keep the groups' alignment (gfx950 global loads and stores take any
+    // element-aligned address); a width that is not a whole number of groups needs
+    // at least one full tile (128 columns), see tile_x0 in the kernel.
     const unsigned long long cb = coeff_dtype == SR_F32 ? 4ull : (coeff_dtype == SR_F16 ? 2ull : 1ull);
-    if (a.W % px != 0 || a.W < px || a.H < 1) return false;
+    const int px = pixel_group(k, coeff_dtype);
+    if (a.W < px || a.H < 1 || (a.W % px != 0 && a.W < 128)) return false;
     if (((uintptr_t)a.coeff % 16) != 0 || ((uintptr_t)a.out % 16) != 0) return false;
-    // the fp8 instantiations read the LR image as aligned 32-bit words
-    if (coeff_dtype == SR_F8E4M3 && ((uintptr_t)a.lr % 4) != 0) return false;
+    // the fp8 instantiations read the LR image as aligned 32-bit words: the image must start on one and,
+    // when it is fp16, end on one
+    if (coeff_dtype == SR_F8E4M3 &&
+        (((uintptr_t)a.lr % 4) != 0 || (a.io_f16 && (((unsigned long long)a.N * a.C * a.h * a.w) & 1ull)))) return false;
     if ((unsigned long long)a.L * a.H * a.W * cb >= (1ull << 32)) return false;           // 32-bit plane offsets
     if ((unsigned long long)a.N * a.C * a.H * a.W * 4ull >= (1ull << 32)) return false;   // 32-bit image offsets
     if (np8_for(k, a.C, a.n_fold, coeff_dtype) == 0) return false;

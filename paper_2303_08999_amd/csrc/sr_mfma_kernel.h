@@ -165,6 +165,11 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     const int t_first = (int)(blockIdx.x % groups) * share + (int)(blockIdx.x / groups);
     const int t_end = min(ntiles, ((int)(blockIdx.x % groups) + 1) * share);
     if (t_first >= t_end) return;                                  // whole workgroup: no tile
+    // First column of a tile.  When the image width is not a whole number of pixel
+    // groups the last tile column is moved left to end at the image edge (a.xlast =
+    // W - TW): it recomputes some pixels of its neighbour (same values, written twice)
+    // and no lane ever holds a group that sticks out of its row.
+    auto tile_x0 = [&](int tx) { return tx == tiles_x - 1 ? a.xlast : tx * F::TW; };
 
     // ---- once per workgroup: weight, plane-offset and dictionary operand tables ---
     const unsigned plane_b = (unsigned)a.H * (unsigned)a.W * (unsigned)F::CB;   // bytes per coefficient plane
@@ -268,7 +273,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     static_assert(!LRBF || F::NLRP * F::NXC <= 32, "one parity bit per footprint slot");
     const unsigned lr_sh = a.io_f16 ? 1u : 2u;          // log2 of the element size
     auto load_lr = [&](const TilePos tp, int lane, unsigned (&lrv)[F::NLRP][F::NXC], unsigned& par) {
-        const TileOrigin o = tile_origin(tp.ty * F::TH, tp.tx * F::TW, F::R, UH, UW, a.H, a.W, a.s);
+        const TileOrigin o = tile_origin(tp.ty * F::TH, tile_x0(tp.tx), F::R, UH, UW, a.H, a.W, a.s);
         if constexpr (LRBF) {
             unsigned xcol[F::NXC];
 #pragma unroll
@@ -320,7 +325,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 
     // coefficient base of a tile for this lane: image base (scalar) + pixel offset
     auto phi_base = [&](const TilePos tp, int unit, int jr, int jc, unsigned& pix_off) -> const char* {
-        const int y = tp.ty * F::TH + (unit * NW + wave) * WR + jr, x = tp.tx * F::TW + PX * jc;
+        const int y = tp.ty * F::TH + (unit * NW + wave) * WR + jr, x = tile_x0(tp.tx) + PX * jc;
         const int yc = y < a.H ? y : a.H - 1, xc = x < a.W ? x : a.W - PX;   // out-of-image lanes re-read
         pix_off = ((unsigned)yc * (unsigned)a.W + (unsigned)xc) * (unsigned)F::CB;   // a valid address; never stored
         return (const char*)a.coeff + (size_t)tp.n * a.L * (size_t)plane_b;
@@ -347,7 +352,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     // (a) tap tables of a tile and its LR footprint, registers -> LDS
     auto stage1_setup = [&](const TilePos tp, int tid) {
         const int lane = tid & 63;
-        const int Y0 = tp.ty * F::TH, X0 = tp.tx * F::TW;
+        const int Y0 = tp.ty * F::TH, X0 = tile_x0(tp.tx);
         const TileOrigin o = tile_origin(Y0, X0, F::R, UH, UW, a.H, a.W, a.s);
         if (tid < UW) {
             int m;
@@ -382,7 +387,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     //     issued together, so that LDS latency is paid once per batch and not twice
     //     per element.  Loads are clamped into range; only the store is guarded.
     auto stage1_vertical = [&](const TilePos tp, int tid) {
-        const TileOrigin o = tile_origin(tp.ty * F::TH, tp.tx * F::TW, F::R, UH, UW, a.H, a.W, a.s);
+        const TileOrigin o = tile_origin(tp.ty * F::TH, tile_x0(tp.tx), F::R, UH, UW, a.H, a.W, a.s);
         const int sh = o.nlx <= 32 ? 5 : (o.nlx <= 64 ? 6 : 7);
         const int total = (C * UH) << sh;
         const int rx = tid & ((1 << sh) - 1);
@@ -451,7 +456,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         asm volatile("" : "+v"(tid));
         const int lane = tid & 63;
         const int hf = lane >> 5, j = lane & 31, jr = j / F::WC, jc = j % F::WC;
-        const int Y0 = cur.ty * F::TH, X0 = cur.tx * F::TW;
+        const int Y0 = cur.ty * F::TH, X0 = tile_x0(cur.tx);
         const bool more_tiles = t + G < t_end;
         const TilePos nxt = more_tiles ? advance(cur) : cur;
 
@@ -639,10 +644,16 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 // Host side: launch of one instantiation on a persistent grid.
 // ---------------------------------------------------------------------------
 template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT = CT_F16, int SMIN = 2>
-hipError_t launch_one(const AssembleArgs& a, hipStream_t st) {
+hipError_t launch_one(const AssembleArgs& a0, hipStream_t st) {
     using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN>;
-    if (a.s < SMIN) return hipErrorInvalidValue;        // its LDS footprint buffers would be too small
+    if (a0.s < SMIN) return hipErrorInvalidValue;       // its LDS footprint buffers would be too small
+    AssembleArgs a = a0;
     const int tiles_x = (a.W + F::TW - 1) / F::TW, tiles_y = (a.H + F::TH - 1) / F::TH;
+    a.xlast = (tiles_x - 1) * F::TW;
+    if (a.W % PX != 0) {                                // ragged rows: the last tile column ends at the image edge
+        if (a.W < F::TW) return hipErrorInvalidValue;
+        a.xlast = a.W - F::TW;
+    }
     const long long nt = (long long)tiles_x * tiles_y * a.N;
     if (nt > 0x7fffffffLL) return hipErrorInvalidValue;
     // as many workgroups as stay resident (WPE wavefronts per SIMD)

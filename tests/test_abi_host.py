@@ -78,7 +78,9 @@ def test_plan_accepts_a_good_case(lib):
     assert plan(*case(cd=sr.SR_F32, w=15, s=2), s=2) == sr.SR_KERNEL_MFMA   # HR width 30: even is enough
     assert plan(*case(k=3), k=3) == sr.SR_KERNEL_MFMA
     assert plan(*case(k=3, C=2), k=3, C=2) == sr.SR_KERNEL_GENERIC          # one or three channels only
-    assert plan(*case(w=15, s=3), s=3) == sr.SR_KERNEL_GENERIC   # HR width 45: not a multiple of 4
+    assert plan(*case(w=15, s=3), s=3) == sr.SR_KERNEL_GENERIC   # HR width 45: not whole groups of four pixels and under 128
+    assert plan(*case(w=43, s=3), s=3) == sr.SR_KERNEL_MFMA      # HR width 129: the last tile column ends at the image edge
+    assert plan(*case(w=1, s=3), s=3) == sr.SR_KERNEL_GENERIC    # HR width 3: not even one group of four pixels
     assert plan(*case(w=15), opts=sr.make_options(sr.SR_KERNEL_MFMA)) == sr.SR_KERNEL_MFMA   # width 60
     assert plan(*case(L=73), L=73) == sr.SR_KERNEL_GENERIC       # more atoms than the 5x5 kernel holds
     assert plan(*case(L=128, k=7), L=128, k=7) == sr.SR_KERNEL_MFMA
@@ -197,8 +199,14 @@ def test_e4m3_coefficients_are_a_coefficient_format_only(lib):
     assert plan(lr, coeff, d, out) == sr.SR_KERNEL_MFMA              # 5x5, 72 atoms, width % 4 == 0
     lr, coeff, d, out = case(cd=F8, w=15)                             # HR width 60 is fine, 4-byte loads
     assert plan(lr, coeff, d, out) == sr.SR_KERNEL_MFMA
-    lr, coeff, d, out = case(cd=F8, s=2, w=15)                        # HR width 30: not a multiple of 4
+    lr, coeff, d, out = case(cd=F8, s=2, w=15)                        # HR width 30: not whole groups, under 128
     assert plan(lr, coeff, d, out, s=2) == sr.SR_KERNEL_GENERIC
+    lr, coeff, d, out = case(cd=F8, s=2, w=75)                        # HR width 150
+    assert plan(lr, coeff, d, out, s=2) == sr.SR_KERNEL_MFMA
+    lr, coeff, d, out = case(cd=F8, io=sr.SR_F16, C=1, h=3, w=5)      # fp16 image with an odd element count
+    assert plan(lr, coeff, d, out, C=1) == sr.SR_KERNEL_GENERIC
+    lr, coeff, d, out = case(cd=F8, io=sr.SR_F16, C=1, h=3, w=6)
+    assert plan(lr, coeff, d, out, C=1) == sr.SR_KERNEL_MFMA
     lr, coeff, d, out = case(cd=F8, k=7, L=100)
     assert plan(lr, coeff, d, out, L=100, k=7) == sr.SR_KERNEL_MFMA          # 7x7: 17 to 128 atoms
     lr, coeff, d, out = case(cd=F8, k=7, L=200)

@@ -202,11 +202,11 @@ RAGGED = [
     (16, 96, 4, 3, 8, 5, "f16", "f32", 1),
     (16, 48, 4, 3, 13, 7, "f16", "f16", 1),
     (23, 27, 4, 3, 72, 5, "f16", "f32", 1),     # HR width 108: multiple of 4, not of 8
-    (19, 31, 2, 3, 72, 5, "f16", "f32", 1),     # HR width 62: matrix-core kernel declines (k = 5)
+    (19, 31, 2, 3, 72, 5, "f16", "f32", 1),     # HR width 62: not whole groups of four and under 128: generic kernel only
     (19, 31, 2, 3, 100, 7, "f16", "f16", 2),    # HR width 62: fine for 7x7 (2 pixels per lane)
     (14, 29, 4, 1, 30, 5, "f16", "f16", 1),     # HR width 116, one channel, fp16 output
     (25, 33, 2, 3, 72, 5, "f32", "f32", 2),     # fp32 coefficients on the fp32 matrix-core path, HR width 66
-    (20, 27, 3, 1, 41, 5, "f32", "f16", 1),     # ... HR width 81: odd, generic kernel only
+    (20, 27, 3, 1, 41, 5, "f32", "f16", 1),     # ... HR width 81: odd and under 128: generic kernel only
     (18, 26, 3, 1, 41, 5, "f32", "f16", 1),     # ... HR width 78, one channel, fp16 image
     (31, 45, 4, 3, 9, 5, "f32", "f32", 1),      # ... few atoms
     (6, 8, 2, 16, 9, 3, "f16", "f32", 1),       # the largest channel count accepted
@@ -241,6 +241,15 @@ RAGGED = [
     (24, 36, 3, 1, 20, 3, "f8", "f16", 1),      # ... HR width 108
     (21, 30, 4, 3, 8, 3, "f32", "f32", 1),      # ... fp32 coefficients, 8-atom instantiation
     (21, 30, 4, 1, 5, 3, "f8", "f32", 1),       # ... 8-bit coefficients, 8-atom instantiation
+    (41, 67, 3, 3, 72, 5, "f16", "f32", 2),     # HR width 201: rows start at odd element offsets, last tile column moved left
+    (40, 43, 3, 3, 72, 5, "f16", "f16", 1),     # HR width 129: one column more than a tile, fp16 image
+    (33, 49, 3, 3, 128, 7, "f16", "f16", 1),    # HR width 147, 7x7 (groups of two pixels)
+    (29, 45, 3, 1, 72, 5, "f32", "f32", 1),     # HR width 135, fp32 coefficients
+    (37, 53, 3, 3, 72, 5, "f8", "f32", 1),      # HR width 159, 8-bit coefficients: rows at odd byte offsets
+    (18, 2, 3, 3, 72, 5, "f16", "f32", 1),      # HR width 6: generic kernel only
+    (20, 65, 2, 3, 8, 5, "f16", "f32", 1),      # HR width 130, 8 atoms (tile 64 wide)
+    (20, 64, 2, 3, 72, 5, "f16", "f32", 1),     # HR width 128: exactly one tile
+    (22, 43, 3, 3, 72, 3, "f16", "f32", 2),     # HR width 129, 3x3
 ]
 
 
@@ -455,8 +464,8 @@ def test_tile_sweep_returns_a_valid_shape():
     assert [t for t, _ in res] == list(range(6))
     assert all(ms > 0 for _, ms in res)
     assert tune.best_tile(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, out, reps=3) in range(6)
-    # odd HR width: the matrix-core kernel does not apply, nothing to sweep
-    wl32 = sr_synth.scaled(sr_synth.WORKLOADS["tiny"], w=21, scale=3)
+    # two channels: the matrix-core kernel does not apply, nothing to sweep
+    wl32 = sr_synth.scaled(sr_synth.WORKLOADS["tiny"], c=2)
     i32 = sr_synth.make_inputs(wl32, DEV)
-    o32 = torch.empty((1, 1, wl32.H, wl32.W), device=DEV)
+    o32 = torch.empty((1, wl32.c, wl32.H, wl32.W), device=DEV)
     assert tune.sweep_tiles(i32["lr"], i32["coeff"], i32["dict"], wl32.L, wl32.k, wl32.scale, wl32.c, o32) == []

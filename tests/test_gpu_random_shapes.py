@@ -36,8 +36,6 @@ def draw(rng, index, max_h, max_w):
     io = str(rng.choice(["f32", "f16"]))
     L = int(rng.integers(1, 73)) if k != 7 else int(rng.choice([16, 72, 128, int(rng.integers(1, 129))]))
     h, w = int(rng.integers(1, max_h)), int(rng.integers(1, max_w))
-    if cd == "f8" and rng.random() < 0.5:
-        w = 4 * max(1, w // 4)                     # the matrix-core kernel takes 8-bit planes with W % 4 == 0
     wl = sr_synth.Workload("random", 100 + index, N, C, h, w, s, L, k, cd, io, 0.0, 1.5)
     kept = gamma = None
     if rng.random() < 0.4:
