@@ -65,7 +65,6 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
     const unsigned long long cb = coeff_dtype == SR_F32 ? 4ull : (coeff_dtype == SR_F16 ? 2ull : 1ull);
     const int px = pixel_group(k, coeff_dtype);
     if (a.W < px || a.H < 1 || (a.W % px != 0 && a.W < 128)) return false;
-    if (((uintptr_t)a.coeff % 16) != 0 || ((uintptr_t)a.out % 16) != 0) return false;
     // the fp8 instantiations read the LR image as aligned 32-bit words: the image must start on one and,
     // when it is fp16, end on one
     if (coeff_dtype == SR_F8E4M3 &&

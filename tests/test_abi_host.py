@@ -212,7 +212,7 @@ def test_e4m3_coefficients_are_a_coefficient_format_only(lib):
     lr, coeff, d, out = case(cd=F8, k=7, L=200)
     assert plan(lr, coeff, d, out, L=200, k=7) == sr.SR_KERNEL_GENERIC
     coeff_odd = T(0x11000001, F8, 1, 72, 32, 64)                      # one-byte elements: any address
-    assert plan(lr, coeff_odd, T(0x18000000, sr.SR_F32, 1, 72, 5, 5), out) == sr.SR_KERNEL_GENERIC
+    assert plan(lr, coeff_odd, T(0x18000000, sr.SR_F32, 1, 72, 5, 5), out) == sr.SR_KERNEL_MFMA
     lr8, coeff, d, out = case(io=F8)
     assert plan(lr8, coeff, d, out) == -3                             # images cannot be E4M3
     lr, coeff, d, out = case()

@@ -321,6 +321,29 @@ def test_subnormal_only_coefficients_are_not_flushed(oracle, kernel):
     assert worst < 2e-3
 
 
+@pytest.mark.parametrize("cd,io", [("f16", "f32"), ("f16", "f16"), ("f32", "f32"), ("f8", "f32")])
+def test_tensors_that_start_off_a_16_byte_boundary(oracle, cd, io):
+    """Coefficients and output that start one element into their buffers (a slice of a
+    larger allocation): the matrix-core kernel takes them, same values."""
+    wl = sr_synth.Workload("offset", 14, 1, 3, 30, 41, 4, 72, 5, cd, io, 0.0, 1.5)
+    inp = sr_synth.make_inputs(wl, DEV)
+    cbuf = torch.empty((inp["coeff"].numel() + 1,), device=DEV, dtype=inp["coeff"].dtype)
+    cview = cbuf[1:].view(inp["coeff"].shape)
+    cview.copy_(inp["coeff"])
+    obuf = torch.full((wl.n * wl.c * wl.H * wl.W + 1,), float("nan"), device=DEV, dtype=inp["lr"].dtype)
+    oview = obuf[1:].view(wl.n, wl.c, wl.H, wl.W)
+    opts = sr.make_options(MFMA, 0)
+    assert sr.sr_dict_assemble_plan(inp["lr"], cview, inp["dict"], wl.L, wl.k, wl.scale, wl.c, oview, opts=opts) == MFMA
+    sr.sr_dict_assemble_ex(inp["lr"], cview, inp["dict"], wl.L, wl.k, wl.scale, wl.c, oview, opts=opts)
+    torch.cuda.synchronize()
+    assert torch.isnan(obuf[0])
+    hi = host(inp)
+    ref = oracle.dict_assemble(hi["lr"], hi["coeff"], hi["dict"], wl.scale)
+    worst, tol, ok = tolerance_ok(oview.float().cpu().numpy(), ref, cd in ("f16", "f8"), io == "f16")
+    assert ok, f"worst error {worst:.3e} exceeds {tol:.0e}"
+    assert torch.equal(oview, run_gpu(inp, wl, MFMA))
+
+
 # ---- stage 1 alone, and the delta-atom identity -----------------------------------
 @pytest.mark.parametrize("scale", [2, 3, 4])
 @pytest.mark.parametrize("io", ["f32", "f16"])
