@@ -130,7 +130,7 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
 /*
  * As sr_dict_assemble_selective (kept == NULL means dense), with an explicit
  * kernel choice; `opts` == NULL means SR_KERNEL_AUTO.  The matrix-core kernel
- * qualifies when C is 1 or 3,
+ * qualifies when C is 1 or 3 (or 2 or 4 with f16 coefficients and k = 5),
  * the tensors are small enough for 32-bit byte offsets (L*H*W*sizeof(coeff)
  * < 2^32, N*C*H*W < 2^30), the HR width is a whole number of pixel groups (4
  * pixels; 2 for f32 coefficients and for f16 coefficients with k = 7) or at

@@ -22,6 +22,8 @@ constexpr int N_TILE_SHAPES = 6;
 // only: padding atoms meet zero dictionary rows and re-read a cached plane.
 int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
     const int need = (n_fold + 7) / 8;
+    if (channels == 2 || channels == 4)                                 // 5x5, fp16 coefficients: 32 and 72 atoms
+        return (k == 5 && coeff_dtype == SR_F16 && need <= 9) ? (need <= 4 ? 4 : 9) : 0;
     if (k == 3) {                                                       // 3x3: up to 72 atoms
         if (need > 9) return 0;
         return need <= 1 ? 1 : (need <= 4 ? 4 : 9);
@@ -57,7 +59,7 @@ static int pixel_group(int k, int coeff_dtype) {
 }
 
 bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
-    if ((k != 3 && k != 5 && k != 7) || (a.C != 1 && a.C != 3)) return false;
+    if ((k != 3 && k != 5 && k != 7) || a.C < 1 || a.C > 4) return false;
     // A lane loads one pixel group of a row and stores half a group per channel.  Rows
     // need not keep the groups' alignment (gfx950 global loads and stores take any
     // element-aligned address); a width that is not a whole number of groups needs

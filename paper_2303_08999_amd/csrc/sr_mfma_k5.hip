@@ -38,6 +38,22 @@ hipError_t launch_mfma_k5(const AssembleArgs& a, int np8, int shape, hipStream_t
         default: return hipErrorInvalidValue;
         }
     }
+    // Two and four channels (fp16 coefficients only): 32 and 72 atoms.  Four channels
+    // fill the LDS tile and the registers faster: tile 128 x 8.
+    if (a.C == 2) {
+        switch (np8) {
+        case 4:  return launch_one<5, 2, 4, 4, 1, 4, 4, 2>(a, st);
+        case 9:  return launch_one<5, 2, 9, 4, 1, 4, 4, 2>(a, st);
+        default: return hipErrorInvalidValue;
+        }
+    }
+    if (a.C == 4) {
+        switch (np8) {
+        case 4:  return launch_one<5, 4, 4, 4, 1, 4, 2, 2>(a, st);
+        case 9:  return launch_one<5, 4, 9, 4, 1, 4, 2, 2>(a, st);
+        default: return hipErrorInvalidValue;
+        }
+    }
     switch (np8) {
     case 1:  return launch_one<5, 1, 1, 4, 1, 4, 4, 2>(a, st);
     case 4:  return launch_one<5, 1, 4, 4, 1, 4, 4, 2>(a, st);

@@ -77,7 +77,10 @@ def test_plan_accepts_a_good_case(lib):
     assert plan(*case(cd=sr.SR_F8E4M3, k=7, L=16), k=7, L=16) == sr.SR_KERNEL_GENERIC   # short 7x7 lists stay generic
     assert plan(*case(cd=sr.SR_F32, w=15, s=2), s=2) == sr.SR_KERNEL_MFMA   # HR width 30: even is enough
     assert plan(*case(k=3), k=3) == sr.SR_KERNEL_MFMA
-    assert plan(*case(k=3, C=2), k=3, C=2) == sr.SR_KERNEL_GENERIC          # one or three channels only
+    assert plan(*case(k=3, C=2), k=3, C=2) == sr.SR_KERNEL_GENERIC          # two and four channels: 5x5, fp16 coefficients only
+    assert plan(*case(C=4), C=4) == sr.SR_KERNEL_MFMA
+    assert plan(*case(C=2), C=2) == sr.SR_KERNEL_MFMA
+    assert plan(*case(C=5), C=5) == sr.SR_KERNEL_GENERIC
     assert plan(*case(w=15, s=3), s=3) == sr.SR_KERNEL_GENERIC   # HR width 45: not whole groups of four pixels and under 128
     assert plan(*case(w=43, s=3), s=3) == sr.SR_KERNEL_MFMA      # HR width 129: the last tile column ends at the image edge
     assert plan(*case(w=1, s=3), s=3) == sr.SR_KERNEL_GENERIC    # HR width 3: not even one group of four pixels
@@ -129,7 +132,7 @@ def test_unsupported(lib):
     o.reserved[2] = 1
     assert plan(*case(), opts=o) == -3
     assert plan(*case(cd=sr.SR_F8E4M3, k=7, L=16), k=7, L=16, opts=sr.make_options(sr.SR_KERNEL_MFMA)) == -3
-    assert plan(*case(C=2), C=2, opts=sr.make_options(sr.SR_KERNEL_MFMA)) == -3
+    assert plan(*case(C=5), C=5, opts=sr.make_options(sr.SR_KERNEL_MFMA)) == -3
 
 
 def test_alias_and_alignment(lib):

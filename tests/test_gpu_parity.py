@@ -250,6 +250,11 @@ RAGGED = [
     (20, 65, 2, 3, 8, 5, "f16", "f32", 1),      # HR width 130, 8 atoms (tile 64 wide)
     (20, 64, 2, 3, 72, 5, "f16", "f32", 1),     # HR width 128: exactly one tile
     (22, 43, 3, 3, 72, 3, "f16", "f32", 2),     # HR width 129, 3x3
+    (33, 47, 4, 4, 72, 5, "f16", "f32", 1),     # four channels on the matrix-core path (tile 128 x 8)
+    (27, 45, 3, 4, 30, 5, "f16", "f16", 2),     # ... 32-atom instantiation, fp16 image, ragged width 135
+    (29, 38, 2, 2, 72, 5, "f16", "f32", 1),     # two channels
+    (31, 40, 4, 2, 17, 5, "f16", "f16", 1),     # ... 32-atom instantiation
+    (20, 30, 4, 4, 72, 5, "f32", "f32", 1),     # four channels, fp32 coefficients: generic kernel only
 ]
 
 
@@ -487,7 +492,7 @@ def test_tile_sweep_returns_a_valid_shape():
     assert [t for t, _ in res] == list(range(6))
     assert all(ms > 0 for _, ms in res)
     assert tune.best_tile(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, out, reps=3) in range(6)
-    # two channels: the matrix-core kernel does not apply, nothing to sweep
+    # two channels, fp32 coefficients: the matrix-core kernel does not apply, nothing to sweep
     wl32 = sr_synth.scaled(sr_synth.WORKLOADS["tiny"], c=2)
     i32 = sr_synth.make_inputs(wl32, DEV)
     o32 = torch.empty((1, wl32.c, wl32.H, wl32.W), device=DEV)

@@ -30,7 +30,7 @@ def _need_gpu():
 def draw(rng, index, max_h, max_w):
     k = int(rng.choice([3, 5, 5, 5, 7]))
     s = int(rng.choice([2, 3, 4]))
-    C = int(rng.choice([1, 3, 3, 4]))
+    C = int(rng.choice([1, 2, 3, 3, 4]))
     N = int(rng.choice([1, 1, 2, 3, 9]))
     cd = str(rng.choice(["f16", "f16", "f32", "f8"]))
     io = str(rng.choice(["f32", "f16"]))
