@@ -1,6 +1,6 @@
 // Matrix-core path, host side: which kernel instantiation serves a call.
 // The kernel itself is in sr_mfma_kernel.h; its instantiations are compiled in
-// sr_mfma_k3.hip, sr_mfma_k5*.hip and sr_mfma_k7.hip.
+// sr_mfma_k3.hip, sr_mfma_k5*.hip and sr_mfma_k7*.hip.
 #include "sr_launch.h"
 
 namespace srd {
