@@ -31,6 +31,8 @@ hipError_t launch_mfma_k5(const AssembleArgs& a, int np8, int shape, hipStream_t
             case 4:  return launch_one<5, 3, 9, 4, 1, 4, 2, 2>(a, st);    // 128 x 8,  2 units
             case 5:  return launch_one<5, 3, 9, 4, 2, 4, 4, 2>(a, st);    //  64 x 32, 4 units
             default:
+                // a frame of a few tiles: 128 x 4 tiles put more CUs to work
+                if ((long long)a.N * a.H * a.W <= 64LL * 128 * 16) return launch_one<5, 3, 9, 4, 1, 4, 1, 2>(a, st);
                 // x4: half the footprint in LDS leaves room for a 128 x 24 tile (6 units)
                 if (a.s == 4) return launch_one<5, 3, 9, 4, 1, 4, 6, 2, CT_F16, 4>(a, st);
                 return launch_one<5, 3, 9, 4, 1, 4, 4, 2>(a, st);    // 128 x 16, 4 units

@@ -4,8 +4,14 @@
 
 namespace srd {
 
+// A frame of a few tiles leaves most CUs idle and takes as long as one workgroup
+// needs for its tile: such frames go in 64 x 4 tiles (one unit per wavefront).
+static bool few_tiles(const AssembleArgs& a) { return (long long)a.N * a.H * a.W <= 64LL * 64 * 16; }
+
 // np8: capacity in groups of 8 folded atoms (kept lists read only their own planes)
 hipError_t launch_mfma_k5_f32(const AssembleArgs& a, int np8, hipStream_t st) {
+    if (np8 == 9 && few_tiles(a))
+        return a.C == 3 ? launch_one<5, 3, 9, 2, 1, 4, 1, 2, CT_F32>(a, st) : launch_one<5, 1, 9, 2, 1, 4, 1, 2, CT_F32>(a, st);
     if (a.C == 3) {
         switch (np8) {
         case 1:  return launch_one<5, 3, 1, 2, 1, 4, 4, 2, CT_F32>(a, st);
