@@ -30,12 +30,20 @@ hipError_t launch_mfma_k5(const AssembleArgs& a, int np8, int shape, hipStream_t
             case 3:  return launch_one<5, 3, 9, 4, 2, 4, 2, 2>(a, st);    //  64 x 16, 2 units per wavefront
             case 4:  return launch_one<5, 3, 9, 4, 1, 4, 2, 2>(a, st);    // 128 x 8,  2 units
             case 5:  return launch_one<5, 3, 9, 4, 2, 4, 4, 2>(a, st);    //  64 x 32, 4 units
-            default:
-                // a frame of a few tiles: 128 x 4 tiles put more CUs to work
-                if ((long long)a.N * a.H * a.W <= 64LL * 128 * 16) return launch_one<5, 3, 9, 4, 1, 4, 1, 2>(a, st);
-                // x4: half the footprint in LDS leaves room for a 128 x 24 tile (6 units)
-                if (a.s == 4) return launch_one<5, 3, 9, 4, 1, 4, 6, 2, CT_F16, 4>(a, st);
+            default: {
+                // Tile by frame size (measured, 0.26 to 8.3 Mpixel frames at every scale).
+                // Small frames: 128 x 4 tiles put more CUs to work (512 x 512: 37 -> 26 us).
+                const long long px = (long long)a.N * a.H * a.W;
+                if (px <= 400000) return launch_one<5, 3, 9, 4, 1, 4, 1, 2>(a, st);
+                // x4: half the footprint in LDS leaves room for a 128 x 24 tile (6 units); up to
+                // about 1080p its few hundred tiles fill the second round of the grid badly
+                // and 64 x 16 is 7-13 % faster
+                if (a.s == 4) {
+                    if (px <= 2600000) return launch_one<5, 3, 9, 4, 2, 4, 2, 2>(a, st);
+                    return launch_one<5, 3, 9, 4, 1, 4, 6, 2, CT_F16, 4>(a, st);
+                }
                 return launch_one<5, 3, 9, 4, 1, 4, 4, 2>(a, st);    // 128 x 16, 4 units
+            }
             }
         default: return hipErrorInvalidValue;
         }
