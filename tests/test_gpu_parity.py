@@ -266,6 +266,27 @@ def test_ragged_shapes(oracle, case, kernel):
     check_full(oracle, wl, kernel)
 
 
+# ---- frames large enough for the big default tiles, with ragged tails ------------
+# (the default tile grows with the frame: these sizes are past the thresholds)
+BIG_RAGGED = [
+    # (h, w, scale, C, L, k, coeff dtype, io dtype, N)
+    (331, 501, 4, 3, 72, 5, "f16", "f32", 1),   # 1324 x 2004 = 2.65 Mpixel: 128 x 24 tiles, 55 rows + 4, 15 columns + 84
+    (233, 267, 3, 3, 72, 5, "f16", "f32", 1),   # 699 x 801: 128 x 16 tiles at x3, odd width
+    (150, 170, 4, 3, 72, 5, "f16", "f16", 1),   # 600 x 680 = 0.41 Mpixel at x4: 64 x 16 tiles
+    (171, 151, 4, 3, 72, 5, "f8", "f32", 1),    # 684 x 604: 128 x 24 tiles, 8-bit coefficients
+    (200, 191, 4, 3, 72, 5, "f32", "f32", 1),   # 800 x 764 = 0.61 Mpixel: 64 x 32 tiles, fp32 coefficients
+    (181, 240, 4, 3, 8, 5, "f16", "f32", 1),    # 8 atoms: 64 x 32 tiles at three workgroups per CU
+    (121, 163, 4, 3, 128, 7, "f16", "f16", 2),  # 7x7: 64 x 24 tiles
+]
+
+
+@pytest.mark.parametrize("case", BIG_RAGGED, ids=lambda c: "h%dw%ds%dC%dL%dk%d%s%sN%d" % c)
+def test_big_default_tiles_with_ragged_tails(oracle, case):
+    h, w, s, C, L, k, cd, io, N = case
+    wl = sr_synth.Workload("bigragged", 8, N, C, h, w, s, L, k, cd, io, 0.0, 1.5)
+    check_full(oracle, wl, MFMA)
+
+
 # ---- dictionary-selective form -------------------------------------------------
 @pytest.mark.parametrize("kernel", KERNELS)
 def test_selective_kept_list_with_and_without_gamma(oracle, kernel):
