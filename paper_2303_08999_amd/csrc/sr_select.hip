@@ -3,16 +3,23 @@
 //
 // GPU part.  A workgroup takes runs of 64 samples (lattice pixels).  For one run and
 // one channel it first forms the responses r_{p,l} = Phi_{p,l} (D_l . B_p) of all
-// atoms (one thread per sample and quarter of the atoms; the dictionary row is
-// wave-uniform, so it comes through scalar loads) into an LDS tile [column][sample],
-// with the ground-truth pixel as one more column.  tile^T tile is a dense
-// contraction over the samples and runs on the matrix cores: the upper triangle is
-// cut into 16 x 16 blocks, dealt to the four wavefronts, and each block takes 16
-// v_mfma_f32_16x16x4_f32 steps per run (a lane reads four consecutive samples of its
-// column with one 16-byte LDS load and spends them on four steps; which sample goes
-// to which step does not matter to the sum as long as both operands agree).  Sums
-// are fp32 within a run and double across runs; each workgroup leaves its partial
-// sums in the caller's scratch and a second kernel adds them in a fixed order.
+// atoms into an LDS tile [column][sample], with the ground-truth pixel as one more
+// column.  tile^T tile is a dense contraction over the samples and runs on the
+// matrix cores: the upper triangle is cut into 16 x 16 blocks, dealt to four
+// wavefronts, and each block takes 16 v_mfma_f32_16x16x4_f32 steps per run (a lane
+// reads four consecutive samples of its column with one 16-byte LDS load and spends
+// them on four steps; which sample goes to which step does not matter to the sum as
+// long as both operands agree).  Sums are fp32 within a run and double across runs;
+// each workgroup leaves its partial sums in the caller's scratch and a second kernel
+// adds them in a fixed order.
+//
+// Two forms of the first kernel.  k_atom_gram_rows (lattice strides up to 4): runs
+// are segments of one lattice row, eight wavefronts per workgroup split into four
+// that form responses (their dot products on the matrix cores too) and four that
+// contract, all global loads coalesced and parked in LDS.  k_atom_gram (any stride):
+// runs are 64 consecutive samples in lattice order, one thread per sample gathers
+// its neighbourhood, the dictionary row comes through scalar loads, and the same
+// four wavefronts form the responses and contract them.
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 #include <math.h>
@@ -250,6 +257,359 @@ __global__ __launch_bounds__(NT, (N16 <= 5 && K <= 5) ? 2 : 1) void k_atom_gram(
         }
 }
 
+// ---------------------------------------------------------------------------
+// Second form of the kernel, for lattice strides up to 4 (every pixel down to every
+// fourth): one workgroup of eight wavefronts per CU.  Four wavefronts form the
+// responses of one (run, channel) while the other four contract the tile of the
+// one before; two LDS tiles, one barrier per iteration.  A run is 64 consecutive
+// lattice samples of ONE lattice row, so the k image rows it needs are contiguous
+// segments and every atom's 64 coefficients one or a few cache lines.
+//
+// The contracting wavefronts have matrix-core work for less than half of an
+// iteration, so they also do every global load: two iterations ahead of the
+// responses they fetch the row segments and the target pixels (coalesced), and once
+// per run the coefficients (one atom's 64 samples per load), and park them in LDS.
+// The response wavefronts touch LDS only.  Their dot products D_l . B_p are a
+// contraction too, (samples x taps) . (taps x atoms), and run on the matrix cores
+// with the dictionary as a register-resident operand: no per-atom scalar loads or
+// broadcasts, whose latency a single wavefront per SIMD cannot hide.
+// ---------------------------------------------------------------------------
+constexpr int NT2 = 512;         // four response + four contraction wavefronts
+constexpr int GRID2 = 256;       // one workgroup per CU (two where registers and LDS allow)
+constexpr int STMAX = 4;         // largest lattice stride whose row segments are staged
+
+// floats of dynamic LDS: tile[2], coefficients of a run [1 or 2], its targets [2], staged segments [2]
+constexpr size_t rows_lds_floats(int k, int n16, int channels) {
+    return (size_t)(2 + (channels == 1 ? 2 : 1)) * n16 * 16 * TSS + 2 * (size_t)channels * RUN +
+           2 * (((size_t)k * (63 * STMAX + k) + 3) & ~(size_t)3);
+}
+
+template <int K, typename TC, int N16>
+__global__ __launch_bounds__(NT2, (N16 <= 5 && K <= 5) ? 4 : 2) void k_atom_gram_rows(const GramArgs a) {
+    constexpr int KK = K * K, R = (K - 1) / 2;
+    constexpr int NTW = N16 == 2 ? 1 : (N16 == 5 ? 4 : 12);     // blocks per contracting wavefront
+    constexpr int NPW = N16 * 4;                      // atoms whose coefficients one contracting wavefront fetches
+    constexpr int TILE = N16 * 16 * TSS;
+    constexpr int PSZ = (K * (63 * STMAX + K) + 3) & ~3;   // staged row segments of one run and channel (whole 16 bytes)
+    constexpr int MM = (PSZ + 255) / 256;             // staged elements per thread
+    // Coefficients of a run, widened and masked, laid out like a tile.  With one channel a
+    // run lasts one iteration and the copy for the next run is written while this one is
+    // read: two copies.  Otherwise the last channel's iteration writes, the first reads.
+    const int phbuf = a.C == 1 ? 2 : 1;
+    extern __shared__ float lds[];                    // tile[2][TILE], phi[phbuf][TILE], target[2][C][RUN], stage[2][PSZ]
+    float* const PH = lds + 2 * TILE;
+    // The run's target pixels, every channel.  They are read in every iteration of the run,
+    // the last of which overlaps the parking of the next run's: always two copies.
+    float* const TGT = PH + phbuf * TILE;
+    float* const stage = TGT + 2 * a.C * RUN;
+
+    const int tid = threadIdx.x, si = tid & 63, c16 = tid & 15, kq = (tid >> 4) & 3;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), g = wave & 3;
+    const bool contracts = wave >= 4;
+
+    const size_t plane = (size_t)a.H * a.W;
+    const int WD = 63 * a.stride + K;                 // columns of a staged segment
+    const int nseg = (a.nx + RUN - 1) / RUN;          // runs per lattice row
+    const long long rpi = (long long)a.ny * nseg, nrun = rpi * a.N;
+    // iterations of this workgroup: its runs blockIdx.x, blockIdx.x + gridDim.x, ... times the channels
+    const long long my_runs = (long long)blockIdx.x < nrun ? (nrun - blockIdx.x + gridDim.x - 1) / gridDim.x : 0;
+    const long long n_it = my_runs * a.C;
+    if (n_it == 0) {
+        // nothing to add: the partial sums must still be defined
+        if (contracts) {
+#pragma unroll
+            for (int t = 0; t < NTW; ++t)
+                if (g + 4 * t < a.ntile) {
+                    double* dst = a.ws + ((size_t)blockIdx.x * a.ntile + (g + 4 * t)) * 256 + si * 4;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) dst[e] = 0.0;
+                }
+        }
+        return;
+    }
+
+    // A run: image, lattice row, 64-sample segment of that row.  This workgroup's
+    // runs are gridDim.x apart; the step is pre-split so that no division is left in the
+    // loop.  All of it is scalar.
+    struct Run { int n, iy, seg; };
+    const int G = gridDim.x;
+    const int step_n = (int)(G / rpi), step_r = (int)(G - step_n * rpi);
+    const int step_y = step_r / nseg, step_s = step_r - step_y * nseg;
+    auto advance = [&](Run r) {
+        r.seg += step_s;
+        if (r.seg >= nseg) { r.seg -= nseg; r.iy += 1; }
+        r.iy += step_y;
+        if (r.iy >= a.ny) { r.iy -= a.ny; r.n += 1; }
+        r.n += step_n;
+        return r;
+    };
+    const int t2 = tid & 255;                            // 0 .. 255 among the wavefronts of one kind
+    // staged elements of this thread: e = t2 + 256 m  <->  (row dy, column q) of the segment
+    int sdy[MM], sq[MM];
+#pragma unroll
+    for (int m = 0; m < MM; ++m) {
+        const int e = t2 + 256 * m;
+        sdy[m] = e / WD;
+        sq[m] = e - sdy[m] * WD;
+        if (sdy[m] >= K) sdy[m] = K - 1;                 // past K * WD: a valid address, not stored
+    }
+    Run run0;
+    {
+        run0.n = (int)(blockIdx.x / rpi);
+        const int rr = (int)(blockIdx.x - (long long)run0.n * rpi);
+        run0.iy = rr / nseg;
+        run0.seg = rr - run0.iy * nseg;
+    }
+    // this lane's sample of a run: pixel index within a plane (fewer than 2^30 pixels, checked
+    // on the host), and whether it exists (past the end of the row: clamped to the last one,
+    // zeroed where it is parked)
+    auto sample_of = [&](const Run& r, bool& ok) {
+        const int X = (r.seg * RUN + si) * a.stride, Xl = (a.nx - 1) * a.stride;
+        ok = X <= Xl;
+        return (unsigned)(r.iy * a.stride) * (unsigned)a.W + (unsigned)(ok ? X : Xl);
+    };
+
+    if (!contracts) {
+        // Response wavefront g takes samples 16 g .. 16 g + 15 of the run and all atoms.
+        // A operand: read from the staged segment; B operand: the dictionary, in
+        // registers for the whole kernel.  A lane ends up with four consecutive samples
+        // of one atom per 16-atom block, which it scales by the coefficients and writes
+        // to the tile with one 16-byte store.
+        constexpr int KS = (KK + 3) / 4;               // 4-tap steps of v_mfma_f32_16x16x4_f32
+        const int kq4 = 16 * g + 4 * kq;               // first of this lane's four samples
+        // lane (c16, kq) holds tap 4 ks + kq of atom 16 nb + c16
+        float Bd[N16][KS];
+#pragma unroll
+        for (int nb = 0; nb < N16; ++nb)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const int l = 16 * nb + c16, tap = 4 * ks + kq;
+                Bd[nb][ks] = (l < a.L && tap < KK) ? a.dict[(size_t)l * KK + tap] : 0.0f;
+            }
+        // offset of this lane's A operand within a staged segment: sample 16 g + c16, tap 4 ks + kq
+        int aoff[KS];
+        bool atap[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int tap = 4 * ks + kq;
+            atap[ks] = tap < KK;
+            const int tc = atap[ks] ? tap : 0, dy = tc / K, dx = tc - dy * K;
+            aoff[ks] = dy * WD + (16 * g + c16) * a.stride + dx;
+        }
+        const int tcol = a.L >> 4;                       // the block that holds column L (the target) ...
+        const bool holds_target = c16 == (a.L & 15);    // ... and the lanes that hold it there
+        // Staging: the segment's elements e = t2 + 256 m of this thread, requested a whole
+        // iteration before they are parked, which is an iteration before they are read.
+        struct Fetch { float sv[MM]; };
+        auto fetch = [&](const Run& r, int c, Fetch& f) {
+            const int Y = r.iy * a.stride, X0 = r.seg * RUN * a.stride;
+            const char* pl = (const char*)(a.up + ((size_t)r.n * a.C + c) * plane);      // wave-uniform
+#pragma unroll
+            for (int m = 0; m < MM; ++m) {
+                const unsigned o = (unsigned)clampi(Y + sdy[m] - R, 0, a.H - 1) * (unsigned)a.W +
+                                   (unsigned)clampi(X0 - R + sq[m], 0, a.W - 1);
+                f.sv[m] = *(const float*)(pl + 4u * o);
+            }
+        };
+        auto park = [&](const Fetch& f, float* S) {
+#pragma unroll
+            for (int m = 0; m < MM; ++m)
+                if (t2 + 256 * m < K * WD) S[t2 + 256 * m] = f.sv[m];
+        };
+        Run ra = run0;
+        int ca = 0;
+        long long ia = 0;
+        auto step_ahead = [&]() {
+            ++ia;
+            if (++ca == a.C) { ca = 0; ra = advance(ra); }
+        };
+        Fetch f;
+        fetch(ra, ca, f);
+        park(f, stage);
+        step_ahead();
+        bool parked = ia >= n_it;
+        if (!parked) fetch(ra, ca, f);
+        step_ahead();
+        float phi[N16][4];
+        int c = 0, pp = 0, tp = 0;
+        const float* H = TGT;                            // targets of the current run
+        __syncthreads();                                // iteration 0 is staged, the first coefficients parked
+        for (long long it = 0; it < n_it; ++it) {
+            const int buf = (int)(it & 1);
+            const float* P = stage + buf * PSZ;
+            if (!parked) park(f, stage + (buf ^ 1) * PSZ);  // iteration it + 1
+            parked = ia >= n_it;                            // ia == it + 2
+            if (!parked) fetch(ra, ca, f);
+            step_ahead();
+            if (c == 0) {                                // a new run: its coefficients
+                const float* Q = PH + pp * TILE;
+                H = TGT + tp * a.C * RUN;
+                tp ^= 1;
+#pragma unroll
+                for (int nb = 0; nb < N16; ++nb) {
+                    const float4 q = *(const float4*)&Q[(16 * nb + c16) * TSS + kq4];
+                    phi[nb][0] = q.x; phi[nb][1] = q.y; phi[nb][2] = q.z; phi[nb][3] = q.w;
+                }
+                pp ^= phbuf - 1;
+            }
+            float av[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) av[ks] = P[aoff[ks]];
+            const float4 h = *(const float4*)&H[c * RUN + kq4];
+            f32x4 dot[N16];
+#pragma unroll
+            for (int nb = 0; nb < N16; ++nb) dot[nb] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const float av_k = atap[ks] ? av[ks] : 0.0f;
+#pragma unroll
+                for (int nb = 0; nb < N16; ++nb)
+                    dot[nb] = __builtin_amdgcn_mfma_f32_16x16x4f32(av_k, Bd[nb][ks], dot[nb], 0, 0, 0);
+            }
+            // responses (and the target column) into the tile: column 16 nb + c16, samples kq4 .. kq4 + 3
+            float* T = lds + buf * TILE;
+#pragma unroll
+            for (int nb = 0; nb < N16; ++nb) {
+                float4 o;
+                o.x = phi[nb][0] * dot[nb][0];          // phi is zero past L and past the end of the row
+                o.y = phi[nb][1] * dot[nb][1];
+                o.z = phi[nb][2] * dot[nb][2];
+                o.w = phi[nb][3] * dot[nb][3];
+                if (nb == tcol && holds_target) o = h;
+                *(float4*)&T[(16 * nb + c16) * TSS + kq4] = o;
+            }
+            __syncthreads();                            // this tile is complete
+            c = c + 1 == a.C ? 0 : c + 1;
+        }
+        return;
+    }
+
+    // ---- contracting wavefronts ----
+    // Coefficients of a run: this lane's sample, atoms g, g + 4, ...; requested a whole
+    // iteration before they are parked
+    // ... and its target pixels of channels g, g + 4, ...
+    constexpr int NCW = (SR_MAX_CHANNELS + 3) / 4;
+    struct Fetch { TC raw[NPW]; float h[NCW]; bool ok; int pp, tp; };
+    auto fetch = [&](const Run& r, Fetch& f) {
+        const unsigned centre = sample_of(r, f.ok);
+#pragma unroll
+        for (int j = 0; j < NCW; ++j) {
+            const int c = g + 4 * j;
+            f.h[j] = a.target[((size_t)r.n * a.C + (c < a.C ? c : a.C - 1)) * plane + centre];
+        }
+        const TC* img = (const TC*)a.coeff + (size_t)r.n * a.L * plane;
+#pragma unroll
+        for (int j = 0; j < NPW; ++j) {
+            const int l = g + 4 * j;
+            f.raw[j] = img[(size_t)(l < a.L ? l : a.L - 1) * plane + centre];            // plane: wave-uniform
+        }
+    };
+    auto park = [&](const Fetch& f) {
+        float* Q = PH + f.pp * TILE;
+        float* Hn = TGT + f.tp * a.C * RUN;
+#pragma unroll
+        for (int j = 0; j < NCW; ++j)
+            if (g + 4 * j < a.C) Hn[(g + 4 * j) * RUN + si] = f.ok ? f.h[j] : 0.0f;
+#pragma unroll
+        for (int j = 0; j < NPW; ++j) {
+            const int l = g + 4 * j;
+            Q[l * TSS + si] = (f.ok && l < a.L) ? widen(f.raw[j]) : 0.0f;
+        }
+    };
+
+    // Blocks g, g + 4, ... of the upper triangle; a wavefront with fewer blocks than the
+    // others repeats the last block (and does not store it) so that the matrix-core loop
+    // has no branches.
+    int bi[NTW], bj[NTW];
+#pragma unroll
+    for (int t = 0; t < NTW; ++t) {
+        const int q = g + 4 * t;
+        block_of(q < a.ntile ? q : a.ntile - 1, a.n16, bi[t], bj[t]);
+    }
+    double dacc[NTW][4];
+#pragma unroll
+    for (int t = 0; t < NTW; ++t)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) dacc[t][e] = 0.0;
+
+    // The run whose coefficients are requested next, the first iteration that reads them
+    // and the copy they go to.  Requested in iteration ia - 3, parked in iteration ia - 2
+    // (after the barrier that ends the last read of a single copy, see phbuf).
+    Run ra = run0;
+    long long ia = 0;
+    int ppa = 0, tpa = 0;
+    auto step_ahead = [&]() {
+        ia += a.C;
+        ra = advance(ra);
+        ppa ^= phbuf - 1;
+        tpa ^= 1;
+    };
+    Fetch f;
+    fetch(ra, f);
+    f.pp = ppa; f.tp = tpa;
+    park(f);
+    step_ahead();
+    bool parked = true;                                 // nothing waits in f
+    if (ia < n_it && ia <= 2) {                         // a run that starts in iteration 1 or 2: request now
+        fetch(ra, f);
+        f.pp = ppa; f.tp = tpa;
+        parked = false;
+        const bool now = ia == 1;                       // ... iteration 1: park before iteration 0 ends
+        step_ahead();
+        __syncthreads();                                // iteration 0 is staged
+        if (now) {
+            park(f);
+            parked = true;
+            if (ia < n_it && ia <= 2) { fetch(ra, f); f.pp = ppa; f.tp = tpa; parked = false; step_ahead(); }
+        }
+    } else {
+        __syncthreads();                                // iteration 0 is staged
+    }
+    for (long long it = 0; it < n_it; ++it) {
+        __syncthreads();                                // the tile of iteration it is complete, it + 1 is staged
+        const int buf = (int)(it & 1);
+        if (!parked) { park(f); parked = true; }        // read from iteration it + 2 on
+        if (ia < n_it && ia <= it + 3) { fetch(ra, f); f.pp = ppa; f.tp = tpa; parked = false; step_ahead(); }
+        const float* T = lds + buf * TILE;
+        f32x4 acc[NTW];
+#pragma unroll
+        for (int t = 0; t < NTW; ++t) acc[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        constexpr int TG = NTW < 4 ? NTW : 4;           // blocks go four at a time, their steps interleaved
+#pragma unroll
+        for (int sg = 0; sg < RUN / 16; ++sg) {
+#pragma unroll
+            for (int t0 = 0; t0 < NTW; t0 += TG) {
+                float4 u[TG], v[TG];
+#pragma unroll
+                for (int t = 0; t < TG; ++t) {
+                    u[t] = *(const float4*)&T[(16 * bi[t0 + t] + c16) * TSS + 16 * sg + 4 * kq];
+                    v[t] = *(const float4*)&T[(16 * bj[t0 + t] + c16) * TSS + 16 * sg + 4 * kq];
+                }
+#pragma unroll
+                for (int t = 0; t < TG; ++t) acc[t0 + t] = __builtin_amdgcn_mfma_f32_16x16x4f32(u[t].x, v[t].x, acc[t0 + t], 0, 0, 0);
+#pragma unroll
+                for (int t = 0; t < TG; ++t) acc[t0 + t] = __builtin_amdgcn_mfma_f32_16x16x4f32(u[t].y, v[t].y, acc[t0 + t], 0, 0, 0);
+#pragma unroll
+                for (int t = 0; t < TG; ++t) acc[t0 + t] = __builtin_amdgcn_mfma_f32_16x16x4f32(u[t].z, v[t].z, acc[t0 + t], 0, 0, 0);
+#pragma unroll
+                for (int t = 0; t < TG; ++t) acc[t0 + t] = __builtin_amdgcn_mfma_f32_16x16x4f32(u[t].w, v[t].w, acc[t0 + t], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < NTW; ++t)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dacc[t][e] += (double)acc[t][e];
+    }
+    // lane (c16, kq), register e of block (bi, bj) holds row 16 bi + 4 kq + e, column 16 bj + c16
+#pragma unroll
+    for (int t = 0; t < NTW; ++t)
+        if (g + 4 * t < a.ntile) {
+            double* dst = a.ws + ((size_t)blockIdx.x * a.ntile + (g + 4 * t)) * 256 + si * 4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dst[e] = dacc[t][e];
+        }
+}
+
 // Adds the workgroups' partial sums in workgroup order and scatters them into
 // G (both triangles), b, hh; also stores the sample count.
 __global__ __launch_bounds__(NT) void k_gram_reduce(const double* __restrict__ ws, int grid, int ntile, int n16, int L,
@@ -379,11 +739,30 @@ int sr_atom_gram(const sr_tensor* up, const sr_tensor* coeff, const sr_tensor* d
     a.n16 = column_blocks(L);
     a.ntile = upper_blocks(a.n16);
     const hipStream_t st = (hipStream_t)stream;
+    // staged row segments (32-bit offsets within a plane; LDS for the tiles), else per-lane gathers
+    const bool rows_ok = stride <= STMAX && (int64_t)up->h * up->w < (1 << 30);
+    bool rows = false;
+    int grid = GRID;
+#define SR_GRAM_LAUNCH_N(KS, TC, N16)                                                                      \
+    do {                                                                                                    \
+        const size_t lds = rows_lds_floats(KS, N16, channels) * sizeof(float);                              \
+        rows = rows_ok && lds <= 160 * 1024;                                                                \
+        if (rows) {                                                                                         \
+            if (lds > 65536 &&                                                                              \
+                hipFuncSetAttribute((const void*)k_atom_gram_rows<KS, TC, N16>,                             \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)    \
+                return SR_ERR_LAUNCH;                                                                       \
+            grid = ((N16) <= 5 && (KS) <= 5 && 2 * lds <= 160 * 1024) ? 2 * GRID2 : GRID2;                  \
+            hipLaunchKernelGGL((k_atom_gram_rows<KS, TC, N16>), dim3(grid), dim3(NT2), lds, st, a);         \
+        } else {                                                                                            \
+            hipLaunchKernelGGL((k_atom_gram<KS, TC, N16>), dim3(GRID), dim3(NT), 0, st, a);                 \
+        }                                                                                                   \
+    } while (0)
 #define SR_GRAM_LAUNCH_T(KS, TC)                                                                           \
     do {                                                                                                    \
-        if (a.n16 <= 2) hipLaunchKernelGGL((k_atom_gram<KS, TC, 2>), dim3(GRID), dim3(NT), 0, st, a);       \
-        else if (a.n16 <= 5) hipLaunchKernelGGL((k_atom_gram<KS, TC, 5>), dim3(GRID), dim3(NT), 0, st, a);  \
-        else hipLaunchKernelGGL((k_atom_gram<KS, TC, 9>), dim3(GRID), dim3(NT), 0, st, a);                  \
+        if (a.n16 <= 2) SR_GRAM_LAUNCH_N(KS, TC, 2);                                                        \
+        else if (a.n16 <= 5) SR_GRAM_LAUNCH_N(KS, TC, 5);                                                   \
+        else SR_GRAM_LAUNCH_N(KS, TC, 9);                                                                   \
     } while (0)
 #define SR_GRAM_LAUNCH(KS)                                                                                  \
     do {                                                                                                    \
@@ -398,11 +777,12 @@ int sr_atom_gram(const sr_tensor* up, const sr_tensor* coeff, const sr_tensor* d
     }
 #undef SR_GRAM_LAUNCH
 #undef SR_GRAM_LAUNCH_T
+#undef SR_GRAM_LAUNCH_N
     if (hipGetLastError() != hipSuccess) return SR_ERR_LAUNCH;
     const double M = (double)a.N * a.ny * a.nx * a.C;
     const int items = a.ntile * 256;
     hipLaunchKernelGGL(k_gram_reduce, dim3((items + NT - 1) / NT), dim3(NT), 0, st,
-                       (const double*)workspace, GRID, a.ntile, a.n16, L, M, normal);
+                       (const double*)workspace, grid, a.ntile, a.n16, L, M, normal);
     return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_LAUNCH;
 }
 

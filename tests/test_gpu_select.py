@@ -21,6 +21,11 @@ CASES = [
     (1, 3, 40, 48, 4, 72, 5, "f16", 5),
     (1, 16, 6, 7, 2, 3, 3, "f32", 1),        # 16 channels
     (2, 3, 11, 14, 4, 40, 5, "f8", 2),       # coefficients stored as 8-bit E4M3
+    # more runs than workgroups, so that every workgroup walks several runs and channels
+    (1, 3, 64, 80, 4, 72, 5, "f16", 1),      # 1280 runs of one lattice row segment each
+    (1, 1, 96, 100, 4, 20, 5, "f32", 1),     # one channel: a new run every iteration, 2688 runs
+    (2, 2, 120, 130, 3, 72, 3, "f8", 2),     # two channels, two images, ragged last segment
+    (1, 3, 30, 500, 2, 100, 7, "f16", 4),    # 7 x 7, 9 column blocks, stride 4: long staged segments
 ]
 
 
