@@ -97,8 +97,9 @@ def selection_leg(sr, torch, wl, inp, stride):
     return {"stride": stride, "samples": int(samples), "gram_ms": round(ms, 4),
             "roofline": {"bound": "mfma", "achieved": round(flop / ms / 1e9, 2), "peak": 157.3, "unit": "TFLOP/s",
                          "frac": round(flop / ms / 1e9 / 157.3, 4),
-                         "note": "fp32 matrix cores for the Gram contraction (60 % of the flops); the responses "
-                                 "(40 %) run on the fp32 vector ALU, whose non-packed peak is 78.6 TFLOP/s"},
+                         "note": "useful flops (responses + upper triangle of the Gram matrix); both run on the "
+                                 "fp32 matrix cores for lattice strides up to 4, the responses on the fp32 vector "
+                                 "ALU beyond; the matrix cores execute 1.35 x the useful flops (16-wide padding)"},
             "host_search_s": round(t_host, 3), "kept": [int(v) for v in kept],
             "gamma": [round(float(g), 4) for g in gamma], "lambda": lam}
 

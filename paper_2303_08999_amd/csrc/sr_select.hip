@@ -284,6 +284,44 @@ constexpr size_t rows_lds_floats(int k, int n16, int channels) {
            2 * (((size_t)k * (63 * STMAX + k) + 3) & ~(size_t)3);
 }
 
+// Five column blocks (64 to 79 atoms, the paper's 72 among them): the 15 blocks of
+// the upper triangle dealt to the four contracting wavefronts so that a wavefront's
+// blocks share their operands.  Wavefront w reads the column blocks col[w][0 .. nc)
+// of the tile (one 16-byte LDS load each per 16 samples: 14 loads for the 15 blocks,
+// where separate operands for every block would take 30) and block t multiplies
+// operand u[w][t] by operand v[w][t]; q is the block's row-major number in the
+// upper triangle.
+struct Deal5 { int nc, nb, col[4], u[4], v[4], q[4]; };
+constexpr Deal5 deal5(int w) {
+    return w == 0 ? Deal5{3, 4, {0, 1, 2, 0}, {0, 0, 1, 0}, {0, 1, 1, 2}, {0, 1, 5, 2}}        // 00 01 11 02
+         : w == 1 ? Deal5{3, 4, {1, 2, 3, 0}, {1, 1, 2, 0}, {1, 2, 2, 1}, {9, 10, 12, 6}}      // 22 23 33 12
+         : w == 2 ? Deal5{4, 4, {1, 2, 3, 4}, {3, 2, 1, 0}, {3, 3, 3, 3}, {14, 13, 11, 8}}     // 44 34 24 14
+                  : Deal5{4, 3, {0, 1, 3, 4}, {0, 0, 1, 0}, {2, 3, 2, 0}, {3, 4, 7, 0}};       // 03 04 13
+}
+template <int W>
+__device__ __forceinline__ void contract5(const float* T, int c16, int kq, f32x4 (&acc)[4]) {
+    constexpr Deal5 d = deal5(W);
+#pragma unroll
+    for (int sg = 0; sg < RUN / 16; ++sg) {
+        float4 x[4];
+#pragma unroll
+        for (int i = 0; i < d.nc; ++i) x[i] = *(const float4*)&T[(16 * d.col[i] + c16) * TSS + 16 * sg + 4 * kq];
+#pragma unroll
+        for (int t = 0; t < d.nb; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[d.u[t]].x, x[d.v[t]].x, acc[t], 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < d.nb; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[d.u[t]].y, x[d.v[t]].y, acc[t], 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < d.nb; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[d.u[t]].z, x[d.v[t]].z, acc[t], 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < d.nb; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[d.u[t]].w, x[d.v[t]].w, acc[t], 0, 0, 0);
+    }
+}
+// block number of slot t of wavefront w in that deal, -1: none
+__device__ __forceinline__ int deal5_block(int w, int t) {
+    const Deal5 d = w == 0 ? deal5(0) : (w == 1 ? deal5(1) : (w == 2 ? deal5(2) : deal5(3)));
+    return t < d.nb ? d.q[t] : -1;
+}
+
 template <int K, typename TC, int N16>
 __global__ __launch_bounds__(NT2, (N16 <= 5 && K <= 5) ? 4 : 2) void k_atom_gram_rows(const GramArgs a) {
     constexpr int KK = K * K, R = (K - 1) / 2;
@@ -531,6 +569,7 @@ __global__ __launch_bounds__(NT2, (N16 <= 5 && K <= 5) ? 4 : 2) void k_atom_gram
     for (int t = 0; t < NTW; ++t)
 #pragma unroll
         for (int e = 0; e < 4; ++e) dacc[t][e] = 0.0;
+    const bool shared_operands = N16 == 5 && a.n16 == 5;     // the deal of deal5() instead
 
     // The run whose coefficients are requested next, the first iteration that reads them
     // and the copy they go to.  Requested in iteration ia - 3, parked in iteration ia - 2
@@ -575,24 +614,36 @@ __global__ __launch_bounds__(NT2, (N16 <= 5 && K <= 5) ? 4 : 2) void k_atom_gram
 #pragma unroll
         for (int t = 0; t < NTW; ++t) acc[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
         constexpr int TG = NTW < 4 ? NTW : 4;           // blocks go four at a time, their steps interleaved
-#pragma unroll
-        for (int sg = 0; sg < RUN / 16; ++sg) {
-#pragma unroll
-            for (int t0 = 0; t0 < NTW; t0 += TG) {
-                float4 u[TG], v[TG];
-#pragma unroll
-                for (int t = 0; t < TG; ++t) {
-                    u[t] = *(const float4*)&T[(16 * bi[t0 + t] + c16) * TSS + 16 * sg + 4 * kq];
-                    v[t] = *(const float4*)&T[(16 * bj[t0 + t] + c16) * TSS + 16 * sg + 4 * kq];
+        if constexpr (N16 == 5) {
+            if (shared_operands) {
+                switch (g) {
+                case 0:  contract5<0>(T, c16, kq, acc); break;
+                case 1:  contract5<1>(T, c16, kq, acc); break;
+                case 2:  contract5<2>(T, c16, kq, acc); break;
+                default: contract5<3>(T, c16, kq, acc); break;
                 }
+            }
+        }
+        if (!shared_operands) {
 #pragma unroll
-                for (int t = 0; t < TG; ++t) acc[t0 + t] = __builtin_amdgcn_mfma_f32_16x16x4f32(u[t].x, v[t].x, acc[t0 + t], 0, 0, 0);
+            for (int sg = 0; sg < RUN / 16; ++sg) {
 #pragma unroll
-                for (int t = 0; t < TG; ++t) acc[t0 + t] = __builtin_amdgcn_mfma_f32_16x16x4f32(u[t].y, v[t].y, acc[t0 + t], 0, 0, 0);
+                for (int t0 = 0; t0 < NTW; t0 += TG) {
+                    float4 u[TG], v[TG];
 #pragma unroll
-                for (int t = 0; t < TG; ++t) acc[t0 + t] = __builtin_amdgcn_mfma_f32_16x16x4f32(u[t].z, v[t].z, acc[t0 + t], 0, 0, 0);
+                    for (int t = 0; t < TG; ++t) {
+                        u[t] = *(const float4*)&T[(16 * bi[t0 + t] + c16) * TSS + 16 * sg + 4 * kq];
+                        v[t] = *(const float4*)&T[(16 * bj[t0 + t] + c16) * TSS + 16 * sg + 4 * kq];
+                    }
 #pragma unroll
-                for (int t = 0; t < TG; ++t) acc[t0 + t] = __builtin_amdgcn_mfma_f32_16x16x4f32(u[t].w, v[t].w, acc[t0 + t], 0, 0, 0);
+                    for (int t = 0; t < TG; ++t) acc[t0 + t] = __builtin_amdgcn_mfma_f32_16x16x4f32(u[t].x, v[t].x, acc[t0 + t], 0, 0, 0);
+#pragma unroll
+                    for (int t = 0; t < TG; ++t) acc[t0 + t] = __builtin_amdgcn_mfma_f32_16x16x4f32(u[t].y, v[t].y, acc[t0 + t], 0, 0, 0);
+#pragma unroll
+                    for (int t = 0; t < TG; ++t) acc[t0 + t] = __builtin_amdgcn_mfma_f32_16x16x4f32(u[t].z, v[t].z, acc[t0 + t], 0, 0, 0);
+#pragma unroll
+                    for (int t = 0; t < TG; ++t) acc[t0 + t] = __builtin_amdgcn_mfma_f32_16x16x4f32(u[t].w, v[t].w, acc[t0 + t], 0, 0, 0);
+                }
             }
         }
 #pragma unroll
@@ -602,28 +653,43 @@ __global__ __launch_bounds__(NT2, (N16 <= 5 && K <= 5) ? 4 : 2) void k_atom_gram
     }
     // lane (c16, kq), register e of block (bi, bj) holds row 16 bi + 4 kq + e, column 16 bj + c16
 #pragma unroll
-    for (int t = 0; t < NTW; ++t)
-        if (g + 4 * t < a.ntile) {
-            double* dst = a.ws + ((size_t)blockIdx.x * a.ntile + (g + 4 * t)) * 256 + si * 4;
+    for (int t = 0; t < NTW; ++t) {
+        int q = g + 4 * t;
+        if (q >= a.ntile) q = -1;
+        if constexpr (N16 == 5) {
+            if (shared_operands) q = deal5_block(g, t);
+        }
+        if (q >= 0) {
+            double* dst = a.ws + ((size_t)blockIdx.x * a.ntile + q) * 256 + si * 4;
 #pragma unroll
             for (int e = 0; e < 4; ++e) dst[e] = dacc[t][e];
         }
+    }
 }
 
-// Adds the workgroups' partial sums in workgroup order and scatters them into
-// G (both triangles), b, hh; also stores the sample count.
+// Adds the workgroups' partial sums and scatters them into G (both triangles), b, hh;
+// also stores the sample count.  Sixteen threads share an entry: thread p adds the
+// partial sums of workgroups p, p + 16, ... in that order and the first thread then
+// adds the sixteen results in order, so the sum depends on the launch shape only.
+constexpr int RED_PARTS = 16, RED_ITEMS = NT / RED_PARTS;
 __global__ __launch_bounds__(NT) void k_gram_reduce(const double* __restrict__ ws, int grid, int ntile, int n16, int L,
                                                     double M, double* __restrict__ normal) {
-    const int idx = blockIdx.x * NT + threadIdx.x;
-    if (idx == 0) normal[(size_t)L * L + L + 1] = M;
-    if (idx >= ntile * 256) return;
+    __shared__ double part_sum[RED_PARTS][RED_ITEMS];
+    const int item = threadIdx.x % RED_ITEMS, part = threadIdx.x / RED_ITEMS;
+    const int idx = blockIdx.x * RED_ITEMS + item;      // ntile * 256 entries, a multiple of RED_ITEMS
+    if (idx == 0 && part == 0) normal[(size_t)L * L + L + 1] = M;
     const int q = idx >> 8, lane = (idx >> 2) & 63, e = idx & 3;
     int bi, bj;
     block_of(q, n16, bi, bj);
     const int row = 16 * bi + 4 * (lane >> 4) + e, col = 16 * bj + (lane & 15);
-    if (row > col || col > L) return;           // diagonal blocks hold both triangles: keep the upper one
+    const bool wanted = row <= col && col <= L;         // diagonal blocks hold both triangles: keep the upper one
     double sum = 0.0;
-    for (int w = 0; w < grid; ++w) sum += ws[((size_t)w * ntile + q) * 256 + (idx & 255)];
+    if (wanted)
+        for (int w = part; w < grid; w += RED_PARTS) sum += ws[((size_t)w * ntile + q) * 256 + (idx & 255)];
+    part_sum[part][item] = sum;
+    __syncthreads();
+    if (part != 0 || !wanted) return;
+    for (int p = 1; p < RED_PARTS; ++p) sum += part_sum[p][item];
     if (col < L) {
         normal[(size_t)row * L + col] = sum;
         normal[(size_t)col * L + row] = sum;
@@ -781,7 +847,7 @@ int sr_atom_gram(const sr_tensor* up, const sr_tensor* coeff, const sr_tensor* d
     if (hipGetLastError() != hipSuccess) return SR_ERR_LAUNCH;
     const double M = (double)a.N * a.ny * a.nx * a.C;
     const int items = a.ntile * 256;
-    hipLaunchKernelGGL(k_gram_reduce, dim3((items + NT - 1) / NT), dim3(NT), 0, st,
+    hipLaunchKernelGGL(k_gram_reduce, dim3(items / RED_ITEMS), dim3(NT), 0, st,
                        (const double*)workspace, grid, a.ntile, a.n16, L, M, normal);
     return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_LAUNCH;
 }
