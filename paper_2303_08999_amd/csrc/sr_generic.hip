@@ -91,60 +91,99 @@ __global__ __launch_bounds__(GNT) void k_assemble_generic(const AssembleArgs a) 
 }
 
 // Stage 1 alone, same arithmetic as the tiles (vertical pass over four LR rows, then
-// horizontal pass over four columns).  A thread produces four consecutive pixels
-// of a row: they share their vertical-pass values (at most six LR columns), and
-// leave as one 16-byte (fp16: 8-byte) store when the rows keep that alignment.
-// (Letting a thread also produce the s rows that share its LR rows saves loads but
-// measured 25 % slower on the 4K frame: fewer, longer threads.)
+// horizontal pass over four columns), so the values agree bit for bit with the U
+// the fused kernels form.  A workgroup produces 256 x 16 pixels: it loads their LR
+// footprint (at most 12 rows x 132 columns) into LDS once, forms the vertical pass
+// of the 16 rows there, and each thread then produces four consecutive pixels of
+// four rows, each group stored with one 16-byte (fp16: 8-byte) store when the rows
+// keep that alignment.
+// (Before: every thread gathered its own 24 LR pixels from global memory; the 4K
+// frame took 50 us against 16 us for the bare 99.5 MB write.)
 template <typename TI, typename TO>
 __global__ __launch_bounds__(256) void k_bicubic(const BicubicArgs a) {
-    constexpr int PXT = 4, NCOL = 6;      // columns floor-1 .. floor+2 of four pixels span <= ceil(3/2) + 4
-    const int X0 = (blockIdx.x * 64 + threadIdx.x % 64) * PXT;
-    const int Y = blockIdx.y * 4 + threadIdx.x / 64;
-    if (X0 >= a.W || Y >= a.H) return;
-    const int nc = blockIdx.z;
+    constexpr int PXT = 4;                // pixels of a thread in a row
+    constexpr int BW = 256, BH = 16;      // pixels of a workgroup
+    constexpr int MAXC = BW / 2 + 4, MAXR = BH / 2 + 4;     // LR footprint at the smallest scale, 2
+    constexpr int MAXS = 4;               // largest scale
+    __shared__ float lrT[MAXR][MAXC];
+    __shared__ float V[BH][MAXC];
+    __shared__ float4 wyT[BH], wxT[2 * MAXS];    // weights of the workgroup's rows; weights by phase m
+    __shared__ int rbT[BH];                      // first footprint row of each row's four taps
+    const int tid = threadIdx.x;
+    const int Xb = blockIdx.x * BW, Yb = blockIdx.y * BH, nc = blockIdx.z;
     const TI* p = (const TI*)a.lr + (size_t)nc * a.h * a.w;
-    int my;
-    const int fy = src_floor(Y, a.s, my);
-    float wy[4];
-    keys_weights(my, a.s, wy);
-    size_t rows[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) rows[i] = (size_t)clampi(fy - 1 + i, 0, a.h - 1) * a.w;
-    int mx0;
-    const int c0 = src_floor(X0, a.s, mx0) - 1;            // first LR column of the group
-    float vcol[NCOL];                                        // vertical pass first, as in the tiled kernels
-#pragma unroll
-    for (int j = 0; j < NCOL; ++j) {
-        const int xs = clampi(c0 + j, 0, a.w - 1);
-        vcol[j] = dot4(wy, ld_as_float(p, rows[0] + xs), ld_as_float(p, rows[1] + xs),
-                       ld_as_float(p, rows[2] + xs), ld_as_float(p, rows[3] + xs));
+    int m;
+    const int c0 = src_floor(Xb, a.s, m) - 1;                                   // first LR column and row (may be -1 or -2: clamped)
+    const int r0 = src_floor(Yb, a.s, m) - 1;
+    const int ncol = src_floor(clampi(Xb + BW - 1, 0, a.W - 1), a.s, m) + 2 - c0 + 1;
+    const int nrow = src_floor(clampi(Yb + BH - 1, 0, a.H - 1), a.s, m) + 2 - r0 + 1;
+    // e / ncol for e < 2^14 without a division per element (4 <= ncol <= 132: exact)
+    const unsigned inv = ((1u << 22) + ncol - 1) / ncol;
+    for (int e = tid; e < nrow * ncol; e += 256) {
+        const int r = (int)(((unsigned)e * inv) >> 22), c = e - r * ncol;
+        lrT[r][c] = ld_as_float(p, (size_t)clampi(r0 + r, 0, a.h - 1) * a.w + clampi(c0 + c, 0, a.w - 1));
     }
-    float res[PXT];
+    if (tid < BH) {
+        int my;
+        rbT[tid] = src_floor(clampi(Yb + tid, 0, a.H - 1), a.s, my) - 1 - r0;
+        float w[4];
+        keys_weights(my, a.s, w);
+        wyT[tid] = make_float4(w[0], w[1], w[2], w[3]);
+    } else if (tid >= 64 && tid < 64 + 2 * a.s) {
+        float w[4];
+        keys_weights(tid - 64, a.s, w);
+        wxT[tid - 64] = make_float4(w[0], w[1], w[2], w[3]);
+    }
+    __syncthreads();
+    for (int e = tid; e < BH * ncol; e += 256) {
+        const int r = (int)(((unsigned)e * inv) >> 22), c = e - r * ncol;
+        const int rb = rbT[r];
+        const float4 w4 = wyT[r];
+        const float wy[4] = {w4.x, w4.y, w4.z, w4.w};
+        V[r][c] = dot4(wy, lrT[rb][c], lrT[rb + 1][c], lrT[rb + 2][c], lrT[rb + 3][c]);
+    }
+    __syncthreads();
+    const int X0 = Xb + (tid % 64) * PXT;
+    if (X0 >= a.W) return;
+    // Each pixel reads its own four vertical-pass columns from LDS.  (Sharing the six
+    // columns of the group in registers needs a select per tap, which the compiler
+    // turns into divergent branches: measured 2 x slower.)
+    int col[PXT];
+    float wx[PXT][4];
 #pragma unroll
     for (int q = 0; q < PXT; ++q) {
         int mx;
-        const int d = src_floor(X0 + q, a.s, mx) - 1 - c0;   // 0, 1 or 2
-        float wx[4], v[4];
-        keys_weights(mx, a.s, wx);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = d == 0 ? vcol[j] : (d == 1 ? vcol[j + 1] : vcol[j + 2]);
-        res[q] = dot4(wx, v[0], v[1], v[2], v[3]);
+        col[q] = src_floor(X0 + q < a.W ? X0 + q : a.W - 1, a.s, mx) - 1 - c0;      // .. + 3 < ncol
+        const float4 w4 = wxT[mx];
+        wx[q][0] = w4.x; wx[q][1] = w4.y; wx[q][2] = w4.z; wx[q][3] = w4.w;
     }
-    TO* dst = (TO*)a.out + ((size_t)nc * a.H + Y) * a.W + X0;
-    if ((a.W & 3) == 0 && ((uintptr_t)a.out & 15) == 0) {    // whole groups, 16-byte aligned rows
-        if constexpr (sizeof(TO) == 4) {
-            *(float4*)dst = make_float4(res[0], res[1], res[2], res[3]);
-        } else {
-            union { __half h[4]; uint2 u; } pk;
+    const bool vec = (a.W & 3) == 0 && ((uintptr_t)a.out & 15) == 0;    // whole groups, 16-byte aligned rows
+    const int rt = tid / 64;
 #pragma unroll
-            for (int q = 0; q < PXT; ++q) pk.h[q] = narrow_f16(res[q]);
-            *(uint2*)dst = pk.u;
+    for (int i = 0; i < BH / 4; ++i) {
+        const int r = rt + 4 * i;
+        if (Yb + r >= a.H) break;
+        float res[PXT];
+#pragma unroll
+        for (int q = 0; q < PXT; ++q) {
+            const float* v = &V[r][col[q]];
+            res[q] = dot4(wx[q], v[0], v[1], v[2], v[3]);
         }
-    } else {
+        TO* dst = (TO*)a.out + ((size_t)nc * a.H + Yb + r) * a.W + X0;
+        if (vec) {
+            if constexpr (sizeof(TO) == 4) {
+                *(float4*)dst = make_float4(res[0], res[1], res[2], res[3]);
+            } else {
+                union { __half h[4]; uint2 u; } pk;
 #pragma unroll
-        for (int q = 0; q < PXT; ++q)
-            if (X0 + q < a.W) st_from_float(dst, q, res[q]);
+                for (int q = 0; q < PXT; ++q) pk.h[q] = narrow_f16(res[q]);
+                *(uint2*)dst = pk.u;
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < PXT; ++q)
+                if (X0 + q < a.W) st_from_float(dst, q, res[q]);
+        }
     }
 }
 
@@ -169,7 +208,7 @@ hipError_t launch_generic(const AssembleArgs& a, int k, bool io_f16, hipStream_t
 }
 
 hipError_t launch_bicubic(const BicubicArgs& a, bool in_f16, bool out_f16, hipStream_t st) {
-    const dim3 grid((a.W + 255) / 256, (a.H + 3) / 4, a.NC);
+    const dim3 grid((a.W + 255) / 256, (a.H + 15) / 16, a.NC);
     if (in_f16) {
         if (out_f16) hipLaunchKernelGGL((k_bicubic<__half, __half>), grid, dim3(256), 0, st, a);
         else         hipLaunchKernelGGL((k_bicubic<__half, float>), grid, dim3(256), 0, st, a);
