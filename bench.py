@@ -104,6 +104,25 @@ def selection_leg(sr, torch, wl, inp, stride):
             "gamma": [round(float(g), 4) for g in gamma], "lambda": lam}
 
 
+def bicubic_leg(sr, torch, wl, inp):
+    """The bicubic-only entry point (stage 1 alone) on the workload's frame."""
+    out = torch.empty((wl.n, wl.c, wl.H, wl.W), device="cuda", dtype=inp["lr"].dtype)
+    run = lambda: sr.sr_bicubic_upsample(inp["lr"], wl.scale, wl.c, out)
+    for _ in range(3):
+        run()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+    torch.cuda.synchronize()
+    for a, b in ev:
+        a.record(); run(); b.record()
+    torch.cuda.synchronize()
+    ms = sum(a.elapsed_time(b) for a, b in ev) / len(ev)
+    nbytes = out.numel() * out.element_size() + inp["lr"].numel() * inp["lr"].element_size()
+    return {"kernel_ms_avg": round(ms, 4), "hr_mpixel_per_s": round(wl.n * wl.H * wl.W / ms / 1e3, 1),
+            "roofline": {"bound": "hbm", "achieved": round(nbytes / ms / 1e6, 1), "peak": 8000.0, "unit": "GB/s",
+                         "frac": round(nbytes / ms / 1e6 / 8000.0, 4),
+                         "note": "algorithmic bytes: the LR image once, the up-sampled image once"}}
+
+
 def sr_synth_stored(t):
     import sr_synth
     return sr_synth.stored_numpy(t)
@@ -173,6 +192,8 @@ def main():
     ap.add_argument("--selection", type=int, default=0, metavar="STRIDE",
                     help="also time the offline dictionary selection (section III-A, Alg. 1) on this frame: "
                          "normal equations on the GPU over every STRIDE-th row and column, then the host search")
+    ap.add_argument("--bicubic", action="store_true",
+                    help="also time the bicubic-only entry point (stage 1 alone) on this frame")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size kernel that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters when profiling)")
@@ -300,6 +321,8 @@ def main():
         result["kept_sweep"] = sweep
     if args.selection > 0 and wl.coeff_dtype in ("f16", "f32") and inp["lr"].dtype == torch.float32 and wl.L <= 128:
         result["selection"] = selection_leg(sr, torch, wl, inp, args.selection)
+    if args.bicubic:
+        result["bicubic"] = bicubic_leg(sr, torch, wl, inp)
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(wl, inp["lr"], coeffs[0], inp["dict"], args.cpu_budget)
     print(json.dumps(result))
