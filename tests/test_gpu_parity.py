@@ -400,6 +400,25 @@ def test_bicubic_entry_point(oracle, scale, io, w):
         assert torch.equal(buf16[1:].view(out.shape), out16) and float(buf16[0]) == 0.0
 
 
+def test_bicubic_entry_point_random_shapes(oracle):
+    """Frames smaller and larger than the 256 x 16 pixels of a workgroup, ragged in both directions."""
+    rng = np.random.default_rng(2024)
+    cases = [(1, 1, 1, 1, 2), (1, 1, 1, 2, 3), (1, 2, 2, 1, 4), (1, 1, 3, 400, 2), (2, 1, 50, 3, 4)]
+    while len(cases) < 30:
+        cases.append((int(rng.integers(1, 3)), int(rng.integers(1, 4)), int(rng.integers(1, 45)),
+                      int(rng.integers(1, 330)), int(rng.integers(2, 5))))
+    for i, (n, c, h, w, scale) in enumerate(cases):
+        io = "f16" if i % 3 == 2 else "f32"
+        wl = sr_synth.Workload("bicr", 40 + i, n, c, h, w, scale, 1, 3, "f32", io)
+        lr = sr_synth.make_lr(wl, DEV)
+        out = torch.full((n, c, wl.H, wl.W), float("nan"), device=DEV, dtype=torch.float32)
+        sr.sr_bicubic_upsample(lr, scale, c, out)
+        torch.cuda.synchronize()
+        ref = oracle.bicubic(lr.cpu().numpy(), scale)
+        got = out.cpu().numpy().astype(np.float64)
+        assert np.all(np.abs(got - ref) <= 1e-5 * np.maximum(1.0, np.abs(ref))), (n, c, h, w, scale, io)
+
+
 @pytest.mark.parametrize("kernel", KERNELS)
 @pytest.mark.parametrize("scale,k", [(2, 5), (3, 5), (4, 5), (4, 7), (3, 3)])
 def test_centred_delta_atom_equals_bicubic_bit_for_bit(kernel, scale, k):
