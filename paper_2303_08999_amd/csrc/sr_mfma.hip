@@ -12,6 +12,7 @@ hipError_t launch_mfma_k5_f32(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_k7_f32(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_k5_f8(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_k7_f8(const AssembleArgs& a, int np8, hipStream_t st);
+hipError_t launch_mfma_k5_big(const AssembleArgs& a, int np8, hipStream_t st);
 
 namespace {
 
@@ -51,6 +52,15 @@ int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
     return 0;
 }
 
+// An image's coefficients beyond 4 GB: byte offsets no longer fit 32 bits.  Instantiations
+// with element offsets exist for 5x5 atoms, three channels, fp16 coefficients (an 8K frame
+// with 72 planes), in capacities 1, 4 and 9.
+bool beyond_4gb(const AssembleArgs& a, int coeff_dtype) {
+    const unsigned long long cb = coeff_dtype == SR_F32 ? 4ull : (coeff_dtype == SR_F16 ? 2ull : 1ull);
+    return (unsigned long long)a.L * a.H * a.W * cb >= (1ull << 32);
+}
+int np8_big(int np8) { return np8 <= 1 ? 1 : (np8 <= 4 ? 4 : 9); }
+
 }  // namespace
 
 // pixels a lane loads with one vector load (its pixel group)
@@ -71,7 +81,9 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
     // when it is fp16, end on one
     if (coeff_dtype == SR_F8E4M3 &&
         (((uintptr_t)a.lr % 4) != 0 || (a.io_f16 && (((unsigned long long)a.N * a.C * a.h * a.w) & 1ull)))) return false;
-    if ((unsigned long long)a.L * a.H * a.W * cb >= (1ull << 32)) return false;           // 32-bit plane offsets
+    if (beyond_4gb(a, coeff_dtype) &&                                                      // 32-bit plane offsets
+        !(k == 5 && a.C == 3 && coeff_dtype == SR_F16 && (unsigned long long)a.L * a.H * a.W < (1ull << 32)))
+        return false;
     if ((unsigned long long)a.N * a.C * a.H * a.W * 4ull >= (1ull << 32)) return false;   // 32-bit image offsets
     if (np8_for(k, a.C, a.n_fold, coeff_dtype) == 0) return false;
     if (tile < 0 || tile >= N_TILE_SHAPES) return false;
@@ -81,6 +93,7 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
 hipError_t launch_mfma(const AssembleArgs& a, int k, bool io_f16, int tile, hipStream_t st) {
     (void)io_f16;
     const int np8 = np8_for(k, a.C, a.n_fold, a.coeff_dtype);
+    if (beyond_4gb(a, a.coeff_dtype)) return launch_mfma_k5_big(a, np8_big(np8), st);
     if (k == 3) return launch_mfma_k3(a, np8, st);
     if (a.coeff_dtype == SR_F32) return k == 5 ? launch_mfma_k5_f32(a, np8, st) : launch_mfma_k7_f32(a, np8, st);
     if (a.coeff_dtype == SR_F8E4M3) return k == 5 ? launch_mfma_k5_f8(a, np8, st) : launch_mfma_k7_f8(a, np8, st);

@@ -137,7 +137,7 @@ __device__ __forceinline__ int tap_of_row(int i, int mb) {
 
 struct TilePos { int n, ty, tx; };
 
-template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT, int SMIN>
+template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT, int SMIN, bool BIG>
 __global__ __launch_bounds__(64 * NW, WPE)
 void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y, const int ntiles) {
     using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN>;
@@ -172,7 +172,16 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     auto tile_x0 = [&](int tx) { return tx == tiles_x - 1 ? a.xlast : tx * F::TW; };
 
     // ---- once per workgroup: weight, plane-offset and dictionary operand tables ---
-    const unsigned plane_b = (unsigned)a.H * (unsigned)a.W * (unsigned)F::CB;   // bytes per coefficient plane
+    // Where a coefficient lies within its image is a 32-bit offset: in bytes, or (BIG) in
+    // elements, which reaches images of up to 2^32 coefficients (an 8K frame with 72 fp16
+    // planes is 4.8 GB) at the price of a 64-bit address per load instead of a scalar base
+    // plus a 32-bit offset.
+    constexpr unsigned OU = BIG ? 1u : (unsigned)F::CB;                          // offset units per element
+    const unsigned plane_b = (unsigned)a.H * (unsigned)a.W * OU;                 // offset units per coefficient plane
+    auto caddr = [&](const char* img, unsigned off) -> const char* {
+        if constexpr (BIG) return img + (size_t)off * (size_t)F::CB;
+        else return img + off;
+    };
     if (tid0 < 2 * a.s) {
         float wt[4];
         keys_weights(tid0, a.s, wt);
@@ -327,8 +336,8 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     auto phi_base = [&](const TilePos tp, int unit, int jr, int jc, unsigned& pix_off) -> const char* {
         const int y = tp.ty * F::TH + (unit * NW + wave) * WR + jr, x = tile_x0(tp.tx) + PX * jc;
         const int yc = y < a.H ? y : a.H - 1, xc = x < a.W ? x : a.W - PX;   // out-of-image lanes re-read
-        pix_off = ((unsigned)yc * (unsigned)a.W + (unsigned)xc) * (unsigned)F::CB;   // a valid address; never stored
-        return (const char*)a.coeff + (size_t)tp.n * a.L * (size_t)plane_b;
+        pix_off = ((unsigned)yc * (unsigned)a.W + (unsigned)xc) * OU;                // a valid address; never stored
+        return (const char*)a.coeff + (size_t)tp.n * a.L * ((size_t)a.H * a.W * F::CB);
     };
 
     Raw raw[F::NLOAD];
@@ -345,7 +354,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         const unsigned* pt = ptab + hf * F::NLOAD;
 #pragma unroll
         for (int i = 0; i < F::NLOAD; ++i)
-            raw[i] = __builtin_nontemporal_load((const Raw*)(cimg + (pix_off + pt[i])));
+            raw[i] = __builtin_nontemporal_load((const Raw*)caddr(cimg, pix_off + pt[i]));
     }
 
     // ---- stage 1 in three steps; a workgroup barrier separates each from the next.
@@ -504,7 +513,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                             av[mb], __uint_as_float(raw_word(raw[st], q)), acc[q][mb], 0, 0, 0);
                 if ((st & 3) == 3) __builtin_amdgcn_sched_barrier(0);
                 if (more)
-                    raw[st] = __builtin_nontemporal_load((const Raw*)(cnext + (pix_next + pt[st])));
+                    raw[st] = __builtin_nontemporal_load((const Raw*)caddr(cnext, pix_next + pt[st]));
                 if ((st & 3) == 3) __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -536,7 +545,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             if (more) {
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
-                    raw[8 * c16 + i] = __builtin_nontemporal_load((const Raw*)(cnext + (pix_next + pt[8 * c16 + i])));
+                    raw[8 * c16 + i] = __builtin_nontemporal_load((const Raw*)caddr(cnext, pix_next + pt[8 * c16 + i]));
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -567,7 +576,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             if (more) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    raw[8 * N16 + i] = __builtin_nontemporal_load((const Raw*)(cnext + (pix_next + pt[8 * N16 + i])));
+                    raw[8 * N16 + i] = __builtin_nontemporal_load((const Raw*)caddr(cnext, pix_next + pt[8 * N16 + i]));
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -643,7 +652,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 // ---------------------------------------------------------------------------
 // Host side: launch of one instantiation on a persistent grid.
 // ---------------------------------------------------------------------------
-template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT = CT_F16, int SMIN = 2>
+template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT = CT_F16, int SMIN = 2, bool BIG = false>
 hipError_t launch_one(const AssembleArgs& a0, hipStream_t st) {
     using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN>;
     if (a0.s < SMIN) return hipErrorInvalidValue;       // its LDS footprint buffers would be too small
@@ -662,7 +671,7 @@ hipError_t launch_one(const AssembleArgs& a0, hipStream_t st) {
         (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     const int cap = cus * (4 * WPE / NW > 0 ? 4 * WPE / NW : 1);
     const int blocks = nt < cap ? (int)nt : cap;
-    hipLaunchKernelGGL((k_assemble_mfma<K, C, NP8, PX, WR, NW, NU, WPE, CT, SMIN>), dim3(blocks), dim3(F::NT), 0, st,
+    hipLaunchKernelGGL((k_assemble_mfma<K, C, NP8, PX, WR, NW, NU, WPE, CT, SMIN, BIG>), dim3(blocks), dim3(F::NT), 0, st,
                        a, tiles_x, tiles_y, (int)nt);
     return hipGetLastError();
 }

@@ -90,6 +90,25 @@ def test_plan_accepts_a_good_case(lib):
     assert plan(*case(), opts=sr.make_options(sr.SR_KERNEL_GENERIC)) == sr.SR_KERNEL_GENERIC
 
 
+def test_plan_for_images_with_more_than_4_gb_of_coefficients(lib):
+    """An 8K frame: 72 fp16 planes of 7680 x 4320 are 4.8 GB.  The matrix-core kernel takes it
+    with element offsets where such instantiations exist (5x5, three channels, fp16)."""
+    def big(L=72, k=5, C=3, cd=sr.SR_F16, h=1080, w=1920, s=4):
+        lr = T(0x10000000, sr.SR_F32, 1, C, h, w)
+        coeff = T(0x100000000, cd, 1, L, s * h, s * w)
+        d = T(0x800000000, sr.SR_F32, 1, L, k, k)
+        out = T(0x900000000, sr.SR_F32, 1, C, s * h, s * w)
+        return lr, coeff, d, out
+    assert plan(*big()) == sr.SR_KERNEL_MFMA
+    assert plan(*big(), kept=[1, 5, 71]) == sr.SR_KERNEL_MFMA
+    assert plan(*big(cd=sr.SR_F8E4M3)) == sr.SR_KERNEL_MFMA          # 2.4 GB: ordinary byte offsets
+    assert plan(*big(C=1), C=1) == sr.SR_KERNEL_GENERIC
+    assert plan(*big(cd=sr.SR_F32)) == sr.SR_KERNEL_GENERIC
+    assert plan(*big(L=128, k=7), L=128, k=7) == sr.SR_KERNEL_GENERIC
+    assert plan(*big(h=2160, w=3840)) == sr.SR_KERNEL_GENERIC        # 16K: more than 2^32 coefficients
+    assert plan(*big(), opts=sr.make_options(sr.SR_KERNEL_MFMA)) == sr.SR_KERNEL_MFMA
+
+
 def test_null_pointers(lib):
     lr, coeff, d, out = case()
     assert plan(None, coeff, d, out) == -1
@@ -229,10 +248,13 @@ def test_matrix_core_kernel_declines_tensors_beyond_32_bit_offsets(lib):
         d = T(0x80000000, sr.SR_F32, 1, L, 5, 5)
         out = T(0x4000000000, sr.SR_F32, n, 3, 4 * h, 4 * w)
         return lr, coeff, d, out
-    # 72 planes of 8192 x 4096 fp16 = 4.5 GiB: plane offsets no longer fit 32 bits
-    lr, coeff, d, out = big(72, sr.SR_F16)
+    # 72 planes of 8192 x 4096 fp32 = 9 GiB: plane offsets no longer fit 32 bits
+    # (fp16 coefficients, 5x5, three channels have instantiations with element offsets)
+    lr, coeff, d, out = big(72, sr.SR_F32)
     assert plan(lr, coeff, d, out) == sr.SR_KERNEL_GENERIC
     assert plan(lr, coeff, d, out, opts=sr.make_options(sr.SR_KERNEL_MFMA, 0)) == -3
+    lr, coeff, d, out = big(72, sr.SR_F16)
+    assert plan(lr, coeff, d, out) == sr.SR_KERNEL_MFMA
     # the same frame with 40 atoms (2.5 GiB) still qualifies
     lr, coeff, d, out = big(40, sr.SR_F16)
     assert plan(lr, coeff, d, out, L=40) == sr.SR_KERNEL_MFMA

@@ -140,6 +140,37 @@ def test_4k_dense_fp8_full_frame(oracle):
     assert float(err.max()) <= 2e-3, f"worst error {err.max():.3e}"
 
 
+def test_8k_frame_with_more_than_4_gb_of_coefficients(oracle):
+    """1080p x4 -> 7680 x 4320 with 72 fp16 planes: 4.8 GB of coefficients, beyond 32-bit
+    byte offsets.  The matrix-core kernel takes it with element offsets: every output of the
+    dense call against the oracle, and sampled pixels (corners, last rows and columns
+    among them) for kept lists that use the two smaller capacities."""
+    wl = sr_synth.Workload("8k", 51, 1, 3, 1080, 1920, 4, 72, 5, "f16", "f32", 0.0, 1.0)
+    inp = sr_synth.make_inputs(wl, DEV)
+    assert planned(inp, wl, sr.SR_KERNEL_AUTO) == MFMA
+    got = run_gpu(inp, wl, sr.SR_KERNEL_AUTO).cpu().numpy()
+    assert not np.isnan(got).any()
+    hi = host(inp)
+    ref = oracle.dict_assemble(hi["lr"], hi["coeff"], hi["dict"], wl.scale)
+    err = np.abs(got.astype(np.float64) - ref)
+    assert float(err.max()) <= 2e-3, f"worst error {err.max():.3e}"
+    del got, ref, err
+    U = oracle.bicubic(hi["lr"], wl.scale)
+    rng = np.random.default_rng(8)
+    pts = np.stack([np.zeros(4000, dtype=np.int64), rng.integers(0, wl.H, 4000), rng.integers(0, wl.W, 4000)], axis=1)
+    pts[:4] = [(0, 0, 0), (0, wl.H - 1, wl.W - 1), (0, 0, wl.W - 1), (0, wl.H - 1, 0)]
+    pts[4:1004, 1] = wl.H - 1 - (pts[4:1004, 1] % 30)            # the last tile rows
+    for n_keep in (8, 30):
+        kept = sorted(int(v) for v in rng.choice(wl.L, n_keep, replace=False))
+        if 71 not in kept:
+            kept[-1] = 71                                          # the plane farthest from the base
+        gamma = [float(v) for v in rng.uniform(0.5, 1.5, n_keep)]
+        assert planned(inp, wl, sr.SR_KERNEL_AUTO, kept) == MFMA
+        have = run_gpu(inp, wl, sr.SR_KERNEL_AUTO, kept=kept, gamma=gamma).cpu().numpy()
+        want = oracle.assemble_points(U, hi["coeff"], hi["dict"], pts, kept=kept, gamma=gamma)
+        assert float(np.abs(have[0][:, pts[:, 1], pts[:, 2]].T - want).max()) <= 2e-3, f"{n_keep} kept atoms"
+
+
 def test_every_fp8_code_is_widened_as_the_oracle_does(oracle):
     """All 254 finite E4M3 codes, one per pixel, through a single centred delta atom on a
     constant image: the output IS the widened coefficient (both kernels, bit for bit)."""
