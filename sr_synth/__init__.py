@@ -86,6 +86,8 @@ WORKLOADS = {
     "4k_dense_fp8": Workload("4k_dense_fp8", 3, 1, 3, 540, 960, 4, 72, 5, "f8", "f32"),
     "4k_selective": Workload("4k_selective", 3, 1, 3, 540, 960, 4, 72, 5, "f16", "f32", 0.0, 1.0, 8),
     "video": Workload("video", 4, 16, 3, 270, 480, 4, 128, 7, "f16", "f16"),
+    # beyond the stated list: 1080p x4, whose 72 fp16 planes (4.8 GB) exceed 32-bit byte offsets
+    "8k_dense": Workload("8k_dense", 5, 1, 3, 1080, 1920, 4, 72, 5, "f16", "f32"),
 }
 
 

@@ -145,7 +145,7 @@ def test_8k_frame_with_more_than_4_gb_of_coefficients(oracle):
     byte offsets.  The matrix-core kernel takes it with element offsets: every output of the
     dense call against the oracle, and sampled pixels (corners, last rows and columns
     among them) for kept lists that use the two smaller capacities."""
-    wl = sr_synth.Workload("8k", 51, 1, 3, 1080, 1920, 4, 72, 5, "f16", "f32", 0.0, 1.0)
+    wl = sr_synth.WORKLOADS["8k_dense"]
     inp = sr_synth.make_inputs(wl, DEV)
     assert planned(inp, wl, sr.SR_KERNEL_AUTO) == MFMA
     got = run_gpu(inp, wl, sr.SR_KERNEL_AUTO).cpu().numpy()
