@@ -51,8 +51,11 @@ extern "C" {
 /* SR_F8E4M3: one byte per value, 1 sign / 4 exponent (bias 7) / 3 mantissa bits,
  * subnormals, no infinities, largest finite 448, 0x7f and 0xff are NaN (the OCP
  * 8-bit "E4M3" format).  Accepted for the coefficient tensor only: a storage
- * format that halves the stream again; it is widened exactly before use. */
-typedef enum { SR_F32 = 0, SR_F16 = 1, SR_F8E4M3 = 2 } sr_dtype;
+ * format that halves the stream again; it is widened exactly before use.
+ * SR_BF16: two bytes per value, the upper half of an IEEE binary32 (1 sign / 8 exponent /
+ * 7 mantissa bits).  Accepted for the coefficient tensor only: what a network that runs in
+ * bfloat16 produces, taken as it is (no conversion pass over the 1.2 GB of a 4K frame). */
+typedef enum { SR_F32 = 0, SR_F16 = 1, SR_F8E4M3 = 2, SR_BF16 = 3 } sr_dtype;
 
 /* Contiguous NCHW tensor in device memory. */
 typedef struct {
@@ -142,7 +145,9 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
  *   f32 coefficients: k = 3 or 5 with at most 72 folded atoms, or k = 7 with 17 to
  *                     128;
  *   f8  coefficients: as f32, and lr->data 4-byte aligned with an even number of
- *                     elements if the image is f16.
+ *                     elements if the image is f16;
+ *   bf16 coefficients: k = 5 with at most 72 folded atoms and C = 1 or 3, or k = 7
+ *                     with at most 128 and C = 3.
  * Every other supported case runs on the generic kernel.
  */
 int sr_dict_assemble_ex(const sr_tensor* lr, const sr_tensor* coeff, const sr_tensor* dict,

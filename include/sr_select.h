@@ -48,7 +48,7 @@ size_t sr_atom_gram_workspace_bytes(int L);
  * Normal equations of Eq. 7.
  *
  *   up      [N][C][H][W]  f32   the up-sampled image (output of sr_bicubic_upsample)
- *   coeff   [N][L][H][W]  f32, f16 or f8e4m3   Phi
+ *   coeff   [N][L][H][W]  f32, f16, bf16 or f8e4m3   Phi
  *   dict    [1][L][k][k]  f32   D
  *   target  [N][C][H][W]  f32   ground truth h
  *   stride  >= 1: HR pixels (Y, X) with Y % stride == 0 and X % stride == 0 are the samples

@@ -23,8 +23,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.environ.get("SR_ORACLE_SRC") or os.path.join(_HERE, "sr_oracle.c")
 _LIB = os.environ.get("SR_ORACLE_LIB") or os.path.join(_HERE, "libsr_oracle.so")
 
-# uint8 arrays are stored 8-bit E4M3 floats (numpy has no such dtype)
-_DT = {np.dtype(np.float32): 0, np.dtype(np.float16): 1, np.dtype(np.float64): 2, np.dtype(np.uint8): 3}
+# uint8 arrays are stored 8-bit E4M3 floats, uint16 arrays stored bfloat16 (numpy has no such dtypes)
+_DT = {np.dtype(np.float32): 0, np.dtype(np.float16): 1, np.dtype(np.float64): 2, np.dtype(np.uint8): 3,
+       np.dtype(np.uint16): 4}
 
 
 def build(force: bool = False) -> str:
@@ -50,6 +51,8 @@ def _load():
         lib.orc_half_to_double.argtypes = [ctypes.c_uint16]
         lib.orc_e4m3_to_double.restype = c_dbl
         lib.orc_e4m3_to_double.argtypes = [ctypes.c_uint8]
+        lib.orc_bf16_to_double.restype = c_dbl
+        lib.orc_bf16_to_double.argtypes = [ctypes.c_uint16]
         lib.orc_keys.restype = c_dbl
         lib.orc_keys.argtypes = [c_dbl, c_dbl]
         lib.orc_taps.restype = None
@@ -78,7 +81,7 @@ def _stored(a, name):
     """The caller's stored bytes, untouched: fp16/fp32/fp64, C-contiguous."""
     a = np.asarray(a)
     if a.dtype not in _DT:
-        raise TypeError(f"{name}: dtype {a.dtype} not one of float16/32/64 or uint8 (= stored E4M3)")
+        raise TypeError(f"{name}: dtype {a.dtype} not one of float16/32/64, uint8 (= stored E4M3) or uint16 (= stored bfloat16)")
     return np.ascontiguousarray(a)
 
 
@@ -88,6 +91,10 @@ def half_to_double(bits: int) -> float:
 
 def e4m3_to_double(bits: int) -> float:
     return _load().orc_e4m3_to_double(int(bits) & 0xFF)
+
+
+def bf16_to_double(bits: int) -> float:
+    return _load().orc_bf16_to_double(int(bits) & 0xFFFF)
 
 
 def keys(t: float, a: float = -0.5) -> float:
@@ -114,8 +121,8 @@ def set_threads(n: int) -> int:
 def bicubic(lr, scale: int, a: float = -0.5) -> np.ndarray:
     """Stage 1: ``lr`` [N][C][h][w] -> float64 [N][C][s*h][s*w]."""
     lr = _stored(lr, "lr")
-    if lr.dtype == np.uint8:
-        raise TypeError("lr: stored E4M3 is a coefficient format only")
+    if lr.dtype in (np.uint8, np.uint16):
+        raise TypeError("lr: stored E4M3 and bfloat16 are coefficient formats only")
     if lr.ndim != 4:
         raise ValueError("lr must be [N][C][h][w]")
     n, c, h, w = lr.shape

@@ -47,6 +47,9 @@ def atom_responses(U, coeff, dictionary, stride=1):
     if coeff.dtype == np.uint8:                      # stored 8-bit E4M3 floats, widened by the assembly oracle's decoder
         from . import e4m3_to_double
         coeff = np.array([e4m3_to_double(b) for b in range(256)])[coeff]
+    elif coeff.dtype == np.uint16:                   # stored bfloat16, likewise
+        from . import bf16_to_double
+        coeff = np.array([bf16_to_double(b) for b in range(65536)])[coeff]
     coeff = coeff.astype(np.float64)
     D = np.asarray(dictionary, dtype=np.float64)
     n, c, H, W = U.shape

@@ -39,7 +39,8 @@
  * bicubic at that library's own a, delta atoms, linearity, constant
  * preservation, an exact-rational apply-then-weight evaluator, a library
  * unfold + einsum for stages 3 + 4; the 8-bit E4M3 decoder by hand-computed
- * codes and a library decoder over all 256 codes (tests/test_oracle_fp8.py).
+ * codes and a library decoder over all 256 codes (tests/test_oracle_fp8.py), the
+ * bfloat16 decoder likewise over all 65536 codes.
  * No function here is unpinned.
  */
 #include <math.h>
@@ -50,7 +51,7 @@
 #include <omp.h>
 #endif
 
-enum { ORC_F32 = 0, ORC_F16 = 1, ORC_F64 = 2, ORC_F8E4M3 = 3 };
+enum { ORC_F32 = 0, ORC_F16 = 1, ORC_F64 = 2, ORC_F8E4M3 = 3, ORC_BF16 = 4 };
 
 /* IEEE binary16 bit pattern -> double, exactly (subnormals, inf, nan). */
 double orc_half_to_double(uint16_t h)
@@ -91,12 +92,34 @@ double orc_e4m3_to_double(uint8_t b)
     return sign ? -v : v;
 }
 
+/*
+ * bfloat16 (1 sign, 8 exponent bits with bias 127, 7 mantissa bits: the upper
+ * half of an IEEE binary32, so exponent field 0 holds subnormals m * 2^-133 and
+ * 255 infinities and NaNs) -> double, exactly.  A storage format for
+ * coefficients only: what a network that runs in bfloat16 produces.
+ */
+double orc_bf16_to_double(uint16_t b)
+{
+    int sign = (b >> 15) & 1;
+    int e = (b >> 7) & 0xff;
+    int m = b & 0x7f;
+    double v;
+    if (e == 0)
+        v = ldexp((double)m, -133);
+    else if (e == 255)
+        v = m ? NAN : INFINITY;
+    else
+        v = ldexp((double)(m + 128), e - 134);
+    return sign ? -v : v;
+}
+
 static double load_elem(const void *p, int dtype, size_t i)
 {
     switch (dtype) {
     case ORC_F32: return (double)((const float *)p)[i];
     case ORC_F16: return orc_half_to_double(((const uint16_t *)p)[i]);
     case ORC_F8E4M3: return orc_e4m3_to_double(((const uint8_t *)p)[i]);
+    case ORC_BF16: return orc_bf16_to_double(((const uint16_t *)p)[i]);
     default:      return ((const double *)p)[i];
     }
 }

@@ -13,7 +13,7 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsrdict.so")
 
-SR_F32, SR_F16, SR_F8E4M3 = 0, 1, 2
+SR_F32, SR_F16, SR_F8E4M3, SR_BF16 = 0, 1, 2, 3
 SR_KERNEL_AUTO, SR_KERNEL_GENERIC, SR_KERNEL_MFMA = 0, 1, 2
 SR_MAX_ATOMS = 256
 
@@ -88,8 +88,10 @@ def describe(t) -> sr_tensor:
         code = SR_F16
     elif t.dtype == torch.float8_e4m3fn:
         code = SR_F8E4M3
+    elif t.dtype == torch.bfloat16:
+        code = SR_BF16
     else:
-        raise TypeError(f"dtype {t.dtype} is not float32/float16/float8_e4m3fn")
+        raise TypeError(f"dtype {t.dtype} is not float32/float16/float8_e4m3fn/bfloat16")
     ptr = t.data_ptr() if t.numel() else 0
     return sr_tensor(ptr or None, code, *[int(v) for v in t.shape])
 

@@ -9,9 +9,9 @@ using namespace srd;
 
 namespace {
 
-size_t elem_size(sr_dtype d) { return d == SR_F16 ? 2 : (d == SR_F8E4M3 ? 1 : 4); }
+size_t elem_size(sr_dtype d) { return (d == SR_F16 || d == SR_BF16) ? 2 : (d == SR_F8E4M3 ? 1 : 4); }
 bool dtype_ok(int d) { return d == SR_F32 || d == SR_F16; }                    // images
-bool coeff_dtype_ok(int d) { return dtype_ok(d) || d == SR_F8E4M3; }           // coefficients
+bool coeff_dtype_ok(int d) { return dtype_ok(d) || d == SR_F8E4M3 || d == SR_BF16; }   // coefficients
 
 size_t tensor_bytes(const sr_tensor* t) {
     return (size_t)t->n * t->c * t->h * t->w * elem_size(t->dtype);

@@ -50,6 +50,11 @@ struct f8e4m3 { unsigned char bits; };
 __device__ __forceinline__ float ld_as_float(const f8e4m3* p, size_t i) {
     return __builtin_amdgcn_cvt_f32_fp8((int)p[i].bits, 0);
 }
+// bfloat16 coefficient, two bytes each: the upper half of a binary32
+struct bf16raw { unsigned short bits; };
+__device__ __forceinline__ float ld_as_float(const bf16raw* p, size_t i) {
+    return __uint_as_float((unsigned)p[i].bits << 16);
+}
 __device__ __forceinline__ void st_from_float(float* p, size_t i, float v) { p[i] = v; }
 // fp32 -> fp16 with the fp32 value materialised first: the empty asm keeps the
 // compiler from folding the producing fma and the narrowing into one

@@ -204,6 +204,8 @@ hipError_t launch_generic(const AssembleArgs& a, int k, bool io_f16, hipStream_t
         return io_f16 ? launch_generic_k<__half, __half>(a, k, st) : launch_generic_k<__half, float>(a, k, st);
     if (a.coeff_dtype == SR_F8E4M3)
         return io_f16 ? launch_generic_k<f8e4m3, __half>(a, k, st) : launch_generic_k<f8e4m3, float>(a, k, st);
+    if (a.coeff_dtype == SR_BF16)
+        return io_f16 ? launch_generic_k<bf16raw, __half>(a, k, st) : launch_generic_k<bf16raw, float>(a, k, st);
     return io_f16 ? launch_generic_k<float, __half>(a, k, st) : launch_generic_k<float, float>(a, k, st);
 }
 

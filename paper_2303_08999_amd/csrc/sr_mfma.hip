@@ -13,6 +13,7 @@ hipError_t launch_mfma_k7_f32(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_k5_f8(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_k7_f8(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_k5_big(const AssembleArgs& a, int np8, hipStream_t st);
+hipError_t launch_mfma_bf16(const AssembleArgs& a, int k, int np8, hipStream_t st);
 
 namespace {
 
@@ -23,6 +24,11 @@ constexpr int N_TILE_SHAPES = 6;
 // only: padding atoms meet zero dictionary rows and re-read a cached plane.
 int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
     const int need = (n_fold + 7) / 8;
+    if (coeff_dtype == SR_BF16) {                                       // bfloat16 coefficients
+        if (k == 5 && (channels == 1 || channels == 3)) return need <= 1 ? 1 : (need <= 4 ? 4 : (need <= 9 ? 9 : 0));
+        if (k == 7 && channels == 3) return need <= 9 ? 9 : (need <= 16 ? 16 : 0);
+        return 0;
+    }
     if (channels == 2 || channels == 4)                                 // 5x5, fp16 coefficients: 32 and 72 atoms
         return (k == 5 && coeff_dtype == SR_F16 && need <= 9) ? (need <= 4 ? 4 : 9) : 0;
     if (k == 3) {                                                       // 3x3: up to 72 atoms
@@ -55,9 +61,11 @@ int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
 // An image's coefficients beyond 4 GB: byte offsets no longer fit 32 bits.  Instantiations
 // with element offsets exist for 5x5 atoms, three channels, fp16 coefficients (an 8K frame
 // with 72 planes), in capacities 1, 4 and 9.
+unsigned long long coeff_bytes(int coeff_dtype) {
+    return coeff_dtype == SR_F32 ? 4ull : (coeff_dtype == SR_F8E4M3 ? 1ull : 2ull);
+}
 bool beyond_4gb(const AssembleArgs& a, int coeff_dtype) {
-    const unsigned long long cb = coeff_dtype == SR_F32 ? 4ull : (coeff_dtype == SR_F16 ? 2ull : 1ull);
-    return (unsigned long long)a.L * a.H * a.W * cb >= (1ull << 32);
+    return (unsigned long long)a.L * a.H * a.W * coeff_bytes(coeff_dtype) >= (1ull << 32);
 }
 int np8_big(int np8) { return np8 <= 1 ? 1 : (np8 <= 4 ? 4 : 9); }
 
@@ -74,7 +82,6 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
     // need not keep the groups' alignment (gfx950 global loads and stores take any
     // element-aligned address); a width that is not a whole number of groups needs
     // at least one full tile (128 columns), see tile_x0 in the kernel.
-    const unsigned long long cb = coeff_dtype == SR_F32 ? 4ull : (coeff_dtype == SR_F16 ? 2ull : 1ull);
     const int px = pixel_group(k, coeff_dtype);
     if (a.W < px || a.H < 1 || (a.W % px != 0 && a.W < 128)) return false;
     // the fp8 instantiations read the LR image as aligned 32-bit words: the image must start on one and,
@@ -94,6 +101,7 @@ hipError_t launch_mfma(const AssembleArgs& a, int k, bool io_f16, int tile, hipS
     (void)io_f16;
     const int np8 = np8_for(k, a.C, a.n_fold, a.coeff_dtype);
     if (beyond_4gb(a, a.coeff_dtype)) return launch_mfma_k5_big(a, np8_big(np8), st);
+    if (a.coeff_dtype == SR_BF16) return launch_mfma_bf16(a, k, np8, st);
     if (k == 3) return launch_mfma_k3(a, np8, st);
     if (a.coeff_dtype == SR_F32) return k == 5 ? launch_mfma_k5_f32(a, np8, st) : launch_mfma_k7_f32(a, np8, st);
     if (a.coeff_dtype == SR_F8E4M3) return k == 5 ? launch_mfma_k5_f8(a, np8, st) : launch_mfma_k7_f8(a, np8, st);

@@ -55,12 +55,14 @@ namespace srd {
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 // how the coefficients are stored (template argument CT of the kernel)
-constexpr int CT_F16 = 0, CT_F32 = 1, CT_F8 = 2;
+constexpr int CT_F16 = 0, CT_F32 = 1, CT_F8 = 2, CT_BF16 = 3;
 
 // SMIN: smallest scale the instantiation may be launched with.  The LR footprint
 // of a tile shrinks with the scale, so an instantiation for scale 4 only needs half
@@ -68,7 +70,7 @@ constexpr int CT_F16 = 0, CT_F32 = 1, CT_F8 = 2;
 // tile (fewer halo rows up-sampled per output row).
 template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int CT = CT_F16, int SMIN = 2>
 struct Cfg {
-    static constexpr bool F32 = CT == CT_F32, F8 = CT == CT_F8;
+    static constexpr bool F32 = CT == CT_F32, F8 = CT == CT_F8, BF = CT == CT_BF16;
     static constexpr int KK = K * K, R = (K - 1) / 2;
     static constexpr int RH0 = (K + 1) / 2;            // filter rows owned by lane half 0
     static constexpr int NSLOT = RH0 * K;              // accumulator rows used per half
@@ -119,6 +121,47 @@ __device__ __forceinline__ void plane_words(const RawV& r, unsigned (&w)[NWORD])
     }
 }
 
+// 16- and 8-atom steps of the fold on packed 16-bit operands: fp16, or (BF) bfloat16
+template <bool BF>
+__device__ __forceinline__ f32x16 mfma_16(const u32x4& a, const u32x4& b, const f32x16& c) {
+    if constexpr (BF)
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+template <bool BF>
+__device__ __forceinline__ f32x16 mfma_8(const u32x2& a, const u32x2& b, const f32x16& c) {
+    if constexpr (BF)
+        return __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(s16x4, a), __builtin_bit_cast(s16x4, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_bit_cast(f16x4, a), __builtin_bit_cast(f16x4, b), c, 0, 0, 0);
+}
+// Dictionary values as two 16-bit operands, d ~ hi + lo: 22 significant bits in fp16,
+// 16 in bfloat16 (whose coefficients carry 8).
+template <bool BF, int N, typename V>
+__device__ __forceinline__ void split_hi_lo(const float (&d)[N], V& hi, V& lo) {
+    unsigned short h[N], l[N];
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        if constexpr (BF) {
+            const __bf16 a = (__bf16)d[j];
+            const __bf16 b = (__bf16)(d[j] - (float)a);
+            h[j] = __builtin_bit_cast(unsigned short, a);
+            l[j] = __builtin_bit_cast(unsigned short, b);
+        } else {
+            const _Float16 a = (_Float16)d[j];
+            const _Float16 b = (_Float16)(d[j] - (float)a);
+            h[j] = __builtin_bit_cast(unsigned short, a);
+            l[j] = __builtin_bit_cast(unsigned short, b);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < N / 2; ++j) {
+        hi[j] = (unsigned)h[2 * j] | ((unsigned)h[2 * j + 1] << 16);
+        lo[j] = (unsigned)l[2 * j] | ((unsigned)l[2 * j + 1] << 16);
+    }
+}
+
 // (atom pair, pixel q) from two planes' packed pixels
 __device__ __forceinline__ unsigned pack_pair(unsigned plane_even, unsigned plane_odd, int q) {
     return __builtin_amdgcn_perm(plane_odd, plane_even, (q & 1) ? 0x07060302u : 0x05040100u);
@@ -141,7 +184,7 @@ template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT
 __global__ __launch_bounds__(64 * NW, WPE)
 void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y, const int ntiles) {
     using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN>;
-    constexpr bool F32 = F::F32, F8 = F::F8;
+    constexpr bool F32 = F::F32, F8 = F::F8, BF = F::BF;
     using Raw = typename RawT<PX * F::CB>::type;
     constexpr int NT = F::NT, P = F::P, NG = F::NG, UH = F::UH, UW = F::UW;
     constexpr int N16 = F::N16, N8 = F::N8, NMB = F::NMB;
@@ -207,29 +250,25 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     for (int e = tid0; e < N16 * NMB * 64; e += NT) {
         const int l = e & 63, blk = e >> 6, mb = blk % NMB, c16 = blk / NMB;
         const int tap = tap_of_row<K>(l & 31, mb);
-        f16x8 hi, lo;
+        float dv[8];
 #pragma unroll
-        for (int jj = 0; jj < 8; ++jj) {
-            const float d = dval(16 * c16 + 8 * (l >> 5) + jj, tap);
-            hi[jj] = (_Float16)d;
-            lo[jj] = (_Float16)(d - (float)hi[jj]);
-        }
-        A16[(blk * 2 + 0) * 64 + l] = __builtin_bit_cast(u32x4, hi);
-        A16[(blk * 2 + 1) * 64 + l] = __builtin_bit_cast(u32x4, lo);
+        for (int jj = 0; jj < 8; ++jj) dv[jj] = dval(16 * c16 + 8 * (l >> 5) + jj, tap);
+        u32x4 hi, lo;
+        split_hi_lo<BF, 8>(dv, hi, lo);
+        A16[(blk * 2 + 0) * 64 + l] = hi;
+        A16[(blk * 2 + 1) * 64 + l] = lo;
     }
     if (N8) {
         for (int e = tid0; e < NMB * 64; e += NT) {
             const int l = e & 63, mb = e >> 6;
             const int tap = tap_of_row<K>(l & 31, mb);
-            f16x4 hi, lo;
+            float dv[4];
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                const float d = dval(16 * N16 + 4 * (l >> 5) + jj, tap);
-                hi[jj] = (_Float16)d;
-                lo[jj] = (_Float16)(d - (float)hi[jj]);
-            }
-            A8[(mb * 2 + 0) * 64 + l] = __builtin_bit_cast(u32x2, hi);
-            A8[(mb * 2 + 1) * 64 + l] = __builtin_bit_cast(u32x2, lo);
+            for (int jj = 0; jj < 4; ++jj) dv[jj] = dval(16 * N16 + 4 * (l >> 5) + jj, tap);
+            u32x2 hi, lo;
+            split_hi_lo<BF, 4>(dv, hi, lo);
+            A8[(mb * 2 + 0) * 64 + l] = hi;
+            A8[(mb * 2 + 1) * 64 + l] = lo;
         }
     }
     __syncthreads();
@@ -519,12 +558,11 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         }
 #pragma unroll
         for (int c16 = 0; c16 < N16; ++c16) {
-            f16x8 av[NMB][2];
+            u32x4 av[NMB][2];
 #pragma unroll
             for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
-                for (int hl = 0; hl < 2; ++hl)
-                    av[mb][hl] = __builtin_bit_cast(f16x8, A16[((c16 * NMB + mb) * 2 + hl) * 64 + lane]);
+                for (int hl = 0; hl < 2; ++hl) av[mb][hl] = A16[((c16 * NMB + mb) * 2 + hl) * 64 + lane];
             constexpr int NWORD = PX / 2 > 0 ? PX / 2 : 1;
             unsigned cw[8][NWORD];                  // the step's 8 planes as fp16 pixel pairs
 #pragma unroll
@@ -534,12 +572,10 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 u32x4 bw;
 #pragma unroll
                 for (int m = 0; m < 4; ++m) bw[m] = pack_pair(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q);
-                const f16x8 b = __builtin_bit_cast(f16x8, bw);
 #pragma unroll
                 for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
-                    for (int hl = 0; hl < 2; ++hl)
-                        acc[q][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av[mb][hl], b, acc[q][mb], 0, 0, 0);
+                    for (int hl = 0; hl < 2; ++hl) acc[q][mb] = mfma_16<BF>(av[mb][hl], bw, acc[q][mb]);
             }
             __builtin_amdgcn_sched_barrier(0);
             if (more) {
@@ -550,12 +586,11 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             __builtin_amdgcn_sched_barrier(0);
         }
         if (N8) {
-            f16x4 av[NMB][2];
+            u32x2 av[NMB][2];
 #pragma unroll
             for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
-                for (int hl = 0; hl < 2; ++hl)
-                    av[mb][hl] = __builtin_bit_cast(f16x4, A8[(mb * 2 + hl) * 64 + lane]);
+                for (int hl = 0; hl < 2; ++hl) av[mb][hl] = A8[(mb * 2 + hl) * 64 + lane];
             constexpr int NWORD = PX / 2 > 0 ? PX / 2 : 1;
             unsigned cw[4][NWORD];
 #pragma unroll
@@ -565,12 +600,10 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 u32x2 bw;
 #pragma unroll
                 for (int m = 0; m < 2; ++m) bw[m] = pack_pair(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q);
-                const f16x4 b = __builtin_bit_cast(f16x4, bw);
 #pragma unroll
                 for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
-                    for (int hl = 0; hl < 2; ++hl)
-                        acc[q][mb] = __builtin_amdgcn_mfma_f32_32x32x8f16(av[mb][hl], b, acc[q][mb], 0, 0, 0);
+                    for (int hl = 0; hl < 2; ++hl) acc[q][mb] = mfma_8<BF>(av[mb][hl], bw, acc[q][mb]);
             }
             __builtin_amdgcn_sched_barrier(0);
             if (more) {

@@ -55,6 +55,8 @@ struct e4m3 { unsigned char bits; };        // 8-bit E4M3 storage, widened exact
 __device__ __forceinline__ float widen(float v) { return v; }
 __device__ __forceinline__ float widen(__half v) { return __half2float(v); }
 __device__ __forceinline__ float widen(e4m3 v) { return __builtin_amdgcn_cvt_f32_fp8((int)v.bits, 0); }
+struct bf16v { unsigned short bits; };      // bfloat16 storage: the upper half of a binary32
+__device__ __forceinline__ float widen(bf16v v) { return __uint_as_float((unsigned)v.bits << 16); }
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
 // q-th block of the upper triangle of an n x n block matrix, row-major: (bi, bj) with bi <= bj
@@ -779,7 +781,8 @@ int sr_atom_gram(const sr_tensor* up, const sr_tensor* coeff, const sr_tensor* d
                  double* normal, void* stream) {
     if (!up || !coeff || !dict || !target || !normal) return SR_ERR_NULL;
     if (up->dtype != SR_F32 || target->dtype != SR_F32 || dict->dtype != SR_F32 ||
-        (coeff->dtype != SR_F32 && coeff->dtype != SR_F16 && coeff->dtype != SR_F8E4M3)) return SR_ERR_UNSUPPORTED;
+        (coeff->dtype != SR_F32 && coeff->dtype != SR_F16 && coeff->dtype != SR_F8E4M3 && coeff->dtype != SR_BF16))
+        return SR_ERR_UNSUPPORTED;
     if ((k != 3 && k != 5 && k != 7) || L < 1 || L > SR_SELECT_MAX_ATOMS || channels < 1 ||
         channels > SR_MAX_CHANNELS || stride < 1) return SR_ERR_UNSUPPORTED;
     if (up->n < 0 || up->c < 0 || up->h < 0 || up->w < 0) return SR_ERR_SHAPE;
@@ -794,7 +797,7 @@ int sr_atom_gram(const sr_tensor* up, const sr_tensor* coeff, const sr_tensor* d
     if (!empty) {
         if (!up->data || !coeff->data || !dict->data || !target->data) return SR_ERR_NULL;
         if ((uintptr_t)up->data % 4 || (uintptr_t)target->data % 4 || (uintptr_t)dict->data % 4 ||
-            (uintptr_t)coeff->data % (coeff->dtype == SR_F16 ? 2 : (coeff->dtype == SR_F32 ? 4 : 1))) return SR_ERR_ALIGN;
+            (uintptr_t)coeff->data % (coeff->dtype == SR_F32 ? 4 : (coeff->dtype == SR_F8E4M3 ? 1 : 2))) return SR_ERR_ALIGN;
     }
     GramArgs a;
     a.up = (const float*)up->data; a.coeff = coeff->data; a.dict = (const float*)dict->data;
@@ -834,6 +837,7 @@ int sr_atom_gram(const sr_tensor* up, const sr_tensor* coeff, const sr_tensor* d
     do {                                                                                                    \
         if (coeff->dtype == SR_F16) SR_GRAM_LAUNCH_T(KS, __half);                                           \
         else if (coeff->dtype == SR_F32) SR_GRAM_LAUNCH_T(KS, float);                                       \
+        else if (coeff->dtype == SR_BF16) SR_GRAM_LAUNCH_T(KS, bf16v);                                      \
         else SR_GRAM_LAUNCH_T(KS, e4m3);                                                                    \
     } while (0)
     switch (k) {

@@ -48,7 +48,7 @@ class Workload:
     scale: int
     L: int
     k: int
-    coeff_dtype: str     # "f32" | "f16" | "f8" (8-bit E4M3 storage)
+    coeff_dtype: str     # "f32" | "f16" | "f8" (8-bit E4M3 storage) | "bf16"
     lr_dtype: str        # "f32" | "f16"  (the output has the LR dtype)
     logit_mean: float = 0.0
     logit_var: float = 1.0
@@ -69,7 +69,7 @@ class Workload:
     def algorithmic_bytes(self, n_read_atoms=None):
         """Bytes per launch that must cross HBM: every read coefficient once,
         the output once, the LR image once."""
-        b_c = {"f32": 4, "f16": 2, "f8": 1}[self.coeff_dtype]
+        b_c = {"f32": 4, "f16": 2, "f8": 1, "bf16": 2}[self.coeff_dtype]
         b_io = 2 if self.lr_dtype == "f16" else 4
         atoms = self.L if n_read_atoms is None else n_read_atoms
         per_px = atoms * b_c + self.c * b_io + self.c * b_io / (self.scale ** 2)
@@ -84,6 +84,8 @@ WORKLOADS = {
     # the 4K frame with the coefficients stored as 8-bit floats (same seed: the same
     # softmax values, rounded to E4M3 instead of fp16)
     "4k_dense_fp8": Workload("4k_dense_fp8", 3, 1, 3, 540, 960, 4, 72, 5, "f8", "f32"),
+    # ... and as bfloat16 (what a network running in bfloat16 hands over)
+    "4k_dense_bf16": Workload("4k_dense_bf16", 3, 1, 3, 540, 960, 4, 72, 5, "bf16", "f32"),
     "4k_selective": Workload("4k_selective", 3, 1, 3, 540, 960, 4, 72, 5, "f16", "f32", 0.0, 1.0, 8),
     "video": Workload("video", 4, 16, 3, 270, 480, 4, 128, 7, "f16", "f16"),
     # beyond the stated list: 1080p x4, whose 72 fp16 planes (4.8 GB) exceed 32-bit byte offsets
@@ -97,14 +99,16 @@ def scaled(wl: Workload, **kw) -> Workload:
 
 
 def torch_dtype(code: str):
-    return {"f32": torch.float32, "f16": torch.float16, "f8": torch.float8_e4m3fn}[code]
+    return {"f32": torch.float32, "f16": torch.float16, "f8": torch.float8_e4m3fn, "bf16": torch.bfloat16}[code]
 
 
 def stored_numpy(t):
     """The stored bytes of a tensor as a numpy array on the host: fp16/fp32 as they are,
-    8-bit E4M3 floats as uint8 (numpy has no such dtype)."""
+    8-bit E4M3 floats as uint8 and bfloat16 as uint16 (numpy has no such dtypes)."""
     if t.dtype == torch.float8_e4m3fn:
         return t.view(torch.uint8).cpu().numpy()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
     return t.cpu().numpy()
 
 

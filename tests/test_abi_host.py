@@ -109,6 +109,25 @@ def test_plan_for_images_with_more_than_4_gb_of_coefficients(lib):
     assert plan(*big(), opts=sr.make_options(sr.SR_KERNEL_MFMA)) == sr.SR_KERNEL_MFMA
 
 
+def test_plan_for_bfloat16_coefficients(lib):
+    BF = sr.SR_BF16
+    assert plan(*case(cd=BF)) == sr.SR_KERNEL_MFMA
+    assert plan(*case(cd=BF, C=1), C=1) == sr.SR_KERNEL_MFMA
+    assert plan(*case(cd=BF, C=2), C=2) == sr.SR_KERNEL_GENERIC          # two and four channels: fp16 only
+    assert plan(*case(cd=BF, k=3), k=3) == sr.SR_KERNEL_GENERIC          # 3x3: not built for bfloat16
+    assert plan(*case(cd=BF, k=7, L=128), k=7, L=128) == sr.SR_KERNEL_MFMA
+    assert plan(*case(cd=BF, k=7, L=128, C=1), k=7, L=128, C=1) == sr.SR_KERNEL_GENERIC
+    assert plan(*case(cd=BF, L=73), L=73) == sr.SR_KERNEL_GENERIC
+    assert plan(*case(cd=BF), kept=[0, 3, 9]) == sr.SR_KERNEL_MFMA
+    lr, coeff, d, out = case(cd=BF)
+    coeff.data = 0x11000001                                              # two-byte elements need two-byte alignment
+    assert plan(lr, coeff, d, out) == -7
+    lrb, coeff, d, out = case(io=BF)
+    assert plan(lrb, coeff, d, out) == -3                                # images cannot be bfloat16
+    lr, coeff, d, out = case()
+    assert plan(lr, coeff, T(0x18000000, BF, 1, 72, 5, 5), out) == -3    # nor the dictionary
+
+
 def test_null_pointers(lib):
     lr, coeff, d, out = case()
     assert plan(None, coeff, d, out) == -1

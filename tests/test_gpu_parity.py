@@ -65,7 +65,7 @@ def check_full(oracle, wl, kernel, kept=None, gamma=None, inp=None, tile=0):
     hi = host(inp)
     ref = oracle.dict_assemble(hi["lr"], hi["coeff"], hi["dict"], wl.scale, kept=kept, gamma=gamma)
     assert not np.isnan(got).any(), "some output pixel was never written"
-    worst, tol, ok = tolerance_ok(got, ref, wl.coeff_dtype in ("f16", "f8"), wl.lr_dtype == "f16")
+    worst, tol, ok = tolerance_ok(got, ref, wl.coeff_dtype in ("f16", "f8", "bf16"), wl.lr_dtype == "f16")
     assert ok, f"{wl.name}: worst error {worst:.3e} exceeds {tol:.0e}"
     return worst
 
@@ -171,6 +171,39 @@ def test_8k_frame_with_more_than_4_gb_of_coefficients(oracle):
         assert float(np.abs(have[0][:, pts[:, 1], pts[:, 2]].T - want).max()) <= 2e-3, f"{n_keep} kept atoms"
 
 
+def test_4k_dense_bf16_full_frame(oracle):
+    """The 4K frame with bfloat16 coefficients: every output against the oracle, which widens
+    the same stored bits."""
+    wl = sr_synth.WORKLOADS["4k_dense_bf16"]
+    inp = sr_synth.make_inputs(wl, DEV)
+    assert planned(inp, wl, sr.SR_KERNEL_AUTO) == MFMA
+    got = run_gpu(inp, wl, sr.SR_KERNEL_AUTO).cpu().numpy()
+    hi = host(inp)
+    assert hi["coeff"].dtype == np.uint16
+    ref = oracle.dict_assemble(hi["lr"], hi["coeff"], hi["dict"], wl.scale)
+    err = np.abs(got.astype(np.float64) - ref)
+    assert not np.isnan(got).any()
+    assert float(err.max()) <= 2e-3, f"worst error {err.max():.3e}"
+    # the dictionary enters as two bfloat16 operands (16 significant bits): far inside the bound
+    assert float(err.max()) <= 1e-4, f"worst error {err.max():.3e}"
+
+
+def test_bfloat16_coefficients_beyond_the_fp16_range(oracle):
+    """Coefficients of 1e6 and 1e-30 (neither representable in fp16) with atoms scaled to
+    bring the result back to order one: both kernels widen bfloat16 exactly."""
+    wl = sr_synth.Workload("bfr", 61, 1, 3, 40, 64, 4, 16, 5, "bf16", "f32")
+    inp = sr_synth.make_inputs(wl, DEV)
+    scale = torch.tensor([1e6, 1e-30] * 8, device=DEV).view(1, 16, 1, 1)
+    inp["coeff"] = (inp["coeff"].float() * scale).to(torch.bfloat16)
+    inp["dict"] = inp["dict"] / scale.view(16, 1, 1)
+    for kernel in (GENERIC, MFMA):
+        assert planned(inp, wl, kernel) == kernel
+        got = run_gpu(inp, wl, kernel).cpu().numpy()
+        hi = host(inp)
+        ref = oracle.dict_assemble(hi["lr"], hi["coeff"], hi["dict"], wl.scale)
+        assert float(np.abs(got - ref).max()) <= 2e-3, f"kernel {kernel}"
+
+
 def test_every_fp8_code_is_widened_as_the_oracle_does(oracle):
     """All 254 finite E4M3 codes, one per pixel, through a single centred delta atom on a
     constant image: the output IS the widened coefficient (both kernels, bit for bit)."""
@@ -242,6 +275,15 @@ RAGGED = [
     (31, 45, 4, 3, 9, 5, "f32", "f32", 1),      # ... few atoms
     (6, 8, 2, 16, 9, 3, "f16", "f32", 1),       # the largest channel count accepted
     (60, 128, 4, 3, 24, 5, "f16", "f32", 9),    # 540 tiles over 9 images: every XCD share crosses image borders
+    (33, 47, 4, 3, 72, 5, "bf16", "f32", 2),    # bfloat16 coefficients on the matrix-core path
+    (29, 36, 3, 1, 72, 5, "bf16", "f16", 1),    # ... one channel, fp16 image, x3
+    (17, 34, 4, 3, 7, 5, "bf16", "f32", 1),     # ... the 8-atom instantiation
+    (30, 41, 2, 3, 30, 5, "bf16", "f32", 1),    # ... the 32-atom instantiation, x2
+    (26, 31, 2, 3, 50, 5, "bf16", "f32", 1),    # ... HR width 62: generic kernel only
+    (12, 20, 4, 3, 100, 7, "bf16", "f16", 1),   # ... 7x7 atoms, the 128-atom instantiation
+    (22, 36, 3, 3, 60, 7, "bf16", "f32", 1),    # ... the 72-atom instantiation, x3
+    (23, 35, 4, 3, 72, 3, "bf16", "f32", 1),    # ... 3x3 atoms: generic kernel
+    (37, 53, 3, 3, 72, 5, "bf16", "f32", 1),    # ... HR width 159: the shifted last tile column
     (33, 47, 4, 3, 72, 5, "f8", "f32", 2),      # 8-bit E4M3 coefficients on the matrix-core path
     (29, 36, 3, 1, 72, 5, "f8", "f16", 1),      # ... one channel, fp16 image, x3
     (17, 34, 4, 3, 7, 5, "f8", "f32", 1),       # ... few atoms (the 8-atom instantiation)
@@ -305,6 +347,8 @@ BIG_RAGGED = [
     (233, 267, 3, 3, 72, 5, "f16", "f32", 1),   # 699 x 801: 128 x 16 tiles at x3, odd width
     (150, 170, 4, 3, 72, 5, "f16", "f16", 1),   # 600 x 680 = 0.41 Mpixel at x4: 64 x 16 tiles
     (171, 151, 4, 3, 72, 5, "f8", "f32", 1),    # 684 x 604: 128 x 24 tiles, 8-bit coefficients
+    (171, 151, 4, 3, 72, 5, "bf16", "f32", 1),  # ... bfloat16 coefficients
+    (130, 200, 3, 1, 72, 5, "bf16", "f16", 1),  # ... 128 x 16 tiles, one channel
     (200, 191, 4, 3, 72, 5, "f32", "f32", 1),   # 800 x 764 = 0.61 Mpixel: 64 x 32 tiles, fp32 coefficients
     (181, 240, 4, 3, 8, 5, "f16", "f32", 1),    # 8 atoms: 64 x 32 tiles at three workgroups per CU
     (121, 163, 4, 3, 128, 7, "f16", "f16", 2),  # 7x7: 64 x 24 tiles
@@ -333,7 +377,7 @@ def test_selective_kept_list_with_and_without_gamma(oracle, kernel):
     check_full(oracle, wl, kernel, kept=np.arange(71, -1, -1), inp=inp)
 
 
-@pytest.mark.parametrize("cd", ["f16", "f32", "f8"])
+@pytest.mark.parametrize("cd", ["f16", "f32", "f8", "bf16"])
 def test_kept_lists_around_every_built_capacity(oracle, cd):
     """The matrix-core kernel is built for 8/16/32/48/72 atoms (fewer sizes for some
     storage types); a kept list runs in the smallest one that holds it.  Lists one
@@ -378,7 +422,7 @@ def test_subnormal_only_coefficients_are_not_flushed(oracle, kernel):
     assert worst < 2e-3
 
 
-@pytest.mark.parametrize("cd,io", [("f16", "f32"), ("f16", "f16"), ("f32", "f32"), ("f8", "f32")])
+@pytest.mark.parametrize("cd,io", [("f16", "f32"), ("f16", "f16"), ("f32", "f32"), ("f8", "f32"), ("bf16", "f32")])
 def test_tensors_that_start_off_a_16_byte_boundary(oracle, cd, io):
     """Coefficients and output that start one element into their buffers (a slice of a
     larger allocation): the matrix-core kernel takes them, same values."""
@@ -396,7 +440,7 @@ def test_tensors_that_start_off_a_16_byte_boundary(oracle, cd, io):
     assert torch.isnan(obuf[0])
     hi = host(inp)
     ref = oracle.dict_assemble(hi["lr"], hi["coeff"], hi["dict"], wl.scale)
-    worst, tol, ok = tolerance_ok(oview.float().cpu().numpy(), ref, cd in ("f16", "f8"), io == "f16")
+    worst, tol, ok = tolerance_ok(oview.float().cpu().numpy(), ref, cd in ("f16", "f8", "bf16"), io == "f16")
     assert ok, f"worst error {worst:.3e} exceeds {tol:.0e}"
     assert torch.equal(oview, run_gpu(inp, wl, MFMA))
 

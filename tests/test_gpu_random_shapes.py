@@ -32,7 +32,7 @@ def draw(rng, index, max_h, max_w):
     s = int(rng.choice([2, 3, 4]))
     C = int(rng.choice([1, 2, 3, 3, 4]))
     N = int(rng.choice([1, 1, 2, 3, 9]))
-    cd = str(rng.choice(["f16", "f16", "f32", "f8"]))
+    cd = str(rng.choice(["f16", "f16", "f32", "f8", "bf16"]))
     io = str(rng.choice(["f32", "f16"]))
     L = int(rng.integers(1, 73)) if k != 7 else int(rng.choice([16, 72, 128, int(rng.integers(1, 129))]))
     h, w = int(rng.integers(1, max_h)), int(rng.integers(1, max_w))
@@ -61,7 +61,7 @@ def test_random_shapes_against_the_oracle(oracle):
                 continue
             got = run_gpu(inp, wl, kernel, kept, gamma, t).float().cpu().numpy()
             assert not np.isnan(got).any(), f"{wl}: some output pixel was never written"
-            worst, tol, ok = tolerance_ok(got, ref, wl.coeff_dtype in ("f16", "f8"), wl.lr_dtype == "f16")
+            worst, tol, ok = tolerance_ok(got, ref, wl.coeff_dtype in ("f16", "f8", "bf16"), wl.lr_dtype == "f16")
             assert ok, f"{wl} kept {kept} tile {t} kernel {kernel}: worst error {worst:.3e} exceeds {tol:.0e}"
             checked[kernel] += 1
     assert checked[GENERIC] == 96 and checked[MFMA] >= 20, checked

@@ -21,6 +21,7 @@ CASES = [
     (1, 3, 40, 48, 4, 72, 5, "f16", 5),
     (1, 16, 6, 7, 2, 3, 3, "f32", 1),        # 16 channels
     (2, 3, 11, 14, 4, 40, 5, "f8", 2),       # coefficients stored as 8-bit E4M3
+    (1, 3, 40, 50, 4, 72, 5, "bf16", 1),     # ... as bfloat16, several runs per workgroup
     # more runs than workgroups, so that every workgroup walks several runs and channels
     (1, 3, 64, 80, 4, 72, 5, "f16", 1),      # 1280 runs of one lattice row segment each
     (1, 1, 96, 100, 4, 20, 5, "f32", 1),     # one channel: a new run every iteration, 2688 runs
