@@ -398,6 +398,8 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 
     // ---- stage 1 in three steps; a workgroup barrier separates each from the next.
     // (a) tap tables of a tile and its LR footprint, registers -> LDS
+    // the first UW threads fill the column tables, UH of the last 64 the row tables
+    static_assert(UH <= 64 && UW <= NT - 64, "tile too large for the table set-up");
     auto stage1_setup = [&](const TilePos tp, int tid) {
         const int lane = tid & 63;
         const int Y0 = tp.ty * F::TH, X0 = tile_x0(tp.tx);
