@@ -59,7 +59,7 @@ int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
 }
 
 // An image's coefficients beyond 4 GB: byte offsets no longer fit 32 bits.  Instantiations
-// with element offsets exist for 5x5 atoms, three channels, fp16 coefficients (an 8K frame
+// with element offsets exist for 5x5 atoms, three channels, fp16 or bfloat16 coefficients (an 8K frame
 // with 72 planes), in capacities 1, 4 and 9.
 unsigned long long coeff_bytes(int coeff_dtype) {
     return coeff_dtype == SR_F32 ? 4ull : (coeff_dtype == SR_F8E4M3 ? 1ull : 2ull);
@@ -89,7 +89,8 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
     if (coeff_dtype == SR_F8E4M3 &&
         (((uintptr_t)a.lr % 4) != 0 || (a.io_f16 && (((unsigned long long)a.N * a.C * a.h * a.w) & 1ull)))) return false;
     if (beyond_4gb(a, coeff_dtype) &&                                                      // 32-bit plane offsets
-        !(k == 5 && a.C == 3 && coeff_dtype == SR_F16 && (unsigned long long)a.L * a.H * a.W < (1ull << 32)))
+        !(k == 5 && a.C == 3 && (coeff_dtype == SR_F16 || coeff_dtype == SR_BF16) &&
+          (unsigned long long)a.L * a.H * a.W < (1ull << 32)))
         return false;
     if ((unsigned long long)a.N * a.C * a.H * a.W * 4ull >= (1ull << 32)) return false;   // 32-bit image offsets
     if (np8_for(k, a.C, a.n_fold, coeff_dtype) == 0) return false;

@@ -102,6 +102,7 @@ def test_plan_for_images_with_more_than_4_gb_of_coefficients(lib):
     assert plan(*big()) == sr.SR_KERNEL_MFMA
     assert plan(*big(), kept=[1, 5, 71]) == sr.SR_KERNEL_MFMA
     assert plan(*big(cd=sr.SR_F8E4M3)) == sr.SR_KERNEL_MFMA          # 2.4 GB: ordinary byte offsets
+    assert plan(*big(cd=sr.SR_BF16)) == sr.SR_KERNEL_MFMA
     assert plan(*big(C=1), C=1) == sr.SR_KERNEL_GENERIC
     assert plan(*big(cd=sr.SR_F32)) == sr.SR_KERNEL_GENERIC
     assert plan(*big(L=128, k=7), L=128, k=7) == sr.SR_KERNEL_GENERIC

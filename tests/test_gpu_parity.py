@@ -169,6 +169,15 @@ def test_8k_frame_with_more_than_4_gb_of_coefficients(oracle):
         have = run_gpu(inp, wl, sr.SR_KERNEL_AUTO, kept=kept, gamma=gamma).cpu().numpy()
         want = oracle.assemble_points(U, hi["coeff"], hi["dict"], pts, kept=kept, gamma=gamma)
         assert float(np.abs(have[0][:, pts[:, 1], pts[:, 2]].T - want).max()) <= 2e-3, f"{n_keep} kept atoms"
+    # the same frame with its coefficients as bfloat16: sampled pixels of the dense call
+    del inp["coeff"]
+    wlb = sr_synth.scaled(wl, coeff_dtype="bf16")
+    inp["coeff"] = sr_synth.make_coeff(wlb, DEV)
+    assert planned(inp, wlb, sr.SR_KERNEL_AUTO) == MFMA
+    have = run_gpu(inp, wlb, sr.SR_KERNEL_AUTO).cpu().numpy()
+    assert not np.isnan(have).any()
+    want = oracle.assemble_points(U, sr_synth.stored_numpy(inp["coeff"]), hi["dict"], pts)
+    assert float(np.abs(have[0][:, pts[:, 1], pts[:, 2]].T - want).max()) <= 2e-3, "bfloat16"
 
 
 def test_4k_dense_bf16_full_frame(oracle):
