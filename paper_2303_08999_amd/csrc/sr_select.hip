@@ -261,20 +261,21 @@ __global__ __launch_bounds__(NT, (N16 <= 5 && K <= 5) ? 2 : 1) void k_atom_gram(
 
 // ---------------------------------------------------------------------------
 // Second form of the kernel, for lattice strides up to 4 (every pixel down to every
-// fourth): one workgroup of eight wavefronts per CU.  Four wavefronts form the
+// fourth): workgroups of eight wavefronts, one or two per CU.  Four wavefronts form the
 // responses of one (run, channel) while the other four contract the tile of the
 // one before; two LDS tiles, one barrier per iteration.  A run is 64 consecutive
 // lattice samples of ONE lattice row, so the k image rows it needs are contiguous
 // segments and every atom's 64 coefficients one or a few cache lines.
 //
-// The contracting wavefronts have matrix-core work for less than half of an
-// iteration, so they also do every global load: two iterations ahead of the
-// responses they fetch the row segments and the target pixels (coalesced), and once
-// per run the coefficients (one atom's 64 samples per load), and park them in LDS.
-// The response wavefronts touch LDS only.  Their dot products D_l . B_p are a
-// contraction too, (samples x taps) . (taps x atoms), and run on the matrix cores
-// with the dictionary as a register-resident operand: no per-atom scalar loads or
-// broadcasts, whose latency a single wavefront per SIMD cannot hide.
+// Every global load is coalesced, requested a whole iteration before its data is
+// parked in LDS and two before it is read, and the duty is split by role so that
+// neither kind of wavefront waits for the other: the response wavefronts stage the
+// row segments of the next channel, the contracting ones fetch the coefficients and
+// target pixels of the next run (one atom's 64 samples per load) and park them
+// widened and masked.  The dot products D_l . B_p of the responses are a contraction
+// too, (samples x taps) . (taps x atoms), and run on the matrix cores with the
+// dictionary as a register-resident operand: no per-atom scalar loads or broadcasts,
+// whose latency a single wavefront per SIMD cannot hide.
 // ---------------------------------------------------------------------------
 constexpr int NT2 = 512;         // four response + four contraction wavefronts
 constexpr int GRID2 = 256;       // one workgroup per CU (two where registers and LDS allow)
