@@ -97,7 +97,7 @@ typedef struct {
  * Dense dictionary assembly (Eq. 2 / Eq. 3 with stage 1 fused in).
  *
  *   lr     [N][C][h][w]            f32 or f16   LR image x
- *   coeff  [N][L][s*h][s*w]        f32, f16 or f8e4m3   Phi, one plane per atom
+ *   coeff  [N][L][s*h][s*w]        f32, f16, bf16 or f8e4m3   Phi, one plane per atom
  *   dict   [1][L][k][k]            f32          D, row-major taps
  *   out    [N][C][s*h][s*w]        same dtype as lr; written
  *   L, k, scale, channels          must equal coeff->c, dict->h (= dict->w),
