@@ -64,6 +64,41 @@ def test_normal_equations_match_the_oracle(oracle, case):
     assert abs(hh - hh0) <= 1e-6 * hh0
 
 
+def test_normal_equations_on_random_shapes(oracle):
+    """Sixty seeded shapes over both kernel forms: every stride from 1 to 7, one to sixteen
+    channels, all four coefficient types, atom counts around every block boundary."""
+    rng = np.random.default_rng(5)
+    done = 0
+    while done < 60:
+        k = int(rng.choice([3, 5, 5, 7]))
+        s = int(rng.choice([2, 3, 4]))
+        C = int(rng.choice([1, 1, 2, 3, 3, 4, 7, 16]))
+        N = int(rng.choice([1, 1, 2, 3]))
+        cd = str(rng.choice(["f16", "bf16", "f32", "f8"]))
+        L = int(rng.choice([int(rng.integers(1, 129)), 72, 16, 31, 32, 33, 79, 80, 81, 128]))
+        stride = int(rng.choice([1, 1, 2, 3, 4, 5, 7]))
+        h, w = int(rng.integers(2, 60)), int(rng.integers(2, 120))
+        if L * C * h * w * s * s * N > 40e6:
+            continue
+        done += 1
+        wl = sr_synth.Workload("gramr", 300 + done, N, C, h, w, s, L, k, cd, "f32", 0.0, 1.5)
+        inp = sr_synth.make_inputs(wl, DEV)
+        up = torch.empty((N, C, wl.H, wl.W), device=DEV)
+        sr.sr_bicubic_upsample(inp["lr"], s, C, up)
+        g = torch.Generator(device=DEV).manual_seed(77 + done)
+        target = torch.rand((N, C, wl.H, wl.W), device=DEV, generator=g)
+        got = sr.sr_atom_gram(up, inp["coeff"], inp["dict"], target, L, k, C, stride).cpu().numpy()
+        G, b, hh, M = got[:L * L].reshape(L, L), got[L * L:L * L + L], got[L * L + L], got[L * L + L + 1]
+        G0, b0, hh0, M0 = so.normal_equations(up.cpu().numpy().astype(np.float64), sr_synth.stored_numpy(inp["coeff"]),
+                                              inp["dict"].cpu().numpy(), target.cpu().numpy(), stride)
+        case = (N, C, h, w, s, L, k, cd, stride)
+        scale = np.sqrt(np.outer(np.diag(G0), np.diag(G0)))
+        assert M == M0 and np.array_equal(G, G.T), case
+        assert np.abs(G - G0).max() <= 2e-5 * scale.max() and (np.abs(G - G0) <= 2e-5 * scale + 1e-12).all(), case
+        assert (np.abs(b - b0) <= 2e-5 * np.sqrt(np.diag(G0) * hh0) + 1e-12).all(), case
+        assert abs(hh - hh0) <= 1e-6 * hh0, case
+
+
 def test_empty_batch_and_undersized_scratch():
     wl, inp, up, target = _inputs(CASES[0])
     z = torch.empty((0, 3, wl.H, wl.W), device=DEV)
