@@ -40,7 +40,7 @@
  * preservation, an exact-rational apply-then-weight evaluator, a library
  * unfold + einsum for stages 3 + 4; the 8-bit E4M3 decoder by hand-computed
  * codes and a library decoder over all 256 codes (tests/test_oracle_fp8.py), the
- * bfloat16 decoder likewise over all 65536 codes.
+ * bfloat16 decoder likewise over all 65536 codes (tests/test_oracle_bf16.py).
  * No function here is unpinned.
  */
 #include <math.h>
