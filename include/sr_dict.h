@@ -133,7 +133,7 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
 /*
  * As sr_dict_assemble_selective (kept == NULL means dense), with an explicit
  * kernel choice; `opts` == NULL means SR_KERNEL_AUTO.  The matrix-core kernel
- * qualifies when C is 1 or 3 (or 2 or 4 with f16 coefficients and k = 5),
+ * qualifies when C is 1 or 3 (or 2 or 4 with f16 or bf16 coefficients and k = 5),
  * the tensors are small enough for 32-bit byte offsets (L*H*W*sizeof(coeff)
  * < 2^32, N*C*H*W < 2^30; with k = 5, C = 3 and f16 or bf16 coefficients an image of up
  * to 2^32 coefficients, e.g. an 8K frame with 72 planes, also qualifies: element
@@ -146,8 +146,8 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
  *                     128;
  *   f8  coefficients: as f32, and lr->data 4-byte aligned with an even number of
  *                     elements if the image is f16;
- *   bf16 coefficients: k = 5 with at most 72 folded atoms and C = 1 or 3, or k = 7
- *                     with at most 128 and C = 3.
+ *   bf16 coefficients: as f16, except that k = 7 takes at most 128 folded atoms in
+ *                     capacities of 72 and 128 only.
  * Every other supported case runs on the generic kernel.
  */
 int sr_dict_assemble_ex(const sr_tensor* lr, const sr_tensor* coeff, const sr_tensor* dict,

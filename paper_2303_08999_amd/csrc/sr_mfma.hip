@@ -24,13 +24,12 @@ constexpr int N_TILE_SHAPES = 6;
 // only: padding atoms meet zero dictionary rows and re-read a cached plane.
 int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
     const int need = (n_fold + 7) / 8;
-    if (coeff_dtype == SR_BF16) {                                       // bfloat16 coefficients
-        if (k == 5 && (channels == 1 || channels == 3)) return need <= 1 ? 1 : (need <= 4 ? 4 : (need <= 9 ? 9 : 0));
-        if (k == 7 && channels == 3) return need <= 9 ? 9 : (need <= 16 ? 16 : 0);
-        return 0;
+    if (channels == 2 || channels == 4)                                 // 5x5, 16-bit coefficients: 32 and 72 atoms
+        return (k == 5 && (coeff_dtype == SR_F16 || coeff_dtype == SR_BF16) && need <= 9) ? (need <= 4 ? 4 : 9) : 0;
+    if (coeff_dtype == SR_BF16 && k != 3) {                             // bfloat16 coefficients (3x3: below)
+        if (k == 5) return need <= 1 ? 1 : (need <= 4 ? 4 : (need <= 9 ? 9 : 0));
+        return need <= 9 ? 9 : (need <= 16 ? 16 : 0);
     }
-    if (channels == 2 || channels == 4)                                 // 5x5, fp16 coefficients: 32 and 72 atoms
-        return (k == 5 && coeff_dtype == SR_F16 && need <= 9) ? (need <= 4 ? 4 : 9) : 0;
     if (k == 3) {                                                       // 3x3: up to 72 atoms
         if (need > 9) return 0;
         return need <= 1 ? 1 : (need <= 4 ? 4 : 9);
@@ -102,7 +101,7 @@ hipError_t launch_mfma(const AssembleArgs& a, int k, bool io_f16, int tile, hipS
     (void)io_f16;
     const int np8 = np8_for(k, a.C, a.n_fold, a.coeff_dtype);
     if (beyond_4gb(a, a.coeff_dtype)) return launch_mfma_k5_big(a, np8_big(np8), st);
-    if (a.coeff_dtype == SR_BF16) return launch_mfma_bf16(a, k, np8, st);
+    if (a.coeff_dtype == SR_BF16 && k != 3) return launch_mfma_bf16(a, k, np8, st);
     if (k == 3) return launch_mfma_k3(a, np8, st);
     if (a.coeff_dtype == SR_F32) return k == 5 ? launch_mfma_k5_f32(a, np8, st) : launch_mfma_k7_f32(a, np8, st);
     if (a.coeff_dtype == SR_F8E4M3) return k == 5 ? launch_mfma_k5_f8(a, np8, st) : launch_mfma_k7_f8(a, np8, st);

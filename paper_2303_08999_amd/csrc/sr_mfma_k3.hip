@@ -29,6 +29,8 @@ hipError_t launch_mfma_k3(const AssembleArgs& a, int np8, hipStream_t st) {
         return a.C == 3 ? launch_k3_np8<3, CT_F32>(a, np8, st) : launch_k3_np8<1, CT_F32>(a, np8, st);
     if (a.coeff_dtype == SR_F8E4M3)
         return a.C == 3 ? launch_k3_np8<3, CT_F8>(a, np8, st) : launch_k3_np8<1, CT_F8>(a, np8, st);
+    if (a.coeff_dtype == SR_BF16)
+        return a.C == 3 ? launch_k3_np8<3, CT_BF16>(a, np8, st) : launch_k3_np8<1, CT_BF16>(a, np8, st);
     return a.C == 3 ? launch_k3_np8<3, CT_F16>(a, np8, st) : launch_k3_np8<1, CT_F16>(a, np8, st);
 }
 

@@ -114,10 +114,12 @@ def test_plan_for_bfloat16_coefficients(lib):
     BF = sr.SR_BF16
     assert plan(*case(cd=BF)) == sr.SR_KERNEL_MFMA
     assert plan(*case(cd=BF, C=1), C=1) == sr.SR_KERNEL_MFMA
-    assert plan(*case(cd=BF, C=2), C=2) == sr.SR_KERNEL_GENERIC          # two and four channels: fp16 only
-    assert plan(*case(cd=BF, k=3), k=3) == sr.SR_KERNEL_GENERIC          # 3x3: not built for bfloat16
+    assert plan(*case(cd=BF, C=2), C=2) == sr.SR_KERNEL_MFMA             # two and four channels: 5x5 only
+    assert plan(*case(cd=BF, C=4, k=7), C=4, k=7) == sr.SR_KERNEL_GENERIC
+    assert plan(*case(cd=BF, k=3), k=3) == sr.SR_KERNEL_MFMA
     assert plan(*case(cd=BF, k=7, L=128), k=7, L=128) == sr.SR_KERNEL_MFMA
-    assert plan(*case(cd=BF, k=7, L=128, C=1), k=7, L=128, C=1) == sr.SR_KERNEL_GENERIC
+    assert plan(*case(cd=BF, k=7, L=128, C=1), k=7, L=128, C=1) == sr.SR_KERNEL_MFMA
+    assert plan(*case(cd=BF, C=5), C=5) == sr.SR_KERNEL_GENERIC
     assert plan(*case(cd=BF, L=73), L=73) == sr.SR_KERNEL_GENERIC
     assert plan(*case(cd=BF), kept=[0, 3, 9]) == sr.SR_KERNEL_MFMA
     lr, coeff, d, out = case(cd=BF)

@@ -291,7 +291,11 @@ RAGGED = [
     (26, 31, 2, 3, 50, 5, "bf16", "f32", 1),    # ... HR width 62: generic kernel only
     (12, 20, 4, 3, 100, 7, "bf16", "f16", 1),   # ... 7x7 atoms, the 128-atom instantiation
     (22, 36, 3, 3, 60, 7, "bf16", "f32", 1),    # ... the 72-atom instantiation, x3
-    (23, 35, 4, 3, 72, 3, "bf16", "f32", 1),    # ... 3x3 atoms: generic kernel
+    (23, 35, 4, 3, 72, 3, "bf16", "f32", 1),    # ... 3x3 atoms
+    (24, 36, 3, 1, 20, 3, "bf16", "f16", 1),    # ... one channel, x3, fp16 image
+    (30, 41, 4, 2, 72, 5, "bf16", "f32", 1),    # ... two channels
+    (30, 41, 2, 4, 20, 5, "bf16", "f16", 2),    # ... four channels, 32-atom instantiation
+    (22, 36, 4, 1, 128, 7, "bf16", "f32", 1),   # ... 7x7, one channel
     (37, 53, 3, 3, 72, 5, "bf16", "f32", 1),    # ... HR width 159: the shifted last tile column
     (33, 47, 4, 3, 72, 5, "f8", "f32", 2),      # 8-bit E4M3 coefficients on the matrix-core path
     (29, 36, 3, 1, 72, 5, "f8", "f16", 1),      # ... one channel, fp16 image, x3
