@@ -40,7 +40,7 @@ def read_traffic(workload):
 def empirical_ceilings(sr, torch, wl, coeffs, outs, kernel_ms):
     """Secondary roofline context: the machine's own streaming rates for this byte mix,
     from the library's probes (no arithmetic in them), timed like the kernel."""
-    if wl.coeff_dtype != "f16" or wl.L not in (72, 128) or wl.hr_pixels % 128 or outs[0].dtype != torch.float32:
+    if wl.coeff_dtype not in ("f16", "bf16") or wl.L not in (72, 128) or wl.hr_pixels % 128 or outs[0].dtype != torch.float32:
         return None
     sink = torch.zeros(4, device="cuda", dtype=torch.int32)
 
