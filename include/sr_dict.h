@@ -138,16 +138,14 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
  * < 2^32, N*C*H*W < 2^30; with k = 5, C = 3 and f16 or bf16 coefficients an image of up
  * to 2^32 coefficients, e.g. an 8K frame with 72 planes, also qualifies: element
  * offsets), the HR width is a whole number of pixel groups (4
- * pixels; 2 for f32 coefficients and for f16 coefficients with k = 7) or at
+ * pixels; 2 for f32 coefficients and for f16 / bf16 coefficients with k = 7) or at
  * least 128, and
- *   f16 coefficients: k = 3 or 5 with at most 72 folded atoms, or k = 7 with at
- *                     most 128;
+ *   f16 and bf16 coefficients: k = 3 or 5 with at most 72 folded atoms, or k = 7
+ *                     with at most 128;
  *   f32 coefficients: k = 3 or 5 with at most 72 folded atoms, or k = 7 with 17 to
  *                     128;
  *   f8  coefficients: as f32, and lr->data 4-byte aligned with an even number of
- *                     elements if the image is f16;
- *   bf16 coefficients: as f16, except that k = 7 takes at most 128 folded atoms in
- *                     capacities of 72 and 128 only.
+ *                     elements if the image is f16.
  * Every other supported case runs on the generic kernel.
  */
 int sr_dict_assemble_ex(const sr_tensor* lr, const sr_tensor* coeff, const sr_tensor* dict,

@@ -26,10 +26,6 @@ int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
     const int need = (n_fold + 7) / 8;
     if (channels == 2 || channels == 4)                                 // 5x5, 16-bit coefficients: 32 and 72 atoms
         return (k == 5 && (coeff_dtype == SR_F16 || coeff_dtype == SR_BF16) && need <= 9) ? (need <= 4 ? 4 : 9) : 0;
-    if (coeff_dtype == SR_BF16 && k != 3) {                             // bfloat16 coefficients (3x3: below)
-        if (k == 5) return need <= 1 ? 1 : (need <= 4 ? 4 : (need <= 9 ? 9 : 0));
-        return need <= 9 ? 9 : (need <= 16 ? 16 : 0);
-    }
     if (k == 3) {                                                       // 3x3: up to 72 atoms
         if (need > 9) return 0;
         return need <= 1 ? 1 : (need <= 4 ? 4 : 9);
@@ -49,6 +45,7 @@ int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
             if (*built >= need) return *built;
         return 0;
     }
+    // fp16 and bfloat16 coefficients
     static const int k5c3[] = {1, 2, 4, 6, 9, 0}, k5c1[] = {1, 4, 6, 9, 0};
     static const int k7c3[] = {2, 9, 16, 0}, k7c1[] = {2, 9, 16, 0};
     const int* built = k == 5 ? (channels == 3 ? k5c3 : k5c1) : (channels == 3 ? k7c3 : k7c1);
