@@ -135,7 +135,7 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
  * kernel choice; `opts` == NULL means SR_KERNEL_AUTO.  The matrix-core kernel
  * qualifies when C is 1 or 3 (or 2 or 4 with f16 or bf16 coefficients and k = 5),
  * the tensors are small enough for 32-bit byte offsets (L*H*W*sizeof(coeff)
- * < 2^32, N*C*H*W < 2^30; with k = 5, C = 3 and f16 or bf16 coefficients an image of up
+ * < 2^32, C*H*W < 2^30; with k = 5, C = 3 and f16 or bf16 coefficients an image of up
  * to 2^32 coefficients, e.g. an 8K frame with 72 planes, also qualifies: element
  * offsets), the HR width is a whole number of pixel groups (4
  * pixels; 2 for f32 coefficients and for f16 / bf16 coefficients with k = 7) or at

@@ -88,7 +88,7 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
         !(k == 5 && a.C == 3 && (coeff_dtype == SR_F16 || coeff_dtype == SR_BF16) &&
           (unsigned long long)a.L * a.H * a.W < (1ull << 32)))
         return false;
-    if ((unsigned long long)a.N * a.C * a.H * a.W * 4ull >= (1ull << 32)) return false;   // 32-bit image offsets
+    if ((unsigned long long)a.C * a.H * a.W * 4ull >= (1ull << 32)) return false;          // 32-bit offsets within an image
     if (np8_for(k, a.C, a.n_fold, coeff_dtype) == 0) return false;
     if (tile < 0 || tile >= N_TILE_SHAPES) return false;
     return true;

@@ -322,7 +322,12 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     const unsigned lr_sh = a.io_f16 ? 1u : 2u;          // log2 of the element size
     auto load_lr = [&](const TilePos tp, int lane, unsigned (&lrv)[F::NLRP][F::NXC], unsigned& par) {
         const TileOrigin o = tile_origin(tp.ty * F::TH, tile_x0(tp.tx), F::R, UH, UW, a.H, a.W, a.s);
+        // the image's base is a 64-bit scalar; offsets within an image fit 32 bits
+        const char* lr_img = lr_base + (size_t)tp.n * C * ((size_t)a.h * a.w * lr_esz);
         if constexpr (LRBF) {
+            // aligned words: the image may start in the middle of one
+            const unsigned mis = (unsigned)((uintptr_t)lr_img & 3u);
+            const char* lr_al = lr_img - mis;
             unsigned xcol[F::NXC];
 #pragma unroll
             for (int xc = 0; xc < F::NXC; ++xc) {
@@ -335,15 +340,15 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             for (int u = 0; u < F::NLRP; ++u) {
                 const int p = wave + NW * u, c = p / MAXLRY, ry = p - c * MAXLRY;
                 const bool need = p < C * MAXLRY && ry < o.nly;
-                unsigned row = ((unsigned)(tp.n * C + (need ? c : 0)) * (unsigned)a.h +
+                unsigned row = ((unsigned)(need ? c : 0) * (unsigned)a.h +
                                 (unsigned)clampi(o.ly0 + (need ? ry : 0), 0, a.h - 1)) * (unsigned)a.w;   // in elements
                 if (u == 0) row0 = row;
                 if (!need) row = row0;
 #pragma unroll
                 for (int xc = 0; xc < F::NXC; ++xc) {
-                    const unsigned byte = (row + xcol[xc]) << lr_sh;
+                    const unsigned byte = ((row + xcol[xc]) << lr_sh) + mis;
                     par |= ((byte >> 1) & 1u) << (u * F::NXC + xc);
-                    lrv[u][xc] = *(const unsigned*)(lr_base + (size_t)(byte & ~3u));
+                    lrv[u][xc] = *(const unsigned*)(lr_al + (size_t)(byte & ~3u));
                 }
             }
         } else {
@@ -355,12 +360,12 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 for (int u = 0; u < F::NLRP; ++u) {
                     const int p = wave + NW * u, c = p / MAXLRY, ry = p - c * MAXLRY;
                     if (p < C * MAXLRY && ry < o.nly) {
-                        const unsigned row = ((unsigned)(tp.n * C + c) * (unsigned)a.h +
+                        const unsigned row = ((unsigned)c * (unsigned)a.h +
                                               (unsigned)clampi(o.ly0 + ry, 0, a.h - 1)) * (unsigned)a.w * lr_esz;
 #pragma unroll
                         for (int xc = 0; xc < F::NXC; ++xc)
                             if (xc == 0 || 64 * xc < o.nlx) {     // whole 64-column chunks the tile never reads
-                                const char* q = lr_base + (size_t)(row + xo[xc]);
+                                const char* q = lr_img + (size_t)(row + xo[xc]);
                                 lrv[u][xc] = decltype(f16)::value ? (unsigned)*(const unsigned short*)q : *(const unsigned*)q;
                             }
                     }
@@ -642,7 +647,8 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         const int y = Y0 + (unit * NW + wave) * WR + jr, x = X0 + PX * jc;
         const bool valid = y < a.H && x < a.W;
         const unsigned plane_px = (unsigned)a.H * (unsigned)a.W;
-        const unsigned o0 = ((unsigned)(cur.n * C) * (unsigned)a.H + (unsigned)y) * (unsigned)a.W + x + hf * (PX / 2);
+        const unsigned o0 = (unsigned)y * (unsigned)a.W + x + hf * (PX / 2);       // within the image
+        char* const out_img = (char*)a.out + (size_t)cur.n * C * ((size_t)plane_px * (a.io_f16 ? 2 : 4));
 #pragma unroll
         for (int c = 0; c < C; ++c) {
             float tot[PX / 2];
@@ -655,7 +661,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             if (valid) {
                 const unsigned oe = o0 + c * plane_px;
                 if (a.io_f16) {
-                    __half* op = (__half*)((char*)a.out + (size_t)(oe * 2u));
+                    __half* op = (__half*)(out_img + (size_t)(oe * 2u));
                     if constexpr (PX >= 4) {
 #pragma unroll
                         for (int q = 0; q < PX / 2; q += 2) {
@@ -668,7 +674,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                         op[0] = narrow_f16(tot[0]);
                     }
                 } else {
-                    float* op = (float*)((char*)a.out + (size_t)(oe * 4u));
+                    float* op = (float*)(out_img + (size_t)(oe * 4u));
                     if constexpr (PX == 8) *(float4*)op = make_float4(tot[0], tot[1], tot[2], tot[3]);
                     else if constexpr (PX == 4) *(float2*)op = make_float2(tot[0], tot[1]);
                     else op[0] = tot[0];

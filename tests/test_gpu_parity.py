@@ -213,6 +213,32 @@ def test_bfloat16_coefficients_beyond_the_fp16_range(oracle):
         assert float(np.abs(got - ref).max()) <= 2e-3, f"kernel {kernel}"
 
 
+@pytest.mark.parametrize("cd,io", [("f16", "f32"), ("f8", "f16")])
+def test_batch_whose_output_exceeds_32_bit_offsets(oracle, cd, io):
+    """Forty-four 4K frames (fp16 images: ninety) with two atoms: the output is 4.4 GB, past
+    32-bit byte offsets, while each image is not.  Sampled pixels of the first, the last and
+    the image that straddles the 4 GB mark, oracle pixel by pixel."""
+    n = 44 if io == "f32" else 90
+    wl = sr_synth.Workload("batch", 71, n, 3, 540, 960, 4, 2, 5, cd, io, 0.0, 1.0)
+    inp = sr_synth.make_inputs(wl, DEV)
+    assert planned(inp, wl, sr.SR_KERNEL_AUTO) == MFMA
+    got = run_gpu(inp, wl, sr.SR_KERNEL_AUTO)
+    assert not torch.isnan(got).any()
+    lr, D = inp["lr"].float().cpu().numpy(), inp["dict"].cpu().numpy()
+    rng = np.random.default_rng(9)
+    esz = 4 if io == "f32" else 2
+    straddle = (1 << 32) // (3 * wl.H * wl.W * esz)
+    assert 0 < straddle < n
+    for frame in sorted({0, straddle - 1, straddle, n - 1}):
+        U = oracle.bicubic(sr_synth.stored_numpy(inp["lr"][frame:frame + 1]), wl.scale)
+        pts = np.stack([np.zeros(800, dtype=np.int64), rng.integers(0, wl.H, 800), rng.integers(0, wl.W, 800)], axis=1)
+        pts[:4] = [(0, 0, 0), (0, wl.H - 1, wl.W - 1), (0, 0, wl.W - 1), (0, wl.H - 1, 0)]
+        want = oracle.assemble_points(U, sr_synth.stored_numpy(inp["coeff"][frame:frame + 1]), D, pts)
+        have = got[frame].float().cpu().numpy()[:, pts[:, 1], pts[:, 2]].T
+        tol = 2e-3 if io == "f32" else 3e-3
+        assert float(np.abs(have - want).max()) <= tol, f"frame {frame}"
+
+
 def test_every_fp8_code_is_widened_as_the_oracle_does(oracle):
     """All 254 finite E4M3 codes, one per pixel, through a single centred delta atom on a
     constant image: the output IS the widened coefficient (both kernels, bit for bit)."""
