@@ -46,7 +46,7 @@ int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
         return 0;
     }
     // fp16 and bfloat16 coefficients
-    static const int k5c3[] = {1, 2, 4, 6, 9, 0}, k5c1[] = {1, 4, 6, 9, 0};
+    static const int k5c3[] = {1, 2, 4, 6, 9, 16, 0}, k5c1[] = {1, 4, 6, 9, 16, 0};
     static const int k7c3[] = {2, 9, 16, 0}, k7c1[] = {2, 9, 16, 0};
     const int* built = k == 5 ? (channels == 3 ? k5c3 : k5c1) : (channels == 3 ? k7c3 : k7c1);
     for (; *built; ++built)

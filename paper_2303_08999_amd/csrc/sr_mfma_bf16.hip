@@ -29,6 +29,9 @@ static hipError_t launch_k5(const AssembleArgs& a, int np8, hipStream_t st) {
         if ((long long)a.N * a.H * a.W <= 400000) return launch_one<5, C, 9, 4, 1, 4, 1, 2, CT_BF16>(a, st);
         if (a.s == 4) return launch_one<5, C, 9, 4, 1, 4, 6, 2, CT_BF16, 4>(a, st);
         return launch_one<5, C, 9, 4, 1, 4, 4, 2, CT_BF16>(a, st);
+    case 16:                                                             // 73 to 128 atoms: two pixels per lane, as 7x7
+        if (a.s == 4) return launch_one<5, C, 16, 2, 1, 4, 6, 2, CT_BF16, 4>(a, st);
+        return launch_one<5, C, 16, 2, 1, 4, 4, 2, CT_BF16>(a, st);
     default: return hipErrorInvalidValue;
     }
 }

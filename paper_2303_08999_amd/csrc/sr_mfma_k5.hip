@@ -45,6 +45,9 @@ hipError_t launch_mfma_k5(const AssembleArgs& a, int np8, int shape, hipStream_t
                 return launch_one<5, 3, 9, 4, 1, 4, 4, 2>(a, st);    // 128 x 16, 4 units
             }
             }
+        case 16:                                                         // 73 to 128 atoms: two pixels per lane, as 7x7
+            if (a.s == 4) return launch_one<5, 3, 16, 2, 1, 4, 6, 2, CT_F16, 4>(a, st);
+            return launch_one<5, 3, 16, 2, 1, 4, 4, 2>(a, st);
         default: return hipErrorInvalidValue;
         }
     }
@@ -71,6 +74,9 @@ hipError_t launch_mfma_k5(const AssembleArgs& a, int np8, int shape, hipStream_t
     case 9:
         if (a.s == 4) return launch_one<5, 1, 9, 4, 1, 4, 6, 2, CT_F16, 4>(a, st);
         return launch_one<5, 1, 9, 4, 1, 4, 4, 2>(a, st);
+    case 16:
+        if (a.s == 4) return launch_one<5, 1, 16, 2, 1, 4, 6, 2, CT_F16, 4>(a, st);
+        return launch_one<5, 1, 16, 2, 1, 4, 4, 2>(a, st);
     default: return hipErrorInvalidValue;
     }
 }

@@ -85,7 +85,9 @@ def test_plan_accepts_a_good_case(lib):
     assert plan(*case(w=43, s=3), s=3) == sr.SR_KERNEL_MFMA      # HR width 129: the last tile column ends at the image edge
     assert plan(*case(w=1, s=3), s=3) == sr.SR_KERNEL_GENERIC    # HR width 3: not even one group of four pixels
     assert plan(*case(w=15), opts=sr.make_options(sr.SR_KERNEL_MFMA)) == sr.SR_KERNEL_MFMA   # width 60
-    assert plan(*case(L=73), L=73) == sr.SR_KERNEL_GENERIC       # more atoms than the 5x5 kernel holds
+    assert plan(*case(L=73), L=73) == sr.SR_KERNEL_MFMA          # 73 to 128 atoms of 5x5: fp16 and bfloat16
+    assert plan(*case(L=129), L=129) == sr.SR_KERNEL_GENERIC     # more atoms than the 5x5 kernel holds
+    assert plan(*case(L=73, cd=sr.SR_F32), L=73) == sr.SR_KERNEL_GENERIC
     assert plan(*case(L=128, k=7), L=128, k=7) == sr.SR_KERNEL_MFMA
     assert plan(*case(), opts=sr.make_options(sr.SR_KERNEL_GENERIC)) == sr.SR_KERNEL_GENERIC
 
@@ -120,7 +122,8 @@ def test_plan_for_bfloat16_coefficients(lib):
     assert plan(*case(cd=BF, k=7, L=128), k=7, L=128) == sr.SR_KERNEL_MFMA
     assert plan(*case(cd=BF, k=7, L=128, C=1), k=7, L=128, C=1) == sr.SR_KERNEL_MFMA
     assert plan(*case(cd=BF, C=5), C=5) == sr.SR_KERNEL_GENERIC
-    assert plan(*case(cd=BF, L=73), L=73) == sr.SR_KERNEL_GENERIC
+    assert plan(*case(cd=BF, L=73), L=73) == sr.SR_KERNEL_MFMA
+    assert plan(*case(cd=BF, L=129), L=129) == sr.SR_KERNEL_GENERIC
     assert plan(*case(cd=BF), kept=[0, 3, 9]) == sr.SR_KERNEL_MFMA
     lr, coeff, d, out = case(cd=BF)
     coeff.data = 0x11000001                                              # two-byte elements need two-byte alignment

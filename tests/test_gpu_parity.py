@@ -310,6 +310,10 @@ RAGGED = [
     (31, 45, 4, 3, 9, 5, "f32", "f32", 1),      # ... few atoms
     (6, 8, 2, 16, 9, 3, "f16", "f32", 1),       # the largest channel count accepted
     (60, 128, 4, 3, 24, 5, "f16", "f32", 9),    # 540 tiles over 9 images: every XCD share crosses image borders
+    (33, 47, 4, 3, 128, 5, "f16", "f32", 2),    # 128 atoms of 5x5: two pixels per lane
+    (29, 36, 3, 1, 100, 5, "f16", "f16", 1),    # ... one channel, x3, fp16 image
+    (26, 31, 2, 3, 73, 5, "bf16", "f32", 1),    # ... bfloat16, x2, HR width 62
+    (40, 67, 4, 3, 128, 5, "bf16", "f32", 1),   # ... HR width 268, several tiles
     (33, 47, 4, 3, 72, 5, "bf16", "f32", 2),    # bfloat16 coefficients on the matrix-core path
     (29, 36, 3, 1, 72, 5, "bf16", "f16", 1),    # ... one channel, fp16 image, x3
     (17, 34, 4, 3, 7, 5, "bf16", "f32", 1),     # ... the 8-atom instantiation
