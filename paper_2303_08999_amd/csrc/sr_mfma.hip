@@ -31,7 +31,7 @@ int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
         return need <= 1 ? 1 : (need <= 4 ? 4 : 9);
     }
     if (coeff_dtype == SR_F32) {                                        // fp32 coefficients
-        static const int k5c3[] = {1, 2, 4, 6, 9, 0}, k5c1[] = {1, 4, 6, 9, 0}, k7[] = {9, 16, 0};
+        static const int k5c3[] = {1, 2, 4, 6, 9, 16, 0}, k5c1[] = {1, 4, 6, 9, 16, 0}, k7[] = {9, 16, 0};
         if (k == 7 && need <= 2) return 0;                                // short 7x7 lists: the generic kernel is faster
         const int* built = k == 5 ? (channels == 3 ? k5c3 : k5c1) : k7;
         for (; *built; ++built)
@@ -39,7 +39,7 @@ int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
         return 0;
     }
     if (coeff_dtype == SR_F8E4M3) {                                     // 8-bit coefficients
-        static const int c3[] = {1, 4, 6, 9, 0}, c1[] = {1, 4, 9, 0};
+        static const int c3[] = {1, 4, 6, 9, 16, 0}, c1[] = {1, 4, 9, 16, 0};
         if (k == 7) return need <= 2 ? 0 : (need <= 9 ? 9 : (need <= 16 ? 16 : 0));   // short lists: generic kernel
         for (const int* built = channels == 3 ? c3 : c1; *built; ++built)
             if (*built >= need) return *built;

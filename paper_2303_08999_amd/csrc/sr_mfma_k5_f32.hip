@@ -23,6 +23,7 @@ hipError_t launch_mfma_k5_f32(const AssembleArgs& a, int np8, hipStream_t st) {
             // 720p fits the grid in one round of 460 tiles)
             if (a.s == 4 && (long long)a.N * a.H * a.W > 600000) return launch_one<5, 3, 9, 2, 1, 4, 8, 2, CT_F32, 4>(a, st);
             return launch_one<5, 3, 9, 2, 1, 4, 4, 2, CT_F32>(a, st);
+        case 16: return launch_one<5, 3, 16, 2, 1, 4, 4, 1, CT_F32>(a, st);      // 73 to 128 atoms: one wavefront per SIMD, as 7x7
         default: return hipErrorInvalidValue;
         }
     }
@@ -31,6 +32,7 @@ hipError_t launch_mfma_k5_f32(const AssembleArgs& a, int np8, hipStream_t st) {
     case 4:  return launch_one<5, 1, 4, 2, 1, 4, 4, 2, CT_F32>(a, st);
     case 6:  return launch_one<5, 1, 6, 2, 1, 4, 4, 2, CT_F32>(a, st);
     case 9:  return launch_one<5, 1, 9, 2, 1, 4, 4, 2, CT_F32>(a, st);
+    case 16: return launch_one<5, 1, 16, 2, 1, 4, 4, 1, CT_F32>(a, st);
     default: return hipErrorInvalidValue;
     }
 }

@@ -28,10 +28,12 @@ hipError_t launch_mfma_k5_f8(const AssembleArgs& a, int np8, hipStream_t st) {
             if (a.s == 4) return launch_one<5, 3, 9, 4, 1, 4, 6, 2, CT_F8, 4>(a, st);    // 128 x 24
             return launch_one<5, 3, 9, 4, 1, 4, 4, 2, CT_F8>(a, st);
         }
+        case 16: return launch_one<5, 3, 16, 4, 1, 4, 4, 1, CT_F8>(a, st);       // 73 to 128 atoms: one wavefront per SIMD, as 7x7
         default: return hipErrorInvalidValue;
         }
     }
     switch (np8) {
+    case 16: return launch_one<5, 1, 16, 4, 1, 4, 4, 1, CT_F8>(a, st);
     case 1:  return launch_one<5, 1, 1, 4, 1, 4, 4, 2, CT_F8>(a, st);
     case 4:  return launch_one<5, 1, 4, 4, 1, 4, 4, 2, CT_F8>(a, st);
     case 9:
