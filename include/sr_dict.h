@@ -140,10 +140,8 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
  * offsets), the HR width is a whole number of pixel groups (4
  * pixels; 2 for f32 coefficients and for f16 / bf16 coefficients with k = 7) or at
  * least 128, and
- *   f16 and bf16 coefficients: k = 3 with at most 72 folded atoms, k = 5 or 7 with
- *                     at most 128 (k = 5, C = 2 or 4: 72);
- *   f32 coefficients: k = 3 with at most 72 folded atoms, k = 5 with at most 128, or
- *                     k = 7 with 17 to 128;
+ *   f16 and bf16 coefficients: at most 128 folded atoms (k = 5, C = 2 or 4: 72);
+ *   f32 coefficients: at most 128 folded atoms; k = 7: 17 to 128;
  *   f8  coefficients: as f32, and lr->data 4-byte aligned with an even number of
  *                     elements if the image is f16.
  * Every other supported case runs on the generic kernel.

@@ -26,9 +26,9 @@ int np8_for(int k, int channels, int n_fold, int coeff_dtype) {
     const int need = (n_fold + 7) / 8;
     if (channels == 2 || channels == 4)                                 // 5x5, 16-bit coefficients: 32 and 72 atoms
         return (k == 5 && (coeff_dtype == SR_F16 || coeff_dtype == SR_BF16) && need <= 9) ? (need <= 4 ? 4 : 9) : 0;
-    if (k == 3) {                                                       // 3x3: up to 72 atoms
-        if (need > 9) return 0;
-        return need <= 1 ? 1 : (need <= 4 ? 4 : 9);
+    if (k == 3) {                                                       // 3x3: up to 128 atoms
+        if (need > 16) return 0;
+        return need <= 1 ? 1 : (need <= 4 ? 4 : (need <= 9 ? 9 : 16));
     }
     if (coeff_dtype == SR_F32) {                                        // fp32 coefficients
         static const int k5c3[] = {1, 2, 4, 6, 9, 16, 0}, k5c1[] = {1, 4, 6, 9, 16, 0}, k7[] = {9, 16, 0};

@@ -89,7 +89,8 @@ def test_plan_accepts_a_good_case(lib):
     assert plan(*case(L=129), L=129) == sr.SR_KERNEL_GENERIC     # more atoms than the 5x5 kernel holds
     assert plan(*case(L=73, cd=sr.SR_F32), L=73) == sr.SR_KERNEL_MFMA
     assert plan(*case(L=128, cd=sr.SR_F8E4M3), L=128) == sr.SR_KERNEL_MFMA
-    assert plan(*case(L=73, k=3), L=73, k=3) == sr.SR_KERNEL_GENERIC      # 3x3: 72 atoms
+    assert plan(*case(L=73, k=3), L=73, k=3) == sr.SR_KERNEL_MFMA
+    assert plan(*case(L=129, k=3), L=129, k=3) == sr.SR_KERNEL_GENERIC
     assert plan(*case(L=128, k=7), L=128, k=7) == sr.SR_KERNEL_MFMA
     assert plan(*case(), opts=sr.make_options(sr.SR_KERNEL_GENERIC)) == sr.SR_KERNEL_GENERIC
 

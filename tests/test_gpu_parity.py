@@ -310,6 +310,10 @@ RAGGED = [
     (31, 45, 4, 3, 9, 5, "f32", "f32", 1),      # ... few atoms
     (6, 8, 2, 16, 9, 3, "f16", "f32", 1),       # the largest channel count accepted
     (60, 128, 4, 3, 24, 5, "f16", "f32", 9),    # 540 tiles over 9 images: every XCD share crosses image borders
+    (33, 47, 4, 3, 128, 3, "f16", "f32", 1),    # 128 atoms of 3x3
+    (30, 36, 3, 1, 100, 3, "bf16", "f16", 1),   # ... bfloat16, one channel, x3, fp16 image
+    (33, 47, 2, 3, 128, 3, "f32", "f32", 1),    # ... fp32 coefficients, x2
+    (33, 48, 4, 3, 90, 3, "f8", "f32", 2),      # ... 8-bit coefficients
     (33, 47, 4, 3, 128, 5, "f32", "f32", 2),    # 128 atoms of 5x5, fp32 coefficients: one wavefront per SIMD
     (29, 36, 3, 1, 90, 5, "f32", "f16", 1),     # ... one channel, x3, fp16 image
     (33, 48, 4, 3, 128, 5, "f8", "f32", 1),     # ... 8-bit coefficients
