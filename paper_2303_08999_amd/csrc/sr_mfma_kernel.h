@@ -443,21 +443,26 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     //     per element.  Loads are clamped into range; only the store is guarded.
     auto stage1_vertical = [&](const TilePos tp, int tid) {
         const TileOrigin o = tile_origin(tp.ty * F::TH, tile_x0(tp.tx), F::R, UH, UW, a.H, a.W, a.s);
-        const int sh = o.nlx <= 32 ? 5 : (o.nlx <= 64 ? 6 : 7);
-        const int total = (C * UH) << sh;
-        const int rx = tid & ((1 << sh) - 1);
-        const int rxc = rx < MAXLRX ? rx : MAXLRX - 1;
+        // Items (row pr, footprint column rx), nlx columns to a row, dealt to the threads with
+        // no idle lanes (rows padded to 32, 64 or 128 columns left 38 % of them idle at x4:
+        // 8 atoms at 4K 90 -> 85 us, the E4M3 frame 160 -> 154 us).  idx / nlx by a multiply,
+        // exact for idx < 2^22 / nlx and free of overflow for idx < 1024 nlx.
+        static_assert(C * UH <= 256 && MAXLRX <= 128, "item index beyond the exact range of the division");
+        const int nlx = o.nlx < 4 ? 4 : o.nlx;
+        const unsigned inv = ((1u << 22) + nlx - 1) / nlx;
+        const int total = C * UH * nlx;
         for (int base = tid; base < total; base += 4 * NT) {
             float4 w4[4];
             int src[4], dst[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const int idx = base + k * NT;
-                const int pr = idx < total ? idx >> sh : C * UH - 1;
+                const int idc = idx < total ? idx : total - 1;
+                const int pr = (int)(((unsigned)idc * inv) >> 22), rx = idc - pr * nlx;
                 const int c = pr / UH, yy = pr - c * UH;
                 w4[k] = yw[yy];
-                src[k] = (c * MAXLRY + yb[yy]) * MAXLRX + rxc;
-                dst[k] = (idx < total && rx < MAXLRX) ? pr * MAXLRX + rx : -1;
+                src[k] = (c * MAXLRY + yb[yy]) * MAXLRX + rx;
+                dst[k] = idx < total ? pr * MAXLRX + rx : -1;
             }
             __builtin_amdgcn_sched_barrier(0);
             float v[4][4];
