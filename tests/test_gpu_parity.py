@@ -335,6 +335,8 @@ RAGGED = [
     (30, 41, 2, 4, 20, 5, "bf16", "f16", 2),    # ... four channels, 32-atom instantiation
     (22, 36, 4, 1, 128, 7, "bf16", "f32", 1),   # ... 7x7, one channel
     (37, 53, 3, 3, 72, 5, "bf16", "f32", 1),    # ... HR width 159: the shifted last tile column
+    (29, 35, 4, 1, 40, 5, "f8", "f16", 2),      # 8-bit coefficients, fp16 images of 1015 elements: the second starts mid-word
+    (13, 15, 4, 3, 72, 5, "f8", "f16", 4),      # ... 585 elements each, four images
     (33, 47, 4, 3, 72, 5, "f8", "f32", 2),      # 8-bit E4M3 coefficients on the matrix-core path
     (29, 36, 3, 1, 72, 5, "f8", "f16", 1),      # ... one channel, fp16 image, x3
     (17, 34, 4, 3, 7, 5, "f8", "f32", 1),       # ... few atoms (the 8-atom instantiation)
