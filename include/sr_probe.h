@@ -33,6 +33,35 @@ int sr_probe_read(const void* src, size_t bytes, void* sink, void* stream);
  * planes must be 72 or 128, 1 <= channels <= 4, pixels a multiple of 128. */
 int sr_probe_mix(const void* coeff, int planes, size_t pixels, void* out, int channels, void* stream);
 
+/* A byte mix with NOTHING of the assembly kernel's access pattern in it: one launch of
+ * `blocks` workgroups of 256 threads in which every `writer_every`-th workgroup only
+ * writes (16-byte stores sweeping `dst`, `write_bytes` in all) and all others only read
+ * (16-byte non-temporal loads sweeping `src`, `read_bytes` in all), so that loads and
+ * stores never share a wavefront.  writer_every = 0 (with write_bytes = 0): read only;
+ * writer_every = 1 (with read_bytes = 0): write only.  `lds_bytes` of dynamic LDS per
+ * workgroup are requested but not used: they cap the workgroups resident per CU
+ * (more than 80 KB leaves one per CU, so `blocks` <= 256 then counts the CUs in use).
+ * nt_store != 0 writes with non-temporal stores.  Sizes are multiples of 16, pointers
+ * 16-byte aligned; `sink` as for sr_probe_read. */
+int sr_probe_stream(const void* src, size_t read_bytes, void* dst, size_t write_bytes, int blocks,
+                    int writer_every, int lds_bytes, int nt_store, void* sink, void* stream);
+
+/* The byte mix of a frame with 72 fp16 coefficient planes and 3 fp32 output planes of
+ * `pixels` elements each (a multiple of 128), changing one property of sr_probe_stream's
+ * ideal pattern at a time: read_planes != 0 reads 256-byte pieces from each of the 72
+ * planes of `src` (8 bytes per lane, as the assembly kernel does) instead of one
+ * contiguous sweep; write_planes != 0 writes 512-byte pieces into each of the 3 planes of
+ * `dst` (8 bytes per lane) instead of one contiguous sweep; same_wave != 0 lets every
+ * wavefront read and write (otherwise every writer_every-th workgroup, >= 2, only writes).
+ * read_planes == 2 (with write_planes and same_wave set): 16 bytes per lane both ways,
+ * i.e. 512-byte pieces of the coefficient planes and 1 KB pieces of the output planes.
+ * plane_pad_bytes (a multiple of 16, plane reads only) is added to the distance between
+ * coefficient planes, which shows what the planes' common low address bits cost.
+ * pixels is a multiple of 256; src holds 72 * (2 * pixels + plane_pad_bytes) bytes, dst
+ * 12 * pixels bytes, both 16-byte aligned. */
+int sr_probe_pattern(const void* src, void* dst, size_t pixels, int read_planes, int write_planes, int same_wave,
+                     int blocks, int writer_every, size_t plane_pad_bytes, void* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

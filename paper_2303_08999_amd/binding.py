@@ -19,7 +19,7 @@ SR_MAX_ATOMS = 256
 
 EXPORTS = ("sr_dict_assemble", "sr_dict_assemble_selective", "sr_dict_assemble_ex",
            "sr_bicubic_upsample", "sr_dict_assemble_plan", "sr_strerror", "sr_version",
-           "sr_probe_read", "sr_probe_mix",
+           "sr_probe_read", "sr_probe_mix", "sr_probe_stream", "sr_probe_pattern",
            "sr_atom_gram_workspace_bytes", "sr_atom_gram", "sr_select_atoms")
 
 
@@ -62,6 +62,8 @@ def load():
     lib.sr_strerror.argtypes = [i]
     lib.sr_probe_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     lib.sr_probe_mix.argtypes = [vp, i, ctypes.c_size_t, vp, i, vp]
+    lib.sr_probe_pattern.argtypes = [vp, vp, ctypes.c_size_t, i, i, i, i, i, ctypes.c_size_t, vp, vp]
+    lib.sr_probe_stream.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_size_t, i, i, i, i, vp, vp]
     dp = ctypes.POINTER(ctypes.c_double)
     lib.sr_atom_gram_workspace_bytes.argtypes = [i]
     lib.sr_atom_gram.argtypes = [T, T, T, T, i, i, i, i, vp, ctypes.c_size_t, vp, vp]
@@ -194,6 +196,27 @@ def sr_probe_mix(coeff, planes, pixels, out, channels, stream=None):
     assert out.numel() * out.element_size() >= channels * pixels * 4
     _check(load().sr_probe_mix(ctypes.c_void_p(coeff.data_ptr()), planes, pixels,
                                ctypes.c_void_p(out.data_ptr()), channels, _stream(stream)))
+
+
+def sr_probe_stream(src, read_bytes, dst, write_bytes, blocks, writer_every, sink, lds_bytes=0, nt_store=0, stream=None):
+    """Readers and writers in separate workgroups, 16 bytes per lane (include/sr_probe.h)."""
+    assert src is None or src.numel() * src.element_size() >= read_bytes
+    assert dst is None or dst.numel() * dst.element_size() >= write_bytes
+    _check(load().sr_probe_stream(ctypes.c_void_p(src.data_ptr() if src is not None else 0), read_bytes,
+                                  ctypes.c_void_p(dst.data_ptr() if dst is not None else 0), write_bytes,
+                                  blocks, writer_every, lds_bytes, nt_store,
+                                  ctypes.c_void_p(sink.data_ptr()), _stream(stream)))
+
+
+def sr_probe_pattern(src, dst, pixels, read_planes, write_planes, same_wave, blocks, writer_every, sink,
+                     plane_pad_bytes=0, stream=None):
+    """72 fp16 planes read, 3 fp32 planes written, one pattern property at a time (include/sr_probe.h)."""
+    assert src.numel() * src.element_size() >= 72 * (2 * pixels + plane_pad_bytes)
+    assert dst.numel() * dst.element_size() >= 12 * pixels
+    _check(load().sr_probe_pattern(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(dst.data_ptr()), pixels,
+                                   int(read_planes), int(write_planes), int(same_wave), blocks, writer_every,
+                                   plane_pad_bytes,
+                                   ctypes.c_void_p(sink.data_ptr()), _stream(stream)))
 
 
 def sr_atom_gram_workspace_bytes(L: int) -> int:
