@@ -59,11 +59,71 @@ def empirical_ceilings(sr, torch, wl, coeffs, outs, kernel_ms):
     t_read = timed(lambda i: sr.sr_probe_read(coeffs[i % len(coeffs)][0], sink))
     t_mix = timed(lambda i: sr.sr_probe_mix(coeffs[i % len(coeffs)][0], wl.L, px, outs[i % 2][0], wl.c))
     mix_bytes = coeff_bytes + wl.c * px * 4
+    # the same bytes with nothing of the kernel's access pattern: 16-byte accesses, readers and
+    # writers in separate workgroups, two workgroups per CU, every 9th one a writer
+    t_stream = timed(lambda i: sr.sr_probe_stream(coeffs[i % len(coeffs)][0], coeff_bytes, outs[i % 2][0], wl.c * px * 4,
+                                                  512, 9, sink, nt_store=1))
     return {"read_only_GBps": round(coeff_bytes / t_read / 1e6, 1),
             "mix_GBps": round(mix_bytes / t_mix / 1e6, 1), "mix_ms": round(t_mix, 4),
             "kernel_time_over_mix_time": round(kernel_ms * 1.0 / (t_mix * wl.n), 3),
-            "note": "streaming probes of the same library on one frame's coefficient planes: read-only, and "
-                    "the kernel's read + write mix with no arithmetic (same planes, same output size)"}
+            "independent_mix_GBps": round(mix_bytes / t_stream / 1e6, 1), "independent_mix_ms": round(t_stream, 4),
+            "kernel_time_over_independent_mix_time": round(kernel_ms * 1.0 / (t_stream * wl.n), 3),
+            "note": "streaming probes of the same library on one frame's coefficient planes: read-only; the kernel's "
+                    "own read + write pattern with no arithmetic (mix); and the same bytes with 16-byte accesses by "
+                    "separate reader and writer workgroups (independent_mix), whose writers finish before its readers, so "
+                    "that part of the reading runs undisturbed"}
+
+
+def probe_study(sr, torch, hr_h=2160, hr_w=3840):
+    """What the memory system delivers for the 4K frame's byte mix (72 fp16 planes read, 3 fp32
+    planes written) under access patterns of increasing likeness to the assembly kernel's, timed
+    like the kernel (HIP events, three rotating source buffers).  Times in microseconds."""
+    px = hr_h * hr_w
+    rb, wb = 144 * px, 12 * px
+    srcs = [torch.empty(rb, device="cuda", dtype=torch.uint8).random_(0, 255) for _ in range(3)]
+    dsts = [torch.empty(wb, device="cuda", dtype=torch.uint8) for _ in range(2)]
+    sink = torch.zeros(4, device="cuda", dtype=torch.int32)
+
+    def timed(fn, reps=12):
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for i, (a, b) in enumerate(ev):
+            a.record(); fn(i); b.record()
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in ev)
+        return round(ms[len(ms) // 2] * 1e3, 1)
+
+    S, D = (lambda i: srcs[i % 3]), (lambda i: dsts[i % 2])
+    out = {"pixels": px, "read_bytes": rb, "write_bytes": wb}
+    out["stream_read_only_one_workgroup_per_cu"] = {
+        nb: timed(lambda i: sr.sr_probe_stream(S(i), rb, None, 0, nb, 0, sink, lds_bytes=96 * 1024))
+        for nb in (64, 128, 192, 256)}
+    out["stream_read_only_512_blocks"] = timed(lambda i: sr.sr_probe_stream(S(i), rb, None, 0, 512, 0, sink))
+    out["stream_write_only_1024_blocks"] = timed(lambda i: sr.sr_probe_stream(None, 0, D(i), wb, 1024, 1, sink))
+    out["stream_mix_512_blocks"] = {
+        f"writer_every_{we}_nt_{nt}": timed(lambda i: sr.sr_probe_stream(S(i), rb, D(i), wb, 512, we, sink, nt_store=nt))
+        for we in (7, 9, 13) for nt in (0, 1)}
+    names = {0: "contiguous_16B", 1: "two_planes_per_load_8B_256B_pieces", 2: "two_planes_per_load_16B_512B_pieces",
+             3: "one_plane_per_load_8B_512B_pieces"}
+    out["pattern_same_wave_512_blocks"] = {
+        names[rp]: {"read_write": timed(lambda i: sr.sr_probe_pattern(S(i), D(i), px, rp, 1, 1, 512, 0, sink)),
+                    "read_write_stores_through_l2": timed(lambda i: sr.sr_probe_pattern(S(i), D(i), px, rp, 3, 1, 512, 0, sink)),
+                    "read_only": timed(lambda i: sr.sr_probe_pattern(S(i), D(i), px, rp, 2, 1, 512, 0, sink))}
+        for rp in (0, 1, 2, 3)}
+    out["pattern_separate_writers_512_blocks"] = {
+        f"read_planes_{rp}_write_planes_{wp}_writer_every_13":
+            timed(lambda i: sr.sr_probe_pattern(S(i), D(i), px, rp, wp, 0, 512, 13, sink))
+        for rp in (0, 1) for wp in (0, 1)}
+    bit = lambda b: "+".join(n for k, n in ((1, "sc0"), (2, "sc1"), (4, "nt")) if b & k) or "plain"
+    out["kernel_pattern_cache_policy_bits"] = {
+        f"loads_{bit(lp)}": {f"stores_{bit(sp)}": timed(lambda i: sr.sr_probe_policy_bits(S(i), D(i), px, lp, sp, 512, sink), reps=8)
+                             for sp in range(8)} for lp in (0, 4, 6)}
+    out["kernel_pattern_l2_write_back_every_n_runs"] = {
+        fe: timed(lambda i: sr.sr_probe_policy(S(i), D(i), px, 1, 0, fe, 512, sink)) for fe in (0, 1, 2, 4, 16)}
+    out["kernel_pattern_probe_sr_probe_mix"] = timed(lambda i: sr.sr_probe_mix(S(i), 72, px, D(i), 3))
+    return out
 
 
 def selection_leg(sr, torch, wl, inp, stride):
@@ -194,6 +254,12 @@ def main():
                          "normal equations on the GPU over every STRIDE-th row and column, then the host search")
     ap.add_argument("--bicubic", action="store_true",
                     help="also time the bicubic-only entry point (stage 1 alone) on this frame")
+    ap.add_argument("--lib", default=None, metavar="PATH",
+                    help="load this build of the library instead of the in-tree one (measurement builds "
+                         "with a part of the kernel switched off, see sr_mfma_kernel.h)")
+    ap.add_argument("--probe-study", action="store_true",
+                    help="instead of the kernel, time the library's streaming probes on the 4K frame's byte mix "
+                         "and print them as one JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size kernel that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters when profiling)")
@@ -207,7 +273,13 @@ def main():
     import sr_synth
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    if args.lib:
+        from paper_2303_08999_amd import binding
+        binding.LIB_PATH = os.path.abspath(args.lib)
     sr.load()
+    if args.probe_study:
+        print(json.dumps({"probe_study_us": probe_study(sr, torch)}))
+        return
     wl = sr_synth.WORKLOADS[args.workload]
     dev = "cuda"
     inp = sr_synth.make_inputs(wl, dev)
@@ -285,6 +357,9 @@ def main():
                    "kernel": {1: "generic", 2: "mfma"}[plan], "rotating_coeff_buffers": N_ROTATE},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(wl.name),
+                     "traffic_source": (f"profiles/sr_mfma_{wl.name}_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an "
+                                        "earlier run of this command; not measured in this run)"
+                                        if read_traffic(wl.name) is not None else None),
                      "kernel_ms_avg": round(avg_ms, 4), "kernel_ms_min": round(min(kernel_ms), 4),
                      "kernel_ms_single_launch_avg": round(sum(kernel_ms) / len(kernel_ms), 4),
                      "algorithmic_bytes": alg_bytes},

@@ -62,6 +62,18 @@ int sr_probe_stream(const void* src, size_t read_bytes, void* dst, size_t write_
 int sr_probe_pattern(const void* src, void* dst, size_t pixels, int read_planes, int write_planes, int same_wave,
                      int blocks, int writer_every, size_t plane_pad_bytes, void* sink, void* stream);
 
+/* The assembly kernel's own mix (sr_probe_pattern with read_planes = write_planes =
+ * same_wave = 1) under other cache policies: load_policy / store_policy 0 plain, 1
+ * non-temporal, 2 agent scope, 3 system scope.  flush_every > 0: one wavefront per XCD also
+ * has its L2 write its dirty lines back after every flush_every-th of its runs.  blocks >= 8. */
+int sr_probe_policy(const void* src, void* dst, size_t pixels, int load_policy, int store_policy, int flush_every,
+                    int blocks, void* sink, void* stream);
+
+/* As sr_probe_policy, with any combination of the three cache-policy bits of a gfx950 global
+ * load / store: load_bits, store_bits = sc0 (1) | sc1 (2) | nt (4). */
+int sr_probe_policy_bits(const void* src, void* dst, size_t pixels, int load_bits, int store_bits, int blocks,
+                         void* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -45,6 +45,14 @@
 //     dictionary stays fp32, products and sums are true fp32;
 //   * CT_F8 (8-bit E4M3 storage): 4 pixels per 4-byte load, widened exactly to
 //     fp16 pairs in registers, then the fp16 steps above.
+//
+// Measurement builds (python -m paper_2303_08999_amd.build -o other.so -DSR_ABLATE_...): the
+// same launch with a part switched off, to see what that part costs.  SR_ABLATE_STORES keeps
+// every instruction but never executes the output stores; SR_ABLATE_STAGE1 skips the two
+// up-sampling passes (their barriers stay); results are then wrong by construction.
+// SR_STORES_WRITE_THROUGH writes the fp32 output of the four-pixel instantiations through the L2
+// (agent scope) instead of leaving dirty lines in it; results are unchanged.  The library built
+// by default contains none of them.
 #pragma once
 #include <type_traits>
 
@@ -525,8 +533,14 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         //     LDS traffic cost more than the shorter gap between tiles gains.)
         stage1_setup(cur, tid);
         __syncthreads();
+#ifdef SR_ABLATE_STAGE1
+        if (a.N < 0)
+#endif
         stage1_vertical(cur, tid);
         __syncthreads();      // also: every wavefront is done with the previous tile's U
+#ifdef SR_ABLATE_STAGE1
+        if (a.N < 0)
+#endif
         stage1_horizontal(tid);
         __syncthreads();
         const unsigned* pt = ptab + hf * F::NLOAD;
@@ -663,7 +677,11 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                                                                  __float_as_uint(outp[c][q + PX / 2]), false, false);
                 tot[q] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
             }
+#ifdef SR_ABLATE_STORES
+            if (valid && a.N < 0) {                       // never true: the stores stay in the code, unexecuted
+#else
             if (valid) {
+#endif
                 const unsigned oe = o0 + c * plane_px;
                 if (a.io_f16) {
                     __half* op = (__half*)(out_img + (size_t)(oe * 2u));
@@ -681,7 +699,13 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 } else {
                     float* op = (float*)(out_img + (size_t)(oe * 4u));
                     if constexpr (PX == 8) *(float4*)op = make_float4(tot[0], tot[1], tot[2], tot[3]);
+#ifdef SR_STORES_WRITE_THROUGH
+                    else if constexpr (PX == 4)
+                        __hip_atomic_store((unsigned long long*)op, __builtin_bit_cast(unsigned long long, make_float2(tot[0], tot[1])),
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#else
                     else if constexpr (PX == 4) *(float2*)op = make_float2(tot[0], tot[1]);
+#endif
                     else op[0] = tot[0];
                 }
             }

@@ -125,12 +125,25 @@ __global__ __launch_bounds__(256) void k_probe_stream(const u32x4* __restrict__ 
 // (8 bytes per lane, as the assembly kernel writes).  SAME: every wavefront reads and
 // writes its runs (the next run's loads issued before this run's stores); otherwise
 // every writer_every-th workgroup only writes and the others only read.
-template <int RMODE, int WMODE, bool SAME>
+__device__ __forceinline__ void st16(void* a, float4 v, bool wt) {
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const f32x4 r = {v.x, v.y, v.z, v.w};
+    if (wt) asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(a), "v"(r) : "memory");
+    else *(f32x4*)a = r;
+}
+__device__ __forceinline__ void st8(void* a, float2 v, bool wt) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const f32x2 r = {v.x, v.y};
+    if (wt) asm volatile("global_store_dwordx2 %0, %1, off sc1" : : "v"(a), "v"(r) : "memory");
+    else *(f32x2*)a = r;
+}
+
+template <int RMODE, int WMODE, bool SAME, bool WT = false>
 __global__ __launch_bounds__(256) void k_probe_pattern(const char* __restrict__ src, char* __restrict__ dst,
                                                        size_t pixels, size_t plane_b, int writer_every, unsigned* sink) {
-    constexpr int NL = RMODE == 0 ? 18 : 36;
-    constexpr int RUN = RMODE == 2 ? 256 : 128;                       // pixels per run
-    typedef typename std::conditional<RMODE == 1, u32x2, u32x4>::type V;
+    constexpr int NL = RMODE == 0 ? 18 : (RMODE >= 3 ? 72 : 36);
+    constexpr int RUN = RMODE == 2 || RMODE == 3 ? 256 : (RMODE == 4 ? 512 : 128);   // pixels per run
+    typedef typename std::conditional<RMODE == 1 || RMODE == 3, u32x2, u32x4>::type V;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hf = lane >> 5, j = lane & 31;
     const size_t runs = pixels / RUN;
     const size_t b = blockIdx.x, nb = gridDim.x;
@@ -146,6 +159,10 @@ __global__ __launch_bounds__(256) void k_probe_pattern(const char* __restrict__ 
             const char* q = src + u * (size_t)(72 * 256) + (size_t)lane * 16;
 #pragma unroll
             for (int i = 0; i < NL; ++i) v[i] = __builtin_nontemporal_load((const V*)(q + (size_t)i * 1024));
+        } else if constexpr (RMODE >= 3) {
+            const char* q = src + u * (RUN * 2) + (size_t)lane * sizeof(V);
+#pragma unroll
+            for (int i = 0; i < NL; ++i) v[i] = __builtin_nontemporal_load((const V*)(q + (size_t)i * plane_b));
         } else {
             const char* q = src + u * (RUN * 2) + (size_t)j * sizeof(V) + (size_t)hf * plane_b;
 #pragma unroll
@@ -157,23 +174,31 @@ __global__ __launch_bounds__(256) void k_probe_pattern(const char* __restrict__ 
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             acc ^= v[i][0] ^ v[i][1];
-            if constexpr (RMODE != 1) acc ^= v[i][2] ^ v[i][3];
+            if constexpr (RMODE != 1 && RMODE != 3) acc ^= v[i][2] ^ v[i][3];
         }
         return acc;
     };
     auto store_run = [&](size_t u, float f) {
         if constexpr (WMODE == 0) {
             char* q = dst + u * 1536;
-            *(float4*)(q + (size_t)lane * 16) = make_float4(f, f + 1.0f, f, f);
-            if (lane < 32) *(float4*)(q + 1024 + (size_t)lane * 16) = make_float4(f, f, f + 2.0f, f);
-        } else if constexpr (RMODE == 2) {
+            st16(q + (size_t)lane * 16, make_float4(f, f + 1.0f, f, f), WT);
+            if (lane < 32) st16(q + 1024 + (size_t)lane * 16, make_float4(f, f, f + 2.0f, f), WT);
+        } else if constexpr (WMODE == 2) {
+            (void)u; (void)f;                               // read only
+        } else if constexpr (RMODE == 2 || RMODE == 3) {
 #pragma unroll
             for (int c = 0; c < 3; ++c)
-                *(float4*)(dst + ((size_t)c * pixels + u * 256 + 8 * j + 4 * hf) * 4) = make_float4(f, f + (float)c, f, f);
+                st16(dst + ((size_t)c * pixels + u * 256 + 4 * lane) * 4, make_float4(f, f + (float)c, f, f), WT);
+        } else if constexpr (RMODE == 4) {
+#pragma unroll
+            for (int c = 0; c < 3; ++c)
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2)
+                    st16(dst + ((size_t)c * pixels + u * 512 + 256 * h2 + 4 * lane) * 4, make_float4(f, f + (float)c, f, f), WT);
         } else {
 #pragma unroll
             for (int c = 0; c < 3; ++c)
-                *(float2*)(dst + ((size_t)c * pixels + u * 128 + 4 * j + 2 * hf) * 4) = make_float2(f, f + (float)c);
+                st8(dst + ((size_t)c * pixels + u * 128 + 4 * j + 2 * hf) * 4, make_float2(f, f + (float)c), WT);
         }
     };
     if (writer) {
@@ -193,6 +218,159 @@ __global__ __launch_bounds__(256) void k_probe_pattern(const char* __restrict__ 
         if (SAME) store_run(u, (float)(acc & 0xffu));
     }
     if (keep == 0x9e3779b9u) *sink = keep;
+}
+
+
+// The assembly kernel's own mix (256-byte pieces of 72 planes in, 512-byte pieces of 3 planes
+// out, every wavefront does both) under other cache policies.  LP / SP, policy of the loads /
+// stores: 0 plain, 1 non-temporal, 2 agent scope (sc1), 3 system scope (sc0 sc1), the scoped forms
+// as relaxed atomics.  flush_every > 0: one wavefront per XCD also asks its L2 to write its dirty
+// lines back (an agent-scope release fence) after every flush_every-th run.
+template <int LP, int SP>
+__global__ __launch_bounds__(256) void k_probe_policy(const char* __restrict__ src, char* __restrict__ dst,
+                                                      size_t pixels, int flush_every, unsigned* sink) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hf = lane >> 5, j = lane & 31;
+    const size_t runs = pixels / 128, plane_b = pixels * 2, stride = (size_t)gridDim.x * 4;
+    auto load_run = [&](size_t u, unsigned long long (&v)[36]) {
+        const char* q = src + u * 256 + (size_t)j * 8 + (size_t)hf * plane_b;
+#pragma unroll
+        for (int i = 0; i < 36; ++i) {
+            const unsigned long long* a = (const unsigned long long*)(q + (size_t)(2 * i) * plane_b);
+            if constexpr (LP == 0) v[i] = *a;
+            else if constexpr (LP == 1) v[i] = __builtin_nontemporal_load(a);
+            else if constexpr (LP == 2) v[i] = __hip_atomic_load(a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else v[i] = __hip_atomic_load(a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    };
+    size_t u = (size_t)blockIdx.x * 4 + wave;
+    if (u >= runs) return;
+    unsigned long long v[36];
+    load_run(u, v);
+    unsigned keep = 0;
+    const bool flusher = flush_every > 0 && blockIdx.x < 8 && wave == 0;
+    int it = 0;
+    for (; u < runs; u += stride) {
+        unsigned long long acc = 0;
+#pragma unroll
+        for (int i = 0; i < 36; ++i) acc ^= v[i];
+        keep ^= (unsigned)acc ^ (unsigned)(acc >> 32);
+        if (u + stride < runs) load_run(u + stride, v);
+        const float f = (float)(acc & 0xffu);
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            float2 val = make_float2(f, f + (float)c);
+            unsigned long long bits = __builtin_bit_cast(unsigned long long, val);
+            unsigned long long* a = (unsigned long long*)(dst + ((size_t)c * pixels + u * 128 + 4 * j + 2 * hf) * 4);
+            if constexpr (SP == 0) *a = bits;
+            else if constexpr (SP == 1) __builtin_nontemporal_store(bits, a);
+            else if constexpr (SP == 2) __hip_atomic_store(a, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else __hip_atomic_store(a, bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+        if (flusher && ++it % flush_every == 0) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    }
+    if (keep == 0x9e3779b9u) *sink = keep;
+}
+
+// The same mix with every combination of the three cache-policy bits of a global load or store
+// (sc0 = 1, sc1 = 2, nt = 4), which only assembly text can spell.  The compiler does not track
+// loads it did not emit, so the waits are written out: the loaded registers pass through the
+// wait statements and cannot be read before them.
+template <int BITS> __device__ __forceinline__ unsigned long long policy_load(const void* a);
+template <int BITS> __device__ __forceinline__ void policy_store(void* a, unsigned long long v);
+#define SR_POLICY_LOAD(bits, text)                                                                        \
+    template <> __device__ __forceinline__ unsigned long long policy_load<bits>(const void* a) {          \
+        unsigned long long v;                                                                             \
+        asm volatile("global_load_dwordx2 %0, %1, off" text : "=v"(v) : "v"(a) : "memory");               \
+        return v;                                                                                         \
+    }                                                                                                     \
+    template <> __device__ __forceinline__ void policy_store<bits>(void* a, unsigned long long v) {       \
+        asm volatile("global_store_dwordx2 %0, %1, off" text : : "v"(a), "v"(v) : "memory");              \
+    }
+SR_POLICY_LOAD(0, "")
+SR_POLICY_LOAD(1, " sc0")
+SR_POLICY_LOAD(2, " sc1")
+SR_POLICY_LOAD(3, " sc0 sc1")
+SR_POLICY_LOAD(4, " nt")
+SR_POLICY_LOAD(5, " sc0 nt")
+SR_POLICY_LOAD(6, " sc1 nt")
+SR_POLICY_LOAD(7, " sc0 sc1 nt")
+#undef SR_POLICY_LOAD
+
+template <int N>
+__device__ __forceinline__ void wait_loads(unsigned long long (&v)[36]) {     // at most N memory operations stay in flight
+    static_assert(N == 0 || N == 3, "");
+#define SR_W9(o) "+v"(v[o]), "+v"(v[o + 1]), "+v"(v[o + 2]), "+v"(v[o + 3]), "+v"(v[o + 4]), "+v"(v[o + 5]), "+v"(v[o + 6]), "+v"(v[o + 7]), "+v"(v[o + 8])
+    if constexpr (N == 0) {
+        asm volatile("s_waitcnt vmcnt(0)" : SR_W9(0), SR_W9(9) : : "memory");
+        asm volatile("s_waitcnt vmcnt(0)" : SR_W9(18), SR_W9(27) : : "memory");
+    } else {
+        asm volatile("s_waitcnt vmcnt(3)" : SR_W9(0), SR_W9(9) : : "memory");
+        asm volatile("s_waitcnt vmcnt(3)" : SR_W9(18), SR_W9(27) : : "memory");
+    }
+#undef SR_W9
+}
+
+template <int LP, int SP>
+__global__ __launch_bounds__(256) void k_probe_policy_bits(const char* __restrict__ src, char* __restrict__ dst,
+                                                           size_t pixels, unsigned* sink) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hf = lane >> 5, j = lane & 31;
+    const size_t runs = pixels / 128, plane_b = pixels * 2, stride = (size_t)gridDim.x * 4;
+    size_t u = (size_t)blockIdx.x * 4 + wave;
+    if (u >= runs) return;
+    unsigned long long v[36];
+    {
+        const char* q = src + u * 256 + (size_t)j * 8 + (size_t)hf * plane_b;
+#pragma unroll
+        for (int i = 0; i < 36; ++i) v[i] = policy_load<LP>(q + (size_t)(2 * i) * plane_b);
+    }
+    wait_loads<0>(v);
+    unsigned keep = 0;
+    for (; u < runs; u += stride) {
+        unsigned long long acc = 0;
+#pragma unroll
+        for (int i = 0; i < 36; ++i) acc ^= v[i];
+        keep ^= (unsigned)acc ^ (unsigned)(acc >> 32);
+        asm volatile("" : "+v"(acc) : : "memory");          // the fold is done before the registers are loaded again
+        const bool next = u + stride < runs;
+        if (next) {
+            const char* q = src + (u + stride) * 256 + (size_t)j * 8 + (size_t)hf * plane_b;
+#pragma unroll
+            for (int i = 0; i < 36; ++i) v[i] = policy_load<LP>(q + (size_t)(2 * i) * plane_b);
+        }
+        const float f = (float)(acc & 0xffu);
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            const float2 val = make_float2(f, f + (float)c);
+            policy_store<SP>(dst + ((size_t)c * pixels + u * 128 + 4 * j + 2 * hf) * 4, __builtin_bit_cast(unsigned long long, val));
+        }
+        if (next) wait_loads<3>(v);                          // the three stores issued after the loads may still be in flight
+    }
+    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");
+    if (keep == 0x9e3779b9u) *sink = keep;
+}
+
+template <int LP>
+static auto policy_bits_kernel(int sp) -> void (*)(const char*, char*, size_t, unsigned*) {
+    switch (sp) {
+    case 0: return k_probe_policy_bits<LP, 0>;
+    case 1: return k_probe_policy_bits<LP, 1>;
+    case 2: return k_probe_policy_bits<LP, 2>;
+    case 3: return k_probe_policy_bits<LP, 3>;
+    case 4: return k_probe_policy_bits<LP, 4>;
+    case 5: return k_probe_policy_bits<LP, 5>;
+    case 6: return k_probe_policy_bits<LP, 6>;
+    default: return k_probe_policy_bits<LP, 7>;
+    }
+}
+
+template <int LP>
+static auto policy_kernel(int sp) -> void (*)(const char*, char*, size_t, int, unsigned*) {
+    switch (sp) {
+    case 0: return k_probe_policy<LP, 0>;
+    case 1: return k_probe_policy<LP, 1>;
+    case 2: return k_probe_policy<LP, 2>;
+    default: return k_probe_policy<LP, 3>;
+    }
 }
 
 }  // namespace
@@ -251,13 +429,17 @@ extern "C" __attribute__((visibility("default")))
 int sr_probe_pattern(const void* src, void* dst, size_t pixels, int read_planes, int write_planes, int same_wave,
                      int blocks, int writer_every, size_t plane_pad_bytes, void* sink, void* stream) {
     if (!src || !dst || !sink) return SR_ERR_NULL;
-    if (pixels % 256 != 0 || read_planes < 0 || read_planes > 2 || (read_planes == 2 && !(write_planes && same_wave)) ||
+    if (pixels % 512 != 0 || read_planes < 0 || read_planes > 4 || write_planes < 0 || write_planes > 3 ||
+        ((read_planes >= 2 || write_planes >= 2) && !(write_planes && same_wave)) ||
         plane_pad_bytes % 16 != 0 || (plane_pad_bytes && !read_planes) || blocks < 1 || blocks > (1 << 20) || (!same_wave && (writer_every < 2 || blocks < writer_every)))
         return SR_ERR_UNSUPPORTED;
     if ((uintptr_t)src % 16 != 0 || (uintptr_t)dst % 16 != 0 || (uintptr_t)sink % 4 != 0) return SR_ERR_ALIGN;
     if (pixels == 0) return SR_OK;
     void (*kern)(const char*, char*, size_t, size_t, int, unsigned*);
-    const int sel = read_planes == 2 ? 8 : ((read_planes ? 4 : 0) | (write_planes ? 2 : 0) | (same_wave ? 1 : 0));
+    const bool wt = write_planes == 3;                    // agent-scope write-through stores
+    if (wt) write_planes = 1;
+    const int sel = wt ? 16 + read_planes : write_planes == 2 ? 11 + read_planes : (read_planes >= 2 ? 6 + read_planes :
+                    ((read_planes ? 4 : 0) | (write_planes ? 2 : 0) | (same_wave ? 1 : 0)));
     switch (sel) {
     case 0: kern = k_probe_pattern<0, 0, false>; break;
     case 1: kern = k_probe_pattern<0, 0, true>; break;
@@ -267,9 +449,62 @@ int sr_probe_pattern(const void* src, void* dst, size_t pixels, int read_planes,
     case 5: kern = k_probe_pattern<1, 0, true>; break;
     case 6: kern = k_probe_pattern<1, 1, false>; break;
     case 7: kern = k_probe_pattern<1, 1, true>; break;
-    default: kern = k_probe_pattern<2, 1, true>; break;
+    case 8: kern = k_probe_pattern<2, 1, true>; break;
+    case 9: kern = k_probe_pattern<3, 1, true>; break;
+    case 10: kern = k_probe_pattern<4, 1, true>; break;
+    case 11: kern = k_probe_pattern<0, 2, true>; break;
+    case 12: kern = k_probe_pattern<1, 2, true>; break;
+    case 13: kern = k_probe_pattern<2, 2, true>; break;
+    case 14: kern = k_probe_pattern<3, 2, true>; break;
+    case 15: kern = k_probe_pattern<4, 2, true>; break;
+    case 16: kern = k_probe_pattern<0, 0, true, true>; break;
+    case 17: kern = k_probe_pattern<1, 1, true, true>; break;
+    case 18: kern = k_probe_pattern<2, 1, true, true>; break;
+    case 19: kern = k_probe_pattern<3, 1, true, true>; break;
+    default: kern = k_probe_pattern<4, 1, true, true>; break;
     }
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
                        (const char*)src, (char*)dst, pixels, pixels * 2 + plane_pad_bytes, writer_every, (unsigned*)sink);
+    return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_LAUNCH;
+}
+
+extern "C" __attribute__((visibility("default")))
+int sr_probe_policy(const void* src, void* dst, size_t pixels, int load_policy, int store_policy, int flush_every,
+                    int blocks, void* sink, void* stream) {
+    if (!src || !dst || !sink) return SR_ERR_NULL;
+    if (pixels % 128 != 0 || load_policy < 0 || load_policy > 3 || store_policy < 0 || store_policy > 3 ||
+        flush_every < 0 || blocks < 8 || blocks > (1 << 20))
+        return SR_ERR_UNSUPPORTED;
+    if ((uintptr_t)src % 16 != 0 || (uintptr_t)dst % 16 != 0 || (uintptr_t)sink % 4 != 0) return SR_ERR_ALIGN;
+    if (pixels == 0) return SR_OK;
+    auto kern = load_policy == 0 ? policy_kernel<0>(store_policy) : load_policy == 1 ? policy_kernel<1>(store_policy)
+              : load_policy == 2 ? policy_kernel<2>(store_policy) : policy_kernel<3>(store_policy);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
+                       (const char*)src, (char*)dst, pixels, flush_every, (unsigned*)sink);
+    return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_LAUNCH;
+}
+
+extern "C" __attribute__((visibility("default")))
+int sr_probe_policy_bits(const void* src, void* dst, size_t pixels, int load_bits, int store_bits, int blocks,
+                         void* sink, void* stream) {
+    if (!src || !dst || !sink) return SR_ERR_NULL;
+    if (pixels % 128 != 0 || load_bits < 0 || load_bits > 7 || store_bits < 0 || store_bits > 7 || blocks < 1 ||
+        blocks > (1 << 20))
+        return SR_ERR_UNSUPPORTED;
+    if ((uintptr_t)src % 16 != 0 || (uintptr_t)dst % 16 != 0 || (uintptr_t)sink % 4 != 0) return SR_ERR_ALIGN;
+    if (pixels == 0) return SR_OK;
+    void (*kern)(const char*, char*, size_t, unsigned*);
+    switch (load_bits) {
+    case 0: kern = policy_bits_kernel<0>(store_bits); break;
+    case 1: kern = policy_bits_kernel<1>(store_bits); break;
+    case 2: kern = policy_bits_kernel<2>(store_bits); break;
+    case 3: kern = policy_bits_kernel<3>(store_bits); break;
+    case 4: kern = policy_bits_kernel<4>(store_bits); break;
+    case 5: kern = policy_bits_kernel<5>(store_bits); break;
+    case 6: kern = policy_bits_kernel<6>(store_bits); break;
+    default: kern = policy_bits_kernel<7>(store_bits); break;
+    }
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
+                       (const char*)src, (char*)dst, pixels, (unsigned*)sink);
     return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_LAUNCH;
 }
