@@ -13,6 +13,7 @@ import pytest
 torch = pytest.importorskip("torch")
 import paper_2303_08999_amd as sr
 import sr_synth
+from test_gpu_parity import parity_bound
 from test_oracle_mutations import MUTATIONS, ROOT, SRC
 
 pytestmark = pytest.mark.gpu
@@ -22,7 +23,11 @@ pytestmark = pytest.mark.gpu
 PLANTED = ["keys_inner_coefficient", "keys_outer_coefficient", "no_half_pixel_centres", "first_tap_off_by_one",
            "inner_tap_weights_swapped", "upsampler_axes_transposed", "lr_border_not_replicated",
            "kept_position_instead_of_atom", "gamma_dropped", "filter_transposed", "filter_flipped",
-           "patch_not_centred", "hr_border_zero_instead_of_replicate", "same_channel_for_all"]
+           "patch_not_centred", "hr_border_zero_instead_of_replicate", "same_channel_for_all",
+           # a precision mistake, not a structural one: the dictionary with 11 significant bits (what a single
+           # fp16 operand would hold; about 5e-4 relative).  Inside the stated 2e-3 target, outside the bound
+           # the tests assert.
+           "dictionary_rounded_to_half"]
 
 
 def _oracle_copy(text, workdir, tag):
@@ -42,8 +47,8 @@ def _oracle_copy(text, workdir, tag):
     return mod
 
 
-@pytest.mark.parametrize("coeff_dtype,tol", [("f16", 2e-3), ("f32", 1e-5)])
-def test_parity_tolerances_tell_broken_oracles_apart(tmp_path, coeff_dtype, tol):
+@pytest.mark.parametrize("coeff_dtype", ["f16", "f8", "f32"])
+def test_parity_tolerances_tell_broken_oracles_apart(tmp_path, coeff_dtype):
     wl = sr_synth.Workload("sharp", 23, 1, 3, 21, 34, 2, 40, 5, coeff_dtype, "f32", 0.0, 1.5)
     inp = sr_synth.make_inputs(wl, "cuda")
     kept = np.array([5, 1, 33, 8, 20, 39, 2], dtype=np.int32)       # any order, not sorted
@@ -57,8 +62,7 @@ def test_parity_tolerances_tell_broken_oracles_apart(tmp_path, coeff_dtype, tol)
 
     def agrees(mod):
         ref = mod.dict_assemble(lr, cf, D, wl.scale, kept=kept, gamma=gamma.astype(np.float64))
-        bound = tol if coeff_dtype == "f16" else tol * np.maximum(1.0, np.abs(ref))
-        return bool((np.abs(got - ref) <= bound).all())
+        return bool((np.abs(got - ref) <= parity_bound(ref, coeff_dtype)).all())
 
     text = open(SRC).read()
     assert agrees(_oracle_copy(text, str(tmp_path), "control")), "GPU result disagrees with the true oracle"

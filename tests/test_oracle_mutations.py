@@ -26,6 +26,9 @@ MUTATIONS = {
     "lr_column_clamped_to_height": ("clampl(fx + j, 0, w - 1)", "clampl(fx + j, 0, h - 1)"),
     "lr_border_not_replicated": ("long yy = clampl(fy + i, 0, h - 1);", "long yy = clampl(fy + i, 1, h - 1);"),
     "kept_position_instead_of_atom": ("F[j] += phi * dict[(size_t)l * kk + j];", "F[j] += phi * dict[(size_t)i * kk + j];"),
+    "dictionary_rounded_to_half": (
+        "F[j] += phi * dict[(size_t)l * kk + j];",
+        "{ int e2; double m2 = frexp((double)dict[(size_t)l * kk + j], &e2); F[j] += phi * ldexp(nearbyint(ldexp(m2, 11)), e2 - 11); }"),
     "gamma_dropped": ("        if (gamma)\n            phi *= gamma[i];", "        (void)gamma;"),
     "filter_transposed": ("acc += F[dy * k + dx] * Uplane", "acc += F[dx * k + dy] * Uplane"),
     "filter_flipped": ("clampl(Y + dy - r, 0, H - 1)", "clampl(Y - dy + r, 0, H - 1)"),
