@@ -89,7 +89,9 @@ typedef enum {
 
 typedef struct {
     int kernel;                /* sr_kernel                                        */
-    int tile;                  /* MFMA kernel tile shape index, 0 = default        */
+    int tile;                  /* matrix-core kernel tile shape index, 0 = the
+                                  library's default for the frame; see
+                                  sr_dict_assemble_tile                            */
     int reserved[6];           /* must be zero                                     */
 } sr_options;
 
@@ -143,8 +145,18 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
  *   f16 and bf16 coefficients: at most 128 folded atoms (k = 5, C = 2 or 4: 72);
  *   f32 coefficients: at most 128 folded atoms; k = 7: 17 to 128;
  *   f8  coefficients: as f32, and lr->data 4-byte aligned with an even number of
- *                     elements if the image is f16.
+ *                     elements if the image is f16;
+ *   images beyond 4 GB of coefficients (element offsets): at most 72 folded atoms.
  * Every other supported case runs on the generic kernel.
+ *
+ * opts->tile (the launch-shape search of section III-B, Eq. 11-12, as a small set of compiled
+ * tile shapes): index 0 is the library's default for the frame and is always accepted.  Other
+ * indices exist only where alternative shapes are built - k = 5, C = 3, 65 to 72 folded f16
+ * atoms, byte offsets: 1 = 64x8, 2 = 128x4, 3 = 64x16, 4 = 128x8, 5 = 64x32, 6 = 128x16,
+ * 7 = 128x24 (scale 4 only) HR pixels per workgroup, i.e. 1, 1, 2, 2, 4, 4, 6 row groups per
+ * wavefront - and are an option of the matrix-core kernel: with SR_KERNEL_AUTO or
+ * SR_KERNEL_MFMA an index the case does not have is SR_ERR_UNSUPPORTED, never a silent
+ * fall-back, so a sweep over the indices times each accepted one as a different kernel.
  */
 int sr_dict_assemble_ex(const sr_tensor* lr, const sr_tensor* coeff, const sr_tensor* dict,
                         int L, int k, int scale, int channels,
@@ -169,6 +181,15 @@ int sr_dict_assemble_plan(const sr_tensor* lr, const sr_tensor* coeff, const sr_
                           int L, int k, int scale, int channels,
                           const sr_tensor* out,
                           const int* kept, int n_kept, const sr_options* opts);
+
+/* As sr_dict_assemble_plan, and also reports the tile (HR pixels per workgroup) of the
+ * matrix-core instantiation that would run: *tile_w x *tile_h, or 0 x 0 where the library
+ * does not report it (generic kernel; families with a single built shape).  Host only. */
+int sr_dict_assemble_tile(const sr_tensor* lr, const sr_tensor* coeff, const sr_tensor* dict,
+                          int L, int k, int scale, int channels,
+                          const sr_tensor* out,
+                          const int* kept, int n_kept, const sr_options* opts,
+                          int* tile_w, int* tile_h);
 
 /* Static, NUL-terminated description of a status code. */
 const char* sr_strerror(int status);

@@ -18,8 +18,8 @@ SR_KERNEL_AUTO, SR_KERNEL_GENERIC, SR_KERNEL_MFMA = 0, 1, 2
 SR_MAX_ATOMS = 256
 
 EXPORTS = ("sr_dict_assemble", "sr_dict_assemble_selective", "sr_dict_assemble_ex",
-           "sr_bicubic_upsample", "sr_dict_assemble_plan", "sr_strerror", "sr_version",
-           "sr_probe_read", "sr_probe_mix", "sr_probe_stream", "sr_probe_pattern",
+           "sr_bicubic_upsample", "sr_dict_assemble_plan", "sr_dict_assemble_tile", "sr_strerror", "sr_version",
+           "sr_probe_read", "sr_probe_mix", "sr_probe_stream", "sr_probe_pattern", "sr_probe_policy", "sr_probe_policy_bits",
            "sr_atom_gram_workspace_bytes", "sr_atom_gram", "sr_select_atoms")
 
 
@@ -58,11 +58,14 @@ def load():
     lib.sr_dict_assemble_selective.argtypes = [T, T, T, i, i, i, i, T, vp, ip, i, fp]
     lib.sr_dict_assemble_ex.argtypes = [T, T, T, i, i, i, i, T, vp, ip, i, fp, O]
     lib.sr_dict_assemble_plan.argtypes = [T, T, T, i, i, i, i, T, ip, i, O]
+    lib.sr_dict_assemble_tile.argtypes = [T, T, T, i, i, i, i, T, ip, i, O, ip, ip]
     lib.sr_bicubic_upsample.argtypes = [T, i, i, T, vp]
     lib.sr_strerror.argtypes = [i]
     lib.sr_probe_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     lib.sr_probe_mix.argtypes = [vp, i, ctypes.c_size_t, vp, i, vp]
     lib.sr_probe_pattern.argtypes = [vp, vp, ctypes.c_size_t, i, i, i, i, i, ctypes.c_size_t, vp, vp]
+    lib.sr_probe_policy.argtypes = [vp, vp, ctypes.c_size_t, i, i, i, i, vp, vp]
+    lib.sr_probe_policy_bits.argtypes = [vp, vp, ctypes.c_size_t, i, i, i, vp, vp]
     lib.sr_probe_stream.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_size_t, i, i, i, i, vp, vp]
     dp = ctypes.POINTER(ctypes.c_double)
     lib.sr_atom_gram_workspace_bytes.argtypes = [i]
@@ -177,6 +180,17 @@ def sr_dict_assemble_plan(lr, coeff, dict, L, k, scale, channels, out, kept=None
     return load().sr_dict_assemble_plan(a, b, c, L, k, scale, channels, o, ka, n, op)
 
 
+def sr_dict_assemble_tile(lr, coeff, dict, L, k, scale, channels, out, kept=None, n_kept=None, opts=None):
+    """(kernel or negative status, tile width, tile height) the call would run with."""
+    a, b, c, o = describe(lr), describe(coeff), describe(_dict4(dict)), describe(out)
+    ka, n, _ga, _keep = _host_lists(kept, None)
+    n = n if n_kept is None else int(n_kept)
+    op = ctypes.byref(opts) if opts is not None else None
+    tw, th = ctypes.c_int(0), ctypes.c_int(0)
+    st = load().sr_dict_assemble_tile(a, b, c, L, k, scale, channels, o, ka, n, op, ctypes.byref(tw), ctypes.byref(th))
+    return st, tw.value, th.value
+
+
 def sr_bicubic_upsample(lr, scale, channels, out, stream=None):
     _check(load().sr_bicubic_upsample(describe(lr), scale, channels, describe(out), _stream(stream)))
     return out
@@ -217,6 +231,21 @@ def sr_probe_pattern(src, dst, pixels, read_planes, write_planes, same_wave, blo
                                    int(read_planes), int(write_planes), int(same_wave), blocks, writer_every,
                                    plane_pad_bytes,
                                    ctypes.c_void_p(sink.data_ptr()), _stream(stream)))
+
+
+def sr_probe_policy(src, dst, pixels, load_policy, store_policy, flush_every, blocks, sink, stream=None):
+    """The assembly kernel's byte mix under other cache policies (include/sr_probe.h)."""
+    assert src.numel() * src.element_size() >= 144 * pixels and dst.numel() * dst.element_size() >= 12 * pixels
+    _check(load().sr_probe_policy(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(dst.data_ptr()), pixels,
+                                  load_policy, store_policy, flush_every, blocks,
+                                  ctypes.c_void_p(sink.data_ptr()), _stream(stream)))
+
+
+def sr_probe_policy_bits(src, dst, pixels, load_bits, store_bits, blocks, sink, stream=None):
+    """The assembly kernel's byte mix under any cache-policy bits, sc0 | sc1 << 1 | nt << 2 (include/sr_probe.h)."""
+    assert src.numel() * src.element_size() >= 144 * pixels and dst.numel() * dst.element_size() >= 12 * pixels
+    _check(load().sr_probe_policy_bits(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(dst.data_ptr()), pixels,
+                                       load_bits, store_bits, blocks, ctypes.c_void_p(sink.data_ptr()), _stream(stream)))
 
 
 def sr_atom_gram_workspace_bytes(L: int) -> int:

@@ -57,7 +57,8 @@ void make_plan(Plan& p, const sr_tensor* lr, const sr_tensor* coeff, const sr_te
         coeff->n != lr->n || out->n != lr->n ||
         (int64_t)lr->h * scale != coeff->h || (int64_t)lr->w * scale != coeff->w ||
         out->h != coeff->h || out->w != coeff->w) { p.status = SR_ERR_SHAPE; return; }
-    if ((int64_t)lr->n > 65535 || (int64_t)coeff->h > (1 << 18) || (int64_t)coeff->w > (1 << 20)) {
+    // limits of the launch grids: the generic kernel takes four rows per workgroup in grid.y (<= 65535)
+    if ((int64_t)lr->n > 65535 || (int64_t)coeff->h > 4 * 65535 || (int64_t)coeff->w > (1 << 20)) {
         p.status = SR_ERR_UNSUPPORTED; return;
     }
     if (opts) {
@@ -99,7 +100,8 @@ void make_plan(Plan& p, const sr_tensor* lr, const sr_tensor* coeff, const sr_te
     const int want = opts ? opts->kernel : SR_KERNEL_AUTO;
     const int tile = opts ? opts->tile : 0;
     const bool can_mfma = !p.empty && mfma_supported(a, k, coeff->dtype, tile);
-    if (want == SR_KERNEL_MFMA && !can_mfma) { p.status = SR_ERR_UNSUPPORTED; return; }
+    // a tile index other than 0 is an option of the matrix-core kernel: it never falls back silently
+    if ((want == SR_KERNEL_MFMA || (tile != 0 && want != SR_KERNEL_GENERIC)) && !can_mfma) { p.status = SR_ERR_UNSUPPORTED; return; }
     p.kernel = (want == SR_KERNEL_GENERIC || !can_mfma) ? SR_KERNEL_GENERIC : SR_KERNEL_MFMA;
     p.tile = tile;
 }
@@ -143,6 +145,18 @@ __attribute__((visibility("default"))) int sr_dict_assemble_plan(const sr_tensor
     Plan p;
     make_plan(p, lr, coeff, dict, L, k, scale, channels, out, kept, n_kept, nullptr, opts);
     return p.status != SR_OK ? p.status : p.kernel;
+}
+
+__attribute__((visibility("default"))) int sr_dict_assemble_tile(const sr_tensor* lr, const sr_tensor* coeff, const sr_tensor* dict,
+                          int L, int k, int scale, int channels, const sr_tensor* out,
+                          const int* kept, int n_kept, const sr_options* opts, int* tile_w, int* tile_h) {
+    if (!tile_w || !tile_h) return SR_ERR_NULL;
+    Plan p;
+    make_plan(p, lr, coeff, dict, L, k, scale, channels, out, kept, n_kept, nullptr, opts);
+    if (p.status != SR_OK) return p.status;
+    *tile_w = *tile_h = 0;
+    if (p.kernel == SR_KERNEL_MFMA && !p.empty) mfma_tile_shape(p.args, k, coeff->dtype, p.tile, tile_w, tile_h);
+    return p.kernel;
 }
 
 __attribute__((visibility("default"))) int sr_bicubic_upsample(const sr_tensor* lr, int scale, int channels, sr_tensor* out, void* stream) {

@@ -11,5 +11,6 @@ hipError_t launch_bicubic(const BicubicArgs& a, bool in_f16, bool out_f16, hipSt
 // Matrix-core kernel.  mfma_supported() is a pure host-side predicate.
 bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile);
 hipError_t launch_mfma(const AssembleArgs& a, int k, bool io_f16, int tile, hipStream_t st);
+bool mfma_tile_shape(const AssembleArgs& a, int k, int coeff_dtype, int tile, int* tw, int* th);
 
 }  // namespace srd

@@ -7,6 +7,7 @@ namespace srd {
 
 hipError_t launch_mfma_k3(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_k5(const AssembleArgs& a, int np8, int shape, hipStream_t st);
+bool tile_shape_k5(const AssembleArgs& a, int shape, int* tw, int* th);
 hipError_t launch_mfma_k7(const AssembleArgs& a, int np8, int shape, hipStream_t st);
 hipError_t launch_mfma_k5_f32(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_k7_f32(const AssembleArgs& a, int np8, hipStream_t st);
@@ -17,7 +18,6 @@ hipError_t launch_mfma_bf16(const AssembleArgs& a, int k, int np8, hipStream_t s
 
 namespace {
 
-constexpr int N_TILE_SHAPES = 6;
 
 // Capacity (in groups of 8 folded atoms) of the smallest built instantiation
 // that holds n_fold atoms; 0 = none.  Unused capacity costs MFMA issue slots
@@ -63,9 +63,20 @@ unsigned long long coeff_bytes(int coeff_dtype) {
 bool beyond_4gb(const AssembleArgs& a, int coeff_dtype) {
     return (unsigned long long)a.L * a.H * a.W * coeff_bytes(coeff_dtype) >= (1ull << 32);
 }
-int np8_big(int np8) { return np8 <= 1 ? 1 : (np8 <= 4 ? 4 : 9); }
+int np8_big(int np8) { return np8 <= 1 ? 1 : (np8 <= 4 ? 4 : (np8 <= 9 ? 9 : 0)); }   // 0: none built
 
 }  // namespace
+
+static bool has_tile_shapes(const AssembleArgs& a, int k, int np8, int coeff_dtype) {
+    return k == 5 && a.C == 3 && np8 == 9 && coeff_dtype == SR_F16 && !beyond_4gb(a, coeff_dtype);
+}
+
+// Tile of the instantiation that serves the call, where the library can say (the family with
+// alternative shapes); false elsewhere.
+bool mfma_tile_shape(const AssembleArgs& a, int k, int coeff_dtype, int tile, int* tw, int* th) {
+    const int np8 = np8_for(k, a.C, a.n_fold, coeff_dtype);
+    return has_tile_shapes(a, k, np8, coeff_dtype) && tile_shape_k5(a, tile, tw, th);
+}
 
 // pixels a lane loads with one vector load (its pixel group)
 static int pixel_group(int k, int coeff_dtype) {
@@ -89,15 +100,25 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
           (unsigned long long)a.L * a.H * a.W < (1ull << 32)))
         return false;
     if ((unsigned long long)a.C * a.H * a.W * 4ull >= (1ull << 32)) return false;          // 32-bit offsets within an image
-    if (np8_for(k, a.C, a.n_fold, coeff_dtype) == 0) return false;
-    if (tile < 0 || tile >= N_TILE_SHAPES) return false;
+    const int np8 = np8_for(k, a.C, a.n_fold, coeff_dtype);
+    if (np8 == 0) return false;
+    if (beyond_4gb(a, coeff_dtype) && np8_big(np8) == 0) return false;                     // element offsets: up to 72 atoms
+    // Alternative tile shapes exist for one family only (5x5 atoms, three channels, 65 to 72 fp16
+    // atoms, byte offsets); everywhere else only the default (index 0) is accepted, so that a
+    // sweep over the indices never times one kernel under several names.
+    if (tile < 0) return false;
+    if (tile != 0) {
+        int tw, th;
+        if (!has_tile_shapes(a, k, np8, coeff_dtype) || !tile_shape_k5(a, tile, &tw, &th)) return false;
+    }
     return true;
 }
 
 hipError_t launch_mfma(const AssembleArgs& a, int k, bool io_f16, int tile, hipStream_t st) {
     (void)io_f16;
     const int np8 = np8_for(k, a.C, a.n_fold, a.coeff_dtype);
-    if (beyond_4gb(a, a.coeff_dtype)) return launch_mfma_k5_big(a, np8_big(np8), st);
+    if (beyond_4gb(a, a.coeff_dtype))
+        return np8_big(np8) ? launch_mfma_k5_big(a, np8_big(np8), st) : hipErrorInvalidValue;
     if (a.coeff_dtype == SR_BF16 && k != 3) return launch_mfma_bf16(a, k, np8, st);
     if (k == 3) return launch_mfma_k3(a, np8, st);
     if (a.coeff_dtype == SR_F32) return k == 5 ? launch_mfma_k5_f32(a, np8, st) : launch_mfma_k7_f32(a, np8, st);

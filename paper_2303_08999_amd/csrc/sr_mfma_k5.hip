@@ -3,6 +3,31 @@
 
 namespace srd {
 
+// Tile shapes of the family with alternatives (three channels, 65 to 72 fp16 atoms), by index
+// 1 .. 7: width x height in HR pixels.  Index 7 holds half the LR footprint in LDS and runs at
+// scale 4 only.
+static const int kShapeW[8] = {0, 64, 128, 64, 128, 64, 128, 128};
+static const int kShapeH[8] = {0, 8, 4, 16, 8, 32, 16, 24};
+
+// Index 0 = the default for the frame (measured, 0.26 to 8.3 Mpixel frames at every scale):
+// small frames take 128 x 4 tiles, which put more CUs to work (512 x 512: 37 -> 26 us); at x4
+// half the footprint in LDS leaves room for 128 x 24, but up to about 1080p its few hundred tiles
+// fill the second round of the grid badly and 64 x 16 is 7-13 % faster; else 128 x 16.
+int resolve_shape_k5(const AssembleArgs& a, int shape) {
+    if (shape != 0) return (shape >= 1 && shape <= 7 && (shape != 7 || a.s == 4)) ? shape : -1;
+    const long long px = (long long)a.N * a.H * a.W;
+    if (px <= 400000) return 2;
+    if (a.s == 4) return px <= 2600000 ? 3 : 7;
+    return 6;
+}
+bool tile_shape_k5(const AssembleArgs& a, int shape, int* tw, int* th) {
+    const int r = resolve_shape_k5(a, shape);
+    if (r < 1) return false;
+    *tw = kShapeW[r];
+    *th = kShapeH[r];
+    return true;
+}
+
 // np8: capacity in groups of 8 folded atoms; shape: tile shape index (C = 3, np8 = 9 only)
 hipError_t launch_mfma_k5(const AssembleArgs& a, int np8, int shape, hipStream_t st) {
     // Few atoms: the kernel is bound by up-sampling, filtering and the output
@@ -24,26 +49,15 @@ hipError_t launch_mfma_k5(const AssembleArgs& a, int np8, int shape, hipStream_t
             if (a.s == 4) return launch_one<5, 3, 6, 4, 1, 4, 6, 2, CT_F16, 4>(a, st);
             return launch_one<5, 3, 6, 4, 1, 4, 4, 2>(a, st);
         case 9:
-            switch (shape) {
+            switch (resolve_shape_k5(a, shape)) {
             case 1:  return launch_one<5, 3, 9, 4, 2, 4, 1, 2>(a, st);    //  64 x 8
             case 2:  return launch_one<5, 3, 9, 4, 1, 4, 1, 2>(a, st);    // 128 x 4
             case 3:  return launch_one<5, 3, 9, 4, 2, 4, 2, 2>(a, st);    //  64 x 16, 2 units per wavefront
             case 4:  return launch_one<5, 3, 9, 4, 1, 4, 2, 2>(a, st);    // 128 x 8,  2 units
             case 5:  return launch_one<5, 3, 9, 4, 2, 4, 4, 2>(a, st);    //  64 x 32, 4 units
-            default: {
-                // Tile by frame size (measured, 0.26 to 8.3 Mpixel frames at every scale).
-                // Small frames: 128 x 4 tiles put more CUs to work (512 x 512: 37 -> 26 us).
-                const long long px = (long long)a.N * a.H * a.W;
-                if (px <= 400000) return launch_one<5, 3, 9, 4, 1, 4, 1, 2>(a, st);
-                // x4: half the footprint in LDS leaves room for a 128 x 24 tile (6 units); up to
-                // about 1080p its few hundred tiles fill the second round of the grid badly
-                // and 64 x 16 is 7-13 % faster
-                if (a.s == 4) {
-                    if (px <= 2600000) return launch_one<5, 3, 9, 4, 2, 4, 2, 2>(a, st);
-                    return launch_one<5, 3, 9, 4, 1, 4, 6, 2, CT_F16, 4>(a, st);
-                }
-                return launch_one<5, 3, 9, 4, 1, 4, 4, 2>(a, st);    // 128 x 16, 4 units
-            }
+            case 6:  return launch_one<5, 3, 9, 4, 1, 4, 4, 2>(a, st);    // 128 x 16, 4 units
+            case 7:  return launch_one<5, 3, 9, 4, 1, 4, 6, 2, CT_F16, 4>(a, st);   // 128 x 24, 6 units (x4 only)
+            default: return hipErrorInvalidValue;
             }
         case 16:                                                         // 73 to 128 atoms: two pixels per lane, as 7x7
             if (a.s == 4) return launch_one<5, 3, 16, 2, 1, 4, 6, 2, CT_F16, 4>(a, st);

@@ -13,7 +13,7 @@ from . import binding as _b
 
 
 def sweep_tiles(lr, coeff, dict, L, k, scale, channels, out, kept=None, gamma=None,
-                reps: int = 5, max_tiles: int = 16):
+                reps: int = 5, max_tiles: int = 8):
     """Time every tile shape of the matrix-core kernel for these arguments.
 
     Returns a list of (tile index, median milliseconds); empty if the
@@ -25,7 +25,7 @@ def sweep_tiles(lr, coeff, dict, L, k, scale, channels, out, kept=None, gamma=No
         opts = _b.make_options(_b.SR_KERNEL_MFMA, tile)
         if _b.sr_dict_assemble_plan(lr, coeff, dict, L, k, scale, channels, out, kept=kept, opts=opts) \
                 != _b.SR_KERNEL_MFMA:
-            break
+            continue                   # an index this case does not have (never a second name for another kernel)
 
         def run():
             _b.sr_dict_assemble_ex(lr, coeff, dict, L, k, scale, channels, out,

@@ -113,6 +113,76 @@ def test_plan_for_images_with_more_than_4_gb_of_coefficients(lib):
     assert plan(*big(L=128, k=7), L=128, k=7) == sr.SR_KERNEL_GENERIC
     assert plan(*big(h=2160, w=3840)) == sr.SR_KERNEL_GENERIC        # 16K: more than 2^32 coefficients
     assert plan(*big(), opts=sr.make_options(sr.SR_KERNEL_MFMA)) == sr.SR_KERNEL_MFMA
+    # the element-offset instantiations hold at most 72 folded atoms: more must not be served by them
+    for L in (73, 100, 128):
+        assert L * 4320 * 7680 < 2**32 <= 2 * L * 4320 * 7680
+        assert plan(*big(L=L), L=L) == sr.SR_KERNEL_GENERIC
+        assert plan(*big(L=L, cd=sr.SR_BF16), L=L) == sr.SR_KERNEL_GENERIC
+        assert plan(*big(L=L), L=L, opts=sr.make_options(sr.SR_KERNEL_MFMA)) == -3
+        assert plan(*big(L=L), L=L, kept=list(range(72))) == sr.SR_KERNEL_MFMA     # a list of 72 of them is fine
+        assert plan(*big(L=L), L=L, kept=list(range(73))) == sr.SR_KERNEL_GENERIC
+
+
+def tile_of(lr, coeff, d, out, L=72, k=5, s=4, C=3, kept=None, opts=None):
+    ka, n = None, 0
+    if kept is not None:
+        ka, n = (ctypes.c_int * max(1, len(kept)))(*kept), len(kept)
+    tw, th = ctypes.c_int(-1), ctypes.c_int(-1)
+    st = sr.load().sr_dict_assemble_tile(lr, coeff, d, L, k, s, C, out, ka, n,
+                                         ctypes.byref(opts) if opts is not None else None, ctypes.byref(tw), ctypes.byref(th))
+    return st, tw.value, th.value
+
+
+def test_tile_indices_name_distinct_instantiations_or_are_refused(lib):
+    """The launch-shape option (section III-B): every accepted index is a different tile, and a family
+    with one built shape accepts index 0 only - a sweep never times one kernel under several names."""
+    MF, AUTO = sr.SR_KERNEL_MFMA, sr.SR_KERNEL_AUTO
+
+    def far(**kw):                                   # the same descriptors, 64 GB apart: room for whole frames
+        ts = case(**kw)
+        for i, t in enumerate(ts):
+            t.data = 0x1000000000 * (i + 1)
+        return ts
+    shapes = {}
+    for tile in range(0, 10):
+        st, tw, th = tile_of(*far(h=540, w=960), opts=sr.make_options(MF, tile))
+        if tile <= 7:
+            assert st == MF and tw > 0 and th > 0, (tile, st)
+            shapes[tile] = (tw, th)
+        else:
+            assert st == -3
+    assert len({shapes[t] for t in range(1, 8)}) == 7                      # seven different tiles
+    assert shapes[0] == shapes[7] == (128, 24)                              # the 4K frame's default
+    assert tile_of(*far(h=64, w=64), opts=sr.make_options(MF, 0))[1:] == (128, 4)       # small frame
+    assert tile_of(*far(h=270, w=480), opts=sr.make_options(MF, 0))[1:] == (64, 16)     # 1080p at x4
+    assert tile_of(*far(h=360, w=640, s=3), s=3, opts=sr.make_options(MF, 0))[1:] == (128, 16)
+    assert tile_of(*far(h=360, w=640, s=3), s=3, opts=sr.make_options(MF, 7))[0] == -3  # 128 x 24 needs scale 4
+    # families without alternatives: index 0 only, under AUTO as well (no silent fall-back to another kernel)
+    for kw, pk in (({"cd": sr.SR_F32}, {}), ({"cd": sr.SR_F8E4M3}, {}), ({"cd": sr.SR_BF16}, {}), ({"k": 7}, {"k": 7}),
+                   ({"k": 3}, {"k": 3}), ({"C": 1}, {"C": 1}), ({"L": 40}, {"L": 40}), ({"L": 100}, {"L": 100})):
+        assert plan(*case(**kw), **pk, opts=sr.make_options(MF, 0)) == MF, kw
+        for tile in (1, 3, 5, 7):
+            assert plan(*case(**kw), **pk, opts=sr.make_options(MF, tile)) == -3, (kw, tile)
+            assert plan(*case(**kw), **pk, opts=sr.make_options(AUTO, tile)) == -3, (kw, tile)
+        assert tile_of(*case(**kw), **pk, opts=sr.make_options(MF, 0))[1:] == (0, 0)
+    assert plan(*case(), kept=list(range(30)), opts=sr.make_options(MF, 2)) == -3            # a short kept list: another capacity
+    assert plan(*case(), kept=list(range(66)), opts=sr.make_options(MF, 2)) == MF
+    assert plan(*case(), opts=sr.make_options(sr.SR_KERNEL_GENERIC, 3)) == sr.SR_KERNEL_GENERIC   # ignored by the generic kernel
+    assert tile_of(*case(), opts=sr.make_options(sr.SR_KERNEL_GENERIC, 0)) == (sr.SR_KERNEL_GENERIC, 0, 0)
+    lr, coeff, d, out = case()
+    assert sr.load().sr_dict_assemble_tile(lr, coeff, d, 72, 5, 4, 3, out, None, 0, None, None, None) == -1
+
+
+def test_tall_frames_stop_where_the_launch_grids_do(lib):
+    def tall(h):
+        ts = case(h=h, w=1, C=1)
+        for i, t in enumerate(ts):
+            t.data = 0x1000000000 * (i + 1)
+        return ts
+    G = sr.make_options(sr.SR_KERNEL_GENERIC)
+    assert plan(*tall(65535), C=1, opts=G) == sr.SR_KERNEL_GENERIC      # 262140 HR rows: the most grid.y holds
+    assert plan(*tall(65536), C=1, opts=G) == -3
+    assert plan(*tall(65536), C=1) == -3
 
 
 def test_plan_for_bfloat16_coefficients(lib):
@@ -240,6 +310,40 @@ def test_probe_argument_checks_launch_nothing(lib):
     assert lib.sr_probe_mix(good, 72, 1280, sink, 5, None) == -3
     assert lib.sr_probe_mix(good, 72, 1280, vp(0x20000008), 3, None) == -7
     assert lib.sr_probe_mix(good, 128, 0, sink, 1, None) == 0
+    # sr_probe_stream(src, read_bytes, dst, write_bytes, blocks, writer_every, lds_bytes, nt_store, sink, stream)
+    ps = lib.sr_probe_stream
+    assert ps(None, 1024, good, 1024, 26, 13, 0, 0, sink, None) == -1
+    assert ps(good, 1024, None, 1024, 26, 13, 0, 0, sink, None) == -1
+    assert ps(good, 1024, good, 1024, 26, 13, 0, 0, None, None) == -1
+    assert ps(good, 1000, None, 0, 26, 0, 0, 0, sink, None) == -3             # not a multiple of 16 bytes
+    assert ps(good, 1024, good, 1024, 26, 0, 0, 0, sink, None) == -3          # bytes to write, nobody to write them
+    assert ps(good, 1024, good, 1024, 26, 1, 0, 0, sink, None) == -3          # bytes to read, only writers
+    assert ps(good, 1024, good, 1024, 5, 13, 0, 0, sink, None) == -3          # fewer workgroups than one writer needs
+    assert ps(good, 1024, None, 0, 0, 0, 0, 0, sink, None) == -3
+    assert ps(good, 1024, None, 0, 8, 0, 161 * 1024, 0, sink, None) == -3     # more LDS than a CU has
+    assert ps(vp(0x10000008), 1024, None, 0, 8, 0, 0, 0, sink, None) == -7
+    assert ps(None, 0, None, 0, 8, 0, 0, 0, sink, None) == 0                  # nothing to do
+    # sr_probe_pattern(src, dst, pixels, read_planes, write_planes, same_wave, blocks, writer_every, pad, sink, stream)
+    pp = lib.sr_probe_pattern
+    assert pp(None, good, 512, 1, 1, 1, 8, 0, 0, sink, None) == -1
+    assert pp(good, good, 500, 1, 1, 1, 8, 0, 0, sink, None) == -3            # not whole runs
+    assert pp(good, good, 512, 5, 1, 1, 8, 0, 0, sink, None) == -3
+    assert pp(good, good, 512, 1, 4, 1, 8, 0, 0, sink, None) == -3
+    assert pp(good, good, 512, 2, 1, 0, 26, 13, 0, sink, None) == -3          # 16-byte plane reads: same-wave form only
+    assert pp(good, good, 512, 1, 1, 0, 26, 1, 0, sink, None) == -3           # every workgroup a writer
+    assert pp(good, good, 512, 0, 1, 1, 8, 0, 128, sink, None) == -3          # padding without plane reads
+    assert pp(good, good, 512, 1, 1, 1, 8, 0, 24, sink, None) == -3
+    assert pp(good, vp(0x20000004), 512, 1, 1, 1, 8, 0, 0, sink, None) == -7
+    assert pp(good, good, 0, 1, 1, 1, 8, 0, 0, sink, None) == 0
+    # sr_probe_policy(src, dst, pixels, load_policy, store_policy, flush_every, blocks, sink, stream) and its bit form
+    assert lib.sr_probe_policy(good, good, 128, 4, 0, 0, 8, sink, None) == -3
+    assert lib.sr_probe_policy(good, good, 128, 0, 0, 0, 7, sink, None) == -3   # one flushing wavefront per XCD needs 8 workgroups
+    assert lib.sr_probe_policy(good, None, 128, 0, 0, 0, 8, sink, None) == -1
+    assert lib.sr_probe_policy(good, good, 0, 0, 0, 0, 8, sink, None) == 0
+    assert lib.sr_probe_policy_bits(good, good, 128, 8, 0, 8, sink, None) == -3
+    assert lib.sr_probe_policy_bits(good, good, 100, 0, 0, 8, sink, None) == -3
+    assert lib.sr_probe_policy_bits(None, good, 128, 0, 0, 8, sink, None) == -1
+    assert lib.sr_probe_policy_bits(good, good, 0, 7, 7, 8, sink, None) == 0
 
 
 def test_e4m3_coefficients_are_a_coefficient_format_only(lib):
