@@ -76,6 +76,8 @@ def test_random_shapes_kernels_agree(seed, count, max_h, max_w):
         if max_h > 100 and wl.n > 2:
             continue
         inp = sr_synth.make_inputs(wl, DEV)
+        if tile != 0 and planned(inp, wl, MFMA, kept, tile) != MFMA:
+            tile = 0                                    # a tile index this case does not have: its default shape
         if planned(inp, wl, MFMA, kept, tile) != MFMA:
             continue
         a = run_gpu(inp, wl, MFMA, kept, gamma, tile).float()
