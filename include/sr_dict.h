@@ -74,7 +74,9 @@ typedef enum {
     SR_ERR_KEPT        = -5,   /* kept list empty, too long, out of range or with
                                   a repeated index                                 */
     SR_ERR_LAUNCH      = -6,   /* the HIP runtime refused the launch               */
-    SR_ERR_ALIGN       = -7    /* a data pointer is not aligned to its element     */
+    SR_ERR_ALIGN       = -7,   /* a data pointer is not aligned to its element     */
+    SR_ERR_SCRATCH     = -8    /* the call needs more scratch than the library's
+                                  built-in buffer holds (sr_atom_gram_static)      */
 } sr_status;
 
 /* Kernel choice for sr_dict_assemble_ex. */

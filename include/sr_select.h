@@ -38,6 +38,7 @@ extern "C" {
 #endif
 
 #define SR_SELECT_MAX_ATOMS 128
+#define SR_SELECT_STATIC_MAX_ATOMS 79      /* sr_atom_gram_static: what its built-in scratch holds */
 
 /* Bytes of DEVICE scratch sr_atom_gram needs for L atoms (0 if L is out of
  * range).  The caller allocates it; its contents before and after are
@@ -68,6 +69,21 @@ size_t sr_atom_gram_workspace_bytes(int L);
 int sr_atom_gram(const sr_tensor* up, const sr_tensor* coeff, const sr_tensor* dict,
                  const sr_tensor* target, int L, int k, int channels, int stride,
                  void* workspace, size_t workspace_bytes, double* normal, void* stream);
+
+/*
+ * sr_atom_gram for callers that cannot allocate device memory or pass a workspace: code
+ * running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments and result as sr_atom_gram without `workspace`: the per-workgroup partial
+ * sums go to a 15 MiB buffer that is part of the library's device image (every GPU the
+ * library is used on holds its own copy until the process ends).  It holds the scratch of
+ * at most SR_SELECT_STATIC_MAX_ATOMS atoms; more is SR_ERR_SCRATCH, nothing is launched.
+ * The call allocates nothing and frees nothing.  All calls on one GPU share that buffer:
+ * two of them that overlap in time (different streams, or different host threads) race;
+ * calls in stream order on one stream are fine, and nothing needs to be cleared between them.
+ */
+int sr_atom_gram_static(const sr_tensor* up, const sr_tensor* coeff, const sr_tensor* dict,
+                        const sr_tensor* target, int L, int k, int channels, int stride,
+                        double* normal, void* stream);
 
 /*
  * Alg. 1 on the normal equations (HOST arrays; no GPU work).

@@ -20,7 +20,7 @@ SR_MAX_ATOMS = 256
 EXPORTS = ("sr_dict_assemble", "sr_dict_assemble_selective", "sr_dict_assemble_ex",
            "sr_bicubic_upsample", "sr_dict_assemble_plan", "sr_dict_assemble_tile", "sr_strerror", "sr_version",
            "sr_probe_read", "sr_probe_mix", "sr_probe_stream", "sr_probe_pattern", "sr_probe_policy", "sr_probe_policy_bits",
-           "sr_atom_gram_workspace_bytes", "sr_atom_gram", "sr_select_atoms")
+           "sr_atom_gram_workspace_bytes", "sr_atom_gram", "sr_atom_gram_static", "sr_select_atoms")
 
 
 class sr_tensor(ctypes.Structure):
@@ -70,6 +70,7 @@ def load():
     dp = ctypes.POINTER(ctypes.c_double)
     lib.sr_atom_gram_workspace_bytes.argtypes = [i]
     lib.sr_atom_gram.argtypes = [T, T, T, T, i, i, i, i, vp, ctypes.c_size_t, vp, vp]
+    lib.sr_atom_gram_static.argtypes = [T, T, T, T, i, i, i, i, vp, vp]
     lib.sr_select_atoms.argtypes = [dp, i, ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_double,
                                     ip, ip, fp, dp]
     lib.sr_strerror.restype = ctypes.c_char_p
@@ -266,6 +267,14 @@ def sr_atom_gram(up, coeff, dict, target, L, k, channels, stride=1, workspace=No
                                L, k, channels, stride, ctypes.c_void_p(workspace.data_ptr()),
                                workspace.numel() * workspace.element_size(),
                                ctypes.c_void_p(normal.data_ptr()), _stream(stream)))
+    return normal
+
+
+def sr_atom_gram_static(up, coeff, dict, target, L, k, channels, stride, normal, stream=None):
+    """sr_atom_gram on the library's built-in scratch (include/sr_select.h).  Nothing is allocated,
+    here or in the library: `normal` (L*L + L + 2 float64 on the device) is the caller's."""
+    _check(load().sr_atom_gram_static(describe(up), describe(coeff), describe(_dict4(dict)), describe(target),
+                                      L, k, channels, stride, ctypes.c_void_p(normal.data_ptr()), _stream(stream)))
     return normal
 
 

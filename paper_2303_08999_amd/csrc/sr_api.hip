@@ -189,6 +189,7 @@ __attribute__((visibility("default"))) const char* sr_strerror(int status) {
     case SR_ERR_KEPT:        return "bad kept-atom list";
     case SR_ERR_LAUNCH:      return "the HIP runtime refused the kernel launch";
     case SR_ERR_ALIGN:       return "a data pointer is not aligned to its element size";
+    case SR_ERR_SCRATCH:     return "the call needs more scratch memory than the library's built-in buffer holds";
     default:                 return "unknown status";
     }
 }

@@ -25,6 +25,7 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <vector>
 
 #include "../../include/sr_select.h"
@@ -776,10 +777,66 @@ size_t sr_atom_gram_workspace_bytes(int L) {
     return (size_t)GRID * upper_blocks(column_blocks(L)) * 256 * sizeof(double);
 }
 
+namespace {
+
+// Scratch of the entry point that allocates nothing: the per-workgroup partial sums of up to
+// SR_SELECT_STATIC_MAX_ATOMS atoms (five column blocks: 512 workgroups x 15 blocks x 256 doubles,
+// 15 MiB).  Every GPU the library runs on holds its own copy until the process ends.  In host
+// code the array's name is only a stand-in for the symbol: its device address is asked for once
+// per device, with that device current, and everything below uses that address.
+constexpr size_t STATIC_SCRATCH_DOUBLES = (size_t)512 * 15 * 256;
+static __device__ __align__(256) double static_scratch[STATIC_SCRATCH_DOUBLES];
+
+std::mutex static_scratch_lock;
+double* static_scratch_addr[64];          // by device ordinal
+
+hipError_t static_scratch_of_current_device(double** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> hold(static_scratch_lock);
+    if (!static_scratch_addr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(static_scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        static_scratch_addr[dev] = (double*)p;
+    }
+    *out = static_scratch_addr[dev];
+    return hipSuccess;
+}
+
+int atom_gram(const sr_tensor* up, const sr_tensor* coeff, const sr_tensor* dict, const sr_tensor* target,
+              int L, int k, int channels, int stride, void* workspace, size_t workspace_bytes,
+              double* normal, void* stream);
+
+}  // namespace
+
 extern "C" __attribute__((visibility("default")))
 int sr_atom_gram(const sr_tensor* up, const sr_tensor* coeff, const sr_tensor* dict, const sr_tensor* target,
                  int L, int k, int channels, int stride, void* workspace, size_t workspace_bytes,
                  double* normal, void* stream) {
+    return atom_gram(up, coeff, dict, target, L, k, channels, stride, workspace, workspace_bytes, normal, stream);
+}
+
+extern "C" __attribute__((visibility("default")))
+int sr_atom_gram_static(const sr_tensor* up, const sr_tensor* coeff, const sr_tensor* dict, const sr_tensor* target,
+                        int L, int k, int channels, int stride, double* normal, void* stream) {
+    if (L < 1 || L > SR_SELECT_MAX_ATOMS) return SR_ERR_UNSUPPORTED;
+    if (L > SR_SELECT_STATIC_MAX_ATOMS || sr_atom_gram_workspace_bytes(L) > STATIC_SCRATCH_DOUBLES * sizeof(double))
+        return SR_ERR_SCRATCH;
+    double* scratch = nullptr;
+    if (static_scratch_of_current_device(&scratch) != hipSuccess) return SR_ERR_LAUNCH;
+    return atom_gram(up, coeff, dict, target, L, k, channels, stride, scratch, STATIC_SCRATCH_DOUBLES * sizeof(double),
+                     normal, stream);
+}
+
+namespace {
+
+int atom_gram(const sr_tensor* up, const sr_tensor* coeff, const sr_tensor* dict, const sr_tensor* target,
+              int L, int k, int channels, int stride, void* workspace, size_t workspace_bytes,
+              double* normal, void* stream) {
     if (!up || !coeff || !dict || !target || !normal) return SR_ERR_NULL;
     if (up->dtype != SR_F32 || target->dtype != SR_F32 || dict->dtype != SR_F32 ||
         (coeff->dtype != SR_F32 && coeff->dtype != SR_F16 && coeff->dtype != SR_F8E4M3 && coeff->dtype != SR_BF16))
@@ -856,6 +913,8 @@ int sr_atom_gram(const sr_tensor* up, const sr_tensor* coeff, const sr_tensor* d
                        (const double*)workspace, grid, a.ntile, a.n16, L, M, normal);
     return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_LAUNCH;
 }
+
+}  // namespace
 
 extern "C" __attribute__((visibility("default")))
 int sr_select_atoms(const double* normal, int L, double alpha, double delta_alpha, double lambda0, double eps,
