@@ -66,6 +66,8 @@ def _load():
         lib.orc_assemble_points.restype = c_int
         lib.orc_assemble_points.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_vp, c_int, c_int,
                                             c_vp, c_int, c_vp, c_int, c_vp, c_vp, c_int, c_vp]
+        lib.orc_pixel_shuffle.restype = c_int
+        lib.orc_pixel_shuffle.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_vp]
         lib.orc_threads.restype = c_int
         lib.orc_set_threads.restype = c_int
         lib.orc_set_threads.argtypes = [c_int]
@@ -182,6 +184,25 @@ def assemble_points(U, coeff, dictionary, pts, kept=None, gamma=None) -> np.ndar
     return out
 
 
-def dict_assemble(lr, coeff, dictionary, scale: int, kept=None, gamma=None, a: float = -0.5) -> np.ndarray:
-    """The whole path: stage 1, then stages 3 + 4.  float64 [N][C][s*h][s*w]."""
+def pixel_shuffle(coeff_lr, scale: int) -> np.ndarray:
+    """What the pixel-shuffle layer at the end of the coefficient network does to its input
+    ``coeff_lr`` [N][L*s*s][h][w]: the same stored elements as [N][L][s*h][s*w]."""
+    a = _stored(coeff_lr, "coeff_lr")
+    if a.ndim != 4 or a.shape[1] % (scale * scale):
+        raise ValueError("coeff_lr must be [N][L*s*s][h][w]")
+    n, c, h, w = a.shape
+    L = c // (scale * scale)
+    out = np.empty((n, L, h * scale, w * scale), dtype=a.dtype)
+    if _load().orc_pixel_shuffle(_ptr(a), a.dtype.itemsize, n, L, h, w, int(scale), _ptr(out)):
+        raise ValueError("orc_pixel_shuffle rejected its arguments")
+    return out
+
+
+def dict_assemble(lr, coeff, dictionary, scale: int, kept=None, gamma=None, a: float = -0.5,
+                  pre_shuffle: bool = False) -> np.ndarray:
+    """The whole path: stage 1, then stages 3 + 4.  float64 [N][C][s*h][s*w].  With
+    ``pre_shuffle`` the coefficients are what the network holds before its pixel-shuffle
+    layer, [N][L*s*s][h][w]: that layer is applied first."""
+    if pre_shuffle:
+        coeff = pixel_shuffle(coeff, scale)
     return assemble(bicubic(lr, scale, a), coeff, dictionary, kept, gamma)

@@ -40,7 +40,9 @@
  * preservation, an exact-rational apply-then-weight evaluator, a library
  * unfold + einsum for stages 3 + 4; the 8-bit E4M3 decoder by hand-computed
  * codes and a library decoder over all 256 codes (tests/test_oracle_fp8.py), the
- * bfloat16 decoder likewise over all 65536 codes (tests/test_oracle_bf16.py).
+ * bfloat16 decoder likewise over all 65536 codes (tests/test_oracle_bf16.py); the
+ * pixel-shuffle by a hand-written example, by a library routine and by the index
+ * identity it is defined by (tests/test_oracle_shuffle.py).
  * No function here is unpinned.
  */
 #include <math.h>
@@ -306,6 +308,36 @@ int orc_assemble_points(const double *U, int n, int c, int H, int W,
             out[(size_t)p * c + ch] =
                 apply_pixel(U + ((size_t)b * c + ch) * plane, H, W, Y, X, F, k);
     }
+    return 0;
+}
+
+/*
+ * Pixel-shuffle of a coefficient tensor (paper section II-B, stage 2: the coefficient network
+ * ends in a pixel-shuffle layer; what it holds before that layer is [n][L*s*s][h][w] at LR
+ * resolution).  Moves stored elements, of `esize` bytes each, without looking at them:
+ *
+ *     out[b][l][y*s + i][x*s + j] = in[b][l*s*s + i*s + j][y][x]      0 <= i, j < s
+ *
+ * so channel l*s*s + i*s + j of the LR-resolution tensor holds the coefficients of atom l at
+ * the HR pixels whose row is i and whose column is j modulo s.  `out` is [n][L][h*s][w*s].
+ */
+int orc_pixel_shuffle(const void *in, int esize, int n, int L, int h, int w, int s, void *out)
+{
+    if (!in || !out || esize < 1 || esize > 8 || n < 0 || L < 1 || h < 0 || w < 0 || s < 1)
+        return -1;
+    const unsigned char *src = (const unsigned char *)in;
+    unsigned char *dst = (unsigned char *)out;
+    size_t H = (size_t)h * s, W = (size_t)w * s;
+    for (int b = 0; b < n; ++b)
+        for (int l = 0; l < L; ++l)
+            for (int i = 0; i < s; ++i)
+                for (int j = 0; j < s; ++j)
+                    for (int y = 0; y < h; ++y)
+                        for (int x = 0; x < w; ++x) {
+                            size_t from = ((((size_t)b * L + l) * s + i) * s + j) * ((size_t)h * w) + (size_t)y * w + x;
+                            size_t to = ((size_t)b * L + l) * (H * W) + ((size_t)y * s + i) * W + ((size_t)x * s + j);
+                            memcpy(dst + to * esize, src + from * esize, (size_t)esize);
+                        }
     return 0;
 }
 
