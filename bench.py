@@ -254,6 +254,9 @@ def main():
                          "normal equations on the GPU over every STRIDE-th row and column, then the host search")
     ap.add_argument("--bicubic", action="store_true",
                     help="also time the bicubic-only entry point (stage 1 alone) on this frame")
+    ap.add_argument("--pre-shuffle", action="store_true",
+                    help="hand the coefficients over as the coefficient network holds them before its pixel-shuffle "
+                         "layer, [N][L*s*s][h][w] (section II-B, stage 2); same values, same result")
     ap.add_argument("--lib", default=None, metavar="PATH",
                     help="load this build of the library instead of the in-tree one (measurement builds "
                          "with a part of the kernel switched off, see sr_mfma_kernel.h)")
@@ -288,7 +291,12 @@ def main():
     for r in range(1, N_ROTATE):
         coeffs.append(sr_synth.make_coeff(sr_synth.scaled(wl, index=wl.index + 10 * r), dev))
     outs = [torch.empty((wl.n, wl.c, wl.H, wl.W), device=dev, dtype=inp["lr"].dtype) for _ in range(2)]
-    opts = sr.make_options(args.kernel, args.tile)
+    layout = sr.SR_COEFF_PRE_SHUFFLE if args.pre_shuffle else sr.SR_COEFF_PLANAR
+    if args.pre_shuffle:
+        for r in range(N_ROTATE):
+            coeffs[r] = sr_synth.to_pre_shuffle(coeffs[r], wl.scale)
+        inp["coeff"] = coeffs[0]
+    opts = sr.make_options(args.kernel, args.tile, layout)
     plan = sr.sr_dict_assemble_plan(inp["lr"], coeffs[0], inp["dict"], wl.L, wl.k, wl.scale, wl.c,
                                     outs[0], kept=kept, opts=opts)
     assert plan > 0, sr.sr_strerror(plan)
@@ -354,7 +362,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "hr": f"{wl.W}x{wl.H}", "scale": wl.scale, "channels": wl.c,
                    "L": wl.L, "k": wl.k, "atoms_read": n_read, "batch": wl.n,
-                   "kernel": {1: "generic", 2: "mfma"}[plan], "rotating_coeff_buffers": N_ROTATE},
+                   "kernel": {1: "generic", 2: "mfma"}[plan], "rotating_coeff_buffers": N_ROTATE,
+                   "coeff_layout": "pre_shuffle [N][L*s*s][h][w]" if args.pre_shuffle else "planar [N][L][H][W]"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(wl.name),
                      "traffic_source": (f"profiles/sr_mfma_{wl.name}_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an "
@@ -365,7 +374,7 @@ def main():
                      "algorithmic_bytes": alg_bytes},
         "pct_of_hbm_peak": round(100.0 * achieved / HBM_PEAK_GBS, 2),
     }
-    emp = empirical_ceilings(sr, torch, wl, coeffs, outs, avg_ms)
+    emp = None if args.pre_shuffle else empirical_ceilings(sr, torch, wl, coeffs, outs, avg_ms)
     if emp is not None:
         result["roofline"]["empirical"] = emp
     if args.kept_sweep:
@@ -400,7 +409,7 @@ def main():
         result["selection"] = selection_leg(sr, torch, wl, inp, args.selection)
     if args.bicubic:
         result["bicubic"] = bicubic_leg(sr, torch, wl, inp)
-    if not args.no_cpu:
+    if not args.no_cpu and not args.pre_shuffle:      # the oracle leg is timed on the planar layout only
         result["cpu_baseline"] = cpu_baseline(wl, inp["lr"], coeffs[0], inp["dict"], args.cpu_budget)
     print(json.dumps(result))
 

@@ -89,12 +89,22 @@ typedef enum {
                                   not qualify (see sr_dict_assemble_ex)            */
 } sr_kernel;
 
+/* How `coeff` is laid out (sr_options.coeff_layout). */
+typedef enum {
+    SR_COEFF_PLANAR      = 0,  /* [N][L][s*h][s*w]: one HR plane per atom          */
+    SR_COEFF_PRE_SHUFFLE = 1   /* [N][L*s*s][h][w]: what the coefficient network
+                                  holds BEFORE its pixel-shuffle layer (section
+                                  II-B, stage 2); channel l*s*s + i*s + j carries
+                                  atom l at HR pixels (y*s + i, x*s + j)           */
+} sr_coeff_layout;
+
 typedef struct {
     int kernel;                /* sr_kernel                                        */
     int tile;                  /* matrix-core kernel tile shape index, 0 = the
                                   library's default for the frame; see
                                   sr_dict_assemble_tile                            */
-    int reserved[6];           /* must be zero                                     */
+    int coeff_layout;          /* sr_coeff_layout                                  */
+    int reserved[5];           /* must be zero                                     */
 } sr_options;
 
 /*
@@ -150,6 +160,13 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
  *                     elements if the image is f16;
  *   images beyond 4 GB of coefficients (element offsets): at most 72 folded atoms.
  * Every other supported case runs on the generic kernel.
+ *
+ * opts->coeff_layout = SR_COEFF_PRE_SHUFFLE: `coeff` is the tensor the coefficient network
+ * produces before its final pixel-shuffle, [N][L*s*s][h][w] (so coeff->c = L*scale*scale and
+ * coeff->h, coeff->w are the LR sizes); the call gives exactly the result of shuffling it to
+ * [N][L][s*h][s*w] first, without that 2 x (L * H * W) byte pass over memory.  Every kernel
+ * takes it; the matrix-core kernel for k = 5, C = 3, f16 coefficients with up to 8 or 65 to 72
+ * folded atoms (byte offsets), the generic kernel otherwise.
  *
  * opts->tile (the launch-shape search of section III-B, Eq. 11-12, as a small set of compiled
  * tile shapes): index 0 is the library's default for the frame and is always accepted.  Other

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libsrdict.so")
 
 SR_F32, SR_F16, SR_F8E4M3, SR_BF16 = 0, 1, 2, 3
 SR_KERNEL_AUTO, SR_KERNEL_GENERIC, SR_KERNEL_MFMA = 0, 1, 2
+SR_COEFF_PLANAR, SR_COEFF_PRE_SHUFFLE = 0, 1
 SR_MAX_ATOMS = 256
 
 EXPORTS = ("sr_dict_assemble", "sr_dict_assemble_selective", "sr_dict_assemble_ex",
@@ -29,7 +30,8 @@ class sr_tensor(ctypes.Structure):
 
 
 class sr_options(ctypes.Structure):
-    _fields_ = [("kernel", ctypes.c_int), ("tile", ctypes.c_int), ("reserved", ctypes.c_int * 6)]
+    _fields_ = [("kernel", ctypes.c_int), ("tile", ctypes.c_int), ("coeff_layout", ctypes.c_int),
+                ("reserved", ctypes.c_int * 5)]
 
 
 class SrError(RuntimeError):
@@ -157,9 +159,9 @@ def sr_dict_assemble_selective(lr, coeff, dict, L, k, scale, channels, out, stre
     return out
 
 
-def make_options(kernel=SR_KERNEL_AUTO, tile=0) -> sr_options:
+def make_options(kernel=SR_KERNEL_AUTO, tile=0, coeff_layout=SR_COEFF_PLANAR) -> sr_options:
     o = sr_options()
-    o.kernel, o.tile = int(kernel), int(tile)
+    o.kernel, o.tile, o.coeff_layout = int(kernel), int(tile), int(coeff_layout)
     return o
 
 

@@ -52,17 +52,22 @@ void make_plan(Plan& p, const sr_tensor* lr, const sr_tensor* coeff, const sr_te
     if (L < 1 || L > SR_MAX_ATOMS || channels < 1 || channels > SR_MAX_CHANNELS) {
         p.status = SR_ERR_UNSUPPORTED; return;
     }
-    if (lr->c != channels || out->c != channels || coeff->c != L ||
+    if (opts && (opts->coeff_layout < SR_COEFF_PLANAR || opts->coeff_layout > SR_COEFF_PRE_SHUFFLE)) {
+        p.status = SR_ERR_UNSUPPORTED; return;
+    }
+    if (lr->c != channels || out->c != channels ||
         dict->n != 1 || dict->c != L || dict->h != k || dict->w != k ||
         coeff->n != lr->n || out->n != lr->n ||
-        (int64_t)lr->h * scale != coeff->h || (int64_t)lr->w * scale != coeff->w ||
-        out->h != coeff->h || out->w != coeff->w) { p.status = SR_ERR_SHAPE; return; }
+        (int64_t)lr->h * scale != out->h || (int64_t)lr->w * scale != out->w) { p.status = SR_ERR_SHAPE; return; }
+    const bool pre_shuffle = opts && opts->coeff_layout == SR_COEFF_PRE_SHUFFLE;
+    if (pre_shuffle ? (coeff->c != L * scale * scale || coeff->h != lr->h || coeff->w != lr->w)
+                    : (coeff->c != L || coeff->h != out->h || coeff->w != out->w)) { p.status = SR_ERR_SHAPE; return; }
     // limits of the launch grids: the generic kernel takes four rows per workgroup in grid.y (<= 65535)
-    if ((int64_t)lr->n > 65535 || (int64_t)coeff->h > 4 * 65535 || (int64_t)coeff->w > (1 << 20)) {
+    if ((int64_t)lr->n > 65535 || (int64_t)out->h > 4 * 65535 || (int64_t)out->w > (1 << 20)) {
         p.status = SR_ERR_UNSUPPORTED; return;
     }
     if (opts) {
-        for (int i = 0; i < 6; ++i)
+        for (int i = 0; i < 5; ++i)
             if (opts->reserved[i]) { p.status = SR_ERR_UNSUPPORTED; return; }
         if (opts->kernel < SR_KERNEL_AUTO || opts->kernel > SR_KERNEL_MFMA || opts->tile < 0) {
             p.status = SR_ERR_UNSUPPORTED; return;
@@ -95,7 +100,8 @@ void make_plan(Plan& p, const sr_tensor* lr, const sr_tensor* coeff, const sr_te
     }
     a.lr = lr->data; a.coeff = coeff->data; a.dict = (const float*)dict->data; a.out = out->data;
     a.N = lr->n; a.C = channels; a.h = lr->h; a.w = lr->w;
-    a.H = coeff->h; a.W = coeff->w; a.s = scale; a.L = L;
+    a.H = out->h; a.W = out->w; a.s = scale; a.L = L;
+    a.pre_shuffle = pre_shuffle ? 1 : 0;
 
     const int want = opts ? opts->kernel : SR_KERNEL_AUTO;
     const int tile = opts ? opts->tile : 0;

@@ -44,7 +44,12 @@ __global__ __launch_bounds__(GNT) void k_assemble_generic(const AssembleArgs a) 
 #pragma unroll
     for (int t = 0; t < KK; ++t) F[t] = 0.0f;
     if (valid) {
-        const TC* cbase = (const TC*)a.coeff + (size_t)n * a.L * plane + (size_t)Y * a.W + X;
+        // where this pixel's coefficient lies within an atom's H*W elements: row-major HR plane, or (before the
+        // network's pixel-shuffle) s*s LR planes, the one for this pixel's row and column modulo s
+        const size_t within = a.pre_shuffle
+            ? (size_t)((Y % a.s) * a.s + X % a.s) * ((size_t)a.h * a.w) + (size_t)(Y / a.s) * a.w + X / a.s
+            : (size_t)Y * a.W + X;
+        const TC* cbase = (const TC*)a.coeff + (size_t)n * a.L * plane + within;
         // eight atoms at a time: their coefficient loads are in flight together
         constexpr int NB = 8;
         for (int i0 = 0; i0 < a.n_fold; i0 += NB) {

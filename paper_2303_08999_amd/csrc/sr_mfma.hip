@@ -15,6 +15,7 @@ hipError_t launch_mfma_k5_f8(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_k7_f8(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_k5_big(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_bf16(const AssembleArgs& a, int k, int np8, hipStream_t st);
+hipError_t launch_mfma_k5_ps(const AssembleArgs& a, int np8, hipStream_t st);
 
 namespace {
 
@@ -102,6 +103,9 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
     if ((unsigned long long)a.C * a.H * a.W * 4ull >= (1ull << 32)) return false;          // 32-bit offsets within an image
     const int np8 = np8_for(k, a.C, a.n_fold, coeff_dtype);
     if (np8 == 0) return false;
+    // coefficients in the layout before the network's pixel-shuffle: one family built
+    if (a.pre_shuffle && !(k == 5 && a.C == 3 && coeff_dtype == SR_F16 && (np8 == 1 || np8 == 9) &&
+                           !beyond_4gb(a, coeff_dtype) && a.W % px == 0 && tile == 0)) return false;
     if (beyond_4gb(a, coeff_dtype) && np8_big(np8) == 0) return false;                     // element offsets: up to 72 atoms
     // Alternative tile shapes exist for one family only (5x5 atoms, three channels, 65 to 72 fp16
     // atoms, byte offsets); everywhere else only the default (index 0) is accepted, so that a
@@ -117,6 +121,7 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
 hipError_t launch_mfma(const AssembleArgs& a, int k, bool io_f16, int tile, hipStream_t st) {
     (void)io_f16;
     const int np8 = np8_for(k, a.C, a.n_fold, a.coeff_dtype);
+    if (a.pre_shuffle) return launch_mfma_k5_ps(a, np8, st);
     if (beyond_4gb(a, a.coeff_dtype))
         return np8_big(np8) ? launch_mfma_k5_big(a, np8_big(np8), st) : hipErrorInvalidValue;
     if (a.coeff_dtype == SR_BF16 && k != 3) return launch_mfma_bf16(a, k, np8, st);

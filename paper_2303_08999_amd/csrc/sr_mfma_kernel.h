@@ -188,11 +188,26 @@ __device__ __forceinline__ int tap_of_row(int i, int mb) {
 
 struct TilePos { int n, ty, tx; };
 
-template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT, int SMIN, bool BIG>
+// v = q * s + r, 0 <= r < s, for the scales the library takes (wave-uniform branch on s)
+__device__ __forceinline__ void divmod_scale(int v, int s, int& q, int& r) {
+    if (s == 4) { q = v >> 2; r = v & 3; }
+    else if (s == 2) { q = v >> 1; r = v & 1; }
+    else { q = v / 3; r = v - 3 * q; }
+}
+
+// PS: the coefficients are read in the layout the coefficient network holds before its
+// pixel-shuffle layer, [L*s*s][h][w]: the s*s sub-pixels of an LR pixel lie in s*s different LR
+// planes, so the PX consecutive HR pixels of a lane come from up to PX planes, one 16-bit load
+// each (consecutive lanes read consecutive elements, 64 bytes per plane and lane half), placed
+// in the halves of the registers an HR-planar load would have filled.  Everything after the
+// loads is unchanged, and so is the result, bit for bit.
+template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT, int SMIN, bool BIG, bool PS = false>
 __global__ __launch_bounds__(64 * NW, WPE)
 void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y, const int ntiles) {
     using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN>;
     constexpr bool F32 = F::F32, F8 = F::F8, BF = F::BF;
+    static_assert(!PS || (CT == CT_F16 && !BIG && PX == 4), "pre-shuffle layout: 16-bit coefficients, four pixels per lane");
+    constexpr int NPIX = PS ? PX : 1;              // pixel offsets a lane keeps per unit
     using Raw = typename RawT<PX * F::CB>::type;
     constexpr int NT = F::NT, P = F::P, NG = F::NG, UH = F::UH, UW = F::UW;
     constexpr int N16 = F::N16, N8 = F::N8, NMB = F::NMB;
@@ -385,11 +400,40 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     };
 
     // coefficient base of a tile for this lane: image base (scalar) + pixel offset
-    auto phi_base = [&](const TilePos tp, int unit, int jr, int jc, unsigned& pix_off) -> const char* {
+    auto phi_base = [&](const TilePos tp, int unit, int jr, int jc, unsigned (&pix_off)[NPIX]) -> const char* {
         const int y = tp.ty * F::TH + (unit * NW + wave) * WR + jr, x = tile_x0(tp.tx) + PX * jc;
         const int yc = y < a.H ? y : a.H - 1, xc = x < a.W ? x : a.W - PX;   // out-of-image lanes re-read
-        pix_off = ((unsigned)yc * (unsigned)a.W + (unsigned)xc) * OU;                // a valid address; never stored
+        if constexpr (PS) {
+            int ly, iy;
+            divmod_scale(yc, a.s, ly, iy);
+            const unsigned hw = (unsigned)a.h * (unsigned)a.w;
+#pragma unroll
+            for (int q = 0; q < PX; ++q) {
+                int lx, jx;
+                divmod_scale(xc + q, a.s, lx, jx);
+                pix_off[q] = ((unsigned)(iy * a.s + jx) * hw + (unsigned)ly * (unsigned)a.w + (unsigned)lx) * OU;
+            }
+        } else {
+            pix_off[0] = ((unsigned)yc * (unsigned)a.W + (unsigned)xc) * OU;         // a valid address; never stored
+        }
         return (const char*)a.coeff + (size_t)tp.n * a.L * ((size_t)a.H * a.W * F::CB);
+    };
+    // the PX coefficients of one plane (or plane group) that a lane owns
+    auto load_raw = [&](const char* cimg, const unsigned (&pix_off)[NPIX], unsigned plane_off) -> Raw {
+        if constexpr (PS) {
+            typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+            Raw r;
+#pragma unroll
+            for (int m = 0; m < PX / 2; ++m) {
+                h2 v;
+                v[0] = __builtin_nontemporal_load((const _Float16*)(cimg + (pix_off[2 * m] + plane_off)));
+                v[1] = __builtin_nontemporal_load((const _Float16*)(cimg + (pix_off[2 * m + 1] + plane_off)));
+                r[m] = __builtin_bit_cast(unsigned, v);
+            }
+            return r;
+        } else {
+            return __builtin_nontemporal_load((const Raw*)caddr(cimg, pix_off[0] + plane_off));
+        }
     };
 
     Raw raw[F::NLOAD];
@@ -401,27 +445,26 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     {
         const int lane = tid0 & 63, hf = lane >> 5, j = lane & 31;
         load_lr(cur, lane, lrv, lrpar);
-        unsigned pix_off;
+        unsigned pix_off[NPIX];
         const char* cimg = phi_base(cur, 0, j / F::WC, j % F::WC, pix_off);
         const unsigned* pt = ptab + hf * F::NLOAD;
 #pragma unroll
-        for (int i = 0; i < F::NLOAD; ++i)
-            raw[i] = __builtin_nontemporal_load((const Raw*)caddr(cimg, pix_off + pt[i]));
+        for (int i = 0; i < F::NLOAD; ++i) raw[i] = load_raw(cimg, pix_off, pt[i]);
     }
 
     // ---- stage 1 in three steps; a workgroup barrier separates each from the next.
     // (a) tap tables of a tile and its LR footprint, registers -> LDS
     // the first UW threads fill the column tables, UH of the last 64 the row tables
-    static_assert(UH <= 64 && UW <= NT - 64, "tile too large for the table set-up");
+    static_assert(UH <= 64, "tile too tall for the table set-up");
     auto stage1_setup = [&](const TilePos tp, int tid) {
         const int lane = tid & 63;
         const int Y0 = tp.ty * F::TH, X0 = tile_x0(tp.tx);
         const TileOrigin o = tile_origin(Y0, X0, F::R, UH, UW, a.H, a.W, a.s);
-        if (tid < UW) {
+        for (int xx = tid; xx < UW; xx += NT) {       // one pass unless the tile is wider than the workgroup
             int m;
-            const int f = src_floor(clampi(X0 - F::R + tid, 0, a.W - 1), a.s, m);
-            xw[tid] = wk[m];
-            xb[tid] = clampi(f - 1 - o.lx0, 0, MAXLRX - 4);
+            const int f = src_floor(clampi(X0 - F::R + xx, 0, a.W - 1), a.s, m);
+            xw[xx] = wk[m];
+            xb[xx] = clampi(f - 1 - o.lx0, 0, MAXLRX - 4);
         }
         if (tid >= NT - 64 && tid - (NT - 64) < UH) {
             const int i = tid - (NT - 64);
@@ -551,7 +594,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         for (int unit = 0; unit < NU; ++unit) {
         const bool last_unit = unit == NU - 1;
         const bool more = last_unit ? more_tiles : true;
-        unsigned pix_next;
+        unsigned pix_next[NPIX];
         const char* cnext = last_unit ? phi_base(nxt, 0, jr, jc, pix_next) : phi_base(cur, unit + 1, jr, jc, pix_next);
 
         // (3) stage 3 on the matrix cores: atom steps outer, pixel slots inner
@@ -578,7 +621,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                             av[mb], __uint_as_float(raw_word(raw[st], q)), acc[q][mb], 0, 0, 0);
                 if ((st & 3) == 3) __builtin_amdgcn_sched_barrier(0);
                 if (more)
-                    raw[st] = __builtin_nontemporal_load((const Raw*)caddr(cnext, pix_next + pt[st]));
+                    raw[st] = load_raw(cnext, pix_next, pt[st]);
                 if ((st & 3) == 3) __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -607,7 +650,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             if (more) {
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
-                    raw[8 * c16 + i] = __builtin_nontemporal_load((const Raw*)caddr(cnext, pix_next + pt[8 * c16 + i]));
+                    raw[8 * c16 + i] = load_raw(cnext, pix_next, pt[8 * c16 + i]);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -635,7 +678,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             if (more) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    raw[8 * N16 + i] = __builtin_nontemporal_load((const Raw*)caddr(cnext, pix_next + pt[8 * N16 + i]));
+                    raw[8 * N16 + i] = load_raw(cnext, pix_next, pt[8 * N16 + i]);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -735,10 +778,12 @@ inline int compute_units() {
     return known[dev];
 }
 
-template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT = CT_F16, int SMIN = 2, bool BIG = false>
+template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT = CT_F16, int SMIN = 2, bool BIG = false,
+          bool PS = false>
 hipError_t launch_one(const AssembleArgs& a0, hipStream_t st) {
     using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN>;
     if (a0.s < SMIN) return hipErrorInvalidValue;       // its LDS footprint buffers would be too small
+    if ((a0.pre_shuffle != 0) != PS) return hipErrorInvalidValue;
     AssembleArgs a = a0;
     const int tiles_x = (a.W + F::TW - 1) / F::TW, tiles_y = (a.H + F::TH - 1) / F::TH;
     a.xlast = (tiles_x - 1) * F::TW;
@@ -752,7 +797,7 @@ hipError_t launch_one(const AssembleArgs& a0, hipStream_t st) {
     const int cus = compute_units();
     const int cap = cus * (4 * WPE / NW > 0 ? 4 * WPE / NW : 1);
     const int blocks = nt < cap ? (int)nt : cap;
-    hipLaunchKernelGGL((k_assemble_mfma<K, C, NP8, PX, WR, NW, NU, WPE, CT, SMIN, BIG>), dim3(blocks), dim3(F::NT), 0, st,
+    hipLaunchKernelGGL((k_assemble_mfma<K, C, NP8, PX, WR, NW, NU, WPE, CT, SMIN, BIG, PS>), dim3(blocks), dim3(F::NT), 0, st,
                        a, tiles_x, tiles_y, (int)nt);
     return hipGetLastError();
 }

@@ -93,6 +93,15 @@ WORKLOADS = {
 }
 
 
+def to_pre_shuffle(coeff, scale: int):
+    """The same stored coefficients in the layout they have before the coefficient network's
+    pixel-shuffle layer: [N][L][s*h][s*w] -> [N][L*s*s][h][w] (a move of elements, the inverse of
+    that layer; 8-bit floats are moved as bytes)."""
+    raw = coeff.view(torch.uint8) if coeff.dtype == torch.float8_e4m3fn else coeff
+    pre = torch.nn.functional.pixel_unshuffle(raw, scale).contiguous()
+    return pre.view(coeff.dtype) if raw is not coeff else pre
+
+
 def scaled(wl: Workload, **kw) -> Workload:
     """A copy of ``wl`` with some fields replaced (for small test cases)."""
     return dataclasses.replace(wl, **kw)

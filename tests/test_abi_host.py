@@ -173,6 +173,35 @@ def test_tile_indices_name_distinct_instantiations_or_are_refused(lib):
     assert sr.load().sr_dict_assemble_tile(lr, coeff, d, 72, 5, 4, 3, out, None, 0, None, None, None) == -1
 
 
+def test_pre_shuffle_layout_is_checked_on_the_host(lib):
+    """coeff as the network holds it before its pixel-shuffle layer: [N][L*s*s][h][w]."""
+    PS = sr.SR_COEFF_PRE_SHUFFLE
+
+    def ps_case(L=72, k=5, s=4, C=3, h=8, w=16, cd=sr.SR_F16):
+        lr, coeff, d, out = case(L=L, k=k, s=s, C=C, h=h, w=w, cd=cd)
+        coeff.c, coeff.h, coeff.w = L * s * s, h, w
+        return lr, coeff, d, out
+    o = lambda kernel=sr.SR_KERNEL_AUTO, tile=0: sr.make_options(kernel, tile, PS)
+    assert plan(*ps_case(), opts=o()) == sr.SR_KERNEL_MFMA
+    assert plan(*ps_case(), opts=o(sr.SR_KERNEL_GENERIC)) == sr.SR_KERNEL_GENERIC
+    assert plan(*ps_case(), kept=[3, 9, 70], opts=o()) == sr.SR_KERNEL_MFMA
+    assert plan(*ps_case(), kept=list(range(30)), opts=o()) == sr.SR_KERNEL_GENERIC      # capacities built: 8 and 72
+    assert plan(*ps_case(), kept=list(range(30)), opts=o(sr.SR_KERNEL_MFMA)) == -3
+    assert plan(*ps_case(s=3), s=3, opts=o()) == sr.SR_KERNEL_MFMA
+    assert plan(*ps_case(w=15, s=3), s=3, opts=o()) == sr.SR_KERNEL_GENERIC              # HR width 45: not whole groups
+    for kw, pk in (({"cd": sr.SR_F32}, {}), ({"cd": sr.SR_F8E4M3}, {}), ({"cd": sr.SR_BF16}, {}), ({"k": 7}, {"k": 7}),
+                   ({"C": 1}, {"C": 1}), ({"L": 100}, {"L": 100})):
+        assert plan(*ps_case(**kw), **pk, opts=o()) == sr.SR_KERNEL_GENERIC, kw
+    assert plan(*ps_case(), opts=o(sr.SR_KERNEL_MFMA, 3)) == -3                          # no alternative tiles in this layout
+    # the planar shape under the pre-shuffle flag, and the other way round, are shape errors
+    assert plan(*case(), opts=o()) == -2
+    assert plan(*ps_case()) == -2
+    bad = ps_case()
+    bad[1].c = 72 * 16 - 1
+    assert plan(*bad, opts=o()) == -2
+    assert plan(*ps_case(), opts=sr.make_options(0, 0, 2)) == -3                          # unknown layout code
+
+
 def test_tall_frames_stop_where_the_launch_grids_do(lib):
     def tall(h):
         ts = case(h=h, w=1, C=1)

@@ -1,0 +1,93 @@
+"""Coefficients in the layout they have BEFORE the coefficient network's pixel-shuffle layer
+(section II-B, stage 2), [N][L*s*s][h][w]: the HIP path reads that layout directly and must give
+what the oracle gives when it applies the pixel-shuffle first - and, since only the loads differ,
+exactly what the HIP path gives for the shuffled tensor."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2303_08999_amd as sr
+import sr_synth
+from test_gpu_parity import DEV, GENERIC, MFMA, assert_parity, host
+
+pytestmark = pytest.mark.gpu
+
+
+def run(inp, wl, coeff, kernel, layout, kept=None, gamma=None):
+    out = torch.full((wl.n, wl.c, wl.H, wl.W), float("nan"), device=DEV, dtype=inp["lr"].dtype)
+    opts = sr.make_options(kernel, 0, layout)
+    if sr.sr_dict_assemble_plan(inp["lr"], coeff, inp["dict"], wl.L, wl.k, wl.scale, wl.c, out, kept=kept, opts=opts) != kernel:
+        return None
+    sr.sr_dict_assemble_ex(inp["lr"], coeff, inp["dict"], wl.L, wl.k, wl.scale, wl.c, out, kept=kept, gamma=gamma, opts=opts)
+    torch.cuda.synchronize()
+    return out
+
+
+CASES = [
+    # (N, C, h, w, scale, L, k, coeff dtype, image dtype, kept atoms or None)
+    (1, 3, 37, 64, 4, 72, 5, "f16", "f32", None),       # the matrix-core family: several tiles, ragged rows
+    (2, 3, 50, 96, 4, 72, 5, "f16", "f32", None),       # two images, 384 wide: three tile columns
+    (1, 3, 41, 66, 2, 72, 5, "f16", "f32", None),       # scale 2: a lane's four pixels span two LR columns
+    (1, 3, 29, 44, 3, 72, 5, "f16", "f32", None),       # scale 3: the sub-pixel of a lane's first pixel varies
+    (1, 3, 40, 64, 4, 72, 5, "f16", "f32", 8),          # a kept list of 8: the small capacity
+    (1, 3, 33, 48, 3, 72, 5, "f16", "f16", 66),         # fp16 image, 66 kept atoms with gamma
+    (1, 3, 20, 33, 4, 72, 5, "f16", "f32", None),       # HR width 132: not whole tiles
+    (1, 1, 19, 23, 4, 40, 5, "f32", "f32", None),       # everything else runs on the generic kernel
+    (2, 2, 16, 21, 3, 17, 7, "f8", "f16", 5),
+    (1, 3, 18, 20, 2, 30, 3, "bf16", "f32", None),
+    (1, 3, 15, 17, 3, 72, 5, "f16", "f32", None),       # HR width 51: not whole pixel groups
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "N%dC%dh%dw%ds%dL%dk%d%s%s-%s" % c)
+def test_pre_shuffle_layout_against_the_oracle_and_the_planar_call(oracle, case):
+    N, C, h, w, s, L, k, cd, io, nk = case
+    wl = sr_synth.Workload("ps", 50, N, C, h, w, s, L, k, cd, io, 0.0, 1.5)
+    inp = sr_synth.make_inputs(wl, DEV)
+    pre = sr_synth.to_pre_shuffle(inp["coeff"], s)
+    assert pre.shape == (N, L * s * s, h, w)
+    kept = gamma = None
+    if nk:
+        rng = np.random.default_rng(nk)
+        kept = np.sort(rng.choice(L, size=nk, replace=False)).astype(np.int32)
+        gamma = rng.uniform(0.5, 1.5, size=nk).astype(np.float32)
+    hi = host(inp)
+    ref = oracle.dict_assemble(hi["lr"], sr_synth.stored_numpy(pre), hi["dict"], s, kept=kept, gamma=gamma, pre_shuffle=True)
+    ran = 0
+    for kernel in (GENERIC, MFMA):
+        got = run(inp, wl, pre, kernel, sr.SR_COEFF_PRE_SHUFFLE, kept, gamma)
+        if got is None:
+            continue
+        ran += 1
+        assert not torch.isnan(got).any(), "some output pixel was never written"
+        assert_parity(got.float().cpu().numpy(), ref, cd, io == "f16", f"kernel {kernel}")
+        planar = run(inp, wl, inp["coeff"], kernel, sr.SR_COEFF_PLANAR, kept, gamma)
+        if planar is not None:
+            assert torch.equal(got, planar), f"kernel {kernel}: the two layouts must give the same bits"
+    assert ran >= 1
+    if cd == "f16" and C == 3 and k == 5 and (h * s) and (w * s) % 4 == 0 and (nk is None or nk <= 8 or nk >= 65):
+        assert run(inp, wl, pre, MFMA, sr.SR_COEFF_PRE_SHUFFLE, kept, gamma) is not None, "this case belongs to the matrix-core kernel"
+
+
+def test_4k_frame_in_the_pre_shuffle_layout(oracle):
+    """The headline frame handed over as the network's 1152-channel LR tensor: every output equals the
+    planar call's, and sampled pixels (corners and edges among them) are checked against the oracle,
+    which shuffles first."""
+    wl = sr_synth.WORKLOADS["4k_dense"]
+    inp = sr_synth.make_inputs(wl, DEV)
+    planar = run(inp, wl, inp["coeff"], sr.SR_KERNEL_AUTO if False else MFMA, sr.SR_COEFF_PLANAR)
+    pre = sr_synth.to_pre_shuffle(inp["coeff"], wl.scale)
+    host_pre = sr_synth.stored_numpy(pre)
+    del inp["coeff"]
+    got = run(inp, wl, pre, MFMA, sr.SR_COEFF_PRE_SHUFFLE)
+    assert got is not None and planar is not None
+    assert torch.equal(got, planar)
+    rng = np.random.default_rng(12)
+    pts = np.stack([np.zeros(3000, dtype=np.int64), rng.integers(0, wl.H, 3000), rng.integers(0, wl.W, 3000)], axis=1)
+    pts[:4] = [(0, 0, 0), (0, wl.H - 1, wl.W - 1), (0, 0, wl.W - 1), (0, wl.H - 1, 0)]
+    pts[4:504, 1] = wl.H - 1 - (pts[4:504, 1] % 13)
+    pts[504:1004, 2] = wl.W - 1 - (pts[504:1004, 2] % 5)
+    U = oracle.bicubic(inp["lr"].cpu().numpy(), wl.scale)
+    want = oracle.assemble_points(U, oracle.pixel_shuffle(host_pre, wl.scale), inp["dict"].cpu().numpy(), pts)
+    have = got.cpu().numpy()[0][:, pts[:, 1], pts[:, 2]].T
+    assert_parity(have, want, "f16", False, "sampled pixels")
