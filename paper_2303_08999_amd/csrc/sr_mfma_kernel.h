@@ -195,18 +195,32 @@ __device__ __forceinline__ void divmod_scale(int v, int s, int& q, int& r) {
     else { q = v / 3; r = v - 3 * q; }
 }
 
-// PS: the coefficients are read in the layout the coefficient network holds before its
-// pixel-shuffle layer, [L*s*s][h][w]: the s*s sub-pixels of an LR pixel lie in s*s different LR
-// planes, so the PX consecutive HR pixels of a lane come from up to PX planes, one 16-bit load
-// each (consecutive lanes read consecutive elements, 64 bytes per plane and lane half), placed
-// in the halves of the registers an HR-planar load would have filled.  Everything after the
-// loads is unchanged, and so is the result, bit for bit.
-template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT, int SMIN, bool BIG, bool PS = false>
+// PSM != 0: the coefficients are read in the layout the coefficient network holds before its
+// pixel-shuffle layer, [L*s*s][h][w]: the s*s sub-pixels of an LR pixel lie in s*s LR planes.
+//   PSM = 4 (scale 4) and PSM = 2 (scale 2): the fast forms.  Which HR pixel an MFMA column and
+//     pixel slot stand for is free, as long as stage 4 and the store know it.  A lane still loads
+//     8 bytes per plane, but from ONE sub-pixel plane: four consecutive LR pixels, i.e. four HR
+//     pixels s apart, which become its four slots.  With n = lane % 32:
+//       scale 4: j = n % 4 (sub-pixel column), m = n / 4;  slot q is HR pixel X0 + 16 m + 4 q + j
+//       scale 2: j = n % 2,                    m = n / 2;  slot q is HR pixel X0 +  8 m + 2 q + j
+//     so the loads are as many, as wide and as coalesced as in the HR-planar form.  Stage 4 reads
+//     the tile at those pixels (per-lane LDS bases, still free of bank conflicts), and before the
+//     store the lanes of a quad exchange results so that each one holds two adjacent pixels again
+//     and a wavefront still writes 512 contiguous bytes per channel.
+//   PSM = 1 (any scale): the PX consecutive HR pixels of a lane come from up to PX planes, one
+//     16-bit load each, placed in the halves of the registers an HR-planar load would have
+//     filled; everything after the loads is unchanged.  Four times the load instructions and a
+//     register per element in flight: 2.6 x the time of the planar form at 4K.
+// The result is the planar form's, bit for bit, in every case.
+template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT, int SMIN, bool BIG, int PSM = 0>
 __global__ __launch_bounds__(64 * NW, WPE)
 void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y, const int ntiles) {
     using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN>;
     constexpr bool F32 = F::F32, F8 = F::F8, BF = F::BF;
-    static_assert(!PS || (CT == CT_F16 && !BIG && PX == 4), "pre-shuffle layout: 16-bit coefficients, four pixels per lane");
+    constexpr bool PS = PSM == 1;                  // one 16-bit load per pixel
+    constexpr bool PERM = PSM == 2 || PSM == 4;    // permuted pixel slots
+    static_assert(PSM == 0 || (CT == CT_F16 && !BIG && PX == 4), "pre-shuffle layout: 16-bit coefficients, four pixels per lane");
+    static_assert(!PERM || (WR == 1 && SMIN >= PSM), "permuted slots: one row per wavefront and unit");
     constexpr int NPIX = PS ? PX : 1;              // pixel offsets a lane keeps per unit
     using Raw = typename RawT<PX * F::CB>::type;
     constexpr int NT = F::NT, P = F::P, NG = F::NG, UH = F::UH, UW = F::UW;
@@ -403,7 +417,15 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     auto phi_base = [&](const TilePos tp, int unit, int jr, int jc, unsigned (&pix_off)[NPIX]) -> const char* {
         const int y = tp.ty * F::TH + (unit * NW + wave) * WR + jr, x = tile_x0(tp.tx) + PX * jc;
         const int yc = y < a.H ? y : a.H - 1, xc = x < a.W ? x : a.W - PX;   // out-of-image lanes re-read
-        if constexpr (PS) {
+        if constexpr (PERM) {
+            // jc is the lane's column n: sub-pixel plane j = n % PSM, LR columns 4 m .. 4 m + 3, m = n / PSM
+            const int jx = jc % PSM, m = jc / PSM;
+            const int ly = yc / PSM, iy = yc % PSM;
+            int lx = tile_x0(tp.tx) / PSM + 4 * m;
+            lx = lx + 4 <= a.w ? lx : a.w - 4;                                     // lanes past the image re-read
+            pix_off[0] = ((unsigned)(iy * PSM + jx) * ((unsigned)a.h * (unsigned)a.w) +
+                          (unsigned)ly * (unsigned)a.w + (unsigned)lx) * OU;
+        } else if constexpr (PS) {
             int ly, iy;
             divmod_scale(yc, a.s, ly, iy);
             const unsigned hw = (unsigned)a.h * (unsigned)a.w;
@@ -685,7 +707,22 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 
         // (4) stage 4: each half filters its taps against the LDS tile, channel by
         //     channel (a lane's PX slots share most of their patch values)
-        const float* ub = U + ((unit * NW + wave) * WR + jr + hf * F::RH0) * P + jc;
+        const float* ub = U + ((unit * NW + wave) * WR + jr + hf * F::RH0) * P + (PERM ? 0 : jc);
+        // Permuted slots: tile column of slot q, tap dx is e + (16 or 8) m with e = PSM q + dx + j; the
+        // swizzled index of a column x is (x % 4) NG + x / 4.  The lane's j enters through a few per-lane
+        // bases, picked by compile-time e0 = PSM q + dx, so that every read is base + immediate offset.
+        const float* ubp[4];
+        if constexpr (PERM) {
+            const int jx = jc % PSM, m = jc / PSM;
+            if constexpr (PSM == 4) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) ubp[r] = ub + ((r + jx) & 3) * NG + ((r + jx) >> 2) + 4 * m;   // r = e0 % 4
+            } else {
+                ubp[0] = ub + jx * NG + 2 * m;                 // (e0 % 4) + j stays below 4: class e0 % 4 + j
+                ubp[1] = ub + (jx ? 1 : 3 * NG) + 2 * m;       // e0 % 4 == 3: class 3, or (j = 1) class 0 of the next group
+                ubp[2] = ubp[3] = ub;
+            }
+        }
         float outp[C][PX];
 #pragma unroll
         for (int c = 0; c < C; ++c) {
@@ -695,8 +732,17 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 #pragma unroll
                 for (int vv = 0; vv < F::NSLOT; ++vv) {
                     const int dyv = vv / K, dxv = vv % K;
-                    const int off = c * UH * P + dyv * P + ((q + dxv) % PX) * NG + (q + dxv) / PX;
-                    s = fmaf(acc[q][vv / 16][vv % 16], ub[off], s);
+                    if constexpr (PSM == 4) {
+                        // e0 = 4 q + dx: class (dx + j) % 4, group q + (dx % 4 + j) / 4 + dx / 4
+                        s = fmaf(acc[q][vv / 16][vv % 16], ubp[dxv & 3][c * UH * P + dyv * P + q + (dxv >> 2)], s);
+                    } else if constexpr (PSM == 2) {
+                        const int e0 = 2 * q + dxv;
+                        const int imm = c * UH * P + dyv * P + ((e0 & 3) == 3 ? 0 : (e0 & 3) * NG) + (e0 >> 2);
+                        s = fmaf(acc[q][vv / 16][vv % 16], ubp[(e0 & 3) == 3 ? 1 : 0][imm], s);
+                    } else {
+                        const int off = c * UH * P + dyv * P + ((q + dxv) % PX) * NG + (q + dxv) / PX;
+                        s = fmaf(acc[q][vv / 16][vv % 16], ub[off], s);
+                    }
                 }
                 outp[c][q] = s;
             }
@@ -706,10 +752,14 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         // (5) add the two halves' partial sums: one cross-half swap per slot pair
         //     leaves half 0 with pixels 0..PX/2-1 of the lane's group and half 1
         //     with the rest; one vector store per channel
-        const int y = Y0 + (unit * NW + wave) * WR + jr, x = X0 + PX * jc;
+        // (permuted slots: the lane's own pixels start at X0 + 4 PSM m; after the exchange below it stores
+        //  the two adjacent pixels that start at X0 + 4 PSM m + 2 PSM hf + 2 (n % PSM))
+        const int y = Y0 + (unit * NW + wave) * WR + jr;
+        const int x = PERM ? X0 + 4 * PSM * (jc / PSM) : X0 + PX * jc;
         const bool valid = y < a.H && x < a.W;
         const unsigned plane_px = (unsigned)a.H * (unsigned)a.W;
-        const unsigned o0 = (unsigned)y * (unsigned)a.W + x + hf * (PX / 2);       // within the image
+        const unsigned o0 = PERM ? (unsigned)y * (unsigned)a.W + x + hf * (2 * PSM) + 2 * (jc % (PSM == 4 ? 4 : 2))
+                                 : (unsigned)y * (unsigned)a.W + x + hf * (PX / 2);   // within the image
         char* const out_img = (char*)a.out + (size_t)cur.n * C * ((size_t)plane_px * (a.io_f16 ? 2 : 4));
 #pragma unroll
         for (int c = 0; c < C; ++c) {
@@ -719,6 +769,29 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(outp[c][q]),
                                                                  __float_as_uint(outp[c][q + PX / 2]), false, false);
                 tot[q] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+            }
+            if constexpr (PSM == 4) {
+                // The quad (j = 0..3) holds the 8 pixels 16 m + 8 hf + {4 t + j}, t = slot: lane j' takes the
+                // adjacent pair 2 j', 2 j' + 1, i.e. slot j' / 2 of lanes 2 (j' % 2) and 2 (j' % 2) + 1.
+                const unsigned t0 = __float_as_uint(tot[0]), t1 = __float_as_uint(tot[1]);
+                const unsigned a0 = __builtin_amdgcn_update_dpp(0u, t0, 0x88, 0xf, 0xf, false);   // quad_perm [0,2,0,2]
+                const unsigned a1 = __builtin_amdgcn_update_dpp(0u, t1, 0x88, 0xf, 0xf, false);
+                const unsigned b0 = __builtin_amdgcn_update_dpp(0u, t0, 0xDD, 0xf, 0xf, false);   // quad_perm [1,3,1,3]
+                const unsigned b1 = __builtin_amdgcn_update_dpp(0u, t1, 0xDD, 0xf, 0xf, false);
+                const bool hi_slot = (jc & 2) != 0;
+                tot[0] = __uint_as_float(hi_slot ? a1 : a0);
+                tot[1] = __uint_as_float(hi_slot ? b1 : b0);
+            } else if constexpr (PSM == 2) {
+                // The lane pair (j = 0, 1) holds the 4 pixels 8 m + 4 hf + {2 t + j}: lane j' takes 2 j', 2 j' + 1,
+                // i.e. slot j' of both lanes of the pair.
+                const unsigned t0 = __float_as_uint(tot[0]), t1 = __float_as_uint(tot[1]);
+                const unsigned a0 = __builtin_amdgcn_update_dpp(0u, t0, 0xA0, 0xf, 0xf, false);   // quad_perm [0,0,2,2]
+                const unsigned a1 = __builtin_amdgcn_update_dpp(0u, t1, 0xA0, 0xf, 0xf, false);
+                const unsigned b0 = __builtin_amdgcn_update_dpp(0u, t0, 0xF5, 0xf, 0xf, false);   // quad_perm [1,1,3,3]
+                const unsigned b1 = __builtin_amdgcn_update_dpp(0u, t1, 0xF5, 0xf, 0xf, false);
+                const bool hi_slot = (jc & 1) != 0;
+                tot[0] = __uint_as_float(hi_slot ? a1 : a0);
+                tot[1] = __uint_as_float(hi_slot ? b1 : b0);
             }
 #ifdef SR_ABLATE_STORES
             if (valid && a.N < 0) {                       // never true: the stores stay in the code, unexecuted
@@ -779,11 +852,13 @@ inline int compute_units() {
 }
 
 template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT = CT_F16, int SMIN = 2, bool BIG = false,
-          bool PS = false>
+          int PSM = 0>
 hipError_t launch_one(const AssembleArgs& a0, hipStream_t st) {
     using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN>;
     if (a0.s < SMIN) return hipErrorInvalidValue;       // its LDS footprint buffers would be too small
-    if ((a0.pre_shuffle != 0) != PS) return hipErrorInvalidValue;
+    if ((a0.pre_shuffle != 0) != (PSM != 0)) return hipErrorInvalidValue;
+    // permuted pixel slots: a lane owns four whole LR columns, the image must end on such a group
+    if ((PSM == 2 || PSM == 4) && (a0.s != PSM || a0.w % 4 != 0)) return hipErrorInvalidValue;
     AssembleArgs a = a0;
     const int tiles_x = (a.W + F::TW - 1) / F::TW, tiles_y = (a.H + F::TH - 1) / F::TH;
     a.xlast = (tiles_x - 1) * F::TW;
@@ -797,7 +872,7 @@ hipError_t launch_one(const AssembleArgs& a0, hipStream_t st) {
     const int cus = compute_units();
     const int cap = cus * (4 * WPE / NW > 0 ? 4 * WPE / NW : 1);
     const int blocks = nt < cap ? (int)nt : cap;
-    hipLaunchKernelGGL((k_assemble_mfma<K, C, NP8, PX, WR, NW, NU, WPE, CT, SMIN, BIG, PS>), dim3(blocks), dim3(F::NT), 0, st,
+    hipLaunchKernelGGL((k_assemble_mfma<K, C, NP8, PX, WR, NW, NU, WPE, CT, SMIN, BIG, PSM>), dim3(blocks), dim3(F::NT), 0, st,
                        a, tiles_x, tiles_y, (int)nt);
     return hipGetLastError();
 }
