@@ -126,6 +126,43 @@ def probe_study(sr, torch, hr_h=2160, hr_w=3840):
     return out
 
 
+def table1_sweep(sr, torch, sr_synth):
+    """The compression-ratio ablation (the paper's Fig. 7: time of dictionary query + filtering against the
+    share of atoms kept) at the input sizes and scales of its Table I, for fp32 coefficients (the paper's
+    precision) and fp16.  Random kept lists, gamma = 1; microseconds per launch (median of 20), three rotating
+    coefficient tensors where they fit."""
+    import numpy as np
+    rng = np.random.default_rng(7)
+    lists = {n: np.sort(rng.choice(72, size=n, replace=False)).astype(np.int32) for n in (72, 58, 43, 29, 14, 8)}
+    rows = []
+    for (h, w) in ((64, 64), (128, 128), (180, 320), (360, 640)):
+        for scale in (2, 3, 4):
+            for cd in ("f32", "f16"):
+                wl = sr_synth.Workload("table1", 40, 1, 3, h, w, scale, 72, 5, cd, "f32")
+                inp = sr_synth.make_inputs(wl, "cuda")
+                coeffs = [inp["coeff"]] + [sr_synth.make_coeff(sr_synth.scaled(wl, index=wl.index + 10 * r), "cuda")
+                                           for r in (1, 2)]
+                out = torch.empty((1, 3, wl.H, wl.W), device="cuda")
+                row = {"lr": f"{w}x{h}", "scale": scale, "coeff": cd, "us": {}}
+                for n_keep, klist in lists.items():
+                    def run(i):
+                        sr.sr_dict_assemble_ex(inp["lr"], coeffs[i % 3], inp["dict"], 72, 5, scale, 3, out, kept=klist)
+                    for i in range(3):
+                        run(i)
+                    torch.cuda.synchronize()
+                    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+                    for i, (a, b) in enumerate(ev):
+                        a.record(); run(i); b.record()
+                    torch.cuda.synchronize()
+                    ms = sorted(a.elapsed_time(b) for a, b in ev)
+                    row["us"][n_keep] = round(ms[10] * 1e3, 1)
+                row["speedup_at_8_of_72"] = round(row["us"][72] / row["us"][8], 2)
+                rows.append(row)
+                del inp, coeffs, out
+                torch.cuda.empty_cache()
+    return rows
+
+
 def selection_leg(sr, torch, wl, inp, stride):
     """Offline selection on the workload's own frame: the target is the dense result, so the
     search answers "which 10 % of the atoms, rescaled, reproduce the full dictionary best"."""
@@ -263,6 +300,9 @@ def main():
     ap.add_argument("--probe-study", action="store_true",
                     help="instead of the kernel, time the library's streaming probes on the 4K frame's byte mix "
                          "and print them as one JSON line")
+    ap.add_argument("--table1-sweep", action="store_true",
+                    help="instead of the kernel, time kept lists of 72 ... 8 atoms at the paper's Table I input sizes "
+                         "and scales (the analogue of its Fig. 7) and print them as one JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size kernel that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters when profiling)")
@@ -280,6 +320,9 @@ def main():
         from paper_2303_08999_amd import binding
         binding.LIB_PATH = os.path.abspath(args.lib)
     sr.load()
+    if args.table1_sweep:
+        print(json.dumps({"table1_kept_sweep": table1_sweep(sr, torch, sr_synth)}))
+        return
     if args.probe_study:
         print(json.dumps({"probe_study_us": probe_study(sr, torch)}))
         return
