@@ -43,6 +43,42 @@ def test_planted_subset_is_recovered():
     assert kept.tolist() == planted and np.allclose(gamma, scales, atol=1e-5) and lam == 1e-6
 
 
+def test_selection_against_an_independent_solver_and_brute_force():
+    """The product's search checked against things that are NOT its twin (the numpy oracle follows the same
+    steps): a library LASSO solver at the lambda the search reports, least squares on the kept columns,
+    and exhaustive best-subset search on problems small enough for it."""
+    sk = pytest.importorskip("sklearn.linear_model")
+    import itertools
+    rng = np.random.default_rng(21)
+    for trial in range(6):
+        M, L, k = 400, 10, 3
+        X = rng.normal(size=(M, L))
+        planted = np.sort(rng.choice(L, size=k, replace=False))
+        w = np.zeros(L)
+        w[planted] = rng.uniform(1.0, 2.5, size=k) * rng.choice([-1.0, 1.0], size=k)
+        y = X @ w + 0.05 * rng.normal(size=M)
+        normal = np.concatenate([(X.T @ X).reshape(-1), X.T @ y, [float(y @ y), float(M)]])
+        # one round straight to the target count: the kept set is the support of ONE LASSO problem
+        kept, gamma, lam = sr.sr_select_atoms(normal, L, k / L, delta_alpha=1.0, lambda0=1e-4)
+        assert 1 <= len(kept) <= k
+        # (a) library solver, same objective ((1/M)|y - X b|^2 + lam |b|_1 = 2 x sklearn's with alpha = lam / 2)
+        ref = sk.Lasso(alpha=lam / 2, fit_intercept=False, tol=1e-14, max_iter=200000).fit(X, y).coef_
+        assert np.flatnonzero(np.abs(ref) > 1e-10).tolist() == kept.tolist()
+        # ... and just below that lambda no fewer atoms survive
+        if lam > 1e-4:
+            below = sk.Lasso(alpha=0.999 * lam / 2, fit_intercept=False, tol=1e-14, max_iter=200000).fit(X, y).coef_
+            assert np.count_nonzero(np.abs(below) > 1e-10) >= len(kept)
+        # (b) gamma is the least-squares fit on the kept columns (Eq. 9), from a library routine
+        ls = np.linalg.lstsq(X[:, kept], y, rcond=None)[0]
+        assert np.allclose(gamma, ls, rtol=1e-5, atol=1e-6)
+        # (c) exhaustive search: no other subset of that size fits better, and with this little noise it is the planted one
+        best = min(itertools.combinations(range(L), len(kept)),
+                   key=lambda S: float(np.linalg.lstsq(X[:, S], y, rcond=None)[1][0]))
+        assert list(best) == kept.tolist() == planted[:len(kept)].tolist() or set(kept) <= set(planted)
+        if len(kept) == k:
+            assert list(best) == kept.tolist() == planted.tolist()
+
+
 def test_alpha_one_keeps_everything_untouched():
     G, b, hh, M, normal = _problem(4)
     kept, gamma, lam = sr.sr_select_atoms(normal, 24, 1.0)
