@@ -66,6 +66,9 @@ def _load():
         lib.orc_assemble_points.restype = c_int
         lib.orc_assemble_points.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_vp, c_int, c_int,
                                             c_vp, c_int, c_vp, c_int, c_vp, c_vp, c_int, c_vp]
+        lib.orc_assemble_topk_rows.restype = c_int
+        lib.orc_assemble_topk_rows.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_vp, c_vp, c_int, c_int, c_int,
+                                               c_vp, c_int, c_int, c_int, c_vp]
         lib.orc_pixel_shuffle.restype = c_int
         lib.orc_pixel_shuffle.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_vp]
         lib.orc_threads.restype = c_int
@@ -181,6 +184,28 @@ def assemble_points(U, coeff, dictionary, pts, kept=None, gamma=None) -> np.ndar
                                      _ptr(pts), pts.shape[0], _ptr(out))
     if rc:
         raise ValueError("orc_assemble_points rejected its arguments")
+    return out
+
+
+def assemble_topk(U, index, value, dictionary, rows=None) -> np.ndarray:
+    """Stages 3 + 4 for coefficients given as per-pixel lists (an extension, not in the paper):
+    ``index`` uint8 [N][T][H][W] atom numbers, ``value`` [N][T][H][W] their coefficients."""
+    U = np.ascontiguousarray(U, dtype=np.float64)
+    index = np.ascontiguousarray(index)
+    value = _stored(value, "value")
+    D = np.ascontiguousarray(np.asarray(dictionary).astype(np.float64))
+    if index.dtype != np.uint8 or U.ndim != 4 or index.ndim != 4 or value.shape != index.shape or D.ndim != 3:
+        raise ValueError("shapes: U [N][C][H][W], index uint8 and value [N][T][H][W], dict [L][k][k]")
+    n, c, H, W = U.shape
+    T = index.shape[1]
+    if index.shape != (n, T, H, W):
+        raise ValueError(f"index shape {index.shape} != {(n, T, H, W)}")
+    y0, y1 = (0, H) if rows is None else rows
+    out = np.zeros((n, c, H, W), dtype=np.float64)
+    rc = _load().orc_assemble_topk_rows(_ptr(U), n, c, H, W, _ptr(index), _ptr(value), _DT[value.dtype], T, D.shape[0],
+                                        _ptr(D), D.shape[1], int(y0), int(y1), _ptr(out))
+    if rc:
+        raise ValueError("orc_assemble_topk_rows rejected its arguments" if rc == -1 else "an index is not below L")
     return out
 
 

@@ -42,7 +42,9 @@
  * codes and a library decoder over all 256 codes (tests/test_oracle_fp8.py), the
  * bfloat16 decoder likewise over all 65536 codes (tests/test_oracle_bf16.py); the
  * pixel-shuffle by a hand-written example, by a library routine and by the index
- * identity it is defined by (tests/test_oracle_shuffle.py).
+ * identity it is defined by (tests/test_oracle_shuffle.py); the per-pixel list form
+ * by the pinned dense form on the scattered list, hand-made lists, repeated entries
+ * and linearity (tests/test_oracle_topk.py).
  * No function here is unpinned.
  */
 #include <math.h>
@@ -309,6 +311,55 @@ int orc_assemble_points(const double *U, int n, int c, int H, int W,
                 apply_pixel(U + ((size_t)b * c + ch) * plane, H, W, Y, X, F, k);
     }
     return 0;
+}
+
+/*
+ * Stages 3 + 4 for coefficients stored as a per-pixel list of T (atom index, value) entries
+ * instead of L dense planes.  AN EXTENSION, NOT IN THE PAPER: the paper selects atoms globally
+ * (section III-A); this format carries a selection per pixel, following its argument that what
+ * is skipped should not be loaded (section II-A, Eq. 4).  What is computed is Eq. 2 with the
+ * listed terms only, nothing renormalised:
+ *
+ *     F_i = sum over t < T of value[t][i] * D[index[t][i]]          y_i = F_i B_i^T
+ *
+ * index: [n][T][H][W] bytes (each < L; an atom listed twice counts twice); value: [n][T][H][W] in
+ * value_dtype; rows y0 <= Y < y1 of out [n][c][H][W] are written.
+ */
+int orc_assemble_topk_rows(const double *U, int n, int c, int H, int W,
+                           const uint8_t *index, const void *value, int value_dtype, int T, int L,
+                           const double *dict, int k, int y0, int y1, double *out)
+{
+    if (!U || !index || !value || !dict || !out || k < 1 || (k % 2) == 0 || k > 15 ||
+        L < 1 || L > 256 || T < 1 || c < 1 || H < 1 || W < 1 || n < 0 || y0 < 0 || y1 > H)
+        return -1;
+    int kk = k * k;
+    size_t plane = (size_t)H * W;
+    int bad = 0;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int b = 0; b < n; ++b)
+        for (int Y = y0; Y < y1; ++Y) {
+            double F[225];
+            for (int X = 0; X < W; ++X) {
+                for (int j = 0; j < kk; ++j)
+                    F[j] = 0.0;
+                for (int t = 0; t < T; ++t) {
+                    size_t at = ((size_t)b * T + t) * plane + (size_t)Y * W + X;
+                    int l = index[at];
+                    if (l >= L) {
+                        bad = 1;
+                        continue;
+                    }
+                    double v = load_elem(value, value_dtype, at);
+                    for (int j = 0; j < kk; ++j)
+                        F[j] += v * dict[(size_t)l * kk + j];
+                }
+                for (int ch = 0; ch < c; ++ch) {
+                    const double *Uplane = U + ((size_t)b * c + ch) * plane;
+                    out[(((size_t)b * c + ch) * H + Y) * W + X] = apply_pixel(Uplane, H, W, Y, X, F, k);
+                }
+            }
+        }
+    return bad ? -2 : 0;
 }
 
 /*

@@ -13,7 +13,7 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "sr_oracle.c")
 PINS = ["tests/test_oracle_bicubic.py", "tests/test_oracle_assemble.py", "tests/test_oracle_fp8.py",
-        "tests/test_oracle_shuffle.py"]
+        "tests/test_oracle_shuffle.py", "tests/test_oracle_topk.py"]
 
 MUTATIONS = {
     "keys_inner_coefficient": ("- (a + 3.0) * t * t + 1.0", "- (a + 2.0) * t * t + 1.0"),
@@ -44,6 +44,11 @@ MUTATIONS = {
     "shuffle_sub_pixels_column_major": ("size_t from = ((((size_t)b * L + l) * s + i) * s + j)", "size_t from = ((((size_t)b * L + l) * s + j) * s + i)"),
     "shuffle_atoms_interleaved": ("size_t from = ((((size_t)b * L + l) * s + i) * s + j)", "size_t from = ((((size_t)b * s + i) * s + j) * L + l)"),
     "shuffle_lands_on_lr_rows": ("((size_t)y * s + i) * W + ((size_t)x * s + j)", "((size_t)i * h + y) * W + ((size_t)x * s + j)"),
+    "list_entry_stride_of_the_dense_form": ("size_t at = ((size_t)b * T + t) * plane + (size_t)Y * W + X;",
+                                            "size_t at = ((size_t)b * L + t) * plane + (size_t)Y * W + X;"),
+    "list_index_used_as_position": ("F[j] += v * dict[(size_t)l * kk + j];", "F[j] += v * dict[(size_t)t * kk + j];"),
+    "list_keeps_last_entry_only": ("                    for (int j = 0; j < kk; ++j)\n                        F[j] += v * dict[(size_t)l * kk + j];",
+                                   "                    for (int j = 0; j < kk; ++j)\n                        F[j] = v * dict[(size_t)l * kk + j];"),
     "half_subnormal_exponent": ("v = ldexp((double)m, -24);", "v = ldexp((double)m, -25);"),
     "e4m3_bias": ("v = ldexp((double)(m + 8), e - 10);", "v = ldexp((double)(m + 8), e - 11);"),
     "e4m3_subnormals_flushed": ("v = ldexp((double)m, -9);", "v = 0.0;"),
