@@ -163,6 +163,36 @@ def table1_sweep(sr, torch, sr_synth):
     return rows
 
 
+def list_leg(sr, torch, sr_synth, wl, inp, coeffs, entries):
+    """The per-pixel list form (an extension beyond the paper): each pixel's `entries` largest coefficients
+    as (atom index, value) pairs, timed like the kernel on the same frame."""
+    lists = [sr_synth.to_list(c, entries) for c in coeffs]
+    out = torch.empty((wl.n, wl.c, wl.H, wl.W), device="cuda", dtype=inp["lr"].dtype)
+
+    def run(i):
+        idx, val = lists[i % len(lists)]
+        sr.sr_dict_assemble_list(inp["lr"], idx, val, inp["dict"], wl.L, wl.k, wl.scale, wl.c, entries, out)
+    for i in range(3):
+        run(i)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+    torch.cuda.synchronize()
+    for i, (a, b) in enumerate(ev):
+        a.record(); run(i); b.record()
+    torch.cuda.synchronize()
+    ms = sum(a.elapsed_time(b) for a, b in ev) / len(ev)
+    b_io = 2 if wl.lr_dtype == "f16" else 4
+    vb = lists[0][1].element_size()
+    nbytes = wl.hr_pixels * (entries * (1 + vb) + wl.c * b_io + wl.c * b_io / wl.scale ** 2)
+    flop = wl.hr_pixels * 2.0 * (entries * wl.k ** 2 + wl.c * wl.k ** 2)
+    return {"entries": entries, "kernel_ms_avg": round(ms, 4), "hr_mpixel_per_s": round(wl.hr_pixels / ms / 1e3, 1),
+            "algorithmic_bytes": nbytes,
+            "roofline": {"bound": "alu", "achieved": round(flop / ms / 1e9, 2), "peak": 157.3, "unit": "TFLOP/s",
+                         "frac": round(flop / ms / 1e9 / 157.3, 4),
+                         "note": "fp32 multiply-adds of the fold and the filtering against the fp32 vector peak; the kernel's "
+                                 "own bound is the LDS gather of one dictionary row per entry (entries * k*k * 4 bytes per "
+                                 "pixel), HBM is at " + str(round(nbytes / ms / 1e6 / 8000.0, 3)) + " of its peak"}}
+
+
 def selection_leg(sr, torch, wl, inp, stride):
     """Offline selection on the workload's own frame: the target is the dense result, so the
     search answers "which 10 % of the atoms, rescaled, reproduce the full dictionary best"."""
@@ -303,6 +333,9 @@ def main():
     ap.add_argument("--table1-sweep", action="store_true",
                     help="instead of the kernel, time kept lists of 72 ... 8 atoms at the paper's Table I input sizes "
                          "and scales (the analogue of its Fig. 7) and print them as one JSON line")
+    ap.add_argument("--list", type=int, default=0, metavar="ENTRIES", dest="list_entries",
+                    help="also time the per-pixel list form (an extension beyond the paper): each pixel's ENTRIES "
+                         "largest coefficients as (atom index, value) pairs")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size kernel that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters when profiling)")
@@ -450,6 +483,8 @@ def main():
         result["kept_sweep"] = sweep
     if args.selection > 0 and wl.coeff_dtype in ("f16", "f32") and inp["lr"].dtype == torch.float32 and wl.L <= 128:
         result["selection"] = selection_leg(sr, torch, wl, inp, args.selection)
+    if args.list_entries > 0 and not args.pre_shuffle:
+        result["list_form"] = list_leg(sr, torch, sr_synth, wl, inp, coeffs[:2], args.list_entries)
     if args.bicubic:
         result["bicubic"] = bicubic_leg(sr, torch, wl, inp)
     if not args.no_cpu and not args.pre_shuffle:      # the oracle leg is timed on the planar layout only

@@ -54,8 +54,9 @@ extern "C" {
  * format that halves the stream again; it is widened exactly before use.
  * SR_BF16: two bytes per value, the upper half of an IEEE binary32 (1 sign / 8 exponent /
  * 7 mantissa bits).  Accepted for the coefficient tensor only: what a network that runs in
- * bfloat16 produces, taken as it is (no conversion pass over the 1.2 GB of a 4K frame). */
-typedef enum { SR_F32 = 0, SR_F16 = 1, SR_F8E4M3 = 2, SR_BF16 = 3 } sr_dtype;
+ * bfloat16 produces, taken as it is (no conversion pass over the 1.2 GB of a 4K frame).
+ * SR_U8: unsigned bytes; the atom indices of sr_dict_assemble_list only. */
+typedef enum { SR_F32 = 0, SR_F16 = 1, SR_F8E4M3 = 2, SR_BF16 = 3, SR_U8 = 4 } sr_dtype;
 
 /* Contiguous NCHW tensor in device memory. */
 typedef struct {
@@ -192,6 +193,34 @@ int sr_dict_assemble_ex(const sr_tensor* lr, const sr_tensor* coeff, const sr_te
  */
 int sr_bicubic_upsample(const sr_tensor* lr, int scale, int channels,
                         sr_tensor* out, void* stream);
+
+/*
+ * Coefficients as per-pixel lists - AN EXTENSION, NOT IN THE PAPER.  The paper compresses the
+ * dictionary once for the whole model (section III-A); its bandwidth argument (section II-A, Eq. 4:
+ * what is skipped should not be loaded) also holds per pixel: a pixel's few dominant atoms carry
+ * almost all of its coefficient mass.  Here every HR pixel brings `entries` pairs (atom index,
+ * value), 3 bytes each with f16 values, instead of L dense coefficients:
+ *
+ *     F_i = sum over t < entries of value[t][i] * D[index[t][i]]           y_i = F_i B_i^T
+ *
+ *   index  [N][entries][s*h][s*w]  SR_U8        atom numbers, each below L and, within a pixel, all
+ *                                               different (else: unspecified values at that pixel,
+ *                                               never an access outside the dictionary)
+ *   value  [N][entries][s*h][s*w]  f32 or f16   their coefficients; nothing is renormalised
+ *   lr, dict, out, L, k, scale, channels, stream as for sr_dict_assemble; 1 <= entries <= SR_MAX_ATOMS.
+ * Same statuses and rules as sr_dict_assemble (all checks on the host, one launch, no allocation).
+ */
+int sr_dict_assemble_list(const sr_tensor* lr, const sr_tensor* index, const sr_tensor* value,
+                          const sr_tensor* dict, int L, int k, int scale, int channels, int entries,
+                          sr_tensor* out, void* stream);
+
+/* The same with an explicit kernel choice (sr_kernel).  The matrix-core kernel takes k = 5, C = 3,
+ * f16 values, L <= 128, entries <= 16, an HR width that is a multiple of 4 and, for a pixel, atoms
+ * that are all different (an atom listed twice, or an index >= L, gives unspecified values there;
+ * the gather kernel, SR_KERNEL_GENERIC, adds repeated atoms as the definition above says). */
+int sr_dict_assemble_list_ex(const sr_tensor* lr, const sr_tensor* index, const sr_tensor* value,
+                             const sr_tensor* dict, int L, int k, int scale, int channels, int entries,
+                             sr_tensor* out, void* stream, int kernel);
 
 /* Which kernel sr_dict_assemble_ex would run for these arguments
  * (SR_KERNEL_GENERIC or SR_KERNEL_MFMA), or a negative sr_status.  Launches

@@ -13,12 +13,12 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsrdict.so")
 
-SR_F32, SR_F16, SR_F8E4M3, SR_BF16 = 0, 1, 2, 3
+SR_F32, SR_F16, SR_F8E4M3, SR_BF16, SR_U8 = 0, 1, 2, 3, 4
 SR_KERNEL_AUTO, SR_KERNEL_GENERIC, SR_KERNEL_MFMA = 0, 1, 2
 SR_COEFF_PLANAR, SR_COEFF_PRE_SHUFFLE = 0, 1
 SR_MAX_ATOMS = 256
 
-EXPORTS = ("sr_dict_assemble", "sr_dict_assemble_selective", "sr_dict_assemble_ex",
+EXPORTS = ("sr_dict_assemble", "sr_dict_assemble_selective", "sr_dict_assemble_ex", "sr_dict_assemble_list", "sr_dict_assemble_list_ex",
            "sr_bicubic_upsample", "sr_dict_assemble_plan", "sr_dict_assemble_tile", "sr_strerror", "sr_version",
            "sr_probe_read", "sr_probe_mix", "sr_probe_stream", "sr_probe_pattern", "sr_probe_policy", "sr_probe_policy_bits",
            "sr_atom_gram_workspace_bytes", "sr_atom_gram", "sr_atom_gram_static", "sr_select_atoms")
@@ -59,6 +59,8 @@ def load():
     lib.sr_dict_assemble.argtypes = [T, T, T, i, i, i, i, T, vp]
     lib.sr_dict_assemble_selective.argtypes = [T, T, T, i, i, i, i, T, vp, ip, i, fp]
     lib.sr_dict_assemble_ex.argtypes = [T, T, T, i, i, i, i, T, vp, ip, i, fp, O]
+    lib.sr_dict_assemble_list.argtypes = [T, T, T, T, i, i, i, i, i, T, vp]
+    lib.sr_dict_assemble_list_ex.argtypes = [T, T, T, T, i, i, i, i, i, T, vp, i]
     lib.sr_dict_assemble_plan.argtypes = [T, T, T, i, i, i, i, T, ip, i, O]
     lib.sr_dict_assemble_tile.argtypes = [T, T, T, i, i, i, i, T, ip, i, O, ip, ip]
     lib.sr_bicubic_upsample.argtypes = [T, i, i, T, vp]
@@ -98,6 +100,8 @@ def describe(t) -> sr_tensor:
         code = SR_F8E4M3
     elif t.dtype == torch.bfloat16:
         code = SR_BF16
+    elif t.dtype == torch.uint8:
+        code = SR_U8
     else:
         raise TypeError(f"dtype {t.dtype} is not float32/float16/float8_e4m3fn/bfloat16")
     ptr = t.data_ptr() if t.numel() else 0
@@ -181,6 +185,20 @@ def sr_dict_assemble_plan(lr, coeff, dict, L, k, scale, channels, out, kept=None
     n = n if n_kept is None else int(n_kept)
     op = ctypes.byref(opts) if opts is not None else None
     return load().sr_dict_assemble_plan(a, b, c, L, k, scale, channels, o, ka, n, op)
+
+
+def sr_dict_assemble_list(lr, index, value, dict, L, k, scale, channels, entries, out, stream=None):
+    """Coefficients as per-pixel (atom index, value) lists, an extension beyond the paper (include/sr_dict.h)."""
+    _check(load().sr_dict_assemble_list(describe(lr), describe(index), describe(value), describe(_dict4(dict)),
+                                        L, k, scale, channels, entries, describe(out), _stream(stream)))
+    return out
+
+
+def sr_dict_assemble_list_ex(lr, index, value, dict, L, k, scale, channels, entries, out, stream=None,
+                             kernel=SR_KERNEL_AUTO):
+    _check(load().sr_dict_assemble_list_ex(describe(lr), describe(index), describe(value), describe(_dict4(dict)),
+                                           L, k, scale, channels, entries, describe(out), _stream(stream), int(kernel)))
+    return out
 
 
 def sr_dict_assemble_tile(lr, coeff, dict, L, k, scale, channels, out, kept=None, n_kept=None, opts=None):

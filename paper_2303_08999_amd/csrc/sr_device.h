@@ -28,6 +28,8 @@ struct AssembleArgs {
     int n_fold;           // atoms folded: L (dense) or n_kept
     int io_f16;           // lr and out are fp16 (else fp32)
     int coeff_dtype;      // sr_dtype of the stored coefficients
+    const unsigned char* index;   // list form only: atom numbers [N][T][H][W]; `coeff` then holds the values [N][T][H][W]
+    int T;                // list form only: entries per pixel
     int pre_shuffle;      // coefficients are [N][L*s*s][h][w] (before the network's pixel-shuffle), else [N][L][H][W]
     int   kept[SR_MAX_ATOMS];    // plane read for folded atom i (identity when dense)
     float gamma[SR_MAX_ATOMS];   // its scale (1 when dense)

@@ -70,7 +70,12 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 // how the coefficients are stored (template argument CT of the kernel)
-constexpr int CT_F16 = 0, CT_F32 = 1, CT_F8 = 2, CT_BF16 = 3;
+constexpr int CT_F16 = 0, CT_F32 = 1, CT_F8 = 2, CT_BF16 = 3, CT_LIST = 4;
+// CT_LIST: no dense planes; every pixel brings a list of (atom index, fp16 value) entries (an extension
+// beyond the paper, see sr_dict_assemble_list).  A wavefront scatters the entries of its 128 pixels that
+// fall into the current 16-atom step into a 4 KB LDS scratch [pixel][16 atoms] - which is exactly the
+// matrix cores' B operand, one 16-byte read per pixel slot - and the fold then runs as for fp16 planes.
+constexpr int LIST_MAX_ENTRIES = 16;
 
 // SMIN: smallest scale the instantiation may be launched with.  The LR footprint
 // of a tile shrinks with the scale, so an instantiation for scale 4 only needs half
@@ -78,7 +83,7 @@ constexpr int CT_F16 = 0, CT_F32 = 1, CT_F8 = 2, CT_BF16 = 3;
 // tile (fewer halo rows up-sampled per output row).
 template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int CT = CT_F16, int SMIN = 2>
 struct Cfg {
-    static constexpr bool F32 = CT == CT_F32, F8 = CT == CT_F8, BF = CT == CT_BF16;
+    static constexpr bool F32 = CT == CT_F32, F8 = CT == CT_F8, BF = CT == CT_BF16, LIST = CT == CT_LIST;
     static constexpr int KK = K * K, R = (K - 1) / 2;
     static constexpr int RH0 = (K + 1) / 2;            // filter rows owned by lane half 0
     static constexpr int NSLOT = RH0 * K;              // accumulator rows used per half
@@ -96,9 +101,9 @@ struct Cfg {
     static constexpr int MAXLRY = (UH - 1) / SMIN + 5, MAXLRX = (UW - 1) / SMIN + 5;
     // fp16 coefficients: 16-atom MFMA steps and an optional 8-atom step;
     // fp32 coefficients: 2-atom steps of v_mfma_f32_32x32x2_f32, one load each
-    static constexpr int N16 = F32 ? 0 : NP8 / 2, N8 = F32 ? 0 : NP8 % 2;
+    static constexpr int N16 = F32 ? 0 : (LIST ? (NP8 + 1) / 2 : NP8 / 2), N8 = (F32 || LIST) ? 0 : NP8 % 2;
     static constexpr int N2 = F32 ? 4 * NP8 : 0;
-    static constexpr int NLOAD = F32 ? N2 : 8 * N16 + 4 * N8;   // coefficient loads per lane and unit
+    static constexpr int NLOAD = F32 ? N2 : (LIST ? 1 : 8 * N16 + 4 * N8);   // coefficient loads per lane and unit
     static constexpr int CB = F32 ? 4 : (F8 ? 1 : 2);  // bytes per stored coefficient
     static constexpr int NXC = (MAXLRX + 63) / 64;     // 64-column chunks of the LR footprint
     static constexpr int NLRP = (C * MAXLRY + NW - 1) / NW;   // (channel,row) pairs per wavefront
@@ -216,7 +221,9 @@ template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT
 __global__ __launch_bounds__(64 * NW, WPE)
 void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y, const int ntiles) {
     using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN>;
-    constexpr bool F32 = F::F32, F8 = F::F8, BF = F::BF;
+    constexpr bool F32 = F::F32, F8 = F::F8, BF = F::BF, LIST = F::LIST;
+    constexpr int LH = LIST_MAX_ENTRIES / 2;       // list entries a lane half loads
+    static_assert(!LIST || (PX == 4 && WR == 1 && !BIG && PSM == 0 && NU % 2 == 0), "list form: four pixels per lane, one row per unit");
     constexpr bool PS = PSM == 1;                  // one 16-bit load per pixel
     constexpr bool PERM = PSM == 2 || PSM == 4;    // permuted pixel slots
     static_assert(PSM == 0 || (CT == CT_F16 && !BIG && PX == 4), "pre-shuffle layout: 16-bit coefficients, four pixels per lane");
@@ -237,6 +244,8 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     __shared__ u32x2 A8[(F32 ? 1 : NMB * 2) * 64];
     __shared__ float A32[(F32 ? F::N2 * NMB : 1) * 64];   // fp32 path: D[2*step + hf][tap of row]
     __shared__ unsigned ptab[2 * F::NLOAD];         // byte offset of the plane each lane half loads
+    __shared__ unsigned ltab[LIST ? 2 * LH : 1];    // list form: element offset of the entry plane each lane half loads
+    __shared__ u32x4 lscr[LIST ? NW * 256 : 1];     // list form: per wavefront, [128 pixels][16 atoms] fp16
 
     const int tid0 = threadIdx.x;
     const int groups = (gridDim.x & 7) == 0 ? 8 : 1;
@@ -267,7 +276,15 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         keys_weights(tid0, a.s, wt);
         wk[tid0] = make_float4(wt[0], wt[1], wt[2], wt[3]);
     }
-    for (int e = tid0; e < 2 * F::NLOAD; e += NT) {
+    if constexpr (LIST) {
+        // half h takes entries h * ceil(T / 2) ...; slots past the list are marked and later masked
+        const int per_half = (a.T + 1) / 2;
+        for (int e = tid0; e < 2 * LH; e += NT) {
+            const int h = e / LH, i = e - h * LH, t = h * per_half + i;
+            ltab[e] = (i < per_half && t < a.T) ? (unsigned)t * ((unsigned)a.H * (unsigned)a.W) : 0xffffffffu;   // in elements
+        }
+    }
+    for (int e = tid0; e < (LIST ? 0 : 2 * F::NLOAD); e += NT) {
         const int h = e / F::NLOAD, i = e - h * F::NLOAD;
         // load i of half h serves folded atom idx; padding atoms re-read the last plane
         const int idx = F32 ? 2 * i + h
@@ -458,6 +475,27 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         }
     };
 
+    // list form: the entries of a unit, two register sets (the next unit's are loaded while this one is folded)
+    u32x2 lval[2][LIST ? LH : 1];                   // four fp16 values (the lane's four pixels) per entry
+    unsigned lidx[2][LIST ? LH : 1];                // their four atom numbers, one byte each
+    auto load_list = [&](const TilePos tp, int unit, int jc, int hf, u32x2 (&val)[LIST ? LH : 1], unsigned (&idx)[LIST ? LH : 1]) {
+        const int y = tp.ty * F::TH + unit * NW + wave, x = tile_x0(tp.tx) + PX * jc;
+        const int yc = y < a.H ? y : a.H - 1, xc = x < a.W ? x : a.W - PX;
+        const unsigned pix = (unsigned)yc * (unsigned)a.W + (unsigned)xc;           // elements within a plane
+        const size_t img = (size_t)tp.n * a.T * ((size_t)a.H * a.W);
+        const unsigned char* ibase = a.index + img;
+        const char* vbase = (const char*)a.coeff + img * 2;
+        const unsigned* lt = ltab + hf * LH;
+#pragma unroll
+        for (int e = 0; e < LH; ++e) {
+            const unsigned off = lt[e];
+            const bool have = off != 0xffffffffu;
+            const unsigned at = (have ? off : 0u) + pix;                            // slots past the list re-read entry 0
+            const unsigned ix = __builtin_nontemporal_load((const unsigned*)(ibase + at));
+            val[e] = __builtin_nontemporal_load((const u32x2*)(vbase + (size_t)at * 2));
+            idx[e] = have ? ix : 0xffffffffu;                                        // atom 255: in no step of up to 128 atoms
+        }
+    };
     Raw raw[F::NLOAD];
     unsigned lrv[F::NLRP][F::NXC], lrpar = 0u;
 #pragma unroll
@@ -467,11 +505,15 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     {
         const int lane = tid0 & 63, hf = lane >> 5, j = lane & 31;
         load_lr(cur, lane, lrv, lrpar);
-        unsigned pix_off[NPIX];
-        const char* cimg = phi_base(cur, 0, j / F::WC, j % F::WC, pix_off);
-        const unsigned* pt = ptab + hf * F::NLOAD;
+        if constexpr (LIST) {
+            load_list(cur, 0, j, hf, lval[0], lidx[0]);
+        } else {
+            unsigned pix_off[NPIX];
+            const char* cimg = phi_base(cur, 0, j / F::WC, j % F::WC, pix_off);
+            const unsigned* pt = ptab + hf * F::NLOAD;
 #pragma unroll
-        for (int i = 0; i < F::NLOAD; ++i) raw[i] = load_raw(cimg, pix_off, pt[i]);
+            for (int i = 0; i < F::NLOAD; ++i) raw[i] = load_raw(cimg, pix_off, pt[i]);
+        }
     }
 
     // ---- stage 1 in three steps; a workgroup barrier separates each from the next.
@@ -617,7 +659,8 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         const bool last_unit = unit == NU - 1;
         const bool more = last_unit ? more_tiles : true;
         unsigned pix_next[NPIX];
-        const char* cnext = last_unit ? phi_base(nxt, 0, jr, jc, pix_next) : phi_base(cur, unit + 1, jr, jc, pix_next);
+        const char* cnext = nullptr;
+        if constexpr (!LIST) cnext = last_unit ? phi_base(nxt, 0, jr, jc, pix_next) : phi_base(cur, unit + 1, jr, jc, pix_next);
 
         // (3) stage 3 on the matrix cores: atom steps outer, pixel slots inner
         f32x16 acc[PX][NMB];
@@ -627,6 +670,45 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[q][mb][v] = 0.0f;
+        if constexpr (LIST) {
+            // the next unit's entries go into the other register set while this one is folded
+            if (more) {
+                if (last_unit) load_list(nxt, 0, jc, hf, lval[(unit + 1) & 1], lidx[(unit + 1) & 1]);
+                else load_list(cur, unit + 1, jc, hf, lval[(unit + 1) & 1], lidx[(unit + 1) & 1]);
+            }
+            const u32x2 (&val)[LH] = lval[unit & 1];
+            const unsigned (&idx)[LH] = lidx[unit & 1];
+            u32x4* const scr = lscr + wave * 256;
+            unsigned short* const scr16 = (unsigned short*)scr;
+#pragma unroll
+            for (int c16 = 0; c16 < N16; ++c16) {
+                u32x4 av[NMB][2];
+#pragma unroll
+                for (int mb = 0; mb < NMB; ++mb)
+#pragma unroll
+                    for (int hl = 0; hl < 2; ++hl) av[mb][hl] = A16[((c16 * NMB + mb) * 2 + hl) * 64 + lane];
+                const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) scr[lane + 64 * i] = zero;
+#pragma unroll
+                for (int e = 0; e < LH; ++e)
+#pragma unroll
+                    for (int q = 0; q < PX; ++q) {
+                        const unsigned atom = (idx[e] >> (8 * q)) & 0xffu;
+                        if ((atom >> 4) == (unsigned)c16)                 // lanes j and j + 32 hold different entries of the same pixels
+                            scr16[(PX * jc + q) * 16 + (atom & 15u)] = (unsigned short)(val[e][q >> 1] >> (16 * (q & 1)));
+                    }
+#pragma unroll
+                for (int q = 0; q < PX; ++q) {
+                    const u32x4 bw = scr[(PX * jc + q) * 2 + hf];         // atoms 8 hf .. 8 hf + 7 of the step, packed in pairs
+#pragma unroll
+                    for (int mb = 0; mb < NMB; ++mb)
+#pragma unroll
+                        for (int hl = 0; hl < 2; ++hl) acc[q][mb] = mfma_16<false>(av[mb][hl], bw, acc[q][mb]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
         if constexpr (F32) {
             // fp32 coefficients: the loaded words ARE the B operand (lane half hf holds
             // atom 2*step + hf of its pixels), no re-packing, exact fp32 products
@@ -648,7 +730,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             }
         }
 #pragma unroll
-        for (int c16 = 0; c16 < N16; ++c16) {
+        for (int c16 = 0; c16 < (LIST ? 0 : N16); ++c16) {
             u32x4 av[NMB][2];
 #pragma unroll
             for (int mb = 0; mb < NMB; ++mb)

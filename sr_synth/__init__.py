@@ -102,6 +102,17 @@ def to_pre_shuffle(coeff, scale: int):
     return pre.view(coeff.dtype) if raw is not coeff else pre
 
 
+def to_list(coeff, entries: int):
+    """The ``entries`` largest coefficients of every pixel as (atom index uint8, value) planes,
+    [N][entries][H][W] each, largest first (ties: whatever order the library sort gives; both sides
+    of a parity test read the same stored lists).  Values keep the dtype of ``coeff`` (8-bit and
+    bfloat16 coefficients are widened to fp16: the list format stores fp16 or fp32 values)."""
+    wide = coeff.float() if coeff.dtype in (torch.float16, torch.bfloat16, torch.float8_e4m3fn) else coeff
+    val, idx = torch.topk(wide, entries, dim=1)
+    vdt = torch.float32 if coeff.dtype == torch.float32 else torch.float16
+    return idx.to(torch.uint8).contiguous(), val.to(vdt).contiguous()
+
+
 def scaled(wl: Workload, **kw) -> Workload:
     """A copy of ``wl`` with some fields replaced (for small test cases)."""
     return dataclasses.replace(wl, **kw)

@@ -202,6 +202,47 @@ def test_pre_shuffle_layout_is_checked_on_the_host(lib):
     assert plan(*ps_case(), opts=sr.make_options(0, 0, 2)) == -3                          # unknown layout code
 
 
+def test_list_form_argument_checks(lib):
+    """sr_dict_assemble_list(lr, index, value, dict, L, k, scale, channels, entries, out, stream)"""
+    def lcase(L=72, k=5, s=4, C=3, h=8, w=16, T=8, vd=sr.SR_F16, io=sr.SR_F32, idt=sr.SR_U8):
+        base = 0x10000000
+        return (T_(base, io, 1, C, h, w), T_(base + 0x1000000, idt, 1, T, s * h, s * w),
+                T_(base + 0x2000000, vd, 1, T, s * h, s * w), T_(base + 0x8000000, sr.SR_F32, 1, L, k, k),
+                T_(base + 0x9000000, io, 1, C, s * h, s * w))
+    T_ = T
+    f = lib.sr_dict_assemble_list
+
+    def call(ts, L=72, k=5, s=4, C=3, T=8):
+        lr, idx, val, d, out = ts
+        return f(lr, idx, val, d, L, k, s, C, T, out, None)
+    assert call(lcase(idt=sr.SR_F16)) == -3                       # indices must be bytes
+    assert call(lcase(vd=sr.SR_BF16)) == -3                       # values: f32 or f16
+    assert call(lcase(k=4), k=4) == -3
+    assert call(lcase(), T=0) == -3 or call(lcase(), T=0) == -2
+    assert call(lcase(T=9)) == -2                                 # entries disagree with the tensors
+    assert call(lcase(L=257), L=257) == -3
+    ts = lcase()
+    ts[2].w = 60
+    assert call(ts) == -2
+    ts = lcase()
+    ts[4].data = ts[1].data                                       # the output on top of the index planes
+    assert call(ts) == -4
+    ts = lcase()
+    ts[2].data = 0x12000001
+    assert call(ts) == -7
+    assert f(None, *lcase()[1:4], 72, 5, 4, 3, 8, lcase()[4], None) == -1
+    ts = lcase()
+    for t in ts[:3] + ts[4:]:
+        t.n = 0
+    assert call(ts) == 0                                          # an empty batch: nothing to do
+    lr, idx, val, d, out = lcase()
+    assert lib.sr_dict_assemble_list_ex(lr, idx, val, d, 72, 5, 4, 3, 8, out, None, 3) == -3      # no such kernel
+    lr, idx, val, d, out = lcase(T=17)
+    assert lib.sr_dict_assemble_list_ex(lr, idx, val, d, 72, 5, 4, 3, 17, out, None, sr.SR_KERNEL_MFMA) == -3   # 16 entries at most there
+    lr, idx, val, d, out = lcase(vd=sr.SR_F32)
+    assert lib.sr_dict_assemble_list_ex(lr, idx, val, d, 72, 5, 4, 3, 8, out, None, sr.SR_KERNEL_MFMA) == -3    # f16 values only
+
+
 def test_tall_frames_stop_where_the_launch_grids_do(lib):
     def tall(h):
         ts = case(h=h, w=1, C=1)
