@@ -11,12 +11,12 @@ hipError_t launch_mfma_k5_ps(const AssembleArgs& a, int np8, hipStream_t st) {
     const bool perm = (a.s == 4 || a.s == 2) && a.w % 4 == 0;
     switch (np8) {
     case 1:
-        if (perm && a.s == 4) return launch_one<5, 3, 1, 4, 1, 4, 4, 2, CT_F16, 4, false, 4>(a, st);   // 128 x 16
+        if (perm && a.s == 4) return launch_one<5, 3, 1, 4, 1, 4, 4, 2, CT_F16, 4, false, 4>(a, st);   // 256 x 8
         if (perm) return launch_one<5, 3, 1, 4, 1, 4, 2, 2, CT_F16, 2, false, 2>(a, st);               // 128 x 8
         if (a.s == 4) return launch_one<5, 3, 1, 4, 2, 4, 4, 2, CT_F16, 4, false, 1>(a, st);           //  64 x 32
         return launch_one<5, 3, 1, 4, 2, 4, 2, 2, CT_F16, 2, false, 1>(a, st);                         //  64 x 16
     case 9:
-        if (perm && a.s == 4) return launch_one<5, 3, 9, 4, 1, 2, 6, 1, CT_F16, 4, false, 4>(a, st);   // 128 x 12
+        if (perm && a.s == 4) return launch_one<5, 3, 9, 4, 1, 4, 4, 2, CT_F16, 4, false, 4>(a, st);   // 256 x 8
         if (perm) return launch_one<5, 3, 9, 4, 1, 4, 4, 2, CT_F16, 2, false, 2>(a, st);               // 128 x 16
         // One 16-bit load per pixel and plane: every load occupies a register until its pair is packed, twice
         // the registers of the planar form for a unit in flight.  One wavefront per SIMD (371 registers), as

@@ -81,7 +81,7 @@ constexpr int LIST_MAX_ENTRIES = 16;
 // of a tile shrinks with the scale, so an instantiation for scale 4 only needs half
 // the LDS for the footprint and the vertical-pass buffer, and can afford a taller
 // tile (fewer halo rows up-sampled per output row).
-template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int CT = CT_F16, int SMIN = 2>
+template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int CT = CT_F16, int SMIN = 2, int NSUB = 1>
 struct Cfg {
     static constexpr bool F32 = CT == CT_F32, F8 = CT == CT_F8, BF = CT == CT_BF16, LIST = CT == CT_LIST;
     static constexpr int KK = K * K, R = (K - 1) / 2;
@@ -89,8 +89,9 @@ struct Cfg {
     static constexpr int NSLOT = RH0 * K;              // accumulator rows used per half
     static constexpr int NMB = (NSLOT + 15) / 16;      // 32-row MFMA blocks
     static constexpr int WC = 32 / WR;                 // lane columns per wavefront
-    static constexpr int TW = WC * PX;                 // tile of HR pixels per workgroup:
-    static constexpr int TH = WR * NW * NU;            // NU units of WR rows per wavefront
+    static constexpr int TW = WC * PX * NSUB;          // tile of HR pixels per workgroup: NU units per wavefront, each
+    static constexpr int TH = WR * NW * NU / NSUB;     // WR rows of WC * PX pixels; NSUB units share a row (see PSM = 4)
+    static_assert(NU % NSUB == 0, "whole rows per wavefront");
     static constexpr int NT = 64 * NW;
     static constexpr int UW = TW + K - 1;
     static constexpr int UH = TH + K;                  // + one dummy row for half 1
@@ -205,13 +206,19 @@ __device__ __forceinline__ void divmod_scale(int v, int s, int& q, int& r) {
 //   PSM = 4 (scale 4) and PSM = 2 (scale 2): the fast forms.  Which HR pixel an MFMA column and
 //     pixel slot stand for is free, as long as stage 4 and the store know it.  A lane still loads
 //     8 bytes per plane, but from ONE sub-pixel plane: four consecutive LR pixels, i.e. four HR
-//     pixels s apart, which become its four slots.  With n = lane % 32:
-//       scale 4: j = n % 4 (sub-pixel column), m = n / 4;  slot q is HR pixel X0 + 16 m + 4 q + j
-//       scale 2: j = n % 2,                    m = n / 2;  slot q is HR pixel X0 +  8 m + 2 q + j
-//     so the loads are as many, as wide and as coalesced as in the HR-planar form.  Stage 4 reads
-//     the tile at those pixels (per-lane LDS bases, still free of bank conflicts), and before the
-//     store the lanes of a quad exchange results so that each one holds two adjacent pixels again
-//     and a wavefront still writes 512 contiguous bytes per channel.
+//     pixels s apart, which become its four slots.  With n = lane % 32, j = n % 2, m = n / 2:
+//       scale 2: the lane reads sub-pixel column j;  slot q is HR pixel X0 + 8 m + 2 q + j.
+//         A unit is one row of 128 HR pixels = 64 LR pixels = one 128-byte line of each plane.
+//       scale 4: 128 HR pixels of a row would be half a line of each plane, and a half-line
+//         request occupies the L1 like a whole one (measured: the same bytes in 64-byte pieces
+//         take 2.2 x the time unless the same wavefront asks for the other half right away).  So the
+//         tile is 256 pixels wide and a row is TWO units, J = 0, 1: the lane reads sub-pixel column
+//         2 J + j;  slot q is HR pixel X0 + 16 m + 4 q + 2 J + j.  Every load instruction still
+//         covers whole lines (16 lanes x 8 bytes per plane).
+//     Loads are as many and as wide as in the HR-planar form.  Stage 4 reads the tile at those
+//     pixels (per-lane LDS bases), and before the store lanes j = 0, 1 exchange results so that
+//     each holds adjacent pixels again (scale 4: the results of unit J = 0 wait in registers for
+//     J = 1, then a lane stores four adjacent pixels and a wavefront 1 KB per channel).
 //   PSM = 1 (any scale): the PX consecutive HR pixels of a lane come from up to PX planes, one
 //     16-bit load each, placed in the halves of the registers an HR-planar load would have
 //     filled; everything after the loads is unchanged.  Four times the load instructions and a
@@ -220,7 +227,8 @@ __device__ __forceinline__ void divmod_scale(int v, int s, int& q, int& r) {
 template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT, int SMIN, bool BIG, int PSM = 0>
 __global__ __launch_bounds__(64 * NW, WPE)
 void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y, const int ntiles) {
-    using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN>;
+    constexpr int NSUB = PSM == 4 ? 2 : 1;         // units per tile row
+    using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN, NSUB>;
     constexpr bool F32 = F::F32, F8 = F::F8, BF = F::BF, LIST = F::LIST;
     constexpr int LH = LIST_MAX_ENTRIES / 2;       // list entries a lane half loads
     static_assert(!LIST || (PX == 4 && WR == 1 && !BIG && PSM == 0 && NU % 2 == 0), "list form: four pixels per lane, one row per unit");
@@ -228,6 +236,8 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     constexpr bool PERM = PSM == 2 || PSM == 4;    // permuted pixel slots
     static_assert(PSM == 0 || (CT == CT_F16 && !BIG && PX == 4), "pre-shuffle layout: 16-bit coefficients, four pixels per lane");
     static_assert(!PERM || (WR == 1 && SMIN >= PSM), "permuted slots: one row per wavefront and unit");
+    // row of the wavefront's unit within the tile, and which of the row's NSUB units it is
+    auto unit_row = [](int unit, int wave_) { return (unit / NSUB) * NW + wave_; };
     constexpr int NPIX = PS ? PX : 1;              // pixel offsets a lane keeps per unit
     using Raw = typename RawT<PX * F::CB>::type;
     constexpr int NT = F::NT, P = F::P, NG = F::NG, UH = F::UH, UW = F::UW;
@@ -432,11 +442,11 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 
     // coefficient base of a tile for this lane: image base (scalar) + pixel offset
     auto phi_base = [&](const TilePos tp, int unit, int jr, int jc, unsigned (&pix_off)[NPIX]) -> const char* {
-        const int y = tp.ty * F::TH + (unit * NW + wave) * WR + jr, x = tile_x0(tp.tx) + PX * jc;
+        const int y = tp.ty * F::TH + unit_row(unit, wave) * WR + jr, x = tile_x0(tp.tx) + PX * jc;
         const int yc = y < a.H ? y : a.H - 1, xc = x < a.W ? x : a.W - PX;   // out-of-image lanes re-read
         if constexpr (PERM) {
-            // jc is the lane's column n: sub-pixel plane j = n % PSM, LR columns 4 m .. 4 m + 3, m = n / PSM
-            const int jx = jc % PSM, m = jc / PSM;
+            // jc is the lane's column n: sub-pixel column (unit % NSUB) * 2 + n % 2, LR columns 4 m .. 4 m + 3, m = n / 2
+            const int jx = (unit % NSUB) * 2 + jc % 2, m = jc / 2;
             const int ly = yc / PSM, iy = yc % PSM;
             int lx = tile_x0(tp.tx) / PSM + 4 * m;
             lx = lx + 4 <= a.w ? lx : a.w - 4;                                     // lanes past the image re-read
@@ -479,7 +489,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     u32x2 lval[2][LIST ? LH : 1];                   // four fp16 values (the lane's four pixels) per entry
     unsigned lidx[2][LIST ? LH : 1];                // their four atom numbers, one byte each
     auto load_list = [&](const TilePos tp, int unit, int jc, int hf, u32x2 (&val)[LIST ? LH : 1], unsigned (&idx)[LIST ? LH : 1]) {
-        const int y = tp.ty * F::TH + unit * NW + wave, x = tile_x0(tp.tx) + PX * jc;
+        const int y = tp.ty * F::TH + unit_row(unit, wave), x = tile_x0(tp.tx) + PX * jc;
         const int yc = y < a.H ? y : a.H - 1, xc = x < a.W ? x : a.W - PX;
         const unsigned pix = (unsigned)yc * (unsigned)a.W + (unsigned)xc;           // elements within a plane
         const size_t img = (size_t)tp.n * a.T * ((size_t)a.H * a.W);
@@ -651,6 +661,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         stage1_horizontal(tid);
         __syncthreads();
         const unsigned* pt = ptab + hf * F::NLOAD;
+        float park[C][2];                              // scale-4 permuted slots: unit J = 0's results wait for J = 1
         // The wavefront's NU units of this tile, one after the other; while a unit
         // is folded, the coefficients of the next one (same tile, or unit 0 of the
         // next tile) are loaded into the registers that fall free.
@@ -789,44 +800,57 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 
         // (4) stage 4: each half filters its taps against the LDS tile, channel by
         //     channel (a lane's PX slots share most of their patch values)
-        const float* ub = U + ((unit * NW + wave) * WR + jr + hf * F::RH0) * P + (PERM ? 0 : jc);
-        // Permuted slots: tile column of slot q, tap dx is e + (16 or 8) m with e = PSM q + dx + j; the
-        // swizzled index of a column x is (x % 4) NG + x / 4.  The lane's j enters through a few per-lane
-        // bases, picked by compile-time e0 = PSM q + dx, so that every read is base + immediate offset.
-        const float* ubp[4];
+        const float* ub = U + (unit_row(unit, wave) * WR + jr + hf * F::RH0) * P + (PERM ? 0 : jc);
+        // Permuted slots: slot q, tap dx reads tile column G m + s q + e, e = e0 + j, with G = 8 or 16 and the
+        // compile-time e0 = 2 q + dx (scale 2) or 2 J + dx (scale 4).  The swizzled index of a column x is
+        // (x % 4) NG + x / 4.  The lane's j enters through two per-lane bases, so that every read is base +
+        // immediate offset: e0 % 4 < 3: class e0 % 4 + j of the same group; e0 % 4 == 3: class 3, or (j = 1)
+        // class 0 of the next group.
+        unsigned ubo[2] = {0u, 0u};                    // as element offsets into U
         if constexpr (PERM) {
-            const int jx = jc % PSM, m = jc / PSM;
-            if constexpr (PSM == 4) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) ubp[r] = ub + ((r + jx) & 3) * NG + ((r + jx) >> 2) + 4 * m;   // r = e0 % 4
-            } else {
-                ubp[0] = ub + jx * NG + 2 * m;                 // (e0 % 4) + j stays below 4: class e0 % 4 + j
-                ubp[1] = ub + (jx ? 1 : 3 * NG) + 2 * m;       // e0 % 4 == 3: class 3, or (j = 1) class 0 of the next group
-                ubp[2] = ubp[3] = ub;
-            }
+            const int jx = jc % 2, m = jc / 2;
+            const int row0 = (unit_row(unit, wave) * WR + jr + hf * F::RH0) * P;
+            ubo[0] = (unsigned)(row0 + jx * NG + (PSM / 2) * 2 * m);
+            ubo[1] = (unsigned)(row0 + (jx ? 1 : 3 * NG) + (PSM / 2) * 2 * m);
         }
         float outp[C][PX];
 #pragma unroll
         for (int c = 0; c < C; ++c) {
+            if constexpr (PERM) {
+                // The slots share few patch values (they are s pixels apart): taken all at once a channel's
+                // LDS reads would hold three times the registers of the planar form.  One filter row at a
+                // time; the empty statement ties the next row's addresses to this row's sums.
+                static_assert(F::NSLOT % K == 0 && PX == 4, "whole filter rows per lane half");
+                float sq[PX];
 #pragma unroll
-            for (int q = 0; q < PX; ++q) {
-                float s = 0.0f;
+                for (int q = 0; q < PX; ++q) sq[q] = 0.0f;
 #pragma unroll
-                for (int vv = 0; vv < F::NSLOT; ++vv) {
-                    const int dyv = vv / K, dxv = vv % K;
-                    if constexpr (PSM == 4) {
-                        // e0 = 4 q + dx: class (dx + j) % 4, group q + (dx % 4 + j) / 4 + dx / 4
-                        s = fmaf(acc[q][vv / 16][vv % 16], ubp[dxv & 3][c * UH * P + dyv * P + q + (dxv >> 2)], s);
-                    } else if constexpr (PSM == 2) {
-                        const int e0 = 2 * q + dxv;
-                        const int imm = c * UH * P + dyv * P + ((e0 & 3) == 3 ? 0 : (e0 & 3) * NG) + (e0 >> 2);
-                        s = fmaf(acc[q][vv / 16][vv % 16], ubp[(e0 & 3) == 3 ? 1 : 0][imm], s);
-                    } else {
+                for (int dyv = 0; dyv < F::NSLOT / K; ++dyv) {
+#pragma unroll
+                    for (int q = 0; q < PX; ++q)
+#pragma unroll
+                        for (int dxv = 0; dxv < K; ++dxv) {
+                            const int vv = dyv * K + dxv;
+                            const int e0 = PSM == 4 ? 2 * (unit % NSUB) + dxv : 2 * q + dxv;
+                            const int imm = c * UH * P + dyv * P + ((e0 & 3) == 3 ? 0 : (e0 & 3) * NG) + (e0 >> 2) + (PSM == 4 ? q : 0);
+                            sq[q] = fmaf(acc[q][vv / 16][vv % 16], U[ubo[(e0 & 3) == 3 ? 1 : 0] + imm], sq[q]);
+                        }
+                    asm volatile("" : "+v"(ubo[0]), "+v"(ubo[1]), "+v"(sq[0]), "+v"(sq[1]), "+v"(sq[2]), "+v"(sq[3]));
+                }
+#pragma unroll
+                for (int q = 0; q < PX; ++q) outp[c][q] = sq[q];
+            } else {
+#pragma unroll
+                for (int q = 0; q < PX; ++q) {
+                    float s = 0.0f;
+#pragma unroll
+                    for (int vv = 0; vv < F::NSLOT; ++vv) {
+                        const int dyv = vv / K, dxv = vv % K;
                         const int off = c * UH * P + dyv * P + ((q + dxv) % PX) * NG + (q + dxv) / PX;
                         s = fmaf(acc[q][vv / 16][vv % 16], ub[off], s);
                     }
+                    outp[c][q] = s;
                 }
-                outp[c][q] = s;
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -836,16 +860,19 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         //     with the rest; one vector store per channel
         // (permuted slots: the lane's own pixels start at X0 + 4 PSM m; after the exchange below it stores
         //  the two adjacent pixels that start at X0 + 4 PSM m + 2 PSM hf + 2 (n % PSM))
-        const int y = Y0 + (unit * NW + wave) * WR + jr;
-        const int x = PERM ? X0 + 4 * PSM * (jc / PSM) : X0 + PX * jc;
+        // (permuted slots, scale 4: the lane pair's pixels start at X0 + 16 m; a lane stores the four adjacent ones at
+        //  X0 + 16 m + 8 hf + 4 j, once both units of the row are done)
+        const int y = Y0 + unit_row(unit, wave) * WR + jr;
+        const int x = PERM ? X0 + 4 * PSM * (jc / 2) : X0 + PX * jc;
         const bool valid = y < a.H && x < a.W;
         const unsigned plane_px = (unsigned)a.H * (unsigned)a.W;
-        const unsigned o0 = PERM ? (unsigned)y * (unsigned)a.W + x + hf * (2 * PSM) + 2 * (jc % (PSM == 4 ? 4 : 2))
+        const unsigned o0 = PERM ? (unsigned)y * (unsigned)a.W + x + hf * (2 * PSM) + (PSM == 4 ? 4 : 2) * (jc % 2)
                                  : (unsigned)y * (unsigned)a.W + x + hf * (PX / 2);   // within the image
         char* const out_img = (char*)a.out + (size_t)cur.n * C * ((size_t)plane_px * (a.io_f16 ? 2 : 4));
 #pragma unroll
         for (int c = 0; c < C; ++c) {
             float tot[PX / 2];
+            float tot4[4] = {0.0f, 0.0f, 0.0f, 0.0f};  // scale-4 permuted slots: the four adjacent pixels a lane stores
 #pragma unroll
             for (int q = 0; q < PX / 2; ++q) {
                 const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(outp[c][q]),
@@ -853,16 +880,23 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 tot[q] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
             }
             if constexpr (PSM == 4) {
-                // The quad (j = 0..3) holds the 8 pixels 16 m + 8 hf + {4 t + j}, t = slot: lane j' takes the
-                // adjacent pair 2 j', 2 j' + 1, i.e. slot j' / 2 of lanes 2 (j' % 2) and 2 (j' % 2) + 1.
-                const unsigned t0 = __float_as_uint(tot[0]), t1 = __float_as_uint(tot[1]);
-                const unsigned a0 = __builtin_amdgcn_update_dpp(0u, t0, 0x88, 0xf, 0xf, false);   // quad_perm [0,2,0,2]
-                const unsigned a1 = __builtin_amdgcn_update_dpp(0u, t1, 0x88, 0xf, 0xf, false);
-                const unsigned b0 = __builtin_amdgcn_update_dpp(0u, t0, 0xDD, 0xf, 0xf, false);   // quad_perm [1,3,1,3]
-                const unsigned b1 = __builtin_amdgcn_update_dpp(0u, t1, 0xDD, 0xf, 0xf, false);
-                const bool hi_slot = (jc & 2) != 0;
-                tot[0] = __uint_as_float(hi_slot ? a1 : a0);
-                tot[1] = __uint_as_float(hi_slot ? b1 : b0);
+                // The lane pair (j = 0, 1) holds, per unit J, the pixels 16 m + 8 hf + {4 t + 2 J + j}, t = slot.
+                // Unit J = 0 parks its two results; after unit J = 1 lane j' takes slot t = j' of both lanes and
+                // both units: the four adjacent pixels 4 j' + {0, 1 | 2, 3} = {J = 0: j = 0, 1 | J = 1: j = 0, 1}.
+                if (unit % NSUB == 0) {
+                    park[c][0] = tot[0];
+                    park[c][1] = tot[1];
+                    continue;
+                }
+                const bool odd = (jc & 1) != 0;
+                const unsigned g0 = __float_as_uint(odd ? park[c][0] : park[c][1]);    // what the partner stores
+                const unsigned g1 = __float_as_uint(odd ? tot[0] : tot[1]);
+                const float r0 = __uint_as_float(__builtin_amdgcn_update_dpp(0u, g0, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
+                const float r1 = __uint_as_float(__builtin_amdgcn_update_dpp(0u, g1, 0xB1, 0xf, 0xf, false));
+                tot4[0] = odd ? r0 : park[c][0];
+                tot4[1] = odd ? park[c][1] : r0;
+                tot4[2] = odd ? r1 : tot[0];
+                tot4[3] = odd ? tot[1] : r1;
             } else if constexpr (PSM == 2) {
                 // The lane pair (j = 0, 1) holds the 4 pixels 8 m + 4 hf + {2 t + j}: lane j' takes 2 j', 2 j' + 1,
                 // i.e. slot j' of both lanes of the pair.
@@ -881,7 +915,19 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             if (valid) {
 #endif
                 const unsigned oe = o0 + c * plane_px;
-                if (a.io_f16) {
+                if constexpr (PSM == 4) {
+                    if (a.io_f16) {
+                        __half2 lo2, hi2;
+                        lo2.x = narrow_f16(tot4[0]); lo2.y = narrow_f16(tot4[1]);
+                        hi2.x = narrow_f16(tot4[2]); hi2.y = narrow_f16(tot4[3]);
+                        u32x2 w2;
+                        w2[0] = __builtin_bit_cast(unsigned, lo2);
+                        w2[1] = __builtin_bit_cast(unsigned, hi2);
+                        *(u32x2*)(out_img + (size_t)(oe * 2u)) = w2;
+                    } else {
+                        *(float4*)(out_img + (size_t)(oe * 4u)) = make_float4(tot4[0], tot4[1], tot4[2], tot4[3]);
+                    }
+                } else if (a.io_f16) {
                     __half* op = (__half*)(out_img + (size_t)(oe * 2u));
                     if constexpr (PX >= 4) {
 #pragma unroll
@@ -936,7 +982,7 @@ inline int compute_units() {
 template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT = CT_F16, int SMIN = 2, bool BIG = false,
           int PSM = 0>
 hipError_t launch_one(const AssembleArgs& a0, hipStream_t st) {
-    using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN>;
+    using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN, (PSM == 4 ? 2 : 1)>;
     if (a0.s < SMIN) return hipErrorInvalidValue;       // its LDS footprint buffers would be too small
     if ((a0.pre_shuffle != 0) != (PSM != 0)) return hipErrorInvalidValue;
     // permuted pixel slots: a lane owns four whole LR columns, the image must end on such a group

@@ -26,7 +26,11 @@ def run(inp, wl, coeff, kernel, layout, kept=None, gamma=None):
 CASES = [
     # (N, C, h, w, scale, L, k, coeff dtype, image dtype, kept atoms or None)
     (1, 3, 37, 64, 4, 72, 5, "f16", "f32", None),       # the matrix-core family: several tiles, ragged rows
-    (2, 3, 50, 96, 4, 72, 5, "f16", "f32", None),       # two images, 384 wide: three tile columns
+    (2, 3, 50, 96, 4, 72, 5, "f16", "f32", None),       # two images, 384 wide: a full and a partial 256-pixel tile column
+    (2, 3, 21, 72, 4, 72, 5, "f16", "f16", None),       # scale 4 with an fp16 image (a lane stores four pixels as 8 bytes)
+    (1, 3, 33, 132, 4, 72, 5, "f16", "f32", 8),         # scale 4, the small capacity, three tile columns, rows not a multiple of 8
+    (1, 3, 9, 4, 4, 72, 5, "f16", "f32", None),         # scale 4, one LR pixel group wide: one lane pair per row does the work
+    (1, 3, 27, 140, 2, 72, 5, "f16", "f16", 70),        # scale 2, fp16 image, 70 kept atoms with gamma
     (1, 3, 41, 66, 2, 72, 5, "f16", "f32", None),       # scale 2: a lane's four pixels span two LR columns
     (1, 3, 29, 44, 3, 72, 5, "f16", "f32", None),       # scale 3: the sub-pixel of a lane's first pixel varies
     (1, 3, 40, 64, 4, 72, 5, "f16", "f32", 8),          # a kept list of 8: the small capacity
