@@ -28,8 +28,9 @@
  *     accumulation is fp32).
  *
  * All tensors are contiguous NCHW in DEVICE memory, allocated, owned and freed
- * by the caller.  The library allocates nothing, keeps no state between calls
- * and is re-entrant.  Work is enqueued on `stream` and the call returns without
+ * by the caller.  The library allocates nothing, is re-entrant, and keeps nothing
+ * between calls but what it has asked the device once (its number of compute
+ * units, per host thread).  Work is enqueued on `stream` and the call returns without
  * synchronising: inputs and outputs must stay valid until the stream reaches
  * the end of the kernel.  `out` must not overlap any input.
  *

@@ -9,7 +9,7 @@
 // 16-byte groups and every entry gathers its atom's row from there; stage 1 and stage 4 are
 // the generic kernel's (sr_generic.hip), on a 256 x 4 tile.  Bound: the LDS gathers
 // (T * k^2 * 4 bytes per pixel), not HBM.  This kernel takes every supported case; 5x5 atoms, three
-// channels and fp16 values go to the matrix-core kernel instead (CT_LIST in sr_mfma_kernel.h), which
+// channels and fp16 values go to the matrix-core kernel instead (CT_LIST8, CT_LIST16 in sr_mfma_kernel.h), which
 // scatters the lists into dense 16-atom operands and is several times faster.
 #include <stdint.h>
 

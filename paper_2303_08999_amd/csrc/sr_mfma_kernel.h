@@ -70,11 +70,15 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 // how the coefficients are stored (template argument CT of the kernel)
-constexpr int CT_F16 = 0, CT_F32 = 1, CT_F8 = 2, CT_BF16 = 3, CT_LIST = 4;
-// CT_LIST: no dense planes; every pixel brings a list of (atom index, fp16 value) entries (an extension
-// beyond the paper, see sr_dict_assemble_list).  A wavefront scatters the entries of its 128 pixels that
-// fall into the current 16-atom step into a 4 KB LDS scratch [pixel][16 atoms] - which is exactly the
-// matrix cores' B operand, one 16-byte read per pixel slot - and the fold then runs as for fp16 planes.
+constexpr int CT_F16 = 0, CT_F32 = 1, CT_F8 = 2, CT_BF16 = 3, CT_LIST8 = 4, CT_LIST16 = 5;
+// CT_LIST8 / CT_LIST16: no dense planes; every pixel brings a list of up to 8 / 16 (atom index, fp16 value)
+// entries (an extension beyond the paper, see sr_dict_assemble_list).  Each wavefront owns an LDS scratch
+// [group of 8 atoms][32 pixels][8 atoms] fp16, all zero between uses.  Pixel slot by pixel slot it scatters
+// the entries of 32 pixels into it (one 2-byte LDS write each; a lane writes only into its own pixel's 16-byte
+// pieces, so few writes meet in a bank), reads its pieces back with 16-byte loads - the piece of group
+// 2 c + hf is exactly the matrix cores' B operand of 16-atom step c in the dense form - and writes zeros where
+// it wrote values.  The fold, the filtering and
+// the store then run as for fp16 planes.
 constexpr int LIST_MAX_ENTRIES = 16;
 
 // SMIN: smallest scale the instantiation may be launched with.  The LR footprint
@@ -83,7 +87,9 @@ constexpr int LIST_MAX_ENTRIES = 16;
 // tile (fewer halo rows up-sampled per output row).
 template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int CT = CT_F16, int SMIN = 2, int NSUB = 1>
 struct Cfg {
-    static constexpr bool F32 = CT == CT_F32, F8 = CT == CT_F8, BF = CT == CT_BF16, LIST = CT == CT_LIST;
+    static constexpr bool F32 = CT == CT_F32, F8 = CT == CT_F8, BF = CT == CT_BF16, LIST = CT == CT_LIST8 || CT == CT_LIST16;
+    static constexpr int LH = CT == CT_LIST8 ? 4 : 8;  // list form: entries a lane half loads
+    static constexpr int LSW = 4 * NP8 * 32;           // list form: scratch words per wavefront
     static constexpr int KK = K * K, R = (K - 1) / 2;
     static constexpr int RH0 = (K + 1) / 2;            // filter rows owned by lane half 0
     static constexpr int NSLOT = RH0 * K;              // accumulator rows used per half
@@ -102,7 +108,7 @@ struct Cfg {
     static constexpr int MAXLRY = (UH - 1) / SMIN + 5, MAXLRX = (UW - 1) / SMIN + 5;
     // fp16 coefficients: 16-atom MFMA steps and an optional 8-atom step;
     // fp32 coefficients: 2-atom steps of v_mfma_f32_32x32x2_f32, one load each
-    static constexpr int N16 = F32 ? 0 : (LIST ? (NP8 + 1) / 2 : NP8 / 2), N8 = (F32 || LIST) ? 0 : NP8 % 2;
+    static constexpr int N16 = F32 ? 0 : NP8 / 2, N8 = F32 ? 0 : NP8 % 2;
     static constexpr int N2 = F32 ? 4 * NP8 : 0;
     static constexpr int NLOAD = F32 ? N2 : (LIST ? 1 : 8 * N16 + 4 * N8);   // coefficient loads per lane and unit
     static constexpr int CB = F32 ? 4 : (F8 ? 1 : 2);  // bytes per stored coefficient
@@ -230,7 +236,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     constexpr int NSUB = PSM == 4 ? 2 : 1;         // units per tile row
     using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN, NSUB>;
     constexpr bool F32 = F::F32, F8 = F::F8, BF = F::BF, LIST = F::LIST;
-    constexpr int LH = LIST_MAX_ENTRIES / 2;       // list entries a lane half loads
+    constexpr int LH = F::LH;                      // list entries a lane half loads
     static_assert(!LIST || (PX == 4 && WR == 1 && !BIG && PSM == 0 && NU % 2 == 0), "list form: four pixels per lane, one row per unit");
     constexpr bool PS = PSM == 1;                  // one 16-bit load per pixel
     constexpr bool PERM = PSM == 2 || PSM == 4;    // permuted pixel slots
@@ -255,7 +261,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     __shared__ float A32[(F32 ? F::N2 * NMB : 1) * 64];   // fp32 path: D[2*step + hf][tap of row]
     __shared__ unsigned ptab[2 * F::NLOAD];         // byte offset of the plane each lane half loads
     __shared__ unsigned ltab[LIST ? 2 * LH : 1];    // list form: element offset of the entry plane each lane half loads
-    __shared__ u32x4 lscr[LIST ? NW * 256 : 1];     // list form: per wavefront, [128 pixels][16 atoms] fp16
+    __shared__ u32x4 lscr[LIST ? NW * F::LSW / 4 : 1];   // list form: per wavefront, [NP8 groups of 8 atoms][32 pixels][8 atoms] fp16
 
     const int tid0 = threadIdx.x;
     const int groups = (gridDim.x & 7) == 0 ? 8 : 1;
@@ -287,11 +293,15 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         wk[tid0] = make_float4(wt[0], wt[1], wt[2], wt[3]);
     }
     if constexpr (LIST) {
-        // half h takes entries h * ceil(T / 2) ...; slots past the list are marked and later masked
+        for (int e = tid0; e < NW * F::LSW / 4; e += NT) lscr[e] = u32x4{0u, 0u, 0u, 0u};
+        // half h takes entries h * ceil(T / 2) ...; a slot past the list repeats an entry the pixel has (the
+        // half's first one, or entry 0): written twice to the same place with the same value
         const int per_half = (a.T + 1) / 2;
         for (int e = tid0; e < 2 * LH; e += NT) {
-            const int h = e / LH, i = e - h * LH, t = h * per_half + i;
-            ltab[e] = (i < per_half && t < a.T) ? (unsigned)t * ((unsigned)a.H * (unsigned)a.W) : 0xffffffffu;   // in elements
+            const int h = e / LH, i = e - h * LH;
+            int t = h * per_half + i;
+            if (i >= per_half || t >= a.T) t = h * per_half < a.T ? h * per_half : 0;
+            ltab[e] = (unsigned)t * ((unsigned)a.H * (unsigned)a.W);               // in elements
         }
     }
     for (int e = tid0; e < (LIST ? 0 : 2 * F::NLOAD); e += NT) {
@@ -336,6 +346,26 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         }
     }
     __syncthreads();
+
+    // list form, up to 72 atoms: the dictionary operands stay in registers (the fold reads them once per pixel
+    // slot, four times as often as the dense form does)
+    constexpr bool AREG = LIST && NP8 <= 9;
+    u32x4 areg[AREG ? 2 * N16 : 1];
+    u32x2 areg8[AREG && N8 ? 2 : 1];
+    if constexpr (AREG) {
+#pragma unroll
+        for (int i = 0; i < 2 * N16; ++i) {
+            areg[i] = A16[i * 64 + (tid0 & 63)];
+            asm volatile("" : "+v"(areg[i]));           // opaque: or the compiler reloads it from LDS at every use
+        }
+        if constexpr (N8 != 0) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                areg8[i] = A8[i * 64 + (tid0 & 63)];
+                asm volatile("" : "+v"(areg8[i]));
+            }
+        }
+    }
 
     // ---- tile walk.  Workgroups are dealt to the 8 XCDs round-robin by index, and
     //      each XCD has its own L2.  When the grid is a multiple of 8, XCD x (the
@@ -498,12 +528,9 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         const unsigned* lt = ltab + hf * LH;
 #pragma unroll
         for (int e = 0; e < LH; ++e) {
-            const unsigned off = lt[e];
-            const bool have = off != 0xffffffffu;
-            const unsigned at = (have ? off : 0u) + pix;                            // slots past the list re-read entry 0
-            const unsigned ix = __builtin_nontemporal_load((const unsigned*)(ibase + at));
+            const unsigned at = lt[e] + pix;
+            idx[e] = __builtin_nontemporal_load((const unsigned*)(ibase + at));
             val[e] = __builtin_nontemporal_load((const u32x2*)(vbase + (size_t)at * 2));
-            idx[e] = have ? ix : 0xffffffffu;                                        // atom 255: in no step of up to 128 atoms
         }
     };
     Raw raw[F::NLOAD];
@@ -689,36 +716,52 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             }
             const u32x2 (&val)[LH] = lval[unit & 1];
             const unsigned (&idx)[LH] = lidx[unit & 1];
-            u32x4* const scr = lscr + wave * 256;
-            unsigned short* const scr16 = (unsigned short*)scr;
+            static_assert(NMB == 1, "list form: one block of MFMA rows");
+            // (16-bit writes and vector reads of the same words: the write goes through a type that may alias
+            //  anything, or the compiler is free to move a read above the write it depends on)
+            typedef unsigned short __attribute__((may_alias)) u16a;
+            u32x4* const scrw = lscr + wave * (F::LSW / 4);
+            char* const col = (char*)(scrw + jc);              // atom a of the lane's pixel: col + (a / 8) * 512 + (a % 8) * 2
+            // Per pixel slot: scatter, read the operand pieces, write the zeros back - all three go out at once
+            // (LDS serves a wavefront's requests in order) - and only the fold waits for the pieces.  The next
+            // slot's requests are issued before this slot's fold, so that they travel while the matrix cores work.
+            u32x4 bw16[2][N16 ? N16 : 1];
+            u32x2 bw8[2];
+            auto issue = [&](int q, int b) {
+                // lanes j and j + 32 hold different entries of the same pixels.  An atom number the dictionary
+                // does not have (a caller's error) is kept inside the pixel's own pieces.
+                unsigned where[LH];
 #pragma unroll
-            for (int c16 = 0; c16 < N16; ++c16) {
-                u32x4 av[NMB][2];
-#pragma unroll
-                for (int mb = 0; mb < NMB; ++mb)
-#pragma unroll
-                    for (int hl = 0; hl < 2; ++hl) av[mb][hl] = A16[((c16 * NMB + mb) * 2 + hl) * 64 + lane];
-                const u32x4 zero = {0u, 0u, 0u, 0u};
-#pragma unroll
-                for (int i = 0; i < 4; ++i) scr[lane + 64 * i] = zero;
-#pragma unroll
-                for (int e = 0; e < LH; ++e)
-#pragma unroll
-                    for (int q = 0; q < PX; ++q) {
-                        const unsigned atom = (idx[e] >> (8 * q)) & 0xffu;
-                        if ((atom >> 4) == (unsigned)c16)                 // lanes j and j + 32 hold different entries of the same pixels
-                            scr16[(PX * jc + q) * 16 + (atom & 15u)] = (unsigned short)(val[e][q >> 1] >> (16 * (q & 1)));
-                    }
-#pragma unroll
-                for (int q = 0; q < PX; ++q) {
-                    const u32x4 bw = scr[(PX * jc + q) * 2 + hf];         // atoms 8 hf .. 8 hf + 7 of the step, packed in pairs
-#pragma unroll
-                    for (int mb = 0; mb < NMB; ++mb)
-#pragma unroll
-                        for (int hl = 0; hl < 2; ++hl) acc[q][mb] = mfma_16<false>(av[mb][hl], bw, acc[q][mb]);
+                for (int e = 0; e < LH; ++e) {
+                    unsigned atom = (idx[e] >> (8 * q)) & 0xffu;
+                    atom = atom < 8u * NP8 ? atom : 8u * NP8 - 1u;
+                    where[e] = (atom >> 3) * 512u + (atom & 7u) * 2u;
+                    *(u16a*)(col + where[e]) = (unsigned short)(val[e][q >> 1] >> (16 * (q & 1)));
                 }
+#pragma unroll
+                for (int c16 = 0; c16 < N16; ++c16) bw16[b][c16] = scrw[(2 * c16 + hf) * 32 + jc];
+                if constexpr (N8 != 0) bw8[b] = *(const u32x2*)(col + (2 * N16) * 512 + 8 * hf);
+#pragma unroll
+                for (int e = 0; e < LH; ++e) *(u16a*)(col + where[e]) = (unsigned short)0;
+            };
+            issue(0, 0);
+#pragma unroll
+            for (int q = 0; q < PX; ++q) {
                 __builtin_amdgcn_sched_barrier(0);
+                if (q + 1 < PX) issue(q + 1, (q + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int c16 = 0; c16 < N16; ++c16)
+#pragma unroll
+                    for (int hl = 0; hl < 2; ++hl)
+                        acc[q][0] = mfma_16<false>(AREG ? areg[c16 * 2 + hl] : A16[(c16 * 2 + hl) * 64 + lane], bw16[q & 1][c16], acc[q][0]);
+                if constexpr (N8 != 0) {
+#pragma unroll
+                    for (int hl = 0; hl < 2; ++hl)
+                        acc[q][0] = mfma_8<false>(AREG ? areg8[hl] : A8[hl * 64 + lane], bw8[q & 1], acc[q][0]);
+                }
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
         if constexpr (F32) {
             // fp32 coefficients: the loaded words ARE the B operand (lane half hf holds
@@ -741,7 +784,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             }
         }
 #pragma unroll
-        for (int c16 = 0; c16 < (LIST ? 0 : N16); ++c16) {
+        for (int c16 = 0; c16 < (LIST ? 0 : N16); ++c16) {   // (the list form has folded above)
             u32x4 av[NMB][2];
 #pragma unroll
             for (int mb = 0; mb < NMB; ++mb)
@@ -769,7 +812,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (N8) {
+        if constexpr (N8 != 0 && !LIST) {
             u32x2 av[NMB][2];
 #pragma unroll
             for (int mb = 0; mb < NMB; ++mb)
