@@ -221,6 +221,10 @@ __device__ __forceinline__ void divmod_scale(int v, int s, int& q, int& r) {
 //         tile is 256 pixels wide and a row is TWO units, J = 0, 1: the lane reads sub-pixel column
 //         2 J + j;  slot q is HR pixel X0 + 16 m + 4 q + 2 J + j.  Every load instruction still
 //         covers whole lines (16 lanes x 8 bytes per plane).
+//       scale 3: the tile is 384 pixels wide and a row is THREE units, J = 0, 1, 2: every lane reads
+//         sub-pixel column J, lane n the LR columns 4 n .. 4 n + 3;  slot q is HR pixel X0 + 12 n + 3 q + J
+//         (two whole lines of a plane per lane half).  No exchange before the store: after the third
+//         unit a lane holds six adjacent pixels.
 //     Loads are as many and as wide as in the HR-planar form.  Stage 4 reads the tile at those
 //     pixels (per-lane LDS bases), and before the store lanes j = 0, 1 exchange results so that
 //     each holds adjacent pixels again (scale 4: the results of unit J = 0 wait in registers for
@@ -233,13 +237,13 @@ __device__ __forceinline__ void divmod_scale(int v, int s, int& q, int& r) {
 template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT, int SMIN, bool BIG, int PSM = 0>
 __global__ __launch_bounds__(64 * NW, WPE)
 void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y, const int ntiles) {
-    constexpr int NSUB = PSM == 4 ? 2 : 1;         // units per tile row
+    constexpr int NSUB = PSM == 4 ? 2 : (PSM == 3 ? 3 : 1);   // units per tile row
     using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN, NSUB>;
     constexpr bool F32 = F::F32, F8 = F::F8, BF = F::BF, LIST = F::LIST;
     constexpr int LH = F::LH;                      // list entries a lane half loads
     static_assert(!LIST || (PX == 4 && WR == 1 && !BIG && PSM == 0 && NU % 2 == 0), "list form: four pixels per lane, one row per unit");
     constexpr bool PS = PSM == 1;                  // one 16-bit load per pixel
-    constexpr bool PERM = PSM == 2 || PSM == 4;    // permuted pixel slots
+    constexpr bool PERM = PSM == 2 || PSM == 3 || PSM == 4;    // permuted pixel slots
     static_assert(PSM == 0 || (CT == CT_F16 && !BIG && PX == 4), "pre-shuffle layout: 16-bit coefficients, four pixels per lane");
     static_assert(!PERM || (WR == 1 && SMIN >= PSM), "permuted slots: one row per wavefront and unit");
     // row of the wavefront's unit within the tile, and which of the row's NSUB units it is
@@ -476,7 +480,8 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         const int yc = y < a.H ? y : a.H - 1, xc = x < a.W ? x : a.W - PX;   // out-of-image lanes re-read
         if constexpr (PERM) {
             // jc is the lane's column n: sub-pixel column (unit % NSUB) * 2 + n % 2, LR columns 4 m .. 4 m + 3, m = n / 2
-            const int jx = (unit % NSUB) * 2 + jc % 2, m = jc / 2;
+            // (scale 3: every lane reads sub-pixel column unit % 3, lane n the LR columns 4 n .. 4 n + 3)
+            const int jx = PSM == 3 ? unit % NSUB : (unit % NSUB) * 2 + jc % 2, m = PSM == 3 ? jc : jc / 2;
             const int ly = yc / PSM, iy = yc % PSM;
             int lx = tile_x0(tp.tx) / PSM + 4 * m;
             lx = lx + 4 <= a.w ? lx : a.w - 4;                                     // lanes past the image re-read
@@ -599,7 +604,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         // no idle lanes (rows padded to 32, 64 or 128 columns left 38 % of them idle at x4:
         // 8 atoms at 4K 90 -> 85 us, the E4M3 frame 160 -> 154 us).  idx / nlx by a multiply,
         // exact for idx < 2^22 / nlx and free of overflow for idx < 1024 nlx.
-        static_assert(C * UH <= 256 && MAXLRX <= 128, "item index beyond the exact range of the division");
+        static_assert(C * UH * MAXLRX * MAXLRX <= (1 << 22) && C * UH <= 1024, "item index beyond the exact range of the division");
         const int nlx = o.nlx < 4 ? 4 : o.nlx;
         const unsigned inv = ((1u << 22) + nlx - 1) / nlx;
         const int total = C * UH * nlx;
@@ -688,7 +693,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         stage1_horizontal(tid);
         __syncthreads();
         const unsigned* pt = ptab + hf * F::NLOAD;
-        float park[C][2];                              // scale-4 permuted slots: unit J = 0's results wait for J = 1
+        float park[C][NSUB > 1 ? NSUB - 1 : 1][2];     // permuted slots, scales 3 and 4: the results of a row's earlier units wait for the last
         // The wavefront's NU units of this tile, one after the other; while a unit
         // is folded, the coefficients of the next one (same tile, or unit 0 of the
         // next tile) are loaded into the registers that fall free.
@@ -853,8 +858,13 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         if constexpr (PERM) {
             const int jx = jc % 2, m = jc / 2;
             const int row0 = (unit_row(unit, wave) * WR + jr + hf * F::RH0) * P;
-            ubo[0] = (unsigned)(row0 + jx * NG + (PSM / 2) * 2 * m);
-            ubo[1] = (unsigned)(row0 + (jx ? 1 : 3 * NG) + (PSM / 2) * 2 * m);
+            if constexpr (PSM == 3) {
+                // column 12 n + 3 q + J + dx: class and carry are compile-time, the lane enters as group 3 n
+                ubo[0] = ubo[1] = (unsigned)(row0 + 3 * jc);
+            } else {
+                ubo[0] = (unsigned)(row0 + jx * NG + (PSM / 2) * 2 * m);
+                ubo[1] = (unsigned)(row0 + (jx ? 1 : 3 * NG) + (PSM / 2) * 2 * m);
+            }
         }
         float outp[C][PX];
 #pragma unroll
@@ -874,9 +884,14 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 #pragma unroll
                         for (int dxv = 0; dxv < K; ++dxv) {
                             const int vv = dyv * K + dxv;
-                            const int e0 = PSM == 4 ? 2 * (unit % NSUB) + dxv : 2 * q + dxv;
-                            const int imm = c * UH * P + dyv * P + ((e0 & 3) == 3 ? 0 : (e0 & 3) * NG) + (e0 >> 2) + (PSM == 4 ? q : 0);
-                            sq[q] = fmaf(acc[q][vv / 16][vv % 16], U[ubo[(e0 & 3) == 3 ? 1 : 0] + imm], sq[q]);
+                            if constexpr (PSM == 3) {
+                                const int e = 3 * q + (unit % NSUB) + dxv;
+                                sq[q] = fmaf(acc[q][vv / 16][vv % 16], U[ubo[0] + c * UH * P + dyv * P + (e & 3) * NG + (e >> 2)], sq[q]);
+                            } else {
+                                const int e0 = PSM == 4 ? 2 * (unit % NSUB) + dxv : 2 * q + dxv;
+                                const int imm = c * UH * P + dyv * P + ((e0 & 3) == 3 ? 0 : (e0 & 3) * NG) + (e0 >> 2) + (PSM == 4 ? q : 0);
+                                sq[q] = fmaf(acc[q][vv / 16][vv % 16], U[ubo[(e0 & 3) == 3 ? 1 : 0] + imm], sq[q]);
+                            }
                         }
                     asm volatile("" : "+v"(ubo[0]), "+v"(ubo[1]), "+v"(sq[0]), "+v"(sq[1]), "+v"(sq[2]), "+v"(sq[3]));
                 }
@@ -906,16 +921,19 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         // (permuted slots, scale 4: the lane pair's pixels start at X0 + 16 m; a lane stores the four adjacent ones at
         //  X0 + 16 m + 8 hf + 4 j, once both units of the row are done)
         const int y = Y0 + unit_row(unit, wave) * WR + jr;
-        const int x = PERM ? X0 + 4 * PSM * (jc / 2) : X0 + PX * jc;
+        // (scale 3: a lane's pixels start at X0 + 12 n; it stores the six adjacent ones at X0 + 12 n + 6 hf)
+        const int x = PSM == 3 ? X0 + 12 * jc : (PERM ? X0 + 4 * PSM * (jc / 2) : X0 + PX * jc);
         const bool valid = y < a.H && x < a.W;
         const unsigned plane_px = (unsigned)a.H * (unsigned)a.W;
-        const unsigned o0 = PERM ? (unsigned)y * (unsigned)a.W + x + hf * (2 * PSM) + (PSM == 4 ? 4 : 2) * (jc % 2)
+        const unsigned o0 = PSM == 3 ? (unsigned)y * (unsigned)a.W + x + hf * 6
+                          : PERM ? (unsigned)y * (unsigned)a.W + x + hf * (2 * PSM) + (PSM == 4 ? 4 : 2) * (jc % 2)
                                  : (unsigned)y * (unsigned)a.W + x + hf * (PX / 2);   // within the image
         char* const out_img = (char*)a.out + (size_t)cur.n * C * ((size_t)plane_px * (a.io_f16 ? 2 : 4));
 #pragma unroll
         for (int c = 0; c < C; ++c) {
             float tot[PX / 2];
             float tot4[4] = {0.0f, 0.0f, 0.0f, 0.0f};  // scale-4 permuted slots: the four adjacent pixels a lane stores
+            float tot6[6] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};   // scale 3: the six
 #pragma unroll
             for (int q = 0; q < PX / 2; ++q) {
                 const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(outp[c][q]),
@@ -927,19 +945,29 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 // Unit J = 0 parks its two results; after unit J = 1 lane j' takes slot t = j' of both lanes and
                 // both units: the four adjacent pixels 4 j' + {0, 1 | 2, 3} = {J = 0: j = 0, 1 | J = 1: j = 0, 1}.
                 if (unit % NSUB == 0) {
-                    park[c][0] = tot[0];
-                    park[c][1] = tot[1];
+                    park[c][0][0] = tot[0];
+                    park[c][0][1] = tot[1];
                     continue;
                 }
                 const bool odd = (jc & 1) != 0;
-                const unsigned g0 = __float_as_uint(odd ? park[c][0] : park[c][1]);    // what the partner stores
+                const unsigned g0 = __float_as_uint(odd ? park[c][0][0] : park[c][0][1]);    // what the partner stores
                 const unsigned g1 = __float_as_uint(odd ? tot[0] : tot[1]);
                 const float r0 = __uint_as_float(__builtin_amdgcn_update_dpp(0u, g0, 0xB1, 0xf, 0xf, false));   // quad_perm [1,0,3,2]
                 const float r1 = __uint_as_float(__builtin_amdgcn_update_dpp(0u, g1, 0xB1, 0xf, 0xf, false));
-                tot4[0] = odd ? r0 : park[c][0];
-                tot4[1] = odd ? park[c][1] : r0;
+                tot4[0] = odd ? r0 : park[c][0][0];
+                tot4[1] = odd ? park[c][0][1] : r0;
                 tot4[2] = odd ? r1 : tot[0];
                 tot4[3] = odd ? tot[1] : r1;
+            } else if constexpr (PSM == 3) {
+                // Slot t of unit J is pixel 6 hf + 3 t + J of the lane's twelve: after the third unit the lane holds
+                // the six adjacent ones (t = 0: J = 0, 1, 2; t = 1: J = 0, 1, 2).
+                if (unit % NSUB != NSUB - 1) {
+                    park[c][unit % NSUB][0] = tot[0];
+                    park[c][unit % NSUB][1] = tot[1];
+                    continue;
+                }
+                tot6[0] = park[c][0][0]; tot6[1] = park[c][1][0]; tot6[2] = tot[0];
+                tot6[3] = park[c][0][1]; tot6[4] = park[c][1][1]; tot6[5] = tot[1];
             } else if constexpr (PSM == 2) {
                 // The lane pair (j = 0, 1) holds the 4 pixels 8 m + 4 hf + {2 t + j}: lane j' takes 2 j', 2 j' + 1,
                 // i.e. slot j' of both lanes of the pair.
@@ -969,6 +997,18 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                         *(u32x2*)(out_img + (size_t)(oe * 2u)) = w2;
                     } else {
                         *(float4*)(out_img + (size_t)(oe * 4u)) = make_float4(tot4[0], tot4[1], tot4[2], tot4[3]);
+                    }
+                } else if constexpr (PSM == 3) {
+#pragma unroll
+                    for (int i = 0; i < 3; ++i) {
+                        if (a.io_f16) {
+                            __half2 h2;
+                            h2.x = narrow_f16(tot6[2 * i]);
+                            h2.y = narrow_f16(tot6[2 * i + 1]);
+                            *(__half2*)(out_img + (size_t)((oe + 2 * i) * 2u)) = h2;
+                        } else {
+                            *(float2*)(out_img + (size_t)((oe + 2 * i) * 4u)) = make_float2(tot6[2 * i], tot6[2 * i + 1]);
+                        }
                     }
                 } else if (a.io_f16) {
                     __half* op = (__half*)(out_img + (size_t)(oe * 2u));
@@ -1025,11 +1065,11 @@ inline int compute_units() {
 template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT = CT_F16, int SMIN = 2, bool BIG = false,
           int PSM = 0>
 hipError_t launch_one(const AssembleArgs& a0, hipStream_t st) {
-    using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN, (PSM == 4 ? 2 : 1)>;
+    using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN, (PSM == 4 ? 2 : (PSM == 3 ? 3 : 1))>;
     if (a0.s < SMIN) return hipErrorInvalidValue;       // its LDS footprint buffers would be too small
     if ((a0.pre_shuffle != 0) != (PSM != 0)) return hipErrorInvalidValue;
     // permuted pixel slots: a lane owns four whole LR columns, the image must end on such a group
-    if ((PSM == 2 || PSM == 4) && (a0.s != PSM || a0.w % 4 != 0)) return hipErrorInvalidValue;
+    if ((PSM == 2 || PSM == 3 || PSM == 4) && (a0.s != PSM || a0.w % 4 != 0)) return hipErrorInvalidValue;
     AssembleArgs a = a0;
     const int tiles_x = (a.W + F::TW - 1) / F::TW, tiles_y = (a.H + F::TH - 1) / F::TH;
     a.xlast = (tiles_x - 1) * F::TW;

@@ -32,7 +32,9 @@ CASES = [
     (1, 3, 9, 4, 4, 72, 5, "f16", "f32", None),         # scale 4, one LR pixel group wide: one lane pair per row does the work
     (1, 3, 27, 140, 2, 72, 5, "f16", "f16", 70),        # scale 2, fp16 image, 70 kept atoms with gamma
     (1, 3, 41, 66, 2, 72, 5, "f16", "f32", None),       # scale 2: a lane's four pixels span two LR columns
-    (1, 3, 29, 44, 3, 72, 5, "f16", "f32", None),       # scale 3: the sub-pixel of a lane's first pixel varies
+    (1, 3, 29, 44, 3, 72, 5, "f16", "f32", None),       # scale 3, LR width a multiple of 4: 384-pixel rows in three units
+    (2, 3, 20, 260, 3, 72, 5, "f16", "f32", None),      # scale 3, two images, 780 wide: two full tile columns and 12 pixels
+    (1, 3, 30, 132, 3, 72, 5, "f16", "f16", 8),         # scale 3, fp16 image, the small capacity
     (1, 3, 40, 64, 4, 72, 5, "f16", "f32", 8),          # a kept list of 8: the small capacity
     (1, 3, 33, 48, 3, 72, 5, "f16", "f16", 66),         # fp16 image, 66 kept atoms with gamma
     (1, 3, 20, 33, 4, 72, 5, "f16", "f32", None),       # HR width 132: not whole tiles
@@ -40,6 +42,7 @@ CASES = [
     (2, 2, 16, 21, 3, 17, 7, "f8", "f16", 5),
     (1, 3, 18, 20, 2, 30, 3, "bf16", "f32", None),
     (1, 3, 15, 17, 3, 72, 5, "f16", "f32", None),       # HR width 51: not whole pixel groups
+    (1, 3, 23, 18, 3, 72, 5, "f16", "f32", None),       # scale 3, LR width not a multiple of 4: one 16-bit load per pixel and plane
 ]
 
 
