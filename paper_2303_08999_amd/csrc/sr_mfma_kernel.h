@@ -101,8 +101,13 @@ struct Cfg {
     static constexpr int NT = 64 * NW;
     static constexpr int UW = TW + K - 1;
     static constexpr int UH = TH + K;                  // + one dummy row for half 1
-    static constexpr int NG = (UW + PX - 1) / PX;      // stride between x % PX classes
-    static constexpr int P0 = PX * NG;
+    // The tile is stored column-swizzled: column x at (x % SW) * NG + x / SW, so that lanes whose columns are SW
+    // apart read consecutive words.  SW = PX, except in the scale-4 pre-shuffle form (NSUB = 2), whose lane pairs
+    // are 16 columns apart: with eight classes they step by two words, and the odd NG puts a pair's second lane on
+    // the odd banks.
+    static constexpr int SW = NSUB == 2 ? 8 : PX;
+    static constexpr int NG = ((UW + SW - 1) / SW) | (NSUB == 2 ? 1 : 0);   // stride between the classes
+    static constexpr int P0 = SW * NG;
     // rows of one wavefront must land on disjoint banks: pitch == WC (mod 32)
     static constexpr int P = WR == 1 ? P0 : P0 + ((WC - P0 % 32) + 32) % 32;
     static constexpr int MAXLRY = (UH - 1) / SMIN + 5, MAXLRX = (UW - 1) / SMIN + 5;
@@ -645,7 +650,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             const float4 w4 = xw[xx];
             const float wt[4] = {w4.x, w4.y, w4.z, w4.w};
             const float* src = V + c * UH * MAXLRX + xb[xx];
-            float* dst = U + c * UH * P + (xx % PX) * NG + xx / PX;
+            float* dst = U + c * UH * P + (xx % F::SW) * NG + xx / F::SW;
             constexpr int RB = 7;
 #pragma unroll
             for (int y0 = 0; y0 < UH; y0 += RB) {
@@ -849,11 +854,11 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         // (4) stage 4: each half filters its taps against the LDS tile, channel by
         //     channel (a lane's PX slots share most of their patch values)
         const float* ub = U + (unit_row(unit, wave) * WR + jr + hf * F::RH0) * P + (PERM ? 0 : jc);
-        // Permuted slots: slot q, tap dx reads tile column G m + s q + e, e = e0 + j, with G = 8 or 16 and the
-        // compile-time e0 = 2 q + dx (scale 2) or 2 J + dx (scale 4).  The swizzled index of a column x is
-        // (x % 4) NG + x / 4.  The lane's j enters through two per-lane bases, so that every read is base +
-        // immediate offset: e0 % 4 < 3: class e0 % 4 + j of the same group; e0 % 4 == 3: class 3, or (j = 1)
-        // class 0 of the next group.
+        // Permuted slots: slot q, tap dx reads tile column G m + e0 + j, with G = 8 or 16 (two groups of SW = 4 or 8
+        // columns) and the compile-time e0 = 2 q + dx (scale 2) or 4 q + 2 J + dx (scale 4).  The swizzled index
+        // of a column x is (x % SW) NG + x / SW.  The lane's j enters through two per-lane bases, so that every
+        // read is base + immediate offset: e0 % SW < SW - 1: class e0 % SW + j of the same group; otherwise the
+        // last class, or (j = 1) class 0 of the next group.
         unsigned ubo[2] = {0u, 0u};                    // as element offsets into U
         if constexpr (PERM) {
             const int jx = jc % 2, m = jc / 2;
@@ -862,8 +867,9 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 // column 12 n + 3 q + J + dx: class and carry are compile-time, the lane enters as group 3 n
                 ubo[0] = ubo[1] = (unsigned)(row0 + 3 * jc);
             } else {
-                ubo[0] = (unsigned)(row0 + jx * NG + (PSM / 2) * 2 * m);
-                ubo[1] = (unsigned)(row0 + (jx ? 1 : 3 * NG) + (PSM / 2) * 2 * m);
+                // (scale 2 and scale 4 alike: the pair's columns start 8 or 16 apart, two groups of SW columns)
+                ubo[0] = (unsigned)(row0 + jx * NG + 2 * m);
+                ubo[1] = (unsigned)(row0 + (jx ? 1 : (F::SW - 1) * NG) + 2 * m);
             }
         }
         float outp[C][PX];
@@ -888,9 +894,12 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                                 const int e = 3 * q + (unit % NSUB) + dxv;
                                 sq[q] = fmaf(acc[q][vv / 16][vv % 16], U[ubo[0] + c * UH * P + dyv * P + (e & 3) * NG + (e >> 2)], sq[q]);
                             } else {
-                                const int e0 = PSM == 4 ? 2 * (unit % NSUB) + dxv : 2 * q + dxv;
-                                const int imm = c * UH * P + dyv * P + ((e0 & 3) == 3 ? 0 : (e0 & 3) * NG) + (e0 >> 2) + (PSM == 4 ? q : 0);
-                                sq[q] = fmaf(acc[q][vv / 16][vv % 16], U[ubo[(e0 & 3) == 3 ? 1 : 0] + imm], sq[q]);
+                                // column within the pair's group, before the lane's j is added; classes of SW columns
+                                constexpr int SW = F::SW;
+                                const int e0 = PSM == 4 ? 4 * q + 2 * (unit % NSUB) + dxv : 2 * q + dxv;
+                                const bool wrap = e0 % SW == SW - 1;
+                                const int imm = c * UH * P + dyv * P + (wrap ? 0 : (e0 % SW) * NG) + e0 / SW;
+                                sq[q] = fmaf(acc[q][vv / 16][vv % 16], U[ubo[wrap ? 1 : 0] + imm], sq[q]);
                             }
                         }
                     asm volatile("" : "+v"(ubo[0]), "+v"(ubo[1]), "+v"(sq[0]), "+v"(sq[1]), "+v"(sq[2]), "+v"(sq[3]));
