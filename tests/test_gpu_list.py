@@ -119,3 +119,33 @@ def test_4k_frame_top_8(oracle):
         ref = oracle.assemble_topk(U, idx.cpu().numpy(), val.cpu().numpy(), inp["dict"].cpu().numpy(), rows=band)
         err = np.abs(got[:, :, band[0]:band[1]].cpu().numpy().astype(np.float64) - ref[:, :, band[0]:band[1]])
         assert (err <= parity_bound(ref[:, :, band[0]:band[1]], "f16")).all(), f"rows {band}: worst error {err.max():.3e}"
+
+
+def test_random_shapes_both_list_kernels_agree():
+    """Seeded random frames and list lengths: the matrix-core form against the gather kernel (itself checked against
+    the oracle above).  Both widen the same stored values; they differ by fp32 rounding order and by the 2^-22
+    residue of the two-operand dictionary: 5e-5 * max(1, max|out|), plus fp16 rounding for an fp16 image."""
+    rng = np.random.default_rng(20230318)
+    compared = 0
+    for index in range(60):
+        s = int(rng.choice([2, 3, 4]))
+        h, w = int(rng.integers(1, 40)), int(rng.integers(1, 50))
+        if (w * s) % 4:
+            w = 4 * ((w + 3) // 4)
+        n = int(rng.choice([1, 1, 2]))
+        L = int(rng.choice([72, 72, 40, 100, 128, 9]))
+        T = int(rng.integers(1, min(16, L) + 1))
+        io = str(rng.choice(["f32", "f16"]))
+        wl = sr_synth.Workload("listr", 400 + index, n, 3, h, w, s, L, 5, "f16", io, 0.0, 1.5)
+        inp = sr_synth.make_inputs(wl, DEV)
+        idx, val = sr_synth.to_list(inp["coeff"], T)
+        a = run(inp, wl, idx, val, MFMA)
+        assert a is not None, f"{wl} T={T}: this case belongs to the matrix-core kernel"
+        b = run(inp, wl, idx, val, GENERIC)
+        assert torch.isfinite(a).all(), f"{wl}: some output pixel was never written"
+        scale = max(1.0, float(b.float().abs().max()))
+        tol = (5e-5 + (2.0 ** -10 if io == "f16" else 0.0)) * scale
+        err = float((a.float() - b.float()).abs().max())
+        assert err <= tol, f"{wl} T={T}: kernels differ by {err:.3e} > {tol:.1e}"
+        compared += 1
+    assert compared == 60

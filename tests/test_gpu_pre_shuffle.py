@@ -98,3 +98,44 @@ def test_4k_frame_in_the_pre_shuffle_layout(oracle):
     want = oracle.assemble_points(U, oracle.pixel_shuffle(host_pre, wl.scale), inp["dict"].cpu().numpy(), pts)
     have = got.cpu().numpy()[0][:, pts[:, 1], pts[:, 2]].T
     assert_parity(have, want, "f16", False, "sampled pixels")
+
+
+def test_1080p_x3_frame_in_the_pre_shuffle_layout():
+    """The 1080p x3 workload (384-pixel rows in three units, one workgroup of eight wavefronts per CU) equals the
+    planar call bit for bit; the planar call itself is checked against the oracle in test_gpu_parity.py."""
+    wl = sr_synth.WORKLOADS["1080p_fp16"]
+    inp = sr_synth.make_inputs(wl, DEV)
+    planar = run(inp, wl, inp["coeff"], MFMA, sr.SR_COEFF_PLANAR)
+    got = run(inp, wl, sr_synth.to_pre_shuffle(inp["coeff"], wl.scale), MFMA, sr.SR_COEFF_PRE_SHUFFLE)
+    assert got is not None and planar is not None
+    assert torch.equal(got, planar)
+
+
+def test_random_shapes_in_the_pre_shuffle_layout():
+    """Seeded random frames of the matrix-core family (5x5 atoms, three channels, fp16 coefficients, all 72 atoms or a
+    kept list of up to 8): LR widths that are and are not multiples of 4, every scale, one to three images, fp16 and
+    fp32 images.  Whatever form serves the case (permuted slots, or one 16-bit load per pixel), the output must be the
+    planar call's, bit for bit, and every pixel must be written."""
+    rng = np.random.default_rng(20230317)
+    forms = 0
+    for index in range(60):
+        s = int(rng.choice([2, 3, 4]))
+        h = int(rng.integers(1, 40))
+        w = int(rng.integers(1, 30)) * 4 if rng.random() < 0.7 else int(rng.integers(2, 120))
+        n = int(rng.choice([1, 1, 2, 3]))
+        io = str(rng.choice(["f32", "f16"]))
+        wl = sr_synth.Workload("psr", 300 + index, n, 3, h, w, s, 72, 5, "f16", io, 0.0, 1.5)
+        kept = gamma = None
+        if rng.random() < 0.4:
+            nk = int(rng.integers(1, 9))
+            kept = np.sort(rng.choice(72, size=nk, replace=False)).astype(np.int32)
+            gamma = rng.uniform(0.5, 1.5, size=nk).astype(np.float32)
+        inp = sr_synth.make_inputs(wl, DEV)
+        planar = run(inp, wl, inp["coeff"], MFMA, sr.SR_COEFF_PLANAR, kept, gamma)
+        got = run(inp, wl, sr_synth.to_pre_shuffle(inp["coeff"], s), MFMA, sr.SR_COEFF_PRE_SHUFFLE, kept, gamma)
+        if planar is None or got is None:
+            continue                                    # a width the matrix-core kernel does not take
+        assert not torch.isnan(got).any(), f"{wl}: some output pixel was never written"
+        assert torch.equal(got, planar), f"{wl} kept {kept}: the two layouts must give the same bits"
+        forms += 1
+    assert forms >= 40, forms
