@@ -44,7 +44,14 @@
 //     2*step + hf and the loaded words are the B operand as they are; the
 //     dictionary stays fp32, products and sums are true fp32;
 //   * CT_F8 (8-bit E4M3 storage): 4 pixels per 4-byte load, widened exactly to
-//     fp16 pairs in registers, then the fp16 steps above.
+//     fp16 pairs in registers, then the fp16 steps above;
+//   * CT_BF16: the fp16 flow with the bfloat16 matrix instructions and the
+//     dictionary as two bfloat16 operands;
+//   * CT_LIST8 / CT_LIST16 (an extension beyond the paper): no planes, but per-pixel
+//     lists of (atom, value) entries, scattered into the B operand through LDS
+//     (see the constants below).
+// Other coefficient layouts (template argument PSM): the planes as the coefficient
+// network holds them before its pixel-shuffle layer (see the kernel's own comment).
 //
 // Measurement builds (python -m paper_2303_08999_amd.build -o other.so -DSR_ABLATE_...): the
 // same launch with a part switched off, to see what that part costs.  SR_ABLATE_STORES keeps

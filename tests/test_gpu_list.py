@@ -149,3 +149,20 @@ def test_random_shapes_both_list_kernels_agree():
         assert err <= tol, f"{wl} T={T}: kernels differ by {err:.3e} > {tol:.1e}"
         compared += 1
     assert compared == 60
+
+
+def test_list_tensors_at_odd_addresses(oracle):
+    """The index tensor needs no alignment and the values only their own (2 bytes): both kernels must take views that
+    start in the middle of a word (the matrix-core kernel reads four indices and four values at a time)."""
+    wl = sr_synth.Workload("listodd", 63, 1, 3, 23, 36, 4, 72, 5, "f16", "f32", 0.0, 1.5)
+    inp = sr_synth.make_inputs(wl, DEV)
+    idx, val = sr_synth.to_list(inp["coeff"], 6)
+    ibuf = torch.zeros(idx.numel() + 8, device=DEV, dtype=torch.uint8)
+    vbuf = torch.zeros(val.numel() + 8, device=DEV, dtype=val.dtype)
+    for shift_i, shift_v in ((1, 1), (3, 2), (2, 3)):
+        iv = ibuf[shift_i:shift_i + idx.numel()].view(idx.shape)
+        vv = vbuf[shift_v:shift_v + val.numel()].view(val.shape)
+        iv.copy_(idx)
+        vv.copy_(val)
+        assert iv.data_ptr() % 4 == shift_i % 4 and vv.data_ptr() % 8 == (2 * shift_v) % 8
+        check(oracle, wl, 6, iv, vv)
