@@ -129,11 +129,12 @@ def probe_study(sr, torch, hr_h=2160, hr_w=3840):
 def table1_sweep(sr, torch, sr_synth):
     """The compression-ratio ablation (the paper's Fig. 7: time of dictionary query + filtering against the
     share of atoms kept) at the input sizes and scales of its Table I, for fp32 coefficients (the paper's
-    precision) and fp16.  Random kept lists, gamma = 1; microseconds per launch (median of 20), three rotating
-    coefficient tensors where they fit."""
+    precision) and fp16.  Random kept lists with regression scales gamma drawn from U[0.5, 1.5] (section III-A,
+    Eq. 9); microseconds per launch (median of 20), three rotating coefficient tensors where they fit."""
     import numpy as np
     rng = np.random.default_rng(7)
     lists = {n: np.sort(rng.choice(72, size=n, replace=False)).astype(np.int32) for n in (72, 58, 43, 29, 14, 8)}
+    gammas = {n: rng.uniform(0.5, 1.5, size=n).astype(np.float32) for n in lists}
     rows = []
     for (h, w) in ((64, 64), (128, 128), (180, 320), (360, 640)):
         for scale in (2, 3, 4):
@@ -146,7 +147,8 @@ def table1_sweep(sr, torch, sr_synth):
                 row = {"lr": f"{w}x{h}", "scale": scale, "coeff": cd, "us": {}}
                 for n_keep, klist in lists.items():
                     def run(i):
-                        sr.sr_dict_assemble_ex(inp["lr"], coeffs[i % 3], inp["dict"], 72, 5, scale, 3, out, kept=klist)
+                        sr.sr_dict_assemble_ex(inp["lr"], coeffs[i % 3], inp["dict"], 72, 5, scale, 3, out, kept=klist,
+                                               gamma=gammas[n_keep])
                     for i in range(3):
                         run(i)
                     torch.cuda.synchronize()
@@ -461,7 +463,7 @@ def main():
             if n_keep > wl.L:
                 continue
             klist = np.sort(rng.choice(wl.L, size=n_keep, replace=False)).astype(np.int32)
-            gam = np.ones(n_keep, dtype=np.float32)
+            gam = rng.uniform(0.5, 1.5, size=n_keep).astype(np.float32)     # the kept atoms' regression scales (Eq. 9)
 
             def kstep(i):
                 sr.sr_dict_assemble_ex(inp["lr"], coeffs[i % N_ROTATE], inp["dict"], wl.L, wl.k, wl.scale,
