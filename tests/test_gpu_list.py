@@ -166,3 +166,30 @@ def test_list_tensors_at_odd_addresses(oracle):
         vv.copy_(val)
         assert iv.data_ptr() % 4 == shift_i % 4 and vv.data_ptr() % 8 == (2 * shift_v) % 8
         check(oracle, wl, 6, iv, vv)
+
+
+@pytest.mark.parametrize("kernel", [GENERIC, MFMA])
+def test_list_call_replays_inside_a_captured_graph(kernel):
+    """One kernel, no allocation, and the matrix-core form clears and restores its LDS scratch itself: the call
+    can be captured in a HIP graph.  Three replays with new inputs copied into the captured buffers and eager work
+    in between, each compared with an eager call."""
+    wl = sr_synth.Workload("listg", 64, 1, 3, 40, 64, 4, 72, 5, "f16", "f32", 0.0, 1.5)
+    first = sr_synth.make_inputs(wl, DEV)
+    idx0, val0 = sr_synth.to_list(first["coeff"], 8)
+    lr, idx, val, D = first["lr"].clone(), idx0.clone(), val0.clone(), first["dict"].clone()
+    out = torch.zeros((wl.n, wl.c, wl.H, wl.W), device=DEV)
+    call = lambda: sr.sr_dict_assemble_list_ex(lr, idx, val, D, wl.L, wl.k, wl.scale, wl.c, 8, out, kernel=kernel)
+    call()                                                                   # warm-up outside capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for rep in range(3):
+        fresh = sr_synth.make_inputs(sr_synth.scaled(wl, index=wl.index + 1 + rep), DEV)
+        fi, fv = sr_synth.to_list(fresh["coeff"], 8)
+        lr.copy_(fresh["lr"]); idx.copy_(fi); val.copy_(fv); D.copy_(fresh["dict"])
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        eager = run(fresh, wl, fi, fv, kernel)
+        assert torch.equal(out, eager), f"replay {rep}"

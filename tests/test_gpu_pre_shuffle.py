@@ -139,3 +139,29 @@ def test_random_shapes_in_the_pre_shuffle_layout():
         assert torch.equal(got, planar), f"{wl} kept {kept}: the two layouts must give the same bits"
         forms += 1
     assert forms >= 40, forms
+
+
+@pytest.mark.parametrize("scale", [2, 3, 4])
+def test_pre_shuffle_call_replays_inside_a_captured_graph(scale):
+    """The pre-shuffle forms, like the planar one, are one kernel with no allocation: three replays of a captured
+    call with new inputs copied into the captured buffers, each compared with an eager call."""
+    wl = sr_synth.Workload("psg", 65, 1, 3, 24, 64, scale, 72, 5, "f16", "f32", 0.0, 1.5)
+    first = sr_synth.make_inputs(wl, DEV)
+    lr, pre, D = first["lr"].clone(), sr_synth.to_pre_shuffle(first["coeff"], scale).clone(), first["dict"].clone()
+    out = torch.zeros((wl.n, wl.c, wl.H, wl.W), device=DEV)
+    opts = sr.make_options(MFMA, 0, sr.SR_COEFF_PRE_SHUFFLE)
+    call = lambda: sr.sr_dict_assemble_ex(lr, pre, D, wl.L, wl.k, wl.scale, wl.c, out, opts=opts)
+    call()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for rep in range(3):
+        fresh = sr_synth.make_inputs(sr_synth.scaled(wl, index=wl.index + 1 + rep), DEV)
+        fp = sr_synth.to_pre_shuffle(fresh["coeff"], scale)
+        lr.copy_(fresh["lr"]); pre.copy_(fp); D.copy_(fresh["dict"])
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        eager = run(fresh, wl, fp, MFMA, sr.SR_COEFF_PRE_SHUFFLE)
+        assert torch.equal(out, eager), f"replay {rep}"
