@@ -175,7 +175,9 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
  * indices exist only where alternative shapes are built - k = 5, C = 3, 65 to 72 folded f16
  * atoms, byte offsets: 1 = 64x8, 2 = 128x4, 3 = 64x16, 4 = 128x8, 5 = 64x32, 6 = 128x16,
  * 7 = 128x24 (scale 4 only) HR pixels per workgroup, i.e. 1, 1, 2, 2, 4, 4, 6 row groups per
- * wavefront - and are an option of the matrix-core kernel: with SR_KERNEL_AUTO or
+ * wavefront of a four-wavefront workgroup, two workgroups per CU; 8 = 128x16 as one workgroup of
+ * eight wavefronts per CU; 9 = 128x16 as two workgroups of two wavefronts, one wavefront per SIMD
+ * (see sr_dict_assemble_launch_shape) - and are an option of the matrix-core kernel: with SR_KERNEL_AUTO or
  * SR_KERNEL_MFMA an index the case does not have is SR_ERR_UNSUPPORTED, never a silent
  * fall-back, so a sweep over the indices times each accepted one as a different kernel.
  */
@@ -239,6 +241,16 @@ int sr_dict_assemble_tile(const sr_tensor* lr, const sr_tensor* coeff, const sr_
                           const sr_tensor* out,
                           const int* kept, int n_kept, const sr_options* opts,
                           int* tile_w, int* tile_h);
+
+/* The whole launch shape an index stands for (section III-B: the paper searches block size and
+ * occupancy together, Eq. 11-12): shape[0] x shape[1] = the tile as above, shape[2] = wavefronts per
+ * workgroup, shape[3] = workgroups resident per CU; zeros where the library does not report it.
+ * Two indices never name the same four numbers.  Host only. */
+int sr_dict_assemble_launch_shape(const sr_tensor* lr, const sr_tensor* coeff, const sr_tensor* dict,
+                                  int L, int k, int scale, int channels,
+                                  const sr_tensor* out,
+                                  const int* kept, int n_kept, const sr_options* opts,
+                                  int shape[4]);
 
 /* Static, NUL-terminated description of a status code. */
 const char* sr_strerror(int status);

@@ -19,7 +19,7 @@ SR_COEFF_PLANAR, SR_COEFF_PRE_SHUFFLE = 0, 1
 SR_MAX_ATOMS = 256
 
 EXPORTS = ("sr_dict_assemble", "sr_dict_assemble_selective", "sr_dict_assemble_ex", "sr_dict_assemble_list", "sr_dict_assemble_list_ex",
-           "sr_bicubic_upsample", "sr_dict_assemble_plan", "sr_dict_assemble_tile", "sr_strerror", "sr_version",
+           "sr_bicubic_upsample", "sr_dict_assemble_plan", "sr_dict_assemble_tile", "sr_dict_assemble_launch_shape", "sr_strerror", "sr_version",
            "sr_probe_read", "sr_probe_mix", "sr_probe_stream", "sr_probe_pattern", "sr_probe_policy", "sr_probe_policy_bits",
            "sr_atom_gram_workspace_bytes", "sr_atom_gram", "sr_atom_gram_static", "sr_select_atoms")
 
@@ -63,6 +63,8 @@ def load():
     lib.sr_dict_assemble_list_ex.argtypes = [T, T, T, T, i, i, i, i, i, T, vp, i]
     lib.sr_dict_assemble_plan.argtypes = [T, T, T, i, i, i, i, T, ip, i, O]
     lib.sr_dict_assemble_tile.argtypes = [T, T, T, i, i, i, i, T, ip, i, O, ip, ip]
+    lib.sr_dict_assemble_launch_shape.argtypes = [T, T, T, i, i, i, i, T, ip, i, O, ip]
+    lib.sr_dict_assemble_launch_shape.restype = i
     lib.sr_bicubic_upsample.argtypes = [T, i, i, T, vp]
     lib.sr_strerror.argtypes = [i]
     lib.sr_probe_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
@@ -210,6 +212,17 @@ def sr_dict_assemble_tile(lr, coeff, dict, L, k, scale, channels, out, kept=None
     tw, th = ctypes.c_int(0), ctypes.c_int(0)
     st = load().sr_dict_assemble_tile(a, b, c, L, k, scale, channels, o, ka, n, op, ctypes.byref(tw), ctypes.byref(th))
     return st, tw.value, th.value
+
+
+def sr_dict_assemble_launch_shape(lr, coeff, dict, L, k, scale, channels, out, kept=None, n_kept=None, opts=None):
+    """(kernel or negative status, (tile width, tile height, wavefronts per workgroup, workgroups per CU))."""
+    a, b, c, o = describe(lr), describe(coeff), describe(_dict4(dict)), describe(out)
+    ka, n, _ga, _keep = _host_lists(kept, None)
+    n = n if n_kept is None else int(n_kept)
+    op = ctypes.byref(opts) if opts is not None else None
+    shape = (ctypes.c_int * 4)()
+    st = load().sr_dict_assemble_launch_shape(a, b, c, L, k, scale, channels, o, ka, n, op, shape)
+    return st, tuple(shape)
 
 
 def sr_bicubic_upsample(lr, scale, channels, out, stream=None):

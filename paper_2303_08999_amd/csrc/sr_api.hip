@@ -165,6 +165,19 @@ __attribute__((visibility("default"))) int sr_dict_assemble_tile(const sr_tensor
     return p.kernel;
 }
 
+__attribute__((visibility("default"))) int sr_dict_assemble_launch_shape(const sr_tensor* lr, const sr_tensor* coeff, const sr_tensor* dict,
+                          int L, int k, int scale, int channels, const sr_tensor* out,
+                          const int* kept, int n_kept, const sr_options* opts, int shape[4]) {
+    if (!shape) return SR_ERR_NULL;
+    Plan p;
+    make_plan(p, lr, coeff, dict, L, k, scale, channels, out, kept, n_kept, nullptr, opts);
+    if (p.status != SR_OK) return p.status;
+    shape[0] = shape[1] = shape[2] = shape[3] = 0;
+    if (p.kernel == SR_KERNEL_MFMA && !p.empty)
+        mfma_tile_shape(p.args, k, coeff->dtype, p.tile, &shape[0], &shape[1], &shape[2], &shape[3]);
+    return p.kernel;
+}
+
 __attribute__((visibility("default"))) int sr_bicubic_upsample(const sr_tensor* lr, int scale, int channels, sr_tensor* out, void* stream) {
     if (!lr || !out) return SR_ERR_NULL;
     if (!dtype_ok(lr->dtype) || !dtype_ok(out->dtype)) return SR_ERR_UNSUPPORTED;

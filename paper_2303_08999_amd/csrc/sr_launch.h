@@ -14,6 +14,7 @@ hipError_t launch_mfma(const AssembleArgs& a, int k, bool io_f16, int tile, hipS
 // Per-pixel list form (sr_dict_assemble_list) on the matrix cores: a.coeff = values, a.index, a.T set; kept = identity.
 bool mfma_list_supported(const AssembleArgs& a, int k, bool value_f16);
 hipError_t launch_mfma_list(const AssembleArgs& a, hipStream_t st);
-bool mfma_tile_shape(const AssembleArgs& a, int k, int coeff_dtype, int tile, int* tw, int* th);
+bool mfma_tile_shape(const AssembleArgs& a, int k, int coeff_dtype, int tile, int* tw, int* th, int* waves = nullptr,
+                     int* groups = nullptr);
 
 }  // namespace srd

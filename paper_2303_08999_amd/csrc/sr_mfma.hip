@@ -7,7 +7,7 @@ namespace srd {
 
 hipError_t launch_mfma_k3(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_k5(const AssembleArgs& a, int np8, int shape, hipStream_t st);
-bool tile_shape_k5(const AssembleArgs& a, int shape, int* tw, int* th);
+bool tile_shape_k5(const AssembleArgs& a, int shape, int* tw, int* th, int* waves, int* groups);
 hipError_t launch_mfma_k7(const AssembleArgs& a, int np8, int shape, hipStream_t st);
 hipError_t launch_mfma_k5_f32(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_k7_f32(const AssembleArgs& a, int np8, hipStream_t st);
@@ -74,9 +74,9 @@ static bool has_tile_shapes(const AssembleArgs& a, int k, int np8, int coeff_dty
 
 // Tile of the instantiation that serves the call, where the library can say (the family with
 // alternative shapes); false elsewhere.
-bool mfma_tile_shape(const AssembleArgs& a, int k, int coeff_dtype, int tile, int* tw, int* th) {
+bool mfma_tile_shape(const AssembleArgs& a, int k, int coeff_dtype, int tile, int* tw, int* th, int* waves, int* groups) {
     const int np8 = np8_for(k, a.C, a.n_fold, coeff_dtype);
-    return has_tile_shapes(a, k, np8, coeff_dtype) && tile_shape_k5(a, tile, tw, th);
+    return has_tile_shapes(a, k, np8, coeff_dtype) && tile_shape_k5(a, tile, tw, th, waves, groups);
 }
 
 // pixels a lane loads with one vector load (its pixel group)
@@ -113,7 +113,7 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
     if (tile < 0) return false;
     if (tile != 0) {
         int tw, th;
-        if (!has_tile_shapes(a, k, np8, coeff_dtype) || !tile_shape_k5(a, tile, &tw, &th)) return false;
+        if (!has_tile_shapes(a, k, np8, coeff_dtype) || !tile_shape_k5(a, tile, &tw, &th, nullptr, nullptr)) return false;
     }
     return true;
 }

@@ -3,28 +3,36 @@
 
 namespace srd {
 
-// Tile shapes of the family with alternatives (three channels, 65 to 72 fp16 atoms), by index
-// 1 .. 7: width x height in HR pixels.  Index 7 holds half the LR footprint in LDS and runs at
-// scale 4 only.
-static const int kShapeW[8] = {0, 64, 128, 64, 128, 64, 128, 128};
-static const int kShapeH[8] = {0, 8, 4, 16, 8, 32, 16, 24};
+// Launch shapes of the family with alternatives (three channels, 65 to 72 fp16 atoms), by index
+// 1 .. 9: tile width x height in HR pixels, wavefronts per workgroup, workgroups resident per CU.
+// Index 7 holds half the LR footprint in LDS and runs at scale 4 only.  Indices 8 and 9 are the
+// 128 x 16 tile of index 6 in other arrangements: one workgroup of eight wavefronts per CU (two
+// units per wavefront), and two workgroups of two wavefronts (eight units each, one wavefront
+// per SIMD with the whole register file).
+static const int kShapes = 9;
+static const int kShapeW[kShapes + 1] = {0, 64, 128, 64, 128, 64, 128, 128, 128, 128};
+static const int kShapeH[kShapes + 1] = {0, 8, 4, 16, 8, 32, 16, 24, 16, 16};
+static const int kShapeWaves[kShapes + 1] = {0, 4, 4, 4, 4, 4, 4, 4, 8, 2};
+static const int kShapeGroups[kShapes + 1] = {0, 2, 2, 2, 2, 2, 2, 2, 1, 2};
 
 // Index 0 = the default for the frame (measured, 0.26 to 8.3 Mpixel frames at every scale):
 // small frames take 128 x 4 tiles, which put more CUs to work (512 x 512: 37 -> 26 us); at x4
 // half the footprint in LDS leaves room for 128 x 24, but up to about 1080p its few hundred tiles
 // fill the second round of the grid badly and 64 x 16 is 7-13 % faster; else 128 x 16.
 int resolve_shape_k5(const AssembleArgs& a, int shape) {
-    if (shape != 0) return (shape >= 1 && shape <= 7 && (shape != 7 || a.s == 4)) ? shape : -1;
+    if (shape != 0) return (shape >= 1 && shape <= kShapes && (shape != 7 || a.s == 4)) ? shape : -1;
     const long long px = (long long)a.N * a.H * a.W;
     if (px <= 400000) return 2;
     if (a.s == 4) return px <= 2600000 ? 3 : 7;
     return 6;
 }
-bool tile_shape_k5(const AssembleArgs& a, int shape, int* tw, int* th) {
+bool tile_shape_k5(const AssembleArgs& a, int shape, int* tw, int* th, int* waves, int* groups) {
     const int r = resolve_shape_k5(a, shape);
     if (r < 1) return false;
     *tw = kShapeW[r];
     *th = kShapeH[r];
+    if (waves) *waves = kShapeWaves[r];
+    if (groups) *groups = kShapeGroups[r];
     return true;
 }
 
@@ -57,6 +65,8 @@ hipError_t launch_mfma_k5(const AssembleArgs& a, int np8, int shape, hipStream_t
             case 5:  return launch_one<5, 3, 9, 4, 2, 4, 4, 2>(a, st);    //  64 x 32, 4 units
             case 6:  return launch_one<5, 3, 9, 4, 1, 4, 4, 2>(a, st);    // 128 x 16, 4 units
             case 7:  return launch_one<5, 3, 9, 4, 1, 4, 6, 2, CT_F16, 4>(a, st);   // 128 x 24, 6 units (x4 only)
+            case 8:  return launch_one<5, 3, 9, 4, 1, 8, 2, 2>(a, st);    // 128 x 16, eight wavefronts, 2 units
+            case 9:  return launch_one<5, 3, 9, 4, 1, 2, 8, 1>(a, st);    // 128 x 16, two wavefronts, 8 units, one per SIMD
             default: return hipErrorInvalidValue;
             }
         case 16:                                                         // 73 to 128 atoms: two pixels per lane, as 7x7

@@ -13,7 +13,7 @@ from . import binding as _b
 
 
 def sweep_tiles(lr, coeff, dict, L, k, scale, channels, out, kept=None, gamma=None,
-                reps: int = 5, max_tiles: int = 8):
+                reps: int = 5, max_tiles: int = 10):
     """Time every tile shape of the matrix-core kernel for these arguments.
 
     Returns a list of (tile index, median milliseconds); empty if the

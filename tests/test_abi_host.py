@@ -144,15 +144,24 @@ def test_tile_indices_name_distinct_instantiations_or_are_refused(lib):
             t.data = 0x1000000000 * (i + 1)
         return ts
     shapes = {}
-    for tile in range(0, 10):
+    launch = {}
+    for tile in range(0, 12):
         st, tw, th = tile_of(*far(h=540, w=960), opts=sr.make_options(MF, tile))
-        if tile <= 7:
+        ts = far(h=540, w=960)
+        shape4 = (ctypes.c_int * 4)()
+        st2 = lib.sr_dict_assemble_launch_shape(*ts[:3], 72, 5, 4, 3, ts[3], None, 0, ctypes.byref(sr.make_options(MF, tile)), shape4)
+        if tile <= 9:
             assert st == MF and tw > 0 and th > 0, (tile, st)
             shapes[tile] = (tw, th)
+            assert st2 == MF and tuple(shape4)[:2] == (tw, th) and shape4[2] in (2, 4, 8) and shape4[3] in (1, 2)
+            launch[tile] = tuple(shape4)
         else:
-            assert st == -3
+            assert st == -3 and st2 == -3
     assert len({shapes[t] for t in range(1, 8)}) == 7                      # seven different tiles
     assert shapes[0] == shapes[7] == (128, 24)                              # the 4K frame's default
+    assert len({launch[t] for t in range(1, 10)}) == 9                     # nine different launch shapes
+    assert launch[6] == (128, 16, 4, 2) and launch[8] == (128, 16, 8, 1) and launch[9] == (128, 16, 2, 2)
+    assert lib.sr_dict_assemble_launch_shape(*far(h=540, w=960)[:3], 72, 5, 4, 3, far(h=540, w=960)[3], None, 0, None, None) == -1
     assert tile_of(*far(h=64, w=64), opts=sr.make_options(MF, 0))[1:] == (128, 4)       # small frame
     assert tile_of(*far(h=270, w=480), opts=sr.make_options(MF, 0))[1:] == (64, 16)     # 1080p at x4
     assert tile_of(*far(h=360, w=640, s=3), s=3, opts=sr.make_options(MF, 0))[1:] == (128, 16)

@@ -288,7 +288,7 @@ def test_4k_selective_full_frame(oracle):
     assert np.abs(dense[:, :, :8] - ref[:, :, :8]).max() > 1e-2
 
 
-@pytest.mark.parametrize("tile", range(8))
+@pytest.mark.parametrize("tile", range(10))
 @pytest.mark.parametrize("shape", [(50, 72, 4), (37, 40, 3), (61, 100, 2)])
 def test_every_tile_shape_of_the_matrix_core_kernel(oracle, tile, shape):
     """All built tile shapes (a tuning option) on images that leave ragged tails
@@ -672,18 +672,18 @@ def test_tile_sweep_returns_a_valid_shape():
     inp = sr_synth.make_inputs(wl, DEV)
     out = torch.empty((wl.n, wl.c, wl.H, wl.W), device=DEV)
     res = tune.sweep_tiles(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, out, reps=3)
-    assert [t for t, _ in res] == list(range(8))
+    assert [t for t, _ in res] == list(range(10))
     assert all(ms > 0 for _, ms in res)
-    assert tune.best_tile(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, out, reps=3) in range(8)
-    # every swept index is another instantiation (index 0 is the default: one of the seven)
-    tiles = [sr.sr_dict_assemble_tile(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, out,
-                                      opts=sr.make_options(MFMA, t))[1:] for t, _ in res]
-    assert len(set(tiles[1:])) == 7 and tiles[0] in tiles[1:]
+    assert tune.best_tile(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, out, reps=3) in range(10)
+    # every swept index is another launch shape (index 0 is the default: one of the nine)
+    tiles = [sr.sr_dict_assemble_launch_shape(inp["lr"], inp["coeff"], inp["dict"], wl.L, wl.k, wl.scale, wl.c, out,
+                                              opts=sr.make_options(MFMA, t))[1] for t, _ in res]
+    assert len(set(tiles[1:])) == 9 and tiles[0] in tiles[1:]
     # at scale 3 the 128 x 24 tile does not exist, and a family with one built shape sweeps index 0 only
     wl3 = sr_synth.scaled(wl, scale=3)
     i3 = sr_synth.make_inputs(wl3, DEV)
     o3 = torch.empty((wl3.n, wl3.c, wl3.H, wl3.W), device=DEV)
-    assert [t for t, _ in tune.sweep_tiles(i3["lr"], i3["coeff"], i3["dict"], wl3.L, wl3.k, wl3.scale, wl3.c, o3, reps=1)] == list(range(7))
+    assert [t for t, _ in tune.sweep_tiles(i3["lr"], i3["coeff"], i3["dict"], wl3.L, wl3.k, wl3.scale, wl3.c, o3, reps=1)] == [0, 1, 2, 3, 4, 5, 6, 8, 9]
     wl8 = sr_synth.scaled(wl, coeff_dtype="f8")
     i8 = sr_synth.make_inputs(wl8, DEV)
     assert [t for t, _ in tune.sweep_tiles(i8["lr"], i8["coeff"], i8["dict"], wl8.L, wl8.k, wl8.scale, wl8.c, out, reps=1)] == [0]
