@@ -25,6 +25,7 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <algorithm>
 #include <mutex>
 #include <vector>
 
@@ -706,65 +707,119 @@ __global__ __launch_bounds__(NT) void k_gram_reduce(const double* __restrict__ w
 size_t tensor_elems(const sr_tensor* t) { return (size_t)t->n * t->c * t->h * t->w; }
 
 // ---------------------------------------------------------------------------
-// Host side of Alg. 1
+// Host side of Alg. 1 (section III-A).
+//
+// The atoms keep their numbers throughout: what a round removes is a flag, and the
+// rescaling of the kept atoms' coefficients by the regression scales (Eq. 9; the
+// stand-in for fine-tuning the network between rounds) is a per-atom factor that
+// multiplies the normal equations where they are read, G'_ij = c_i c_j G_ij and
+// b'_i = c_i b_i.  Nothing is copied or rewritten between rounds.
 // ---------------------------------------------------------------------------
-typedef std::vector<double> vec;
+struct SelectionProblem {
+    const double* G;            // L x L, row-major
+    const double* b;            // L
+    int L;
+    double M;                   // samples behind the normal equations
+    std::vector<double> scale;  // c_i
+    std::vector<char> alive;    // atoms still in the dictionary
 
-// argmin (1/M)|h - R beta|^2 + lam |beta|_1 by cyclic coordinate descent on the
-// normal equations (G: n x n row-major).  beta holds the start and the result.
-void lasso_cd(const vec& G, const vec& b, int n, double M, double lam, vec& beta) {
-    const double thr = 0.5 * lam * M, tol = 1e-13;
-    for (int sweep = 0; sweep < 100000; ++sweep) {
-        double dmax = 0.0, bmax = 0.0;
-        for (int j = 0; j < n; ++j) {
-            const double gjj = G[(size_t)j * n + j];
-            double nw = 0.0;
+    double g(int i, int j) const { return scale[i] * scale[j] * G[(size_t)i * L + j]; }
+    double rhs(int i) const { return scale[i] * b[i]; }
+};
+
+// Minimiser of (1/M) |h - R w|^2 + lambda |w|_1 over the living atoms (Eq. 7), from the normal
+// equations.  Coordinate descent in the "covariance" form: the correlations of the residual with every
+// atom, corr_i = b'_i - sum_j G'_ij w_j, are kept up to date, so that a coordinate costs O(1) to
+// examine and O(L) only when it moves.  Passes alternate between all living atoms and the current
+// support, as long as a pass over all of them still moves something.  `w` is the starting point (any;
+// the problem is convex) and receives the result; coordinates at zero are exact zeros.
+class LassoSolver {
+public:
+    explicit LassoSolver(const SelectionProblem& p) : p_(p), corr_(p.L) {}
+
+    int solve(double lambda, std::vector<double>& w) {
+        const double threshold = 0.5 * lambda * p_.M;
+        members_.clear();
+        for (int i = 0; i < p_.L; ++i) {
+            if (p_.alive[i]) members_.push_back(i);
+            else w[i] = 0.0;
+        }
+        for (int i : members_) {
+            double c = p_.rhs(i);
+            for (int j : members_) c -= p_.g(i, j) * w[j];
+            corr_[i] = c;
+        }
+        for (int round = 0; round < 100000; ++round) {
+            if (!pass(members_, threshold, w)) break;          // nothing moved anywhere: the optimum
+            support_.clear();
+            for (int i : members_)
+                if (w[i] != 0.0) support_.push_back(i);
+            for (int inner = 0; inner < 100000 && pass(support_, threshold, w); ++inner) {}
+        }
+        int nonzero = 0;
+        for (int i : members_) nonzero += w[i] != 0.0;
+        return nonzero;
+    }
+
+private:
+    // one pass over `which`; true if some weight moved by more than the tolerance
+    bool pass(const std::vector<int>& which, double threshold, std::vector<double>& w) {
+        double moved = 0.0, largest = 1.0;
+        for (int j : which) {
+            const double gjj = p_.g(j, j);
+            double target = 0.0;
             if (gjj > 0.0) {
-                double dot = 0.0;
-                for (int k = 0; k < n; ++k) dot += G[(size_t)j * n + k] * beta[k];
-                const double rho = b[j] - (dot - gjj * beta[j]);
-                nw = (rho > thr ? rho - thr : (rho < -thr ? rho + thr : 0.0)) / gjj;
+                const double z = corr_[j] + gjj * w[j];            // correlation with atom j left out
+                if (z > threshold) target = (z - threshold) / gjj;
+                else if (z < -threshold) target = (z + threshold) / gjj;
             }
-            dmax = fmax(dmax, fabs(nw - beta[j]));
-            beta[j] = nw;
+            const double step = target - w[j];
+            if (step != 0.0) {
+                for (int i : members_) corr_[i] -= p_.g(i, j) * step;
+                w[j] = target;
+                moved = fmax(moved, fabs(step));
+            }
+            largest = fmax(largest, fabs(target));
         }
-        for (int j = 0; j < n; ++j) bmax = fmax(bmax, fabs(beta[j]));
-        if (dmax <= tol * fmax(1.0, bmax)) break;
+        return moved > 1e-13 * largest;
     }
-}
 
-int count_nonzero(const vec& v) {
-    int c = 0;
-    for (double x : v) c += x != 0.0;
-    return c;
-}
+    const SelectionProblem& p_;
+    std::vector<double> corr_;
+    std::vector<int> members_, support_;
+};
 
-// Solves A x = y (n x n, row-major) by Gaussian elimination with partial pivoting;
-// a vanishing pivot leaves that unknown at zero.
-vec solve_dense(vec A, vec y, int n) {
-    std::vector<int> piv_col;
-    for (int col = 0; col < n; ++col) {
-        int p = col;
-        for (int r = col + 1; r < n; ++r)
-            if (fabs(A[(size_t)r * n + col]) > fabs(A[(size_t)p * n + col])) p = r;
-        if (fabs(A[(size_t)p * n + col]) < 1e-300) continue;
-        if (p != col) {
-            for (int k = 0; k < n; ++k) { const double t = A[(size_t)p * n + k]; A[(size_t)p * n + k] = A[(size_t)col * n + k]; A[(size_t)col * n + k] = t; }
-            const double t = y[p]; y[p] = y[col]; y[col] = t;
-        }
-        for (int r = col + 1; r < n; ++r) {
-            const double f = A[(size_t)r * n + col] / A[(size_t)col * n + col];
-            if (f == 0.0) continue;
-            for (int k = col; k < n; ++k) A[(size_t)r * n + k] -= f * A[(size_t)col * n + k];
-            y[r] -= f * y[col];
+// Regression scales of the atoms in `set` (Eq. 9): the least-squares fit of the target by their
+// responses, G'_SS x = b'_S.  Cholesky factorisation; a pivot that vanishes (responses that are
+// linearly dependent on earlier ones) leaves that atom's scale at zero.
+std::vector<double> regression_scales(const SelectionProblem& p, const std::vector<int>& set) {
+    const int m = (int)set.size();
+    std::vector<double> C((size_t)m * m, 0.0), x(m, 0.0);
+    std::vector<char> dropped(m, 0);
+    for (int i = 0; i < m; ++i) {
+        for (int j = 0; j <= i; ++j) {
+            double v = p.g(set[i], set[j]);
+            for (int k = 0; k < j; ++k) v -= C[(size_t)i * m + k] * C[(size_t)j * m + k];
+            if (i == j) {
+                const double floor = 1e-13 * p.g(set[i], set[i]);
+                if (v > floor && v > 0.0) C[(size_t)i * m + i] = sqrt(v);
+                else dropped[i] = 1;
+            } else {
+                C[(size_t)i * m + j] = dropped[j] ? 0.0 : v / C[(size_t)j * m + j];
+            }
         }
     }
-    vec x(n, 0.0);
-    for (int r = n - 1; r >= 0; --r) {
-        double s = y[r];
-        for (int k = r + 1; k < n; ++k) s -= A[(size_t)r * n + k] * x[k];
-        const double d = A[(size_t)r * n + r];
-        x[r] = fabs(d) < 1e-300 ? 0.0 : s / d;
+    for (int i = 0; i < m; ++i) {                     // forward: C y = b'
+        if (dropped[i]) continue;
+        double v = p.rhs(set[i]);
+        for (int k = 0; k < i; ++k) v -= C[(size_t)i * m + k] * x[k];
+        x[i] = v / C[(size_t)i * m + i];
+    }
+    for (int i = m - 1; i >= 0; --i) {                // backward: C^T x = y
+        if (dropped[i]) { x[i] = 0.0; continue; }
+        double v = x[i];
+        for (int k = i + 1; k < m; ++k) v -= C[(size_t)k * m + i] * x[k];
+        x[i] = v / C[(size_t)i * m + i];
     }
     return x;
 }
@@ -922,68 +977,65 @@ int sr_select_atoms(const double* normal, int L, double alpha, double delta_alph
     if (!normal || !kept || !n_kept || !gamma) return SR_ERR_NULL;
     if (L < 1 || L > SR_SELECT_MAX_ATOMS || !(alpha > 0.0) || alpha > 1.0 || !(delta_alpha > 0.0) ||
         !(lambda0 > 0.0) || !(eps >= 0.0)) return SR_ERR_UNSUPPORTED;
-    vec G(normal, normal + (size_t)L * L), b(normal + (size_t)L * L, normal + (size_t)L * L + L);
-    const double M = normal[(size_t)L * L + L + 1];
-    if (!(M > 0.0)) return SR_ERR_UNSUPPORTED;
-    std::vector<int> active(L);
-    for (int i = 0; i < L; ++i) active[i] = i;
-    vec gamma_tot(L, 1.0);
-    double alpha_t = 1.0, lam = lambda0;
-    while (alpha_t > alpha + 1e-12 && !active.empty()) {
-        alpha_t = fmax(alpha, alpha_t - delta_alpha);
-        const double want = alpha_t * L;
-        const int n = (int)active.size();
-        vec Ga((size_t)n * n), ba(n);
-        for (int i = 0; i < n; ++i) {
-            ba[i] = b[active[i]];
-            for (int j = 0; j < n; ++j) Ga[(size_t)i * n + j] = G[(size_t)active[i] * L + active[j]];
-        }
-        auto solve = [&](double lm, vec& bt) {
-            bt.assign(n, 1.0);
-            lasso_cd(Ga, ba, n, M, lm, bt);
-            return count_nonzero(bt);
+    SelectionProblem prob;
+    prob.G = normal;
+    prob.b = normal + (size_t)L * L;
+    prob.L = L;
+    prob.M = normal[(size_t)L * L + L + 1];
+    if (!(prob.M > 0.0)) return SR_ERR_UNSUPPORTED;
+    prob.scale.assign(L, 1.0);
+    prob.alive.assign(L, 1);
+    LassoSolver lasso(prob);
+    int living = L;
+    double lam = lambda0, fraction = 1.0;
+    std::vector<double> w(L), trial(L);
+    // Alg. 1: the kept fraction comes down in steps of delta_alpha; each step finds, by doubling and then
+    // bisection, a lambda whose LASSO solution keeps no more atoms than the step allows, removes the atoms
+    // at zero, and refits the scales of the others.
+    while (fraction > alpha + 1e-12 && living > 0) {
+        fraction = fmax(alpha, fraction - delta_alpha);
+        const double allowed = fraction * L;
+        // every solve starts from all weights at one: the dictionary as it stands, nothing selected yet
+        auto support_at = [&](double lambda, std::vector<double>& weights) {
+            std::fill(weights.begin(), weights.end(), 1.0);
+            return lasso.solve(lambda, weights);
         };
-        // lambda doubles until few enough atoms survive
-        double lam_lo = 0.5 * lam, lam_hi = lam;
-        vec beta;
-        int cnt = solve(lam_hi, beta);
-        while (cnt > want) {
-            lam_lo = lam_hi;
-            lam_hi *= 2.0;
-            cnt = solve(lam_hi, beta);
+        double too_many = 0.5 * lam, few_enough = lam;         // the bracket on lambda
+        int count = support_at(few_enough, w);
+        while (count > allowed) {
+            too_many = few_enough;
+            few_enough *= 2.0;
+            count = support_at(few_enough, w);
         }
-        // bisection towards the target count, keeping a solution that meets it
-        for (int it = 0; it < 60 && fabs(want - cnt) > eps * L && want - cnt >= 1.0; ++it) {
-            const double mid = 0.5 * (lam_lo + lam_hi);
-            vec bm;
-            const int cm = solve(mid, bm);
-            if (cm > want) lam_lo = mid;
-            else { lam_hi = mid; beta = bm; cnt = cm; }
+        // the count may have dropped further than asked: look between the two for a lambda that keeps more,
+        // but still few enough
+        for (int halvings = 0; halvings < 60; ++halvings) {
+            if (allowed - count < 1.0 || fabs(allowed - count) <= eps * L) break;
+            const double middle = 0.5 * (too_many + few_enough);
+            const int c = support_at(middle, trial);
+            if (c > allowed) {
+                too_many = middle;
+            } else {
+                few_enough = middle;
+                count = c;
+                w.swap(trial);
+            }
         }
-        lam = lam_hi;
-        std::vector<int> keep;
-        for (int i = 0; i < n; ++i)
-            if (beta[i] != 0.0) keep.push_back(i);
-        if (keep.empty()) { active.clear(); break; }
-        // regression scales of the kept atoms (Eq. 9): G_SS gamma = b_S
-        const int m = (int)keep.size();
-        vec Gs((size_t)m * m), bs(m);
-        for (int i = 0; i < m; ++i) {
-            bs[i] = ba[keep[i]];
-            for (int j = 0; j < m; ++j) Gs[(size_t)i * m + j] = Ga[(size_t)keep[i] * n + keep[j]];
+        lam = few_enough;
+        std::vector<int> survivors;
+        for (int i = 0; i < L; ++i) {
+            if (prob.alive[i] && w[i] != 0.0) survivors.push_back(i);
+            else prob.alive[i] = 0;
         }
-        const vec gam = solve_dense(Gs, bs, m);
-        std::vector<int> S(m);
-        for (int i = 0; i < m; ++i) { S[i] = active[keep[i]]; gamma_tot[S[i]] *= gam[i]; }
-        // the kept atoms' coefficients are rescaled by gamma from here on
-        for (int i = 0; i < m; ++i) {
-            b[S[i]] *= gam[i];
-            for (int j = 0; j < m; ++j) G[(size_t)S[i] * L + S[j]] *= gam[i] * gam[j];
-        }
-        active = S;
+        living = (int)survivors.size();
+        if (living == 0) break;
+        const std::vector<double> fit = regression_scales(prob, survivors);
+        for (int i = 0; i < living; ++i) prob.scale[survivors[i]] *= fit[i];
     }
-    *n_kept = (int)active.size();
-    for (size_t i = 0; i < active.size(); ++i) { kept[i] = active[i]; gamma[i] = (float)gamma_tot[active[i]]; }
+    int n = 0;
+    for (int i = 0; i < L; ++i)
+        if (prob.alive[i] && living > 0) { kept[n] = i; gamma[n] = (float)prob.scale[i]; ++n; }
+    *n_kept = n;
     if (lambda_out) *lambda_out = lam;
     return SR_OK;
 }
