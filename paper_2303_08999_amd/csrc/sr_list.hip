@@ -4,13 +4,13 @@
 // loaded (section II-A, Eq. 4): 3 T bytes per pixel instead of 2 L.  Computed is Eq. 2 with the
 // listed terms only, F_i = sum_t value[t][i] D[index[t][i]], then y_i = F_i B_i^T as everywhere.
 //
-// A thread owns four consecutive pixels of a row (one 4-byte load of indices and one 8- or
-// 16-byte load of values per entry); the dictionary sits in LDS with rows padded to whole
-// 16-byte groups and every entry gathers its atom's row from there; stage 1 and stage 4 are
-// the generic kernel's (sr_generic.hip), on a 256 x 4 tile.  Bound: the LDS gathers
-// (T * k^2 * 4 bytes per pixel), not HBM.  This kernel takes every supported case; 5x5 atoms, three
-// channels and fp16 values go to the matrix-core kernel instead (CT_LIST8, CT_LIST16 in sr_mfma_kernel.h), which
-// scatters the lists into dense 16-atom operands and is several times faster.
+// A thread owns four consecutive pixels of a row and reads, per entry, their four indices and
+// four values; the dictionary sits in LDS with rows padded to whole 16-byte groups and every
+// entry gathers its atom's row from there; stage 1 and stage 4 are the generic kernel's
+// (sr_generic.hip), on a 256 x 4 tile.  Bound: the LDS gathers (T * k^2 * 4 bytes per pixel),
+// not HBM.  This kernel takes every supported case; 5x5 atoms, three channels and fp16 values
+// go to the matrix-core kernel instead (CT_LIST8, CT_LIST16 in sr_mfma_kernel.h), which scatters
+// the lists into the dense form's operands and is more than twice as fast.
 #include <stdint.h>
 
 #include <string.h>
