@@ -332,6 +332,9 @@ def main():
     ap.add_argument("--probe-study", action="store_true",
                     help="instead of the kernel, time the library's streaming probes on the 4K frame's byte mix "
                          "and print them as one JSON line")
+    ap.add_argument("--tile-sweep", action="store_true",
+                    help="also time every launch shape (tile, workgroup size, residency) the library has for this "
+                         "workload: the measured stand-in for the paper's launch-shape search (section III-B)")
     ap.add_argument("--table1-sweep", action="store_true",
                     help="instead of the kernel, time kept lists of 72 ... 8 atoms at the paper's Table I input sizes "
                          "and scales (the analogue of its Fig. 7) and print them as one JSON line")
@@ -489,6 +492,16 @@ def main():
         result["list_form"] = list_leg(sr, torch, sr_synth, wl, inp, coeffs[:2], args.list_entries)
     if args.bicubic:
         result["bicubic"] = bicubic_leg(sr, torch, wl, inp)
+    if args.tile_sweep and not args.pre_shuffle:
+        # the launch-shape search (section III-B, Eq. 11-12): every shape the library has for this case, timed
+        from paper_2303_08999_amd import tune
+        rows = []
+        for t, ms in tune.sweep_tiles(inp["lr"], coeffs[0], inp["dict"], wl.L, wl.k, wl.scale, wl.c, outs[0], kept=kept, reps=15):
+            shape = sr.sr_dict_assemble_launch_shape(inp["lr"], coeffs[0], inp["dict"], wl.L, wl.k, wl.scale, wl.c, outs[0],
+                                                     kept=kept, opts=sr.make_options(sr.SR_KERNEL_MFMA, t))[1]
+            rows.append({"index": t, "tile": f"{shape[0]}x{shape[1]}", "wavefronts_per_workgroup": shape[2],
+                         "workgroups_per_cu": shape[3], "median_us_single_launch": round(ms * 1e3, 1)})
+        result["tile_sweep"] = rows
     if not args.no_cpu and not args.pre_shuffle:      # the oracle leg is timed on the planar layout only
         result["cpu_baseline"] = cpu_baseline(wl, inp["lr"], coeffs[0], inp["dict"], args.cpu_budget)
     print(json.dumps(result))

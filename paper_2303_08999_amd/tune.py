@@ -14,7 +14,7 @@ from . import binding as _b
 
 def sweep_tiles(lr, coeff, dict, L, k, scale, channels, out, kept=None, gamma=None,
                 reps: int = 5, max_tiles: int = 10):
-    """Time every tile shape of the matrix-core kernel for these arguments.
+    """Time every launch shape (tile, workgroup size, residency) of the matrix-core kernel for these arguments.
 
     Returns a list of (tile index, median milliseconds); empty if the
     matrix-core kernel does not take the case.  `out` is overwritten."""
