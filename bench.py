@@ -37,7 +37,7 @@ def read_traffic(workload):
         return None
 
 
-def empirical_ceilings(sr, torch, wl, coeffs, outs, kernel_ms):
+def empirical_ceilings(sr, torch, wl, coeffs, outs, kernel_ms, inp_lr, inp_dict):
     """Secondary roofline context: the machine's own streaming rates for this byte mix,
     from the library's probes (no arithmetic in them), timed like the kernel."""
     if wl.coeff_dtype not in ("f16", "bf16") or wl.L not in (72, 128) or wl.hr_pixels % 128 or outs[0].dtype != torch.float32:
@@ -59,6 +59,13 @@ def empirical_ceilings(sr, torch, wl, coeffs, outs, kernel_ms):
     t_read = timed(lambda i: sr.sr_probe_read(coeffs[i % len(coeffs)][0], sink))
     t_mix = timed(lambda i: sr.sr_probe_mix(coeffs[i % len(coeffs)][0], wl.L, px, outs[i % 2][0], wl.c))
     mix_bytes = coeff_bytes + wl.c * px * 4
+    # the same requests in the kernel's own order: its tiles (height reported by the library, 16 where it reports none),
+    # its split of the tiles over the XCDs, its rows per wavefront
+    t_tiled = None
+    if wl.W % 128 == 0:
+        shape = sr.sr_dict_assemble_launch_shape(inp_lr, coeffs[0], inp_dict, wl.L, wl.k, wl.scale, wl.c, outs[0])[1]
+        tile_h = shape[1] if shape[0] == 128 else 16
+        t_tiled = timed(lambda i: sr.sr_probe_mix_tiled(coeffs[i % len(coeffs)][0], wl.L, wl.H, wl.W, tile_h, outs[i % 2][0], wl.c))
     # the same bytes with nothing of the kernel's access pattern: 16-byte accesses, readers and
     # writers in separate workgroups, two workgroups per CU, every 9th one a writer
     t_stream = timed(lambda i: sr.sr_probe_stream(coeffs[i % len(coeffs)][0], coeff_bytes, outs[i % 2][0], wl.c * px * 4,
@@ -66,10 +73,13 @@ def empirical_ceilings(sr, torch, wl, coeffs, outs, kernel_ms):
     return {"read_only_GBps": round(coeff_bytes / t_read / 1e6, 1),
             "mix_GBps": round(mix_bytes / t_mix / 1e6, 1), "mix_ms": round(t_mix, 4),
             "kernel_time_over_mix_time": round(kernel_ms * 1.0 / (t_mix * wl.n), 3),
+            "tiled_mix_ms": round(t_tiled, 4) if t_tiled else None,
+            "kernel_time_over_tiled_mix_time": round(kernel_ms * 1.0 / (t_tiled * wl.n), 3) if t_tiled else None,
             "independent_mix_GBps": round(mix_bytes / t_stream / 1e6, 1), "independent_mix_ms": round(t_stream, 4),
             "kernel_time_over_independent_mix_time": round(kernel_ms * 1.0 / (t_stream * wl.n), 3),
             "note": "streaming probes of the same library on one frame's coefficient planes: read-only; the kernel's "
-                    "own read + write pattern with no arithmetic (mix); and the same bytes with 16-byte accesses by "
+                    "own read + write pattern with no arithmetic, run by run (mix) and in the kernel's own tile order (tiled_mix: what is "
+                    "left of the kernel when only its memory requests remain); and the same bytes with 16-byte accesses by "
                     "separate reader and writer workgroups (independent_mix), whose writers finish before its readers, so "
                     "that part of the reading runs undisturbed"}
 
@@ -123,6 +133,8 @@ def probe_study(sr, torch, hr_h=2160, hr_w=3840):
     out["kernel_pattern_l2_write_back_every_n_runs"] = {
         fe: timed(lambda i: sr.sr_probe_policy(S(i), D(i), px, 1, 0, fe, 512, sink)) for fe in (0, 1, 2, 4, 16)}
     out["kernel_pattern_probe_sr_probe_mix"] = timed(lambda i: sr.sr_probe_mix(S(i), 72, px, D(i), 3))
+    out["kernel_order_probe_sr_probe_mix_tiled"] = {
+        f"tile_128x{th}": timed(lambda i: sr.sr_probe_mix_tiled(S(i), 72, hr_h, hr_w, th, D(i), 3)) for th in (4, 8, 16, 24, 32)}
     return out
 
 
@@ -455,7 +467,7 @@ def main():
                      "algorithmic_bytes": alg_bytes},
         "pct_of_hbm_peak": round(100.0 * achieved / HBM_PEAK_GBS, 2),
     }
-    emp = None if args.pre_shuffle else empirical_ceilings(sr, torch, wl, coeffs, outs, avg_ms)
+    emp = None if args.pre_shuffle else empirical_ceilings(sr, torch, wl, coeffs, outs, avg_ms, inp["lr"], inp["dict"])
     if emp is not None:
         result["roofline"]["empirical"] = emp
     if args.kept_sweep:

@@ -33,6 +33,14 @@ int sr_probe_read(const void* src, size_t bytes, void* sink, void* stream);
  * planes must be 72 or 128, 1 <= channels <= 4, pixels a multiple of 128. */
 int sr_probe_mix(const void* coeff, int planes, size_t pixels, void* out, int channels, void* stream);
 
+/* The same bytes in the assembly kernel's own ORDER: persistent workgroups walk 128 x tile_h tiles of a
+ * height x width frame as the kernel does (its split of the tiles over the eight XCDs, four wavefronts on
+ * rows w, w + 4, ... of a tile), each wavefront reading one row of 128 pixels from every plane and writing
+ * it to every output plane; no LDS, no barrier, no arithmetic.  planes 72 or 128, 1 <= channels <= 4,
+ * width a multiple of 128, 1 <= tile_h <= 64, height * width < 2^31. */
+int sr_probe_mix_tiled(const void* coeff, int planes, int height, int width, int tile_h, void* out, int channels,
+                       void* stream);
+
 /* A byte mix with NOTHING of the assembly kernel's access pattern in it: one launch of
  * `blocks` workgroups of 256 threads in which every `writer_every`-th workgroup only
  * writes (16-byte stores sweeping `dst`, `write_bytes` in all) and all others only read

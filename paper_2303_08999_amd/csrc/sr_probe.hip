@@ -69,6 +69,60 @@ __global__ __launch_bounds__(256) void k_probe_mix(const char* __restrict__ p, s
 }
 
 
+// The same traffic in the assembly kernel's own order: persistent workgroups of four wavefronts walk
+// 128 x tile_h tiles of an H x W frame the way the kernel does (workgroup b of the eight groups
+// b % 8 takes its group's contiguous share of the tiles in raster order), wavefront w takes rows
+// w, w + 4, ... of a tile, one row of 128 pixels at a time: the row's 8 bytes per lane from every
+// plane (next row requested before this one's stores), then the row of every output plane.  No LDS,
+// no barrier, no arithmetic: what is left of the kernel when only its memory requests remain.
+template <int L>
+__global__ __launch_bounds__(256, 2) void k_probe_mix_tiled(const char* __restrict__ p, int H, int W, int tile_h, int tiles_x,
+                                                            int ntiles, float* __restrict__ out, int channels) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hf = lane >> 5, j = lane & 31;
+    const size_t pixels = (size_t)H * W, plane_b = pixels * 2;
+    const int groups = (gridDim.x & 7) == 0 ? 8 : 1;
+    const int G = gridDim.x / groups, share = (ntiles + groups - 1) / groups;
+    const int t_first = (int)(blockIdx.x % groups) * share + (int)(blockIdx.x / groups);
+    const int t_end = min(ntiles, ((int)(blockIdx.x % groups) + 1) * share);
+    const int rows = (tile_h - wave + 3) / 4;              // rows of a tile this wavefront takes
+    if (t_first >= t_end || rows <= 0) return;
+    // row r of tile t: image row min(ty * tile_h + wave + 4 r, H - 1) (rows past the image re-read its last row, as the
+    // kernel's clamped loads do, and are not stored), columns tx * 128 + 4 j .. + 3
+    auto offset = [&](int t, int r, bool& inside) -> size_t {
+        const int ty = t / tiles_x, tx = t - ty * tiles_x;
+        const int y = ty * tile_h + wave + 4 * r;
+        inside = y < H;
+        return (size_t)(inside ? y : H - 1) * W + (size_t)tx * 128 + 4 * j;
+    };
+    u32x2 v[L / 2];
+    bool in_cur;
+    size_t cur = offset(t_first, 0, in_cur);
+#pragma unroll
+    for (int i = 0; i < L / 2; ++i) v[i] = __builtin_nontemporal_load((const u32x2*)(p + (size_t)(2 * i + hf) * plane_b + cur * 2));
+    for (int t = t_first; t < t_end; t += G) {
+        for (int r = 0; r < rows; ++r) {
+            unsigned acc = 0;
+#pragma unroll
+            for (int i = 0; i < L / 2; ++i) acc ^= v[i][0] ^ v[i][1];
+            acc ^= __shfl_xor(acc, 32, 64);
+            const float f = (float)(acc & 0xffu);
+            const bool last = r == rows - 1;
+            const bool more = !last || t + G < t_end;
+            bool in_next = false;
+            const size_t nxt = more ? offset(last ? t + G : t, last ? 0 : r + 1, in_next) : cur;
+            if (more) {
+#pragma unroll
+                for (int i = 0; i < L / 2; ++i)
+                    v[i] = __builtin_nontemporal_load((const u32x2*)(p + (size_t)(2 * i + hf) * plane_b + nxt * 2));
+            }
+            if (in_cur)
+                for (int c = 0; c < channels; ++c) *(float2*)(out + (size_t)c * pixels + cur + 2 * hf) = make_float2(f, f + (float)c);
+            cur = nxt;
+            in_cur = in_next;
+        }
+    }
+}
+
 // Readers and writers as separate workgroups of one launch, 16 bytes per lane either
 // way, each role sweeping its own contiguous buffer: workgroup b writes when
 // b % writer_every == writer_every - 1 and reads otherwise; nothing ties a load to a
@@ -402,6 +456,25 @@ int sr_probe_mix(const void* coeff, int planes, size_t pixels, void* out, int ch
     else
         hipLaunchKernelGGL(k_probe_mix<128>, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
                            (const char*)coeff, pixels * 2, runs, (float*)out, pixels, channels);
+    return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_LAUNCH;
+}
+
+extern "C" __attribute__((visibility("default")))
+int sr_probe_mix_tiled(const void* coeff, int planes, int height, int width, int tile_h, void* out, int channels, void* stream) {
+    if (!coeff || !out) return SR_ERR_NULL;
+    if ((planes != 72 && planes != 128) || channels < 1 || channels > 4 || height < 0 || width < 0 || width % 128 != 0 ||
+        tile_h < 1 || tile_h > 64 || (long long)height * width >= (1ll << 31)) return SR_ERR_UNSUPPORTED;
+    if ((uintptr_t)coeff % 16 != 0 || (uintptr_t)out % 16 != 0) return SR_ERR_ALIGN;
+    if (height == 0 || width == 0) return SR_OK;
+    const int tiles_x = width / 128, tiles_y = (height + tile_h - 1) / tile_h;
+    const long long nt = (long long)tiles_x * tiles_y;
+    const int blocks = nt < 512 ? (int)nt : 512;
+    if (planes == 72)
+        hipLaunchKernelGGL(k_probe_mix_tiled<72>, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
+                           (const char*)coeff, height, width, tile_h, tiles_x, (int)nt, (float*)out, channels);
+    else
+        hipLaunchKernelGGL(k_probe_mix_tiled<128>, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
+                           (const char*)coeff, height, width, tile_h, tiles_x, (int)nt, (float*)out, channels);
     return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_LAUNCH;
 }
 

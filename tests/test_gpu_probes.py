@@ -28,6 +28,22 @@ def test_mix_probe_touches_every_plane_and_every_output_pixel(planes, channels, 
         assert torch.equal(out[c], want)
 
 
+@pytest.mark.parametrize("planes,channels,H,W,tile_h", [(72, 3, 50, 256, 24), (72, 3, 61, 128, 16), (128, 2, 9, 384, 4), (72, 1, 3, 128, 1),
+                                                        (72, 3, 700, 1280, 24)])
+def test_tiled_mix_probe_writes_what_the_flat_one_writes(planes, channels, H, W, tile_h):
+    """The probe that walks the frame in the kernel's tile order reads the same planes and writes the same
+    values as the flat one: every output pixel once, whatever the tile height and the ragged last tile row."""
+    pixels = H * W
+    g = torch.Generator(device="cuda").manual_seed(planes + H)
+    words = torch.randint(0, 2**31 - 1, (planes, pixels // 2), device="cuda", dtype=torch.int32, generator=g)
+    flat = torch.full((channels, pixels), -1.0, device="cuda")
+    tiled = torch.full((channels, pixels), -2.0, device="cuda")
+    sr.sr_probe_mix(words, planes, pixels, flat, channels)
+    sr.sr_probe_mix_tiled(words, planes, H, W, tile_h, tiled, channels)
+    torch.cuda.synchronize()
+    assert torch.equal(flat, tiled)
+
+
 def test_read_probe_runs_on_ragged_sizes_and_leaves_the_sink_alone():
     sink = torch.zeros(4, device="cuda", dtype=torch.int32)
     for nbytes in (16, 4096 * 5 + 16, 256 * 16 * 8 * 3 + 48, 1 << 26):
