@@ -168,7 +168,8 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
  * coeff->h, coeff->w are the LR sizes); the call gives exactly the result of shuffling it to
  * [N][L][s*h][s*w] first, without that 2 x (L * H * W) byte pass over memory.  Every kernel
  * takes it; the matrix-core kernel for k = 5, C = 3, f16 coefficients with up to 8 or 65 to 72
- * folded atoms (byte offsets), the generic kernel otherwise.
+ * folded atoms, or bf16 coefficients with 65 to 72 and an LR width that is a multiple of 4 (byte
+ * offsets), the generic kernel otherwise.
  *
  * opts->tile (the launch-shape search of section III-B, Eq. 11-12, as a small set of compiled
  * tile shapes): index 0 is the library's default for the frame and is always accepted.  Other

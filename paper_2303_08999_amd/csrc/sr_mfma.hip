@@ -104,8 +104,10 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
     const int np8 = np8_for(k, a.C, a.n_fold, coeff_dtype);
     if (np8 == 0) return false;
     // coefficients in the layout before the network's pixel-shuffle: one family built
-    if (a.pre_shuffle && !(k == 5 && a.C == 3 && coeff_dtype == SR_F16 && (np8 == 1 || np8 == 9) &&
-                           !beyond_4gb(a, coeff_dtype) && a.W % px == 0 && tile == 0)) return false;
+    // (bfloat16: the forms with permuted pixel slots only, i.e. LR widths that are multiples of 4, all atoms)
+    if (a.pre_shuffle && !(k == 5 && a.C == 3 && (np8 == 1 || np8 == 9) && !beyond_4gb(a, coeff_dtype) && a.W % px == 0 &&
+                           tile == 0 && (coeff_dtype == SR_F16 || (coeff_dtype == SR_BF16 && np8 == 9 && a.w % 4 == 0))))
+        return false;
     if (beyond_4gb(a, coeff_dtype) && np8_big(np8) == 0) return false;                     // element offsets: up to 72 atoms
     // Alternative tile shapes exist for one family only (5x5 atoms, three channels, 65 to 72 fp16
     // atoms, byte offsets); everywhere else only the default (index 0) is accepted, so that a

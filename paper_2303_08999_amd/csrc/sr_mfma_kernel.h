@@ -256,7 +256,8 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     static_assert(!LIST || (PX == 4 && WR == 1 && !BIG && PSM == 0 && NU % 2 == 0), "list form: four pixels per lane, one row per unit");
     constexpr bool PS = PSM == 1;                  // one 16-bit load per pixel
     constexpr bool PERM = PSM == 2 || PSM == 3 || PSM == 4;    // permuted pixel slots
-    static_assert(PSM == 0 || (CT == CT_F16 && !BIG && PX == 4), "pre-shuffle layout: 16-bit coefficients, four pixels per lane");
+    static_assert(PSM == 0 || ((CT == CT_F16 || (CT == CT_BF16 && PSM != 1)) && !BIG && PX == 4),
+                  "pre-shuffle layout: 16-bit coefficients, four pixels per lane");
     static_assert(!PERM || (WR == 1 && SMIN >= PSM), "permuted slots: one row per wavefront and unit");
     // row of the wavefront's unit within the tile, and which of the row's NSUB units it is
     auto unit_row = [](int unit, int wave_) { return (unit / NSUB) * NW + wave_; };

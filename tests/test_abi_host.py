@@ -198,9 +198,14 @@ def test_pre_shuffle_layout_is_checked_on_the_host(lib):
     assert plan(*ps_case(), kept=list(range(30)), opts=o(sr.SR_KERNEL_MFMA)) == -3
     assert plan(*ps_case(s=3), s=3, opts=o()) == sr.SR_KERNEL_MFMA
     assert plan(*ps_case(w=15, s=3), s=3, opts=o()) == sr.SR_KERNEL_GENERIC              # HR width 45: not whole groups
-    for kw, pk in (({"cd": sr.SR_F32}, {}), ({"cd": sr.SR_F8E4M3}, {}), ({"cd": sr.SR_BF16}, {}), ({"k": 7}, {"k": 7}),
+    for kw, pk in (({"cd": sr.SR_F32}, {}), ({"cd": sr.SR_F8E4M3}, {}), ({"k": 7}, {"k": 7}),
                    ({"C": 1}, {"C": 1}), ({"L": 100}, {"L": 100})):
         assert plan(*ps_case(**kw), **pk, opts=o()) == sr.SR_KERNEL_GENERIC, kw
+    # bfloat16: the forms with permuted pixel slots only (LR width a multiple of 4), 65 to 72 atoms
+    assert plan(*ps_case(cd=sr.SR_BF16), opts=o()) == sr.SR_KERNEL_MFMA
+    assert plan(*ps_case(cd=sr.SR_BF16, s=3), s=3, opts=o()) == sr.SR_KERNEL_MFMA
+    assert plan(*ps_case(cd=sr.SR_BF16, w=30), opts=o()) == sr.SR_KERNEL_GENERIC
+    assert plan(*ps_case(cd=sr.SR_BF16), kept=[3, 9, 70], opts=o()) == sr.SR_KERNEL_GENERIC
     assert plan(*ps_case(), opts=o(sr.SR_KERNEL_MFMA, 3)) == -3                          # no alternative tiles in this layout
     # the planar shape under the pre-shuffle flag, and the other way round, are shape errors
     assert plan(*case(), opts=o()) == -2

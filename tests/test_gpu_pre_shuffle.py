@@ -41,6 +41,10 @@ CASES = [
     (1, 1, 19, 23, 4, 40, 5, "f32", "f32", None),       # everything else runs on the generic kernel
     (2, 2, 16, 21, 3, 17, 7, "f8", "f16", 5),
     (1, 3, 18, 20, 2, 30, 3, "bf16", "f32", None),
+    (1, 3, 37, 64, 4, 72, 5, "bf16", "f32", None),      # bfloat16 coefficients in the permuted-slot forms: scale 4,
+    (2, 3, 29, 44, 3, 72, 5, "bf16", "f32", None),      #   scale 3,
+    (1, 3, 41, 68, 2, 72, 5, "bf16", "f16", 70),        #   scale 2 with 70 kept atoms and an fp16 image
+    (1, 3, 20, 30, 4, 72, 5, "bf16", "f32", None),      # bfloat16, LR width not a multiple of 4: the generic kernel
     (1, 3, 15, 17, 3, 72, 5, "f16", "f32", None),       # HR width 51: not whole pixel groups
     (1, 3, 23, 18, 3, 72, 5, "f16", "f32", None),       # scale 3, LR width not a multiple of 4: one 16-bit load per pixel and plane
 ]
@@ -74,6 +78,9 @@ def test_pre_shuffle_layout_against_the_oracle_and_the_planar_call(oracle, case)
     assert ran >= 1
     if cd == "f16" and C == 3 and k == 5 and (h * s) and (w * s) % 4 == 0 and (nk is None or nk <= 8 or nk >= 65):
         assert run(inp, wl, pre, MFMA, sr.SR_COEFF_PRE_SHUFFLE, kept, gamma) is not None, "this case belongs to the matrix-core kernel"
+    if cd == "bf16" and C == 3 and k == 5:
+        takes = run(inp, wl, pre, MFMA, sr.SR_COEFF_PRE_SHUFFLE, kept, gamma) is not None
+        assert takes == (w % 4 == 0 and (nk is None or nk >= 65)), "bfloat16: the permuted-slot forms only"
 
 
 def test_4k_frame_in_the_pre_shuffle_layout(oracle):
