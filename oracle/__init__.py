@@ -69,6 +69,8 @@ def _load():
         lib.orc_assemble_topk_rows.restype = c_int
         lib.orc_assemble_topk_rows.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_vp, c_vp, c_int, c_int, c_int,
                                                c_vp, c_int, c_int, c_int, c_vp]
+        lib.orc_pixel_major_to_planar.restype = c_int
+        lib.orc_pixel_major_to_planar.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_vp]
         lib.orc_pixel_shuffle.restype = c_int
         lib.orc_pixel_shuffle.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_vp]
         lib.orc_threads.restype = c_int
@@ -223,11 +225,27 @@ def pixel_shuffle(coeff_lr, scale: int) -> np.ndarray:
     return out
 
 
+def pixel_major_to_planar(coeff_pm) -> np.ndarray:
+    """Coefficients stored pixel-major, ``coeff_pm`` [N][H][W][L] (the L coefficients of a pixel side by
+    side), as the planar [N][L][H][W] every other function here reads: the same stored elements."""
+    a = _stored(coeff_pm, "coeff_pm")
+    if a.ndim != 4:
+        raise ValueError("coeff_pm must be [N][H][W][L]")
+    n, H, W, L = a.shape
+    out = np.empty((n, L, H, W), dtype=a.dtype)
+    if _load().orc_pixel_major_to_planar(_ptr(a), a.dtype.itemsize, n, L, H, W, _ptr(out)):
+        raise ValueError("orc_pixel_major_to_planar rejected its arguments")
+    return out
+
+
 def dict_assemble(lr, coeff, dictionary, scale: int, kept=None, gamma=None, a: float = -0.5,
-                  pre_shuffle: bool = False) -> np.ndarray:
+                  pre_shuffle: bool = False, pixel_major: bool = False) -> np.ndarray:
     """The whole path: stage 1, then stages 3 + 4.  float64 [N][C][s*h][s*w].  With
     ``pre_shuffle`` the coefficients are what the network holds before its pixel-shuffle
-    layer, [N][L*s*s][h][w]: that layer is applied first."""
+    layer, [N][L*s*s][h][w]: that layer is applied first.  With ``pixel_major`` they are stored
+    [N][H][W][L] and are moved to planes first."""
+    if pixel_major:
+        coeff = pixel_major_to_planar(coeff)
     if pre_shuffle:
         coeff = pixel_shuffle(coeff, scale)
     return assemble(bicubic(lr, scale, a), coeff, dictionary, kept, gamma)

@@ -392,6 +392,31 @@ int orc_pixel_shuffle(const void *in, int esize, int n, int L, int h, int w, int
     return 0;
 }
 
+/*
+ * Coefficients stored pixel-major (an extension of the storage formats, not in the paper: what a producer
+ * that keeps its tensors channels-last writes): in[b][y][x][l] holds the coefficient of atom l at HR pixel
+ * (y, x), the L coefficients of a pixel side by side.  Moves the stored elements (esize bytes each) to the
+ * planar order every other function here reads:
+ *
+ *     out[b][l][y][x] = in[b][y][x][l]
+ */
+int orc_pixel_major_to_planar(const void *in, int esize, int n, int L, int H, int W, void *out)
+{
+    if (!in || !out || esize < 1 || esize > 8 || n < 0 || L < 1 || H < 0 || W < 0)
+        return -1;
+    const unsigned char *src = (const unsigned char *)in;
+    unsigned char *dst = (unsigned char *)out;
+    for (int b = 0; b < n; ++b)
+        for (int y = 0; y < H; ++y)
+            for (int x = 0; x < W; ++x)
+                for (int l = 0; l < L; ++l) {
+                    size_t from = (((size_t)b * H + y) * W + x) * L + l;
+                    size_t to = (((size_t)b * L + l) * H + y) * W + x;
+                    memcpy(dst + to * esize, src + from * esize, (size_t)esize);
+                }
+    return 0;
+}
+
 /* Threads the row loops above will use. */
 int orc_threads(void)
 {

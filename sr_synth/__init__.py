@@ -102,6 +102,14 @@ def to_pre_shuffle(coeff, scale: int):
     return pre.view(coeff.dtype) if raw is not coeff else pre
 
 
+def to_pixel_major(coeff):
+    """The same stored coefficients with the L coefficients of a pixel side by side:
+    [N][L][H][W] -> [N][H][W][L] (a move of elements; 8-bit floats are moved as bytes)."""
+    raw = coeff.view(torch.uint8) if coeff.dtype == torch.float8_e4m3fn else coeff
+    pm = raw.permute(0, 2, 3, 1).contiguous()
+    return pm.view(coeff.dtype) if raw is not coeff else pm
+
+
 def to_list(coeff, entries: int):
     """The ``entries`` largest coefficients of every pixel as (atom index uint8, value) planes,
     [N][entries][H][W] each, largest first (ties: whatever order the library sort gives; both sides

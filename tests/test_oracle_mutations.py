@@ -13,7 +13,7 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "sr_oracle.c")
 PINS = ["tests/test_oracle_bicubic.py", "tests/test_oracle_assemble.py", "tests/test_oracle_fp8.py",
-        "tests/test_oracle_shuffle.py", "tests/test_oracle_topk.py"]
+        "tests/test_oracle_shuffle.py", "tests/test_oracle_topk.py", "tests/test_oracle_pixel_major.py"]
 
 MUTATIONS = {
     "keys_inner_coefficient": ("- (a + 3.0) * t * t + 1.0", "- (a + 2.0) * t * t + 1.0"),
@@ -41,6 +41,8 @@ MUTATIONS = {
                              "apply_pixel(U + ((size_t)b * c) * plane, H, W, Y, X, F, k);\n            }"),
     "batch_stride_of_coefficients": ("size_t pix = (size_t)b * L * plane + (size_t)Y * W + X;\n                fold_pixel",
                                      "size_t pix = (size_t)b * plane + (size_t)Y * W + X;\n                fold_pixel"),
+    "pixel_major_read_as_planar": ("size_t from = (((size_t)b * H + y) * W + x) * L + l;", "size_t from = (((size_t)b * L + l) * H + y) * W + x;"),
+    "pixel_major_rows_and_columns_swapped": ("size_t from = (((size_t)b * H + y) * W + x) * L + l;", "size_t from = (((size_t)b * W + x) * H + y) * L + l;"),
     "shuffle_sub_pixels_column_major": ("size_t from = ((((size_t)b * L + l) * s + i) * s + j)", "size_t from = ((((size_t)b * L + l) * s + j) * s + i)"),
     "shuffle_atoms_interleaved": ("size_t from = ((((size_t)b * L + l) * s + i) * s + j)", "size_t from = ((((size_t)b * s + i) * s + j) * L + l)"),
     "shuffle_lands_on_lr_rows": ("((size_t)y * s + i) * W + ((size_t)x * s + j)", "((size_t)i * h + y) * W + ((size_t)x * s + j)"),
