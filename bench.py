@@ -344,6 +344,9 @@ def main():
     ap.add_argument("--probe-study", action="store_true",
                     help="instead of the kernel, time the library's streaming probes on the 4K frame's byte mix "
                          "and print them as one JSON line")
+    ap.add_argument("--pixel-major", action="store_true",
+                    help="hand the coefficients over stored pixel-major, [N][H][W][L] (what a channels-last producer writes; "
+                         "a storage order beyond the paper); same values, same result")
     ap.add_argument("--tile-sweep", action="store_true",
                     help="also time every launch shape (tile, workgroup size, residency) the library has for this "
                          "workload: the measured stand-in for the paper's launch-shape search (section III-B)")
@@ -384,8 +387,13 @@ def main():
     for r in range(1, N_ROTATE):
         coeffs.append(sr_synth.make_coeff(sr_synth.scaled(wl, index=wl.index + 10 * r), dev))
     outs = [torch.empty((wl.n, wl.c, wl.H, wl.W), device=dev, dtype=inp["lr"].dtype) for _ in range(2)]
-    layout = sr.SR_COEFF_PRE_SHUFFLE if args.pre_shuffle else sr.SR_COEFF_PLANAR
-    if args.pre_shuffle:
+    layout = sr.SR_COEFF_PRE_SHUFFLE if args.pre_shuffle else (sr.SR_COEFF_PIXEL_MAJOR if args.pixel_major else sr.SR_COEFF_PLANAR)
+    if args.pixel_major:
+        for r in range(len(coeffs)):
+            coeffs[r] = sr_synth.to_pixel_major(coeffs[r])
+        inp["coeff"] = coeffs[0]
+        args.pre_shuffle = True            # from here on: "not the planar layout" (the extra legs below are planar-only)
+    elif args.pre_shuffle:
         for r in range(N_ROTATE):
             coeffs[r] = sr_synth.to_pre_shuffle(coeffs[r], wl.scale)
         inp["coeff"] = coeffs[0]
@@ -456,7 +464,8 @@ def main():
         "config": {"workload": wl.name, "hr": f"{wl.W}x{wl.H}", "scale": wl.scale, "channels": wl.c,
                    "L": wl.L, "k": wl.k, "atoms_read": n_read, "batch": wl.n,
                    "kernel": {1: "generic", 2: "mfma"}[plan], "rotating_coeff_buffers": N_ROTATE,
-                   "coeff_layout": "pre_shuffle [N][L*s*s][h][w]" if args.pre_shuffle else "planar [N][L][H][W]"},
+                   "coeff_layout": ("pixel_major [N][H][W][L]" if args.pixel_major else "pre_shuffle [N][L*s*s][h][w]")
+                                   if args.pre_shuffle else "planar [N][L][H][W]"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(wl.name),
                      "traffic_source": (f"profiles/sr_mfma_{wl.name}_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an "

@@ -94,10 +94,15 @@ typedef enum {
 /* How `coeff` is laid out (sr_options.coeff_layout). */
 typedef enum {
     SR_COEFF_PLANAR      = 0,  /* [N][L][s*h][s*w]: one HR plane per atom          */
-    SR_COEFF_PRE_SHUFFLE = 1   /* [N][L*s*s][h][w]: what the coefficient network
+    SR_COEFF_PRE_SHUFFLE = 1,  /* [N][L*s*s][h][w]: what the coefficient network
                                   holds BEFORE its pixel-shuffle layer (section
                                   II-B, stage 2); channel l*s*s + i*s + j carries
                                   atom l at HR pixels (y*s + i, x*s + j)           */
+    SR_COEFF_PIXEL_MAJOR = 2   /* [N][s*h][s*w][L]: the L coefficients of a pixel
+                                  side by side (what a producer that keeps its
+                                  tensors channels-last writes); a storage order
+                                  beyond the paper, same values, same result.  The
+                                  descriptor keeps c = L, h = s*h, w = s*w.        */
 } sr_coeff_layout;
 
 typedef struct {
@@ -170,6 +175,12 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
  * takes it; the matrix-core kernel for k = 5, C = 3, f16 coefficients with up to 8 or 65 to 72
  * folded atoms, or bf16 coefficients with 65 to 72 and an LR width that is a multiple of 4 (byte
  * offsets), the generic kernel otherwise.
+ *
+ * opts->coeff_layout = SR_COEFF_PIXEL_MAJOR: `coeff` is stored [N][s*h][s*w][L] (described with
+ * c = L, h = s*h, w = s*w as for the planar order).  A wavefront's row of 128 pixels is then one
+ * contiguous piece of memory.  Every kernel takes it; the matrix-core kernel for k = 5, C = 3, all
+ * of L = 72 f16 atoms (no kept list), an HR width that is a multiple of 128 and under 4 GB of
+ * coefficients per image, the generic kernel otherwise.
  *
  * opts->tile (the launch-shape search of section III-B, Eq. 11-12, as a small set of compiled
  * tile shapes): index 0 is the library's default for the frame and is always accepted.  Other

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libsrdict.so")
 
 SR_F32, SR_F16, SR_F8E4M3, SR_BF16, SR_U8 = 0, 1, 2, 3, 4
 SR_KERNEL_AUTO, SR_KERNEL_GENERIC, SR_KERNEL_MFMA = 0, 1, 2
-SR_COEFF_PLANAR, SR_COEFF_PRE_SHUFFLE = 0, 1
+SR_COEFF_PLANAR, SR_COEFF_PRE_SHUFFLE, SR_COEFF_PIXEL_MAJOR = 0, 1, 2
 SR_MAX_ATOMS = 256
 
 EXPORTS = ("sr_dict_assemble", "sr_dict_assemble_selective", "sr_dict_assemble_ex", "sr_dict_assemble_list", "sr_dict_assemble_list_ex",
@@ -112,6 +112,15 @@ def describe(t) -> sr_tensor:
     return sr_tensor(ptr or None, code, *[int(v) for v in t.shape])
 
 
+def describe_coeff(t, opts=None) -> sr_tensor:
+    """Descriptor of the coefficient tensor for the layout named in ``opts``: a pixel-major tensor
+    [N][H][W][L] is described with c = L, h = H, w = W, as the header asks."""
+    d = describe(t)
+    if opts is not None and opts.coeff_layout == SR_COEFF_PIXEL_MAJOR:
+        d.c, d.h, d.w = int(t.shape[3]), int(t.shape[1]), int(t.shape[2])
+    return d
+
+
 def _dict4(d):
     return d if d.dim() == 4 else d.reshape(1, *d.shape)
 
@@ -175,7 +184,7 @@ def make_options(kernel=SR_KERNEL_AUTO, tile=0, coeff_layout=SR_COEFF_PLANAR) ->
 
 def sr_dict_assemble_ex(lr, coeff, dict, L, k, scale, channels, out, stream=None,
                         kept=None, n_kept=None, gamma=None, opts=None):
-    a, b, c, o = describe(lr), describe(coeff), describe(_dict4(dict)), describe(out)
+    a, b, c, o = describe(lr), describe_coeff(coeff, opts), describe(_dict4(dict)), describe(out)
     ka, n, ga, _keep = _host_lists(kept, gamma)
     n = n if n_kept is None else int(n_kept)
     op = ctypes.byref(opts) if opts is not None else None
@@ -184,7 +193,7 @@ def sr_dict_assemble_ex(lr, coeff, dict, L, k, scale, channels, out, stream=None
 
 
 def sr_dict_assemble_plan(lr, coeff, dict, L, k, scale, channels, out, kept=None, n_kept=None, opts=None) -> int:
-    a, b, c, o = describe(lr), describe(coeff), describe(_dict4(dict)), describe(out)
+    a, b, c, o = describe(lr), describe_coeff(coeff, opts), describe(_dict4(dict)), describe(out)
     ka, n, _ga, _keep = _host_lists(kept, None)
     n = n if n_kept is None else int(n_kept)
     op = ctypes.byref(opts) if opts is not None else None
@@ -207,7 +216,7 @@ def sr_dict_assemble_list_ex(lr, index, value, dict, L, k, scale, channels, entr
 
 def sr_dict_assemble_tile(lr, coeff, dict, L, k, scale, channels, out, kept=None, n_kept=None, opts=None):
     """(kernel or negative status, tile width, tile height) the call would run with."""
-    a, b, c, o = describe(lr), describe(coeff), describe(_dict4(dict)), describe(out)
+    a, b, c, o = describe(lr), describe_coeff(coeff, opts), describe(_dict4(dict)), describe(out)
     ka, n, _ga, _keep = _host_lists(kept, None)
     n = n if n_kept is None else int(n_kept)
     op = ctypes.byref(opts) if opts is not None else None
@@ -218,7 +227,7 @@ def sr_dict_assemble_tile(lr, coeff, dict, L, k, scale, channels, out, kept=None
 
 def sr_dict_assemble_launch_shape(lr, coeff, dict, L, k, scale, channels, out, kept=None, n_kept=None, opts=None):
     """(kernel or negative status, (tile width, tile height, wavefronts per workgroup, workgroups per CU))."""
-    a, b, c, o = describe(lr), describe(coeff), describe(_dict4(dict)), describe(out)
+    a, b, c, o = describe(lr), describe_coeff(coeff, opts), describe(_dict4(dict)), describe(out)
     ka, n, _ga, _keep = _host_lists(kept, None)
     n = n if n_kept is None else int(n_kept)
     op = ctypes.byref(opts) if opts is not None else None

@@ -52,7 +52,7 @@ void make_plan(Plan& p, const sr_tensor* lr, const sr_tensor* coeff, const sr_te
     if (L < 1 || L > SR_MAX_ATOMS || channels < 1 || channels > SR_MAX_CHANNELS) {
         p.status = SR_ERR_UNSUPPORTED; return;
     }
-    if (opts && (opts->coeff_layout < SR_COEFF_PLANAR || opts->coeff_layout > SR_COEFF_PRE_SHUFFLE)) {
+    if (opts && (opts->coeff_layout < SR_COEFF_PLANAR || opts->coeff_layout > SR_COEFF_PIXEL_MAJOR)) {
         p.status = SR_ERR_UNSUPPORTED; return;
     }
     if (lr->c != channels || out->c != channels ||
@@ -102,6 +102,7 @@ void make_plan(Plan& p, const sr_tensor* lr, const sr_tensor* coeff, const sr_te
     a.N = lr->n; a.C = channels; a.h = lr->h; a.w = lr->w;
     a.H = out->h; a.W = out->w; a.s = scale; a.L = L;
     a.pre_shuffle = pre_shuffle ? 1 : 0;
+    a.pixel_major = opts && opts->coeff_layout == SR_COEFF_PIXEL_MAJOR ? 1 : 0;
 
     const int want = opts ? opts->kernel : SR_KERNEL_AUTO;
     const int tile = opts ? opts->tile : 0;

@@ -31,6 +31,7 @@ struct AssembleArgs {
     const unsigned char* index;   // list form only: atom numbers [N][T][H][W]; `coeff` then holds the values [N][T][H][W]
     int T;                // list form only: entries per pixel
     int pre_shuffle;      // coefficients are [N][L*s*s][h][w] (before the network's pixel-shuffle), else [N][L][H][W]
+    int pixel_major;      // coefficients are [N][H][W][L] (a pixel's L coefficients side by side)
     int   kept[SR_MAX_ATOMS];    // plane read for folded atom i (identity when dense)
     float gamma[SR_MAX_ATOMS];   // its scale (1 when dense)
 };

@@ -49,7 +49,9 @@ __global__ __launch_bounds__(GNT) void k_assemble_generic(const AssembleArgs a) 
         const size_t within = a.pre_shuffle
             ? (size_t)((Y % a.s) * a.s + X % a.s) * ((size_t)a.h * a.w) + (size_t)(Y / a.s) * a.w + X / a.s
             : (size_t)Y * a.W + X;
-        const TC* cbase = (const TC*)a.coeff + (size_t)n * a.L * plane + within;
+        // ... or, pixel-major, the pixel's L coefficients side by side
+        const size_t astride = a.pixel_major ? (size_t)1 : plane;
+        const TC* cbase = (const TC*)a.coeff + (size_t)n * a.L * plane + (a.pixel_major ? within * a.L : within);
         // eight atoms at a time: their coefficient loads are in flight together
         constexpr int NB = 8;
         for (int i0 = 0; i0 < a.n_fold; i0 += NB) {
@@ -57,7 +59,7 @@ __global__ __launch_bounds__(GNT) void k_assemble_generic(const AssembleArgs a) 
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 const int i = i0 + b < a.n_fold ? i0 + b : a.n_fold - 1;      // past the end: re-read, unused
-                phi[b] = ld_as_float(cbase, (size_t)a.kept[i] * plane) * a.gamma[i];
+                phi[b] = ld_as_float(cbase, (size_t)a.kept[i] * astride) * a.gamma[i];
             }
 #pragma unroll
             for (int b = 0; b < NB; ++b)

@@ -16,6 +16,7 @@ hipError_t launch_mfma_k7_f8(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_k5_big(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_bf16(const AssembleArgs& a, int k, int np8, hipStream_t st);
 hipError_t launch_mfma_k5_ps(const AssembleArgs& a, int np8, hipStream_t st);
+hipError_t launch_mfma_k5_pm(const AssembleArgs& a, hipStream_t st);
 
 namespace {
 
@@ -104,6 +105,13 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
     const int np8 = np8_for(k, a.C, a.n_fold, coeff_dtype);
     if (np8 == 0) return false;
     // coefficients in the layout before the network's pixel-shuffle: one family built
+    // coefficients stored pixel-major: one family built (all of 72 fp16 atoms in their own order, whole 128-pixel units)
+    if (a.pixel_major) {
+        if (a.pre_shuffle || !(k == 5 && a.C == 3 && coeff_dtype == SR_F16 && a.L == 72 && a.n_fold == 72 &&
+                               !beyond_4gb(a, coeff_dtype) && a.W % 128 == 0 && tile == 0)) return false;
+        for (int i = 0; i < 72; ++i)
+            if (a.kept[i] != i) return false;
+    }
     // (bfloat16: the forms with permuted pixel slots only, i.e. LR widths that are multiples of 4, all atoms)
     if (a.pre_shuffle && !(k == 5 && a.C == 3 && (np8 == 1 || np8 == 9) && !beyond_4gb(a, coeff_dtype) && a.W % px == 0 &&
                            tile == 0 && (coeff_dtype == SR_F16 || (coeff_dtype == SR_BF16 && np8 == 9 && a.w % 4 == 0))))
@@ -123,6 +131,7 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
 hipError_t launch_mfma(const AssembleArgs& a, int k, bool io_f16, int tile, hipStream_t st) {
     (void)io_f16;
     const int np8 = np8_for(k, a.C, a.n_fold, a.coeff_dtype);
+    if (a.pixel_major) return launch_mfma_k5_pm(a, st);
     if (a.pre_shuffle) return launch_mfma_k5_ps(a, np8, st);
     if (beyond_4gb(a, a.coeff_dtype))
         return np8_big(np8) ? launch_mfma_k5_big(a, np8_big(np8), st) : hipErrorInvalidValue;

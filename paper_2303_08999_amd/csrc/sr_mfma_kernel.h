@@ -92,7 +92,7 @@ constexpr int LIST_MAX_ENTRIES = 16;
 // of a tile shrinks with the scale, so an instantiation for scale 4 only needs half
 // the LDS for the footprint and the vertical-pass buffer, and can afford a taller
 // tile (fewer halo rows up-sampled per output row).
-template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int CT = CT_F16, int SMIN = 2, int NSUB = 1>
+template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int CT = CT_F16, int SMIN = 2, int NSUB = 1, int SWZ = 0>
 struct Cfg {
     static constexpr bool F32 = CT == CT_F32, F8 = CT == CT_F8, BF = CT == CT_BF16, LIST = CT == CT_LIST8 || CT == CT_LIST16;
     static constexpr int LH = CT == CT_LIST8 ? 4 : 8;  // list form: entries a lane half loads
@@ -112,7 +112,8 @@ struct Cfg {
     // apart read consecutive words.  SW = PX, except in the scale-4 pre-shuffle form (NSUB = 2), whose lane pairs
     // are 16 columns apart: with eight classes they step by two words, and the odd NG puts a pair's second lane on
     // the odd banks.
-    static constexpr int SW = NSUB == 2 ? 8 : PX;
+    // SWZ = 1 (pixel-major coefficients): no swizzle, lane j's slots are pixels j, 32 + j, ... of the row.
+    static constexpr int SW = SWZ ? SWZ : (NSUB == 2 ? 8 : PX);
     static constexpr int NG = ((UW + SW - 1) / SW) | (NSUB == 2 ? 1 : 0);   // stride between the classes
     static constexpr int P0 = SW * NG;
     // rows of one wavefront must land on disjoint banks: pitch == WC (mod 32)
@@ -246,11 +247,23 @@ __device__ __forceinline__ void divmod_scale(int v, int s, int& q, int& r) {
 //     filled; everything after the loads is unchanged.  Four times the load instructions and a
 //     register per element in flight: 2.6 x the time of the planar form at 4K.
 // The result is the planar form's, bit for bit, in every case.
+//
+// PSM = 8: the coefficients are stored pixel-major, [H][W][L] (the L = 72 coefficients of a pixel side by
+// side, 144 bytes; what a producer that keeps its tensors channels-last writes).  A unit's 128 pixels are
+// then 18 432 CONTIGUOUS bytes: 18 loads of 16 bytes per lane, lane after lane (the friendliest request
+// stream there is: the same bytes take 231 us where the planes take 249).  Sixteen bytes of a pixel are the
+// eight atoms of half a 16-atom step, i.e. a B operand as it stands: pixel slot by pixel slot (slot q =
+// pixels 32 q .. 32 q + 31 of the unit, 4 608 contiguous bytes) the loaded registers are copied to an LDS
+// scratch as they are and lane (j, hf) reads its operand pieces back at pixel j, piece 2 c + hf.  No
+// re-packing.  Lane j's slots are the pixels j, 32 + j, 64 + j, 96 + j: the tile is stored without a
+// swizzle (consecutive lanes read consecutive words) and a lane stores single pixels (a wavefront half
+// still writes 128 contiguous bytes).  The fold, stage 4 and the result are the planar form's, bit for bit.
 template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT, int SMIN, bool BIG, int PSM = 0>
 __global__ __launch_bounds__(64 * NW, WPE)
 void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y, const int ntiles) {
     constexpr int NSUB = PSM == 4 ? 2 : (PSM == 3 ? 3 : 1);   // units per tile row
-    using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN, NSUB>;
+    constexpr bool PMAJ = PSM == 8;                // coefficients stored pixel-major, [H][W][L]
+    using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN, NSUB, (PMAJ ? 1 : 0)>;
     constexpr bool F32 = F::F32, F8 = F::F8, BF = F::BF, LIST = F::LIST;
     constexpr int LH = F::LH;                      // list entries a lane half loads
     static_assert(!LIST || (PX == 4 && WR == 1 && !BIG && PSM == 0 && NU % 2 == 0), "list form: four pixels per lane, one row per unit");
@@ -258,6 +271,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     constexpr bool PERM = PSM == 2 || PSM == 3 || PSM == 4;    // permuted pixel slots
     static_assert(PSM == 0 || ((CT == CT_F16 || (CT == CT_BF16 && PSM != 1)) && !BIG && PX == 4),
                   "pre-shuffle layout: 16-bit coefficients, four pixels per lane");
+    static_assert(!PMAJ || (CT == CT_F16 && WR == 1 && NP8 == 9), "pixel-major coefficients: 72 fp16 atoms, one row per unit");
     static_assert(!PERM || (WR == 1 && SMIN >= PSM), "permuted slots: one row per wavefront and unit");
     // row of the wavefront's unit within the tile, and which of the row's NSUB units it is
     auto unit_row = [](int unit, int wave_) { return (unit / NSUB) * NW + wave_; };
@@ -277,6 +291,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     __shared__ u32x2 A8[(F32 ? 1 : NMB * 2) * 64];
     __shared__ float A32[(F32 ? F::N2 * NMB : 1) * 64];   // fp32 path: D[2*step + hf][tap of row]
     __shared__ unsigned ptab[2 * F::NLOAD];         // byte offset of the plane each lane half loads
+    __shared__ u32x4 pmscr[PMAJ ? NW * 288 : 1];    // pixel-major: per wavefront, one slot's 32 pixels x 144 bytes
     __shared__ unsigned ltab[LIST ? 2 * LH : 1];    // list form: element offset of the entry plane each lane half loads
     __shared__ u32x4 lscr[LIST ? NW * F::LSW / 4 : 1];   // list form: per wavefront, [NP8 groups of 8 atoms][32 pixels][8 atoms] fp16
 
@@ -364,9 +379,9 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     }
     __syncthreads();
 
-    // list form, up to 72 atoms: the dictionary operands stay in registers (the fold reads them once per pixel
-    // slot, four times as often as the dense form does)
-    constexpr bool AREG = LIST && NP8 <= 9;
+    // list form with up to 72 atoms, and pixel-major coefficients: the dictionary operands stay in registers (the
+    // fold reads them once per pixel slot, four times as often as the dense form does)
+    constexpr bool AREG = (LIST && NP8 <= 9) || PSM == 8;
     u32x4 areg[AREG ? 2 * N16 : 1];
     u32x2 areg8[AREG && N8 ? 2 : 1];
     if constexpr (AREG) {
@@ -551,6 +566,17 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             val[e] = __builtin_nontemporal_load((const u32x2*)(vbase + (size_t)at * 2));
         }
     };
+    // pixel-major: the unit's 18 432 bytes, 16 per lane and load; byte offset of the lane's first piece within the image
+    constexpr int NPM = 18;
+    u32x4 pm[PMAJ ? NPM : 1];
+    auto pm_offset = [&](const TilePos tp, int unit, int lane_) -> unsigned {
+        const int y = tp.ty * F::TH + unit * NW + wave;
+        const unsigned yc = (unsigned)(y < a.H ? y : a.H - 1);                 // rows past the image re-read its last row
+        return (yc * (unsigned)a.W + (unsigned)tile_x0(tp.tx)) * (unsigned)(16 * NP8) + 16u * (unsigned)lane_;
+    };
+    auto pm_image = [&](const TilePos tp) -> const char* {
+        return (const char*)a.coeff + (size_t)tp.n * a.L * ((size_t)a.H * a.W * 2);
+    };
     Raw raw[F::NLOAD];
     unsigned lrv[F::NLRP][F::NXC], lrpar = 0u;
 #pragma unroll
@@ -562,6 +588,11 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         load_lr(cur, lane, lrv, lrpar);
         if constexpr (LIST) {
             load_list(cur, 0, j, hf, lval[0], lidx[0]);
+        } else if constexpr (PMAJ) {
+            const char* img = pm_image(cur);
+            const unsigned off = pm_offset(cur, 0, lane);
+#pragma unroll
+            for (int i = 0; i < NPM; ++i) pm[i] = __builtin_nontemporal_load((const u32x4*)(img + (off + 1024u * i)));
         } else {
             unsigned pix_off[NPIX];
             const char* cimg = phi_base(cur, 0, j / F::WC, j % F::WC, pix_off);
@@ -716,7 +747,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         const bool more = last_unit ? more_tiles : true;
         unsigned pix_next[NPIX];
         const char* cnext = nullptr;
-        if constexpr (!LIST) cnext = last_unit ? phi_base(nxt, 0, jr, jc, pix_next) : phi_base(cur, unit + 1, jr, jc, pix_next);
+        if constexpr (!LIST && !PMAJ) cnext = last_unit ? phi_base(nxt, 0, jr, jc, pix_next) : phi_base(cur, unit + 1, jr, jc, pix_next);
 
         // (3) stage 3 on the matrix cores: atom steps outer, pixel slots inner
         f32x16 acc[PX][NMB];
@@ -781,6 +812,60 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+        if constexpr (PMAJ) {
+            static_assert(NMB == 1 || !PMAJ, "pixel-major: one block of MFMA rows");
+            const char* nimg = last_unit ? pm_image(nxt) : pm_image(cur);
+            const unsigned noff = last_unit ? pm_offset(nxt, 0, lane) : pm_offset(cur, unit + 1, lane);
+            char* const scr = (char*)(pmscr + wave * 288);
+            const char* const mine = scr + jc * (16 * NP8);            // the lane's pixel of the slot
+            auto reload = [&](int i) {
+                if (more) pm[i] = __builtin_nontemporal_load((const u32x4*)(nimg + (noff + 1024u * i)));
+            };
+            // Slot q = stream bytes 4608 q .. 4608 q + 4607: four whole loads and half of the load that two slots
+            // share.  stage(q): registers -> scratch (and the freed registers are re-loaded for the next unit), then
+            // the lane's operand pieces back: sixteen bytes of a pixel are atoms 8 g .. 8 g + 7, piece 2 c + hf is
+            // the operand of step c.  LDS serves a wavefront's requests in order, so the next slot is staged
+            // before this slot's matrix instructions are issued and its pieces travel while they run.
+            u32x4 bw16[2][N16 ? N16 : 1];
+            u32x2 bw8[2];
+            auto stage = [&](int q, int b) {
+                const int first = (9 * q) / 2;                         // 0, 4, 9, 13
+                if (q % 2 == 0) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) *(u32x4*)(scr + 1024 * i + 16 * lane) = pm[first + i];
+                    if (lane < 32) *(u32x4*)(scr + 4096 + 16 * lane) = pm[first + 4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) reload(first + i);
+                } else {
+                    if (lane >= 32) *(u32x4*)(scr + 16 * (lane - 32)) = pm[first];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) *(u32x4*)(scr + 512 + 1024 * i + 16 * lane) = pm[first + 1 + i];
+#pragma unroll
+                    for (int i = 0; i < 5; ++i) reload(first + i);
+                }
+#pragma unroll
+                for (int c16 = 0; c16 < N16; ++c16) bw16[b][c16] = *(const u32x4*)(mine + 32 * c16 + 16 * hf);
+                if constexpr (N8 != 0) bw8[b] = *(const u32x2*)(mine + 32 * N16 + 8 * hf);
+            };
+            stage(0, 0);
+#pragma unroll
+            for (int q = 0; q < PX; ++q) {
+                __builtin_amdgcn_sched_barrier(0);
+                if (q + 1 < PX) stage(q + 1, (q + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int c16 = 0; c16 < N16; ++c16)
+#pragma unroll
+                    for (int hl = 0; hl < 2; ++hl)
+                        acc[q][0] = mfma_16<false>(AREG ? areg[c16 * 2 + hl] : A16[(c16 * 2 + hl) * 64 + lane], bw16[q & 1][c16], acc[q][0]);
+                if constexpr (N8 != 0) {
+#pragma unroll
+                    for (int hl = 0; hl < 2; ++hl)
+                        acc[q][0] = mfma_8<false>(AREG ? areg8[hl] : A8[hl * 64 + lane], bw8[q & 1], acc[q][0]);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
         if constexpr (F32) {
             // fp32 coefficients: the loaded words ARE the B operand (lane half hf holds
             // atom 2*step + hf of its pixels), no re-packing, exact fp32 products
@@ -802,7 +887,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             }
         }
 #pragma unroll
-        for (int c16 = 0; c16 < (LIST ? 0 : N16); ++c16) {   // (the list form has folded above)
+        for (int c16 = 0; c16 < (LIST || PMAJ ? 0 : N16); ++c16) {   // (the list and pixel-major forms have folded above)
             u32x4 av[NMB][2];
 #pragma unroll
             for (int mb = 0; mb < NMB; ++mb)
@@ -830,7 +915,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        if constexpr (N8 != 0 && !LIST) {
+        if constexpr (N8 != 0 && !LIST && !PMAJ) {
             u32x2 av[NMB][2];
 #pragma unroll
             for (int mb = 0; mb < NMB; ++mb)
@@ -868,6 +953,10 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         // read is base + immediate offset: e0 % SW < SW - 1: class e0 % SW + j of the same group; otherwise the
         // last class, or (j = 1) class 0 of the next group.
         unsigned ubo[2] = {0u, 0u};                    // as element offsets into U
+        if constexpr (PMAJ) {
+            // column 32 q + j + dx of an unswizzled tile: the lane enters as j
+            ubo[0] = ubo[1] = (unsigned)((unit_row(unit, wave) * WR + jr + hf * F::RH0) * P + jc);
+        }
         if constexpr (PERM) {
             const int jx = jc % 2, m = jc / 2;
             const int row0 = (unit_row(unit, wave) * WR + jr + hf * F::RH0) * P;
@@ -883,7 +972,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         float outp[C][PX];
 #pragma unroll
         for (int c = 0; c < C; ++c) {
-            if constexpr (PERM) {
+            if constexpr (PERM || PMAJ) {
                 // The slots share few patch values (they are s pixels apart): taken all at once a channel's
                 // LDS reads would hold three times the registers of the planar form.  One filter row at a
                 // time; the empty statement ties the next row's addresses to this row's sums.
@@ -898,7 +987,9 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 #pragma unroll
                         for (int dxv = 0; dxv < K; ++dxv) {
                             const int vv = dyv * K + dxv;
-                            if constexpr (PSM == 3) {
+                            if constexpr (PMAJ) {
+                                sq[q] = fmaf(acc[q][vv / 16][vv % 16], U[ubo[0] + c * UH * P + dyv * P + 32 * q + dxv], sq[q]);
+                            } else if constexpr (PSM == 3) {
                                 const int e = 3 * q + (unit % NSUB) + dxv;
                                 sq[q] = fmaf(acc[q][vv / 16][vv % 16], U[ubo[0] + c * UH * P + dyv * P + (e & 3) * NG + (e >> 2)], sq[q]);
                             } else {
@@ -939,10 +1030,12 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         //  X0 + 16 m + 8 hf + 4 j, once both units of the row are done)
         const int y = Y0 + unit_row(unit, wave) * WR + jr;
         // (scale 3: a lane's pixels start at X0 + 12 n; it stores the six adjacent ones at X0 + 12 n + 6 hf)
-        const int x = PSM == 3 ? X0 + 12 * jc : (PERM ? X0 + 4 * PSM * (jc / 2) : X0 + PX * jc);
+        // (pixel-major: half hf holds the lane's pixels 64 hf + j and 64 hf + 32 + j)
+        const int x = PMAJ ? X0 + jc : PSM == 3 ? X0 + 12 * jc : (PERM ? X0 + 4 * PSM * (jc / 2) : X0 + PX * jc);
         const bool valid = y < a.H && x < a.W;
         const unsigned plane_px = (unsigned)a.H * (unsigned)a.W;
-        const unsigned o0 = PSM == 3 ? (unsigned)y * (unsigned)a.W + x + hf * 6
+        const unsigned o0 = PMAJ ? (unsigned)y * (unsigned)a.W + x + hf * 64
+                          : PSM == 3 ? (unsigned)y * (unsigned)a.W + x + hf * 6
                           : PERM ? (unsigned)y * (unsigned)a.W + x + hf * (2 * PSM) + (PSM == 4 ? 4 : 2) * (jc % 2)
                                  : (unsigned)y * (unsigned)a.W + x + hf * (PX / 2);   // within the image
         char* const out_img = (char*)a.out + (size_t)cur.n * C * ((size_t)plane_px * (a.io_f16 ? 2 : 4));
@@ -1003,7 +1096,13 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             if (valid) {
 #endif
                 const unsigned oe = o0 + c * plane_px;
-                if constexpr (PSM == 4) {
+                if constexpr (PMAJ) {
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        if (a.io_f16) *(__half*)(out_img + (size_t)((oe + 32 * t) * 2u)) = narrow_f16(tot[t]);
+                        else *(float*)(out_img + (size_t)((oe + 32 * t) * 4u)) = tot[t];
+                    }
+                } else if constexpr (PSM == 4) {
                     if (a.io_f16) {
                         __half2 lo2, hi2;
                         lo2.x = narrow_f16(tot4[0]); lo2.y = narrow_f16(tot4[1]);
@@ -1082,9 +1181,10 @@ inline int compute_units() {
 template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT = CT_F16, int SMIN = 2, bool BIG = false,
           int PSM = 0>
 hipError_t launch_one(const AssembleArgs& a0, hipStream_t st) {
-    using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN, (PSM == 4 ? 2 : (PSM == 3 ? 3 : 1))>;
+    using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN, (PSM == 4 ? 2 : (PSM == 3 ? 3 : 1)), (PSM == 8 ? 1 : 0)>;
     if (a0.s < SMIN) return hipErrorInvalidValue;       // its LDS footprint buffers would be too small
-    if ((a0.pre_shuffle != 0) != (PSM != 0)) return hipErrorInvalidValue;
+    if ((a0.pre_shuffle != 0) != (PSM >= 1 && PSM <= 4) || (a0.pixel_major != 0) != (PSM == 8)) return hipErrorInvalidValue;
+    if (PSM == 8 && (a0.W % 128 != 0 || a0.L != 8 * NP8 || a0.n_fold != a0.L)) return hipErrorInvalidValue;
     // permuted pixel slots: a lane owns four whole LR columns, the image must end on such a group
     if ((PSM == 2 || PSM == 3 || PSM == 4) && (a0.s != PSM || a0.w % 4 != 0)) return hipErrorInvalidValue;
     AssembleArgs a = a0;

@@ -213,7 +213,20 @@ def test_pre_shuffle_layout_is_checked_on_the_host(lib):
     bad = ps_case()
     bad[1].c = 72 * 16 - 1
     assert plan(*bad, opts=o()) == -2
-    assert plan(*ps_case(), opts=sr.make_options(0, 0, 2)) == -3                          # unknown layout code
+    assert plan(*ps_case(), opts=sr.make_options(0, 0, 3)) == -3                          # unknown layout code
+    # pixel-major storage [N][H][W][L]: described like the planar tensor; the matrix-core kernel takes all of 72 fp16
+    # atoms of 5x5 on three channels with an HR width of whole 128-pixel units, the generic kernel everything else
+    pm = lambda kernel=sr.SR_KERNEL_AUTO, tile=0: sr.make_options(kernel, tile, sr.SR_COEFF_PIXEL_MAJOR)
+    assert plan(*case(w=64), opts=pm()) == sr.SR_KERNEL_MFMA
+    assert plan(*case(w=64), opts=pm(sr.SR_KERNEL_GENERIC)) == sr.SR_KERNEL_GENERIC
+    assert plan(*case(w=48), opts=pm()) == sr.SR_KERNEL_GENERIC                            # HR width 192
+    assert plan(*case(w=48), opts=pm(sr.SR_KERNEL_MFMA)) == -3
+    assert plan(*case(w=64), kept=[3, 9, 70], opts=pm()) == sr.SR_KERNEL_GENERIC
+    assert plan(*case(w=64), kept=list(range(72)), opts=pm()) == sr.SR_KERNEL_MFMA        # the identity list is no list
+    assert plan(*case(w=64), kept=list(range(71, -1, -1)), opts=pm()) == sr.SR_KERNEL_GENERIC
+    assert plan(*case(w=64), opts=pm(sr.SR_KERNEL_MFMA, 3)) == -3                          # no alternative tiles in this layout
+    for kw, pk in (({"cd": sr.SR_F32}, {}), ({"cd": sr.SR_BF16}, {}), ({"k": 7}, {"k": 7}), ({"C": 1}, {"C": 1}), ({"L": 64}, {"L": 64})):
+        assert plan(*case(w=64, **kw), **pk, opts=pm()) == sr.SR_KERNEL_GENERIC, kw
 
 
 def test_list_form_argument_checks(lib):
