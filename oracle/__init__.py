@@ -73,6 +73,10 @@ def _load():
         lib.orc_pixel_major_to_planar.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_vp]
         lib.orc_pixel_shuffle.restype = c_int
         lib.orc_pixel_shuffle.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_vp]
+        lib.orc_round_to_half.restype = c_dbl
+        lib.orc_round_to_half.argtypes = [c_dbl]
+        lib.orc_softmax_planes.restype = c_int
+        lib.orc_softmax_planes.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_vp]
         lib.orc_threads.restype = c_int
         lib.orc_set_threads.restype = c_int
         lib.orc_set_threads.argtypes = [c_int]
@@ -238,14 +242,37 @@ def pixel_major_to_planar(coeff_pm) -> np.ndarray:
     return out
 
 
+def round_to_half(v: float) -> float:
+    """``v`` rounded to the nearest binary16 value (ties to even), as a double."""
+    return _load().orc_round_to_half(float(v))
+
+
+def softmax_logits(logits, round_half: bool = True) -> np.ndarray:
+    """Coefficients from LOGITS (an extension, not in the paper): per pixel the softmax over the atoms of
+    ``logits`` [N][L][H][W] (any stored type) -> float64, same shape.  With ``round_half`` (the reading the
+    logits form takes) the exponentials ``exp(z - max)`` are rounded to binary16 before they are summed and
+    divided; without it this is the plain softmax."""
+    z = _stored(logits, "logits")
+    if z.ndim != 4:
+        raise ValueError("logits must be [N][L][H][W]")
+    n, L, H, W = z.shape
+    out = np.empty((n, L, H, W), dtype=np.float64)
+    if _load().orc_softmax_planes(_ptr(z), _DT[z.dtype], n, L, H, W, 1 if round_half else 0, _ptr(out)):
+        raise ValueError("orc_softmax_planes rejected its arguments")
+    return out
+
+
 def dict_assemble(lr, coeff, dictionary, scale: int, kept=None, gamma=None, a: float = -0.5,
-                  pre_shuffle: bool = False, pixel_major: bool = False) -> np.ndarray:
+                  pre_shuffle: bool = False, pixel_major: bool = False, logits: bool = False) -> np.ndarray:
     """The whole path: stage 1, then stages 3 + 4.  float64 [N][C][s*h][s*w].  With
     ``pre_shuffle`` the coefficients are what the network holds before its pixel-shuffle
     layer, [N][L*s*s][h][w]: that layer is applied first.  With ``pixel_major`` they are stored
-    [N][H][W][L] and are moved to planes first."""
+    [N][H][W][L] and are moved to planes first.  With ``logits`` the stored values are logits and the
+    coefficients their per-pixel softmax (see softmax_logits)."""
     if pixel_major:
         coeff = pixel_major_to_planar(coeff)
     if pre_shuffle:
         coeff = pixel_shuffle(coeff, scale)
+    if logits:
+        coeff = softmax_logits(coeff)
     return assemble(bicubic(lr, scale, a), coeff, dictionary, kept, gamma)

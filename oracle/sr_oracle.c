@@ -44,7 +44,9 @@
  * pixel-shuffle by a hand-written example, by a library routine and by the index
  * identity it is defined by (tests/test_oracle_shuffle.py); the per-pixel list form
  * by the pinned dense form on the scattered list, hand-made lists, repeated entries
- * and linearity (tests/test_oracle_topk.py).
+ * and linearity (tests/test_oracle_topk.py); the logits form by a hand-made example with exact
+ * values, a closed form (logarithms of integers), two libraries' softmax, the library's binary16
+ * cast for the rounding, shift invariance and large logits (tests/test_oracle_logits.py).
  * No function here is unpinned.
  */
 #include <math.h>
@@ -414,6 +416,67 @@ int orc_pixel_major_to_planar(const void *in, int esize, int n, int L, int H, in
                     size_t to = (((size_t)b * L + l) * H + y) * W + x;
                     memcpy(dst + to * esize, src + from * esize, (size_t)esize);
                 }
+    return 0;
+}
+
+/*
+ * A double rounded to the nearest IEEE binary16 value, ties to the even mantissa, as a double
+ * (finite |v| < 65520; below 2^-14 the binary16 values are the multiples of 2^-24).
+ */
+double orc_round_to_half(double v)
+{
+    if (v == 0.0 || isnan(v) || isinf(v))
+        return v;
+    int e;
+    (void)frexp(fabs(v), &e);                     /* |v| = f * 2^e, 0.5 <= f < 1 */
+    int ulp_exp = e - 11;                         /* 11 significant bits */
+    if (ulp_exp < -24)
+        ulp_exp = -24;                            /* subnormal range: fixed spacing */
+    /* v / ulp is exact (a power of two); nearbyint rounds halves to even in the default mode */
+    return ldexp(nearbyint(ldexp(v, -ulp_exp)), ulp_exp);
+}
+
+/*
+ * Coefficients handed over as LOGITS (an extension, not in the paper: the coefficient network of
+ * section II-B, stage 2, stops before a normalising last layer and the assembly path applies it).
+ * Per pixel, over the L atoms (z_l = stored logit of atom l, any stored type):
+ *
+ *     m     = max_l z_l
+ *     e_l   = exp(z_l - m)          rounded to binary16 if round_half != 0
+ *     Phi_l = e_l / sum_l e_l
+ *
+ * The rounding is the reading taken for this form: the exponentials enter the fold as 16-bit
+ * operands, like stored fp16 coefficients would, and the sum is the sum of the rounded values, so
+ * the Phi of a pixel still add up to one.  round_half == 0 gives the plain softmax (used to pin
+ * this function against a library's).  in: [n][L][H][W] stored values; out: the same shape, double.
+ */
+int orc_softmax_planes(const void *in, int dtype, int n, int L, int H, int W, int round_half, double *out)
+{
+    if (!in || !out || n < 0 || L < 1 || H < 0 || W < 0)
+        return -1;
+    size_t plane = (size_t)H * W;
+    for (int b = 0; b < n; ++b) {
+#pragma omp parallel for schedule(static)
+        for (long p = 0; p < (long)plane; ++p) {
+            size_t base = (size_t)b * L * plane + (size_t)p;
+            double m = load_elem(in, dtype, base);
+            for (int l = 1; l < L; ++l) {
+                double z = load_elem(in, dtype, base + (size_t)l * plane);
+                if (z > m)
+                    m = z;
+            }
+            double sum = 0.0;
+            for (int l = 0; l < L; ++l) {
+                double e = exp(load_elem(in, dtype, base + (size_t)l * plane) - m);
+                if (round_half)
+                    e = orc_round_to_half(e);
+                out[base + (size_t)l * plane] = e;
+                sum += e;
+            }
+            for (int l = 0; l < L; ++l)
+                out[base + (size_t)l * plane] /= sum;
+        }
+    }
     return 0;
 }
 

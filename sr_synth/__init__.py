@@ -17,6 +17,8 @@ Recipe
   * Coefficients [N][L][H][W]: per-pixel softmax over the L atoms of Gaussian
     logits, computed in fp32 and then cast to the storage dtype.  "N(m, v)" in
     the workload list is read as mean m, variance v.
+  * Logits form: the same Gaussian draws stored as they are (no softmax), cast to the
+    storage dtype.
   * Selective workload: a seeded set of 8 dominant atoms has logits N(4, 1) at
     every pixel, the rest N(0, 1).  The kept list is the 8 atoms with the
     largest mean coefficient over the frame (ties go to the lower index).
@@ -219,6 +221,29 @@ def make_coeff(wl: Workload, device="cpu", return_mean=False):
                 total += chunk.to(torch.float64).sum(dim=(1, 2))
     if return_mean:
         return out, (total / float(wl.n * H * W)).cpu().numpy()
+    return out
+
+
+def make_logits(wl: Workload, device="cpu"):
+    """[N][L][H][W] LOGITS in the storage dtype: the Gaussian draws of ``make_coeff`` (same seed, same
+    order) as they are before its softmax, for the path's logits form."""
+    dt = torch_dtype(wl.coeff_dtype)
+    H, W = wl.H, wl.W
+    out = torch.empty((wl.n, wl.L, H, W), device=device, dtype=dt)
+    g = _gen(device, _seed(wl, 2))
+    std = math.sqrt(wl.logit_var)
+    shift = None
+    if wl.dominant:
+        shift = torch.zeros((wl.L, 1, 1), device=device, dtype=torch.float32)
+        shift[torch.from_numpy(dominant_atoms(wl).astype(np.int64)).to(device)] = 4.0
+    for b in range(wl.n):
+        for y0 in range(0, H, _CHUNK_ROWS):
+            rows = min(_CHUNK_ROWS, H - y0)
+            logits = torch.randn((wl.L, rows, W), generator=g, device=device, dtype=torch.float32)
+            logits = logits * std + wl.logit_mean
+            if shift is not None:
+                logits = logits + shift
+            out[b, :, y0:y0 + rows, :] = logits.to(dt)
     return out
 
 

@@ -13,7 +13,8 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "sr_oracle.c")
 PINS = ["tests/test_oracle_bicubic.py", "tests/test_oracle_assemble.py", "tests/test_oracle_fp8.py",
-        "tests/test_oracle_shuffle.py", "tests/test_oracle_topk.py", "tests/test_oracle_pixel_major.py"]
+        "tests/test_oracle_shuffle.py", "tests/test_oracle_topk.py", "tests/test_oracle_pixel_major.py",
+        "tests/test_oracle_logits.py"]
 
 MUTATIONS = {
     "keys_inner_coefficient": ("- (a + 3.0) * t * t + 1.0", "- (a + 2.0) * t * t + 1.0"),
@@ -51,6 +52,23 @@ MUTATIONS = {
     "list_index_used_as_position": ("F[j] += v * dict[(size_t)l * kk + j];", "F[j] += v * dict[(size_t)t * kk + j];"),
     "list_keeps_last_entry_only": ("                    for (int j = 0; j < kk; ++j)\n                        F[j] += v * dict[(size_t)l * kk + j];",
                                    "                    for (int j = 0; j < kk; ++j)\n                        F[j] = v * dict[(size_t)l * kk + j];"),
+    "logits_maximum_not_subtracted": ("double e = exp(load_elem(in, dtype, base + (size_t)l * plane) - m);",
+                                      "double e = exp(load_elem(in, dtype, base + (size_t)l * plane));"),
+    "logits_exponentials_not_rounded": ("                if (round_half)\n                    e = orc_round_to_half(e);", "                (void)round_half;"),
+    "logits_rounded_after_the_division": (
+        "                out[base + (size_t)l * plane] /= sum;",
+        "                out[base + (size_t)l * plane] = round_half ? orc_round_to_half(out[base + (size_t)l * plane] / sum) : out[base + (size_t)l * plane] / sum;"),
+    "logits_sum_of_unrounded_exponentials": (
+        "                out[base + (size_t)l * plane] = e;\n                sum += e;",
+        "                sum += exp(load_elem(in, dtype, base + (size_t)l * plane) - m);\n                out[base + (size_t)l * plane] = e;"),
+    "logits_normalised_over_the_row": ("double z = load_elem(in, dtype, base + (size_t)l * plane);\n                if (z > m)",
+                                       "double z = load_elem(in, dtype, base + (size_t)l);\n                if (z > m)"),
+    "logits_base_two": ("double e = exp(load_elem(in, dtype, base + (size_t)l * plane) - m);",
+                        "double e = exp2(load_elem(in, dtype, base + (size_t)l * plane) - m);"),
+    "half_rounding_truncates": ("return ldexp(nearbyint(ldexp(v, -ulp_exp)), ulp_exp);", "return ldexp(trunc(ldexp(v, -ulp_exp)), ulp_exp);"),
+    "half_rounding_ties_away": ("return ldexp(nearbyint(ldexp(v, -ulp_exp)), ulp_exp);", "return ldexp(round(ldexp(v, -ulp_exp)), ulp_exp);"),
+    "half_rounding_ten_bits": ("int ulp_exp = e - 11;                         /* 11 significant bits */", "int ulp_exp = e - 10;"),
+    "half_rounding_no_subnormals": ("        ulp_exp = -24;                            /* subnormal range: fixed spacing */", "        ulp_exp = e - 11;"),
     "half_subnormal_exponent": ("v = ldexp((double)m, -24);", "v = ldexp((double)m, -25);"),
     "e4m3_bias": ("v = ldexp((double)(m + 8), e - 10);", "v = ldexp((double)(m + 8), e - 11);"),
     "e4m3_subnormals_flushed": ("v = ldexp((double)m, -9);", "v = 0.0;"),
