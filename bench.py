@@ -347,6 +347,9 @@ def main():
     ap.add_argument("--pixel-major", action="store_true",
                     help="hand the coefficients over stored pixel-major, [N][H][W][L] (what a channels-last producer writes; "
                          "a storage order beyond the paper); same values, same result")
+    ap.add_argument("--logits", action="store_true",
+                    help="hand the coefficients over as logits (an extension beyond the paper): the call applies the "
+                         "per-pixel softmax over the atoms itself")
     ap.add_argument("--tile-sweep", action="store_true",
                     help="also time every launch shape (tile, workgroup size, residency) the library has for this "
                          "workload: the measured stand-in for the paper's launch-shape search (section III-B)")
@@ -383,9 +386,13 @@ def main():
     dev = "cuda"
     inp = sr_synth.make_inputs(wl, dev)
     kept = inp.get("kept")
+    if args.logits:
+        assert not (args.pre_shuffle or args.pixel_major) and kept is None, "--logits: planar layout, all atoms"
+        inp["coeff"] = sr_synth.make_logits(wl, dev)
     coeffs = [inp["coeff"]]
     for r in range(1, N_ROTATE):
-        coeffs.append(sr_synth.make_coeff(sr_synth.scaled(wl, index=wl.index + 10 * r), dev))
+        make = sr_synth.make_logits if args.logits else sr_synth.make_coeff
+        coeffs.append(make(sr_synth.scaled(wl, index=wl.index + 10 * r), dev))
     outs = [torch.empty((wl.n, wl.c, wl.H, wl.W), device=dev, dtype=inp["lr"].dtype) for _ in range(2)]
     layout = sr.SR_COEFF_PRE_SHUFFLE if args.pre_shuffle else (sr.SR_COEFF_PIXEL_MAJOR if args.pixel_major else sr.SR_COEFF_PLANAR)
     if args.pixel_major:
@@ -397,7 +404,9 @@ def main():
         for r in range(N_ROTATE):
             coeffs[r] = sr_synth.to_pre_shuffle(coeffs[r], wl.scale)
         inp["coeff"] = coeffs[0]
-    opts = sr.make_options(args.kernel, args.tile, layout)
+    opts = sr.make_options(args.kernel, args.tile, layout, sr.SR_COEFF_LOGITS if args.logits else sr.SR_COEFF_VALUES)
+    if args.logits:
+        args.pre_shuffle = True            # the extra legs below time stored coefficients only
     plan = sr.sr_dict_assemble_plan(inp["lr"], coeffs[0], inp["dict"], wl.L, wl.k, wl.scale, wl.c,
                                     outs[0], kept=kept, opts=opts)
     assert plan > 0, sr.sr_strerror(plan)
@@ -464,8 +473,9 @@ def main():
         "config": {"workload": wl.name, "hr": f"{wl.W}x{wl.H}", "scale": wl.scale, "channels": wl.c,
                    "L": wl.L, "k": wl.k, "atoms_read": n_read, "batch": wl.n,
                    "kernel": {1: "generic", 2: "mfma"}[plan], "rotating_coeff_buffers": N_ROTATE,
-                   "coeff_layout": ("pixel_major [N][H][W][L]" if args.pixel_major else "pre_shuffle [N][L*s*s][h][w]")
-                                   if args.pre_shuffle else "planar [N][L][H][W]"},
+                   "coeff_layout": "planar [N][L][H][W]" if (args.logits or not args.pre_shuffle) else
+                                   ("pixel_major [N][H][W][L]" if args.pixel_major else "pre_shuffle [N][L*s*s][h][w]"),
+                   "coeff_kind": "logits (softmax over the atoms applied by the call)" if args.logits else "values"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(wl.name),
                      "traffic_source": (f"profiles/sr_mfma_{wl.name}_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an "

@@ -105,13 +105,26 @@ typedef enum {
                                   descriptor keeps c = L, h = s*h, w = s*w.        */
 } sr_coeff_layout;
 
+/* What the stored `coeff` values are (sr_options.coeff_kind). */
+typedef enum {
+    SR_COEFF_VALUES = 0,       /* the coefficients Phi themselves                  */
+    SR_COEFF_LOGITS = 1        /* logits z: the coefficients are their per-pixel
+                                  softmax over the L atoms, applied by the call.
+                                  An extension beyond the paper (its coefficient
+                                  network, section II-B stage 2, hands over Phi):
+                                  for a producer whose last layer would be that
+                                  normalisation, it saves a pass that reads and
+                                  writes the whole tensor.                         */
+} sr_coeff_kind;
+
 typedef struct {
     int kernel;                /* sr_kernel                                        */
     int tile;                  /* matrix-core kernel tile shape index, 0 = the
                                   library's default for the frame; see
                                   sr_dict_assemble_tile                            */
     int coeff_layout;          /* sr_coeff_layout                                  */
-    int reserved[5];           /* must be zero                                     */
+    int coeff_kind;            /* sr_coeff_kind                                    */
+    int reserved[4];           /* must be zero                                     */
 } sr_options;
 
 /*
@@ -181,6 +194,18 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
  * contiguous piece of memory.  Every kernel takes it; the matrix-core kernel for k = 5, C = 3, all
  * of L = 72 f16 atoms (no kept list), an HR width that is a multiple of 128 and under 4 GB of
  * coefficients per image, the generic kernel otherwise.
+ *
+ * opts->coeff_kind = SR_COEFF_LOGITS: `coeff` holds logits z (f32, f16 or bf16; any layout above) and the call
+ * computes, per pixel and over all L atoms,
+ *     m = max_l z_l,   e_l = exp(z_l - m) rounded to the nearest binary16 value,   Phi_l = e_l / sum_l e_l
+ * and then the assembly with these Phi: F_i = (sum_l e_l D_l) / (sum_l e_l).  The rounding is where the
+ * exponentials become 16-bit operands of the fold, as stored f16 coefficients would be; the sum runs over the
+ * rounded values, so a pixel's coefficients add up to one.  The exponential is evaluated in fp32 by the hardware
+ * (about one unit in the last place), so a value that lies next to a rounding boundary may round the other way
+ * than in exact arithmetic: one binary16 step in one coefficient.  A kept list or gamma is SR_ERR_UNSUPPORTED
+ * (the normalisation needs every atom), and so are f8 logits.  Logits of -infinity give a zero coefficient;
+ * NaN or +infinity logits give unspecified results.  The matrix-core kernel takes k = 5, C = 3, 49 to 72
+ * f16 planes in the planar order, under 4 GB per image; the generic kernel everything else.
  *
  * opts->tile (the launch-shape search of section III-B, Eq. 11-12, as a small set of compiled
  * tile shapes): index 0 is the library's default for the frame and is always accepted.  Other

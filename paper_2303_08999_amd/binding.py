@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libsrdict.so")
 SR_F32, SR_F16, SR_F8E4M3, SR_BF16, SR_U8 = 0, 1, 2, 3, 4
 SR_KERNEL_AUTO, SR_KERNEL_GENERIC, SR_KERNEL_MFMA = 0, 1, 2
 SR_COEFF_PLANAR, SR_COEFF_PRE_SHUFFLE, SR_COEFF_PIXEL_MAJOR = 0, 1, 2
+SR_COEFF_VALUES, SR_COEFF_LOGITS = 0, 1
 SR_MAX_ATOMS = 256
 
 EXPORTS = ("sr_dict_assemble", "sr_dict_assemble_selective", "sr_dict_assemble_ex", "sr_dict_assemble_list", "sr_dict_assemble_list_ex",
@@ -31,7 +32,7 @@ class sr_tensor(ctypes.Structure):
 
 class sr_options(ctypes.Structure):
     _fields_ = [("kernel", ctypes.c_int), ("tile", ctypes.c_int), ("coeff_layout", ctypes.c_int),
-                ("reserved", ctypes.c_int * 5)]
+                ("coeff_kind", ctypes.c_int), ("reserved", ctypes.c_int * 4)]
 
 
 class SrError(RuntimeError):
@@ -176,9 +177,9 @@ def sr_dict_assemble_selective(lr, coeff, dict, L, k, scale, channels, out, stre
     return out
 
 
-def make_options(kernel=SR_KERNEL_AUTO, tile=0, coeff_layout=SR_COEFF_PLANAR) -> sr_options:
+def make_options(kernel=SR_KERNEL_AUTO, tile=0, coeff_layout=SR_COEFF_PLANAR, coeff_kind=SR_COEFF_VALUES) -> sr_options:
     o = sr_options()
-    o.kernel, o.tile, o.coeff_layout = int(kernel), int(tile), int(coeff_layout)
+    o.kernel, o.tile, o.coeff_layout, o.coeff_kind = int(kernel), int(tile), int(coeff_layout), int(coeff_kind)
     return o
 
 

@@ -52,9 +52,13 @@ void make_plan(Plan& p, const sr_tensor* lr, const sr_tensor* coeff, const sr_te
     if (L < 1 || L > SR_MAX_ATOMS || channels < 1 || channels > SR_MAX_CHANNELS) {
         p.status = SR_ERR_UNSUPPORTED; return;
     }
-    if (opts && (opts->coeff_layout < SR_COEFF_PLANAR || opts->coeff_layout > SR_COEFF_PIXEL_MAJOR)) {
+    if (opts && (opts->coeff_layout < SR_COEFF_PLANAR || opts->coeff_layout > SR_COEFF_PIXEL_MAJOR ||
+                 opts->coeff_kind < SR_COEFF_VALUES || opts->coeff_kind > SR_COEFF_LOGITS)) {
         p.status = SR_ERR_UNSUPPORTED; return;
     }
+    // logits: the softmax runs over all L atoms, so there is no kept list; 8-bit logits are not taken
+    const bool logits = opts && opts->coeff_kind == SR_COEFF_LOGITS;
+    if (logits && (kept || gamma || coeff->dtype == SR_F8E4M3)) { p.status = SR_ERR_UNSUPPORTED; return; }
     if (lr->c != channels || out->c != channels ||
         dict->n != 1 || dict->c != L || dict->h != k || dict->w != k ||
         coeff->n != lr->n || out->n != lr->n ||
@@ -67,7 +71,7 @@ void make_plan(Plan& p, const sr_tensor* lr, const sr_tensor* coeff, const sr_te
         p.status = SR_ERR_UNSUPPORTED; return;
     }
     if (opts) {
-        for (int i = 0; i < 5; ++i)
+        for (int i = 0; i < 4; ++i)
             if (opts->reserved[i]) { p.status = SR_ERR_UNSUPPORTED; return; }
         if (opts->kernel < SR_KERNEL_AUTO || opts->kernel > SR_KERNEL_MFMA || opts->tile < 0) {
             p.status = SR_ERR_UNSUPPORTED; return;
@@ -103,6 +107,7 @@ void make_plan(Plan& p, const sr_tensor* lr, const sr_tensor* coeff, const sr_te
     a.H = out->h; a.W = out->w; a.s = scale; a.L = L;
     a.pre_shuffle = pre_shuffle ? 1 : 0;
     a.pixel_major = opts && opts->coeff_layout == SR_COEFF_PIXEL_MAJOR ? 1 : 0;
+    a.logits = logits ? 1 : 0;
 
     const int want = opts ? opts->kernel : SR_KERNEL_AUTO;
     const int tile = opts ? opts->tile : 0;

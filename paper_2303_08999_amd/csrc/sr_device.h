@@ -32,6 +32,7 @@ struct AssembleArgs {
     int T;                // list form only: entries per pixel
     int pre_shuffle;      // coefficients are [N][L*s*s][h][w] (before the network's pixel-shuffle), else [N][L][H][W]
     int pixel_major;      // coefficients are [N][H][W][L] (a pixel's L coefficients side by side)
+    int logits;           // `coeff` holds logits: the coefficients are their per-pixel softmax over the atoms
     int   kept[SR_MAX_ATOMS];    // plane read for folded atom i (identity when dense)
     float gamma[SR_MAX_ATOMS];   // its scale (1 when dense)
 };
@@ -59,6 +60,11 @@ struct bf16raw { unsigned short bits; };
 __device__ __forceinline__ float ld_as_float(const bf16raw* p, size_t i) {
     return __uint_as_float((unsigned)p[i].bits << 16);
 }
+// Logits form (coefficients = per-pixel softmax over the atoms of stored logits): the exponential of a logit z
+// with nm = logit_shift(the pixel's largest logit), in fp32; every kernel rounds it to fp16 before use.
+constexpr float LOG2E = 1.44269504088896340736f;
+__device__ __forceinline__ float logit_shift(float m) { return -m * LOG2E; }
+__device__ __forceinline__ float logit_exp(float z, float nm) { return __builtin_amdgcn_exp2f(fmaf(z, LOG2E, nm)); }
 __device__ __forceinline__ void st_from_float(float* p, size_t i, float v) { p[i] = v; }
 // fp32 -> fp16 with the fp32 value materialised first: the empty asm keeps the
 // compiler from folding the producing fma and the narrowing into one

@@ -41,6 +41,7 @@ __global__ __launch_bounds__(GNT) void k_assemble_generic(const AssembleArgs a) 
 
     // ---- stage 3: F = Phi_i D, all k^2 taps in registers -------------------
     float F[KK];
+    float esum = 0.0f;                                      // logits form: sum of the pixel's exponentials
 #pragma unroll
     for (int t = 0; t < KK; ++t) F[t] = 0.0f;
     if (valid) {
@@ -54,12 +55,29 @@ __global__ __launch_bounds__(GNT) void k_assemble_generic(const AssembleArgs a) 
         const TC* cbase = (const TC*)a.coeff + (size_t)n * a.L * plane + (a.pixel_major ? within * a.L : within);
         // eight atoms at a time: their coefficient loads are in flight together
         constexpr int NB = 8;
+        // logits instead of coefficients: a first pass over the pixel's planes for the largest logit
+        float nm = 0.0f;
+        if (a.logits) {
+            float m = ld_as_float(cbase, 0);
+            for (int i0 = 0; i0 < a.n_fold; i0 += NB) {
+                float z[NB];
+#pragma unroll
+                for (int b = 0; b < NB; ++b) z[b] = ld_as_float(cbase, (size_t)(i0 + b < a.n_fold ? i0 + b : a.n_fold - 1) * astride);
+#pragma unroll
+                for (int b = 0; b < NB; ++b) m = fmaxf(m, z[b]);
+            }
+            nm = logit_shift(m);
+        }
         for (int i0 = 0; i0 < a.n_fold; i0 += NB) {
             float phi[NB];
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 const int i = i0 + b < a.n_fold ? i0 + b : a.n_fold - 1;      // past the end: re-read, unused
                 phi[b] = ld_as_float(cbase, (size_t)a.kept[i] * astride) * a.gamma[i];
+                if (a.logits) {                             // (no kept list, gamma = 1): exponential, rounded to fp16
+                    phi[b] = __half2float(__float2half_rn(logit_exp(phi[b], nm)));
+                    if (i0 + b < a.n_fold) esum += phi[b];
+                }
             }
 #pragma unroll
             for (int b = 0; b < NB; ++b)
@@ -90,6 +108,7 @@ __global__ __launch_bounds__(GNT) void k_assemble_generic(const AssembleArgs a) 
 #pragma unroll
                 for (int dx = 0; dx < K; ++dx)
                     acc = fmaf(F[dy * K + dx], U[(ty + dy) * UW + tx + dx], acc);
+            if (a.logits) acc = acc * (1.0f / esum);
             st_from_float((TIO*)a.out, ((size_t)n * a.C + c) * plane + (size_t)Y * a.W + X, acc);
         }
         // The next channel's lrT/V writes do not touch U; two barriers separate

@@ -17,6 +17,7 @@ hipError_t launch_mfma_k5_big(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_bf16(const AssembleArgs& a, int k, int np8, hipStream_t st);
 hipError_t launch_mfma_k5_ps(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_k5_pm(const AssembleArgs& a, hipStream_t st);
+hipError_t launch_mfma_k5_lg(const AssembleArgs& a, hipStream_t st);
 
 namespace {
 
@@ -77,7 +78,7 @@ static bool has_tile_shapes(const AssembleArgs& a, int k, int np8, int coeff_dty
 // alternative shapes); false elsewhere.
 bool mfma_tile_shape(const AssembleArgs& a, int k, int coeff_dtype, int tile, int* tw, int* th, int* waves, int* groups) {
     const int np8 = np8_for(k, a.C, a.n_fold, coeff_dtype);
-    return has_tile_shapes(a, k, np8, coeff_dtype) && tile_shape_k5(a, tile, tw, th, waves, groups);
+    return !a.logits && has_tile_shapes(a, k, np8, coeff_dtype) && tile_shape_k5(a, tile, tw, th, waves, groups);
 }
 
 // pixels a lane loads with one vector load (its pixel group)
@@ -112,6 +113,10 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
         for (int i = 0; i < 72; ++i)
             if (a.kept[i] != i) return false;
     }
+    // logits instead of coefficients: one family built (5x5, three channels, 49 to 72 fp16 planes in the planar order)
+    if (a.logits && !(k == 5 && a.C == 3 && coeff_dtype == SR_F16 && np8 == 9 && a.n_fold == a.L && !a.pre_shuffle && !a.pixel_major &&
+                      !beyond_4gb(a, coeff_dtype) && tile == 0))
+        return false;
     // (bfloat16: the forms with permuted pixel slots only, i.e. LR widths that are multiples of 4, all atoms)
     if (a.pre_shuffle && !(k == 5 && a.C == 3 && (np8 == 1 || np8 == 9) && !beyond_4gb(a, coeff_dtype) && a.W % px == 0 &&
                            tile == 0 && (coeff_dtype == SR_F16 || (coeff_dtype == SR_BF16 && np8 == 9 && a.w % 4 == 0))))
@@ -131,6 +136,7 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
 hipError_t launch_mfma(const AssembleArgs& a, int k, bool io_f16, int tile, hipStream_t st) {
     (void)io_f16;
     const int np8 = np8_for(k, a.C, a.n_fold, a.coeff_dtype);
+    if (a.logits) return launch_mfma_k5_lg(a, st);
     if (a.pixel_major) return launch_mfma_k5_pm(a, st);
     if (a.pre_shuffle) return launch_mfma_k5_ps(a, np8, st);
     if (beyond_4gb(a, a.coeff_dtype))

@@ -1,0 +1,14 @@
+// Matrix-core kernel instantiations for coefficients handed over as LOGITS (see CT_LOGIT in sr_mfma_kernel.h; an
+// extension beyond the paper): 5x5 atoms, three channels, 49 to 72 fp16 planes (the capacity of nine groups of eight atoms), all of them folded.
+#include "sr_mfma_kernel.h"
+
+namespace srd {
+
+// The tiles of the fp16 form: 128 x 24 at scale 4 (half the LR footprint), 128 x 16 below.
+hipError_t launch_mfma_k5_lg(const AssembleArgs& a, hipStream_t st) {
+    if (a.C != 3 || a.L < 1 || a.L > 72) return hipErrorInvalidValue;
+    if (a.s == 4) return launch_one<5, 3, 9, 4, 1, 4, 6, 2, CT_LOGIT, 4>(a, st);
+    return launch_one<5, 3, 9, 4, 1, 4, 4, 2, CT_LOGIT, 2>(a, st);
+}
+
+}  // namespace srd

@@ -77,7 +77,14 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 // how the coefficients are stored (template argument CT of the kernel)
-constexpr int CT_F16 = 0, CT_F32 = 1, CT_F8 = 2, CT_BF16 = 3, CT_LIST8 = 4, CT_LIST16 = 5;
+constexpr int CT_F16 = 0, CT_F32 = 1, CT_F8 = 2, CT_BF16 = 3, CT_LIST8 = 4, CT_LIST16 = 5, CT_LOGIT = 6;
+// CT_LOGIT: the fp16 planes hold LOGITS (an extension beyond the paper, see sr_options.coeff_kind).  A unit's planes are
+// loaded as in the fp16 form; once they are all there the lane takes the maximum of its pixels' logits (packed fp16
+// maxima over its half of the planes, then one exchange with the other half), and where the fp16 form re-packs
+// (atom pair, pixel) with a byte permute it forms exp2((z - max) log2 e) in fp32 - one mixed-precision
+// multiply-add on the stored half and one exponential per value - and packs two of them, rounded to fp16, as the
+// operand.  One padding row of the dictionary operand is all ones, so the matrix cores also return the sum of the
+// exponentials of every pixel, in both lane halves; stage 4 multiplies its partial sums by the reciprocal.
 // CT_LIST8 / CT_LIST16: no dense planes; every pixel brings a list of up to 8 / 16 (atom index, fp16 value)
 // entries (an extension beyond the paper, see sr_dict_assemble_list).  Each wavefront owns an LDS scratch
 // [group of 8 atoms][32 pixels][8 atoms] fp16, all zero between uses.  Pixel slot by pixel slot it scatters
@@ -95,6 +102,7 @@ constexpr int LIST_MAX_ENTRIES = 16;
 template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int CT = CT_F16, int SMIN = 2, int NSUB = 1, int SWZ = 0>
 struct Cfg {
     static constexpr bool F32 = CT == CT_F32, F8 = CT == CT_F8, BF = CT == CT_BF16, LIST = CT == CT_LIST8 || CT == CT_LIST16;
+    static constexpr bool LG = CT == CT_LOGIT;
     static constexpr int LH = CT == CT_LIST8 ? 4 : 8;  // list form: entries a lane half loads
     static constexpr int LSW = 4 * NP8 * 32;           // list form: scratch words per wavefront
     static constexpr int KK = K * K, R = (K - 1) / 2;
@@ -200,6 +208,22 @@ __device__ __forceinline__ unsigned pack_pair(unsigned plane_even, unsigned plan
     return __builtin_amdgcn_perm(plane_odd, plane_even, (q & 1) ? 0x07060302u : 0x05040100u);
 }
 
+// logits form: (atom pair, pixel q) as the exponentials exp2(z * log2(e) + nm) of the two planes' logits, rounded to fp16
+__device__ __forceinline__ unsigned exp_pair(unsigned plane_even, unsigned plane_odd, int q, float nm) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    const f2 e = {logit_exp((float)__builtin_bit_cast(h2, plane_even)[q & 1], nm),
+                  logit_exp((float)__builtin_bit_cast(h2, plane_odd)[q & 1], nm)};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(e, h2));      // round to nearest even
+}
+// packed fp16 maximum of stored values (no canonicalising pass over the operands first)
+__device__ __forceinline__ _Float16 __attribute__((ext_vector_type(2))) pk_max_f16(_Float16 __attribute__((ext_vector_type(2))) x,
+                                                                                 _Float16 __attribute__((ext_vector_type(2))) y) {
+    _Float16 __attribute__((ext_vector_type(2))) r;
+    asm("v_pk_max_f16 %0, %1, %2" : "=v"(r) : "v"(x), "v"(y));
+    return r;
+}
+
 // filter tap served by MFMA row i of block mb, or -1 (padding / dummy row)
 template <int K>
 __device__ __forceinline__ int tap_of_row(int i, int mb) {
@@ -209,6 +233,13 @@ __device__ __forceinline__ int tap_of_row(int i, int mb) {
     if (vv >= NSLOT) return -1;
     const int dy = half * RH0 + vv / K, dx = vv % K;
     return dy < K ? dy * K + dx : -1;
+}
+
+// logits form: the MFMA row (one per lane half) that is all ones: the first padding row of the block that holds it
+template <int K>
+__device__ __forceinline__ bool sum_row(int i, int mb) {
+    constexpr int NSLOT = ((K + 1) / 2) * K;
+    return 16 * mb + (((i >> 3) << 2) | (i & 3)) == NSLOT;
 }
 
 struct TilePos { int n, ty, tx; };
@@ -264,7 +295,8 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     constexpr int NSUB = PSM == 4 ? 2 : (PSM == 3 ? 3 : 1);   // units per tile row
     constexpr bool PMAJ = PSM == 8;                // coefficients stored pixel-major, [H][W][L]
     using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN, NSUB, (PMAJ ? 1 : 0)>;
-    constexpr bool F32 = F::F32, F8 = F::F8, BF = F::BF, LIST = F::LIST;
+    constexpr bool F32 = F::F32, F8 = F::F8, BF = F::BF, LIST = F::LIST, LG = F::LG;
+    static_assert(!LG || (PX == 4 && PSM == 0 && !BIG && F::NSLOT < 16 * F::NMB), "logits form: fp16 planes, four pixels per lane, a free MFMA row");
     constexpr int LH = F::LH;                      // list entries a lane half loads
     static_assert(!LIST || (PX == 4 && WR == 1 && !BIG && PSM == 0 && NU % 2 == 0), "list form: four pixels per lane, one row per unit");
     constexpr bool PS = PSM == 1;                  // one 16-bit load per pixel
@@ -356,9 +388,13 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     for (int e = tid0; e < N16 * NMB * 64; e += NT) {
         const int l = e & 63, blk = e >> 6, mb = blk % NMB, c16 = blk / NMB;
         const int tap = tap_of_row<K>(l & 31, mb);
+        const bool ones = LG && sum_row<K>(l & 31, mb);       // logits form: this row sums the exponentials
         float dv[8];
 #pragma unroll
-        for (int jj = 0; jj < 8; ++jj) dv[jj] = dval(16 * c16 + 8 * (l >> 5) + jj, tap);
+        for (int jj = 0; jj < 8; ++jj) {
+            const int idx = 16 * c16 + 8 * (l >> 5) + jj;
+            dv[jj] = ones ? (idx < a.n_fold ? 1.0f : 0.0f) : dval(idx, tap);
+        }
         u32x4 hi, lo;
         split_hi_lo<BF, 8>(dv, hi, lo);
         A16[(blk * 2 + 0) * 64 + l] = hi;
@@ -368,9 +404,13 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         for (int e = tid0; e < NMB * 64; e += NT) {
             const int l = e & 63, mb = e >> 6;
             const int tap = tap_of_row<K>(l & 31, mb);
+            const bool ones = LG && sum_row<K>(l & 31, mb);
             float dv[4];
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) dv[jj] = dval(16 * N16 + 4 * (l >> 5) + jj, tap);
+            for (int jj = 0; jj < 4; ++jj) {
+                const int idx = 16 * N16 + 4 * (l >> 5) + jj;
+                dv[jj] = ones ? (idx < a.n_fold ? 1.0f : 0.0f) : dval(idx, tap);
+            }
             u32x2 hi, lo;
             split_hi_lo<BF, 4>(dv, hi, lo);
             A8[(mb * 2 + 0) * 64 + l] = hi;
@@ -886,6 +926,26 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 if ((st & 3) == 3) __builtin_amdgcn_sched_barrier(0);
             }
         }
+        // logits form: -max * log2(e) of the lane's four pixels, over all planes (both lane halves)
+        float nm[PX];
+        if constexpr (LG) {
+            typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+            h2 mx[PX / 2];
+#pragma unroll
+            for (int m = 0; m < PX / 2; ++m) mx[m] = __builtin_bit_cast(h2, raw_word(raw[0], m));
+#pragma unroll
+            for (int i = 1; i < F::NLOAD; ++i)
+#pragma unroll
+                for (int m = 0; m < PX / 2; ++m) mx[m] = pk_max_f16(mx[m], __builtin_bit_cast(h2, raw_word(raw[i], m)));
+#pragma unroll
+            for (int m = 0; m < PX / 2; ++m) {
+                const unsigned bits = __builtin_bit_cast(unsigned, mx[m]);
+                const auto sw = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);   // one of the two is the other half's
+                mx[m] = pk_max_f16(__builtin_bit_cast(h2, (unsigned)sw[0]), __builtin_bit_cast(h2, (unsigned)sw[1]));
+            }
+#pragma unroll
+            for (int q = 0; q < PX; ++q) nm[q] = logit_shift((float)mx[q >> 1][q & 1]);
+        }
 #pragma unroll
         for (int c16 = 0; c16 < (LIST || PMAJ ? 0 : N16); ++c16) {   // (the list and pixel-major forms have folded above)
             u32x4 av[NMB][2];
@@ -901,7 +961,9 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             for (int q = 0; q < PX; ++q) {
                 u32x4 bw;
 #pragma unroll
-                for (int m = 0; m < 4; ++m) bw[m] = pack_pair(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q);
+                for (int m = 0; m < 4; ++m)
+                    bw[m] = LG ? exp_pair(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q, nm[q])
+                               : pack_pair(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q);
 #pragma unroll
                 for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
@@ -929,7 +991,9 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             for (int q = 0; q < PX; ++q) {
                 u32x2 bw;
 #pragma unroll
-                for (int m = 0; m < 2; ++m) bw[m] = pack_pair(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q);
+                for (int m = 0; m < 2; ++m)
+                    bw[m] = LG ? exp_pair(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q, nm[q])
+                               : pack_pair(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q);
 #pragma unroll
                 for (int mb = 0; mb < NMB; ++mb)
 #pragma unroll
@@ -970,6 +1034,11 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             }
         }
         float outp[C][PX];
+        float rinv[PX];                                // logits form: one over the sum of the pixel's exponentials
+        if constexpr (LG) {
+#pragma unroll
+            for (int q = 0; q < PX; ++q) rinv[q] = 1.0f / acc[q][F::NSLOT / 16][F::NSLOT % 16];
+        }
 #pragma unroll
         for (int c = 0; c < C; ++c) {
             if constexpr (PERM || PMAJ) {
@@ -1015,7 +1084,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                         const int off = c * UH * P + dyv * P + ((q + dxv) % PX) * NG + (q + dxv) / PX;
                         s = fmaf(acc[q][vv / 16][vv % 16], ub[off], s);
                     }
-                    outp[c][q] = s;
+                    outp[c][q] = LG ? s * rinv[q] : s;
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -1184,6 +1253,8 @@ hipError_t launch_one(const AssembleArgs& a0, hipStream_t st) {
     using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN, (PSM == 4 ? 2 : (PSM == 3 ? 3 : 1)), (PSM == 8 ? 1 : 0)>;
     if (a0.s < SMIN) return hipErrorInvalidValue;       // its LDS footprint buffers would be too small
     if ((a0.pre_shuffle != 0) != (PSM >= 1 && PSM <= 4) || (a0.pixel_major != 0) != (PSM == 8)) return hipErrorInvalidValue;
+    // logits: a softmax over every atom, so every plane is folded
+    if ((a0.logits != 0) != (CT == CT_LOGIT) || (a0.logits && a0.n_fold != a0.L)) return hipErrorInvalidValue;
     if (PSM == 8 && (a0.W % 128 != 0 || a0.L != 8 * NP8 || a0.n_fold != a0.L)) return hipErrorInvalidValue;
     // permuted pixel slots: a lane owns four whole LR columns, the image must end on such a group
     if ((PSM == 2 || PSM == 3 || PSM == 4) && (a0.s != PSM || a0.w % 4 != 0)) return hipErrorInvalidValue;

@@ -229,6 +229,29 @@ def test_pre_shuffle_layout_is_checked_on_the_host(lib):
         assert plan(*case(w=64, **kw), **pk, opts=pm()) == sr.SR_KERNEL_GENERIC, kw
 
 
+def test_logits_option_is_checked_on_the_host(lib):
+    """coeff_kind = SR_COEFF_LOGITS: the softmax needs every atom, so no kept list; f32, f16 or bf16 logits."""
+    lg = lambda kernel=sr.SR_KERNEL_AUTO, tile=0, layout=sr.SR_COEFF_PLANAR: sr.make_options(kernel, tile, layout, sr.SR_COEFF_LOGITS)
+    assert plan(*case(), opts=lg()) == sr.SR_KERNEL_MFMA
+    assert plan(*case(), opts=lg(sr.SR_KERNEL_GENERIC)) == sr.SR_KERNEL_GENERIC
+    assert plan(*case(L=65), L=65, opts=lg()) == sr.SR_KERNEL_MFMA
+    assert plan(*case(L=49), L=49, opts=lg()) == sr.SR_KERNEL_MFMA                       # the capacity of nine groups of eight
+    for kw, pk in (({"cd": sr.SR_F32}, {}), ({"cd": sr.SR_BF16}, {}), ({"k": 7}, {"k": 7}), ({"C": 1}, {"C": 1}),
+                   ({"L": 48}, {"L": 48}), ({"L": 100}, {"L": 100})):
+        assert plan(*case(**kw), **pk, opts=lg()) == sr.SR_KERNEL_GENERIC, kw
+        assert plan(*case(**kw), **pk, opts=lg(sr.SR_KERNEL_MFMA)) == -3, kw
+    assert plan(*case(), kept=[3, 9, 70], opts=lg()) == -3
+    assert plan(*case(), kept=list(range(72)), opts=lg()) == -3                          # not even the identity list
+    assert plan(*case(cd=sr.SR_F8E4M3), opts=lg()) == -3
+    assert plan(*case(), opts=lg(sr.SR_KERNEL_MFMA, 6)) == -3                            # no alternative tiles in this form
+    assert plan(*case(), opts=sr.make_options(0, 0, 0, 2)) == -3                         # unknown kind
+    assert plan(*case(w=64), opts=lg(layout=sr.SR_COEFF_PIXEL_MAJOR)) == sr.SR_KERNEL_GENERIC
+    assert plan(*case(w=64), opts=lg(sr.SR_KERNEL_MFMA, 0, sr.SR_COEFF_PIXEL_MAJOR)) == -3
+    o = sr.make_options(0, 0, 0, sr.SR_COEFF_LOGITS)
+    o.reserved[3] = 1
+    assert plan(*case(), opts=o) == -3                                                   # reserved fields stay zero
+
+
 def test_list_form_argument_checks(lib):
     """sr_dict_assemble_list(lr, index, value, dict, L, k, scale, channels, entries, out, stream)"""
     def lcase(L=72, k=5, s=4, C=3, h=8, w=16, T=8, vd=sr.SR_F16, io=sr.SR_F32, idt=sr.SR_U8):
