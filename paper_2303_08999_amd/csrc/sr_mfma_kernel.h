@@ -1037,7 +1037,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         float rinv[PX];                                // logits form: one over the sum of the pixel's exponentials
         if constexpr (LG) {
 #pragma unroll
-            for (int q = 0; q < PX; ++q) rinv[q] = 1.0f / acc[q][F::NSLOT / 16][F::NSLOT % 16];
+            for (int q = 0; q < PX; ++q) rinv[q] = __builtin_amdgcn_rcpf(acc[q][F::NSLOT / 16][F::NSLOT % 16]);   // the sum is at least 1
         }
 #pragma unroll
         for (int c = 0; c < C; ++c) {

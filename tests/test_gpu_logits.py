@@ -3,14 +3,13 @@ HIP path applies the per-pixel softmax over the atoms itself, its exponentials r
 and the fold, and must give what the oracle gives for that reading.
 
 Tolerance.  Both sides round exp(z - max) to binary16; the oracle evaluates it in double, the GPU in fp32 with the
-hardware's exponential (about 1 unit in the last place after a multiply-add whose rounding error grows with
-|z - max|: a relative error of up to ~1e-6).  A value within that distance of a rounding boundary, about one in
-500, rounds the other way: one binary16 step, at most 2^-10 relative, in that coefficient, which moves the output by
-Phi_l * 2^-10 * |D_l.B - y|.  So
+hardware's exponential after one multiply-add (a relative error of a few 1e-7).  A value within that distance of a
+rounding boundary, about one in a thousand, rounds the other way: one binary16 step, at most 2^-10 relative, in that
+coefficient, which moves the output by Phi_l * 2^-10 * |D_l.B - y|.  So
   * every element: |gpu - ref| <= LOGIT_STEP * max(1, |ref|), LOGIT_STEP = 2.5e-4 (a step in a coefficient of 0.25
-    against a response 1 away from the output; the workloads' largest coefficients are 0.1 to 0.3), plus half an fp16
-    unit for an fp16 image,
-  * nearly all elements are untouched by a step: at most 2 % may exceed the 2e-5 rule of stored fp16 coefficients,
+    against a response 1 away from the output), plus half an fp16 unit for an fp16 image,
+  * nearly all elements are untouched by a step in a large coefficient: at most one in a thousand may exceed the 2e-5
+    rule of stored fp16 coefficients (measured on frames of 92 000 pixels: none does, the worst error is 6e-6),
   * and the GPU must be closer to this oracle than to the plain softmax without the rounding (a sharpness check:
     the two differ by 2^-12 relative per coefficient)."""
 import numpy as np
@@ -43,7 +42,7 @@ def assert_logits_parity(got, ref, out_f16, what):
     worst = float((err / np.maximum(1.0, np.abs(ref))).max(initial=0.0))
     assert (err <= LOGIT_STEP * np.maximum(1.0, np.abs(ref)) + half_ulp).all(), f"{what}: worst error {worst:.3e}"
     beyond = float((err > parity_bound(ref, "f16", out_f16)).mean()) if err.size else 0.0
-    assert beyond <= 0.02, f"{what}: {100 * beyond:.2f} % of the elements are beyond the 2e-5 rule"
+    assert beyond <= 1e-3, f"{what}: {100 * beyond:.3f} % of the elements are beyond the 2e-5 rule"
     return worst, beyond
 
 
