@@ -387,7 +387,7 @@ def main():
     inp = sr_synth.make_inputs(wl, dev)
     kept = inp.get("kept")
     if args.logits:
-        assert not (args.pre_shuffle or args.pixel_major) and kept is None, "--logits: planar layout, all atoms"
+        assert kept is None, "--logits: the softmax runs over all atoms"
         inp["coeff"] = sr_synth.make_logits(wl, dev)
     coeffs = [inp["coeff"]]
     for r in range(1, N_ROTATE):
@@ -473,8 +473,8 @@ def main():
         "config": {"workload": wl.name, "hr": f"{wl.W}x{wl.H}", "scale": wl.scale, "channels": wl.c,
                    "L": wl.L, "k": wl.k, "atoms_read": n_read, "batch": wl.n,
                    "kernel": {1: "generic", 2: "mfma"}[plan], "rotating_coeff_buffers": N_ROTATE,
-                   "coeff_layout": "planar [N][L][H][W]" if (args.logits or not args.pre_shuffle) else
-                                   ("pixel_major [N][H][W][L]" if args.pixel_major else "pre_shuffle [N][L*s*s][h][w]"),
+                   "coeff_layout": {sr.SR_COEFF_PLANAR: "planar [N][L][H][W]", sr.SR_COEFF_PIXEL_MAJOR: "pixel_major [N][H][W][L]",
+                                    sr.SR_COEFF_PRE_SHUFFLE: "pre_shuffle [N][L*s*s][h][w]"}[layout],
                    "coeff_kind": "logits (softmax over the atoms applied by the call)" if args.logits else "values"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(wl.name),

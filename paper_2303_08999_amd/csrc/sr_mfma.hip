@@ -114,8 +114,9 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
             if (a.kept[i] != i) return false;
     }
     // logits instead of coefficients: one family built (5x5, three channels, 49 to 72 fp16 planes in the planar order)
-    if (a.logits && !(k == 5 && a.C == 3 && coeff_dtype == SR_F16 && np8 == 9 && a.n_fold == a.L && !a.pre_shuffle && !a.pixel_major &&
-                      !beyond_4gb(a, coeff_dtype) && tile == 0))
+    // (in the layout before the pixel-shuffle: its permuted-slot forms, LR widths that are multiples of 4)
+    if (a.logits && !(k == 5 && a.C == 3 && coeff_dtype == SR_F16 && np8 == 9 && a.n_fold == a.L && !a.pixel_major &&
+                      (!a.pre_shuffle || a.w % 4 == 0) && !beyond_4gb(a, coeff_dtype) && tile == 0))
         return false;
     // (bfloat16: the forms with permuted pixel slots only, i.e. LR widths that are multiples of 4, all atoms)
     if (a.pre_shuffle && !(k == 5 && a.C == 3 && (np8 == 1 || np8 == 9) && !beyond_4gb(a, coeff_dtype) && a.W % px == 0 &&

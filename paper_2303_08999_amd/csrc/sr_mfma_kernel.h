@@ -296,12 +296,13 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     constexpr bool PMAJ = PSM == 8;                // coefficients stored pixel-major, [H][W][L]
     using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN, NSUB, (PMAJ ? 1 : 0)>;
     constexpr bool F32 = F::F32, F8 = F::F8, BF = F::BF, LIST = F::LIST, LG = F::LG;
-    static_assert(!LG || (PX == 4 && PSM == 0 && !BIG && F::NSLOT < 16 * F::NMB), "logits form: fp16 planes, four pixels per lane, a free MFMA row");
+    static_assert(!LG || (PX == 4 && (PSM == 0 || PSM == 2 || PSM == 3 || PSM == 4) && !BIG && F::NSLOT < 16 * F::NMB),
+                  "logits form: fp16 planes (or the permuted-slot forms of the layout before the pixel-shuffle), four pixels per lane, a free MFMA row");
     constexpr int LH = F::LH;                      // list entries a lane half loads
     static_assert(!LIST || (PX == 4 && WR == 1 && !BIG && PSM == 0 && NU % 2 == 0), "list form: four pixels per lane, one row per unit");
     constexpr bool PS = PSM == 1;                  // one 16-bit load per pixel
     constexpr bool PERM = PSM == 2 || PSM == 3 || PSM == 4;    // permuted pixel slots
-    static_assert(PSM == 0 || ((CT == CT_F16 || (CT == CT_BF16 && PSM != 1)) && !BIG && PX == 4),
+    static_assert(PSM == 0 || ((CT == CT_F16 || ((CT == CT_BF16 || CT == CT_LOGIT) && PSM != 1 && PSM != 8)) && !BIG && PX == 4),
                   "pre-shuffle layout: 16-bit coefficients, four pixels per lane");
     static_assert(!PMAJ || (CT == CT_F16 && WR == 1 && NP8 == 9), "pixel-major coefficients: 72 fp16 atoms, one row per unit");
     static_assert(!PERM || (WR == 1 && SMIN >= PSM), "permuted slots: one row per wavefront and unit");
@@ -1073,7 +1074,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                     asm volatile("" : "+v"(ubo[0]), "+v"(ubo[1]), "+v"(sq[0]), "+v"(sq[1]), "+v"(sq[2]), "+v"(sq[3]));
                 }
 #pragma unroll
-                for (int q = 0; q < PX; ++q) outp[c][q] = sq[q];
+                for (int q = 0; q < PX; ++q) outp[c][q] = LG ? sq[q] * rinv[q] : sq[q];
             } else {
 #pragma unroll
                 for (int q = 0; q < PX; ++q) {

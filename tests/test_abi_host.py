@@ -245,6 +245,14 @@ def test_logits_option_is_checked_on_the_host(lib):
     assert plan(*case(cd=sr.SR_F8E4M3), opts=lg()) == -3
     assert plan(*case(), opts=lg(sr.SR_KERNEL_MFMA, 6)) == -3                            # no alternative tiles in this form
     assert plan(*case(), opts=sr.make_options(0, 0, 0, 2)) == -3                         # unknown kind
+    def ps_case(s=4, w=16):
+        lr, coeff, d, out = case(s=s, w=w)
+        coeff.c, coeff.h, coeff.w = 72 * s * s, 8, w
+        return lr, coeff, d, out
+    for s in (2, 3, 4):                                                                  # before the pixel-shuffle: LR widths that are multiples of 4
+        assert plan(*ps_case(s), s=s, opts=lg(layout=sr.SR_COEFF_PRE_SHUFFLE)) == sr.SR_KERNEL_MFMA
+    assert plan(*ps_case(4, 18), opts=lg(layout=sr.SR_COEFF_PRE_SHUFFLE)) == sr.SR_KERNEL_GENERIC
+    assert plan(*ps_case(4, 18), opts=lg(sr.SR_KERNEL_MFMA, 0, sr.SR_COEFF_PRE_SHUFFLE)) == -3
     assert plan(*case(w=64), opts=lg(layout=sr.SR_COEFF_PIXEL_MAJOR)) == sr.SR_KERNEL_GENERIC
     assert plan(*case(w=64), opts=lg(sr.SR_KERNEL_MFMA, 0, sr.SR_COEFF_PIXEL_MAJOR)) == -3
     o = sr.make_options(0, 0, 0, sr.SR_COEFF_LOGITS)

@@ -92,8 +92,27 @@ def test_logits_against_the_oracle(oracle, case):
     assert takes == (cd == "f16" and C == 3 and k == 5 and 49 <= L <= 72)
 
 
+@pytest.mark.parametrize("shape", [(1, 23, 64, 4, 72), (2, 19, 96, 3, 72), (1, 21, 64, 2, 72), (1, 9, 36, 3, 65), (1, 30, 68, 4, 50)],
+                         ids=lambda c: "N%dh%dw%ds%dL%d" % c)
+def test_logits_before_the_pixel_shuffle_on_the_matrix_cores(oracle, shape):
+    """What the network's last convolution writes when the normalisation is left to the call: logits in the layout
+    before the pixel-shuffle.  Against the oracle (shuffle, then softmax, then the definition) and, bit for bit,
+    against the call with the shuffled logits."""
+    N, h, w, s, L = shape
+    wl = sr_synth.Workload("lg", 57, N, 3, h, w, s, L, 5, "f16", "f32", 0.0, 1.5)
+    inp = sr_synth.make_inputs(wl, DEV)
+    z = sr_synth.make_logits(wl, DEV)
+    pre = sr_synth.to_pre_shuffle(z, s)
+    hi = host(inp)
+    ref = oracle.dict_assemble(hi["lr"], sr_synth.stored_numpy(pre), hi["dict"], s, logits=True, pre_shuffle=True)
+    got = run(inp, wl, pre, MFMA, sr.SR_COEFF_PRE_SHUFFLE)
+    assert got is not None and not torch.isnan(got).any()
+    assert_logits_parity(got.cpu().numpy(), ref, False, "pre-shuffle logits")
+    assert torch.equal(got, run(inp, wl, z, MFMA))
+
+
 def test_logits_in_the_other_layouts_run_on_the_generic_kernel(oracle):
-    wl = sr_synth.Workload("lg", 54, 1, 3, 12, 32, 4, 72, 5, "f16", "f32", 0.0, 1.0)
+    wl = sr_synth.Workload("lg", 54, 1, 3, 12, 30, 4, 72, 5, "f16", "f32", 0.0, 1.0)   # LR width not a multiple of 4
     inp = sr_synth.make_inputs(wl, DEV)
     z = sr_synth.make_logits(wl, DEV)
     hi = host(inp)
@@ -147,6 +166,10 @@ def test_4k_frame_of_logits(oracle):
     got = run(inp, wl, z, MFMA)
     assert got is not None and torch.isfinite(got).all()
     assert (got - dense).abs().max().item() < 1e-3
+    # the same logits in the layout before the network's pixel-shuffle: the same bits
+    pre = sr_synth.to_pre_shuffle(z, wl.scale)
+    assert torch.equal(run(inp, wl, pre, MFMA, sr.SR_COEFF_PRE_SHUFFLE), got)
+    del pre
     rng = np.random.default_rng(14)
     npts = 3000
     pts = np.stack([np.zeros(npts, dtype=np.int64), rng.integers(0, wl.H, npts), rng.integers(0, wl.W, npts)], axis=1)
