@@ -459,8 +459,11 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(wall / args.steps * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": ("bf16" if wl.coeff_dtype == "bf16" else "f16") if (plan == 2 and wl.coeff_dtype in ("f16", "f8", "bf16")) else "f32",
+        "dtype": ("bf16" if (wl.coeff_dtype == "bf16" and not args.logits) else "f16") if (plan == 2 and wl.coeff_dtype in ("f16", "f8", "bf16")) else "f32",
         "arithmetic": ("f32 vector ALU" if plan != 2 else
+                       f"{wl.coeff_dtype} logits -> exp2((z - max) log2 e) in f32, rounded to f16 -> x f16 (hi+lo) dictionary on MFMA "
+                       "with f32 accumulation, a row of ones returning the sum of the exponentials; f32 up-sampling and filtering"
+                       if args.logits else
                        "f16 coefficients x f16 (hi+lo) dictionary on MFMA with f32 accumulation; f32 up-sampling "
                        "and filtering" if wl.coeff_dtype == "f16" else
                        "coefficients stored as 8-bit E4M3, widened exactly to f16 in registers, x f16 (hi+lo) "

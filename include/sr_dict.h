@@ -205,7 +205,7 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
  * than in exact arithmetic: one binary16 step in one coefficient.  A kept list or gamma is SR_ERR_UNSUPPORTED
  * (the normalisation needs every atom), and so are f8 logits.  Logits of -infinity give a zero coefficient;
  * NaN or +infinity logits give unspecified results.  The matrix-core kernel takes k = 5, C = 3, 49 to 72
- * f16 atoms in the planar order or (LR width a multiple of 4) in the order before the pixel-shuffle, under 4 GB
+ * f16 or bf16 atoms in the planar order or (LR width a multiple of 4) in the order before the pixel-shuffle, under 4 GB
  * per image; the generic kernel everything else.
  *
  * opts->tile (the launch-shape search of section III-B, Eq. 11-12, as a small set of compiled

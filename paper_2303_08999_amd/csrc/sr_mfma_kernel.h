@@ -77,7 +77,7 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 // how the coefficients are stored (template argument CT of the kernel)
-constexpr int CT_F16 = 0, CT_F32 = 1, CT_F8 = 2, CT_BF16 = 3, CT_LIST8 = 4, CT_LIST16 = 5, CT_LOGIT = 6;
+constexpr int CT_F16 = 0, CT_F32 = 1, CT_F8 = 2, CT_BF16 = 3, CT_LIST8 = 4, CT_LIST16 = 5, CT_LOGIT = 6, CT_LOGIT_BF16 = 7;
 // CT_LOGIT: the fp16 planes hold LOGITS (an extension beyond the paper, see sr_options.coeff_kind).  A unit's planes are
 // loaded as in the fp16 form; once they are all there the lane takes the maximum of its pixels' logits (packed fp16
 // maxima over its half of the planes, then one exchange with the other half), and where the fp16 form re-packs
@@ -85,6 +85,11 @@ constexpr int CT_F16 = 0, CT_F32 = 1, CT_F8 = 2, CT_BF16 = 3, CT_LIST8 = 4, CT_L
 // multiply-add on the stored half and one exponential per value - and packs two of them, rounded to fp16, as the
 // operand.  One padding row of the dictionary operand is all ones, so the matrix cores also return the sum of the
 // exponentials of every pixel, in both lane halves; stage 4 multiplies its partial sums by the reciprocal.
+// CT_LOGIT_BF16: bfloat16 logits.  The exponentials are fp16 operands all the same (11 significant bits, the range
+// (0, 1]); a stored value is widened with a shift or a mask before the multiply-add.  The maxima are taken with the
+// same packed fp16 instruction on the stored bits: sign, then magnitude bits, order bfloat16 values exactly as they
+// order fp16 values, and the patterns that read as fp16 NaNs (bfloat16 magnitudes of 2^121 and up, the infinities
+// among them) are passed over, which is what a logit of minus infinity, an atom switched off, asks for.
 // CT_LIST8 / CT_LIST16: no dense planes; every pixel brings a list of up to 8 / 16 (atom index, fp16 value)
 // entries (an extension beyond the paper, see sr_dict_assemble_list).  Each wavefront owns an LDS scratch
 // [group of 8 atoms][32 pixels][8 atoms] fp16, all zero between uses.  Pixel slot by pixel slot it scatters
@@ -102,7 +107,7 @@ constexpr int LIST_MAX_ENTRIES = 16;
 template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int CT = CT_F16, int SMIN = 2, int NSUB = 1, int SWZ = 0>
 struct Cfg {
     static constexpr bool F32 = CT == CT_F32, F8 = CT == CT_F8, BF = CT == CT_BF16, LIST = CT == CT_LIST8 || CT == CT_LIST16;
-    static constexpr bool LG = CT == CT_LOGIT;
+    static constexpr bool LG = CT == CT_LOGIT || CT == CT_LOGIT_BF16, LGB = CT == CT_LOGIT_BF16;
     static constexpr int LH = CT == CT_LIST8 ? 4 : 8;  // list form: entries a lane half loads
     static constexpr int LSW = 4 * NP8 * 32;           // list form: scratch words per wavefront
     static constexpr int KK = K * K, R = (K - 1) / 2;
@@ -209,11 +214,16 @@ __device__ __forceinline__ unsigned pack_pair(unsigned plane_even, unsigned plan
 }
 
 // logits form: (atom pair, pixel q) as the exponentials exp2(z * log2(e) + nm) of the two planes' logits, rounded to fp16
+// (BF16: the stored logits are bfloat16, the upper half of a binary32)
+template <bool BF16>
 __device__ __forceinline__ unsigned exp_pair(unsigned plane_even, unsigned plane_odd, int q, float nm) {
     typedef _Float16 h2 __attribute__((ext_vector_type(2)));
     typedef float f2 __attribute__((ext_vector_type(2)));
-    const f2 e = {logit_exp((float)__builtin_bit_cast(h2, plane_even)[q & 1], nm),
-                  logit_exp((float)__builtin_bit_cast(h2, plane_odd)[q & 1], nm)};
+    auto widen = [&](unsigned w) -> float {
+        if constexpr (BF16) return __uint_as_float((q & 1) ? (w & 0xffff0000u) : (w << 16));
+        else return (float)__builtin_bit_cast(h2, w)[q & 1];
+    };
+    const f2 e = {logit_exp(widen(plane_even), nm), logit_exp(widen(plane_odd), nm)};
     return __builtin_bit_cast(unsigned, __builtin_convertvector(e, h2));      // round to nearest even
 }
 // packed fp16 maximum of stored values (no canonicalising pass over the operands first)
@@ -302,7 +312,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     static_assert(!LIST || (PX == 4 && WR == 1 && !BIG && PSM == 0 && NU % 2 == 0), "list form: four pixels per lane, one row per unit");
     constexpr bool PS = PSM == 1;                  // one 16-bit load per pixel
     constexpr bool PERM = PSM == 2 || PSM == 3 || PSM == 4;    // permuted pixel slots
-    static_assert(PSM == 0 || ((CT == CT_F16 || ((CT == CT_BF16 || CT == CT_LOGIT) && PSM != 1 && PSM != 8)) && !BIG && PX == 4),
+    static_assert(PSM == 0 || ((CT == CT_F16 || ((CT == CT_BF16 || CT == CT_LOGIT || CT == CT_LOGIT_BF16) && PSM != 1 && PSM != 8)) && !BIG && PX == 4),
                   "pre-shuffle layout: 16-bit coefficients, four pixels per lane");
     static_assert(!PMAJ || (CT == CT_F16 && WR == 1 && NP8 == 9), "pixel-major coefficients: 72 fp16 atoms, one row per unit");
     static_assert(!PERM || (WR == 1 && SMIN >= PSM), "permuted slots: one row per wavefront and unit");
@@ -945,7 +955,10 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 mx[m] = pk_max_f16(__builtin_bit_cast(h2, (unsigned)sw[0]), __builtin_bit_cast(h2, (unsigned)sw[1]));
             }
 #pragma unroll
-            for (int q = 0; q < PX; ++q) nm[q] = logit_shift((float)mx[q >> 1][q & 1]);
+            for (int q = 0; q < PX; ++q) {
+                if constexpr (F::LGB) nm[q] = logit_shift(__uint_as_float((__builtin_bit_cast(unsigned, mx[q >> 1]) >> (16 * (q & 1))) << 16));
+                else nm[q] = logit_shift((float)mx[q >> 1][q & 1]);
+            }
         }
 #pragma unroll
         for (int c16 = 0; c16 < (LIST || PMAJ ? 0 : N16); ++c16) {   // (the list and pixel-major forms have folded above)
@@ -963,7 +976,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 u32x4 bw;
 #pragma unroll
                 for (int m = 0; m < 4; ++m)
-                    bw[m] = LG ? exp_pair(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q, nm[q])
+                    bw[m] = LG ? exp_pair<F::LGB>(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q, nm[q])
                                : pack_pair(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q);
 #pragma unroll
                 for (int mb = 0; mb < NMB; ++mb)
@@ -993,7 +1006,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 u32x2 bw;
 #pragma unroll
                 for (int m = 0; m < 2; ++m)
-                    bw[m] = LG ? exp_pair(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q, nm[q])
+                    bw[m] = LG ? exp_pair<F::LGB>(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q, nm[q])
                                : pack_pair(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q);
 #pragma unroll
                 for (int mb = 0; mb < NMB; ++mb)
@@ -1255,7 +1268,8 @@ hipError_t launch_one(const AssembleArgs& a0, hipStream_t st) {
     if (a0.s < SMIN) return hipErrorInvalidValue;       // its LDS footprint buffers would be too small
     if ((a0.pre_shuffle != 0) != (PSM >= 1 && PSM <= 4) || (a0.pixel_major != 0) != (PSM == 8)) return hipErrorInvalidValue;
     // logits: a softmax over every atom, so every plane is folded
-    if ((a0.logits != 0) != (CT == CT_LOGIT) || (a0.logits && a0.n_fold != a0.L)) return hipErrorInvalidValue;
+    if ((a0.logits != 0) != (CT == CT_LOGIT || CT == CT_LOGIT_BF16) || (a0.logits && a0.n_fold != a0.L)) return hipErrorInvalidValue;
+    if (a0.logits && (a0.coeff_dtype == SR_BF16) != (CT == CT_LOGIT_BF16)) return hipErrorInvalidValue;
     if (PSM == 8 && (a0.W % 128 != 0 || a0.L != 8 * NP8 || a0.n_fold != a0.L)) return hipErrorInvalidValue;
     // permuted pixel slots: a lane owns four whole LR columns, the image must end on such a group
     if ((PSM == 2 || PSM == 3 || PSM == 4) && (a0.s != PSM || a0.w % 4 != 0)) return hipErrorInvalidValue;

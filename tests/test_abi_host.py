@@ -236,7 +236,8 @@ def test_logits_option_is_checked_on_the_host(lib):
     assert plan(*case(), opts=lg(sr.SR_KERNEL_GENERIC)) == sr.SR_KERNEL_GENERIC
     assert plan(*case(L=65), L=65, opts=lg()) == sr.SR_KERNEL_MFMA
     assert plan(*case(L=49), L=49, opts=lg()) == sr.SR_KERNEL_MFMA                       # the capacity of nine groups of eight
-    for kw, pk in (({"cd": sr.SR_F32}, {}), ({"cd": sr.SR_BF16}, {}), ({"k": 7}, {"k": 7}), ({"C": 1}, {"C": 1}),
+    assert plan(*case(cd=sr.SR_BF16), opts=lg()) == sr.SR_KERNEL_MFMA                    # bfloat16 logits
+    for kw, pk in (({"cd": sr.SR_F32}, {}), ({"k": 7}, {"k": 7}), ({"C": 1}, {"C": 1}),
                    ({"L": 48}, {"L": 48}), ({"L": 100}, {"L": 100})):
         assert plan(*case(**kw), **pk, opts=lg()) == sr.SR_KERNEL_GENERIC, kw
         assert plan(*case(**kw), **pk, opts=lg(sr.SR_KERNEL_MFMA)) == -3, kw

@@ -57,6 +57,9 @@ CASES = [
     (1, 3, 21, 34, 4, 65, 5, "f16", "f32", 1.0),        # 65 planes: seven padding atoms in the last group
     (1, 3, 21, 34, 4, 70, 5, "f16", "f32", 9.0),        # 70 planes; a few atoms dominate
     (1, 3, 21, 36, 3, 50, 5, "f16", "f32", 1.0),        # 50 planes: 22 padding atoms, two whole groups among them
+    (1, 3, 37, 64, 4, 72, 5, "bf16", "f32", 1.0),       # bfloat16 logits on the matrix cores
+    (2, 3, 29, 128, 3, 72, 5, "bf16", "f16", 4.0),
+    (1, 3, 21, 36, 2, 66, 5, "bf16", "f32", 1.0),
     (1, 3, 18, 32, 4, 40, 5, "f16", "f32", 1.0),        # 40 atoms: generic kernel
     (1, 1, 19, 23, 4, 40, 5, "f32", "f32", 1.0),        # fp32 logits
     (2, 2, 16, 21, 3, 17, 7, "bf16", "f16", 1.0),       # bfloat16 logits, 7x7 atoms
@@ -89,17 +92,18 @@ def test_logits_against_the_oracle(oracle, case):
             assert rms_ref < 0.5 * rms_plain, f"kernel {kernel}: as close to the unrounded softmax ({rms_plain:.2e}) as to the rounded one ({rms_ref:.2e})"
     assert ran >= 1
     takes = run(inp, wl, z, MFMA) is not None
-    assert takes == (cd == "f16" and C == 3 and k == 5 and 49 <= L <= 72)
+    assert takes == (cd in ("f16", "bf16") and C == 3 and k == 5 and 49 <= L <= 72)
 
 
+@pytest.mark.parametrize("cd", ["f16", "bf16"])
 @pytest.mark.parametrize("shape", [(1, 23, 64, 4, 72), (2, 19, 96, 3, 72), (1, 21, 64, 2, 72), (1, 9, 36, 3, 65), (1, 30, 68, 4, 50)],
                          ids=lambda c: "N%dh%dw%ds%dL%d" % c)
-def test_logits_before_the_pixel_shuffle_on_the_matrix_cores(oracle, shape):
+def test_logits_before_the_pixel_shuffle_on_the_matrix_cores(oracle, shape, cd):
     """What the network's last convolution writes when the normalisation is left to the call: logits in the layout
     before the pixel-shuffle.  Against the oracle (shuffle, then softmax, then the definition) and, bit for bit,
     against the call with the shuffled logits."""
     N, h, w, s, L = shape
-    wl = sr_synth.Workload("lg", 57, N, 3, h, w, s, L, 5, "f16", "f32", 0.0, 1.5)
+    wl = sr_synth.Workload("lg", 57, N, 3, h, w, s, L, 5, cd, "f32", 0.0, 1.5)
     inp = sr_synth.make_inputs(wl, DEV)
     z = sr_synth.make_logits(wl, DEV)
     pre = sr_synth.to_pre_shuffle(z, s)
@@ -127,15 +131,18 @@ def test_logits_in_the_other_layouts_run_on_the_generic_kernel(oracle):
         assert torch.equal(got, run(inp, wl, z, GENERIC))
 
 
-def test_masked_atoms_and_shifted_logits(oracle):
+@pytest.mark.parametrize("cd", ["f16", "bf16"])
+def test_masked_atoms_and_shifted_logits(oracle, cd):
     """Logits of minus infinity are atoms switched off (coefficient zero); a common shift of a pixel's logits changes
     nothing; logits far from zero do not overflow."""
-    wl = sr_synth.Workload("lg", 55, 1, 3, 16, 32, 4, 72, 5, "f16", "f32", 0.0, 1.0)
+    wl = sr_synth.Workload("lg", 55, 1, 3, 16, 32, 4, 72, 5, cd, "f32", 0.0, 1.0)
     inp = sr_synth.make_inputs(wl, DEV)
     z = sr_synth.make_logits(wl, DEV)
     g = torch.Generator(device="cpu").manual_seed(7)
     mask = (torch.rand(z.shape, generator=g) < 0.3).to(DEV)
     mask[:, 5] = False                                   # every pixel keeps an atom
+    mask[:, 0, :8] = True                                # the first plane a lane half loads starts some maxima switched off
+    mask[:, 1, 4:12] = True
     zm = z.masked_fill(mask, float("-inf"))
     hi = host(inp)
     ref = oracle.dict_assemble(hi["lr"], sr_synth.stored_numpy(zm), hi["dict"], wl.scale, logits=True)
@@ -144,8 +151,10 @@ def test_masked_atoms_and_shifted_logits(oracle):
         assert got is not None and torch.isfinite(got).all()
         assert_logits_parity(got.cpu().numpy(), ref, False, f"masked, kernel {kernel}")
     # multiples of 1/8 keep the shifted logits exact in fp16
-    zq = (torch.round(z.float() * 8.0) / 8.0).to(torch.float16)
-    shift = torch.randint(-200, 200, (1, 1, wl.H, wl.W), generator=g).to(DEV).to(torch.float16)
+    # (bfloat16: multiples of 1/8 up to 16)
+    zq = (torch.round(z.float() * 8.0) / 8.0).to(z.dtype)
+    span = 200 if cd == "f16" else 8
+    shift = torch.randint(-span, span, (1, 1, wl.H, wl.W), generator=g).to(DEV).to(z.dtype)
     for kernel in (GENERIC, MFMA):
         a, b = run(inp, wl, zq, kernel), run(inp, wl, zq + shift, kernel)
         # (the shift enters the exponent as -max * log2(e), rounded once: a few units in the last place of fp32)
