@@ -161,6 +161,35 @@ def test_masked_atoms_and_shifted_logits(oracle, cd):
         assert torch.isfinite(b).all() and (a - b).abs().max().item() <= LOGIT_STEP
 
 
+def test_random_shapes_the_two_kernels_agree_on_logits():
+    """Seeded random frames, scales, atom counts 49 to 72, both 16-bit types, both layouts: the matrix-core form against
+    the generic kernel.  Both evaluate the same fp32 expression for an exponential, so they round it the same way and
+    differ by fp32 summation order only."""
+    rng = np.random.default_rng(77)
+    compared = 0
+    for index in range(120):
+        s = int(rng.choice([2, 3, 4]))
+        h, w = int(rng.integers(1, 60)), int(rng.integers(1, 100))
+        L, N = int(rng.integers(49, 73)), int(rng.choice([1, 1, 2, 3]))
+        cd, io = str(rng.choice(["f16", "bf16"])), str(rng.choice(["f32", "f16"]))
+        wl = sr_synth.Workload("lgr", 300 + index, N, 3, h, w, s, L, 5, cd, io, 0.0, float(rng.choice([0.5, 1.0, 4.0])))
+        inp = sr_synth.make_inputs(wl, DEV)
+        z = sr_synth.make_logits(wl, DEV)
+        layout = sr.SR_COEFF_PLANAR
+        if rng.random() < 0.4:
+            z, layout = sr_synth.to_pre_shuffle(z, s), sr.SR_COEFF_PRE_SHUFFLE
+        a = run(inp, wl, z, MFMA, layout)
+        if a is None:
+            continue                                    # narrow ragged frames, LR widths the permuted forms do not take
+        b = run(inp, wl, z, GENERIC, layout)
+        assert torch.isfinite(a).all(), f"{wl}: some output pixel was never written"
+        tol = (5e-5 + (2.0 ** -10 if io == "f16" else 0.0)) * max(1.0, float(b.abs().max()))
+        err = float((a.float() - b.float()).abs().max())
+        assert err <= tol, f"{wl} layout {layout}: kernels differ by {err:.3e} > {tol:.1e}"
+        compared += 1
+    assert compared >= 40, compared
+
+
 def test_4k_frame_of_logits(oracle):
     """The headline frame handed over as logits, in the launch configuration the benchmark times: sampled pixels
     (corners and edges among them) against the oracle, and the whole frame against the frame computed from the
