@@ -43,8 +43,9 @@
 //   * CT_F32: 2-atom steps of v_mfma_f32_32x32x2_f32; lane half hf loads plane
 //     2*step + hf and the loaded words are the B operand as they are; the
 //     dictionary stays fp32, products and sums are true fp32;
-//   * CT_F8 (8-bit E4M3 storage): 4 pixels per 4-byte load, widened exactly to
-//     fp16 pairs in registers, then the fp16 steps above;
+//   * CT_F8 (8-bit E4M3 storage): 4 pixels per 4-byte load; the bytes of two planes
+//     are paired per pixel with a byte permute and each pair is widened exactly to
+//     the fp16 operand word, then the fp16 steps above;
 //   * CT_BF16: the fp16 flow with the bfloat16 matrix instructions and the
 //     dictionary as two bfloat16 operands;
 //   * CT_LIST8 / CT_LIST16 (an extension beyond the paper): no planes, but per-pixel
@@ -211,6 +212,21 @@ __device__ __forceinline__ void split_hi_lo(const float (&d)[N], V& hi, V& lo) {
 // (atom pair, pixel q) from two planes' packed pixels
 __device__ __forceinline__ unsigned pack_pair(unsigned plane_even, unsigned plane_odd, int q) {
     return __builtin_amdgcn_perm(plane_odd, plane_even, (q & 1) ? 0x07060302u : 0x05040100u);
+}
+
+// 8-bit coefficients: the four pixels of two planes as byte pairs (even plane, odd plane), pixels 0, 1 in w[0] and
+// 2, 3 in w[1]; widen_pair then widens the pair of pixel q to the fp16 operand word (every E4M3 value is exact in fp16).
+// Six instructions per plane pair where widening every plane first and pairing afterwards takes eight.
+template <int NWORD>
+__device__ __forceinline__ void pair_bytes(unsigned plane_even, unsigned plane_odd, unsigned (&w)[NWORD]) {
+    static_assert(NWORD == 2, "8-bit coefficients: four pixels per lane");
+    w[0] = __builtin_amdgcn_perm(plane_odd, plane_even, 0x05010400u);
+    w[1] = __builtin_amdgcn_perm(plane_odd, plane_even, 0x07030602u);
+}
+__device__ __forceinline__ unsigned widen_pair(unsigned pairs, int q) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    return (q & 1) ? __builtin_bit_cast(unsigned, (h2)__builtin_amdgcn_cvt_scalef32_pk_f16_fp8(pairs, 1.0f, true))
+                   : __builtin_bit_cast(unsigned, (h2)__builtin_amdgcn_cvt_scalef32_pk_f16_fp8(pairs, 1.0f, false));
 }
 
 // logits form: (atom pair, pixel q) as the exponentials exp2(z * log2(e) + nm) of the two planes' logits, rounded to fp16
@@ -969,14 +985,21 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 for (int hl = 0; hl < 2; ++hl) av[mb][hl] = A16[((c16 * NMB + mb) * 2 + hl) * 64 + lane];
             constexpr int NWORD = PX / 2 > 0 ? PX / 2 : 1;
             unsigned cw[8][NWORD];                  // the step's 8 planes as fp16 pixel pairs
+            if constexpr (F8) {
+                // 8-bit coefficients: pair the planes' BYTES first (two permutes per plane pair), widen afterwards
 #pragma unroll
-            for (int i = 0; i < 8; ++i) plane_words<F8>(raw[8 * c16 + i], cw[i]);
+                for (int m = 0; m < 4; ++m) pair_bytes(raw_word(raw[8 * c16 + 2 * m], 0), raw_word(raw[8 * c16 + 2 * m + 1], 0), cw[2 * m]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) plane_words<F8>(raw[8 * c16 + i], cw[i]);
+            }
 #pragma unroll
             for (int q = 0; q < PX; ++q) {
                 u32x4 bw;
 #pragma unroll
                 for (int m = 0; m < 4; ++m)
-                    bw[m] = LG ? exp_pair<F::LGB>(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q, nm[q])
+                    bw[m] = F8 ? widen_pair(cw[2 * m][q >> 1], q)
+                          : LG ? exp_pair<F::LGB>(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q, nm[q])
                                : pack_pair(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q);
 #pragma unroll
                 for (int mb = 0; mb < NMB; ++mb)
@@ -999,14 +1022,20 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 for (int hl = 0; hl < 2; ++hl) av[mb][hl] = A8[(mb * 2 + hl) * 64 + lane];
             constexpr int NWORD = PX / 2 > 0 ? PX / 2 : 1;
             unsigned cw[4][NWORD];
+            if constexpr (F8) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) plane_words<F8>(raw[8 * N16 + i], cw[i]);
+                for (int m = 0; m < 2; ++m) pair_bytes(raw_word(raw[8 * N16 + 2 * m], 0), raw_word(raw[8 * N16 + 2 * m + 1], 0), cw[2 * m]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) plane_words<F8>(raw[8 * N16 + i], cw[i]);
+            }
 #pragma unroll
             for (int q = 0; q < PX; ++q) {
                 u32x2 bw;
 #pragma unroll
                 for (int m = 0; m < 2; ++m)
-                    bw[m] = LG ? exp_pair<F::LGB>(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q, nm[q])
+                    bw[m] = F8 ? widen_pair(cw[2 * m][q >> 1], q)
+                          : LG ? exp_pair<F::LGB>(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q, nm[q])
                                : pack_pair(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q);
 #pragma unroll
                 for (int mb = 0; mb < NMB; ++mb)
