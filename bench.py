@@ -40,8 +40,9 @@ def read_traffic(workload):
 def empirical_ceilings(sr, torch, wl, coeffs, outs, kernel_ms, inp_lr, inp_dict):
     """Secondary roofline context: the machine's own streaming rates for this byte mix,
     from the library's probes (no arithmetic in them), timed like the kernel."""
-    if wl.coeff_dtype not in ("f16", "bf16") or wl.L not in (72, 128) or wl.hr_pixels % 128 or outs[0].dtype != torch.float32:
+    if wl.coeff_dtype not in ("f16", "bf16", "f8") or wl.L not in (72, 128) or wl.hr_pixels % 128 or outs[0].dtype != torch.float32:
         return None
+    eb = coeffs[0].element_size()                    # the flat mix probe reads two-byte coefficients only
     sink = torch.zeros(4, device="cuda", dtype=torch.int32)
 
     def timed(fn, reps=20):
@@ -55,24 +56,26 @@ def empirical_ceilings(sr, torch, wl, coeffs, outs, kernel_ms, inp_lr, inp_dict)
         return sum(a.elapsed_time(b) for a, b in ev) / reps
 
     px = wl.hr_pixels // wl.n
-    coeff_bytes = wl.L * px * 2
+    coeff_bytes = wl.L * px * eb
     t_read = timed(lambda i: sr.sr_probe_read(coeffs[i % len(coeffs)][0], sink))
-    t_mix = timed(lambda i: sr.sr_probe_mix(coeffs[i % len(coeffs)][0], wl.L, px, outs[i % 2][0], wl.c))
+    t_mix = timed(lambda i: sr.sr_probe_mix(coeffs[i % len(coeffs)][0], wl.L, px, outs[i % 2][0], wl.c)) if eb == 2 else None
     mix_bytes = coeff_bytes + wl.c * px * 4
     # the same requests in the kernel's own order: its tiles (height reported by the library, 16 where it reports none),
     # its split of the tiles over the XCDs, its rows per wavefront
     t_tiled = None
     if wl.W % 128 == 0:
         shape = sr.sr_dict_assemble_launch_shape(inp_lr, coeffs[0], inp_dict, wl.L, wl.k, wl.scale, wl.c, outs[0])[1]
-        tile_h = shape[1] if shape[0] == 128 else 16
-        t_tiled = timed(lambda i: sr.sr_probe_mix_tiled(coeffs[i % len(coeffs)][0], wl.L, wl.H, wl.W, tile_h, outs[i % 2][0], wl.c))
+        # (the 8-bit family has one built shape per case and reports none: 128 x 24 at scale 4 on large frames)
+        tile_h = shape[1] if shape[0] == 128 else (24 if eb == 1 and wl.scale == 4 and wl.hr_pixels > 400000 else 16)
+        t_tiled = timed(lambda i: sr.sr_probe_mix_tiled(coeffs[i % len(coeffs)][0], wl.L, wl.H, wl.W, tile_h, outs[i % 2][0], wl.c,
+                                                        elem_bytes=eb))
     # the same bytes with nothing of the kernel's access pattern: 16-byte accesses, readers and
     # writers in separate workgroups, two workgroups per CU, every 9th one a writer
     t_stream = timed(lambda i: sr.sr_probe_stream(coeffs[i % len(coeffs)][0], coeff_bytes, outs[i % 2][0], wl.c * px * 4,
                                                   512, 9, sink, nt_store=1))
     return {"read_only_GBps": round(coeff_bytes / t_read / 1e6, 1),
-            "mix_GBps": round(mix_bytes / t_mix / 1e6, 1), "mix_ms": round(t_mix, 4),
-            "kernel_time_over_mix_time": round(kernel_ms * 1.0 / (t_mix * wl.n), 3),
+            "mix_GBps": round(mix_bytes / t_mix / 1e6, 1) if t_mix else None, "mix_ms": round(t_mix, 4) if t_mix else None,
+            "kernel_time_over_mix_time": round(kernel_ms * 1.0 / (t_mix * wl.n), 3) if t_mix else None,
             "tiled_mix_ms": round(t_tiled, 4) if t_tiled else None,
             "kernel_time_over_tiled_mix_time": round(kernel_ms * 1.0 / (t_tiled * wl.n), 3) if t_tiled else None,
             "independent_mix_GBps": round(mix_bytes / t_stream / 1e6, 1), "independent_mix_ms": round(t_stream, 4),

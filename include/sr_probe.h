@@ -41,6 +41,11 @@ int sr_probe_mix(const void* coeff, int planes, size_t pixels, void* out, int ch
 int sr_probe_mix_tiled(const void* coeff, int planes, int height, int width, int tile_h, void* out, int channels,
                        void* stream);
 
+/* As sr_probe_mix_tiled, for planes of `elem_bytes`-byte coefficients: 2 (the call above) or 1 (the kernel's
+ * 8-bit form: 4 bytes per lane and plane, half the read stream for the same writes). */
+int sr_probe_mix_tiled_bytes(const void* coeff, int planes, int elem_bytes, int height, int width, int tile_h, void* out,
+                             int channels, void* stream);
+
 /* A byte mix with NOTHING of the assembly kernel's access pattern in it: one launch of
  * `blocks` workgroups of 256 threads in which every `writer_every`-th workgroup only
  * writes (16-byte stores sweeping `dst`, `write_bytes` in all) and all others only read

@@ -75,11 +75,17 @@ __global__ __launch_bounds__(256) void k_probe_mix(const char* __restrict__ p, s
 // w, w + 4, ... of a tile, one row of 128 pixels at a time: the row's 8 bytes per lane from every
 // plane (next row requested before this one's stores), then the row of every output plane.  No LDS,
 // no barrier, no arithmetic: what is left of the kernel when only its memory requests remain.
-template <int L>
+// (EB: bytes per stored coefficient, 2 or 1; with one byte the row is 4 bytes per lane, as the kernel's 8-bit form loads)
+template <int L, int EB>
 __global__ __launch_bounds__(256, 2) void k_probe_mix_tiled(const char* __restrict__ p, int H, int W, int tile_h, int tiles_x,
                                                             int ntiles, float* __restrict__ out, int channels) {
+    typedef typename std::conditional<EB == 2, u32x2, unsigned>::type Piece;       // a lane's four pixels of a plane
+    auto fold = [](const Piece& v) -> unsigned {
+        if constexpr (EB == 2) return v[0] ^ v[1];
+        else return v;
+    };
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hf = lane >> 5, j = lane & 31;
-    const size_t pixels = (size_t)H * W, plane_b = pixels * 2;
+    const size_t pixels = (size_t)H * W, plane_b = pixels * EB;
     const int groups = (gridDim.x & 7) == 0 ? 8 : 1;
     const int G = gridDim.x / groups, share = (ntiles + groups - 1) / groups;
     const int t_first = (int)(blockIdx.x % groups) * share + (int)(blockIdx.x / groups);
@@ -94,16 +100,16 @@ __global__ __launch_bounds__(256, 2) void k_probe_mix_tiled(const char* __restri
         inside = y < H;
         return (size_t)(inside ? y : H - 1) * W + (size_t)tx * 128 + 4 * j;
     };
-    u32x2 v[L / 2];
+    Piece v[L / 2];
     bool in_cur;
     size_t cur = offset(t_first, 0, in_cur);
 #pragma unroll
-    for (int i = 0; i < L / 2; ++i) v[i] = __builtin_nontemporal_load((const u32x2*)(p + (size_t)(2 * i + hf) * plane_b + cur * 2));
+    for (int i = 0; i < L / 2; ++i) v[i] = __builtin_nontemporal_load((const Piece*)(p + (size_t)(2 * i + hf) * plane_b + cur * EB));
     for (int t = t_first; t < t_end; t += G) {
         for (int r = 0; r < rows; ++r) {
             unsigned acc = 0;
 #pragma unroll
-            for (int i = 0; i < L / 2; ++i) acc ^= v[i][0] ^ v[i][1];
+            for (int i = 0; i < L / 2; ++i) acc ^= fold(v[i]);
             acc ^= __shfl_xor(acc, 32, 64);
             const float f = (float)(acc & 0xffu);
             const bool last = r == rows - 1;
@@ -113,7 +119,7 @@ __global__ __launch_bounds__(256, 2) void k_probe_mix_tiled(const char* __restri
             if (more) {
 #pragma unroll
                 for (int i = 0; i < L / 2; ++i)
-                    v[i] = __builtin_nontemporal_load((const u32x2*)(p + (size_t)(2 * i + hf) * plane_b + nxt * 2));
+                    v[i] = __builtin_nontemporal_load((const Piece*)(p + (size_t)(2 * i + hf) * plane_b + nxt * EB));
             }
             if (in_cur)
                 for (int c = 0; c < channels; ++c) *(float2*)(out + (size_t)c * pixels + cur + 2 * hf) = make_float2(f, f + (float)c);
@@ -461,20 +467,24 @@ int sr_probe_mix(const void* coeff, int planes, size_t pixels, void* out, int ch
 
 extern "C" __attribute__((visibility("default")))
 int sr_probe_mix_tiled(const void* coeff, int planes, int height, int width, int tile_h, void* out, int channels, void* stream) {
+    return sr_probe_mix_tiled_bytes(coeff, planes, 2, height, width, tile_h, out, channels, stream);
+}
+
+extern "C" __attribute__((visibility("default")))
+int sr_probe_mix_tiled_bytes(const void* coeff, int planes, int elem_bytes, int height, int width, int tile_h, void* out, int channels,
+                             void* stream) {
     if (!coeff || !out) return SR_ERR_NULL;
-    if ((planes != 72 && planes != 128) || channels < 1 || channels > 4 || height < 0 || width < 0 || width % 128 != 0 ||
-        tile_h < 1 || tile_h > 64 || (long long)height * width >= (1ll << 31)) return SR_ERR_UNSUPPORTED;
+    if ((planes != 72 && planes != 128) || (elem_bytes != 1 && elem_bytes != 2) || channels < 1 || channels > 4 || height < 0 ||
+        width < 0 || width % 128 != 0 || tile_h < 1 || tile_h > 64 || (long long)height * width >= (1ll << 31)) return SR_ERR_UNSUPPORTED;
     if ((uintptr_t)coeff % 16 != 0 || (uintptr_t)out % 16 != 0) return SR_ERR_ALIGN;
     if (height == 0 || width == 0) return SR_OK;
     const int tiles_x = width / 128, tiles_y = (height + tile_h - 1) / tile_h;
     const long long nt = (long long)tiles_x * tiles_y;
     const int blocks = nt < 512 ? (int)nt : 512;
-    if (planes == 72)
-        hipLaunchKernelGGL(k_probe_mix_tiled<72>, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
-                           (const char*)coeff, height, width, tile_h, tiles_x, (int)nt, (float*)out, channels);
-    else
-        hipLaunchKernelGGL(k_probe_mix_tiled<128>, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
-                           (const char*)coeff, height, width, tile_h, tiles_x, (int)nt, (float*)out, channels);
+    auto kern = planes == 72 ? (elem_bytes == 2 ? k_probe_mix_tiled<72, 2> : k_probe_mix_tiled<72, 1>)
+                             : (elem_bytes == 2 ? k_probe_mix_tiled<128, 2> : k_probe_mix_tiled<128, 1>);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
+                       (const char*)coeff, height, width, tile_h, tiles_x, (int)nt, (float*)out, channels);
     return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_LAUNCH;
 }
 

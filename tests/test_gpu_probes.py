@@ -44,6 +44,25 @@ def test_tiled_mix_probe_writes_what_the_flat_one_writes(planes, channels, H, W,
     assert torch.equal(flat, tiled)
 
 
+@pytest.mark.parametrize("planes,channels,H,W,tile_h", [(72, 3, 50, 256, 24), (128, 2, 9, 384, 4), (72, 3, 700, 1280, 24)])
+def test_tiled_mix_probe_for_one_byte_coefficients(planes, channels, H, W, tile_h):
+    """Planes of 8-bit coefficients: a lane reads the 4 bytes of its four pixels from every plane; the written value is the
+    low byte of the exclusive-or of those words over all planes, as in the two-byte form."""
+    pixels = H * W
+    g = torch.Generator(device="cuda").manual_seed(planes + H)
+    words = torch.randint(0, 2**31 - 1, (planes, pixels // 4), device="cuda", dtype=torch.int32, generator=g)
+    out = torch.full((channels, pixels), -2.0, device="cuda")
+    sr.sr_probe_mix_tiled(words, planes, H, W, tile_h, out, channels, elem_bytes=1)
+    torch.cuda.synchronize()
+    acc = words[0].clone()
+    for p in range(1, planes):
+        acc ^= words[p]
+    f = (acc & 0xFF).to(torch.float32).repeat_interleave(4)                      # one value per 4 pixels
+    odd = torch.arange(pixels, device="cuda") % 2 == 1
+    for c in range(channels):
+        assert torch.equal(out[c], torch.where(odd, f + c, f))
+
+
 def test_read_probe_runs_on_ragged_sizes_and_leaves_the_sink_alone():
     sink = torch.zeros(4, device="cuda", dtype=torch.int32)
     for nbytes in (16, 4096 * 5 + 16, 256 * 16 * 8 * 3 + 48, 1 << 26):
