@@ -190,6 +190,41 @@ def test_random_shapes_the_two_kernels_agree_on_logits():
     assert compared >= 40, compared
 
 
+def test_random_small_shapes_against_the_oracle(oracle):
+    """Seeded random small cases over everything the call takes with logits (kernel sizes, channel counts, atom counts from
+    one up, the three logit types, the three layouts, batches, ragged sizes): every kernel that takes the case against the
+    oracle."""
+    rng = np.random.default_rng(78)
+    ran = {GENERIC: 0, MFMA: 0}
+    for index in range(48):
+        k, s = int(rng.choice([3, 5, 5, 7])), int(rng.choice([2, 3, 4]))
+        C, N = int(rng.choice([1, 2, 3, 3, 4])), int(rng.choice([1, 1, 2, 3]))
+        L = int(rng.integers(1, 73)) if rng.random() < 0.6 else int(rng.integers(49, 73))
+        if k == 5 and C == 3 and rng.random() < 0.5:
+            L = int(rng.integers(49, 73))
+        h, w = int(rng.integers(1, 24)), int(rng.integers(1, 40))
+        cd, io = str(rng.choice(["f16", "f16", "bf16", "f32"])), str(rng.choice(["f32", "f16"]))
+        wl = sr_synth.Workload("lgs", 500 + index, N, C, h, w, s, L, k, cd, io, 0.0, float(rng.choice([1.0, 3.0])))
+        inp = sr_synth.make_inputs(wl, DEV)
+        z = sr_synth.make_logits(wl, DEV)
+        hi = host(inp)
+        ref = oracle.dict_assemble(hi["lr"], sr_synth.stored_numpy(z), hi["dict"], s, logits=True)
+        layout, moved = sr.SR_COEFF_PLANAR, z
+        pick = rng.random()
+        if pick < 0.3:
+            layout, moved = sr.SR_COEFF_PRE_SHUFFLE, sr_synth.to_pre_shuffle(z, s)
+        elif pick < 0.5:
+            layout, moved = sr.SR_COEFF_PIXEL_MAJOR, sr_synth.to_pixel_major(z)
+        for kernel in (GENERIC, MFMA):
+            got = run(inp, wl, moved, kernel, layout)
+            if got is None:
+                continue
+            assert not torch.isnan(got).any(), f"{wl} layout {layout} kernel {kernel}: some output pixel was never written"
+            assert_logits_parity(got.float().cpu().numpy(), ref, io == "f16", f"{wl} layout {layout} kernel {kernel}")
+            ran[kernel] += 1
+    assert ran[GENERIC] == 48 and ran[MFMA] >= 1, ran            # (the matrix-core form has its own random test above)
+
+
 def test_4k_frame_of_logits(oracle):
     """The headline frame handed over as logits, in the launch configuration the benchmark times: sampled pixels
     (corners and edges among them) against the oracle, and the whole frame against the frame computed from the
