@@ -38,6 +38,14 @@ def test_every_declared_symbol_is_exported(lib):
         assert getattr(lib, name) is not None
 
 
+def test_a_missing_library_fails_loudly(lib, tmp_path, monkeypatch):
+    """There is no fallback path: with no built library the binding raises, it computes nothing another way."""
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libsrdict.so"))
+    monkeypatch.setattr(binding, "_lib", None, raising=False)
+    with pytest.raises(ImportError, match="is missing"):
+        binding.load()
+
+
 def test_version_and_strerror(lib):
     assert sr.sr_version() == 200
     assert sr.sr_strerror(0) == "success"
