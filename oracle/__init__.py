@@ -71,6 +71,8 @@ def _load():
                                                c_vp, c_int, c_int, c_int, c_vp]
         lib.orc_pixel_major_to_planar.restype = c_int
         lib.orc_pixel_major_to_planar.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_vp]
+        lib.orc_blocked_to_planar.restype = c_int
+        lib.orc_blocked_to_planar.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_vp]
         lib.orc_pixel_shuffle.restype = c_int
         lib.orc_pixel_shuffle.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_vp]
         lib.orc_round_to_half.restype = c_dbl
@@ -242,6 +244,21 @@ def pixel_major_to_planar(coeff_pm) -> np.ndarray:
     return out
 
 
+def blocked_to_planar(coeff_blk, L: int) -> np.ndarray:
+    """Coefficients stored blocked (an extension: the order in which a matrix-core kernel consumes them; see
+    orc_blocked_to_planar), ``coeff_blk`` [N][H][W * L] (a row's units of 128 pixels one after the other), as the planar
+    [N][L][H][W]: the same stored elements."""
+    a = _stored(coeff_blk, "coeff_blk")
+    if a.ndim != 3 or a.shape[2] % L:
+        raise ValueError("coeff_blk must be [N][H][W * L]")
+    n, H, WL = a.shape
+    W = WL // L
+    out = np.empty((n, L, H, W), dtype=a.dtype)
+    if _load().orc_blocked_to_planar(_ptr(a), a.dtype.itemsize, n, int(L), H, W, _ptr(out)):
+        raise ValueError("orc_blocked_to_planar rejected its arguments (L % 8 == 0 and W % 128 == 0 are needed)")
+    return out
+
+
 def round_to_half(v: float) -> float:
     """``v`` rounded to the nearest binary16 value (ties to even), as a double."""
     return _load().orc_round_to_half(float(v))
@@ -263,12 +280,15 @@ def softmax_logits(logits, round_half: bool = True) -> np.ndarray:
 
 
 def dict_assemble(lr, coeff, dictionary, scale: int, kept=None, gamma=None, a: float = -0.5,
-                  pre_shuffle: bool = False, pixel_major: bool = False, logits: bool = False) -> np.ndarray:
+                  pre_shuffle: bool = False, pixel_major: bool = False, logits: bool = False, blocked: bool = False) -> np.ndarray:
     """The whole path: stage 1, then stages 3 + 4.  float64 [N][C][s*h][s*w].  With
     ``pre_shuffle`` the coefficients are what the network holds before its pixel-shuffle
     layer, [N][L*s*s][h][w]: that layer is applied first.  With ``pixel_major`` they are stored
-    [N][H][W][L] and are moved to planes first.  With ``logits`` the stored values are logits and the
+    [N][H][W][L] and are moved to planes first; with ``blocked`` they are stored in the blocked order
+    (blocked_to_planar) and are moved to planes first.  With ``logits`` the stored values are logits and the
     coefficients their per-pixel softmax (see softmax_logits)."""
+    if blocked:                                      # [N][H][W * L], see blocked_to_planar
+        coeff = blocked_to_planar(coeff, np.asarray(dictionary).shape[0])
     if pixel_major:
         coeff = pixel_major_to_planar(coeff)
     if pre_shuffle:

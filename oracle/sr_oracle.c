@@ -44,7 +44,8 @@
  * pixel-shuffle by a hand-written example, by a library routine and by the index
  * identity it is defined by (tests/test_oracle_shuffle.py); the per-pixel list form
  * by the pinned dense form on the scattered list, hand-made lists, repeated entries
- * and linearity (tests/test_oracle_topk.py); the logits form by a hand-made example with exact
+ * and linearity (tests/test_oracle_topk.py); the blocked storage order by hand-worked positions, a library's
+ * reshape and axis move, and the whole path (tests/test_oracle_blocked.py); the logits form by a hand-made example with exact
  * values, a closed form (logarithms of integers), two libraries' softmax, the library's binary16
  * cast for the rounding, shift invariance and large logits (tests/test_oracle_logits.py).
  * No function here is unpinned.
@@ -413,6 +414,46 @@ int orc_pixel_major_to_planar(const void *in, int esize, int n, int L, int H, in
             for (int x = 0; x < W; ++x)
                 for (int l = 0; l < L; ++l) {
                     size_t from = (((size_t)b * H + y) * W + x) * L + l;
+                    size_t to = (((size_t)b * L + l) * H + y) * W + x;
+                    memcpy(dst + to * esize, src + from * esize, (size_t)esize);
+                }
+    return 0;
+}
+
+/*
+ * Coefficients stored BLOCKED (an extension of the storage formats, not in the paper: the order in which a
+ * matrix-core kernel consumes them, for a producer that is willing to write it).  A row of the HR image is cut
+ * into units of 128 pixels; pixel 4 j + q of a unit (0 <= j < 32, 0 <= q < 4) is "slot q, column j".  The stored
+ * order is [b][y][unit][q][piece][half][j][e]:
+ *   pieces 0 .. L/16 - 1   16 atoms each: atom 16 piece + 8 half + e, 0 <= e < 8
+ *   one last piece if L % 16 == 8: atom 16 (L/16) + 4 half + e, 0 <= e < 4
+ * so a unit holds 128 L elements and the whole tensor has the size of the planar one.  Needs L % 8 == 0 and
+ * W % 128 == 0.  Moves the stored elements (esize bytes each) to the planar order every other function reads:
+ *
+ *     out[b][l][y][x] = in[b][y][x / 128][x % 4][piece(l)][half(l)][(x % 128) / 4][e(l)]
+ */
+int orc_blocked_to_planar(const void *in, int esize, int n, int L, int H, int W, void *out)
+{
+    if (!in || !out || esize < 1 || esize > 8 || n < 0 || L < 8 || L % 8 || H < 0 || W < 0 || W % 128)
+        return -1;
+    const unsigned char *src = (const unsigned char *)in;
+    unsigned char *dst = (unsigned char *)out;
+    int full = L / 16;                                     /* pieces of 16 atoms */
+    size_t slot_elems = (size_t)32 * L;                    /* one slot: 32 pixels x L atoms */
+    for (int b = 0; b < n; ++b)
+        for (int y = 0; y < H; ++y)
+            for (int x = 0; x < W; ++x)
+                for (int l = 0; l < L; ++l) {
+                    int unit = x / 128, j = (x % 128) / 4, q = x % 4;
+                    size_t within;                         /* position inside the slot */
+                    if (l < 16 * full) {
+                        int piece = l / 16, half = (l % 16) / 8, e = l % 8;
+                        within = (size_t)piece * 512 + (size_t)half * 256 + (size_t)j * 8 + e;
+                    } else {
+                        int half = (l - 16 * full) / 4, e = (l - 16 * full) % 4;
+                        within = (size_t)full * 512 + (size_t)half * 128 + (size_t)j * 4 + e;
+                    }
+                    size_t from = ((((size_t)b * H + y) * (W / 128) + unit) * 4 + q) * slot_elems + within;
                     size_t to = (((size_t)b * L + l) * H + y) * W + x;
                     memcpy(dst + to * esize, src + from * esize, (size_t)esize);
                 }

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "sr_oracle.c")
 PINS = ["tests/test_oracle_bicubic.py", "tests/test_oracle_assemble.py", "tests/test_oracle_fp8.py",
         "tests/test_oracle_shuffle.py", "tests/test_oracle_topk.py", "tests/test_oracle_pixel_major.py",
-        "tests/test_oracle_logits.py"]
+        "tests/test_oracle_logits.py", "tests/test_oracle_blocked.py"]
 
 MUTATIONS = {
     "keys_inner_coefficient": ("- (a + 3.0) * t * t + 1.0", "- (a + 2.0) * t * t + 1.0"),
@@ -52,6 +52,13 @@ MUTATIONS = {
     "list_index_used_as_position": ("F[j] += v * dict[(size_t)l * kk + j];", "F[j] += v * dict[(size_t)t * kk + j];"),
     "list_keeps_last_entry_only": ("                    for (int j = 0; j < kk; ++j)\n                        F[j] += v * dict[(size_t)l * kk + j];",
                                    "                    for (int j = 0; j < kk; ++j)\n                        F[j] = v * dict[(size_t)l * kk + j];"),
+    "blocked_slot_is_the_pixel_quarter": ("int unit = x / 128, j = (x % 128) / 4, q = x % 4;", "int unit = x / 128, j = (x % 128) % 32, q = (x % 128) / 32;"),
+    "blocked_halves_after_the_pixels": ("within = (size_t)piece * 512 + (size_t)half * 256 + (size_t)j * 8 + e;",
+                                        "within = (size_t)piece * 512 + (size_t)j * 16 + (size_t)half * 8 + e;"),
+    "blocked_last_piece_as_a_full_one": ("within = (size_t)full * 512 + (size_t)half * 128 + (size_t)j * 4 + e;",
+                                         "within = (size_t)full * 512 + (size_t)half * 256 + (size_t)j * 8 + e;"),
+    "blocked_slots_before_units": ("size_t from = ((((size_t)b * H + y) * (W / 128) + unit) * 4 + q) * slot_elems + within;",
+                                   "size_t from = ((((size_t)b * H + y) * 4 + q) * (W / 128) + unit) * slot_elems + within;"),
     "logits_maximum_not_subtracted": ("double e = exp(load_elem(in, dtype, base + (size_t)l * plane) - m);",
                                       "double e = exp(load_elem(in, dtype, base + (size_t)l * plane));"),
     "logits_exponentials_not_rounded": ("                if (round_half)\n                    e = orc_round_to_half(e);", "                (void)round_half;"),
