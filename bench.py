@@ -350,6 +350,9 @@ def main():
     ap.add_argument("--pixel-major", action="store_true",
                     help="hand the coefficients over stored pixel-major, [N][H][W][L] (what a channels-last producer writes; "
                          "a storage order beyond the paper); same values, same result")
+    ap.add_argument("--blocked", action="store_true",
+                    help="hand the coefficients over stored blocked (SR_COEFF_BLOCKED: the order in which the matrix-core kernel "
+                         "consumes them; a storage order beyond the paper); same values, same result")
     ap.add_argument("--logits", action="store_true",
                     help="hand the coefficients over as logits (an extension beyond the paper): the call applies the "
                          "per-pixel softmax over the atoms itself")
@@ -397,8 +400,14 @@ def main():
         make = sr_synth.make_logits if args.logits else sr_synth.make_coeff
         coeffs.append(make(sr_synth.scaled(wl, index=wl.index + 10 * r), dev))
     outs = [torch.empty((wl.n, wl.c, wl.H, wl.W), device=dev, dtype=inp["lr"].dtype) for _ in range(2)]
-    layout = sr.SR_COEFF_PRE_SHUFFLE if args.pre_shuffle else (sr.SR_COEFF_PIXEL_MAJOR if args.pixel_major else sr.SR_COEFF_PLANAR)
-    if args.pixel_major:
+    layout = sr.SR_COEFF_PRE_SHUFFLE if args.pre_shuffle else (sr.SR_COEFF_PIXEL_MAJOR if args.pixel_major else
+                                                               (sr.SR_COEFF_BLOCKED if args.blocked else sr.SR_COEFF_PLANAR))
+    if args.blocked:
+        for r in range(len(coeffs)):
+            coeffs[r] = sr_synth.to_blocked(coeffs[r])
+        inp["coeff"] = coeffs[0]
+        args.pre_shuffle = True            # from here on: "not the planar layout" (the extra legs below are planar-only)
+    elif args.pixel_major:
         for r in range(len(coeffs)):
             coeffs[r] = sr_synth.to_pixel_major(coeffs[r])
         inp["coeff"] = coeffs[0]
@@ -480,7 +489,8 @@ def main():
                    "L": wl.L, "k": wl.k, "atoms_read": n_read, "batch": wl.n,
                    "kernel": {1: "generic", 2: "mfma"}[plan], "rotating_coeff_buffers": N_ROTATE,
                    "coeff_layout": {sr.SR_COEFF_PLANAR: "planar [N][L][H][W]", sr.SR_COEFF_PIXEL_MAJOR: "pixel_major [N][H][W][L]",
-                                    sr.SR_COEFF_PRE_SHUFFLE: "pre_shuffle [N][L*s*s][h][w]"}[layout],
+                                    sr.SR_COEFF_PRE_SHUFFLE: "pre_shuffle [N][L*s*s][h][w]",
+                                    sr.SR_COEFF_BLOCKED: "blocked [N][H][W/128][4 slots][pieces of 16 atoms][lane half][32][8]"}[layout],
                    "coeff_kind": "logits (softmax over the atoms applied by the call)" if args.logits else "values"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": read_traffic(wl.name),

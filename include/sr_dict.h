@@ -98,11 +98,22 @@ typedef enum {
                                   holds BEFORE its pixel-shuffle layer (section
                                   II-B, stage 2); channel l*s*s + i*s + j carries
                                   atom l at HR pixels (y*s + i, x*s + j)           */
-    SR_COEFF_PIXEL_MAJOR = 2   /* [N][s*h][s*w][L]: the L coefficients of a pixel
+    SR_COEFF_PIXEL_MAJOR = 2,  /* [N][s*h][s*w][L]: the L coefficients of a pixel
                                   side by side (what a producer that keeps its
                                   tensors channels-last writes); a storage order
                                   beyond the paper, same values, same result.  The
                                   descriptor keeps c = L, h = s*h, w = s*w.        */
+    SR_COEFF_BLOCKED     = 3   /* the order in which the matrix-core kernel consumes
+                                  the coefficients, for a producer willing to write
+                                  it (beyond the paper; same values, same result):
+                                  [N][s*h][s*w/128][4][piece][2][32][e].  A row is cut
+                                  into units of 128 pixels; pixel 4 j + q of a unit is
+                                  slot q, column j; a slot holds its 32 pixels' L
+                                  atoms as pieces of 16 atoms, [half][j][8 atoms]:
+                                  atom 16 piece + 8 half + e, and, if L % 16 == 8, a
+                                  last piece [half][j][4 atoms]: atom 16 (L/16) +
+                                  4 half + e.  Needs L % 8 == 0 and s*w % 128 == 0.
+                                  The descriptor keeps c = L, h = s*h, w = s*w.     */
 } sr_coeff_layout;
 
 /* What the stored `coeff` values are (sr_options.coeff_kind). */
@@ -194,6 +205,11 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
  * contiguous piece of memory.  Every kernel takes it; the matrix-core kernel for k = 5, C = 3, all
  * of L = 72 f16 atoms (no kept list), an HR width that is a multiple of 128 and under 4 GB of
  * coefficients per image, the generic kernel otherwise.
+ *
+ * opts->coeff_layout = SR_COEFF_BLOCKED: see sr_coeff_layout; L % 8 != 0 or an HR width that is not a multiple of 128 is
+ * SR_ERR_UNSUPPORTED.  A unit's 128 L coefficients are contiguous and every 16 bytes of it are a matrix-core operand of the
+ * lane that loads them: no re-packing, no staging.  Every kernel takes it; the matrix-core kernel for k = 5, C = 3, all of
+ * L = 72 f16 atoms (no kept list) and under 4 GB of coefficients per image, the generic kernel otherwise.
  *
  * opts->coeff_kind = SR_COEFF_LOGITS: `coeff` holds logits z (f32, f16 or bf16; any layout above) and the call
  * computes, per pixel and over all L atoms,

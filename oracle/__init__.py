@@ -244,18 +244,18 @@ def pixel_major_to_planar(coeff_pm) -> np.ndarray:
     return out
 
 
-def blocked_to_planar(coeff_blk, L: int) -> np.ndarray:
+def blocked_to_planar(coeff_blk) -> np.ndarray:
     """Coefficients stored blocked (an extension: the order in which a matrix-core kernel consumes them; see
-    orc_blocked_to_planar), ``coeff_blk`` [N][H][W * L] (a row's units of 128 pixels one after the other), as the planar
-    [N][L][H][W]: the same stored elements."""
+    orc_blocked_to_planar), ``coeff_blk`` [N][H][W / 128][128 * L] (a row's units of 128 pixels one after the other), as
+    the planar [N][L][H][W]: the same stored elements."""
     a = _stored(coeff_blk, "coeff_blk")
-    if a.ndim != 3 or a.shape[2] % L:
-        raise ValueError("coeff_blk must be [N][H][W * L]")
-    n, H, WL = a.shape
-    W = WL // L
+    if a.ndim != 4 or a.shape[3] % 128:
+        raise ValueError("coeff_blk must be [N][H][W / 128][128 * L]")
+    n, H, units, unit_elems = a.shape
+    L, W = unit_elems // 128, units * 128
     out = np.empty((n, L, H, W), dtype=a.dtype)
     if _load().orc_blocked_to_planar(_ptr(a), a.dtype.itemsize, n, int(L), H, W, _ptr(out)):
-        raise ValueError("orc_blocked_to_planar rejected its arguments (L % 8 == 0 and W % 128 == 0 are needed)")
+        raise ValueError("orc_blocked_to_planar rejected its arguments (L % 8 == 0 is needed)")
     return out
 
 
@@ -287,8 +287,8 @@ def dict_assemble(lr, coeff, dictionary, scale: int, kept=None, gamma=None, a: f
     [N][H][W][L] and are moved to planes first; with ``blocked`` they are stored in the blocked order
     (blocked_to_planar) and are moved to planes first.  With ``logits`` the stored values are logits and the
     coefficients their per-pixel softmax (see softmax_logits)."""
-    if blocked:                                      # [N][H][W * L], see blocked_to_planar
-        coeff = blocked_to_planar(coeff, np.asarray(dictionary).shape[0])
+    if blocked:                                      # [N][H][W / 128][128 * L], see blocked_to_planar
+        coeff = blocked_to_planar(coeff)
     if pixel_major:
         coeff = pixel_major_to_planar(coeff)
     if pre_shuffle:

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libsrdict.so")
 
 SR_F32, SR_F16, SR_F8E4M3, SR_BF16, SR_U8 = 0, 1, 2, 3, 4
 SR_KERNEL_AUTO, SR_KERNEL_GENERIC, SR_KERNEL_MFMA = 0, 1, 2
-SR_COEFF_PLANAR, SR_COEFF_PRE_SHUFFLE, SR_COEFF_PIXEL_MAJOR = 0, 1, 2
+SR_COEFF_PLANAR, SR_COEFF_PRE_SHUFFLE, SR_COEFF_PIXEL_MAJOR, SR_COEFF_BLOCKED = 0, 1, 2, 3
 SR_COEFF_VALUES, SR_COEFF_LOGITS = 0, 1
 SR_MAX_ATOMS = 256
 
@@ -117,10 +117,12 @@ def describe(t) -> sr_tensor:
 
 def describe_coeff(t, opts=None) -> sr_tensor:
     """Descriptor of the coefficient tensor for the layout named in ``opts``: a pixel-major tensor
-    [N][H][W][L] is described with c = L, h = H, w = W, as the header asks."""
+    [N][H][W][L] is described with c = L, h = H, w = W, as the header asks, and so is a blocked one."""
     d = describe(t)
     if opts is not None and opts.coeff_layout == SR_COEFF_PIXEL_MAJOR:
         d.c, d.h, d.w = int(t.shape[3]), int(t.shape[1]), int(t.shape[2])
+    if opts is not None and opts.coeff_layout == SR_COEFF_BLOCKED:           # [N][H][W / 128][128 * L]
+        d.c, d.h, d.w = int(t.shape[3]) // 128, int(t.shape[1]), int(t.shape[2]) * 128
     return d
 
 

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsrdict.so")
-SOURCES = ["sr_api.hip", "sr_generic.hip", "sr_list.hip", "sr_mfma.hip", "sr_mfma_k3.hip", "sr_mfma_k5.hip", "sr_mfma_k5_big.hip", "sr_mfma_k5_ps.hip", "sr_mfma_k5_pm.hip", "sr_mfma_k5_lg.hip", "sr_mfma_list.hip", "sr_mfma_k5_f32.hip", "sr_mfma_k5_f8.hip", "sr_mfma_k7.hip", "sr_mfma_k7_f8.hip", "sr_mfma_bf16.hip", "sr_probe.hip", "sr_select.hip"]
+SOURCES = ["sr_api.hip", "sr_generic.hip", "sr_list.hip", "sr_mfma.hip", "sr_mfma_k3.hip", "sr_mfma_k5.hip", "sr_mfma_k5_big.hip", "sr_mfma_k5_ps.hip", "sr_mfma_k5_pm.hip", "sr_mfma_k5_lg.hip", "sr_mfma_k5_blk.hip", "sr_mfma_list.hip", "sr_mfma_k5_f32.hip", "sr_mfma_k5_f8.hip", "sr_mfma_k7.hip", "sr_mfma_k7_f8.hip", "sr_mfma_bf16.hip", "sr_probe.hip", "sr_select.hip"]
 HEADERS = ["sr_device.h", "sr_launch.h", "sr_mfma_kernel.h", os.path.join("..", "..", "include", "sr_dict.h"),
            os.path.join("..", "..", "include", "sr_probe.h"),
            os.path.join("..", "..", "include", "sr_select.h")]

@@ -52,7 +52,7 @@ void make_plan(Plan& p, const sr_tensor* lr, const sr_tensor* coeff, const sr_te
     if (L < 1 || L > SR_MAX_ATOMS || channels < 1 || channels > SR_MAX_CHANNELS) {
         p.status = SR_ERR_UNSUPPORTED; return;
     }
-    if (opts && (opts->coeff_layout < SR_COEFF_PLANAR || opts->coeff_layout > SR_COEFF_PIXEL_MAJOR ||
+    if (opts && (opts->coeff_layout < SR_COEFF_PLANAR || opts->coeff_layout > SR_COEFF_BLOCKED ||
                  opts->coeff_kind < SR_COEFF_VALUES || opts->coeff_kind > SR_COEFF_LOGITS)) {
         p.status = SR_ERR_UNSUPPORTED; return;
     }
@@ -108,6 +108,8 @@ void make_plan(Plan& p, const sr_tensor* lr, const sr_tensor* coeff, const sr_te
     a.pre_shuffle = pre_shuffle ? 1 : 0;
     a.pixel_major = opts && opts->coeff_layout == SR_COEFF_PIXEL_MAJOR ? 1 : 0;
     a.logits = logits ? 1 : 0;
+    a.blocked = opts && opts->coeff_layout == SR_COEFF_BLOCKED ? 1 : 0;
+    if (a.blocked && (L % 8 != 0 || out->w % 128 != 0)) { p.status = SR_ERR_UNSUPPORTED; return; }   // the order does not exist
 
     const int want = opts ? opts->kernel : SR_KERNEL_AUTO;
     const int tile = opts ? opts->tile : 0;

@@ -32,6 +32,7 @@ struct AssembleArgs {
     int T;                // list form only: entries per pixel
     int pre_shuffle;      // coefficients are [N][L*s*s][h][w] (before the network's pixel-shuffle), else [N][L][H][W]
     int pixel_major;      // coefficients are [N][H][W][L] (a pixel's L coefficients side by side)
+    int blocked;          // coefficients are stored in the blocked order (SR_COEFF_BLOCKED)
     int logits;           // `coeff` holds logits: the coefficients are their per-pixel softmax over the atoms
     int   kept[SR_MAX_ATOMS];    // plane read for folded atom i (identity when dense)
     float gamma[SR_MAX_ATOMS];   // its scale (1 when dense)

@@ -52,7 +52,18 @@ __global__ __launch_bounds__(GNT) void k_assemble_generic(const AssembleArgs a) 
             : (size_t)Y * a.W + X;
         // ... or, pixel-major, the pixel's L coefficients side by side
         const size_t astride = a.pixel_major ? (size_t)1 : plane;
-        const TC* cbase = (const TC*)a.coeff + (size_t)n * a.L * plane + (a.pixel_major ? within * a.L : within);
+        // ... or blocked: units of 128 pixels, four slots (pixel 4 j + q is slot q, column j) of 32 L elements, pieces of
+        // 16 atoms [half][j][8] and a last piece [half][j][4] (see SR_COEFF_BLOCKED); atom l of this pixel is at
+        // blk_slot + blk_atom(l)
+        const size_t blk_slot = (((size_t)Y * (a.W / 128) + X / 128) * 4 + X % 4) * ((size_t)32 * a.L);
+        const int blk_j = (X % 128) / 4, blk_full = a.L / 16;
+        auto blk_atom = [&](int l) -> size_t {
+            if (l < 16 * blk_full) return (size_t)(l / 16) * 512 + (size_t)((l % 16) / 8) * 256 + (size_t)blk_j * 8 + l % 8;
+            const int t = l - 16 * blk_full;
+            return (size_t)blk_full * 512 + (size_t)(t / 4) * 128 + (size_t)blk_j * 4 + t % 4;
+        };
+        const TC* cbase = (const TC*)a.coeff + (size_t)n * a.L * plane + (a.blocked ? blk_slot : a.pixel_major ? within * a.L : within);
+        auto coff = [&](int l) -> size_t { return a.blocked ? blk_atom(l) : (size_t)l * astride; };
         // eight atoms at a time: their coefficient loads are in flight together
         constexpr int NB = 8;
         // logits instead of coefficients: a first pass over the pixel's planes for the largest logit
@@ -62,7 +73,7 @@ __global__ __launch_bounds__(GNT) void k_assemble_generic(const AssembleArgs a) 
             for (int i0 = 0; i0 < a.n_fold; i0 += NB) {
                 float z[NB];
 #pragma unroll
-                for (int b = 0; b < NB; ++b) z[b] = ld_as_float(cbase, (size_t)(i0 + b < a.n_fold ? i0 + b : a.n_fold - 1) * astride);
+                for (int b = 0; b < NB; ++b) z[b] = ld_as_float(cbase, coff(i0 + b < a.n_fold ? i0 + b : a.n_fold - 1));
 #pragma unroll
                 for (int b = 0; b < NB; ++b) m = fmaxf(m, z[b]);
             }
@@ -73,7 +84,7 @@ __global__ __launch_bounds__(GNT) void k_assemble_generic(const AssembleArgs a) 
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 const int i = i0 + b < a.n_fold ? i0 + b : a.n_fold - 1;      // past the end: re-read, unused
-                phi[b] = ld_as_float(cbase, (size_t)a.kept[i] * astride) * a.gamma[i];
+                phi[b] = ld_as_float(cbase, coff(a.kept[i])) * a.gamma[i];
                 if (a.logits) {                             // (no kept list, gamma = 1): exponential, rounded to fp16
                     phi[b] = __half2float(__float2half_rn(logit_exp(phi[b], nm)));
                     if (i0 + b < a.n_fold) esum += phi[b];

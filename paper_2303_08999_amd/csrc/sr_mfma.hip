@@ -18,6 +18,7 @@ hipError_t launch_mfma_bf16(const AssembleArgs& a, int k, int np8, hipStream_t s
 hipError_t launch_mfma_k5_ps(const AssembleArgs& a, int np8, hipStream_t st);
 hipError_t launch_mfma_k5_pm(const AssembleArgs& a, hipStream_t st);
 hipError_t launch_mfma_k5_lg(const AssembleArgs& a, hipStream_t st);
+hipError_t launch_mfma_k5_blk(const AssembleArgs& a, hipStream_t st);
 
 namespace {
 
@@ -78,7 +79,7 @@ static bool has_tile_shapes(const AssembleArgs& a, int k, int np8, int coeff_dty
 // alternative shapes); false elsewhere.
 bool mfma_tile_shape(const AssembleArgs& a, int k, int coeff_dtype, int tile, int* tw, int* th, int* waves, int* groups) {
     const int np8 = np8_for(k, a.C, a.n_fold, coeff_dtype);
-    return !a.logits && has_tile_shapes(a, k, np8, coeff_dtype) && tile_shape_k5(a, tile, tw, th, waves, groups);
+    return !a.logits && !a.blocked && has_tile_shapes(a, k, np8, coeff_dtype) && tile_shape_k5(a, tile, tw, th, waves, groups);
 }
 
 // pixels a lane loads with one vector load (its pixel group)
@@ -113,6 +114,14 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
         for (int i = 0; i < 72; ++i)
             if (a.kept[i] != i) return false;
     }
+    // coefficients stored blocked: one family built (all of 72 fp16 atoms, stored coefficients)
+    if (a.blocked) {
+        if (a.pre_shuffle || a.pixel_major || a.logits ||
+            !(k == 5 && a.C == 3 && coeff_dtype == SR_F16 && a.L == 72 && a.n_fold == 72 && !beyond_4gb(a, coeff_dtype) &&
+              a.W % 128 == 0 && tile == 0)) return false;
+        for (int i = 0; i < 72; ++i)
+            if (a.kept[i] != i) return false;
+    }
     // logits instead of coefficients: one family built (5x5, three channels, 49 to 72 fp16 or bfloat16 planes)
     // (in the layout before the pixel-shuffle: its permuted-slot forms, LR widths that are multiples of 4)
     if (a.logits && !(k == 5 && a.C == 3 && (coeff_dtype == SR_F16 || coeff_dtype == SR_BF16) && np8 == 9 && a.n_fold == a.L && !a.pixel_major &&
@@ -137,6 +146,7 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
 hipError_t launch_mfma(const AssembleArgs& a, int k, bool io_f16, int tile, hipStream_t st) {
     (void)io_f16;
     const int np8 = np8_for(k, a.C, a.n_fold, a.coeff_dtype);
+    if (a.blocked) return launch_mfma_k5_blk(a, st);
     if (a.logits) return launch_mfma_k5_lg(a, st);
     if (a.pixel_major) return launch_mfma_k5_pm(a, st);
     if (a.pre_shuffle) return launch_mfma_k5_ps(a, np8, st);

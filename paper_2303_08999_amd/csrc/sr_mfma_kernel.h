@@ -315,11 +315,19 @@ __device__ __forceinline__ void divmod_scale(int v, int s, int& q, int& r) {
 // re-packing.  Lane j's slots are the pixels j, 32 + j, 64 + j, 96 + j: the tile is stored without a
 // swizzle (consecutive lanes read consecutive words) and a lane stores single pixels (a wavefront half
 // still writes 128 contiguous bytes).  The fold, stage 4 and the result are the planar form's, bit for bit.
+//
+// PSM = 9: the coefficients are stored BLOCKED (SR_COEFF_BLOCKED; a storage order beyond the paper, for a producer that
+// is willing to write it): a unit's 128 x 72 coefficients are 18 432 contiguous bytes laid out as this kernel consumes
+// them - slot q (pixel 4 j + q of the unit), then pieces of 16 atoms [lane half][column j][8 atoms] and a last piece
+// [lane half][column j][4 atoms].  Lane (j, hf) = lane j + 32 hf loads 16 bytes at 16 * lane of a piece (a wavefront: 1 KB
+// of contiguous memory per load) and holds the B operand of that 16-atom step and slot as it stands: no re-packing, no
+// staging, and the slots are the planar form's four adjacent pixels, so stage 4 and the store are the planar form's too.
 template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT, int SMIN, bool BIG, int PSM = 0>
 __global__ __launch_bounds__(64 * NW, WPE)
 void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y, const int ntiles) {
     constexpr int NSUB = PSM == 4 ? 2 : (PSM == 3 ? 3 : 1);   // units per tile row
     constexpr bool PMAJ = PSM == 8;                // coefficients stored pixel-major, [H][W][L]
+    constexpr bool BLK = PSM == 9;                 // coefficients stored blocked: the loaded registers are the operands
     using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN, NSUB, (PMAJ ? 1 : 0)>;
     constexpr bool F32 = F::F32, F8 = F::F8, BF = F::BF, LIST = F::LIST, LG = F::LG;
     static_assert(!LG || (PX == 4 && (PSM == 0 || PSM == 2 || PSM == 3 || PSM == 4) && !BIG && F::NSLOT < 16 * F::NMB),
@@ -331,6 +339,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     static_assert(PSM == 0 || ((CT == CT_F16 || ((CT == CT_BF16 || CT == CT_LOGIT || CT == CT_LOGIT_BF16) && PSM != 1 && PSM != 8)) && !BIG && PX == 4),
                   "pre-shuffle layout: 16-bit coefficients, four pixels per lane");
     static_assert(!PMAJ || (CT == CT_F16 && WR == 1 && NP8 == 9), "pixel-major coefficients: 72 fp16 atoms, one row per unit");
+    static_assert(!BLK || (CT == CT_F16 && WR == 1 && PX == 4), "blocked coefficients: fp16, one row of 128 pixels per unit");
     static_assert(!PERM || (WR == 1 && SMIN >= PSM), "permuted slots: one row per wavefront and unit");
     // row of the wavefront's unit within the tile, and which of the row's NSUB units it is
     auto unit_row = [](int unit, int wave_) { return (unit / NSUB) * NW + wave_; };
@@ -644,6 +653,21 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     auto pm_image = [&](const TilePos tp) -> const char* {
         return (const char*)a.coeff + (size_t)tp.n * a.L * ((size_t)a.H * a.W * 2);
     };
+    // blocked: byte offset of a unit within its image (a unit: 128 pixels x 8 NP8 atoms, contiguous), and its loads
+    u32x4 b16[BLK ? PX : 1][BLK && N16 ? N16 : 1];
+    u32x2 b8[BLK ? PX : 1];
+    constexpr unsigned SLOT_B = 32u * 16u * NP8;   // bytes of a slot: 32 pixels x 8 NP8 fp16 atoms
+    auto blk_offset = [&](const TilePos tp, int unit) -> unsigned {
+        const int y = tp.ty * F::TH + unit * NW + wave;
+        const unsigned yc = (unsigned)(y < a.H ? y : a.H - 1);                 // rows past the image re-read its last row
+        return (yc * (unsigned)(a.W / 128) + (unsigned)tp.tx) * (4u * SLOT_B);
+    };
+    auto blk_load16 = [&](const char* img, unsigned unit_off, int lane_, int q, int c16) -> u32x4 {
+        return __builtin_nontemporal_load((const u32x4*)(img + (unit_off + (unsigned)q * SLOT_B + 1024u * c16 + 16u * lane_)));
+    };
+    auto blk_load8 = [&](const char* img, unsigned unit_off, int lane_, int q) -> u32x2 {
+        return __builtin_nontemporal_load((const u32x2*)(img + (unit_off + (unsigned)q * SLOT_B + 1024u * N16 + 8u * lane_)));
+    };
     Raw raw[F::NLOAD];
     unsigned lrv[F::NLRP][F::NXC], lrpar = 0u;
 #pragma unroll
@@ -660,6 +684,15 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             const unsigned off = pm_offset(cur, 0, lane);
 #pragma unroll
             for (int i = 0; i < NPM; ++i) pm[i] = __builtin_nontemporal_load((const u32x4*)(img + (off + 1024u * i)));
+        } else if constexpr (BLK) {
+            const char* img = pm_image(cur);
+            const unsigned off = blk_offset(cur, 0);
+#pragma unroll
+            for (int q = 0; q < PX; ++q) {
+#pragma unroll
+                for (int c16 = 0; c16 < N16; ++c16) b16[q][c16] = blk_load16(img, off, lane, q, c16);
+                if constexpr (N8 != 0) b8[q] = blk_load8(img, off, lane, q);
+            }
         } else {
             unsigned pix_off[NPIX];
             const char* cimg = phi_base(cur, 0, j / F::WC, j % F::WC, pix_off);
@@ -814,7 +847,13 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         const bool more = last_unit ? more_tiles : true;
         unsigned pix_next[NPIX];
         const char* cnext = nullptr;
-        if constexpr (!LIST && !PMAJ) cnext = last_unit ? phi_base(nxt, 0, jr, jc, pix_next) : phi_base(cur, unit + 1, jr, jc, pix_next);
+        if constexpr (!LIST && !PMAJ && !BLK) cnext = last_unit ? phi_base(nxt, 0, jr, jc, pix_next) : phi_base(cur, unit + 1, jr, jc, pix_next);
+        const char* bimg = nullptr;                    // blocked: the next unit's image and offset
+        unsigned boff = 0u;
+        if constexpr (BLK) {
+            bimg = last_unit ? pm_image(nxt) : pm_image(cur);
+            boff = last_unit ? blk_offset(nxt, 0) : blk_offset(cur, unit + 1);
+        }
 
         // (3) stage 3 on the matrix cores: atom steps outer, pixel slots inner
         f32x16 acc[PX][NMB];
@@ -985,7 +1024,9 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 for (int hl = 0; hl < 2; ++hl) av[mb][hl] = A16[((c16 * NMB + mb) * 2 + hl) * 64 + lane];
             constexpr int NWORD = PX / 2 > 0 ? PX / 2 : 1;
             unsigned cw[8][NWORD];                  // the step's 8 planes as fp16 pixel pairs
-            if constexpr (F8) {
+            if constexpr (BLK) {
+                // (blocked: the loaded registers are the operands)
+            } else if constexpr (F8) {
                 // 8-bit coefficients: pair the planes' BYTES first (two permutes per plane pair), widen afterwards
 #pragma unroll
                 for (int m = 0; m < 4; ++m) pair_bytes(raw_word(raw[8 * c16 + 2 * m], 0), raw_word(raw[8 * c16 + 2 * m + 1], 0), cw[2 * m]);
@@ -996,8 +1037,9 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 #pragma unroll
             for (int q = 0; q < PX; ++q) {
                 u32x4 bw;
+                if constexpr (BLK) bw = b16[q][c16];
 #pragma unroll
-                for (int m = 0; m < 4; ++m)
+                for (int m = 0; m < (BLK ? 0 : 4); ++m)
                     bw[m] = F8 ? widen_pair(cw[2 * m][q >> 1], q)
                           : LG ? exp_pair<F::LGB>(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q, nm[q])
                                : pack_pair(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q);
@@ -1008,9 +1050,14 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             }
             __builtin_amdgcn_sched_barrier(0);
             if (more) {
+                if constexpr (BLK) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    raw[8 * c16 + i] = load_raw(cnext, pix_next, pt[8 * c16 + i]);
+                    for (int q = 0; q < PX; ++q) b16[q][c16] = blk_load16(bimg, boff, lane, q, c16);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        raw[8 * c16 + i] = load_raw(cnext, pix_next, pt[8 * c16 + i]);
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -1022,7 +1069,8 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 for (int hl = 0; hl < 2; ++hl) av[mb][hl] = A8[(mb * 2 + hl) * 64 + lane];
             constexpr int NWORD = PX / 2 > 0 ? PX / 2 : 1;
             unsigned cw[4][NWORD];
-            if constexpr (F8) {
+            if constexpr (BLK) {
+            } else if constexpr (F8) {
 #pragma unroll
                 for (int m = 0; m < 2; ++m) pair_bytes(raw_word(raw[8 * N16 + 2 * m], 0), raw_word(raw[8 * N16 + 2 * m + 1], 0), cw[2 * m]);
             } else {
@@ -1032,8 +1080,9 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 #pragma unroll
             for (int q = 0; q < PX; ++q) {
                 u32x2 bw;
+                if constexpr (BLK) bw = b8[q];
 #pragma unroll
-                for (int m = 0; m < 2; ++m)
+                for (int m = 0; m < (BLK ? 0 : 2); ++m)
                     bw[m] = F8 ? widen_pair(cw[2 * m][q >> 1], q)
                           : LG ? exp_pair<F::LGB>(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q, nm[q])
                                : pack_pair(cw[2 * m][q >> 1], cw[2 * m + 1][q >> 1], q);
@@ -1044,9 +1093,14 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             }
             __builtin_amdgcn_sched_barrier(0);
             if (more) {
+                if constexpr (BLK) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    raw[8 * N16 + i] = load_raw(cnext, pix_next, pt[8 * N16 + i]);
+                    for (int q = 0; q < PX; ++q) b8[q] = blk_load8(bimg, boff, lane, q);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        raw[8 * N16 + i] = load_raw(cnext, pix_next, pt[8 * N16 + i]);
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -1300,6 +1354,8 @@ hipError_t launch_one(const AssembleArgs& a0, hipStream_t st) {
     if ((a0.logits != 0) != (CT == CT_LOGIT || CT == CT_LOGIT_BF16) || (a0.logits && a0.n_fold != a0.L)) return hipErrorInvalidValue;
     if (a0.logits && (a0.coeff_dtype == SR_BF16) != (CT == CT_LOGIT_BF16)) return hipErrorInvalidValue;
     if (PSM == 8 && (a0.W % 128 != 0 || a0.L != 8 * NP8 || a0.n_fold != a0.L)) return hipErrorInvalidValue;
+    if ((a0.blocked != 0) != (PSM == 9)) return hipErrorInvalidValue;
+    if (PSM == 9 && (a0.W % 128 != 0 || a0.L != 8 * NP8 || a0.n_fold != a0.L)) return hipErrorInvalidValue;
     // permuted pixel slots: a lane owns four whole LR columns, the image must end on such a group
     if ((PSM == 2 || PSM == 3 || PSM == 4) && (a0.s != PSM || a0.w % 4 != 0)) return hipErrorInvalidValue;
     AssembleArgs a = a0;

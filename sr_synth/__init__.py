@@ -114,7 +114,7 @@ def to_pixel_major(coeff):
 
 def to_blocked(coeff):
     """The same stored coefficients in the blocked order (the order in which a matrix-core kernel consumes them; an
-    extension of the storage formats): [N][L][H][W] -> [N][H][W * L] with, per row, units of 128 pixels, per unit four
+    extension of the storage formats): [N][L][H][W] -> [N][H][W / 128][128 * L] with, per row, units of 128 pixels, per unit four
     slots q (pixel 4 j + q is slot q, column j), per slot pieces of 16 atoms [half][j][8 atoms] and, if L % 16 == 8, a
     last piece [half][j][4 atoms].  A move of elements; needs L % 8 == 0 and W % 128 == 0."""
     raw = coeff.view(torch.uint8) if coeff.dtype == torch.float8_e4m3fn else coeff
@@ -129,7 +129,7 @@ def to_blocked(coeff):
     if L % 16:
         parts.append(x[:, 16 * full:].reshape(n, 2, 4, H, units, 32, 4)
                      .permute(0, 3, 4, 6, 1, 5, 2).reshape(n, H, units, 4, 256))
-    blk = torch.cat(parts, dim=4).reshape(n, H, W * L).contiguous()
+    blk = torch.cat(parts, dim=4).reshape(n, H, units, 128 * L).contiguous()
     return blk.view(coeff.dtype) if raw is not coeff else blk
 
 

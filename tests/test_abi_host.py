@@ -221,7 +221,7 @@ def test_pre_shuffle_layout_is_checked_on_the_host(lib):
     bad = ps_case()
     bad[1].c = 72 * 16 - 1
     assert plan(*bad, opts=o()) == -2
-    assert plan(*ps_case(), opts=sr.make_options(0, 0, 3)) == -3                          # unknown layout code
+    assert plan(*ps_case(), opts=sr.make_options(0, 0, 4)) == -3                          # unknown layout code
     # pixel-major storage [N][H][W][L]: described like the planar tensor; the matrix-core kernel takes all of 72 fp16
     # atoms of 5x5 on three channels with an HR width of whole 128-pixel units, the generic kernel everything else
     pm = lambda kernel=sr.SR_KERNEL_AUTO, tile=0: sr.make_options(kernel, tile, sr.SR_COEFF_PIXEL_MAJOR)
@@ -235,6 +235,23 @@ def test_pre_shuffle_layout_is_checked_on_the_host(lib):
     assert plan(*case(w=64), opts=pm(sr.SR_KERNEL_MFMA, 3)) == -3                          # no alternative tiles in this layout
     for kw, pk in (({"cd": sr.SR_F32}, {}), ({"cd": sr.SR_BF16}, {}), ({"k": 7}, {"k": 7}), ({"C": 1}, {"C": 1}), ({"L": 64}, {"L": 64})):
         assert plan(*case(w=64, **kw), **pk, opts=pm()) == sr.SR_KERNEL_GENERIC, kw
+
+
+def test_blocked_layout_is_checked_on_the_host(lib):
+    """SR_COEFF_BLOCKED: units of 128 pixels and groups of 8 atoms or the order does not exist; described like the planar tensor."""
+    bl = lambda kernel=sr.SR_KERNEL_AUTO, tile=0: sr.make_options(kernel, tile, sr.SR_COEFF_BLOCKED)
+    assert plan(*case(w=64), opts=bl()) == sr.SR_KERNEL_MFMA
+    assert plan(*case(w=64), opts=bl(sr.SR_KERNEL_GENERIC)) == sr.SR_KERNEL_GENERIC
+    assert plan(*case(w=48), opts=bl()) == -3                                             # HR width 192: not whole units
+    assert plan(*case(w=64, L=70), L=70, opts=bl()) == -3                                 # not whole groups of 8 atoms
+    assert plan(*case(w=64), kept=[3, 9, 70], opts=bl()) == sr.SR_KERNEL_GENERIC
+    assert plan(*case(w=64), kept=list(range(72)), opts=bl()) == sr.SR_KERNEL_MFMA        # the identity list is no list
+    assert plan(*case(w=64), opts=bl(sr.SR_KERNEL_MFMA, 3)) == -3                          # no alternative tiles in this layout
+    for kw, pk in (({"cd": sr.SR_F32}, {}), ({"cd": sr.SR_BF16}, {}), ({"k": 7}, {"k": 7}), ({"C": 1}, {"C": 1}), ({"L": 64}, {"L": 64})):
+        assert plan(*case(w=64, **kw), **pk, opts=bl()) == sr.SR_KERNEL_GENERIC, kw
+    lg = sr.make_options(0, 0, sr.SR_COEFF_BLOCKED, sr.SR_COEFF_LOGITS)
+    assert plan(*case(w=64), opts=lg) == sr.SR_KERNEL_GENERIC                             # blocked logits: the generic kernel
+    assert plan(*case(w=64), opts=sr.make_options(0, 0, 4)) == -3                          # unknown layout code
 
 
 def test_logits_option_is_checked_on_the_host(lib):
