@@ -54,6 +54,18 @@
 // Other coefficient layouts (template argument PSM): the planes as the coefficient
 // network holds them before its pixel-shuffle layer (see the kernel's own comment).
 //
+// L2 write-back pacing.  The output leaves the CUs as ordinary stores and sits in the XCDs' L2s as dirty lines that
+// the L2 writes to memory when it sees fit, interleaved with the read stream; reads and writes that alternate at the
+// memory cost more than their bytes (the stores of the 4K frame, 7.6 % of the bytes, cost 22 % of the time).  One
+// wavefront per XCD (wavefront 0 of workgroups 0 .. 7, which the dispatcher deals to the eight XCDs) therefore asks
+// its L2 every 16 us - by a constant-rate clock, checked once per unit - to write its dirty lines back NOW (an
+// agent-scope release fence, which the compiler turns into the L2 write-back instruction and a wait): the writes
+// reach memory in bursts and the reads in between run undisturbed.  Measured: 4K frame 254 -> 241 us, the blocked
+// order 240 -> 231 us, 1080p 68 -> 65.5 us, sixteen video frames 1.80 -> 1.72 ms, 58 kept atoms 224 -> 215 us; neutral
+// at 43 kept atoms and for 720p fp32, 1-2 % slower with fewer atoms and with 8-bit coefficients, which are not bound
+// by the stream: those instantiations are launched without it.  The period was swept from 4 to 48 us (8 us and
+// less cost time, beyond 32 us the gain fades); results are bit-identical.  -DSR_NO_L2_WRITEBACK builds without it.
+//
 // Measurement builds (python -m paper_2303_08999_amd.build -o other.so -DSR_ABLATE_...): the
 // same launch with a part switched off, to see what that part costs.  SR_ABLATE_STORES keeps
 // every instruction but never executes the output stores; SR_ABLATE_STAGE1 skips the two
@@ -809,6 +821,7 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         }
     };
 
+    unsigned long long wb_last = a.wb_ticks > 0 ? __builtin_amdgcn_s_memrealtime() : 0ull;
     for (int t = t_first; t < t_end; t += G) {
         // Per-iteration copy of the thread id the optimiser cannot see through:
         // index arithmetic derived from it is recomputed each tile instead of
@@ -1319,6 +1332,14 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 }
             }
         }
+        // (6) L2 write-back pacing, see the note at the top of this file: workgroups 0 .. 7 run on the eight XCDs
+        if (a.wb_ticks > 0 && (int)blockIdx.x < 8 && wave == 0) {
+            const unsigned long long now = __builtin_amdgcn_s_memrealtime();
+            if (now - wb_last >= (unsigned long long)a.wb_ticks) {
+                wb_last = now;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            }
+        }
         // (2) prefetch the next tile's LR footprint from inside the unit loop, where
         //     the wavefront waits on memory anyway, and not in the barrier-to-barrier
         //     up-sampling phase that every wavefront of the workgroup has to sit out
@@ -1344,6 +1365,20 @@ inline int compute_units() {
     return known[dev];
 }
 
+// rate of the constant clock s_memrealtime reads, in kHz (asked once per device and thread; 100 MHz if the runtime
+// does not say)
+inline long long wall_clock_khz() {
+    static thread_local int known[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 100000;
+    if (known[dev] == 0) {
+        int khz = 0;
+        if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz < 1000) khz = 100000;
+        known[dev] = khz;
+    }
+    return known[dev];
+}
+
 template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT = CT_F16, int SMIN = 2, bool BIG = false,
           int PSM = 0>
 hipError_t launch_one(const AssembleArgs& a0, hipStream_t st) {
@@ -1359,6 +1394,12 @@ hipError_t launch_one(const AssembleArgs& a0, hipStream_t st) {
     // permuted pixel slots: a lane owns four whole LR columns, the image must end on such a group
     if ((PSM == 2 || PSM == 3 || PSM == 4) && (a0.s != PSM || a0.w % 4 != 0)) return hipErrorInvalidValue;
     AssembleArgs a = a0;
+#ifndef SR_NO_L2_WRITEBACK
+    // L2 write-back pacing where the coefficient stream is the bound: 49 atoms and more, not the 8-bit and list forms
+    // (measured neutral at 43 kept atoms, 1-2 % slower below and with 8-bit coefficients)
+    if (NP8 >= 9 && CT != CT_F8 && !F::LIST)
+        a.wb_ticks = (int)(16LL * wall_clock_khz() / 1000);     // 16 us of the constant-rate clock the kernel reads
+#endif
     const int tiles_x = (a.W + F::TW - 1) / F::TW, tiles_y = (a.H + F::TH - 1) / F::TH;
     a.xlast = (tiles_x - 1) * F::TW;
     if (a.W % PX != 0) {                                // ragged rows: the last tile column ends at the image edge
