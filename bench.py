@@ -69,6 +69,8 @@ def empirical_ceilings(sr, torch, wl, coeffs, outs, kernel_ms, inp_lr, inp_dict)
         tile_h = shape[1] if shape[0] == 128 else (24 if eb == 1 and wl.scale == 4 and wl.hr_pixels > 400000 else 16)
         t_tiled = timed(lambda i: sr.sr_probe_mix_tiled(coeffs[i % len(coeffs)][0], wl.L, wl.H, wl.W, tile_h, outs[i % 2][0], wl.c,
                                                         elem_bytes=eb))
+        t_paced = timed(lambda i: sr.sr_probe_mix_tiled(coeffs[i % len(coeffs)][0], wl.L, wl.H, wl.W, tile_h, outs[i % 2][0], wl.c,
+                                                        elem_bytes=eb, pace_us=16))
     # the same bytes with nothing of the kernel's access pattern: 16-byte accesses, readers and
     # writers in separate workgroups, two workgroups per CU, every 9th one a writer
     t_stream = timed(lambda i: sr.sr_probe_stream(coeffs[i % len(coeffs)][0], coeff_bytes, outs[i % 2][0], wl.c * px * 4,
@@ -78,11 +80,14 @@ def empirical_ceilings(sr, torch, wl, coeffs, outs, kernel_ms, inp_lr, inp_dict)
             "kernel_time_over_mix_time": round(kernel_ms * 1.0 / (t_mix * wl.n), 3) if t_mix else None,
             "tiled_mix_ms": round(t_tiled, 4) if t_tiled else None,
             "kernel_time_over_tiled_mix_time": round(kernel_ms * 1.0 / (t_tiled * wl.n), 3) if t_tiled else None,
+            "tiled_mix_paced_ms": round(t_paced, 4) if t_tiled else None,
+            "kernel_time_over_tiled_mix_paced_time": round(kernel_ms * 1.0 / (t_paced * wl.n), 3) if t_tiled else None,
             "independent_mix_GBps": round(mix_bytes / t_stream / 1e6, 1), "independent_mix_ms": round(t_stream, 4),
             "kernel_time_over_independent_mix_time": round(kernel_ms * 1.0 / (t_stream * wl.n), 3),
             "note": "streaming probes of the same library on one frame's coefficient planes: read-only; the kernel's "
                     "own read + write pattern with no arithmetic, run by run (mix) and in the kernel's own tile order (tiled_mix: what is "
-                    "left of the kernel when only its memory requests remain); and the same bytes with 16-byte accesses by "
+                    "left of the kernel when only its memory requests remain; tiled_mix_paced: with the kernel's L2 write-back "
+                    "pacing, every 16 us, among them); and the same bytes with 16-byte accesses by "
                     "separate reader and writer workgroups (independent_mix), whose writers finish before its readers, so "
                     "that part of the reading runs undisturbed"}
 

@@ -46,6 +46,12 @@ int sr_probe_mix_tiled(const void* coeff, int planes, int height, int width, int
 int sr_probe_mix_tiled_bytes(const void* coeff, int planes, int elem_bytes, int height, int width, int tile_h, void* out,
                              int channels, void* stream);
 
+/* As sr_probe_mix_tiled_bytes, with the assembly kernel's L2 write-back pacing among the requests: pace_us > 0 makes one
+ * wavefront per XCD ask its L2 every pace_us microseconds to write its dirty lines back (the kernel's period is 16);
+ * 0 = none, 0 <= pace_us <= 1 000 000. */
+int sr_probe_mix_tiled_paced(const void* coeff, int planes, int elem_bytes, int height, int width, int tile_h, void* out,
+                             int channels, int pace_us, void* stream);
+
 /* A byte mix with NOTHING of the assembly kernel's access pattern in it: one launch of
  * `blocks` workgroups of 256 threads in which every `writer_every`-th workgroup only
  * writes (16-byte stores sweeping `dst`, `write_bytes` in all) and all others only read

@@ -21,7 +21,7 @@ SR_MAX_ATOMS = 256
 
 EXPORTS = ("sr_dict_assemble", "sr_dict_assemble_selective", "sr_dict_assemble_ex", "sr_dict_assemble_list", "sr_dict_assemble_list_ex",
            "sr_bicubic_upsample", "sr_dict_assemble_plan", "sr_dict_assemble_tile", "sr_dict_assemble_launch_shape", "sr_strerror", "sr_version",
-           "sr_probe_read", "sr_probe_mix", "sr_probe_mix_tiled", "sr_probe_mix_tiled_bytes", "sr_probe_stream", "sr_probe_pattern", "sr_probe_policy", "sr_probe_policy_bits",
+           "sr_probe_read", "sr_probe_mix", "sr_probe_mix_tiled", "sr_probe_mix_tiled_bytes", "sr_probe_mix_tiled_paced", "sr_probe_stream", "sr_probe_pattern", "sr_probe_policy", "sr_probe_policy_bits",
            "sr_atom_gram_workspace_bytes", "sr_atom_gram", "sr_atom_gram_static", "sr_select_atoms")
 
 
@@ -74,6 +74,8 @@ def load():
     lib.sr_probe_mix_tiled.restype = i
     lib.sr_probe_mix_tiled_bytes.argtypes = [vp, i, i, i, i, i, vp, i, vp]
     lib.sr_probe_mix_tiled_bytes.restype = i
+    lib.sr_probe_mix_tiled_paced.argtypes = [vp, i, i, i, i, i, vp, i, i, vp]
+    lib.sr_probe_mix_tiled_paced.restype = i
     lib.sr_probe_pattern.argtypes = [vp, vp, ctypes.c_size_t, i, i, i, i, i, ctypes.c_size_t, vp, vp]
     lib.sr_probe_policy.argtypes = [vp, vp, ctypes.c_size_t, i, i, i, i, vp, vp]
     lib.sr_probe_policy_bits.argtypes = [vp, vp, ctypes.c_size_t, i, i, i, vp, vp]
@@ -262,12 +264,16 @@ def sr_probe_mix(coeff, planes, pixels, out, channels, stream=None):
                                ctypes.c_void_p(out.data_ptr()), channels, _stream(stream)))
 
 
-def sr_probe_mix_tiled(coeff, planes, height, width, tile_h, out, channels, stream=None, elem_bytes=2):
+def sr_probe_mix_tiled(coeff, planes, height, width, tile_h, out, channels, stream=None, elem_bytes=2, pace_us=0):
     """The assembly kernel's memory requests in its own tile order, nothing else (include/sr_probe.h);
-    ``elem_bytes`` = 1 for planes of 8-bit coefficients (sr_probe_mix_tiled_bytes)."""
+    ``elem_bytes`` = 1 for planes of 8-bit coefficients (sr_probe_mix_tiled_bytes); ``pace_us`` > 0 adds the kernel's
+    L2 write-back pacing (sr_probe_mix_tiled_paced)."""
     assert coeff.numel() * coeff.element_size() >= planes * height * width * elem_bytes
     assert out.numel() * out.element_size() >= channels * height * width * 4
-    if elem_bytes == 2:
+    if pace_us:
+        _check(load().sr_probe_mix_tiled_paced(ctypes.c_void_p(coeff.data_ptr()), planes, elem_bytes, height, width, tile_h,
+                                               ctypes.c_void_p(out.data_ptr()), channels, int(pace_us), _stream(stream)))
+    elif elem_bytes == 2:
         _check(load().sr_probe_mix_tiled(ctypes.c_void_p(coeff.data_ptr()), planes, height, width, tile_h,
                                          ctypes.c_void_p(out.data_ptr()), channels, _stream(stream)))
     else:

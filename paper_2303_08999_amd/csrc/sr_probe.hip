@@ -78,8 +78,12 @@ __global__ __launch_bounds__(256) void k_probe_mix(const char* __restrict__ p, s
 // (EB: bytes per stored coefficient, 2 or 1; with one byte the row is 4 bytes per lane, as the kernel's 8-bit form loads)
 template <int L, int EB>
 __global__ __launch_bounds__(256, 2) void k_probe_mix_tiled(const char* __restrict__ p, int H, int W, int tile_h, int tiles_x,
-                                                            int ntiles, float* __restrict__ out, int channels) {
+                                                            int ntiles, float* __restrict__ out, int channels, int pace_ticks) {
     typedef typename std::conditional<EB == 2, u32x2, unsigned>::type Piece;       // a lane's four pixels of a plane
+    // pace_ticks > 0: as the kernel does, wavefront 0 of workgroups 0 .. 7 (one per XCD) asks its L2 to write its dirty
+    // lines back whenever that many ticks of the constant-rate clock have passed (checked once per row)
+    const bool pacer = pace_ticks > 0 && blockIdx.x < 8 && (threadIdx.x >> 6) == 0;
+    unsigned long long paced_at = pacer ? __builtin_amdgcn_s_memrealtime() : 0ull;
     auto fold = [](const Piece& v) -> unsigned {
         if constexpr (EB == 2) return v[0] ^ v[1];
         else return v;
@@ -125,6 +129,13 @@ __global__ __launch_bounds__(256, 2) void k_probe_mix_tiled(const char* __restri
                 for (int c = 0; c < channels; ++c) *(float2*)(out + (size_t)c * pixels + cur + 2 * hf) = make_float2(f, f + (float)c);
             cur = nxt;
             in_cur = in_next;
+            if (pacer) {
+                const unsigned long long now = __builtin_amdgcn_s_memrealtime();
+                if (now - paced_at >= (unsigned long long)pace_ticks) {
+                    paced_at = now;
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                }
+            }
         }
     }
 }
@@ -473,9 +484,16 @@ int sr_probe_mix_tiled(const void* coeff, int planes, int height, int width, int
 extern "C" __attribute__((visibility("default")))
 int sr_probe_mix_tiled_bytes(const void* coeff, int planes, int elem_bytes, int height, int width, int tile_h, void* out, int channels,
                              void* stream) {
+    return sr_probe_mix_tiled_paced(coeff, planes, elem_bytes, height, width, tile_h, out, channels, 0, stream);
+}
+
+extern "C" __attribute__((visibility("default")))
+int sr_probe_mix_tiled_paced(const void* coeff, int planes, int elem_bytes, int height, int width, int tile_h, void* out, int channels,
+                             int pace_us, void* stream) {
     if (!coeff || !out) return SR_ERR_NULL;
     if ((planes != 72 && planes != 128) || (elem_bytes != 1 && elem_bytes != 2) || channels < 1 || channels > 4 || height < 0 ||
-        width < 0 || width % 128 != 0 || tile_h < 1 || tile_h > 64 || (long long)height * width >= (1ll << 31)) return SR_ERR_UNSUPPORTED;
+        width < 0 || width % 128 != 0 || tile_h < 1 || tile_h > 64 || (long long)height * width >= (1ll << 31) ||
+        pace_us < 0 || pace_us > 1000000) return SR_ERR_UNSUPPORTED;
     if ((uintptr_t)coeff % 16 != 0 || (uintptr_t)out % 16 != 0) return SR_ERR_ALIGN;
     if (height == 0 || width == 0) return SR_OK;
     const int tiles_x = width / 128, tiles_y = (height + tile_h - 1) / tile_h;
@@ -483,8 +501,12 @@ int sr_probe_mix_tiled_bytes(const void* coeff, int planes, int elem_bytes, int 
     const int blocks = nt < 512 ? (int)nt : 512;
     auto kern = planes == 72 ? (elem_bytes == 2 ? k_probe_mix_tiled<72, 2> : k_probe_mix_tiled<72, 1>)
                              : (elem_bytes == 2 ? k_probe_mix_tiled<128, 2> : k_probe_mix_tiled<128, 1>);
+    int khz = 0, dev = 0;                              // rate of the constant clock the kernel reads (100 MHz if the runtime does not say)
+    if (pace_us > 0 && (hipGetDevice(&dev) != hipSuccess ||
+                        hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz < 1000)) khz = 100000;
+    const int pace_ticks = (int)((long long)pace_us * khz / 1000);
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
-                       (const char*)coeff, height, width, tile_h, tiles_x, (int)nt, (float*)out, channels);
+                       (const char*)coeff, height, width, tile_h, tiles_x, (int)nt, (float*)out, channels, pace_ticks);
     return hipGetLastError() == hipSuccess ? SR_OK : SR_ERR_LAUNCH;
 }
 

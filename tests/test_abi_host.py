@@ -473,6 +473,8 @@ def test_probe_argument_checks_launch_nothing(lib):
     assert lib.sr_probe_mix_tiled_bytes(good, 72, 4, 16, 128, 16, sink, 3, None) == -3   # one or two bytes per coefficient
     assert lib.sr_probe_mix_tiled_bytes(None, 72, 1, 16, 128, 16, sink, 3, None) == -1
     assert lib.sr_probe_mix_tiled_bytes(good, 72, 1, 0, 128, 16, sink, 3, None) == 0
+    assert lib.sr_probe_mix_tiled_paced(good, 72, 2, 16, 128, 16, sink, 3, -1, None) == -3
+    assert lib.sr_probe_mix_tiled_paced(good, 72, 2, 0, 128, 16, sink, 3, 16, None) == 0
     # sr_probe_stream(src, read_bytes, dst, write_bytes, blocks, writer_every, lds_bytes, nt_store, sink, stream)
     ps = lib.sr_probe_stream
     assert ps(None, 1024, good, 1024, 26, 13, 0, 0, sink, None) == -1

@@ -42,6 +42,11 @@ def test_tiled_mix_probe_writes_what_the_flat_one_writes(planes, channels, H, W,
     sr.sr_probe_mix_tiled(words, planes, H, W, tile_h, tiled, channels)
     torch.cuda.synchronize()
     assert torch.equal(flat, tiled)
+    # with the L2 write-back pacing among its requests (a period short enough to fire): the same values
+    paced = torch.full((channels, pixels), -3.0, device="cuda")
+    sr.sr_probe_mix_tiled(words, planes, H, W, tile_h, paced, channels, pace_us=1)
+    torch.cuda.synchronize()
+    assert torch.equal(flat, paced)
 
 
 @pytest.mark.parametrize("planes,channels,H,W,tile_h", [(72, 3, 50, 256, 24), (128, 2, 9, 384, 4), (72, 3, 700, 1280, 24)])
