@@ -45,7 +45,7 @@
 extern "C" {
 #endif
 
-#define SR_VERSION 200           /* major*10000 + minor*100 + patch */
+#define SR_VERSION 300           /* major*10000 + minor*100 + patch */
 #define SR_MAX_ATOMS 256         /* largest L (and n_kept) accepted   */
 #define SR_MAX_CHANNELS 16       /* largest C accepted                */
 

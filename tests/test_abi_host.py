@@ -47,7 +47,7 @@ def test_a_missing_library_fails_loudly(lib, tmp_path, monkeypatch):
 
 
 def test_version_and_strerror(lib):
-    assert sr.sr_version() == 200
+    assert sr.sr_version() == 300
     assert sr.sr_strerror(0) == "success"
     for code in range(-8, 0):
         assert sr.sr_strerror(code) not in ("", "success", "unknown status")
