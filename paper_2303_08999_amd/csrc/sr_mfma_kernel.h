@@ -64,7 +64,8 @@
 // order 240 -> 231 us, 1080p 68 -> 65.5 us, sixteen video frames 1.80 -> 1.72 ms, 58 kept atoms 224 -> 215 us; neutral
 // at 43 kept atoms and for 720p fp32, 1-2 % slower with fewer atoms and with 8-bit coefficients, which are not bound
 // by the stream: those instantiations are launched without it.  The period was swept from 4 to 48 us (8 us and
-// less cost time, beyond 32 us the gain fades); results are bit-identical.  -DSR_NO_L2_WRITEBACK builds without it.
+// less cost time, beyond 32 us the gain fades; sixteen video frames of 7x7 atoms: 1.72 ms at 16 us, 1.69 at 24 to 32,
+// hence 28 us there); results are bit-identical.  -DSR_NO_L2_WRITEBACK builds without it.
 //
 // Measurement builds (python -m paper_2303_08999_amd.build -o other.so -DSR_ABLATE_...): the
 // same launch with a part switched off, to see what that part costs.  SR_ABLATE_STORES keeps
@@ -1398,7 +1399,8 @@ hipError_t launch_one(const AssembleArgs& a0, hipStream_t st) {
     // L2 write-back pacing where the coefficient stream is the bound: 49 atoms and more, not the 8-bit and list forms
     // (measured neutral at 43 kept atoms, 1-2 % slower below and with 8-bit coefficients)
     if (NP8 >= 9 && CT != CT_F8 && !F::LIST)
-        a.wb_ticks = (int)(16LL * wall_clock_khz() / 1000);     // 16 us of the constant-rate clock the kernel reads
+        a.wb_ticks = (int)((K == 7 ? 28LL : 16LL) * wall_clock_khz() / 1000);   // 16 us of the constant-rate clock the kernel
+                                                                                  // reads (7x7 atoms: 28 us, measured)
 #endif
     const int tiles_x = (a.W + F::TW - 1) / F::TW, tiles_y = (a.H + F::TH - 1) / F::TH;
     a.xlast = (tiles_x - 1) * F::TW;
