@@ -50,9 +50,12 @@
 //     dictionary as two bfloat16 operands;
 //   * CT_LIST8 / CT_LIST16 (an extension beyond the paper): no planes, but per-pixel
 //     lists of (atom, value) entries, scattered into the B operand through LDS
-//     (see the constants below).
+//     (see the constants below);
+//   * CT_LOGIT / CT_LOGIT_BF16 (an extension beyond the paper): the planes hold logits and the
+//     softmax over the atoms is part of the operand path (see the constants below).
 // Other coefficient layouts (template argument PSM): the planes as the coefficient
-// network holds them before its pixel-shuffle layer (see the kernel's own comment).
+// network holds them before its pixel-shuffle layer, pixel-major storage and the blocked
+// order that needs no re-packing at all (see the kernel's own comment).
 //
 // L2 write-back pacing.  The output leaves the CUs as ordinary stores and sits in the XCDs' L2s as dirty lines that
 // the L2 writes to memory when it sees fit, interleaved with the read stream; reads and writes that alternate at the
