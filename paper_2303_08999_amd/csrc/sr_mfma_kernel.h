@@ -338,6 +338,7 @@ __device__ __forceinline__ void divmod_scale(int v, int s, int& q, int& r) {
 // [lane half][column j][4 atoms].  Lane (j, hf) = lane j + 32 hf loads 16 bytes at 16 * lane of a piece (a wavefront: 1 KB
 // of contiguous memory per load) and holds the B operand of that 16-atom step and slot as it stands: no re-packing, no
 // staging, and the slots are the planar form's four adjacent pixels, so stage 4 and the store are the planar form's too.
+// (8-bit coefficients in the same order: 8 bytes per lane and piece, widened to the operand with four conversions.)
 template <int K, int C, int NP8, int PX, int WR, int NW, int NU, int WPE, int CT, int SMIN, bool BIG, int PSM = 0>
 __global__ __launch_bounds__(64 * NW, WPE)
 void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y, const int ntiles) {
@@ -352,10 +353,11 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     static_assert(!LIST || (PX == 4 && WR == 1 && !BIG && PSM == 0 && NU % 2 == 0), "list form: four pixels per lane, one row per unit");
     constexpr bool PS = PSM == 1;                  // one 16-bit load per pixel
     constexpr bool PERM = PSM == 2 || PSM == 3 || PSM == 4;    // permuted pixel slots
-    static_assert(PSM == 0 || ((CT == CT_F16 || ((CT == CT_BF16 || CT == CT_LOGIT || CT == CT_LOGIT_BF16) && PSM != 1 && PSM != 8)) && !BIG && PX == 4),
+    static_assert(PSM == 0 || ((CT == CT_F16 || (CT == CT_F8 && PSM == 9) ||
+                                ((CT == CT_BF16 || CT == CT_LOGIT || CT == CT_LOGIT_BF16) && PSM != 1 && PSM != 8)) && !BIG && PX == 4),
                   "pre-shuffle layout: 16-bit coefficients, four pixels per lane");
     static_assert(!PMAJ || (CT == CT_F16 && WR == 1 && NP8 == 9), "pixel-major coefficients: 72 fp16 atoms, one row per unit");
-    static_assert(!BLK || (CT == CT_F16 && WR == 1 && PX == 4), "blocked coefficients: fp16, one row of 128 pixels per unit");
+    static_assert(!BLK || ((CT == CT_F16 || CT == CT_F8) && WR == 1 && PX == 4), "blocked coefficients: fp16 or 8-bit, one row of 128 pixels per unit");
     static_assert(!PERM || (WR == 1 && SMIN >= PSM), "permuted slots: one row per wavefront and unit");
     // row of the wavefront's unit within the tile, and which of the row's NSUB units it is
     auto unit_row = [](int unit, int wave_) { return (unit / NSUB) * NW + wave_; };
@@ -667,22 +669,44 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         return (yc * (unsigned)a.W + (unsigned)tile_x0(tp.tx)) * (unsigned)(16 * NP8) + 16u * (unsigned)lane_;
     };
     auto pm_image = [&](const TilePos tp) -> const char* {
-        return (const char*)a.coeff + (size_t)tp.n * a.L * ((size_t)a.H * a.W * 2);
+        return (const char*)a.coeff + (size_t)tp.n * a.L * ((size_t)a.H * a.W * F::CB);
     };
     // blocked: byte offset of a unit within its image (a unit: 128 pixels x 8 NP8 atoms, contiguous), and its loads
-    u32x4 b16[BLK ? PX : 1][BLK && N16 ? N16 : 1];
-    u32x2 b8[BLK ? PX : 1];
-    constexpr unsigned SLOT_B = 32u * 16u * NP8;   // bytes of a slot: 32 pixels x 8 NP8 fp16 atoms
+    // (8-bit coefficients: the same order of elements, half the bytes: 8 bytes per lane and 16-atom piece, widened to the
+    //  operand at its use)
+    using B16 = typename std::conditional<F8, u32x2, u32x4>::type;
+    using B8 = typename std::conditional<F8, unsigned, u32x2>::type;
+    constexpr unsigned CBB = (unsigned)F::CB;
+    B16 b16[BLK ? PX : 1][BLK && N16 ? N16 : 1];
+    B8 b8[BLK ? PX : 1];
+    constexpr unsigned SLOT_B = 32u * 8u * NP8 * CBB;   // bytes of a slot: 32 pixels x 8 NP8 atoms
     auto blk_offset = [&](const TilePos tp, int unit) -> unsigned {
         const int y = tp.ty * F::TH + unit * NW + wave;
         const unsigned yc = (unsigned)(y < a.H ? y : a.H - 1);                 // rows past the image re-read its last row
         return (yc * (unsigned)(a.W / 128) + (unsigned)tp.tx) * (4u * SLOT_B);
     };
-    auto blk_load16 = [&](const char* img, unsigned unit_off, int lane_, int q, int c16) -> u32x4 {
-        return __builtin_nontemporal_load((const u32x4*)(img + (unit_off + (unsigned)q * SLOT_B + 1024u * c16 + 16u * lane_)));
+    auto blk_load16 = [&](const char* img, unsigned unit_off, int lane_, int q, int c16) -> B16 {
+        return __builtin_nontemporal_load((const B16*)(img + (unit_off + (unsigned)q * SLOT_B + 512u * CBB * c16 + 8u * CBB * lane_)));
     };
-    auto blk_load8 = [&](const char* img, unsigned unit_off, int lane_, int q) -> u32x2 {
-        return __builtin_nontemporal_load((const u32x2*)(img + (unit_off + (unsigned)q * SLOT_B + 1024u * N16 + 8u * lane_)));
+    auto blk_load8 = [&](const char* img, unsigned unit_off, int lane_, int q) -> B8 {
+        return __builtin_nontemporal_load((const B8*)(img + (unit_off + (unsigned)q * SLOT_B + 512u * CBB * N16 + 4u * CBB * lane_)));
+    };
+    // an 8-atom run of 8-bit coefficients widened to the fp16 operand (exact), two values per conversion
+    auto widen16 = [&](const u32x2& v) -> u32x4 {
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+        u32x4 r;
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+            r[m] = (m & 1) ? __builtin_bit_cast(unsigned, (h2)__builtin_amdgcn_cvt_scalef32_pk_f16_fp8(v[m >> 1], 1.0f, true))
+                           : __builtin_bit_cast(unsigned, (h2)__builtin_amdgcn_cvt_scalef32_pk_f16_fp8(v[m >> 1], 1.0f, false));
+        return r;
+    };
+    auto widen8 = [&](unsigned v) -> u32x2 {
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+        u32x2 r;
+        r[0] = __builtin_bit_cast(unsigned, (h2)__builtin_amdgcn_cvt_scalef32_pk_f16_fp8(v, 1.0f, false));
+        r[1] = __builtin_bit_cast(unsigned, (h2)__builtin_amdgcn_cvt_scalef32_pk_f16_fp8(v, 1.0f, true));
+        return r;
     };
     Raw raw[F::NLOAD];
     unsigned lrv[F::NLRP][F::NXC], lrpar = 0u;
@@ -1054,7 +1078,10 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 #pragma unroll
             for (int q = 0; q < PX; ++q) {
                 u32x4 bw;
-                if constexpr (BLK) bw = b16[q][c16];
+                if constexpr (BLK) {
+                    if constexpr (F8) bw = widen16(b16[q][c16]);
+                    else bw = b16[q][c16];
+                }
 #pragma unroll
                 for (int m = 0; m < (BLK ? 0 : 4); ++m)
                     bw[m] = F8 ? widen_pair(cw[2 * m][q >> 1], q)
@@ -1097,7 +1124,10 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
 #pragma unroll
             for (int q = 0; q < PX; ++q) {
                 u32x2 bw;
-                if constexpr (BLK) bw = b8[q];
+                if constexpr (BLK) {
+                    if constexpr (F8) bw = widen8(b8[q]);
+                    else bw = b8[q];
+                }
 #pragma unroll
                 for (int m = 0; m < (BLK ? 0 : 2); ++m)
                     bw[m] = F8 ? widen_pair(cw[2 * m][q >> 1], q)

@@ -31,6 +31,9 @@ CASES = [
     (1, 3, 29, 128, 3, 72, 5, "f16", "f16", None),      # scale 3, fp16 image
     (1, 3, 9, 32, 4, 72, 5, "f16", "f32", None),        # fewer rows than a tile
     (3, 3, 1, 32, 4, 72, 5, "f16", "f32", None),        # one LR row, three images
+    (1, 3, 37, 64, 4, 72, 5, "f8", "f32", None),        # 8-bit coefficients in the same order: the matrix-core family
+    (2, 3, 29, 128, 3, 72, 5, "f8", "f16", None),
+    (1, 3, 21, 64, 2, 72, 5, "f8", "f32", None),
     (1, 3, 40, 64, 4, 72, 5, "f16", "f32", 8),          # a kept list: the generic kernel
     (1, 3, 18, 32, 4, 40, 5, "f16", "f32", None),       # 40 atoms (two pieces and a last one): generic
     (1, 1, 19, 32, 4, 64, 5, "f32", "f32", None),       # 64 atoms: no last piece
@@ -66,13 +69,14 @@ def test_blocked_layout_against_the_oracle_and_the_planar_call(oracle, case):
             assert torch.equal(got, planar), f"kernel {kernel}: the two storage orders must give the same bits"
     assert ran >= 1
     takes = run(inp, wl, blk, MFMA, BLK, kept, gamma) is not None
-    assert takes == (cd == "f16" and C == 3 and k == 5 and L == 72 and nk is None)
+    assert takes == (cd in ("f16", "f8") and C == 3 and k == 5 and L == 72 and nk is None)
 
 
-def test_4k_frame_stored_blocked(oracle):
+@pytest.mark.parametrize("name", ["4k_dense", "4k_dense_fp8"])
+def test_4k_frame_stored_blocked(oracle, name):
     """The headline frame with its coefficients stored blocked: every output equals the planar call's, and sampled pixels
     (corners and edges among them) are checked against the oracle."""
-    wl = sr_synth.WORKLOADS["4k_dense"]
+    wl = sr_synth.WORKLOADS[name]
     inp = sr_synth.make_inputs(wl, DEV)
     planar = run(inp, wl, inp["coeff"], MFMA, sr.SR_COEFF_PLANAR)
     blk = sr_synth.to_blocked(inp["coeff"])
@@ -88,4 +92,4 @@ def test_4k_frame_stored_blocked(oracle):
     U = oracle.bicubic(inp["lr"].cpu().numpy(), wl.scale)
     want = oracle.assemble_points(U, oracle.blocked_to_planar(sr_synth.stored_numpy(blk)), inp["dict"].cpu().numpy(), pts)
     have = got.cpu().numpy()[0][:, pts[:, 1], pts[:, 2]].T
-    assert_parity(have, want, "f16", False, "sampled pixels")
+    assert_parity(have, want, wl.coeff_dtype, False, "sampled pixels")
