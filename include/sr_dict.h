@@ -30,7 +30,7 @@
  * All tensors are contiguous NCHW in DEVICE memory, allocated, owned and freed
  * by the caller.  The library allocates nothing, is re-entrant, and keeps nothing
  * between calls but what it has asked the device once (its number of compute
- * units, per host thread).  Work is enqueued on `stream` and the call returns without
+ * units and the rate of its constant clock, per host thread).  Work is enqueued on `stream` and the call returns without
  * synchronising: inputs and outputs must stay valid until the stream reaches
  * the end of the kernel.  `out` must not overlap any input.
  *
