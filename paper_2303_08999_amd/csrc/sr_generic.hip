@@ -69,7 +69,7 @@ __global__ __launch_bounds__(GNT) void k_assemble_generic(const AssembleArgs a) 
         // logits instead of coefficients: a first pass over the pixel's planes for the largest logit
         float nm = 0.0f;
         if (a.logits) {
-            float m = ld_as_float(cbase, 0);
+            float m = ld_as_float(cbase, coff(0));
             for (int i0 = 0; i0 < a.n_fold; i0 += NB) {
                 float z[NB];
 #pragma unroll

@@ -116,7 +116,7 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
     }
     // coefficients stored blocked: one family built (all of 72 fp16 or 8-bit atoms, stored coefficients)
     if (a.blocked) {
-        if (a.pre_shuffle || a.pixel_major || a.logits ||
+        if (a.pre_shuffle || a.pixel_major || (a.logits && coeff_dtype != SR_F16) ||
             !(k == 5 && a.C == 3 && (coeff_dtype == SR_F16 || coeff_dtype == SR_F8E4M3) && a.L == 72 && a.n_fold == 72 &&
               !beyond_4gb(a, coeff_dtype) && a.W % 128 == 0 && tile == 0)) return false;
         for (int i = 0; i < 72; ++i)
@@ -124,7 +124,7 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
     }
     // logits instead of coefficients: one family built (5x5, three channels, 49 to 72 fp16 or bfloat16 planes)
     // (in the layout before the pixel-shuffle: its permuted-slot forms, LR widths that are multiples of 4)
-    if (a.logits && !(k == 5 && a.C == 3 && (coeff_dtype == SR_F16 || coeff_dtype == SR_BF16) && np8 == 9 && a.n_fold == a.L && !a.pixel_major &&
+    if (a.logits && !a.blocked && !(k == 5 && a.C == 3 && (coeff_dtype == SR_F16 || coeff_dtype == SR_BF16) && np8 == 9 && a.n_fold == a.L && !a.pixel_major &&
                       (!a.pre_shuffle || a.w % 4 == 0) && !beyond_4gb(a, coeff_dtype) && tile == 0))
         return false;
     // (bfloat16: the forms with permuted pixel slots only, i.e. LR widths that are multiples of 4, all atoms)

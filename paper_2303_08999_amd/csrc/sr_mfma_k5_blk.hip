@@ -12,6 +12,10 @@ hipError_t launch_mfma_k5_blk(const AssembleArgs& a, hipStream_t st) {
         return launch_one<5, 3, 9, 4, 1, 4, 4, 2, CT_F8, 2, false, 9>(a, st);
     }
     if (a.coeff_dtype != SR_F16) return hipErrorInvalidValue;
+    if (a.logits) {                     // logits in the blocked order: the softmax in the operand path (see CT_LOGIT)
+        if (a.s == 4) return launch_one<5, 3, 9, 4, 1, 4, 6, 2, CT_LOGIT, 4, false, 9>(a, st);
+        return launch_one<5, 3, 9, 4, 1, 4, 4, 2, CT_LOGIT, 2, false, 9>(a, st);
+    }
     if (a.s == 4) return launch_one<5, 3, 9, 4, 1, 4, 6, 2, CT_F16, 4, false, 9>(a, st);
     return launch_one<5, 3, 9, 4, 1, 4, 4, 2, CT_F16, 2, false, 9>(a, st);
 }

@@ -258,6 +258,14 @@ __device__ __forceinline__ unsigned exp_pair(unsigned plane_even, unsigned plane
     const f2 e = {logit_exp(widen(plane_even), nm), logit_exp(widen(plane_odd), nm)};
     return __builtin_bit_cast(unsigned, __builtin_convertvector(e, h2));      // round to nearest even
 }
+// ... of one word's two logits (blocked order: two atoms of one pixel side by side)
+__device__ __forceinline__ unsigned exp_word(unsigned pair, float nm) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    const h2 z = __builtin_bit_cast(h2, pair);
+    const f2 e = {logit_exp((float)z[0], nm), logit_exp((float)z[1], nm)};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(e, h2));
+}
 // packed fp16 maximum of stored values (no canonicalising pass over the operands first)
 __device__ __forceinline__ _Float16 __attribute__((ext_vector_type(2))) pk_max_f16(_Float16 __attribute__((ext_vector_type(2))) x,
                                                                                  _Float16 __attribute__((ext_vector_type(2))) y) {
@@ -347,17 +355,19 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     constexpr bool BLK = PSM == 9;                 // coefficients stored blocked: the loaded registers are the operands
     using F = Cfg<K, C, NP8, PX, WR, NW, NU, CT, SMIN, NSUB, (PMAJ ? 1 : 0)>;
     constexpr bool F32 = F::F32, F8 = F::F8, BF = F::BF, LIST = F::LIST, LG = F::LG;
-    static_assert(!LG || (PX == 4 && (PSM == 0 || PSM == 2 || PSM == 3 || PSM == 4) && !BIG && F::NSLOT < 16 * F::NMB),
+    static_assert(!LG || (PX == 4 && (PSM == 0 || PSM == 2 || PSM == 3 || PSM == 4 || PSM == 9) && !BIG && F::NSLOT < 16 * F::NMB),
                   "logits form: fp16 planes (or the permuted-slot forms of the layout before the pixel-shuffle), four pixels per lane, a free MFMA row");
     constexpr int LH = F::LH;                      // list entries a lane half loads
     static_assert(!LIST || (PX == 4 && WR == 1 && !BIG && PSM == 0 && NU % 2 == 0), "list form: four pixels per lane, one row per unit");
     constexpr bool PS = PSM == 1;                  // one 16-bit load per pixel
     constexpr bool PERM = PSM == 2 || PSM == 3 || PSM == 4;    // permuted pixel slots
     static_assert(PSM == 0 || ((CT == CT_F16 || (CT == CT_F8 && PSM == 9) ||
-                                ((CT == CT_BF16 || CT == CT_LOGIT || CT == CT_LOGIT_BF16) && PSM != 1 && PSM != 8)) && !BIG && PX == 4),
+                                ((CT == CT_BF16 || CT == CT_LOGIT || CT == CT_LOGIT_BF16) && PSM != 1 && PSM != 8 &&
+                                 (PSM != 9 || CT == CT_LOGIT))) && !BIG && PX == 4),
                   "pre-shuffle layout: 16-bit coefficients, four pixels per lane");
     static_assert(!PMAJ || (CT == CT_F16 && WR == 1 && NP8 == 9), "pixel-major coefficients: 72 fp16 atoms, one row per unit");
-    static_assert(!BLK || ((CT == CT_F16 || CT == CT_F8) && WR == 1 && PX == 4), "blocked coefficients: fp16 or 8-bit, one row of 128 pixels per unit");
+    static_assert(!BLK || ((CT == CT_F16 || CT == CT_F8 || CT == CT_LOGIT) && WR == 1 && PX == 4),
+                  "blocked coefficients: fp16 (values or logits) or 8-bit, one row of 128 pixels per unit");
     static_assert(!PERM || (WR == 1 && SMIN >= PSM), "permuted slots: one row per wavefront and unit");
     // row of the wavefront's unit within the tile, and which of the row's NSUB units it is
     auto unit_row = [](int unit, int wave_) { return (unit / NSUB) * NW + wave_; };
@@ -1035,7 +1045,35 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
         }
         // logits form: -max * log2(e) of the lane's four pixels, over all planes (both lane halves)
         float nm[PX];
-        if constexpr (LG) {
+        if constexpr (LG && BLK) {
+            // blocked order: a word holds two atoms of ONE pixel (slot q); per slot the packed maximum over the lane's
+            // words, the larger of its two halves, then the other lane half's
+            typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+            for (int q = 0; q < PX; ++q) {
+                h2 mq = __builtin_bit_cast(h2, N16 ? b16[q][0][0] : b8[q][0]);
+#pragma unroll
+                for (int c16 = 0; c16 < N16; ++c16)
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) {
+                        const unsigned word = b16[q][c16][m];       // (by value: a bit cast straight from the vector element read element 0)
+                        mq = pk_max_f16(mq, __builtin_bit_cast(h2, word));
+                    }
+                if constexpr (N8 != 0) {
+#pragma unroll
+                    for (int m = 0; m < 2; ++m) {
+                        const unsigned word = b8[q][m];
+                        mq = pk_max_f16(mq, __builtin_bit_cast(h2, word));
+                    }
+                }
+                const unsigned bits = __builtin_bit_cast(unsigned, mq);
+                mq = pk_max_f16(mq, __builtin_bit_cast(h2, (bits >> 16) | (bits << 16)));       // both halves: the larger one
+                const unsigned one = __builtin_bit_cast(unsigned, mq);
+                const auto sw = __builtin_amdgcn_permlane32_swap(one, one, false, false);
+                mq = pk_max_f16(__builtin_bit_cast(h2, (unsigned)sw[0]), __builtin_bit_cast(h2, (unsigned)sw[1]));
+                nm[q] = logit_shift((float)mq[0]);
+            }
+        } else if constexpr (LG) {
             typedef _Float16 h2 __attribute__((ext_vector_type(2)));
             h2 mx[PX / 2];
 #pragma unroll
@@ -1080,7 +1118,10 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 u32x4 bw;
                 if constexpr (BLK) {
                     if constexpr (F8) bw = widen16(b16[q][c16]);
-                    else bw = b16[q][c16];
+                    else if constexpr (LG) {
+#pragma unroll
+                        for (int m = 0; m < 4; ++m) bw[m] = exp_word(b16[q][c16][m], nm[q]);
+                    } else bw = b16[q][c16];
                 }
 #pragma unroll
                 for (int m = 0; m < (BLK ? 0 : 4); ++m)
@@ -1126,7 +1167,10 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 u32x2 bw;
                 if constexpr (BLK) {
                     if constexpr (F8) bw = widen8(b8[q]);
-                    else bw = b8[q];
+                    else if constexpr (LG) {
+#pragma unroll
+                        for (int m = 0; m < 2; ++m) bw[m] = exp_word(b8[q][m], nm[q]);
+                    } else bw = b8[q];
                 }
 #pragma unroll
                 for (int m = 0; m < (BLK ? 0 : 2); ++m)

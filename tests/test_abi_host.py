@@ -251,7 +251,8 @@ def test_blocked_layout_is_checked_on_the_host(lib):
     for kw, pk in (({"cd": sr.SR_F32}, {}), ({"cd": sr.SR_BF16}, {}), ({"k": 7}, {"k": 7}), ({"C": 1}, {"C": 1}), ({"L": 64}, {"L": 64})):
         assert plan(*case(w=64, **kw), **pk, opts=bl()) == sr.SR_KERNEL_GENERIC, kw
     lg = sr.make_options(0, 0, sr.SR_COEFF_BLOCKED, sr.SR_COEFF_LOGITS)
-    assert plan(*case(w=64), opts=lg) == sr.SR_KERNEL_GENERIC                             # blocked logits: the generic kernel
+    assert plan(*case(w=64), opts=lg) == sr.SR_KERNEL_MFMA                                # blocked fp16 logits as well
+    assert plan(*case(w=64, cd=sr.SR_BF16), opts=lg) == sr.SR_KERNEL_GENERIC
     assert plan(*case(w=64), opts=sr.make_options(0, 0, 4)) == -3                          # unknown layout code
 
 

@@ -115,6 +115,33 @@ def test_logits_before_the_pixel_shuffle_on_the_matrix_cores(oracle, shape, cd):
     assert torch.equal(got, run(inp, wl, z, MFMA))
 
 
+@pytest.mark.parametrize("shape", [(1, 23, 64, 4), (2, 19, 128, 3), (1, 21, 64, 2), (1, 5, 32, 4)], ids=lambda c: "N%dh%dw%ds%d" % c)
+def test_logits_in_the_blocked_order_on_the_matrix_cores(oracle, shape):
+    """Logits stored in the blocked order (the matrix-core kernel's own operand order): against the oracle (blocked to planar,
+    softmax, the definition) and, bit for bit, against the call with the planar logits."""
+    N, h, w, s = shape
+    wl = sr_synth.Workload("lg", 59, N, 3, h, w, s, 72, 5, "f16", "f32", 0.0, 2.0)
+    inp = sr_synth.make_inputs(wl, DEV)
+    z = sr_synth.make_logits(wl, DEV)
+    blk = sr_synth.to_blocked(z)
+    hi = host(inp)
+    ref = oracle.dict_assemble(hi["lr"], sr_synth.stored_numpy(blk), hi["dict"], s, logits=True, blocked=True)
+    got = run(inp, wl, blk, MFMA, sr.SR_COEFF_BLOCKED)
+    assert got is not None and not torch.isnan(got).any()
+    assert_logits_parity(got.cpu().numpy(), ref, False, "blocked logits")
+    assert torch.equal(got, run(inp, wl, z, MFMA))
+    gen = run(inp, wl, blk, GENERIC, sr.SR_COEFF_BLOCKED)
+    assert_logits_parity(gen.cpu().numpy(), ref, False, "blocked logits, generic kernel")
+    # the shift is the pixel's own largest logit (any other shift rounds the exponentials elsewhere): as close to the oracle
+    # as the planar call of the same kernel, and closer to it than to the softmax without the rounding
+    plain = oracle.assemble(oracle.bicubic(hi["lr"], s), oracle.softmax_logits(sr_synth.stored_numpy(z), round_half=False), hi["dict"])
+    for name, t in (("matrix-core", got), ("generic", gen)):
+        g = t.cpu().numpy().astype(np.float64)
+        rms_ref, rms_plain = np.sqrt(np.mean((g - ref) ** 2)), np.sqrt(np.mean((g - plain) ** 2))
+        assert rms_ref < 0.5 * rms_plain, f"{name}: rms {rms_ref:.2e} against the rounded form, {rms_plain:.2e} against the unrounded one"
+    assert torch.equal(gen, run(inp, wl, z, GENERIC))
+
+
 def test_logits_in_the_other_layouts_run_on_the_generic_kernel(oracle):
     wl = sr_synth.Workload("lg", 54, 1, 3, 12, 30, 4, 72, 5, "f16", "f32", 0.0, 1.0)   # LR width not a multiple of 4
     inp = sr_synth.make_inputs(wl, DEV)
@@ -126,6 +153,7 @@ def test_logits_in_the_other_layouts_run_on_the_generic_kernel(oracle):
         assert run(inp, wl, moved, MFMA, layout) is None
         got = run(inp, wl, moved, GENERIC, layout)
         assert_logits_parity(got.cpu().numpy(), ref, False, flag)
+        assert np.sqrt(np.mean((got.cpu().numpy() - ref) ** 2)) < 2e-7, flag      # (a wrong shift would leave 1e-6)
         again = oracle.dict_assemble(hi["lr"], sr_synth.stored_numpy(moved), hi["dict"], wl.scale, logits=True, **{flag: True})
         assert np.array_equal(again, ref)
         assert torch.equal(got, run(inp, wl, z, GENERIC))
