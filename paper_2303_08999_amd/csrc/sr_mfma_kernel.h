@@ -1051,7 +1051,8 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
             typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 #pragma unroll
             for (int q = 0; q < PX; ++q) {
-                h2 mq = __builtin_bit_cast(h2, N16 ? b16[q][0][0] : b8[q][0]);
+                const unsigned first = N16 ? b16[q][0][0] : b8[q][0];
+                h2 mq = __builtin_bit_cast(h2, first);
 #pragma unroll
                 for (int c16 = 0; c16 < N16; ++c16)
 #pragma unroll
