@@ -34,6 +34,7 @@ struct AssembleArgs {
     int pixel_major;      // coefficients are [N][H][W][L] (a pixel's L coefficients side by side)
     int blocked;          // coefficients are stored in the blocked order (SR_COEFF_BLOCKED)
     int wb_ticks;         // matrix-core kernel (set at launch): period of the L2 write-back pacing in ticks of the constant clock, 0 = off
+    int wb_flushers;      // ... and the workgroups 0 .. wb_flushers - 1 that ask for it: one per XCD of the device
     int logits;           // `coeff` holds logits: the coefficients are their per-pixel softmax over the atoms
     int   kept[SR_MAX_ATOMS];    // plane read for folded atom i (identity when dense)
     float gamma[SR_MAX_ATOMS];   // its scale (1 when dense)

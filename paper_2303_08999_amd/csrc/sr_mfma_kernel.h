@@ -1411,8 +1411,8 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
                 }
             }
         }
-        // (6) L2 write-back pacing, see the note at the top of this file: workgroups 0 .. 7 run on the eight XCDs
-        if (a.wb_ticks > 0 && (int)blockIdx.x < 8 && wave == 0) {
+        // (6) L2 write-back pacing, see the note at the top of this file: workgroups 0 .. 7 run on the eight XCDs (fewer on a partition)
+        if (a.wb_ticks > 0 && (int)blockIdx.x < a.wb_flushers && wave == 0) {
             const unsigned long long now = __builtin_amdgcn_s_memrealtime();
             if (now - wb_last >= (unsigned long long)a.wb_ticks) {
                 wb_last = now;
@@ -1476,9 +1476,13 @@ hipError_t launch_one(const AssembleArgs& a0, hipStream_t st) {
 #ifndef SR_NO_L2_WRITEBACK
     // L2 write-back pacing where the coefficient stream is the bound: 49 atoms and more, not the 8-bit and list forms
     // (measured neutral at 43 kept atoms, 1-2 % slower below and with 8-bit coefficients)
-    if (NP8 >= 9 && CT != CT_F8 && !F::LIST)
-        a.wb_ticks = (int)((K == 7 ? 28LL : 16LL) * wall_clock_khz() / 1000);   // 16 us of the constant-rate clock the kernel
-                                                                                  // reads (7x7 atoms: 28 us, measured)
+    if (NP8 >= 9 && CT != CT_F8 && !F::LIST) {
+        // 16 us of the constant-rate clock the kernel reads (7x7 atoms: 28 us, measured); one asking workgroup per XCD
+        // (32 CUs each: eight on the whole device, fewer on a partition of it)
+        a.wb_ticks = (int)((K == 7 ? 28LL : 16LL) * wall_clock_khz() / 1000);
+        const int xcds = compute_units() / 32;
+        a.wb_flushers = xcds < 1 ? 1 : (xcds > 8 ? 8 : xcds);
+    }
 #endif
     const int tiles_x = (a.W + F::TW - 1) / F::TW, tiles_y = (a.H + F::TH - 1) / F::TH;
     a.xlast = (tiles_x - 1) * F::TW;
