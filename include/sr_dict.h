@@ -209,7 +209,7 @@ int sr_dict_assemble_selective(const sr_tensor* lr, const sr_tensor* coeff, cons
  * opts->coeff_layout = SR_COEFF_BLOCKED: see sr_coeff_layout; L % 8 != 0 or an HR width that is not a multiple of 128 is
  * SR_ERR_UNSUPPORTED.  A unit's 128 L coefficients are contiguous and every 16 bytes of it are a matrix-core operand of the
  * lane that loads them: no re-packing, no staging.  Every kernel takes it; the matrix-core kernel for k = 5, C = 3, all of
- * L = 72 f16 or f8 atoms, or f16 logits (no kept list), and under 4 GB of coefficients per image, the generic kernel otherwise.
+ * L = 72 f16, bf16 or f8 atoms, or f16 logits (no kept list), and under 4 GB of coefficients per image, the generic kernel otherwise.
  *
  * opts->coeff_kind = SR_COEFF_LOGITS: `coeff` holds logits z (f32, f16 or bf16; any layout above) and the call
  * computes, per pixel and over all L atoms,

@@ -114,10 +114,10 @@ bool mfma_supported(const AssembleArgs& a, int k, int coeff_dtype, int tile) {
         for (int i = 0; i < 72; ++i)
             if (a.kept[i] != i) return false;
     }
-    // coefficients stored blocked: one family built (all of 72 fp16 or 8-bit atoms, stored coefficients)
+    // coefficients stored blocked: one family built (all of 72 fp16, bfloat16 or 8-bit atoms; fp16 logits)
     if (a.blocked) {
         if (a.pre_shuffle || a.pixel_major || (a.logits && coeff_dtype != SR_F16) ||
-            !(k == 5 && a.C == 3 && (coeff_dtype == SR_F16 || coeff_dtype == SR_F8E4M3) && a.L == 72 && a.n_fold == 72 &&
+            !(k == 5 && a.C == 3 && (coeff_dtype == SR_F16 || coeff_dtype == SR_BF16 || coeff_dtype == SR_F8E4M3) && a.L == 72 && a.n_fold == 72 &&
               !beyond_4gb(a, coeff_dtype) && a.W % 128 == 0 && tile == 0)) return false;
         for (int i = 0; i < 72; ++i)
             if (a.kept[i] != i) return false;

@@ -363,11 +363,11 @@ void k_assemble_mfma(const AssembleArgs a, const int tiles_x, const int tiles_y,
     constexpr bool PERM = PSM == 2 || PSM == 3 || PSM == 4;    // permuted pixel slots
     static_assert(PSM == 0 || ((CT == CT_F16 || (CT == CT_F8 && PSM == 9) ||
                                 ((CT == CT_BF16 || CT == CT_LOGIT || CT == CT_LOGIT_BF16) && PSM != 1 && PSM != 8 &&
-                                 (PSM != 9 || CT == CT_LOGIT))) && !BIG && PX == 4),
+                                 (PSM != 9 || CT == CT_LOGIT || CT == CT_BF16))) && !BIG && PX == 4),
                   "pre-shuffle layout: 16-bit coefficients, four pixels per lane");
     static_assert(!PMAJ || (CT == CT_F16 && WR == 1 && NP8 == 9), "pixel-major coefficients: 72 fp16 atoms, one row per unit");
-    static_assert(!BLK || ((CT == CT_F16 || CT == CT_F8 || CT == CT_LOGIT) && WR == 1 && PX == 4),
-                  "blocked coefficients: fp16 (values or logits) or 8-bit, one row of 128 pixels per unit");
+    static_assert(!BLK || ((CT == CT_F16 || CT == CT_BF16 || CT == CT_F8 || CT == CT_LOGIT) && WR == 1 && PX == 4),
+                  "blocked coefficients: fp16 (values or logits), bfloat16 or 8-bit, one row of 128 pixels per unit");
     static_assert(!PERM || (WR == 1 && SMIN >= PSM), "permuted slots: one row per wavefront and unit");
     // row of the wavefront's unit within the tile, and which of the row's NSUB units it is
     auto unit_row = [](int unit, int wave_) { return (unit / NSUB) * NW + wave_; };

@@ -248,7 +248,8 @@ def test_blocked_layout_is_checked_on_the_host(lib):
     assert plan(*case(w=64), kept=list(range(72)), opts=bl()) == sr.SR_KERNEL_MFMA        # the identity list is no list
     assert plan(*case(w=64), opts=bl(sr.SR_KERNEL_MFMA, 3)) == -3                          # no alternative tiles in this layout
     assert plan(*case(w=64, cd=sr.SR_F8E4M3), opts=bl()) == sr.SR_KERNEL_MFMA              # 8-bit coefficients in the same order
-    for kw, pk in (({"cd": sr.SR_F32}, {}), ({"cd": sr.SR_BF16}, {}), ({"k": 7}, {"k": 7}), ({"C": 1}, {"C": 1}), ({"L": 64}, {"L": 64})):
+    assert plan(*case(w=64, cd=sr.SR_BF16), opts=bl()) == sr.SR_KERNEL_MFMA
+    for kw, pk in (({"cd": sr.SR_F32}, {}), ({"k": 7}, {"k": 7}), ({"C": 1}, {"C": 1}), ({"L": 64}, {"L": 64})):
         assert plan(*case(w=64, **kw), **pk, opts=bl()) == sr.SR_KERNEL_GENERIC, kw
     lg = sr.make_options(0, 0, sr.SR_COEFF_BLOCKED, sr.SR_COEFF_LOGITS)
     assert plan(*case(w=64), opts=lg) == sr.SR_KERNEL_MFMA                                # blocked fp16 logits as well

@@ -34,6 +34,8 @@ CASES = [
     (1, 3, 37, 64, 4, 72, 5, "f8", "f32", None),        # 8-bit coefficients in the same order: the matrix-core family
     (2, 3, 29, 128, 3, 72, 5, "f8", "f16", None),
     (1, 3, 21, 64, 2, 72, 5, "f8", "f32", None),
+    (1, 3, 37, 64, 4, 72, 5, "bf16", "f32", None),      # bfloat16 coefficients
+    (1, 3, 29, 128, 3, 72, 5, "bf16", "f16", None),
     (1, 3, 40, 64, 4, 72, 5, "f16", "f32", 8),          # a kept list: the generic kernel
     (1, 3, 18, 32, 4, 40, 5, "f16", "f32", None),       # 40 atoms (two pieces and a last one): generic
     (1, 1, 19, 32, 4, 64, 5, "f32", "f32", None),       # 64 atoms: no last piece
@@ -69,7 +71,7 @@ def test_blocked_layout_against_the_oracle_and_the_planar_call(oracle, case):
             assert torch.equal(got, planar), f"kernel {kernel}: the two storage orders must give the same bits"
     assert ran >= 1
     takes = run(inp, wl, blk, MFMA, BLK, kept, gamma) is not None
-    assert takes == (cd in ("f16", "f8") and C == 3 and k == 5 and L == 72 and nk is None)
+    assert takes == (cd in ("f16", "f8", "bf16") and C == 3 and k == 5 and L == 72 and nk is None)
 
 
 @pytest.mark.parametrize("name", ["4k_dense", "4k_dense_fp8"])
