@@ -95,3 +95,35 @@ def test_4k_frame_stored_blocked(oracle, name):
     want = oracle.assemble_points(U, oracle.blocked_to_planar(sr_synth.stored_numpy(blk)), inp["dict"].cpu().numpy(), pts)
     have = got.cpu().numpy()[0][:, pts[:, 1], pts[:, 2]].T
     assert_parity(have, want, wl.coeff_dtype, False, "sampled pixels")
+
+
+@pytest.mark.parametrize("kind", ["values", "logits"])
+def test_blocked_call_replays_inside_a_captured_graph(kind):
+    """The blocked forms (stored coefficients and logits), with the kernel's L2 write-back pacing in them, are one kernel with
+    no allocation: three replays of a captured call with new inputs copied into the captured buffers, each compared with an
+    eager call.  The frame is large enough (several tiles per workgroup, a launch longer than the pacing period) for the
+    write-back requests to fire."""
+    wl = sr_synth.Workload("blg", 66, 2, 3, 270, 480, 4, 72, 5, "f16", "f32", 0.0, 1.5)
+    make = sr_synth.make_logits if kind == "logits" else sr_synth.make_coeff
+    first = sr_synth.make_inputs(wl, DEV)
+    lr, blk, D = first["lr"].clone(), sr_synth.to_blocked(make(wl, DEV)).clone(), first["dict"].clone()
+    out = torch.zeros((wl.n, wl.c, wl.H, wl.W), device=DEV)
+    opts = sr.make_options(MFMA, 0, BLK, sr.SR_COEFF_LOGITS if kind == "logits" else sr.SR_COEFF_VALUES)
+    call = lambda: sr.sr_dict_assemble_ex(lr, blk, D, wl.L, wl.k, wl.scale, wl.c, out, opts=opts)
+    call()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for rep in range(3):
+        w2 = sr_synth.scaled(wl, index=wl.index + 1 + rep)
+        fresh = sr_synth.make_inputs(w2, DEV)
+        fb = sr_synth.to_blocked(make(w2, DEV))
+        lr.copy_(fresh["lr"]); blk.copy_(fb); D.copy_(fresh["dict"])
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        eager = torch.full_like(out, float("nan"))
+        sr.sr_dict_assemble_ex(fresh["lr"], fb, fresh["dict"], wl.L, wl.k, wl.scale, wl.c, eager, opts=opts)
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {rep}"
